@@ -1,0 +1,216 @@
+"""Benchmark of the RapidGNN data path on one MI355X.
+
+One step = one pass of the whole hot path over one epoch of one synthetic
+workload: rg_build_schedule (seeds, shuffle, every hop's sampling and
+frontiers), rg_build_cache (tally, TopHot, VectorPull, plans) and
+rg_gather_batch for every batch of the epoch.  Inputs are resident in HBM when
+the timed region starts; a second, separately reported pass keeps the remote
+feature table in pinned host memory (the stand-in for remote partitions), so
+its misses cross the host link.
+
+Prints ONE JSON line.  `value` is sampled edges per second over whole steps;
+the gathered-feature rate and the per-kernel roofline figures ride along.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+import torch
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+from paper_2509_05207_amd import accounting, synth       # noqa: E402
+
+HBM_PEAK_GBPS = 8000.0
+METRIC = "sampled edges/s + gathered feature GB/s (fraction of HBM peak), 1 GPU"
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def algorithmic_bytes(rg, sched, indptr, fanout):
+    """Per hop: (frontier nodes, sum of degrees, sampled edges, algorithmic bytes of the sampler launch).
+    Per frontier node: 16 B of indptr, 4 B frontier ID, 8 B sample offset, 4 B per row entry read,
+    4 B per sampled neighbour written."""
+    out = []
+    for hop, f in enumerate(fanout):
+        ids, _, off = rg.rg_schedule_frontier(sched, hop)
+        v = ids.long()
+        deg = indptr[v + 1] - indptr[v]
+        n, sdeg = int(ids.numel()), int(deg.sum().item())
+        samp = int(torch.clamp(deg, max=f).sum().item())
+        out.append(dict(nodes=n, sum_deg=sdeg, sampled=samp, bytes=n * (16 + 4 + 8) + 4 * sdeg + 4 * samp))
+    return out
+
+
+def run_step(rg, W, feat, out_buf, out_stride, cap_rows, side):
+    cfg = W.cfg
+    s = rg.rg_build_schedule(W.indptr, W.indices, W.train, cfg.batch_size, cfg.fanout, cfg.s0, cfg.worker, cfg.epoch)
+    c = rg.rg_build_cache([s], feat, W.K)
+    for b in range(s.n_batches):
+        rg.rg_gather_batch(s, c, feat, b, out_buf, out_stride=out_stride, out_capacity_rows=cap_rows, side_stream=side,
+                           want_stats=False)
+    return s, c
+
+
+def timed(rg, W, feat, out_buf, out_stride, cap_rows, side, steps, warmup):
+    for _ in range(warmup):
+        run_step(rg, W, feat, out_buf, out_stride, cap_rows, side)
+    torch.cuda.synchronize()
+    rg.rg_profile_reset()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        s, c = run_step(rg, W, feat, out_buf, out_stride, cap_rows, side)
+        del s, c
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    return dt, rg.rg_profile_read()
+
+
+def cpu_baseline(W, indptr_h, indices_h, train_h, budget_s=15.0):
+    """The oracle, as it stands, on a bounded prefix of the epoch's batches."""
+    import oracle
+    cfg = W.cfg
+    threads = max(1, min(16, oracle.max_threads(), os.cpu_count() or 1))
+    feats = oracle.Features(W.is_local.cpu().numpy(), W.row_of.cpu().numpy(),
+                            W.local_rows.contiguous().view(torch.uint8).cpu().numpy(), W.stride_bytes,
+                            W.remote_rows.contiguous().view(torch.uint8).cpu().numpy(), W.stride_bytes, W.row_bytes)
+    beta = accounting.batches_per_epoch(cfg.n_train, cfg.batch_size)
+
+    def one(nb):
+        t0 = time.perf_counter()
+        s = oracle.Schedule(indptr_h, indices_h, train_h, cfg.batch_size, cfg.fanout, cfg.s0, cfg.worker, cfg.epoch,
+                            batch_lo=0, batch_hi=nb, n_threads=threads)
+        freq = oracle.frequency([s], W.n_nodes)
+        ids, _ = oracle.top_hot(freq, feats.is_local, W.K)
+        oracle.cache_fill(ids, feats, table_stride=W.stride_bytes)
+        for b in range(s.n_batches):
+            oracle.gather_batch(s, b, feats, out_stride=W.stride_bytes)
+        dt = time.perf_counter() - t0
+        edges = sum(int(s.samples(h)[1].size) for h in range(s.L))
+        return dt, edges
+    dt1, _ = one(min(threads, beta))
+    nb = int(max(threads, min(beta, threads * max(1.0, budget_s / max(dt1, 1e-3)))))
+    nb = min(beta, nb // threads * threads if nb >= threads else nb)
+    dt, edges = one(nb)
+    return dict(value=edges / dt, unit="sampled edges/s", cores=threads, kind="oracle",
+                sample=f"first {nb} of {beta} batches of the epoch: schedule ({threads} threads, one batch per thread), "
+                       f"frequency, TopHot, cache fill and gather of those batches (single thread); {dt:.1f} s")
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=5)
+    ap.add_argument("--warmup", type=int, default=1)
+    ap.add_argument("--workload", default="medium", choices=sorted(synth.CONFIGS))
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-pcie-pass", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs on ONE GPU only (no collectives, no sharding); use --gpus 1")
+    if not torch.cuda.is_available():
+        sys.exit("bench.py: no GPU visible; the HIP path has no CPU fallback")
+
+    from paper_2509_05207_amd import binding as rg
+    rg.lib()
+    torch.cuda.set_device(0)
+    cfg = synth.CONFIGS[args.workload]
+    t0 = time.perf_counter()
+    W = synth.make_workload(cfg, device="cuda", feature_device="cuda", pin_remote=not args.no_pcie_pass)
+    torch.cuda.synchronize()
+    log(f"[bench] workload {cfg.name}: {W.n_nodes} nodes, {W.indices.numel()} edges, K={W.K}, generated in {time.perf_counter() - t0:.1f} s")
+    assert rg.rg_graph_validate(W.indptr, W.indices) == 0
+
+    remote_hbm = W.remote_rows.cuda()
+    feat_hbm = rg.make_features(W.is_local, W.row_of, W.local_rows, remote_hbm, W.row_bytes)
+    side = torch.cuda.Stream()
+
+    # sizes and algorithmic bytes from one untimed pass
+    s = rg.rg_build_schedule(W.indptr, W.indices, W.train, cfg.batch_size, cfg.fanout, cfg.s0, cfg.worker, cfg.epoch)
+    hops = algorithmic_bytes(rg, s, W.indptr, cfg.fanout)
+    _, _, off_L = rg.rg_schedule_frontier(s, s.L)
+    rows_per_epoch = int(off_L[-1])
+    m_max = int(np.diff(off_L).max())
+    c = rg.rg_build_cache([s], feat_hbm, W.K)
+    stats = [rg.rg_gather_batch(s, c, feat_hbm, b, torch.empty(m_max * W.stride_bytes, dtype=torch.uint8, device="cuda"),
+                                out_stride=W.stride_bytes, out_capacity_rows=m_max) for b in (0,)]
+    k_eff = rg.rg_cache_view(c, W.n_nodes)["K_eff"]
+    n_batches = s.n_batches
+    del s, c
+    sampled_edges = sum(h["sampled"] for h in hops)
+    out_buf = torch.empty(m_max * W.stride_bytes, dtype=torch.uint8, device="cuda")
+    log(f"[bench] {n_batches} batches, {sampled_edges} sampled edges/epoch, {rows_per_epoch} gathered rows/epoch, K_eff={k_eff}, batch0 {stats[0]}")
+
+    rg.rg_profile_enable(True)
+    dt, prof = timed(rg, W, feat_hbm, out_buf, W.stride_bytes, m_max, side, args.steps, args.warmup)
+    ms_per_step = dt / args.steps * 1e3
+    value = sampled_edges * args.steps / dt
+    log(f"[bench] HBM-resident: {ms_per_step:.2f} ms/step; kernel groups: " +
+        ", ".join(f"{k}={v['ms'] / args.steps:.2f}ms/{v['launches'] // args.steps}" for k, v in prof.items()))
+
+    # roofline of the dominant kernel (by device time)
+    samp_ms = prof["sampler"]["ms"] / args.steps
+    gath_ms = (prof["gather"]["ms"] + prof["gather_miss"]["ms"]) / args.steps
+    samp_bytes = sum(h["bytes"] for h in hops)
+    gath_bytes = accounting.gather_traffic_bytes(rows_per_epoch, W.row_bytes)
+    samp_gbps = samp_bytes / (samp_ms * 1e-3) / 1e9 if samp_ms > 0 else 0.0
+    gath_gbps = gath_bytes / (gath_ms * 1e-3) / 1e9 if gath_ms > 0 else 0.0
+    dominant = max(prof.items(), key=lambda kv: kv[1]["ms"])[0]
+    if dominant in ("gather", "gather_miss"):
+        roof = dict(kernel="gather_rows_kernel", bound="hbm", achieved=gath_gbps, peak=HBM_PEAK_GBPS, unit="GB/s",
+                    frac=gath_gbps / HBM_PEAK_GBPS, traffic=None,
+                    launches_per_step=(prof["gather"]["launches"] + prof["gather_miss"]["launches"]) // args.steps,
+                    avg_launch_ms=gath_ms / max(1, (prof["gather"]["launches"] + prof["gather_miss"]["launches"]) // args.steps),
+                    algorithmic_bytes_per_step=gath_bytes)
+    else:
+        roof = dict(kernel="sample_kernel", bound="hbm", achieved=samp_gbps, peak=HBM_PEAK_GBPS, unit="GB/s",
+                    frac=samp_gbps / HBM_PEAK_GBPS, traffic=None,
+                    launches_per_step=prof["sampler"]["launches"] // args.steps,
+                    avg_launch_ms=samp_ms / max(1, prof["sampler"]["launches"] // args.steps),
+                    algorithmic_bytes_per_step=samp_bytes)
+    roof["dominant_group_by_time"] = dominant
+
+    result = {
+        "metric": METRIC, "value": value, "unit": "sampled edges/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "u32",
+        "data": "synthetic",
+        "config": {"workload": f"{cfg.name}: {W.n_nodes} nodes, {W.indices.numel()} edges (Chung-Lu, exponent {cfg.gamma}), "
+                               f"{cfg.feat_dtype} features dim {cfg.feat_dim}, fanout {cfg.fanout}, batch {cfg.batch_size}, "
+                               f"{cfg.n_train} train nodes, K={W.K}, remote table in HBM",
+                   "n_batches": n_batches, "sampled_edges_per_epoch": sampled_edges, "gathered_rows_per_epoch": rows_per_epoch,
+                   "K_eff": int(k_eff)},
+        "roofline": roof,
+        "sampler": {"edges_per_s_kernel": sampled_edges / (samp_ms * 1e-3) if samp_ms else None, "GBps": samp_gbps,
+                    "frac_hbm": samp_gbps / HBM_PEAK_GBPS, "ms_per_step": samp_ms, "scanned_row_entries": sum(h["sum_deg"] for h in hops)},
+        "gather": {"GBps": gath_gbps, "frac_hbm": gath_gbps / HBM_PEAK_GBPS, "ms_per_step": gath_ms,
+                   "delivered_GBps": rows_per_epoch * W.row_bytes / (gath_ms * 1e-3) / 1e9 if gath_ms else None},
+        "kernel_ms_per_step": {k: v["ms"] / args.steps for k, v in prof.items()},
+    }
+
+    if not args.no_pcie_pass:
+        feat_pin = rg.make_features(W.is_local, W.row_of, W.local_rows, W.remote_rows, W.row_bytes)
+        steps2 = max(1, min(args.steps, 2))
+        dt2, prof2 = timed(rg, W, feat_pin, out_buf, W.stride_bytes, m_max, side, steps2, 1)
+        miss_ms = prof2["gather_miss"]["ms"] / steps2
+        fill_ms = prof2["cache_fill"]["ms"] / steps2
+        result["pcie_inclusive"] = {"value": sampled_edges * steps2 / dt2, "unit": "sampled edges/s", "ms_per_step": dt2 / steps2 * 1e3,
+                                    "steps": steps2, "miss_pull_ms_per_step": miss_ms, "cache_fill_ms_per_step": fill_ms,
+                                    "note": "remote feature table in pinned host memory; misses and the cache fill cross the host link"}
+        log(f"[bench] pinned-host remote table: {dt2 / steps2 * 1e3:.2f} ms/step (miss pull {miss_ms:.2f} ms, cache fill {fill_ms:.2f} ms)")
+    rg.rg_profile_enable(False)
+
+    if not args.no_cpu_baseline:
+        t0 = time.perf_counter()
+        result["cpu_baseline"] = cpu_baseline(W, W.indptr.cpu().numpy(), W.indices.cpu().numpy(), W.train.cpu().numpy())
+        log(f"[bench] cpu baseline took {time.perf_counter() - t0:.1f} s: {result['cpu_baseline']}")
+    print(json.dumps(result), flush=True)
+
+
+if __name__ == "__main__":
+    main()

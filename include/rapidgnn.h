@@ -1,0 +1,210 @@
+/*
+ * rapidgnn.h -- C ABI of the MI355X (gfx950) data-path library for RapidGNN
+ * (arXiv 2509.05207): deterministic seeded K-hop fan-out sampling of a whole
+ * epoch's mini-batch schedule, the access-frequency tally and TopHot selection
+ * that build the steady feature cache, and the per-batch feature-block gather.
+ *
+ * Conventions
+ *  - Every function returns rg_status (0 = RG_OK, negative = error).  On error
+ *    nothing is written through output handle pointers, and rg_last_error()
+ *    describes the failure (thread-local, valid until the next call on this
+ *    thread).  No exception crosses this boundary.
+ *  - "dev" pointers are device (HBM) addresses on the current HIP device;
+ *    "host" pointers are ordinary host addresses; "dev-visible" means either
+ *    device memory or pinned host memory (hipHostMalloc) that kernels can read.
+ *  - Node IDs are int32 (0 <= id < n_nodes < 2^31); row offsets and flat
+ *    positions are int64; counts are uint32/uint64.  Epoch, batch, hop and
+ *    worker indices are zero-based (the paper's text counts from 1).
+ *  - The caller owns every input buffer and the gather output buffer.  Inputs
+ *    are borrowed: the graph and train nodes only during rg_build_schedule;
+ *    the rg_features arrays during rg_build_cache and every rg_gather_batch.
+ *    Handles (rg_schedule, rg_cache) are owned by the library and released by
+ *    the matching *_destroy, through the allocator they were created with.
+ *  - Kernels are enqueued on the caller's hipStream_t (passed as void*; NULL =
+ *    the default stream).  The build calls return after the stream has
+ *    drained (they need sizes on the host); rg_gather_batch is asynchronous
+ *    when it is served from a cache's prepared plan.
+ */
+#ifndef RAPIDGNN_H
+#define RAPIDGNN_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef int32_t rg_status;
+#define RG_OK        0
+#define RG_EINVAL   (-1)   /* bad argument (null pointer, zero batch size, ...) */
+#define RG_ENOMEM   (-2)   /* an allocation failed */
+#define RG_EHIP     (-3)   /* a HIP runtime call failed */
+#define RG_ERANGE   (-4)   /* a size is beyond a documented limit, or an output buffer is too small */
+
+#define RG_MAX_HOPS    8u      /* L <= 8 */
+#define RG_MAX_FANOUT  1984u   /* every fanout[l] <= 1984 */
+
+const char *rg_last_error(void);
+
+/* Optional allocator: lets the host framework own all memory (e.g. a caching
+ * allocator).  kind 1 = device memory, kind 0 = pinned host memory.  alloc
+ * returns NULL on failure.  Passing a NULL rg_allocator* selects
+ * hipMalloc / hipHostMalloc. */
+typedef struct rg_allocator {
+    void *(*alloc)(uint64_t bytes, int kind, void *ctx);
+    void (*free)(void *p, int kind, void *ctx);
+    void *ctx;
+} rg_allocator;
+
+/* CSR adjacency the sampler reads ("the graph structure visible to the
+ * neighbourhood sampler", Sec. 2.3).  Precondition: within each row the
+ * neighbour IDs are strictly ascending (sorted, duplicate free) and in
+ * [0, n_nodes); rg_graph_validate checks it. */
+typedef struct rg_graph {
+    int64_t n_nodes;
+    const int64_t *indptr;    /* dev, [n_nodes + 1], indptr[0] = 0, non-decreasing */
+    const int32_t *indices;   /* dev, [indptr[n_nodes]] */
+} rg_graph;
+
+/* Checks the precondition above on the device.  *n_bad (host) receives the
+ * number of violations (rows that decrease, neighbour out of range, indptr
+ * decreasing); RG_OK is returned whenever the check itself ran. */
+rg_status rg_graph_validate(const rg_graph *g, void *stream, uint64_t *n_bad);
+
+typedef struct rg_schedule rg_schedule;
+typedef struct rg_cache rg_cache;
+
+/*
+ * rg_build_schedule -- one epoch of the precomputed schedule (Alg. 1 step 1;
+ * Sec. 3 "Offline enumeration and cache construction"; Sec. 4 par. (1)-(3)).
+ *
+ * Derives the per-batch seeds s_{e,i}^{(w)} = H(s0, worker, epoch, i)
+ * (Sec. 3 "Seeding and reproducibility"), shuffles train_nodes with the
+ * epoch's stream and cuts them into beta = ceil(T / batch_size) batches (the
+ * last one may be partial), then for every batch runs the K-hop uniform
+ * fan-out sampler: at hop l every node of the frontier U_l is sampled with
+ * SAMPLE(eta(v), fanout[l]) (uniform, without replacement, min(deg, fanout[l])
+ * neighbours, emitted in row order; fanout[0] applies to the seeds), and
+ * U_{l+1} = U_l followed by the newly reached IDs in ascending order.  The
+ * batch's input-node set N_i^e is U_L.  The result is a pure function of the
+ * arguments: it does not depend on launch shape or timing.
+ *
+ *   g            graph (struct on host, arrays on device)
+ *   train_nodes  dev, [T], distinct node IDs
+ *   batch_size   > 0 (unless T == 0)
+ *   fanout       host, [L]; L <= RG_MAX_HOPS, fanout[l] <= RG_MAX_FANOUT; L may be 0
+ *   a            allocator or NULL
+ *   out          receives the handle
+ * Scratch: two bitmaps of n_batches * n_nodes bits for the duration of the call.
+ */
+rg_status rg_build_schedule(const rg_graph *g, const int32_t *train_nodes, uint64_t T,
+                            uint32_t batch_size, const uint32_t *fanout, uint32_t L,
+                            uint64_t s0, uint32_t worker, uint32_t epoch,
+                            const rg_allocator *a, void *stream, rg_schedule **out);
+
+/* Read-only views ("metadata blocks": ordered batches, arrays N_i^e, offsets;
+ * Sec. 4 par. (3)).  Device pointers stay valid until rg_schedule_destroy. */
+rg_status rg_schedule_info(const rg_schedule *s, uint32_t *n_batches, uint32_t *L, int64_t *n_nodes);
+
+/* Frontier U_hop of every batch, concatenated; hop in [0, L]; hop 0 = the
+ * shuffled seeds, hop L = the input-node sets N_i^e.  batch_off has
+ * n_batches + 1 entries and is given both on the device and on the host. */
+rg_status rg_schedule_frontier(const rg_schedule *s, uint32_t hop, const int32_t **ids_dev,
+                               const int64_t **batch_off_dev, const int64_t **batch_off_host);
+
+/* Samples of hop in [0, L): samp_off_dev has |U_hop| + 1 entries indexed by
+ * position in frontier(hop); node at position j drew
+ * samp_nbr_dev[samp_off[j] .. samp_off[j+1]).  *n_samples = samp_off[|U_hop|]. */
+rg_status rg_schedule_samples(const rg_schedule *s, uint32_t hop, const int64_t **samp_off_dev,
+                              const int32_t **samp_nbr_dev, int64_t *n_samples);
+
+/* Feature storage, as byte rows (any element type): X[v] is
+ * local_rows + row_of[v] * local_stride when is_local[v], else
+ * remote_rows + row_of[v] * remote_stride ("N_local: nodes whose features
+ * reside on this worker", Eq. 2).  The remote table stands for the other
+ * partitions' memory behind VectorPull / SyncPull. */
+typedef struct rg_features {
+    const uint8_t *is_local;    /* dev, [n_nodes], 1 = local */
+    const int32_t *row_of;      /* dev, [n_nodes] */
+    const void *local_rows;     /* dev */
+    uint64_t local_stride;      /* bytes, >= row_bytes */
+    const void *remote_rows;    /* dev-visible: pinned host memory or device memory */
+    uint64_t remote_stride;     /* bytes, >= row_bytes */
+    uint32_t row_bytes;         /* bytes of one feature row, > 0 */
+} rg_features;
+
+/*
+ * rg_build_cache -- Alg. 1 steps 2-4 (Eq. 2; Sec. 4 par. (5)-(6)).
+ *
+ * Tallies freq(v) = number of batches, over the given epochs, whose N_i^e
+ * contains v; takes N_remote = {v : !is_local[v], freq(v) > 0}; selects
+ * N_cache = the min(K, |N_remote|) members ranked first by (freq descending,
+ * id ascending); pulls their rows from the remote table into a device table
+ * (VectorPull; slot j holds the j-th smallest cached id); and prepares, for
+ * every batch of every given epoch, the routing of each input node (local
+ * table / cache slot / remote miss), the miss list M_i^e and the batch's
+ * counts.
+ *
+ *   epochs    host array of n_epochs >= 1 schedule handles over the same n_nodes
+ *   f         feature storage (borrowed for the life of the cache)
+ *   K         n_hot, the cache capacity in rows (0 = no row cached)
+ * Device memory of the table: K_eff * round_up(row_bytes, 16) <= n_hot * d
+ * (one buffer of the bound in Sec. 3 "Invariants and bounds").
+ */
+rg_status rg_build_cache(const rg_schedule *const *epochs, uint32_t n_epochs, const rg_features *f,
+                         uint64_t K, const rg_allocator *a, void *stream, rg_cache **out);
+
+/* Views of the cache: K_eff, the cached ids (dev, ascending), freq (dev,
+ * [n_nodes]), slot_of (dev, [n_nodes], -1 = not cached), the table and its row
+ * stride.  Any output pointer may be NULL. */
+rg_status rg_cache_view(const rg_cache *c, uint64_t *K_eff, const int32_t **cache_ids_dev,
+                        const uint32_t **freq_dev, const int32_t **slot_of_dev,
+                        const void **rows_dev, uint64_t *stride);
+
+typedef struct rg_gather_stats {
+    uint64_t n_rows;    /* |N_i^e| */
+    uint64_t n_local;   /* served from the local table */
+    uint64_t n_hit;     /* served from the steady cache C_s */
+    uint64_t n_miss;    /* |M_i^e|: the batch's RPC count (Alg. 1 inner loop) */
+} rg_gather_stats;
+
+/*
+ * rg_gather_batch -- the feature block of batch `batch` (Alg. 1 inner loop:
+ * GetFeatureFromCache, M_i^e, SyncPull; Sec. 4 par. (7)):
+ *     out[r, 0:row_bytes] = X[N_i^e[r], 0:row_bytes],  r < |N_i^e|,
+ * bytes between row_bytes and out_stride are left untouched.  Local rows and
+ * cache hits are read from HBM on `stream`; the miss set is pulled from the
+ * remote table on `side_stream` (NULL = on `stream`) and joined back, so on
+ * return all writes to `out` are ordered before later work on `stream`.
+ * Routing never changes a byte of the result.
+ *
+ *   c      cache or NULL (no cache: every remote row is a miss).  If `s` is
+ *          one of the epochs the cache was built from, the prepared plan is
+ *          used and the call does not synchronise; otherwise rows are
+ *          classified on the fly and the call waits for its counts.
+ *   out    dev, out_capacity_rows * out_stride bytes; out_stride >= row_bytes
+ *   stats  host or NULL; filled on return
+ * RG_ERANGE if out_capacity_rows < |N_i^e| or batch >= n_batches (nothing is written).
+ */
+rg_status rg_gather_batch(const rg_schedule *s, const rg_cache *c, const rg_features *f, uint32_t batch,
+                          void *out, uint64_t out_stride, uint64_t out_capacity_rows,
+                          void *stream, void *side_stream, rg_gather_stats *stats);
+
+void rg_schedule_destroy(rg_schedule *s);
+void rg_cache_destroy(rg_cache *c);
+
+/* Timing aid for benchmarks: sums, since the last reset, the device time spent
+ * in the named kernel group when profiling is enabled (HIP events around each
+ * launch on the launch stream; adds a little latency).  Groups: 0 sampler
+ * (the per-node sampling kernel alone), 1 frontier (mark/scan/emit), 2 shuffle
+ * sort, 3 histogram, 4 top-K, 5 plan, 6 cache fill, 7 gather (HBM sources),
+ * 8 gather (miss pull), 9 sample sizes and their prefix sum. */
+#define RG_N_KERNEL_GROUPS 10
+void rg_profile_enable(int on);
+void rg_profile_reset(void);
+rg_status rg_profile_read(double *ms /* host, [RG_N_KERNEL_GROUPS] */, uint64_t *launches /* host, same */);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* RAPIDGNN_H */

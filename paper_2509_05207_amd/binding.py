@@ -1,0 +1,272 @@
+"""ctypes binding of librapidgnn_hip.so: same names as include/rapidgnn.h.
+
+Argument marshalling only.  Every step of the data path runs in the library's
+HIP kernels; torch is used for device memory (inputs, the gather output) and
+for stream handles.  There is no CPU fallback: if the library has not been
+built, importing the entry points raises.
+"""
+import ctypes as C
+import os
+
+import numpy as np
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "librapidgnn_hip.so")
+
+RG_OK, RG_EINVAL, RG_ENOMEM, RG_EHIP, RG_ERANGE = 0, -1, -2, -3, -4
+RG_MAX_HOPS, RG_MAX_FANOUT = 8, 1984
+KERNEL_GROUPS = ("sampler", "frontier", "shuffle_sort", "histogram", "topk", "plan", "cache_fill", "gather", "gather_miss", "sample_offsets")
+
+EXPORTS = ("rg_last_error", "rg_graph_validate", "rg_build_schedule", "rg_schedule_info", "rg_schedule_frontier",
+           "rg_schedule_samples", "rg_build_cache", "rg_cache_view", "rg_gather_batch", "rg_schedule_destroy",
+           "rg_cache_destroy", "rg_profile_enable", "rg_profile_reset", "rg_profile_read")
+
+
+class RgError(RuntimeError):
+    def __init__(self, status, message):
+        super().__init__(f"rapidgnn status {status}: {message}")
+        self.status = status
+
+
+class rg_graph(C.Structure):
+    _fields_ = [("n_nodes", C.c_int64), ("indptr", C.c_void_p), ("indices", C.c_void_p)]
+
+
+class rg_features(C.Structure):
+    _fields_ = [("is_local", C.c_void_p), ("row_of", C.c_void_p), ("local_rows", C.c_void_p), ("local_stride", C.c_uint64),
+                ("remote_rows", C.c_void_p), ("remote_stride", C.c_uint64), ("row_bytes", C.c_uint32)]
+
+
+class rg_gather_stats(C.Structure):
+    _fields_ = [("n_rows", C.c_uint64), ("n_local", C.c_uint64), ("n_hit", C.c_uint64), ("n_miss", C.c_uint64)]
+
+
+ALLOC_FN = C.CFUNCTYPE(C.c_void_p, C.c_uint64, C.c_int, C.c_void_p)
+FREE_FN = C.CFUNCTYPE(None, C.c_void_p, C.c_int, C.c_void_p)
+
+
+class rg_allocator(C.Structure):
+    _fields_ = [("alloc", ALLOC_FN), ("free", FREE_FN), ("ctx", C.c_void_p)]
+
+
+_lib = None
+
+
+def lib():
+    """The loaded library; raises if it has not been built (python -m paper_2509_05207_amd.build)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(_LIB_PATH):
+            raise RuntimeError(f"{_LIB_PATH} is missing: build it with `python -m paper_2509_05207_amd.build` "
+                               "(there is no fallback path)")
+        L = C.CDLL(_LIB_PATH)
+        vp, u64, u32, i64 = C.c_void_p, C.c_uint64, C.c_uint32, C.c_int64
+        P = C.POINTER
+        L.rg_last_error.restype = C.c_char_p
+        L.rg_graph_validate.argtypes = [P(rg_graph), vp, P(u64)]
+        L.rg_build_schedule.argtypes = [P(rg_graph), vp, u64, u32, P(u32), u32, u64, u32, u32, P(rg_allocator), vp, P(vp)]
+        L.rg_schedule_info.argtypes = [vp, P(u32), P(u32), P(i64)]
+        L.rg_schedule_frontier.argtypes = [vp, u32, P(vp), P(vp), P(vp)]
+        L.rg_schedule_samples.argtypes = [vp, u32, P(vp), P(vp), P(i64)]
+        L.rg_build_cache.argtypes = [P(vp), u32, P(rg_features), u64, P(rg_allocator), vp, P(vp)]
+        L.rg_cache_view.argtypes = [vp, P(u64), P(vp), P(vp), P(vp), P(vp), P(u64)]
+        L.rg_gather_batch.argtypes = [vp, vp, P(rg_features), u32, vp, u64, u64, vp, vp, P(rg_gather_stats)]
+        L.rg_schedule_destroy.argtypes = [vp]; L.rg_schedule_destroy.restype = None
+        L.rg_cache_destroy.argtypes = [vp]; L.rg_cache_destroy.restype = None
+        L.rg_profile_enable.argtypes = [C.c_int]; L.rg_profile_enable.restype = None
+        L.rg_profile_reset.argtypes = []; L.rg_profile_reset.restype = None
+        L.rg_profile_read.argtypes = [P(C.c_double), P(u64)]
+        for name in ("rg_graph_validate", "rg_build_schedule", "rg_schedule_info", "rg_schedule_frontier", "rg_schedule_samples",
+                     "rg_build_cache", "rg_cache_view", "rg_gather_batch", "rg_profile_read"):
+            getattr(L, name).restype = C.c_int32
+        _lib = L
+    return _lib
+
+
+def _check(status):
+    if status != RG_OK:
+        raise RgError(status, lib().rg_last_error().decode())
+
+
+def _stream_ptr(stream):
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    return C.c_void_p(stream.cuda_stream if hasattr(stream, "cuda_stream") else int(stream))
+
+
+def _dev_ptr(t, dtype=None):
+    if t is None:
+        return None
+    assert t.is_cuda and t.is_contiguous(), "expected a contiguous device tensor"
+    if dtype is not None:
+        assert t.dtype == dtype, f"expected {dtype}, got {t.dtype}"
+    return C.c_void_p(t.data_ptr())
+
+
+class _DevView:
+    """Zero-copy view of library-owned device memory for torch.as_tensor."""
+
+    def __init__(self, ptr, n, typestr):
+        self.__cuda_array_interface__ = {"shape": (int(n),), "typestr": typestr, "data": (int(ptr), False), "version": 2}
+
+
+def _view(ptr, n, typestr, owner):
+    if n == 0 or not ptr:
+        dt = {"<i4": torch.int32, "<i8": torch.int64, "<u1": torch.uint8}[typestr]
+        return torch.empty(0, dtype=dt, device="cuda")
+    t = torch.as_tensor(_DevView(ptr, n, typestr), device="cuda")
+    t._rg_owner = owner          # keep the handle alive as long as the view
+    return t
+
+
+def _graph_struct(indptr, indices):
+    n = indptr.numel() - 1
+    return rg_graph(n, _dev_ptr(indptr, torch.int64), _dev_ptr(indices, torch.int32) if indices.numel() else None)
+
+
+def rg_graph_validate(indptr, indices, stream=None):
+    """Number of violations of the CSR precondition (0 = valid)."""
+    g = _graph_struct(indptr, indices)
+    bad = C.c_uint64(0)
+    _check(lib().rg_graph_validate(C.byref(g), _stream_ptr(stream), C.byref(bad)))
+    return bad.value
+
+
+class Schedule:
+    def __init__(self, handle):
+        self.h = C.c_void_p(handle)
+        nb, L, nn = C.c_uint32(), C.c_uint32(), C.c_int64()
+        _check(lib().rg_schedule_info(self.h, C.byref(nb), C.byref(L), C.byref(nn)))
+        self.n_batches, self.L, self.n_nodes = nb.value, L.value, nn.value
+
+    def __del__(self):
+        if getattr(self, "h", None) and _lib is not None:
+            _lib.rg_schedule_destroy(self.h)
+            self.h = None
+
+
+class Cache:
+    def __init__(self, handle, keep):
+        self.h = C.c_void_p(handle)
+        self._keep = keep            # borrowed inputs (feature tensors, schedules) must outlive the cache
+
+    def __del__(self):
+        if getattr(self, "h", None) and _lib is not None:
+            _lib.rg_cache_destroy(self.h)
+            self.h = None
+
+
+def rg_build_schedule(indptr, indices, train_nodes, batch_size, fanout, s0=0, worker=0, epoch=0, allocator=None, stream=None):
+    g = _graph_struct(indptr, indices)
+    fan = (C.c_uint32 * max(len(fanout), 1))(*[int(x) for x in fanout])
+    out = C.c_void_p()
+    T = train_nodes.numel()
+    _check(lib().rg_build_schedule(C.byref(g), _dev_ptr(train_nodes, torch.int32) if T else None, T, int(batch_size), fan,
+                                   len(fanout), int(s0), int(worker), int(epoch),
+                                   C.byref(allocator) if allocator is not None else None, _stream_ptr(stream), C.byref(out)))
+    return Schedule(out.value)
+
+
+def rg_schedule_frontier(s, hop):
+    """(ids device tensor, batch offsets device tensor, batch offsets numpy)."""
+    ids, offd, offh = C.c_void_p(), C.c_void_p(), C.c_void_p()
+    _check(lib().rg_schedule_frontier(s.h, int(hop), C.byref(ids), C.byref(offd), C.byref(offh)))
+    off_host = np.ctypeslib.as_array(C.cast(offh, C.POINTER(C.c_int64)), shape=(s.n_batches + 1,)).copy()
+    n = int(off_host[-1])
+    return _view(ids.value, n, "<i4", s), _view(offd.value, s.n_batches + 1, "<i8", s), off_host
+
+
+def rg_schedule_samples(s, hop):
+    """(samp_off device tensor [|U_hop| + 1], samp_nbr device tensor)."""
+    so, sn, ns = C.c_void_p(), C.c_void_p(), C.c_int64()
+    _check(lib().rg_schedule_samples(s.h, int(hop), C.byref(so), C.byref(sn), C.byref(ns)))
+    _, _, off_host = rg_schedule_frontier(s, hop)
+    return _view(so.value, int(off_host[-1]) + 1, "<i8", s), _view(sn.value, ns.value, "<i4", s)
+
+
+def make_features(is_local, row_of, local_rows, remote_rows, row_bytes, local_stride=None, remote_stride=None):
+    """rg_features over torch tensors.  remote_rows may be a device tensor or a pinned host tensor."""
+    assert remote_rows.is_cuda or remote_rows.is_pinned() or remote_rows.numel() == 0, "remote rows must be device-visible"
+    assert local_rows.is_contiguous() and remote_rows.is_contiguous()
+    ls = local_stride if local_stride is not None else (local_rows.stride(0) * local_rows.element_size() if local_rows.dim() == 2 else row_bytes)
+    rs = remote_stride if remote_stride is not None else (remote_rows.stride(0) * remote_rows.element_size() if remote_rows.dim() == 2 else row_bytes)
+    f = rg_features(_dev_ptr(is_local, torch.uint8), _dev_ptr(row_of, torch.int32), C.c_void_p(local_rows.data_ptr()), int(ls),
+                    C.c_void_p(remote_rows.data_ptr()), int(rs), int(row_bytes))
+    f._keep = (is_local, row_of, local_rows, remote_rows)
+    return f
+
+
+def rg_build_cache(schedules, features, K, allocator=None, stream=None):
+    hs = (C.c_void_p * len(schedules))(*[s.h for s in schedules])
+    out = C.c_void_p()
+    _check(lib().rg_build_cache(hs, len(schedules), C.byref(features), int(K),
+                                C.byref(allocator) if allocator is not None else None, _stream_ptr(stream), C.byref(out)))
+    return Cache(out.value, (features, list(schedules), allocator))
+
+
+def rg_cache_view(c, n_nodes):
+    """dict with K_eff, cache_ids, freq, slot_of (device tensors), rows pointer and stride."""
+    k, ids, fr, so, rows, stride = C.c_uint64(), C.c_void_p(), C.c_void_p(), C.c_void_p(), C.c_void_p(), C.c_uint64()
+    _check(lib().rg_cache_view(c.h, C.byref(k), C.byref(ids), C.byref(fr), C.byref(so), C.byref(rows), C.byref(stride)))
+    freq_i32 = _view(fr.value, n_nodes, "<i4", c)           # counts are < 2^31: reinterpretation is exact
+    return dict(K_eff=k.value, cache_ids=_view(ids.value, k.value, "<i4", c), freq=freq_i32,
+                slot_of=_view(so.value, n_nodes, "<i4", c),
+                rows=_view(rows.value, k.value * stride.value, "<u1", c), stride=stride.value)
+
+
+def rg_gather_batch(s, c, features, batch, out, out_stride=None, out_capacity_rows=None, stream=None, side_stream=None,
+                    want_stats=True):
+    """Fills `out` (device tensor) with the batch's feature rows; returns the stats dict."""
+    assert out.is_cuda and out.is_contiguous()
+    if out_stride is None:
+        out_stride = out.stride(0) * out.element_size()
+    if out_capacity_rows is None:
+        out_capacity_rows = out.numel() * out.element_size() // out_stride
+    st = rg_gather_stats()
+    side = _stream_ptr(side_stream) if side_stream is not None else None
+    _check(lib().rg_gather_batch(s.h, c.h if c is not None else None, C.byref(features), int(batch), C.c_void_p(out.data_ptr()),
+                                 int(out_stride), int(out_capacity_rows), _stream_ptr(stream), side,
+                                 C.byref(st) if want_stats else None))
+    return dict(n_rows=st.n_rows, n_local=st.n_local, n_hit=st.n_hit, n_miss=st.n_miss) if want_stats else None
+
+
+def rg_profile_enable(on=True):
+    lib().rg_profile_enable(1 if on else 0)
+
+
+def rg_profile_reset():
+    lib().rg_profile_reset()
+
+
+def rg_profile_read():
+    ms = (C.c_double * len(KERNEL_GROUPS))()
+    n = (C.c_uint64 * len(KERNEL_GROUPS))()
+    _check(lib().rg_profile_read(ms, n))
+    return {g: dict(ms=ms[i], launches=int(n[i])) for i, g in enumerate(KERNEL_GROUPS)}
+
+
+class TorchAllocator:
+    """rg_allocator backed by torch: device buffers from the caching allocator, pinned buffers from pinned tensors."""
+
+    def __init__(self):
+        self.live = {}
+        self.n_alloc = 0
+
+        def _alloc(nbytes, kind, _ctx):
+            try:
+                if kind == 1:
+                    t = torch.empty(int(nbytes), dtype=torch.uint8, device="cuda")
+                else:
+                    t = torch.empty(int(nbytes), dtype=torch.uint8, pin_memory=True)
+            except Exception:       # noqa: BLE001 -- report failure to the library as NULL
+                return None
+            self.live[t.data_ptr()] = t
+            self.n_alloc += 1
+            return t.data_ptr()
+
+        def _free(p, _kind, _ctx):
+            self.live.pop(p, None)
+
+        self._a, self._f = ALLOC_FN(_alloc), FREE_FN(_free)
+        self.struct = rg_allocator(self._a, self._f, None)

@@ -1,0 +1,419 @@
+// rg_build_cache: access-frequency tally, TopHot selection, VectorPull into the
+// device table, and the per-batch routing plans (Alg. 1 steps 2-4).
+#include "rg_internal.h"
+
+#include <algorithm>
+
+namespace rg {
+
+// ---------------------------------------------------------------- a6: freq(v)
+// Every batch's input set is duplicate free, so each listed ID adds one.
+__global__ void tally_kernel(const int32_t *__restrict__ ids, int64_t n, uint32_t *__restrict__ freq)
+{
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride) atomicAdd(&freq[ids[i]], 1u);
+}
+
+// ---------------------------------------------------------------- a7: TopHot
+// Candidates: remote IDs with freq > 0.  The K-th largest frequency t is found
+// by a most-significant-digit-first radix select over the candidates' freq
+// values (8-bit digits, as many passes as max_freq needs; LDS-privatised digit
+// histograms merged with atomics).  Selected: freq > t, plus the first r
+// candidates with freq == t in ascending ID order (the tie-break), found by one
+// prefix sum over the nodes that also yields the slots: cache_ids ascending.
+struct SelectState {
+    uint32_t prefix;        // digits of t decided so far (high bits), already shifted into place
+    uint32_t prefix_mask;   // which bits of prefix are decided
+    uint64_t want;          // how many still to take among candidates matching the prefix
+    uint64_t n_candidates;  // set by the first pass
+    uint32_t take_all;      // 1: K >= #candidates, every candidate is selected
+    uint32_t t;             // final threshold
+    uint64_t r;             // how many of the freq == t candidates to take
+    uint64_t k_eff;
+};
+
+constexpr int TOPK_THREADS = 256;
+constexpr int DIGIT_BITS = 8;
+constexpr int DIGIT_BINS = 1 << DIGIT_BITS;
+
+__global__ void __launch_bounds__(TOPK_THREADS) digit_histogram_kernel(const uint32_t *__restrict__ freq, const uint8_t *__restrict__ is_local, int64_t n,
+                                                                       const SelectState *__restrict__ stp, int shift,
+                                                                       unsigned long long *__restrict__ bins)
+{
+    __shared__ unsigned int h[DIGIT_BINS];
+    for (int k = threadIdx.x; k < DIGIT_BINS; k += TOPK_THREADS) h[k] = 0;
+    __syncthreads();
+    const uint32_t prefix = stp->prefix, pmask = stp->prefix_mask;
+    if (stp->take_all) return;
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    for (int64_t v = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; v < n; v += stride) {
+        const uint32_t fv = freq[v];
+        if (fv != 0 && !is_local[v] && (fv & pmask) == prefix) atomicAdd(&h[(fv >> shift) & (DIGIT_BINS - 1)], 1u);
+    }
+    __syncthreads();
+    for (int k = threadIdx.x; k < DIGIT_BINS; k += TOPK_THREADS)
+        if (h[k]) atomicAdd(&bins[k], (unsigned long long)h[k]);
+}
+
+// One thread: walk the digit bins from the top until `want` is covered.
+__global__ void choose_digit_kernel(SelectState *__restrict__ stp, unsigned long long *__restrict__ bins, int shift, int first_pass, uint64_t K)
+{
+    if (threadIdx.x != 0 || blockIdx.x != 0) return;
+    SelectState st = *stp;
+    if (first_pass) {
+        uint64_t tot = 0;
+        for (int k = 0; k < DIGIT_BINS; ++k) tot += bins[k];
+        st.n_candidates = tot;
+        st.want = K;
+        if (K >= tot) { st.take_all = 1; st.t = 0; st.r = 0; st.k_eff = tot; }
+        else st.k_eff = K;
+    }
+    if (!st.take_all) {
+        uint64_t above = 0;
+        int d = DIGIT_BINS - 1;
+        for (; d > 0; --d) {
+            if (above + bins[d] >= st.want) break;
+            above += bins[d];
+        }
+        st.want -= above;                         // still to take inside digit d
+        st.prefix |= (uint32_t)d << shift;
+        st.prefix_mask |= (uint32_t)(DIGIT_BINS - 1) << shift;
+        if (shift == 0) { st.t = st.prefix; st.r = st.want; }
+    }
+    for (int k = 0; k < DIGIT_BINS; ++k) bins[k] = 0;
+    *stp = st;
+}
+
+// Packed counters per node: high 32 bits = selected outright (freq > t), low 32 bits = tied (freq == t).
+__device__ __forceinline__ uint64_t classify_node(uint32_t fv, uint8_t local, const SelectState &st)
+{
+    if (fv == 0 || local) return 0;
+    if (st.take_all || fv > st.t) return (uint64_t)1 << 32;
+    return fv == st.t ? 1ull : 0ull;
+}
+
+constexpr int SEL_PER_THREAD = 8;
+constexpr int SEL_TILE = TOPK_THREADS * SEL_PER_THREAD;
+
+__device__ __forceinline__ uint64_t block_exclusive_scan_u64(uint64_t x, uint64_t *total, uint64_t *lds)
+{
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    uint64_t incl = x;
+    for (int d = 1; d < 64; d <<= 1) {
+        uint64_t y = __shfl_up(incl, d, 64);
+        if (lane >= d) incl += y;
+    }
+    if (lane == 63) lds[wave] = incl;
+    __syncthreads();
+    uint64_t base = 0, tot = 0;
+    for (int w = 0; w < TOPK_THREADS / 64; ++w) {
+        const uint64_t s = lds[w];
+        if (w < wave) base += s;
+        tot += s;
+    }
+    __syncthreads();
+    *total = tot;
+    return base + incl - x;
+}
+
+__global__ void __launch_bounds__(TOPK_THREADS) select_block_totals(const uint32_t *__restrict__ freq, const uint8_t *__restrict__ is_local, int64_t n,
+                                                                    const SelectState *__restrict__ stp, uint64_t *__restrict__ block_tot)
+{
+    __shared__ uint64_t lds[TOPK_THREADS / 64];
+    const SelectState st = *stp;
+    const int64_t first = (int64_t)blockIdx.x * SEL_TILE + (int64_t)threadIdx.x * SEL_PER_THREAD;
+    uint64_t s = 0;
+    for (int k = 0; k < SEL_PER_THREAD; ++k) {
+        const int64_t v = first + k;
+        if (v < n) s += classify_node(freq[v], is_local[v], st);
+    }
+    uint64_t tot;
+    (void)block_exclusive_scan_u64(s, &tot, lds);
+    if (threadIdx.x == 0) block_tot[blockIdx.x] = tot;
+}
+
+__global__ void __launch_bounds__(TOPK_THREADS) select_scan_totals(uint64_t *__restrict__ block_tot, int64_t n_blocks)
+{
+    __shared__ uint64_t lds[TOPK_THREADS / 64];
+    uint64_t carry = 0;
+    for (int64_t base = 0; base < n_blocks; base += TOPK_THREADS) {
+        const int64_t i = base + threadIdx.x;
+        const uint64_t x = i < n_blocks ? block_tot[i] : 0;
+        uint64_t tot;
+        const uint64_t ex = block_exclusive_scan_u64(x, &tot, lds);
+        if (i < n_blocks) block_tot[i] = carry + ex;
+        carry += tot;
+    }
+}
+
+__global__ void __launch_bounds__(TOPK_THREADS) select_emit_kernel(const uint32_t *__restrict__ freq, const uint8_t *__restrict__ is_local, int64_t n,
+                                                                   const SelectState *__restrict__ stp, const uint64_t *__restrict__ block_base,
+                                                                   int32_t *__restrict__ cache_ids, int32_t *__restrict__ slot_of)
+{
+    __shared__ uint64_t lds[TOPK_THREADS / 64];
+    const SelectState st = *stp;
+    const int64_t first = (int64_t)blockIdx.x * SEL_TILE + (int64_t)threadIdx.x * SEL_PER_THREAD;
+    uint64_t c[SEL_PER_THREAD];
+    uint64_t s = 0;
+    for (int k = 0; k < SEL_PER_THREAD; ++k) {
+        const int64_t v = first + k;
+        c[k] = v < n ? classify_node(freq[v], is_local[v], st) : 0;
+        s += c[k];
+    }
+    uint64_t tot;
+    uint64_t run = block_base[blockIdx.x] + block_exclusive_scan_u64(s, &tot, lds);
+    for (int k = 0; k < SEL_PER_THREAD; ++k) {
+        const int64_t v = first + k;
+        if (v < n) {
+            const uint64_t gt_before = run >> 32, eq_before = run & 0xFFFFFFFFull;
+            const bool sel = (c[k] >> 32) != 0 || (c[k] == 1 && eq_before < st.r);
+            int32_t slot = -1;
+            if (sel) {
+                slot = (int32_t)(gt_before + (eq_before < st.r ? eq_before : st.r));
+                cache_ids[slot] = (int32_t)v;
+            }
+            slot_of[v] = slot;
+        }
+        run += c[k];
+    }
+}
+
+// ---------------------------------------------------------------- a8: VectorPull entries
+__global__ void fill_entries_kernel(const int32_t *__restrict__ cache_ids, uint64_t k_eff, const int32_t *__restrict__ row_of, int64_t *__restrict__ entries)
+{
+    const uint64_t j = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (j < k_eff) entries[j] = (TAG_REMOTE << TAG_SHIFT) | (int64_t)row_of[cache_ids[j]];
+}
+
+// ---------------------------------------------------------------- a5/a9: routing plan
+__device__ __forceinline__ uint32_t batch_of_pos(const int64_t *__restrict__ off, uint32_t n_batches, int64_t i)
+{
+    uint32_t lo = 0, hi = n_batches;
+    while (hi - lo > 1) {
+        const uint32_t mid = (lo + hi) >> 1;
+        if (off[mid] <= i) lo = mid; else hi = mid;
+    }
+    return lo;
+}
+
+// entry[j] for every listed input node, the miss flag (for the miss-list scan) and per-batch counts.
+__global__ void __launch_bounds__(256) plan_kernel(const int32_t *__restrict__ ids, int64_t n, const int64_t *__restrict__ batch_off, uint32_t n_batches,
+                                                   const uint8_t *__restrict__ is_local, const int32_t *__restrict__ row_of,
+                                                   const int32_t *__restrict__ slot_of, int64_t *__restrict__ entry, int32_t *__restrict__ miss_flag,
+                                                   unsigned long long *__restrict__ counts /* [n_batches][2]: local, hit */)
+{
+    const int64_t j = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const bool in = j < n;
+    int64_t tag = -1;
+    uint32_t b = 0;
+    if (in) {
+        const int32_t v = ids[j];
+        b = batch_of_pos(batch_off, n_batches, j);
+        int64_t row;
+        if (is_local[v]) { tag = TAG_LOCAL; row = row_of[v]; }
+        else {
+            const int32_t slot = slot_of ? slot_of[v] : -1;
+            if (slot >= 0) { tag = TAG_CACHE; row = slot; }
+            else { tag = TAG_REMOTE; row = row_of[v]; }
+        }
+        if (entry) entry[j] = (tag << TAG_SHIFT) | row;
+        if (miss_flag) miss_flag[j] = tag == TAG_REMOTE ? 1 : 0;
+    }
+    // wave-aggregated counts when the whole wave sits in one batch (the common case)
+    const uint32_t b0 = __shfl(b, 0, 64);
+    const bool uniform = __ballot(in && b != b0) == 0ull;
+    if (uniform) {
+        const unsigned long long ml = __ballot(tag == TAG_LOCAL), mh = __ballot(tag == TAG_CACHE);
+        if ((threadIdx.x & 63) == 0) {
+            if (ml) atomicAdd(&counts[2 * (uint64_t)b0], (unsigned long long)__popcll(ml));
+            if (mh) atomicAdd(&counts[2 * (uint64_t)b0 + 1], (unsigned long long)__popcll(mh));
+        }
+    } else if (in) {
+        if (tag == TAG_LOCAL) atomicAdd(&counts[2 * (uint64_t)b], 1ull);
+        else if (tag == TAG_CACHE) atomicAdd(&counts[2 * (uint64_t)b + 1], 1ull);
+    }
+}
+
+// miss_rows[miss_scan[j]] = j - batch_off[batch(j)] for every miss; miss_off[b] = miss_scan[batch_off[b]]
+__global__ void miss_list_kernel(const int32_t *__restrict__ miss_flag, const int64_t *__restrict__ miss_scan, int64_t n,
+                                 const int64_t *__restrict__ batch_off, uint32_t n_batches, int32_t *__restrict__ miss_rows)
+{
+    const int64_t j = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (j >= n || !miss_flag[j]) return;
+    const uint32_t b = batch_of_pos(batch_off, n_batches, j);
+    miss_rows[miss_scan[j]] = (int32_t)(j - batch_off[b]);
+}
+
+__global__ void miss_offsets_kernel(const int64_t *__restrict__ miss_scan, const int64_t *__restrict__ batch_off, uint32_t n_batches, int64_t *__restrict__ miss_off)
+{
+    const uint32_t b = blockIdx.x * blockDim.x + threadIdx.x;
+    if (b <= n_batches) miss_off[b] = miss_scan[batch_off[b]];
+}
+
+// Routing + counts of one schedule against (is_local, slot_of).  want_plan: keep entries and
+// miss lists in `keep`; otherwise everything lives in `tmp`.
+rg_status build_plan(const rg_schedule *s, const rg_features *f, const int32_t *slot_of, Arena &keep, Arena &tmp, hipStream_t st, Plan *plan)
+{
+    const uint32_t beta = s->n_batches;
+    const HopData &h = s->hop[s->L];
+    const int64_t n = beta ? h.off_host[beta] : 0;
+    plan->schedule_uid = s->uid;
+    plan->miss_off.assign((size_t)beta + 1, 0);
+    plan->stats.assign(beta, rg_gather_stats{0, 0, 0, 0});
+    RG_TRY(keep.dev_n<int64_t>((uint64_t)n, &plan->entry));
+    if (beta == 0) { RG_TRY(keep.dev_n<int32_t>(0, &plan->miss_rows)); return RG_OK; }
+
+    int32_t *miss_flag = nullptr;
+    int64_t *miss_scan = nullptr, *miss_off_dev = nullptr;
+    unsigned long long *counts = nullptr;
+    RG_TRY(tmp.dev_n<int32_t>((uint64_t)n, &miss_flag));
+    RG_TRY(tmp.dev_n<int64_t>((uint64_t)n + 1, &miss_scan));
+    RG_TRY(tmp.dev_n<int64_t>((uint64_t)beta + 1, &miss_off_dev));
+    RG_TRY(tmp.dev_n<unsigned long long>(2 * (uint64_t)beta, &counts));
+    RG_HIP(hipMemsetAsync(counts, 0, 2 * (uint64_t)beta * sizeof(unsigned long long), st));
+    {
+        ScopedTimer tm(KG_PLAN, st);
+        if (n > 0)
+            hipLaunchKernelGGL(plan_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, h.ids, n, h.off_dev, beta, f->is_local, f->row_of,
+                               slot_of, plan->entry, miss_flag, counts);
+        RG_TRY(scan_i32_to_i64(miss_flag, miss_scan, n, tmp, st));
+        hipLaunchKernelGGL(miss_offsets_kernel, dim3((beta + 1 + 255) / 256), dim3(256), 0, st, miss_scan, h.off_dev, beta, miss_off_dev);
+    }
+    std::vector<unsigned long long> hc(2 * (size_t)beta);
+    RG_HIP(hipMemcpyAsync(plan->miss_off.data(), miss_off_dev, ((size_t)beta + 1) * sizeof(int64_t), hipMemcpyDeviceToHost, st));
+    RG_HIP(hipMemcpyAsync(hc.data(), counts, hc.size() * sizeof(unsigned long long), hipMemcpyDeviceToHost, st));
+    RG_HIP(hipStreamSynchronize(st));
+    const int64_t n_miss = plan->miss_off[beta];
+    RG_TRY(keep.dev_n<int32_t>((uint64_t)n_miss, &plan->miss_rows));
+    if (n_miss > 0) {
+        ScopedTimer tm(KG_PLAN, st);
+        hipLaunchKernelGGL(miss_list_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, miss_flag, miss_scan, n, h.off_dev, beta, plan->miss_rows);
+    }
+    RG_HIP(hipGetLastError());
+    for (uint32_t b = 0; b < beta; ++b) {
+        rg_gather_stats &g = plan->stats[b];
+        g.n_rows = (uint64_t)(h.off_host[b + 1] - h.off_host[b]);
+        g.n_local = hc[2 * (size_t)b];
+        g.n_hit = hc[2 * (size_t)b + 1];
+        g.n_miss = (uint64_t)(plan->miss_off[b + 1] - plan->miss_off[b]);
+    }
+    RG_HIP(hipStreamSynchronize(st));
+    return RG_OK;
+}
+
+static rg_status build_cache_impl(const rg_schedule *const *epochs, uint32_t n_epochs, const rg_features *f, uint64_t K,
+                                  const rg_allocator *a, hipStream_t st, rg_cache *c)
+{
+    const int64_t n = epochs[0]->n_nodes;
+    c->n_nodes = n;
+    c->row_bytes = f->row_bytes;
+    c->stride = ((uint64_t)f->row_bytes + 15) / 16 * 16;
+    Arena tmp(a);
+    RG_HIP(hipEventCreateWithFlags(&c->ev_fork, hipEventDisableTiming));
+    RG_HIP(hipEventCreateWithFlags(&c->ev_join, hipEventDisableTiming));
+
+    int dev = 0, n_cu = 256;
+    RG_HIP(hipGetDevice(&dev));
+    RG_HIP(hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, dev));
+
+    // ---- a6: tally
+    RG_TRY(c->arena.dev_n<uint32_t>((uint64_t)n, &c->freq));
+    RG_TRY(c->arena.dev_n<int32_t>((uint64_t)n, &c->slot_of));
+    RG_HIP(hipMemsetAsync(c->freq, 0, (uint64_t)n * sizeof(uint32_t), st));
+    uint64_t max_freq = 0;
+    for (uint32_t e = 0; e < n_epochs; ++e) {
+        const rg_schedule *s = epochs[e];
+        max_freq += s->n_batches;
+        if (s->n_batches == 0) continue;
+        const HopData &h = s->hop[s->L];
+        const int64_t m = h.off_host[s->n_batches];
+        if (m == 0) continue;
+        ScopedTimer tm(KG_HIST, st);
+        const unsigned grid = (unsigned)std::min<int64_t>((m + 255) / 256, (int64_t)n_cu * 32);
+        hipLaunchKernelGGL(tally_kernel, dim3(grid), dim3(256), 0, st, h.ids, m, c->freq);
+    }
+    RG_HIP(hipGetLastError());
+
+    // ---- a7: TopHot
+    SelectState *stp = nullptr;
+    unsigned long long *bins = nullptr;
+    RG_TRY(tmp.dev_n<SelectState>(1, &stp));
+    RG_TRY(tmp.dev_n<unsigned long long>(DIGIT_BINS, &bins));
+    RG_HIP(hipMemsetAsync(stp, 0, sizeof(SelectState), st));
+    RG_HIP(hipMemsetAsync(bins, 0, DIGIT_BINS * sizeof(unsigned long long), st));
+    int bits = 1;
+    while (bits < 32 && (max_freq >> bits) != 0) ++bits;
+    const int passes = (bits + DIGIT_BITS - 1) / DIGIT_BITS;
+    const int64_t sel_blocks = (n + SEL_TILE - 1) / SEL_TILE;
+    uint64_t *block_tot = nullptr;
+    RG_TRY(tmp.dev_n<uint64_t>((uint64_t)(sel_blocks ? sel_blocks : 1), &block_tot));
+    {
+        ScopedTimer tm(KG_TOPK, st);
+        const unsigned grid = (unsigned)std::max<int64_t>(1, std::min<int64_t>((n + TOPK_THREADS - 1) / TOPK_THREADS, (int64_t)n_cu * 16));
+        for (int p = 0; p < passes; ++p) {
+            const int shift = (passes - 1 - p) * DIGIT_BITS;
+            hipLaunchKernelGGL(digit_histogram_kernel, dim3(grid), dim3(TOPK_THREADS), 0, st, c->freq, f->is_local, n, stp, shift, bins);
+            hipLaunchKernelGGL(choose_digit_kernel, dim3(1), dim3(64), 0, st, stp, bins, shift, p == 0 ? 1 : 0, K);
+        }
+        if (sel_blocks > 0) {
+            hipLaunchKernelGGL(select_block_totals, dim3((unsigned)sel_blocks), dim3(TOPK_THREADS), 0, st, c->freq, f->is_local, n, stp, block_tot);
+            hipLaunchKernelGGL(select_scan_totals, dim3(1), dim3(TOPK_THREADS), 0, st, block_tot, sel_blocks);
+        }
+    }
+    SelectState hs;
+    RG_HIP(hipMemcpyAsync(&hs, stp, sizeof(SelectState), hipMemcpyDeviceToHost, st));
+    RG_HIP(hipStreamSynchronize(st));
+    c->K_eff = hs.k_eff;
+    RG_TRY(c->arena.dev_n<int32_t>(c->K_eff, &c->cache_ids));
+    if (sel_blocks > 0) {
+        ScopedTimer tm(KG_TOPK, st);
+        hipLaunchKernelGGL(select_emit_kernel, dim3((unsigned)sel_blocks), dim3(TOPK_THREADS), 0, st, c->freq, f->is_local, n, stp, block_tot,
+                           c->cache_ids, c->slot_of);
+    }
+    RG_HIP(hipGetLastError());
+
+    // ---- a8: VectorPull -- one bulk gather of the selected rows out of the remote table
+    RG_TRY(c->arena.dev(c->K_eff * c->stride, &c->rows));
+    if (c->K_eff > 0) {
+        int64_t *fill_entries = nullptr;
+        RG_TRY(tmp.dev_n<int64_t>(c->K_eff, &fill_entries));
+        hipLaunchKernelGGL(fill_entries_kernel, dim3((unsigned)((c->K_eff + 255) / 256)), dim3(256), 0, st, c->cache_ids, c->K_eff, f->row_of, fill_entries);
+        RowSources src{(const uint8_t *)f->local_rows, f->local_stride, (const uint8_t *)c->rows, c->stride,
+                       (const uint8_t *)f->remote_rows, f->remote_stride};
+        RG_TRY(launch_gather(fill_entries, (int64_t)c->K_eff, nullptr, 0, 1, src, f->row_bytes, (uint8_t *)c->rows, c->stride, st, KG_FILL));
+    }
+
+    // ---- a5/a9: plans, miss lists and counts for every batch of every epoch
+    c->plans.resize(n_epochs);
+    for (uint32_t e = 0; e < n_epochs; ++e) RG_TRY(build_plan(epochs[e], f, c->slot_of, c->arena, tmp, st, &c->plans[e]));
+    RG_HIP(hipStreamSynchronize(st));
+    return RG_OK;
+}
+
+}  // namespace rg
+
+using namespace rg;
+
+extern "C" rg_status rg_build_cache(const rg_schedule *const *epochs, uint32_t n_epochs, const rg_features *f, uint64_t K,
+                                    const rg_allocator *a, void *stream, rg_cache **out)
+{
+    if (!epochs || n_epochs == 0 || !f || !out) { set_error("rg_build_cache: null argument or no epoch"); return RG_EINVAL; }
+    for (uint32_t e = 0; e < n_epochs; ++e) {
+        if (!epochs[e]) { set_error("rg_build_cache: epochs[%u] is null", e); return RG_EINVAL; }
+        if (epochs[e]->n_nodes != epochs[0]->n_nodes) { set_error("rg_build_cache: epochs disagree on n_nodes"); return RG_EINVAL; }
+    }
+    if (epochs[0]->n_nodes > 0 && (!f->is_local || !f->row_of)) { set_error("rg_build_cache: null is_local / row_of"); return RG_EINVAL; }
+    if (f->row_bytes == 0) { set_error("rg_build_cache: row_bytes must be > 0"); return RG_EINVAL; }
+    if (f->local_stride < f->row_bytes || f->remote_stride < f->row_bytes) { set_error("rg_build_cache: a stride is smaller than row_bytes"); return RG_EINVAL; }
+
+    rg_cache *c = new (std::nothrow) rg_cache(a);
+    if (!c) { set_error("rg_build_cache: out of host memory"); return RG_ENOMEM; }
+    rg_status rc = build_cache_impl(epochs, n_epochs, f, K, a, as_stream(stream), c);
+    if (rc != RG_OK) {
+        (void)hipStreamSynchronize(as_stream(stream));
+        rg_cache_destroy(c);
+        return rc;
+    }
+    *out = c;
+    return RG_OK;
+}

@@ -1,0 +1,363 @@
+// Error reporting, memory arena, kernel-group timers, the device prefix sum,
+// graph validation and the handle accessors.
+#include "rg_internal.h"
+
+#include <atomic>
+#include <cstdarg>
+#include <cstdio>
+#include <mutex>
+
+namespace rg {
+
+// ---------------------------------------------------------------- errors
+static thread_local char g_err[512] = "";
+
+void set_error(const char *fmt, ...)
+{
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_err, sizeof(g_err), fmt, ap);
+    va_end(ap);
+}
+
+// ---------------------------------------------------------------- arena
+Arena::Arena(const rg_allocator *a)
+{
+    custom_ = (a != nullptr && a->alloc != nullptr && a->free != nullptr);
+    if (custom_) a_ = *a; else a_ = rg_allocator{nullptr, nullptr, nullptr};
+}
+
+Arena::~Arena() { release_all(); }
+
+rg_status Arena::dev(uint64_t bytes, void **out)
+{
+    uint64_t want = bytes ? bytes : 256;
+    void *p = nullptr;
+    if (custom_) {
+        p = a_.alloc(want, 1, a_.ctx);
+        if (!p) { set_error("allocator callback returned NULL for %llu device bytes", (unsigned long long)want); return RG_ENOMEM; }
+    } else {
+        hipError_t e = hipMalloc(&p, want);
+        if (e != hipSuccess) {
+            (void)hipGetLastError();
+            set_error("hipMalloc(%llu) failed: %s", (unsigned long long)want, hipGetErrorString(e));
+            return RG_ENOMEM;
+        }
+    }
+    items_.push_back({p, 1, want});
+    in_use_ += want;
+    *out = p;
+    return RG_OK;
+}
+
+rg_status Arena::pinned(uint64_t bytes, void **out)
+{
+    uint64_t want = bytes ? bytes : 256;
+    void *p = nullptr;
+    if (custom_) {
+        p = a_.alloc(want, 0, a_.ctx);
+        if (!p) { set_error("allocator callback returned NULL for %llu pinned bytes", (unsigned long long)want); return RG_ENOMEM; }
+    } else {
+        hipError_t e = hipHostMalloc(&p, want, hipHostMallocDefault);
+        if (e != hipSuccess) {
+            (void)hipGetLastError();
+            set_error("hipHostMalloc(%llu) failed: %s", (unsigned long long)want, hipGetErrorString(e));
+            return RG_ENOMEM;
+        }
+    }
+    items_.push_back({p, 0, want});
+    in_use_ += want;
+    *out = p;
+    return RG_OK;
+}
+
+void Arena::free_one(void *p)
+{
+    if (!p) return;
+    for (size_t i = 0; i < items_.size(); ++i) {
+        if (items_[i].p == p) {
+            if (custom_) a_.free(p, items_[i].kind, a_.ctx);
+            else if (items_[i].kind == 1) (void)hipFree(p);
+            else (void)hipHostFree(p);
+            in_use_ -= items_[i].bytes;
+            items_[i] = items_.back();
+            items_.pop_back();
+            return;
+        }
+    }
+}
+
+void Arena::release_all()
+{
+    for (auto &it : items_) {
+        if (custom_) a_.free(it.p, it.kind, a_.ctx);
+        else if (it.kind == 1) (void)hipFree(it.p);
+        else (void)hipHostFree(it.p);
+    }
+    items_.clear();
+    in_use_ = 0;
+}
+
+// ---------------------------------------------------------------- profiling
+static std::atomic<int> g_prof_on{0};
+static std::mutex g_prof_mu;
+struct Pending { int group; hipEvent_t e0, e1; };
+static std::vector<Pending> g_pending;
+static double g_ms[RG_N_KERNEL_GROUPS];
+static uint64_t g_launches[RG_N_KERNEL_GROUPS];
+
+bool profiling_on() { return g_prof_on.load(std::memory_order_relaxed) != 0; }
+
+ScopedTimer::ScopedTimer(int g, hipStream_t s) : group(g), st(s)
+{
+    if (!profiling_on()) return;
+    if (hipEventCreate(&e0) != hipSuccess || hipEventCreate(&e1) != hipSuccess) { e0 = e1 = nullptr; return; }
+    (void)hipEventRecord(e0, st);
+}
+
+ScopedTimer::~ScopedTimer()
+{
+    if (!e0) return;
+    (void)hipEventRecord(e1, st);
+    std::lock_guard<std::mutex> lk(g_prof_mu);
+    g_pending.push_back({group, e0, e1});
+}
+
+static void drain_pending_locked()
+{
+    for (auto &p : g_pending) {
+        float ms = 0.f;
+        if (hipEventSynchronize(p.e1) == hipSuccess && hipEventElapsedTime(&ms, p.e0, p.e1) == hipSuccess) {
+            g_ms[p.group] += ms;
+            g_launches[p.group] += 1;
+        }
+        (void)hipEventDestroy(p.e0);
+        (void)hipEventDestroy(p.e1);
+    }
+    g_pending.clear();
+}
+
+// ---------------------------------------------------------------- prefix sum
+// Three launches: per-block totals, one block scanning the totals, per-block
+// local scan plus base.  Each block covers SCAN_TILE consecutive elements.
+constexpr int SCAN_THREADS = 256;
+constexpr int SCAN_PER_THREAD = 16;
+constexpr int SCAN_TILE = SCAN_THREADS * SCAN_PER_THREAD;
+
+__device__ __forceinline__ int64_t block_exclusive_scan_i64(int64_t x, int64_t *total, int64_t *lds /* [SCAN_THREADS/64 + 1] */)
+{
+    // wave-level inclusive scan by shuffles, then across the block's waves through LDS
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    int64_t incl = x;
+    for (int d = 1; d < 64; d <<= 1) {
+        int64_t y = __shfl_up(incl, d, 64);
+        if (lane >= d) incl += y;
+    }
+    if (lane == 63) lds[wave] = incl;
+    __syncthreads();
+    int64_t base = 0, tot = 0;
+    const int nw = blockDim.x >> 6;
+    for (int w = 0; w < nw; ++w) {
+        int64_t s = lds[w];
+        if (w < wave) base += s;
+        tot += s;
+    }
+    __syncthreads();
+    *total = tot;
+    return base + incl - x;
+}
+
+__global__ void __launch_bounds__(SCAN_THREADS) scan_block_totals(const int32_t *__restrict__ in, int64_t n, int64_t *__restrict__ block_tot)
+{
+    __shared__ int64_t lds[SCAN_THREADS / 64 + 1];
+    const int64_t base = (int64_t)blockIdx.x * SCAN_TILE;
+    int64_t s = 0;
+    for (int k = 0; k < SCAN_PER_THREAD; ++k) {
+        int64_t i = base + (int64_t)k * SCAN_THREADS + threadIdx.x;
+        if (i < n) s += in[i];
+    }
+    int64_t tot;
+    (void)block_exclusive_scan_i64(s, &tot, lds);
+    if (threadIdx.x == 0) block_tot[blockIdx.x] = tot;
+}
+
+__global__ void __launch_bounds__(SCAN_THREADS) scan_of_totals(int64_t *__restrict__ block_tot, int64_t n_blocks, int64_t *__restrict__ grand_total)
+{
+    __shared__ int64_t lds[SCAN_THREADS / 64 + 1];
+    int64_t carry = 0;
+    for (int64_t base = 0; base < n_blocks; base += SCAN_THREADS) {
+        int64_t i = base + threadIdx.x;
+        int64_t x = i < n_blocks ? block_tot[i] : 0;
+        int64_t tot;
+        int64_t ex = block_exclusive_scan_i64(x, &tot, lds);
+        if (i < n_blocks) block_tot[i] = carry + ex;
+        carry += tot;
+    }
+    if (threadIdx.x == 0) *grand_total = carry;
+}
+
+__global__ void __launch_bounds__(SCAN_THREADS) scan_apply(const int32_t *__restrict__ in, int64_t n, const int64_t *__restrict__ block_base,
+                                                           int64_t *__restrict__ out)
+{
+    __shared__ int64_t lds[SCAN_THREADS / 64 + 1];
+    // thread t owns SCAN_PER_THREAD consecutive elements so one block scan suffices
+    const int64_t first = (int64_t)blockIdx.x * SCAN_TILE + (int64_t)threadIdx.x * SCAN_PER_THREAD;
+    int32_t v[SCAN_PER_THREAD];
+    int64_t s = 0;
+    for (int k = 0; k < SCAN_PER_THREAD; ++k) {
+        int64_t i = first + k;
+        v[k] = i < n ? in[i] : 0;
+        s += v[k];
+    }
+    int64_t tot;
+    int64_t run = block_base[blockIdx.x] + block_exclusive_scan_i64(s, &tot, lds);
+    for (int k = 0; k < SCAN_PER_THREAD; ++k) {
+        int64_t i = first + k;
+        if (i < n) out[i] = run;
+        run += v[k];
+    }
+}
+
+rg_status scan_i32_to_i64(const int32_t *in, int64_t *out, int64_t n, Arena &tmp, hipStream_t st)
+{
+    const int64_t n_blocks = (n + SCAN_TILE - 1) / SCAN_TILE;
+    int64_t *block_tot = nullptr;
+    RG_TRY(tmp.dev_n<int64_t>((uint64_t)(n_blocks > 0 ? n_blocks : 1), &block_tot));
+    if (n_blocks > 0)
+        hipLaunchKernelGGL(scan_block_totals, dim3((unsigned)n_blocks), dim3(SCAN_THREADS), 0, st, in, n, block_tot);
+    hipLaunchKernelGGL(scan_of_totals, dim3(1), dim3(SCAN_THREADS), 0, st, block_tot, n_blocks, out + n);
+    if (n_blocks > 0)
+        hipLaunchKernelGGL(scan_apply, dim3((unsigned)n_blocks), dim3(SCAN_THREADS), 0, st, in, n, block_tot, out);
+    RG_HIP(hipGetLastError());
+    return RG_OK;
+}
+
+// ---------------------------------------------------------------- graph validation
+__global__ void validate_rows(int64_t n_nodes, const int64_t *__restrict__ indptr, const int32_t *__restrict__ indices,
+                              unsigned long long *__restrict__ n_bad)
+{
+    // one wave per row, grid-stride
+    const int lane = threadIdx.x & 63;
+    const int64_t wave0 = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) >> 6;
+    const int64_t n_waves = ((int64_t)gridDim.x * blockDim.x) >> 6;
+    unsigned long long bad = 0;
+    for (int64_t v = wave0; v < n_nodes; v += n_waves) {
+        const int64_t b = indptr[v], e = indptr[v + 1];
+        if (e < b || (v == 0 && b != 0)) { if (lane == 0) ++bad; continue; }
+        for (int64_t j = b + lane; j < e; j += 64) {
+            const int32_t u = indices[j];
+            if (u < 0 || u >= n_nodes) ++bad;
+            else if (j > b && indices[j - 1] >= u) ++bad;
+        }
+    }
+    if (bad) atomicAdd(n_bad, bad);
+}
+
+}  // namespace rg
+
+using namespace rg;
+
+extern "C" {
+
+const char *rg_last_error(void) { return g_err; }
+
+void rg_profile_enable(int on) { g_prof_on.store(on ? 1 : 0); }
+
+void rg_profile_reset(void)
+{
+    std::lock_guard<std::mutex> lk(g_prof_mu);
+    drain_pending_locked();
+    for (int i = 0; i < RG_N_KERNEL_GROUPS; ++i) { g_ms[i] = 0.0; g_launches[i] = 0; }
+}
+
+rg_status rg_profile_read(double *ms, uint64_t *launches)
+{
+    if (!ms || !launches) { set_error("rg_profile_read: null output"); return RG_EINVAL; }
+    std::lock_guard<std::mutex> lk(g_prof_mu);
+    drain_pending_locked();
+    for (int i = 0; i < RG_N_KERNEL_GROUPS; ++i) { ms[i] = g_ms[i]; launches[i] = g_launches[i]; }
+    return RG_OK;
+}
+
+rg_status rg_graph_validate(const rg_graph *g, void *stream, uint64_t *n_bad)
+{
+    if (!g || !n_bad || !g->indptr) { set_error("rg_graph_validate: null argument"); return RG_EINVAL; }
+    if (g->n_nodes < 0 || g->n_nodes >= ((int64_t)1 << 31)) { set_error("rg_graph_validate: n_nodes out of range"); return RG_ERANGE; }
+    hipStream_t st = as_stream(stream);
+    unsigned long long *d = nullptr;
+    RG_HIP(hipMalloc((void **)&d, sizeof(unsigned long long)));
+    rg_status rc = RG_OK;
+    do {
+        if (hipMemsetAsync(d, 0, sizeof(unsigned long long), st) != hipSuccess) { rc = RG_EHIP; break; }
+        if (g->n_nodes > 0) {
+            int64_t blocks = (g->n_nodes + 3) / 4;
+            if (blocks > 65536) blocks = 65536;
+            hipLaunchKernelGGL(validate_rows, dim3((unsigned)blocks), dim3(256), 0, st, g->n_nodes, g->indptr, g->indices, d);
+        }
+        unsigned long long h = 0;
+        if (hipMemcpyAsync(&h, d, sizeof(h), hipMemcpyDeviceToHost, st) != hipSuccess) { rc = RG_EHIP; break; }
+        if (hipStreamSynchronize(st) != hipSuccess) { rc = RG_EHIP; break; }
+        *n_bad = h;
+    } while (0);
+    if (rc != RG_OK) set_error("rg_graph_validate: HIP call failed: %s", hipGetErrorString(hipGetLastError()));
+    (void)hipFree(d);
+    return rc;
+}
+
+rg_status rg_schedule_info(const rg_schedule *s, uint32_t *n_batches, uint32_t *L, int64_t *n_nodes)
+{
+    if (!s) { set_error("rg_schedule_info: null schedule"); return RG_EINVAL; }
+    if (n_batches) *n_batches = s->n_batches;
+    if (L) *L = s->L;
+    if (n_nodes) *n_nodes = s->n_nodes;
+    return RG_OK;
+}
+
+rg_status rg_schedule_frontier(const rg_schedule *s, uint32_t hop, const int32_t **ids_dev,
+                               const int64_t **batch_off_dev, const int64_t **batch_off_host)
+{
+    if (!s) { set_error("rg_schedule_frontier: null schedule"); return RG_EINVAL; }
+    if (hop > s->L) { set_error("rg_schedule_frontier: hop %u > L = %u", hop, s->L); return RG_ERANGE; }
+    const HopData &h = s->hop[hop];
+    if (ids_dev) *ids_dev = h.ids;
+    if (batch_off_dev) *batch_off_dev = h.off_dev;
+    if (batch_off_host) *batch_off_host = h.off_host.data();
+    return RG_OK;
+}
+
+rg_status rg_schedule_samples(const rg_schedule *s, uint32_t hop, const int64_t **samp_off_dev,
+                              const int32_t **samp_nbr_dev, int64_t *n_samples)
+{
+    if (!s) { set_error("rg_schedule_samples: null schedule"); return RG_EINVAL; }
+    if (hop >= s->L) { set_error("rg_schedule_samples: hop %u >= L = %u", hop, s->L); return RG_ERANGE; }
+    const HopData &h = s->hop[hop];
+    if (samp_off_dev) *samp_off_dev = h.samp_off;
+    if (samp_nbr_dev) *samp_nbr_dev = h.samp_nbr;
+    if (n_samples) *n_samples = h.n_samples;
+    return RG_OK;
+}
+
+rg_status rg_cache_view(const rg_cache *c, uint64_t *K_eff, const int32_t **cache_ids_dev, const uint32_t **freq_dev,
+                        const int32_t **slot_of_dev, const void **rows_dev, uint64_t *stride)
+{
+    if (!c) { set_error("rg_cache_view: null cache"); return RG_EINVAL; }
+    if (K_eff) *K_eff = c->K_eff;
+    if (cache_ids_dev) *cache_ids_dev = c->cache_ids;
+    if (freq_dev) *freq_dev = c->freq;
+    if (slot_of_dev) *slot_of_dev = c->slot_of;
+    if (rows_dev) *rows_dev = c->rows;
+    if (stride) *stride = c->stride;
+    return RG_OK;
+}
+
+void rg_schedule_destroy(rg_schedule *s) { delete s; }
+
+void rg_cache_destroy(rg_cache *c)
+{
+    if (!c) return;
+    if (c->ev_fork) (void)hipEventDestroy(c->ev_fork);
+    if (c->ev_join) (void)hipEventDestroy(c->ev_join);
+    delete c;
+}
+
+}  // extern "C"

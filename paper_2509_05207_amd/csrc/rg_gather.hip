@@ -1,0 +1,232 @@
+// rg_gather_batch: the feature block of one batch (Alg. 1 inner loop).
+//
+// A row is a run of bytes; each row is copied by a group of G lanes (G a power
+// of two, chosen so that one pass of the group covers the row when it can), in
+// vectors of up to 16 bytes per lane, several rows in flight per group.  The
+// source of a row comes from its 8-byte routing entry: local table, cache
+// table or remote table.  The miss set is copied by the same kernel over the
+// batch's miss list, on the side stream, reading the remote table directly
+// (pinned host memory is mapped into the device's address space, so SyncPull
+// is a kernel whose loads cross the host link; no host-side packing).
+#include "rg_internal.h"
+
+#include <algorithm>
+
+namespace rg {
+
+template <int W> struct VecT;
+template <> struct VecT<16> { using type = uint4; };
+template <> struct VecT<8> { using type = uint2; };
+template <> struct VecT<4> { using type = uint32_t; };
+template <> struct VecT<2> { using type = uint16_t; };
+template <> struct VecT<1> { using type = uint8_t; };
+
+template <int W>
+__device__ __forceinline__ void copy_piece(const uint8_t *src, uint8_t *dst)
+{
+    using T = typename VecT<W>::type;
+    *reinterpret_cast<T *>(dst) = *reinterpret_cast<const T *>(src);
+}
+
+template <int VEC>
+__device__ __forceinline__ void copy_tail(const uint8_t *src, uint8_t *dst, uint32_t tail)
+{
+    // tail < VEC; pieces of decreasing power-of-two width stay aligned because the offset so far is a multiple of VEC
+    if constexpr (VEC > 8) { if (tail & 8u) { copy_piece<8>(src, dst); src += 8; dst += 8; } }
+    if constexpr (VEC > 4) { if (tail & 4u) { copy_piece<4>(src, dst); src += 4; dst += 4; } }
+    if constexpr (VEC > 2) { if (tail & 2u) { copy_piece<2>(src, dst); src += 2; dst += 2; } }
+    if constexpr (VEC > 1) { if (tail & 1u) { copy_piece<1>(src, dst); } }
+}
+
+constexpr int GATHER_THREADS = 256;
+constexpr int ROWS_IN_FLIGHT = 4;
+
+template <int VEC>
+__global__ void __launch_bounds__(GATHER_THREADS) gather_rows_kernel(const int64_t *__restrict__ entries, int64_t n_rows,
+                                                                     const int32_t *__restrict__ list, int64_t n_list, int mode,
+                                                                     RowSources src, uint32_t row_bytes, uint32_t group_lanes,
+                                                                     uint8_t *__restrict__ out, uint64_t out_stride)
+{
+    using T = typename VecT<VEC>::type;
+    const uint32_t cpr = row_bytes / VEC, tail = row_bytes % VEC;
+    const uint32_t G = group_lanes;                               // power of two <= 64
+    const uint32_t lane_g = threadIdx.x & (G - 1);
+    const int64_t group = ((int64_t)blockIdx.x * GATHER_THREADS + threadIdx.x) / G;
+    const int64_t n_groups = ((int64_t)gridDim.x * GATHER_THREADS) / G;
+    const int64_t n_work = list ? n_list : n_rows;
+
+    for (int64_t r0 = group * ROWS_IN_FLIGHT; r0 < n_work; r0 += n_groups * ROWS_IN_FLIGHT) {
+        const uint8_t *sp[ROWS_IN_FLIGHT];
+        uint8_t *dp[ROWS_IN_FLIGHT];
+        bool ok[ROWS_IN_FLIGHT];
+#pragma unroll
+        for (int k = 0; k < ROWS_IN_FLIGHT; ++k) {
+            const int64_t w = r0 + k;
+            ok[k] = w < n_work;
+            sp[k] = nullptr; dp[k] = nullptr;
+            if (ok[k]) {
+                const int64_t r = list ? (int64_t)list[w] : w;
+                const int64_t e = entries[r];
+                const int64_t tag = e >> TAG_SHIFT, row = e & ROW_MASK;
+                if (mode == 0 && tag == TAG_REMOTE) ok[k] = false;
+                else {
+                    sp[k] = tag == TAG_LOCAL ? src.local_rows + (uint64_t)row * src.local_stride
+                          : tag == TAG_CACHE ? src.cache_rows + (uint64_t)row * src.cache_stride
+                                             : src.remote_rows + (uint64_t)row * src.remote_stride;
+                    dp[k] = out + (uint64_t)r * out_stride;
+                }
+            }
+        }
+        for (uint32_t c = lane_g; c < cpr; c += G) {
+            T v[ROWS_IN_FLIGHT];
+#pragma unroll
+            for (int k = 0; k < ROWS_IN_FLIGHT; ++k)
+                if (ok[k]) v[k] = *reinterpret_cast<const T *>(sp[k] + (uint64_t)c * VEC);
+#pragma unroll
+            for (int k = 0; k < ROWS_IN_FLIGHT; ++k)
+                if (ok[k]) *reinterpret_cast<T *>(dp[k] + (uint64_t)c * VEC) = v[k];
+        }
+        if (tail) {
+#pragma unroll
+            for (int k = 0; k < ROWS_IN_FLIGHT; ++k)
+                if (ok[k] && lane_g == (uint32_t)k % G) copy_tail<VEC>(sp[k] + (uint64_t)cpr * VEC, dp[k] + (uint64_t)cpr * VEC, tail);
+        }
+    }
+}
+
+static int common_alignment(const RowSources &s, const uint8_t *out, uint64_t out_stride)
+{
+    uint64_t bits = (uint64_t)(uintptr_t)s.local_rows | s.local_stride | (uint64_t)(uintptr_t)s.cache_rows | s.cache_stride |
+                    (uint64_t)(uintptr_t)s.remote_rows | s.remote_stride | (uint64_t)(uintptr_t)out | out_stride;
+    if ((bits & 15) == 0) return 16;
+    if ((bits & 7) == 0) return 8;
+    if ((bits & 3) == 0) return 4;
+    return 1;
+}
+
+rg_status launch_gather(const int64_t *entries, int64_t n_rows, const int32_t *list, int64_t n_list, int mode, const RowSources &src,
+                        uint32_t row_bytes, uint8_t *out, uint64_t out_stride, hipStream_t st, int group)
+{
+    const int64_t n_work = list ? n_list : n_rows;
+    if (n_work <= 0) return RG_OK;
+    const int vec = common_alignment(src, out, out_stride);
+    const uint32_t cpr = std::max<uint32_t>(1, row_bytes / (uint32_t)vec);
+    uint32_t G = 1;
+    while (G < 64 && G < cpr) G <<= 1;
+    int dev = 0, n_cu = 256;
+    RG_HIP(hipGetDevice(&dev));
+    RG_HIP(hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, dev));
+    const int64_t groups_per_block = GATHER_THREADS / G;
+    int64_t blocks = (n_work + groups_per_block * ROWS_IN_FLIGHT - 1) / (groups_per_block * ROWS_IN_FLIGHT);
+    blocks = std::max<int64_t>(1, std::min<int64_t>(blocks, (int64_t)n_cu * 32));
+    ScopedTimer tm(group, st);
+    switch (vec) {
+    case 16: hipLaunchKernelGGL(gather_rows_kernel<16>, dim3((unsigned)blocks), dim3(GATHER_THREADS), 0, st, entries, n_rows, list, n_list, mode, src, row_bytes, G, out, out_stride); break;
+    case 8:  hipLaunchKernelGGL(gather_rows_kernel<8>, dim3((unsigned)blocks), dim3(GATHER_THREADS), 0, st, entries, n_rows, list, n_list, mode, src, row_bytes, G, out, out_stride); break;
+    case 4:  hipLaunchKernelGGL(gather_rows_kernel<4>, dim3((unsigned)blocks), dim3(GATHER_THREADS), 0, st, entries, n_rows, list, n_list, mode, src, row_bytes, G, out, out_stride); break;
+    default: hipLaunchKernelGGL(gather_rows_kernel<1>, dim3((unsigned)blocks), dim3(GATHER_THREADS), 0, st, entries, n_rows, list, n_list, mode, src, row_bytes, G, out, out_stride); break;
+    }
+    RG_HIP(hipGetLastError());
+    return RG_OK;
+}
+
+// Routing of a single batch computed on the spot (no cache, or a schedule the cache has no plan for).
+__global__ void route_batch_kernel(const int32_t *__restrict__ ids, int64_t n, const uint8_t *__restrict__ is_local, const int32_t *__restrict__ row_of,
+                                   const int32_t *__restrict__ slot_of, int64_t *__restrict__ entry, unsigned long long *__restrict__ counts /* local, hit, miss */)
+{
+    const int64_t j = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    int64_t tag = -1;
+    if (j < n) {
+        const int32_t v = ids[j];
+        int64_t row;
+        if (is_local[v]) { tag = TAG_LOCAL; row = row_of[v]; }
+        else {
+            const int32_t slot = slot_of ? slot_of[v] : -1;
+            if (slot >= 0) { tag = TAG_CACHE; row = slot; }
+            else { tag = TAG_REMOTE; row = row_of[v]; }
+        }
+        entry[j] = (tag << TAG_SHIFT) | row;
+    }
+    const unsigned long long ml = __ballot(tag == TAG_LOCAL), mh = __ballot(tag == TAG_CACHE), mm = __ballot(tag == TAG_REMOTE);
+    if ((threadIdx.x & 63) == 0) {
+        if (ml) atomicAdd(&counts[0], (unsigned long long)__popcll(ml));
+        if (mh) atomicAdd(&counts[1], (unsigned long long)__popcll(mh));
+        if (mm) atomicAdd(&counts[2], (unsigned long long)__popcll(mm));
+    }
+}
+
+}  // namespace rg
+
+using namespace rg;
+
+extern "C" rg_status rg_gather_batch(const rg_schedule *s, const rg_cache *c, const rg_features *f, uint32_t batch, void *out,
+                                     uint64_t out_stride, uint64_t out_capacity_rows, void *stream, void *side_stream,
+                                     rg_gather_stats *stats)
+{
+    if (!s || !f) { set_error("rg_gather_batch: null schedule or features"); return RG_EINVAL; }
+    if (batch >= s->n_batches) { set_error("rg_gather_batch: batch %u >= n_batches = %u", batch, s->n_batches); return RG_ERANGE; }
+    if (f->row_bytes == 0 || out_stride < f->row_bytes || f->local_stride < f->row_bytes || f->remote_stride < f->row_bytes) {
+        set_error("rg_gather_batch: row_bytes = %u with strides out %llu local %llu remote %llu", f->row_bytes,
+                  (unsigned long long)out_stride, (unsigned long long)f->local_stride, (unsigned long long)f->remote_stride);
+        return RG_EINVAL;
+    }
+    if (c && (c->n_nodes != s->n_nodes || c->row_bytes != f->row_bytes)) { set_error("rg_gather_batch: cache does not match schedule / features"); return RG_EINVAL; }
+    const HopData &h = s->hop[s->L];
+    const int64_t off = h.off_host[batch];
+    const int64_t m = h.off_host[batch + 1] - off;
+    if ((uint64_t)m > out_capacity_rows) {
+        set_error("rg_gather_batch: batch %u has %lld rows, output holds %llu", batch, (long long)m, (unsigned long long)out_capacity_rows);
+        return RG_ERANGE;
+    }
+    if (m > 0 && !out) { set_error("rg_gather_batch: null output"); return RG_EINVAL; }
+    hipStream_t st = as_stream(stream);
+    hipStream_t side = side_stream ? as_stream(side_stream) : st;
+    RowSources src{(const uint8_t *)f->local_rows, f->local_stride, c ? (const uint8_t *)c->rows : (const uint8_t *)f->local_rows,
+                   c ? c->stride : f->local_stride, (const uint8_t *)f->remote_rows, f->remote_stride};
+
+    const Plan *plan = nullptr;
+    if (c)
+        for (const Plan &p : c->plans)
+            if (p.schedule_uid == s->uid) { plan = &p; break; }
+
+    if (plan) {
+        const int64_t n_miss = plan->miss_off[batch + 1] - plan->miss_off[batch];
+        const int64_t *entries = plan->entry + off;
+        if (n_miss > 0 && side != st) {
+            RG_HIP(hipEventRecord(c->ev_fork, st));            // earlier work on `stream` may still use `out`
+            RG_HIP(hipStreamWaitEvent(side, c->ev_fork, 0));
+            RG_TRY(launch_gather(entries, m, plan->miss_rows + plan->miss_off[batch], n_miss, 1, src, f->row_bytes, (uint8_t *)out, out_stride, side, KG_MISS));
+            RG_HIP(hipEventRecord(c->ev_join, side));
+            RG_TRY(launch_gather(entries, m, nullptr, 0, 0, src, f->row_bytes, (uint8_t *)out, out_stride, st, KG_GATHER));
+            RG_HIP(hipStreamWaitEvent(st, c->ev_join, 0));
+        } else {
+            RG_TRY(launch_gather(entries, m, nullptr, 0, 0, src, f->row_bytes, (uint8_t *)out, out_stride, st, KG_GATHER));
+            if (n_miss > 0)
+                RG_TRY(launch_gather(entries, m, plan->miss_rows + plan->miss_off[batch], n_miss, 1, src, f->row_bytes, (uint8_t *)out, out_stride, st, KG_MISS));
+        }
+        if (stats) *stats = plan->stats[batch];
+        return RG_OK;
+    }
+
+    // No prepared plan: classify this batch now, copy every row on `stream`, wait for the counts.
+    Arena tmp(nullptr);
+    int64_t *entry = nullptr;
+    unsigned long long *counts = nullptr;
+    RG_TRY(tmp.dev_n<int64_t>((uint64_t)m, &entry));
+    RG_TRY(tmp.dev_n<unsigned long long>(3, &counts));
+    RG_HIP(hipMemsetAsync(counts, 0, 3 * sizeof(unsigned long long), st));
+    if (m > 0) {
+        {
+            ScopedTimer tm(KG_PLAN, st);
+            hipLaunchKernelGGL(route_batch_kernel, dim3((unsigned)((m + 255) / 256)), dim3(256), 0, st, h.ids + off, m, f->is_local, f->row_of,
+                               c ? c->slot_of : nullptr, entry, counts);
+        }
+        RG_HIP(hipGetLastError());
+        RG_TRY(launch_gather(entry, m, nullptr, 0, 1, src, f->row_bytes, (uint8_t *)out, out_stride, st, KG_GATHER));
+    }
+    unsigned long long hc[3] = {0, 0, 0};
+    RG_HIP(hipMemcpyAsync(hc, counts, sizeof(hc), hipMemcpyDeviceToHost, st));
+    RG_HIP(hipStreamSynchronize(st));
+    if (stats) { stats->n_rows = (uint64_t)m; stats->n_local = hc[0]; stats->n_hit = hc[1]; stats->n_miss = hc[2]; }
+    return RG_OK;
+}

@@ -1,0 +1,148 @@
+// Internal declarations shared by the translation units of librapidgnn_hip.so.
+// Nothing in here is part of the ABI (see include/rapidgnn.h).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <stddef.h>
+#include <string>
+#include <vector>
+#include <utility>
+
+#include "rapidgnn.h"
+
+namespace rg {
+
+// ---------------------------------------------------------------- errors
+void set_error(const char *fmt, ...);
+
+#define RG_HIP(call)                                                                        \
+    do {                                                                                    \
+        hipError_t e__ = (call);                                                            \
+        if (e__ != hipSuccess) {                                                            \
+            rg::set_error("%s failed: %s (%s:%d)", #call, hipGetErrorString(e__), __FILE__, \
+                          __LINE__);                                                        \
+            return RG_EHIP;                                                                 \
+        }                                                                                   \
+    } while (0)
+
+#define RG_TRY(expr)                  \
+    do {                              \
+        rg_status s__ = (expr);       \
+        if (s__ != RG_OK) return s__; \
+    } while (0)
+
+// ---------------------------------------------------------------- memory
+// Owns every buffer it hands out; frees them (through the same allocator) on
+// destruction or release_all().
+class Arena {
+  public:
+    explicit Arena(const rg_allocator *a);
+    ~Arena();
+    Arena(const Arena &) = delete;
+    Arena &operator=(const Arena &) = delete;
+
+    // Device memory, 256-byte aligned by the underlying allocator.  bytes == 0
+    // still returns a valid (tiny) allocation so kernels can take the pointer.
+    rg_status dev(uint64_t bytes, void **out);
+    rg_status pinned(uint64_t bytes, void **out);
+    template <typename T> rg_status dev_n(uint64_t n, T **out) { return dev(n * sizeof(T), (void **)out); }
+    void free_one(void *p);     // early release of a single buffer
+    void release_all();
+    uint64_t bytes_in_use() const { return in_use_; }
+
+  private:
+    struct Item { void *p; int kind; uint64_t bytes; };
+    rg_allocator a_;
+    bool custom_;
+    std::vector<Item> items_;
+    uint64_t in_use_ = 0;
+};
+
+// ---------------------------------------------------------------- profiling
+enum KernelGroup {
+    KG_SAMPLER = 0, KG_FRONTIER = 1, KG_SORT = 2, KG_HIST = 3, KG_TOPK = 4,
+    KG_PLAN = 5, KG_FILL = 6, KG_GATHER = 7, KG_MISS = 8, KG_OFFSETS = 9
+};
+bool profiling_on();
+// Records an event pair around a launch when profiling is enabled.
+struct ScopedTimer {
+    ScopedTimer(int group, hipStream_t st);
+    ~ScopedTimer();
+    int group; hipStream_t st; hipEvent_t e0 = nullptr, e1 = nullptr;
+};
+
+// ---------------------------------------------------------------- handles
+struct HopData {
+    int32_t *ids = nullptr;          // dev, frontier U_l, batches concatenated
+    int64_t *off_dev = nullptr;      // dev, [beta + 1]
+    std::vector<int64_t> off_host;   // [beta + 1]
+    int64_t *samp_off = nullptr;     // dev, [|U_l| + 1]  (hops 0..L-1)
+    int32_t *samp_nbr = nullptr;     // dev
+    int64_t n_samples = 0;
+};
+
+}  // namespace rg
+
+struct rg_schedule {
+    rg::Arena arena;
+    int64_t n_nodes = 0;
+    uint32_t n_batches = 0, L = 0;
+    uint64_t T = 0;
+    uint64_t uid = 0;                // identity for plan lookup (pointers can be reused)
+    std::vector<rg::HopData> hop;    // L + 1 entries
+    explicit rg_schedule(const rg_allocator *a) : arena(a) {}
+};
+
+namespace rg {
+
+struct Plan {
+    uint64_t schedule_uid = 0;
+    int64_t *entry = nullptr;            // dev, [|U_L| total]: (tag << 62) | source row
+    int32_t *miss_rows = nullptr;        // dev, output-row index of every miss, batches concatenated
+    std::vector<int64_t> miss_off;       // host, [beta + 1]
+    std::vector<rg_gather_stats> stats;  // host, [beta]
+};
+
+constexpr int64_t TAG_LOCAL = 0, TAG_CACHE = 1, TAG_REMOTE = 2;
+constexpr int TAG_SHIFT = 62;
+constexpr int64_t ROW_MASK = ((int64_t)1 << TAG_SHIFT) - 1;
+
+}  // namespace rg
+
+struct rg_cache {
+    rg::Arena arena;
+    int64_t n_nodes = 0;
+    uint64_t K_eff = 0;
+    uint32_t row_bytes = 0;
+    uint64_t stride = 0;
+    int32_t *cache_ids = nullptr;    // dev, ascending
+    uint32_t *freq = nullptr;        // dev, [n_nodes]
+    int32_t *slot_of = nullptr;      // dev, [n_nodes]
+    void *rows = nullptr;            // dev, K_eff * stride
+    std::vector<rg::Plan> plans;
+    hipEvent_t ev_fork = nullptr, ev_join = nullptr;
+    explicit rg_cache(const rg_allocator *a) : arena(a) {}
+};
+
+namespace rg {
+
+// ---------------------------------------------------------------- shared device-side helpers (host launchers)
+// Exclusive prefix sum of n int32 counts into n + 1 int64 offsets (out[n] = total).
+rg_status scan_i32_to_i64(const int32_t *in, int64_t *out, int64_t n, Arena &tmp, hipStream_t st);
+
+// Copies rows selected by plan entries; see rg_gather.hip.
+struct RowSources {
+    const uint8_t *local_rows; uint64_t local_stride;
+    const uint8_t *cache_rows; uint64_t cache_stride;
+    const uint8_t *remote_rows; uint64_t remote_stride;
+};
+// mode 0: copy rows whose tag is local or cache (skip misses); mode 1: copy every row;
+// list != nullptr: only the rows list[0..n_list) (used for the miss set).
+rg_status launch_gather(const int64_t *entries, int64_t n_rows, const int32_t *list, int64_t n_list, int mode,
+                        const RowSources &src, uint32_t row_bytes, uint8_t *out, uint64_t out_stride,
+                        hipStream_t st, int group);
+
+inline hipStream_t as_stream(void *p) { return reinterpret_cast<hipStream_t>(p); }
+
+}  // namespace rg

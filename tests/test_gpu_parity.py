@@ -1,0 +1,275 @@
+"""GPU parity: the HIP library against the CPU oracle, element by element, through the C ABI.
+
+Integer and byte work throughout, so the bar is bit-exact equality."""
+import numpy as np
+import pytest
+import torch
+
+from paper_2509_05207_amd import synth
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def rg():
+    from paper_2509_05207_amd import binding
+    binding.lib()
+    assert torch.cuda.is_available(), "GPU tests need a GPU"
+    return binding
+
+
+def np_bytes(t):
+    return t.contiguous().view(torch.uint8).cpu().numpy()
+
+
+class Case:
+    """One workload, built by the oracle on the host and by the library on the device."""
+
+    def __init__(self, name, orc, rg, s0=0, worker=0, epoch=0, pinned_remote=False):
+        w = synth.make_workload(name)
+        self.w, self.name = w, name
+        self.s0, self.worker, self.epoch = s0, worker, epoch
+        self.osched = orc.Schedule(w.indptr.numpy(), w.indices.numpy(), w.train.numpy(), w.cfg.batch_size, w.cfg.fanout,
+                                   s0, worker, epoch, n_threads=8)
+        self.ofeat = orc.Features(w.is_local.numpy(), w.row_of.numpy(), np_bytes(w.local_rows), w.stride_bytes,
+                                  np_bytes(w.remote_rows), w.stride_bytes, w.row_bytes)
+        d = "cuda"
+        self.indptr, self.indices, self.train = w.indptr.to(d), w.indices.to(d), w.train.to(d)
+        self.is_local, self.row_of = w.is_local.to(d), w.row_of.to(d)
+        self.local_rows = w.local_rows.to(d)
+        self.remote_rows = w.remote_rows.pin_memory() if pinned_remote else w.remote_rows.to(d)
+        self.gsched = rg.rg_build_schedule(self.indptr, self.indices, self.train, w.cfg.batch_size, w.cfg.fanout, s0, worker, epoch)
+        self.gfeat = rg.make_features(self.is_local, self.row_of, self.local_rows, self.remote_rows, w.row_bytes)
+
+
+@pytest.fixture(scope="module", params=["small", "tiny", "mid", "mid_bf16"])
+def case(request, orc, rg):
+    return Case(request.param, orc, rg, s0=request.param_index, worker=request.param_index % 2, epoch=request.param_index % 3,
+                pinned_remote=(request.param in ("small", "mid_bf16")))
+
+
+def assert_schedules_equal(rg, gs, osched):
+    assert gs.n_batches == osched.n_batches and gs.L == osched.L
+    for hop in range(osched.L + 1):
+        ids, off = osched.frontier(hop)
+        gids, goff_dev, goff = rg.rg_schedule_frontier(gs, hop)
+        assert np.array_equal(goff, off), f"frontier offsets differ at hop {hop}"
+        assert np.array_equal(goff_dev.cpu().numpy(), off)
+        assert np.array_equal(gids.cpu().numpy(), ids), f"frontier ids differ at hop {hop}"
+    for hop in range(osched.L):
+        so, nb = osched.samples(hop)
+        gso, gnb = rg.rg_schedule_samples(gs, hop)
+        assert np.array_equal(gso.cpu().numpy(), so), f"sample offsets differ at hop {hop}"
+        assert np.array_equal(gnb.cpu().numpy(), nb), f"sampled neighbours differ at hop {hop}"
+
+
+def test_schedule_matches_oracle(case, rg):
+    assert rg.rg_graph_validate(case.indptr, case.indices) == 0
+    assert_schedules_equal(rg, case.gsched, case.osched)
+
+
+def test_schedule_is_reproducible_and_seed_dependent(case, rg):
+    w = case.w
+    again = rg.rg_build_schedule(case.indptr, case.indices, case.train, w.cfg.batch_size, w.cfg.fanout, case.s0, case.worker, case.epoch)
+    other = rg.rg_build_schedule(case.indptr, case.indices, case.train, w.cfg.batch_size, w.cfg.fanout, case.s0, case.worker, case.epoch + 1)
+    for hop in range(case.gsched.L + 1):
+        a = rg.rg_schedule_frontier(case.gsched, hop)[0]
+        b = rg.rg_schedule_frontier(again, hop)[0]
+        assert torch.equal(a, b)
+    a = rg.rg_schedule_frontier(case.gsched, 0)[0]
+    c = rg.rg_schedule_frontier(other, 0)[0]
+    assert not torch.equal(a, c)
+
+
+@pytest.mark.parametrize("kmode", ["config", "zero", "all", "one"])
+def test_cache_matches_oracle(case, rg, orc, kmode):
+    w = case.w
+    freq = orc.frequency([case.osched], w.n_nodes)
+    n_cand = int(((w.is_local.numpy() == 0) & (freq > 0)).sum())
+    K = {"config": w.K, "zero": 0, "all": n_cand + 10, "one": 1}[kmode]
+    ids, slot = orc.top_hot(freq, w.is_local.numpy(), K)
+    table = orc.cache_fill(ids, case.ofeat, table_stride=(w.row_bytes + 15) // 16 * 16)
+    gc = rg.rg_build_cache([case.gsched], case.gfeat, K)
+    v = rg.rg_cache_view(gc, w.n_nodes)
+    assert v["K_eff"] == ids.size
+    assert np.array_equal(v["freq"].cpu().numpy().view(np.uint32), freq)
+    assert np.array_equal(v["cache_ids"].cpu().numpy(), ids)
+    assert np.array_equal(v["slot_of"].cpu().numpy(), slot)
+    assert v["stride"] == (w.row_bytes + 15) // 16 * 16
+    got = v["rows"].cpu().numpy().reshape(ids.size, v["stride"])
+    assert np.array_equal(got[:, :w.row_bytes], table[:, :w.row_bytes])
+    assert v["K_eff"] * w.row_bytes <= max(K, 0) * w.row_bytes             # n_hot * d bound of one buffer
+
+
+def check_gather(case, rg, orc, cache, slot, batches, out_stride, use_side_stream):
+    w = case.w
+    ids, off = case.osched.input_nodes()
+    m_max = int(np.diff(off).max())
+    side = torch.cuda.Stream() if use_side_stream else None
+    out = torch.empty((m_max + 3) * out_stride, dtype=torch.uint8, device="cuda")
+    for b in batches:
+        out.fill_(0xCD)
+        st = rg.rg_gather_batch(case.gsched, cache, case.gfeat, b, out, out_stride=out_stride, out_capacity_rows=m_max + 3,
+                                side_stream=side)
+        torch.cuda.synchronize()
+        ref = orc.gather_batch(case.osched, b, case.ofeat, out_stride=out_stride, fill=0xCD)
+        m = ref.shape[0]
+        got = out.cpu().numpy().reshape(m_max + 3, out_stride)
+        assert np.array_equal(got[:m], ref), f"batch {b}: gathered bytes differ"
+        assert np.all(got[m:] == 0xCD), f"batch {b}: rows beyond the batch were written"
+        assert st == orc.batch_stats(case.osched, b, w.is_local.numpy(), slot), f"batch {b}: stats differ"
+
+
+@pytest.mark.parametrize("routing", ["no_cache", "k_zero", "k_config", "k_all"])
+def test_gather_matches_oracle_under_every_routing(case, rg, orc, routing):
+    w = case.w
+    freq = orc.frequency([case.osched], w.n_nodes)
+    nb = case.osched.n_batches
+    batches = sorted({0, nb // 2, nb - 1})
+    if routing == "no_cache":
+        cache, slot = None, None
+    else:
+        K = {"k_zero": 0, "k_config": w.K, "k_all": 10 ** 9}[routing]
+        cache = rg.rg_build_cache([case.gsched], case.gfeat, K)
+        _, slot = orc.top_hot(freq, w.is_local.numpy(), K)
+    for out_stride, side in ((w.row_bytes, False), (w.stride_bytes + 16, True)):
+        check_gather(case, rg, orc, cache, slot, batches, out_stride, side)
+
+
+def test_gather_from_a_cache_built_on_another_epoch(case, rg, orc):
+    """The cache has no plan for this schedule: rows are classified on the fly against its slot table."""
+    w = case.w
+    other_o = orc.Schedule(w.indptr.numpy(), w.indices.numpy(), w.train.numpy(), w.cfg.batch_size, w.cfg.fanout,
+                           case.s0, case.worker, case.epoch + 1, n_threads=8)
+    other_g = rg.rg_build_schedule(case.indptr, case.indices, case.train, w.cfg.batch_size, w.cfg.fanout, case.s0, case.worker, case.epoch + 1)
+    cache = rg.rg_build_cache([other_g], case.gfeat, w.K)
+    _, slot = orc.top_hot(orc.frequency([other_o], w.n_nodes), w.is_local.numpy(), w.K)
+    check_gather(case, rg, orc, cache, slot, [0, case.osched.n_batches - 1], w.stride_bytes, True)
+
+
+def test_cache_over_two_epochs(rg, orc):
+    c = Case("small", orc, rg, s0=5)
+    w = c.w
+    o2 = orc.Schedule(w.indptr.numpy(), w.indices.numpy(), w.train.numpy(), w.cfg.batch_size, w.cfg.fanout, 5, 0, 1)
+    g2 = rg.rg_build_schedule(c.indptr, c.indices, c.train, w.cfg.batch_size, w.cfg.fanout, 5, 0, 1)
+    assert_schedules_equal(rg, g2, o2)
+    freq = orc.frequency([c.osched, o2], w.n_nodes)
+    ids, slot = orc.top_hot(freq, w.is_local.numpy(), w.K)
+    cache = rg.rg_build_cache([c.gsched, g2], c.gfeat, w.K)
+    v = rg.rg_cache_view(cache, w.n_nodes)
+    assert np.array_equal(v["freq"].cpu().numpy().view(np.uint32), freq)
+    assert np.array_equal(v["cache_ids"].cpu().numpy(), ids)
+    # both epochs have a plan in this cache
+    c2 = Case.__new__(Case)
+    c2.__dict__.update(c.__dict__)
+    c2.osched, c2.gsched = o2, g2
+    check_gather(c, rg, orc, cache, slot, [0, 3], w.stride_bytes, True)
+    check_gather(c2, rg, orc, cache, slot, [1, o2.n_batches - 1], w.stride_bytes, False)
+
+
+# ---------------------------------------------------------------- edge cases
+def small_graph():
+    w = synth.make_workload("small")
+    return w, w.indptr.cuda(), w.indices.cuda(), w.train.cuda()
+
+
+def test_degenerate_schedules(rg, orc):
+    w, indptr, indices, train = small_graph()
+    ip, ix, tr = w.indptr.numpy(), w.indices.numpy(), w.train.numpy()
+    for T, B, fan in ((0, 16, [3, 2]), (10, 4, []), (10, 4, [0, 0]), (1, 1000, [2]), (33, 1, [3]), (64, 64, [1, 1, 1, 1, 1, 1, 1, 1])):
+        g = rg.rg_build_schedule(indptr, indices, train[:T], B, fan, 9, 1, 1)
+        o = orc.Schedule(ip, ix, tr[:T], B, fan, 9, 1, 1)
+        assert_schedules_equal(rg, g, o)
+
+
+def test_wide_fanouts_and_long_rows(rg, orc):
+    """Fan-outs on both sides of every candidate-buffer size, rows far longer than the buffer, one hub row."""
+    n = 6000
+    rng = np.random.default_rng(12)
+    deg = rng.integers(0, 700, n)
+    deg[:8] = [0, 1, 63, 64, 65, 255, 256, 5999]
+    rows = [np.sort(rng.choice(np.delete(np.arange(n), v), size=int(d), replace=False)).astype(np.int32) for v, d in enumerate(deg)]
+    indptr = np.zeros(n + 1, np.int64)
+    indptr[1:] = np.cumsum(deg)
+    indices = np.concatenate(rows)
+    train = rng.permutation(n)[:300].astype(np.int32)
+    train[:8] = np.arange(8)
+    dp, dx, dt = torch.from_numpy(indptr).cuda(), torch.from_numpy(indices).cuda(), torch.from_numpy(train).cuda()
+    assert rg.rg_graph_validate(dp, dx) == 0
+    for fan in ([1], [63], [64], [65], [191, 2], [192], [193], [448], [449], [960], [1984], [3, 1984]):
+        g = rg.rg_build_schedule(dp, dx, dt, 37, fan, 1, 0, 0)
+        o = orc.Schedule(indptr, indices, train, 37, fan, 1, 0, 0, n_threads=8)
+        assert_schedules_equal(rg, g, o)
+
+
+def test_errors_are_reported_not_crashes(rg):
+    w, indptr, indices, train = small_graph()
+    with pytest.raises(rg.RgError) as e:
+        rg.rg_build_schedule(indptr, indices, train, 16, [2] * 9)
+    assert e.value.status == rg.RG_ERANGE
+    with pytest.raises(rg.RgError) as e:
+        rg.rg_build_schedule(indptr, indices, train, 16, [1985])
+    assert e.value.status == rg.RG_ERANGE
+    with pytest.raises(rg.RgError) as e:
+        rg.rg_build_schedule(indptr, indices, train, 0, [2])
+    assert e.value.status == rg.RG_EINVAL
+    s = rg.rg_build_schedule(indptr, indices, train, 100, [3, 2])
+    f = rg.make_features(w.is_local.cuda(), w.row_of.cuda(), w.local_rows.cuda(), w.remote_rows.cuda(), w.row_bytes)
+    out = torch.zeros(4 * w.row_bytes, dtype=torch.uint8, device="cuda")
+    with pytest.raises(rg.RgError) as e:
+        rg.rg_gather_batch(s, None, f, 0, out, out_stride=w.row_bytes, out_capacity_rows=4)
+    assert e.value.status == rg.RG_ERANGE
+    assert int(out.sum().item()) == 0                          # nothing written
+    with pytest.raises(rg.RgError) as e:
+        rg.rg_gather_batch(s, None, f, s.n_batches, out, out_stride=w.row_bytes, out_capacity_rows=4)
+    assert e.value.status == rg.RG_ERANGE
+    with pytest.raises(rg.RgError) as e:
+        rg.rg_gather_batch(s, None, f, 0, out, out_stride=w.row_bytes - 1, out_capacity_rows=10 ** 6)
+    assert e.value.status == rg.RG_EINVAL
+
+
+def test_graph_validate_counts_violations(rg):
+    indptr = torch.tensor([0, 3, 5, 5, 8], dtype=torch.int64, device="cuda")
+    good = torch.tensor([1, 2, 3, 0, 2, 0, 1, 2], dtype=torch.int32, device="cuda")
+    assert rg.rg_graph_validate(indptr, good) == 0
+    bad = torch.tensor([2, 1, 3, 0, 0, 0, 1, 9], dtype=torch.int32, device="cuda")     # unsorted, duplicate, out of range
+    assert rg.rg_graph_validate(indptr, bad) == 3
+
+
+def test_torch_backed_allocator(rg, orc):
+    w, indptr, indices, train = small_graph()
+    alloc = rg.TorchAllocator()
+    g = rg.rg_build_schedule(indptr, indices, train, w.cfg.batch_size, w.cfg.fanout, 2, 0, 0, allocator=alloc.struct)
+    o = orc.Schedule(w.indptr.numpy(), w.indices.numpy(), w.train.numpy(), w.cfg.batch_size, w.cfg.fanout, 2, 0, 0)
+    assert_schedules_equal(rg, g, o)
+    assert alloc.n_alloc > 0 and len(alloc.live) > 0
+    f = rg.make_features(w.is_local.cuda(), w.row_of.cuda(), w.local_rows.cuda(), w.remote_rows.cuda(), w.row_bytes)
+    c = rg.rg_build_cache([g], f, w.K, allocator=alloc.struct)
+    ids, _ = orc.top_hot(orc.frequency([o], w.n_nodes), w.is_local.numpy(), w.K)
+    assert np.array_equal(rg.rg_cache_view(c, w.n_nodes)["cache_ids"].cpu().numpy(), ids)
+    del c, g
+    assert len(alloc.live) == 0                                  # everything handed back
+
+
+def test_rows_of_odd_width_and_alignment(rg, orc):
+    """Row widths that force the 8-, 4- and 1-byte paths and the tail pieces."""
+    w, indptr, indices, train = small_graph()
+    ip, ix, tr = w.indptr.numpy(), w.indices.numpy(), w.train.numpy()
+    o = orc.Schedule(ip, ix, tr, 100, [5, 3], 3, 0, 0)
+    g = rg.rg_build_schedule(indptr, indices, train, 100, [5, 3], 3, 0, 0)
+    n_local, n_remote = w.extra["n_local"], w.extra["n_remote"]
+    rng = np.random.default_rng(5)
+    for row_bytes, stride in ((2408, 2416), (2408, 2408), (100, 100), (7, 7), (33, 36), (1, 1), (24, 32), (30, 30)):
+        loc = rng.integers(0, 256, (n_local, stride), dtype=np.uint8)
+        rem = rng.integers(0, 256, (n_remote, stride), dtype=np.uint8)
+        of = orc.Features(w.is_local.numpy(), w.row_of.numpy(), loc, stride, rem, stride, row_bytes)
+        gf = rg.make_features(w.is_local.cuda(), w.row_of.cuda(), torch.from_numpy(loc).cuda(), torch.from_numpy(rem).cuda(), row_bytes,
+                              local_stride=stride, remote_stride=stride)
+        cache = rg.rg_build_cache([g], gf, 200)
+        for out_stride in (stride, stride + 5 if stride % 4 else stride + 8):
+            m = int(np.diff(o.input_nodes()[1]).max())
+            out = torch.full((m * out_stride,), 0xEE, dtype=torch.uint8, device="cuda")
+            rg.rg_gather_batch(g, cache, gf, 1, out, out_stride=out_stride, out_capacity_rows=m)
+            torch.cuda.synchronize()
+            ref = orc.gather_batch(o, 1, of, out_stride=out_stride, fill=0xEE)
+            assert np.array_equal(out.cpu().numpy()[: ref.size].reshape(ref.shape), ref), (row_bytes, stride, out_stride)
