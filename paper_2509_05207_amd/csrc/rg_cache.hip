@@ -182,7 +182,7 @@ __global__ void __launch_bounds__(TOPK_THREADS) select_emit_kernel(const uint32_
 __global__ void fill_entries_kernel(const int32_t *__restrict__ cache_ids, uint64_t k_eff, const int32_t *__restrict__ row_of, int64_t *__restrict__ entries)
 {
     const uint64_t j = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (j < k_eff) entries[j] = (TAG_REMOTE << TAG_SHIFT) | (int64_t)row_of[cache_ids[j]];
+    if (j < k_eff) entries[j] = make_entry(TAG_REMOTE, row_of[cache_ids[j]]);
 }
 
 // ---------------------------------------------------------------- a5/a9: routing plan
@@ -196,41 +196,64 @@ __device__ __forceinline__ uint32_t batch_of_pos(const int64_t *__restrict__ off
     return lo;
 }
 
-// entry[j] for every listed input node, the miss flag (for the miss-list scan) and per-batch counts.
-__global__ void __launch_bounds__(256) plan_kernel(const int32_t *__restrict__ ids, int64_t n, const int64_t *__restrict__ batch_off, uint32_t n_batches,
-                                                   const uint8_t *__restrict__ is_local, const int32_t *__restrict__ row_of,
-                                                   const int32_t *__restrict__ slot_of, int64_t *__restrict__ entry, int32_t *__restrict__ miss_flag,
-                                                   unsigned long long *__restrict__ counts /* [n_batches][2]: local, hit */)
+// route[v] = (tag << 62) | row for every node ID: where a request for v's feature row is served from.
+__global__ void route_table_kernel(int64_t n, const uint8_t *__restrict__ is_local, const int32_t *__restrict__ row_of,
+                                   const int32_t *__restrict__ slot_of, int64_t *__restrict__ route)
 {
-    const int64_t j = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    const bool in = j < n;
-    int64_t tag = -1;
-    uint32_t b = 0;
-    if (in) {
-        const int32_t v = ids[j];
-        b = batch_of_pos(batch_off, n_batches, j);
-        int64_t row;
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    for (int64_t v = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; v < n; v += stride) {
+        int64_t tag, row;
         if (is_local[v]) { tag = TAG_LOCAL; row = row_of[v]; }
         else {
-            const int32_t slot = slot_of ? slot_of[v] : -1;
+            const int32_t slot = slot_of[v];
             if (slot >= 0) { tag = TAG_CACHE; row = slot; }
             else { tag = TAG_REMOTE; row = row_of[v]; }
         }
-        if (entry) entry[j] = (tag << TAG_SHIFT) | row;
-        if (miss_flag) miss_flag[j] = tag == TAG_REMOTE ? 1 : 0;
+        route[v] = make_entry(tag, row);
     }
-    // wave-aggregated counts when the whole wave sits in one batch (the common case)
-    const uint32_t b0 = __shfl(b, 0, 64);
-    const bool uniform = __ballot(in && b != b0) == 0ull;
-    if (uniform) {
-        const unsigned long long ml = __ballot(tag == TAG_LOCAL), mh = __ballot(tag == TAG_CACHE);
-        if ((threadIdx.x & 63) == 0) {
-            if (ml) atomicAdd(&counts[2 * (uint64_t)b0], (unsigned long long)__popcll(ml));
-            if (mh) atomicAdd(&counts[2 * (uint64_t)b0 + 1], (unsigned long long)__popcll(mh));
+}
+
+// entry[j] = route[ids[j]] for every listed input node, the miss flag (for the miss-list scan) and
+// per-batch counts of local rows and cache hits.  A block covers PLAN_TILE consecutive positions and
+// adds its counts once when it lies inside one batch (nearly always), else position by position.
+constexpr int PLAN_THREADS = 256;
+constexpr int PLAN_PER_THREAD = 4;
+constexpr int PLAN_TILE = PLAN_THREADS * PLAN_PER_THREAD;
+
+__global__ void __launch_bounds__(PLAN_THREADS) plan_kernel(const int32_t *__restrict__ ids, int64_t n, const int64_t *__restrict__ batch_off, uint32_t n_batches,
+                                                            const int64_t *__restrict__ route, int64_t *__restrict__ entry, int32_t *__restrict__ miss_flag,
+                                                            unsigned long long *__restrict__ counts /* [n_batches][2]: local, hit */)
+{
+    __shared__ unsigned int red[2][PLAN_THREADS / 64];
+    const int64_t tile0 = (int64_t)blockIdx.x * PLAN_TILE;
+    const int64_t tile_last = (tile0 + PLAN_TILE <= n ? tile0 + PLAN_TILE : n) - 1;
+    const uint32_t b_first = batch_of_pos(batch_off, n_batches, tile0);
+    const bool one_batch = batch_off[b_first + 1] > tile_last;                 // block-uniform
+    unsigned int n_local = 0, n_hit = 0;
+#pragma unroll
+    for (int k = 0; k < PLAN_PER_THREAD; ++k) {
+        const int64_t j = tile0 + (int64_t)k * PLAN_THREADS + threadIdx.x;
+        if (j < n) {
+            const int64_t e = route[ids[j]];
+            const int64_t tag = entry_tag(e);
+            entry[j] = e;
+            miss_flag[j] = tag == TAG_REMOTE ? 1 : 0;
+            if (one_batch) { n_local += tag == TAG_LOCAL; n_hit += tag == TAG_CACHE; }
+            else if (tag != TAG_REMOTE) {
+                const uint32_t b = batch_of_pos(batch_off, n_batches, j);
+                atomicAdd(&counts[2 * (uint64_t)b + (tag == TAG_CACHE ? 1 : 0)], 1ull);
+            }
         }
-    } else if (in) {
-        if (tag == TAG_LOCAL) atomicAdd(&counts[2 * (uint64_t)b], 1ull);
-        else if (tag == TAG_CACHE) atomicAdd(&counts[2 * (uint64_t)b + 1], 1ull);
+    }
+    if (!one_batch) return;
+    for (int o = 32; o > 0; o >>= 1) { n_local += __shfl_down(n_local, o, 64); n_hit += __shfl_down(n_hit, o, 64); }
+    if ((threadIdx.x & 63) == 0) { red[0][threadIdx.x >> 6] = n_local; red[1][threadIdx.x >> 6] = n_hit; }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        unsigned int a = 0, h = 0;
+        for (int w = 0; w < PLAN_THREADS / 64; ++w) { a += red[0][w]; h += red[1][w]; }
+        if (a) atomicAdd(&counts[2 * (uint64_t)b_first], (unsigned long long)a);
+        if (h) atomicAdd(&counts[2 * (uint64_t)b_first + 1], (unsigned long long)h);
     }
 }
 
@@ -250,9 +273,9 @@ __global__ void miss_offsets_kernel(const int64_t *__restrict__ miss_scan, const
     if (b <= n_batches) miss_off[b] = miss_scan[batch_off[b]];
 }
 
-// Routing + counts of one schedule against (is_local, slot_of).  want_plan: keep entries and
-// miss lists in `keep`; otherwise everything lives in `tmp`.
-rg_status build_plan(const rg_schedule *s, const rg_features *f, const int32_t *slot_of, Arena &keep, Arena &tmp, hipStream_t st, Plan *plan)
+// Routing entries, miss lists and counts of one schedule from the per-node route table.  What the
+// plan keeps lives in `keep`; scratch in `tmp`.
+rg_status build_plan(const rg_schedule *s, const int64_t *route, Arena &keep, Arena &tmp, hipStream_t st, Plan *plan)
 {
     const uint32_t beta = s->n_batches;
     const HopData &h = s->hop[s->L];
@@ -274,8 +297,8 @@ rg_status build_plan(const rg_schedule *s, const rg_features *f, const int32_t *
     {
         ScopedTimer tm(KG_PLAN, st);
         if (n > 0)
-            hipLaunchKernelGGL(plan_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, h.ids, n, h.off_dev, beta, f->is_local, f->row_of,
-                               slot_of, plan->entry, miss_flag, counts);
+            hipLaunchKernelGGL(plan_kernel, dim3((unsigned)((n + PLAN_TILE - 1) / PLAN_TILE)), dim3(PLAN_THREADS), 0, st, h.ids, n, h.off_dev, beta,
+                               route, plan->entry, miss_flag, counts);
         RG_TRY(scan_i32_to_i64(miss_flag, miss_scan, n, tmp, st));
         hipLaunchKernelGGL(miss_offsets_kernel, dim3((beta + 1 + 255) / 256), dim3(256), 0, st, miss_scan, h.off_dev, beta, miss_off_dev);
     }
@@ -308,6 +331,8 @@ static rg_status build_cache_impl(const rg_schedule *const *epochs, uint32_t n_e
     c->n_nodes = n;
     c->row_bytes = f->row_bytes;
     c->stride = ((uint64_t)f->row_bytes + 15) / 16 * 16;
+    c->remote_rows_seen = f->remote_rows;
+    c->remote_is_device = is_device_memory(f->remote_rows);
     Arena tmp(a);
     RG_HIP(hipEventCreateWithFlags(&c->ev_fork, hipEventDisableTiming));
     RG_HIP(hipEventCreateWithFlags(&c->ev_join, hipEventDisableTiming));
@@ -385,7 +410,14 @@ static rg_status build_cache_impl(const rg_schedule *const *epochs, uint32_t n_e
 
     // ---- a5/a9: plans, miss lists and counts for every batch of every epoch
     c->plans.resize(n_epochs);
-    for (uint32_t e = 0; e < n_epochs; ++e) RG_TRY(build_plan(epochs[e], f, c->slot_of, c->arena, tmp, st, &c->plans[e]));
+    int64_t *route = nullptr;
+    RG_TRY(tmp.dev_n<int64_t>((uint64_t)n, &route));
+    if (n > 0) {
+        ScopedTimer tm(KG_PLAN, st);
+        const unsigned grid = (unsigned)std::max<int64_t>(1, std::min<int64_t>((n + 255) / 256, (int64_t)n_cu * 16));
+        hipLaunchKernelGGL(route_table_kernel, dim3(grid), dim3(256), 0, st, n, f->is_local, f->row_of, c->slot_of, route);
+    }
+    for (uint32_t e = 0; e < n_epochs; ++e) RG_TRY(build_plan(epochs[e], route, c->arena, tmp, st, &c->plans[e]));
     RG_HIP(hipStreamSynchronize(st));
     return RG_OK;
 }

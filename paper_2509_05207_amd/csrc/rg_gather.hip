@@ -1,22 +1,30 @@
 // rg_gather_batch: the feature block of one batch (Alg. 1 inner loop).
 //
-// A row is a run of bytes; each row is copied by a group of G lanes (G a power
-// of two, chosen so that one pass of the group covers the row when it can), in
-// vectors of up to 16 bytes per lane, several rows in flight per group.  The
-// source of a row comes from its 8-byte routing entry: local table, cache
-// table or remote table.  The miss set is copied by the same kernel over the
-// batch's miss list, on the side stream, reading the remote table directly
-// (pinned host memory is mapped into the device's address space, so SyncPull
-// is a kernel whose loads cross the host link; no host-side packing).
+// A batch's block is n_rows byte rows; the kernel works on the flat space of
+// (row, vector) pairs so that consecutive lanes copy consecutive vectors of a
+// row and run on into the next row: no lane idles whatever the row width.
+// Each thread keeps CHUNKS_IN_FLIGHT independent loads outstanding before it
+// stores (stores are non-temporal: the block is consumed by a later kernel,
+// not by this one).  The source of a row comes from its 8-byte routing entry:
+// local table, cache table or remote table.
+//
+// The miss set is copied by the same kernel over the batch's miss list.  When
+// the remote table is pinned host memory (mapped into the device's address
+// space) that launch goes to the side stream and its loads cross the host
+// link -- SyncPull without host-side packing or staging.  When the remote
+// table is device memory, one launch on the main stream copies every row.
 #include "rg_internal.h"
 
 #include <algorithm>
 
 namespace rg {
 
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
+
 template <int W> struct VecT;
-template <> struct VecT<16> { using type = uint4; };
-template <> struct VecT<8> { using type = uint2; };
+template <> struct VecT<16> { using type = u32x4; };
+template <> struct VecT<8> { using type = u32x2; };
 template <> struct VecT<4> { using type = uint32_t; };
 template <> struct VecT<2> { using type = uint16_t; };
 template <> struct VecT<1> { using type = uint8_t; };
@@ -39,57 +47,59 @@ __device__ __forceinline__ void copy_tail(const uint8_t *src, uint8_t *dst, uint
 }
 
 constexpr int GATHER_THREADS = 256;
-constexpr int ROWS_IN_FLIGHT = 4;
+constexpr int CHUNKS_IN_FLIGHT = 8;
 
 template <int VEC>
 __global__ void __launch_bounds__(GATHER_THREADS) gather_rows_kernel(const int64_t *__restrict__ entries, int64_t n_rows,
                                                                      const int32_t *__restrict__ list, int64_t n_list, int mode,
-                                                                     RowSources src, uint32_t row_bytes, uint32_t group_lanes,
+                                                                     RowSources src, uint32_t row_bytes,
                                                                      uint8_t *__restrict__ out, uint64_t out_stride)
 {
     using T = typename VecT<VEC>::type;
     const uint32_t cpr = row_bytes / VEC, tail = row_bytes % VEC;
-    const uint32_t G = group_lanes;                               // power of two <= 64
-    const uint32_t lane_g = threadIdx.x & (G - 1);
-    const int64_t group = ((int64_t)blockIdx.x * GATHER_THREADS + threadIdx.x) / G;
-    const int64_t n_groups = ((int64_t)gridDim.x * GATHER_THREADS) / G;
-    const int64_t n_work = list ? n_list : n_rows;
+    const uint32_t cpt = cpr + (tail ? 1u : 0u);                  // pieces per row: full vectors, then the tail piece
+    const uint64_t n_work = (uint64_t)(list ? n_list : n_rows);
+    const uint64_t total = n_work * cpt;
+    const uint64_t n_threads = (uint64_t)gridDim.x * GATHER_THREADS;
+    // flat index -> (work item, piece); advanced by n_threads without dividing again
+    const uint64_t dq = n_threads / cpt;
+    const uint32_t dr = (uint32_t)(n_threads - dq * cpt);
+    uint64_t idx = (uint64_t)blockIdx.x * GATHER_THREADS + threadIdx.x;
+    uint64_t w = idx / cpt;
+    uint32_t c = (uint32_t)(idx - w * cpt);
 
-    for (int64_t r0 = group * ROWS_IN_FLIGHT; r0 < n_work; r0 += n_groups * ROWS_IN_FLIGHT) {
-        const uint8_t *sp[ROWS_IN_FLIGHT];
-        uint8_t *dp[ROWS_IN_FLIGHT];
-        bool ok[ROWS_IN_FLIGHT];
+    while (idx < total) {
+        T v[CHUNKS_IN_FLIGHT];
+        const uint8_t *sp[CHUNKS_IN_FLIGHT];
+        uint8_t *dp[CHUNKS_IN_FLIGHT];
+        int kind[CHUNKS_IN_FLIGHT];                                // 0 nothing, 1 full vector, 2 tail piece
 #pragma unroll
-        for (int k = 0; k < ROWS_IN_FLIGHT; ++k) {
-            const int64_t w = r0 + k;
-            ok[k] = w < n_work;
+        for (int k = 0; k < CHUNKS_IN_FLIGHT; ++k) {
+            kind[k] = 0;
             sp[k] = nullptr; dp[k] = nullptr;
-            if (ok[k]) {
-                const int64_t r = list ? (int64_t)list[w] : w;
+            if (idx < total) {
+                const int64_t r = list ? (int64_t)list[w] : (int64_t)w;
                 const int64_t e = entries[r];
-                const int64_t tag = e >> TAG_SHIFT, row = e & ROW_MASK;
-                if (mode == 0 && tag == TAG_REMOTE) ok[k] = false;
-                else {
-                    sp[k] = tag == TAG_LOCAL ? src.local_rows + (uint64_t)row * src.local_stride
-                          : tag == TAG_CACHE ? src.cache_rows + (uint64_t)row * src.cache_stride
-                                             : src.remote_rows + (uint64_t)row * src.remote_stride;
-                    dp[k] = out + (uint64_t)r * out_stride;
+                const int64_t tag = entry_tag(e), row = entry_row(e);
+                if (!(mode == 0 && tag == TAG_REMOTE)) {
+                    const uint8_t *base = tag == TAG_LOCAL ? src.local_rows + (uint64_t)row * src.local_stride
+                                        : tag == TAG_CACHE ? src.cache_rows + (uint64_t)row * src.cache_stride
+                                                           : src.remote_rows + (uint64_t)row * src.remote_stride;
+                    sp[k] = base + (uint64_t)c * VEC;
+                    dp[k] = out + (uint64_t)r * out_stride + (uint64_t)c * VEC;
+                    kind[k] = c < cpr ? 1 : 2;
+                    if (kind[k] == 1) v[k] = *reinterpret_cast<const T *>(sp[k]);
                 }
             }
+            idx += n_threads;
+            w += dq;
+            c += dr;
+            if (c >= cpt) { c -= cpt; ++w; }
         }
-        for (uint32_t c = lane_g; c < cpr; c += G) {
-            T v[ROWS_IN_FLIGHT];
 #pragma unroll
-            for (int k = 0; k < ROWS_IN_FLIGHT; ++k)
-                if (ok[k]) v[k] = *reinterpret_cast<const T *>(sp[k] + (uint64_t)c * VEC);
-#pragma unroll
-            for (int k = 0; k < ROWS_IN_FLIGHT; ++k)
-                if (ok[k]) *reinterpret_cast<T *>(dp[k] + (uint64_t)c * VEC) = v[k];
-        }
-        if (tail) {
-#pragma unroll
-            for (int k = 0; k < ROWS_IN_FLIGHT; ++k)
-                if (ok[k] && lane_g == (uint32_t)k % G) copy_tail<VEC>(sp[k] + (uint64_t)cpr * VEC, dp[k] + (uint64_t)cpr * VEC, tail);
+        for (int k = 0; k < CHUNKS_IN_FLIGHT; ++k) {
+            if (kind[k] == 1) __builtin_nontemporal_store(v[k], reinterpret_cast<T *>(dp[k]));
+            else if (kind[k] == 2) copy_tail<VEC>(sp[k], dp[k], tail);
         }
     }
 }
@@ -110,24 +120,31 @@ rg_status launch_gather(const int64_t *entries, int64_t n_rows, const int32_t *l
     const int64_t n_work = list ? n_list : n_rows;
     if (n_work <= 0) return RG_OK;
     const int vec = common_alignment(src, out, out_stride);
-    const uint32_t cpr = std::max<uint32_t>(1, row_bytes / (uint32_t)vec);
-    uint32_t G = 1;
-    while (G < 64 && G < cpr) G <<= 1;
+    const uint64_t cpt = row_bytes / (uint32_t)vec + (row_bytes % (uint32_t)vec ? 1 : 0);
     int dev = 0, n_cu = 256;
     RG_HIP(hipGetDevice(&dev));
     RG_HIP(hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, dev));
-    const int64_t groups_per_block = GATHER_THREADS / G;
-    int64_t blocks = (n_work + groups_per_block * ROWS_IN_FLIGHT - 1) / (groups_per_block * ROWS_IN_FLIGHT);
-    blocks = std::max<int64_t>(1, std::min<int64_t>(blocks, (int64_t)n_cu * 32));
+    const uint64_t per_block = (uint64_t)GATHER_THREADS * CHUNKS_IN_FLIGHT;
+    uint64_t blocks = ((uint64_t)n_work * cpt + per_block - 1) / per_block;
+    blocks = std::max<uint64_t>(1, std::min<uint64_t>(blocks, (uint64_t)n_cu * 32));
     ScopedTimer tm(group, st);
     switch (vec) {
-    case 16: hipLaunchKernelGGL(gather_rows_kernel<16>, dim3((unsigned)blocks), dim3(GATHER_THREADS), 0, st, entries, n_rows, list, n_list, mode, src, row_bytes, G, out, out_stride); break;
-    case 8:  hipLaunchKernelGGL(gather_rows_kernel<8>, dim3((unsigned)blocks), dim3(GATHER_THREADS), 0, st, entries, n_rows, list, n_list, mode, src, row_bytes, G, out, out_stride); break;
-    case 4:  hipLaunchKernelGGL(gather_rows_kernel<4>, dim3((unsigned)blocks), dim3(GATHER_THREADS), 0, st, entries, n_rows, list, n_list, mode, src, row_bytes, G, out, out_stride); break;
-    default: hipLaunchKernelGGL(gather_rows_kernel<1>, dim3((unsigned)blocks), dim3(GATHER_THREADS), 0, st, entries, n_rows, list, n_list, mode, src, row_bytes, G, out, out_stride); break;
+    case 16: hipLaunchKernelGGL(gather_rows_kernel<16>, dim3((unsigned)blocks), dim3(GATHER_THREADS), 0, st, entries, n_rows, list, n_list, mode, src, row_bytes, out, out_stride); break;
+    case 8:  hipLaunchKernelGGL(gather_rows_kernel<8>, dim3((unsigned)blocks), dim3(GATHER_THREADS), 0, st, entries, n_rows, list, n_list, mode, src, row_bytes, out, out_stride); break;
+    case 4:  hipLaunchKernelGGL(gather_rows_kernel<4>, dim3((unsigned)blocks), dim3(GATHER_THREADS), 0, st, entries, n_rows, list, n_list, mode, src, row_bytes, out, out_stride); break;
+    default: hipLaunchKernelGGL(gather_rows_kernel<1>, dim3((unsigned)blocks), dim3(GATHER_THREADS), 0, st, entries, n_rows, list, n_list, mode, src, row_bytes, out, out_stride); break;
     }
     RG_HIP(hipGetLastError());
     return RG_OK;
+}
+
+// True when p is device memory (then "remote" rows are plain HBM reads and need no side stream).
+bool is_device_memory(const void *p)
+{
+    if (!p) return false;
+    hipPointerAttribute_t attr;
+    if (hipPointerGetAttributes(&attr, p) != hipSuccess) { (void)hipGetLastError(); return false; }
+    return attr.type == hipMemoryTypeDevice;
 }
 
 // Routing of a single batch computed on the spot (no cache, or a schedule the cache has no plan for).
@@ -145,7 +162,7 @@ __global__ void route_batch_kernel(const int32_t *__restrict__ ids, int64_t n, c
             if (slot >= 0) { tag = TAG_CACHE; row = slot; }
             else { tag = TAG_REMOTE; row = row_of[v]; }
         }
-        entry[j] = (tag << TAG_SHIFT) | row;
+        entry[j] = make_entry(tag, row);
     }
     const unsigned long long ml = __ballot(tag == TAG_LOCAL), mh = __ballot(tag == TAG_CACHE), mm = __ballot(tag == TAG_REMOTE);
     if ((threadIdx.x & 63) == 0) {
@@ -192,7 +209,11 @@ extern "C" rg_status rg_gather_batch(const rg_schedule *s, const rg_cache *c, co
     if (plan) {
         const int64_t n_miss = plan->miss_off[batch + 1] - plan->miss_off[batch];
         const int64_t *entries = plan->entry + off;
-        if (n_miss > 0 && side != st) {
+        const bool remote_in_hbm = n_miss > 0 && (f->remote_rows == c->remote_rows_seen ? c->remote_is_device : is_device_memory(f->remote_rows));
+        if (n_miss == 0 || remote_in_hbm) {
+            // every source is HBM: one launch copies the whole block
+            RG_TRY(launch_gather(entries, m, nullptr, 0, 1, src, f->row_bytes, (uint8_t *)out, out_stride, st, KG_GATHER));
+        } else if (side != st) {
             RG_HIP(hipEventRecord(c->ev_fork, st));            // earlier work on `stream` may still use `out`
             RG_HIP(hipStreamWaitEvent(side, c->ev_fork, 0));
             RG_TRY(launch_gather(entries, m, plan->miss_rows + plan->miss_off[batch], n_miss, 1, src, f->row_bytes, (uint8_t *)out, out_stride, side, KG_MISS));
@@ -201,8 +222,7 @@ extern "C" rg_status rg_gather_batch(const rg_schedule *s, const rg_cache *c, co
             RG_HIP(hipStreamWaitEvent(st, c->ev_join, 0));
         } else {
             RG_TRY(launch_gather(entries, m, nullptr, 0, 0, src, f->row_bytes, (uint8_t *)out, out_stride, st, KG_GATHER));
-            if (n_miss > 0)
-                RG_TRY(launch_gather(entries, m, plan->miss_rows + plan->miss_off[batch], n_miss, 1, src, f->row_bytes, (uint8_t *)out, out_stride, st, KG_MISS));
+            RG_TRY(launch_gather(entries, m, plan->miss_rows + plan->miss_off[batch], n_miss, 1, src, f->row_bytes, (uint8_t *)out, out_stride, st, KG_MISS));
         }
         if (stats) *stats = plan->stats[batch];
         return RG_OK;

@@ -104,9 +104,13 @@ struct Plan {
     std::vector<rg_gather_stats> stats;  // host, [beta]
 };
 
+// Routing entry: source tag in the top two bits, source row below (handled as unsigned bits).
 constexpr int64_t TAG_LOCAL = 0, TAG_CACHE = 1, TAG_REMOTE = 2;
 constexpr int TAG_SHIFT = 62;
-constexpr int64_t ROW_MASK = ((int64_t)1 << TAG_SHIFT) - 1;
+constexpr uint64_t ROW_MASK = ((uint64_t)1 << TAG_SHIFT) - 1;
+__host__ __device__ inline int64_t make_entry(int64_t tag, int64_t row) { return (int64_t)(((uint64_t)tag << TAG_SHIFT) | ((uint64_t)row & ROW_MASK)); }
+__host__ __device__ inline int64_t entry_tag(int64_t e) { return (int64_t)((uint64_t)e >> TAG_SHIFT); }
+__host__ __device__ inline int64_t entry_row(int64_t e) { return (int64_t)((uint64_t)e & ROW_MASK); }
 
 }  // namespace rg
 
@@ -122,6 +126,8 @@ struct rg_cache {
     void *rows = nullptr;            // dev, K_eff * stride
     std::vector<rg::Plan> plans;
     hipEvent_t ev_fork = nullptr, ev_join = nullptr;
+    const void *remote_rows_seen = nullptr;   // the remote table the cache was built over ...
+    bool remote_is_device = false;            // ... and whether it is device memory
     explicit rg_cache(const rg_allocator *a) : arena(a) {}
 };
 
@@ -142,6 +148,9 @@ struct RowSources {
 rg_status launch_gather(const int64_t *entries, int64_t n_rows, const int32_t *list, int64_t n_list, int mode,
                         const RowSources &src, uint32_t row_bytes, uint8_t *out, uint64_t out_stride,
                         hipStream_t st, int group);
+
+// True when p is device memory on the current device (false for pinned host memory).
+bool is_device_memory(const void *p);
 
 inline hipStream_t as_stream(void *p) { return reinterpret_cast<hipStream_t>(p); }
 
