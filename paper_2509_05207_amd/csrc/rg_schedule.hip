@@ -1,5 +1,5 @@
 // rg_build_schedule: seed derivation, epoch shuffle, per-hop fan-out sampling
-// and frontier construction for all batches of an epoch at once.
+// (rg_sampler.hip) and frontier construction for all batches of an epoch.
 //
 // Layout in HBM.  Batches are independent, so a hop is one launch over the
 // concatenated frontiers of every batch.  Per batch the library keeps two
@@ -10,41 +10,15 @@
 // table is involved and the result does not depend on the order in which
 // waves mark bits.
 #include "rg_internal.h"
+#include "rg_device.h"
 
 #include <algorithm>
 #include <atomic>
 
 namespace rg {
 
-// ---------------------------------------------------------------- hash family
-// H of Sec. 3 "Seeding and reproducibility": a 64-bit multiply / xor-shift
-// mixer.  Constants: floor(2^64/phi), frac(sqrt 2) * 2^64 made odd,
-// frac(sqrt 3) * 2^64; the 32-bit ones are the top words of the same numbers.
-constexpr uint64_t HG64 = 0x9E3779B97F4A7C15ull;
-constexpr uint64_t HA64 = 0x6A09E667F3BCC909ull;
-constexpr uint64_t HB64 = 0xBB67AE8584CAA73Bull;
-constexpr uint32_t HG32 = 0x9E3779B9u;
-constexpr uint32_t HA32 = 0x6A09E667u;
-constexpr uint32_t HB32 = 0xBB67AE85u;
-
-__host__ __device__ __forceinline__ uint64_t mix64(uint64_t x)
-{
-    x ^= x >> 32; x *= HA64; x ^= x >> 29; x *= HB64; x ^= x >> 32;
-    return x;
-}
-__host__ __device__ __forceinline__ uint64_t combine(uint64_t h, uint64_t x) { return mix64(h ^ mix64(x + HG64)); }
-
-// Key of neighbour u under a node's state (lo, hi).  For fixed state this is a
-// bijection of 32-bit words, so the keys of one row never tie.
-__device__ __forceinline__ uint32_t key32(uint32_t lo, uint32_t hi, uint32_t u)
-{
-    uint32_t x = u ^ lo;
-    x *= HG32; x ^= x >> 16;
-    x += hi;
-    x *= HA32; x ^= x >> 15;
-    x *= HB32; x ^= x >> 16;
-    return x;
-}
+rg_status sample_hop(const rg_graph *g, HopData &cur, uint32_t beta, const uint64_t *batch_seed, uint32_t hop, uint32_t fanout,
+                     uint32_t *seen, uint32_t *fresh, uint64_t words_per_batch, Arena &keep, Arena &tmp, int n_cu, hipStream_t st);
 
 // ---------------------------------------------------------------- a1/a2: seeds, shuffle keys
 __global__ void batch_seeds_kernel(uint64_t s0, uint32_t worker, uint32_t epoch, uint32_t n_batches, uint64_t *__restrict__ seeds)
@@ -126,171 +100,12 @@ __global__ void apply_shuffle_kernel(const KeyPos *__restrict__ kp, const int32_
     if (t < T) seeds[t] = train[kp[t].pos];
 }
 
-// ---------------------------------------------------------------- batch lookup
-// Batch of flat frontier position i: the b with off[b] <= i < off[b+1].
-__device__ __forceinline__ uint32_t batch_of(const int64_t *__restrict__ off, uint32_t n_batches, int64_t i)
-{
-    uint32_t lo = 0, hi = n_batches;          // invariant: off[lo] <= i < off[hi]
-    while (hi - lo > 1) {
-        const uint32_t mid = (lo + hi) >> 1;
-        if (off[mid] <= i) lo = mid; else hi = mid;
-    }
-    return lo;
-}
-
-// ---------------------------------------------------------------- bitmaps
 __global__ void mark_seeds_kernel(const int32_t *__restrict__ seeds, uint64_t T, uint32_t batch_size, uint32_t *__restrict__ seen, uint64_t words_per_batch)
 {
     const uint64_t t = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (t >= T) return;
     const uint32_t v = (uint32_t)seeds[t];
     atomicOr(&seen[(t / batch_size) * words_per_batch + (v >> 5)], 1u << (v & 31));
-}
-
-// A sampled ID is new to the batch iff its `seen` bit was clear; the wave that
-// flips it also sets the `fresh` bit.  Bits are only ever set here, so the
-// plain pre-check can at worst cause a redundant atomic.
-__device__ __forceinline__ void mark_reached(uint32_t *__restrict__ seen_b, uint32_t *__restrict__ fresh_b, uint32_t u)
-{
-    const uint32_t w = u >> 5, bit = 1u << (u & 31);
-    if (seen_b[w] & bit) return;
-    const uint32_t old = atomicOr(&seen_b[w], bit);
-    if (!(old & bit)) atomicOr(&fresh_b[w], bit);
-}
-
-// ---------------------------------------------------------------- a3: per-node sample sizes
-__global__ void sample_counts_kernel(const int64_t *__restrict__ indptr, const int32_t *__restrict__ frontier, int64_t n, uint32_t fanout,
-                                     int32_t *__restrict__ cnt)
-{
-    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (i >= n) return;
-    const int32_t v = frontier[i];
-    const int64_t deg = indptr[v + 1] - indptr[v];
-    cnt[i] = (int32_t)(deg < (int64_t)fanout ? deg : (int64_t)fanout);
-}
-
-// ---------------------------------------------------------------- a3: the sampler
-// One wavefront per frontier node (grid-stride over nodes), one wave per
-// workgroup.  The row is streamed once, 64 neighbours per step, coalesced.
-// SAMPLE keeps the `fanout` neighbours with the smallest keys.  Candidates
-// (key below the current cut) are appended to an LDS buffer in row order; when
-// the buffer could overflow, the exact fanout-th smallest key among them is
-// found by a bitwise search on ballots and the buffer is compacted in place,
-// still in row order, which also tightens the cut for the rest of the row.
-// What is left after the last step is the sample, already in row order.
-template <int CAP>
-struct Selector {
-    static constexpr int E = CAP / 64;      // buffer entries per lane
-
-    // Keeps the `keep` smallest-key entries of buf[0..cnt), order preserved; returns the cut
-    // (the keep-th smallest key).  Precondition: cnt > keep >= 1, cnt <= CAP.
-    static __device__ __forceinline__ uint32_t prune(uint32_t *buf, int cnt, int keep, uint32_t lo, uint32_t hi, int lane)
-    {
-        uint32_t u[E], k[E];
-        bool valid[E];
-#pragma unroll
-        for (int e = 0; e < E; ++e) {
-            const int idx = e * 64 + lane;
-            valid[e] = idx < cnt;
-            u[e] = valid[e] ? buf[idx] : 0u;
-            k[e] = key32(lo, hi, u[e]);
-        }
-        // largest cut with |{key < cut}| < keep  ==  the keep-th smallest key
-        uint32_t cut = 0;
-        for (int bit = 31; bit >= 0; --bit) {
-            const uint32_t trial = cut | (1u << bit);
-            int below = 0;
-#pragma unroll
-            for (int e = 0; e < E; ++e) below += __popcll(__ballot(valid[e] && k[e] < trial));
-            if (below < keep) cut = trial;
-        }
-        __syncthreads();          // every lane has read its entries before any is overwritten
-        int base = 0;
-#pragma unroll
-        for (int e = 0; e < E; ++e) {
-            const bool keep_it = valid[e] && k[e] <= cut;
-            const unsigned long long m = __ballot(keep_it);
-            if (keep_it) buf[base + __popcll(m & ((1ull << lane) - 1ull))] = u[e];
-            base += __popcll(m);
-        }
-        __syncthreads();
-        return cut;
-    }
-};
-
-template <int CAP>
-__global__ void __launch_bounds__(64) sample_kernel(const int64_t *__restrict__ indptr, const int32_t *__restrict__ indices,
-                                                    const int32_t *__restrict__ frontier, int64_t n_frontier,
-                                                    const int64_t *__restrict__ batch_off, uint32_t n_batches,
-                                                    const uint64_t *__restrict__ batch_seed, uint32_t hop, uint32_t fanout,
-                                                    const int64_t *__restrict__ samp_off, int32_t *__restrict__ samp_nbr,
-                                                    uint32_t *__restrict__ seen, uint32_t *__restrict__ fresh, uint64_t words_per_batch)
-{
-    __shared__ uint32_t buf[CAP];
-    const int lane = threadIdx.x;
-    const int f = (int)fanout;
-    for (int64_t i = blockIdx.x; i < n_frontier; i += gridDim.x) {
-        const int32_t v = frontier[i];
-        const int64_t row_begin = indptr[v];
-        const int64_t deg = indptr[v + 1] - row_begin;
-        if (deg == 0 || f == 0) continue;
-        const uint32_t b = batch_of(batch_off, n_batches, i);
-        uint32_t *seen_b = seen + (uint64_t)b * words_per_batch;
-        uint32_t *fresh_b = fresh + (uint64_t)b * words_per_batch;
-        const int32_t *row = indices + row_begin;
-        int32_t *out = samp_nbr + samp_off[i];
-
-        if (deg <= f) {                       // the whole row is the sample
-            for (int64_t j = lane; j < deg; j += 64) {
-                const int32_t u = row[j];
-                out[j] = u;
-                mark_reached(seen_b, fresh_b, (uint32_t)u);
-            }
-            continue;
-        }
-        const uint64_t S = combine(combine(batch_seed[b], (uint64_t)hop + 1u), (uint64_t)(uint32_t)v);
-        const uint32_t lo = (uint32_t)S, hi = (uint32_t)(S >> 32);
-
-        int cnt = 0;                          // wave-uniform
-        bool open = true;                     // no cut yet: everything is a candidate
-        uint32_t cut = 0;
-        for (int64_t base = 0; base < deg; base += 256) {
-            uint32_t u[4], k[4];
-            bool ok[4];
-#pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                const int64_t j = base + e * 64 + lane;
-                ok[e] = j < deg;
-                u[e] = ok[e] ? (uint32_t)row[j] : 0u;
-            }
-#pragma unroll
-            for (int e = 0; e < 4; ++e) k[e] = key32(lo, hi, u[e]);
-            if (!open) {
-                const bool any = (ok[0] && k[0] < cut) || (ok[1] && k[1] < cut) || (ok[2] && k[2] < cut) || (ok[3] && k[3] < cut);
-                if (__ballot(any) == 0ull) continue;
-            }
-#pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                if (cnt > CAP - 64) {         // the next 64 might not fit: tighten first
-                    cut = Selector<CAP>::prune(buf, cnt, f, lo, hi, lane);
-                    cnt = f;
-                    open = false;
-                }
-                const bool pass = ok[e] && (open || k[e] < cut);
-                const unsigned long long m = __ballot(pass);
-                if (pass) buf[cnt + __popcll(m & ((1ull << lane) - 1ull))] = u[e];
-                cnt += __popcll(m);
-            }
-        }
-        __syncthreads();
-        if (cnt > f) { (void)Selector<CAP>::prune(buf, cnt, f, lo, hi, lane); cnt = f; }
-        for (int j = lane; j < f; j += 64) {
-            const uint32_t u = buf[j];
-            out[j] = (int32_t)u;
-            mark_reached(seen_b, fresh_b, u);
-        }
-        __syncthreads();                      // buffer is reused by the next node
-    }
 }
 
 // ---------------------------------------------------------------- a4: frontier from the fresh bitmap
@@ -402,15 +217,6 @@ static rg_status sort_keypos(KeyPos *kp, uint64_t n_pad, hipStream_t st)
     return RG_OK;
 }
 
-template <int CAP>
-static void launch_sampler(unsigned grid, hipStream_t st, const rg_graph *g, const int32_t *frontier, int64_t n_frontier,
-                           const int64_t *batch_off, uint32_t n_batches, const uint64_t *batch_seed, uint32_t hop, uint32_t fanout,
-                           const int64_t *samp_off, int32_t *samp_nbr, uint32_t *seen, uint32_t *fresh, uint64_t wpb)
-{
-    hipLaunchKernelGGL(sample_kernel<CAP>, dim3(grid), dim3(64), 0, st, g->indptr, g->indices, frontier, n_frontier, batch_off,
-                       n_batches, batch_seed, hop, fanout, samp_off, samp_nbr, seen, fresh, wpb);
-}
-
 static rg_status build_schedule_impl(const rg_graph *g, const int32_t *train, uint64_t T, uint32_t B, const uint32_t *fanout,
                                      uint32_t L, uint64_t s0, uint32_t worker, uint32_t epoch, const rg_allocator *a, hipStream_t st, rg_schedule *s)
 {
@@ -488,36 +294,11 @@ static rg_status build_schedule_impl(const rg_graph *g, const int32_t *train, ui
         HopData &cur = s->hop[l];
         HopData &nxt = s->hop[l + 1];
         const int64_t n_cur = cur.off_host[beta];
-        const uint32_t f = fanout[l];
 
-        // sample sizes -> offsets
-        int32_t *cnt = nullptr;
-        RG_TRY(tmp.dev_n<int32_t>((uint64_t)n_cur, &cnt));
-        RG_TRY(s->arena.dev_n<int64_t>((uint64_t)n_cur + 1, &cur.samp_off));
-        {
-            ScopedTimer tm(KG_OFFSETS, st);
-            hipLaunchKernelGGL(sample_counts_kernel, dim3((unsigned)((n_cur + 255) / 256)), dim3(256), 0, st, g->indptr, cur.ids, n_cur, f, cnt);
-            RG_TRY(scan_i32_to_i64(cnt, cur.samp_off, n_cur, tmp, st));
-        }
-        RG_HIP(hipMemcpyAsync(&cur.n_samples, cur.samp_off + n_cur, sizeof(int64_t), hipMemcpyDeviceToHost, st));
-        RG_HIP(hipStreamSynchronize(st));
-        tmp.free_one(cnt);
-        RG_TRY(s->arena.dev_n<int32_t>((uint64_t)cur.n_samples, &cur.samp_nbr));
+        // a3: the samples of this hop; reached IDs are marked in seen / fresh as they are written
+        RG_TRY(sample_hop(g, cur, beta, batch_seed, l, fanout[l], seen, fresh, wpb, s->arena, tmp, n_cu, st));
 
-        // the sampler, marking reached IDs as it writes them
-        {
-            ScopedTimer tm(KG_SAMPLER, st);
-            const unsigned grid = (unsigned)std::min<int64_t>(n_cur, (int64_t)n_cu * 64);
-            const uint32_t need = f + 64;
-            if (need <= 128) launch_sampler<128>(grid, st, g, cur.ids, n_cur, cur.off_dev, beta, batch_seed, l, f, cur.samp_off, cur.samp_nbr, seen, fresh, wpb);
-            else if (need <= 256) launch_sampler<256>(grid, st, g, cur.ids, n_cur, cur.off_dev, beta, batch_seed, l, f, cur.samp_off, cur.samp_nbr, seen, fresh, wpb);
-            else if (need <= 512) launch_sampler<512>(grid, st, g, cur.ids, n_cur, cur.off_dev, beta, batch_seed, l, f, cur.samp_off, cur.samp_nbr, seen, fresh, wpb);
-            else if (need <= 1024) launch_sampler<1024>(grid, st, g, cur.ids, n_cur, cur.off_dev, beta, batch_seed, l, f, cur.samp_off, cur.samp_nbr, seen, fresh, wpb);
-            else launch_sampler<2048>(grid, st, g, cur.ids, n_cur, cur.off_dev, beta, batch_seed, l, f, cur.samp_off, cur.samp_nbr, seen, fresh, wpb);
-            RG_HIP(hipGetLastError());
-        }
-
-        // fresh IDs per (batch, chunk) -> positions -> next frontier
+        // a4: fresh IDs per (batch, chunk) -> positions -> next frontier
         RG_TRY(s->arena.dev_n<int64_t>((uint64_t)beta + 1, &nxt.off_dev));
         {
             ScopedTimer tm(KG_FRONTIER, st);

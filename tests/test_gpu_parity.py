@@ -202,6 +202,35 @@ def test_wide_fanouts_and_long_rows(rg, orc):
         assert_schedules_equal(rg, g, o)
 
 
+def test_rows_longer_than_a_tile(rg, orc):
+    """Rows beyond the tile length (16384) are sampled tile by tile and merged: 2, 3 and 5 tiles, a row of
+    exactly one tile and one of a tile plus one, as seeds and as neighbours of seeds."""
+    n = 90000
+    rng = np.random.default_rng(21)
+    deg = rng.integers(0, 40, n)
+    big = {0: 16384, 1: 16385, 2: 20000, 3: 40001, 4: 70000}
+    for v, d in big.items():
+        deg[v] = d
+    rows = []
+    for v in range(n):
+        if v in big:
+            r = rng.choice(n - 1, size=big[v], replace=False)
+        else:
+            r = np.unique(np.concatenate([rng.integers(0, n - 1, int(deg[v])), rng.integers(0, 5, 2)]))   # small rows point at the big ones
+        r = np.sort(np.where(r >= v, r + 1, r)).astype(np.int32)
+        rows.append(r)
+    indptr = np.zeros(n + 1, np.int64)
+    indptr[1:] = np.cumsum([r.size for r in rows])
+    indices = np.concatenate(rows)
+    train = np.concatenate([np.arange(5), rng.permutation(np.arange(5, n))[:400]]).astype(np.int32)
+    dp, dx, dt = torch.from_numpy(indptr).cuda(), torch.from_numpy(indices).cuda(), torch.from_numpy(train).cuda()
+    assert rg.rg_graph_validate(dp, dx) == 0
+    for fan in ([3, 7], [64], [100, 5], [1984]):
+        g = rg.rg_build_schedule(dp, dx, dt, 50, fan, 4, 1, 2)
+        o = orc.Schedule(indptr, indices, train, 50, fan, 4, 1, 2, n_threads=8)
+        assert_schedules_equal(rg, g, o)
+
+
 def test_errors_are_reported_not_crashes(rg):
     w, indptr, indices, train = small_graph()
     with pytest.raises(rg.RgError) as e:
