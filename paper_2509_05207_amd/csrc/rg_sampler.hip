@@ -15,8 +15,8 @@
 // sampled.
 //
 //  - deg <= f: the row is the sample; it is copied.
-//  - deg <= 256: the row sits in registers (1 or 4 IDs per lane).  The exact
-//    f-th smallest key is found by a 32-step bitwise search on ballots, and the
+//  - deg <= 256: the row sits in registers (1 or 4 IDs per lane).  A threshold
+//    that exactly f keys do not exceed is found by bisection on ballots, and the
 //    kept IDs are compacted straight into the output with ballot/popcount
 //    ranks, which preserves row order.
 //  - longer rows are streamed once, 256 IDs per step, the next step's loads
@@ -79,20 +79,26 @@ __device__ __forceinline__ int64_t bcast64(int64_t x, int src_lane)
     return (int64_t)(((uint64_t)hi << 32) | lo);
 }
 
-// The keep-th smallest of the keys held in registers (E per lane): the largest cut with
-// |{key < cut}| < keep.  Keys are distinct, so exactly `keep` of them are <= the result.
+// A threshold that exactly `keep` of the keys held in registers (E per lane, `total` >= keep of
+// them valid) do not exceed.  Bisection on the key value, counting with ballots: the keep-th
+// smallest key stays inside [lo, lo + 2^(bit+1)), and the search stops as soon as the number of
+// keys below the bracket's upper end is exactly `keep` -- after about log2(total) steps for
+// spread-out keys, 32 at most (keys are distinct).
 template <int E>
-__device__ __forceinline__ uint32_t kth_smallest_key(const uint32_t (&k)[E], const bool (&valid)[E], int keep)
+__device__ __forceinline__ uint32_t kth_key_threshold(const uint32_t (&k)[E], const bool (&valid)[E], int keep, int total)
 {
-    uint32_t cut = 0;
-    for (int bit = 31; bit >= 0; --bit) {
-        const uint32_t trial = cut | (1u << bit);
+    uint32_t lo = 0;
+    int below_hi = total;
+    int bit = 31;
+    while (below_hi != keep) {
+        const uint32_t trial = lo | (1u << bit);
         int below = 0;
 #pragma unroll
         for (int e = 0; e < E; ++e) below += __popcll(__ballot(valid[e] && k[e] < trial));
-        if (below < keep) cut = trial;
+        if (below < keep) lo = trial; else below_hi = below;
+        --bit;
     }
-    return cut;
+    return lo + (uint32_t)((((uint64_t)1) << (bit + 1)) - 1u);
 }
 
 // Row of f < len <= 64 * E IDs held in registers (u[e] of lane l is row[e * 64 + l]),
@@ -108,7 +114,7 @@ __device__ __forceinline__ void sample_registers(const uint32_t (&u)[E], int len
         valid[e] = e * 64 + lane < len;
         k[e] = key32(lo, hi, u[e]);
     }
-    const uint32_t cut = kth_smallest_key<E>(k, valid, f);
+    const uint32_t cut = kth_key_threshold<E>(k, valid, f, len);
     int base = 0;
 #pragma unroll
     for (int e = 0; e < E; ++e) {
@@ -122,7 +128,8 @@ __device__ __forceinline__ void sample_registers(const uint32_t (&u)[E], int len
     }
 }
 
-// Keeps the `keep` smallest-key entries of buf[0..cnt), order preserved; returns the cut.
+// Keeps the `keep` smallest-key entries of buf[0..cnt), order preserved; returns a threshold that
+// exactly those entries' keys do not exceed.
 // Precondition: cnt > keep >= 1, cnt <= CAP.
 template <int CAP>
 __device__ __forceinline__ uint32_t prune_buffer(uint32_t *buf, int cnt, int keep, uint32_t lo, uint32_t hi, int lane)
@@ -137,7 +144,7 @@ __device__ __forceinline__ uint32_t prune_buffer(uint32_t *buf, int cnt, int kee
         u[e] = valid[e] ? buf[idx] : 0u;
         k[e] = key32(lo, hi, u[e]);
     }
-    const uint32_t cut = kth_smallest_key<E>(k, valid, keep);
+    const uint32_t cut = kth_key_threshold<E>(k, valid, keep, cnt);
     __syncthreads();          // every lane has read its entries before any is overwritten
     int base = 0;
 #pragma unroll
@@ -155,7 +162,7 @@ __device__ __forceinline__ uint32_t prune_buffer(uint32_t *buf, int cnt, int kee
 struct Stream {
     int cnt;          // entries in the buffer (wave-uniform)
     bool open;        // no cut yet: every ID is a candidate
-    uint32_t cut;     // candidates must have key < cut once !open
+    uint32_t cut;     // candidates must have key <= cut once !open
 };
 
 // One step of 256 IDs (cur[e] of lane l is step[e * 64 + l]); FULL: all 256 are inside the row.
@@ -169,7 +176,7 @@ __device__ __forceinline__ void stream_step(const uint32_t (&cur)[4], int count,
 #pragma unroll
     for (int e = 0; e < 4; ++e) ok[e] = FULL || e * 64 + lane < count;
     if (!s.open) {
-        const bool any = (ok[0] && k[0] < s.cut) || (ok[1] && k[1] < s.cut) || (ok[2] && k[2] < s.cut) || (ok[3] && k[3] < s.cut);
+        const bool any = (ok[0] && k[0] <= s.cut) || (ok[1] && k[1] <= s.cut) || (ok[2] && k[2] <= s.cut) || (ok[3] && k[3] <= s.cut);
         if (__ballot(any) == 0ull) return;
     }
 #pragma unroll
@@ -179,7 +186,7 @@ __device__ __forceinline__ void stream_step(const uint32_t (&cur)[4], int count,
             s.cnt = f;
             s.open = false;
         }
-        const bool pass = ok[e] && (s.open || k[e] < s.cut);
+        const bool pass = ok[e] && (s.open || k[e] <= s.cut);
         const unsigned long long m = __ballot(pass);
         if (pass) buf[s.cnt + lanes_below(m, lane)] = cur[e];
         s.cnt += __popcll(m);
