@@ -50,15 +50,12 @@ __device__ __forceinline__ uint32_t batch_of(const int64_t *__restrict__ off, ui
 }
 
 // ---------------------------------------------------------------- reached-ID bitmaps
-// A sampled ID is new to the batch iff its `seen` bit was clear; the lane that
-// flips it also sets the `fresh` bit.  Bits are only ever set here, so the
-// plain pre-check can at worst cause a redundant atomic.
-__device__ __forceinline__ void mark_reached(uint32_t *__restrict__ seen_b, uint32_t *__restrict__ fresh_b, uint32_t u)
+// Every sampled ID sets its bit in the batch's `reached` bitmap.  The OR needs no return value, so
+// the wave never waits for it; which of the reached IDs are new to the batch is decided afterwards,
+// word by word, against the batch's `seen` bitmap.
+__device__ __forceinline__ void mark_reached(uint32_t *__restrict__ reached_b, uint32_t u)
 {
-    const uint32_t w = u >> 5, bit = 1u << (u & 31);
-    if (seen_b[w] & bit) return;
-    const uint32_t old = atomicOr(&seen_b[w], bit);
-    if (!(old & bit)) atomicOr(&fresh_b[w], bit);
+    (void)__hip_atomic_fetch_or(&reached_b[u >> 5], 1u << (u & 31), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
 }  // namespace rg

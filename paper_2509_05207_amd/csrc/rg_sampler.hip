@@ -19,12 +19,13 @@
 //    that exactly f keys do not exceed is found by bisection on ballots, and the
 //    kept IDs are compacted straight into the output with ballot/popcount
 //    ranks, which preserves row order.
-//  - longer rows are streamed once, 256 IDs per step, the next step's loads
-//    already in flight.  IDs whose key is below the current cut are appended
-//    (ballot ranks again, so in row order) to an LDS buffer of CAP >= f + 64
-//    IDs; when the buffer could overflow it is pruned to the f smallest keys
-//    with the same search and an in-place ordered compaction, which also
-//    tightens the cut.  What is left after the last step is the sample.
+//  - longer rows are streamed once in 1 KB blocks aligned to cache lines, one
+//    16-byte load per lane, the next block's load already in flight.  IDs whose
+//    key is not above the current cut are appended (ballot ranks again, so in
+//    row order) to an LDS buffer of CAP >= f + 64 IDs; when the buffer would
+//    overflow it is pruned to the f smallest keys with the same search and an
+//    in-place ordered compaction, which also tightens the cut.  What is left
+//    after the last block is the sample.
 //  - rows longer than BIG_ROW are cut into T near-equal tiles, each sampled by
 //    its own wave into scratch (f IDs per tile, row order); a second small
 //    launch samples the concatenation of a row's tile results, which is the
@@ -72,29 +73,49 @@ __global__ void node_records_kernel(const int64_t *__restrict__ indptr, const in
 
 __device__ __forceinline__ int lanes_below(unsigned long long m, int lane) { return __popcll(m & ((1ull << lane) - 1ull)); }
 
+// The lane mask of a predicate, taken straight from the compare.
+__device__ __forceinline__ unsigned long long ballot64(bool p) { return __builtin_amdgcn_ballot_w64(p); }
+
+// Values that are the same in every lane of the wave, pinned to scalar registers so that the
+// branches and loops they steer are scalar too.
+__device__ __forceinline__ int uni(int x) { return __builtin_amdgcn_readfirstlane(x); }
+__device__ __forceinline__ uint32_t uni(uint32_t x) { return (uint32_t)__builtin_amdgcn_readfirstlane((int)x); }
+__device__ __forceinline__ bool uni(bool x) { return __builtin_amdgcn_readfirstlane((int)x) != 0; }
+
 __device__ __forceinline__ int64_t bcast64(int64_t x, int src_lane)
 {
-    const uint32_t lo = (uint32_t)__shfl((int)(uint32_t)x, src_lane, 64);
-    const uint32_t hi = (uint32_t)__shfl((int)(uint32_t)((uint64_t)x >> 32), src_lane, 64);
+    const uint32_t lo = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)x, src_lane);
+    const uint32_t hi = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)((uint64_t)x >> 32), src_lane);
     return (int64_t)(((uint64_t)hi << 32) | lo);
 }
 
-// A threshold that exactly `keep` of the keys held in registers (E per lane, `total` >= keep of
-// them valid) do not exceed.  Bisection on the key value, counting with ballots: the keep-th
-// smallest key stays inside [lo, lo + 2^(bit+1)), and the search stops as soon as the number of
-// keys below the bracket's upper end is exactly `keep` -- after about log2(total) steps for
-// spread-out keys, 32 at most (keys are distinct).
-template <int E>
-__device__ __forceinline__ uint32_t kth_key_threshold(const uint32_t (&k)[E], const bool (&valid)[E], int keep, int total)
+// The lanes 0 .. n-1 (n clamped to [0, 64]) as a mask.
+__device__ __forceinline__ unsigned long long low_lanes(int n)
 {
+    return n >= 64 ? ~0ull : (n <= 0 ? 0ull : (1ull << n) - 1ull);
+}
+
+// Lane masks instead of per-lane booleans: a mask is one compare (ballot of a single comparison)
+// and everything after it -- AND with the valid lanes, population counts, comparisons with f --
+// is scalar work that the vector unit never sees.
+
+// A threshold that exactly `keep` of the keys held in registers do not exceed.  k[e] is valid in
+// the lanes of vm[e]; `total` >= keep keys are valid in all.  Bisection on the key value: the
+// keep-th smallest key stays inside [lo, lo + 2^(bit+1)), and the search stops as soon as the
+// number of keys below the bracket's upper end is exactly `keep` -- after about log2(total)
+// steps for spread-out keys, 32 at most (keys are distinct).
+template <int E>
+__device__ __forceinline__ uint32_t kth_key_threshold(const uint32_t (&k)[E], const unsigned long long (&vm)[E], int keep, int total)
+{
+    keep = uni(keep);
     uint32_t lo = 0;
-    int below_hi = total;
+    int below_hi = uni(total);
     int bit = 31;
     while (below_hi != keep) {
         const uint32_t trial = lo | (1u << bit);
         int below = 0;
 #pragma unroll
-        for (int e = 0; e < E; ++e) below += __popcll(__ballot(valid[e] && k[e] < trial));
+        for (int e = 0; e < E; ++e) below += __popcll(ballot64(k[e] < trial) & vm[e]);
         if (below < keep) lo = trial; else below_hi = below;
         --bit;
     }
@@ -105,24 +126,24 @@ __device__ __forceinline__ uint32_t kth_key_threshold(const uint32_t (&k)[E], co
 // sampled and written to out in row order.
 template <int E, bool MARK>
 __device__ __forceinline__ void sample_registers(const uint32_t (&u)[E], int len, int f, uint32_t lo, uint32_t hi, int lane,
-                                                 int32_t *__restrict__ out, uint32_t *__restrict__ seen_b, uint32_t *__restrict__ fresh_b)
+                                                 int32_t *__restrict__ out, uint32_t *__restrict__ reached_b)
 {
+    len = uni(len); f = uni(f); lo = uni(lo); hi = uni(hi);
     uint32_t k[E];
-    bool valid[E];
+    unsigned long long vm[E];
 #pragma unroll
     for (int e = 0; e < E; ++e) {
-        valid[e] = e * 64 + lane < len;
+        vm[e] = low_lanes(len - e * 64);
         k[e] = key32(lo, hi, u[e]);
     }
-    const uint32_t cut = kth_key_threshold<E>(k, valid, f, len);
+    const uint32_t cut = kth_key_threshold<E>(k, vm, f, len);
     int base = 0;
 #pragma unroll
     for (int e = 0; e < E; ++e) {
-        const bool keep_it = valid[e] && k[e] <= cut;
-        const unsigned long long m = __ballot(keep_it);
-        if (keep_it) {
+        const unsigned long long m = ballot64(k[e] <= cut) & vm[e];
+        if (e * 64 + lane < len && k[e] <= cut) {
             out[base + lanes_below(m, lane)] = (int32_t)u[e];
-            if (MARK) mark_reached(seen_b, fresh_b, u[e]);
+            if (MARK) mark_reached(reached_b, u[e]);
         }
         base += __popcll(m);
     }
@@ -135,23 +156,23 @@ template <int CAP>
 __device__ __forceinline__ uint32_t prune_buffer(uint32_t *buf, int cnt, int keep, uint32_t lo, uint32_t hi, int lane)
 {
     constexpr int E = CAP / 64;
+    cnt = uni(cnt); keep = uni(keep); lo = uni(lo); hi = uni(hi);
     uint32_t u[E], k[E];
-    bool valid[E];
+    unsigned long long vm[E];
 #pragma unroll
     for (int e = 0; e < E; ++e) {
         const int idx = e * 64 + lane;
-        valid[e] = idx < cnt;
-        u[e] = valid[e] ? buf[idx] : 0u;
+        vm[e] = low_lanes(cnt - e * 64);
+        u[e] = idx < cnt ? buf[idx] : 0u;
         k[e] = key32(lo, hi, u[e]);
     }
-    const uint32_t cut = kth_key_threshold<E>(k, valid, keep, cnt);
+    const uint32_t cut = uni(kth_key_threshold<E>(k, vm, keep, cnt));
     __syncthreads();          // every lane has read its entries before any is overwritten
     int base = 0;
 #pragma unroll
     for (int e = 0; e < E; ++e) {
-        const bool keep_it = valid[e] && k[e] <= cut;
-        const unsigned long long m = __ballot(keep_it);
-        if (keep_it) buf[base + lanes_below(m, lane)] = u[e];
+        const unsigned long long m = ballot64(k[e] <= cut) & vm[e];
+        if (e * 64 + lane < cnt && k[e] <= cut) buf[base + lanes_below(m, lane)] = u[e];
         base += __popcll(m);
     }
     __syncthreads();
@@ -165,59 +186,163 @@ struct Stream {
     uint32_t cut;     // candidates must have key <= cut once !open
 };
 
-// One step of 256 IDs (cur[e] of lane l is step[e * 64 + l]); FULL: all 256 are inside the row.
-template <int CAP, bool FULL>
-__device__ __forceinline__ void stream_step(const uint32_t (&cur)[4], int count, int f, uint32_t lo, uint32_t hi, int lane, uint32_t *buf, Stream &s)
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+// A block is up to 256 consecutive IDs of the row; lane l holds IDs 4l .. 4l+3 of the block (one
+// 16-byte load), so row order is lane-major and ID e of a lane is valid in the lanes of vm[e].
+// Appends the block's candidates to the buffer in row order.  If they do not fit, the buffer is
+// pruned first (which tightens the cut and may drop some of them); if they still do not fit, the
+// block goes in four quarters of 64 consecutive IDs.
+template <int CAP>
+__device__ __forceinline__ void append_block(const uint32_t (&u)[4], const uint32_t (&k)[4], const unsigned long long (&vm)[4], int f, uint32_t lo,
+                                             uint32_t hi, int lane, uint32_t *buf, Stream &s)
 {
-    uint32_t k[4];
-#pragma unroll
-    for (int e = 0; e < 4; ++e) k[e] = key32(lo, hi, cur[e]);
-    bool ok[4];
-#pragma unroll
-    for (int e = 0; e < 4; ++e) ok[e] = FULL || e * 64 + lane < count;
-    if (!s.open) {
-        const bool any = (ok[0] && k[0] <= s.cut) || (ok[1] && k[1] <= s.cut) || (ok[2] && k[2] <= s.cut) || (ok[3] && k[3] <= s.cut);
-        if (__ballot(any) == 0ull) return;
-    }
+    f = uni(f); lo = uni(lo); hi = uni(hi);
+    s.cnt = uni(s.cnt); s.open = uni(s.open); s.cut = uni(s.cut);
+    const unsigned long long me = 1ull << lane;
+    unsigned long long m[4];
+    int total = 0;
 #pragma unroll
     for (int e = 0; e < 4; ++e) {
-        if (s.cnt > CAP - 64) {               // the next 64 might not fit: tighten first
+        m[e] = s.open ? vm[e] : (ballot64(k[e] <= s.cut) & vm[e]);
+        total += __popcll(m[e]);
+    }
+    if (total == 0) return;
+    if (s.cnt + total > CAP && s.cnt > f) {
+        s.cut = prune_buffer<CAP>(buf, s.cnt, f, lo, hi, lane);
+        s.cnt = f;
+        s.open = false;
+        total = 0;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            m[e] &= ballot64(k[e] <= s.cut);
+            total += __popcll(m[e]);
+        }
+        if (total == 0) return;
+    }
+    if (s.cnt + total <= CAP) {
+        int rank = s.cnt;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) rank += lanes_below(m[e], lane);
+#pragma unroll
+        for (int e = 0; e < 4; ++e)
+            if (m[e] & me) buf[rank++] = u[e];
+        s.cnt += total;
+        return;
+    }
+    for (int q = 0; q < 4; ++q) {             // lanes 16q .. 16q+15 hold 64 consecutive IDs
+        if (s.cnt > CAP - 64) {
             s.cut = prune_buffer<CAP>(buf, s.cnt, f, lo, hi, lane);
             s.cnt = f;
             s.open = false;
         }
-        const bool pass = ok[e] && (s.open || k[e] <= s.cut);
-        const unsigned long long m = __ballot(pass);
-        if (pass) buf[s.cnt + lanes_below(m, lane)] = cur[e];
-        s.cnt += __popcll(m);
+        const unsigned long long quarter = 0xFFFFull << (16 * q);
+        unsigned long long mq[4];
+        int rank = s.cnt, sub = 0;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            mq[e] = m[e] & quarter;
+            if (!s.open) mq[e] &= ballot64(k[e] <= s.cut);
+            rank += lanes_below(mq[e], lane);
+            sub += __popcll(mq[e]);
+        }
+#pragma unroll
+        for (int e = 0; e < 4; ++e)
+            if (mq[e] & me) buf[rank++] = u[e];
+        s.cnt += sub;
     }
 }
 
-// Row of len > 256 IDs streamed once; `first` holds row[lane]; on return buf[0..f) is the sample in row order.
-template <int CAP>
-__device__ __forceinline__ void sample_long_row(const int32_t *__restrict__ row, int len, uint32_t first, int f, uint32_t lo, uint32_t hi, int lane,
-                                                uint32_t *buf)
+// IDs p[4 * lane .. 4 * lane + 3] of a block of which `left` (> 0) IDs lie inside the row; p is 16-byte aligned.
+__device__ __forceinline__ u32x4 load_block(const int32_t *__restrict__ p, int left, int lane)
 {
-    Stream s{0, true, 0u};
-    const int n_full = len >> 8, tail = len & 255;
-    uint32_t cur[4], nxt[4] = {0u, 0u, 0u, 0u};
-    cur[0] = first;
+    const int j = 4 * lane;
+    if (left >= 256 || j + 3 < left) return *reinterpret_cast<const u32x4 *>(p + j);
+    u32x4 r = {0u, 0u, 0u, 0u};
+    if (j < left) r.x = (uint32_t)p[j];
+    if (j + 1 < left) r.y = (uint32_t)p[j + 1];
+    if (j + 2 < left) r.z = (uint32_t)p[j + 2];
+    return r;
+}
+
+// Valid lanes of ID e of a block that holds `count` IDs: 4 * lane + e < count.
+__device__ __forceinline__ unsigned long long block_lanes(int count, int e) { return low_lanes((count - e + 3) >> 2); }
+
+template <int CAP, bool FULL>
+__device__ __forceinline__ void stream_block(const u32x4 &blk, int count, int f, uint32_t lo, uint32_t hi, int lane, uint32_t *buf, Stream &s)
+{
+    count = uni(count); f = uni(f); lo = uni(lo); hi = uni(hi);
+    const uint32_t u[4] = {blk.x, blk.y, blk.z, blk.w};
+    uint32_t k[4];
+    unsigned long long vm[4];
 #pragma unroll
-    for (int e = 1; e < 4; ++e) cur[e] = (uint32_t)row[e * 64 + lane];
-    for (int c = 0; c < n_full; ++c) {
-        const int32_t *p = row + (c + 1) * 256;                  // next step's loads go out before this step's keys are computed
-        if (c + 1 < n_full) {
-#pragma unroll
-            for (int e = 0; e < 4; ++e) nxt[e] = (uint32_t)p[e * 64 + lane];
-        } else if (tail) {
-#pragma unroll
-            for (int e = 0; e < 4; ++e) nxt[e] = e * 64 + lane < tail ? (uint32_t)p[e * 64 + lane] : 0u;
-        }
-        stream_step<CAP, true>(cur, 256, f, lo, hi, lane, buf, s);
-#pragma unroll
-        for (int e = 0; e < 4; ++e) cur[e] = nxt[e];
+    for (int e = 0; e < 4; ++e) {
+        k[e] = key32(lo, hi, u[e]);
+        vm[e] = FULL ? ~0ull : block_lanes(count, e);
     }
-    if (tail) stream_step<CAP, false>(cur, tail, f, lo, hi, lane, buf, s);
+    append_block<CAP>(u, k, vm, f, lo, hi, lane, buf, s);
+}
+
+// Row of len > 256 IDs streamed once; on return buf[0..f) is the sample in row order.  The IDs in
+// front of the first 128-byte boundary go first (one per lane); from there on the row is read in
+// blocks of 1 KB, one aligned 16-byte load per lane, so no two loads of a wave share a cache line,
+// and the next block's load is in flight while the current block's keys are computed.
+template <int CAP>
+__device__ __forceinline__ void sample_long_row(const int32_t *__restrict__ row, int len, int f, uint32_t lo, uint32_t hi, int lane, uint32_t *buf)
+{
+    len = uni(len); f = uni(f); lo = uni(lo); hi = uni(hi);
+    Stream s{0, true, 0u};
+    int head = uni((32 - (int)(((uintptr_t)row >> 2) & 31)) & 31);
+    if (head > len) head = len;
+    const int32_t *p = row + head;
+    const int rem = len - head;                                  // > 0: len > 256 and head < 32
+    const int n_blocks = (rem + 255) >> 8;
+    const uint32_t head_u = lane < head ? (uint32_t)row[lane] : 0u;
+    u32x4 cur = load_block(p, rem, lane), nxt = {0u, 0u, 0u, 0u};
+    int c0 = 0;
+    const int count0 = rem < 256 ? rem : 256;
+    if (head + count0 > f) {
+        // The usual case: the head and the first block (up to 287 IDs, all in registers) already hold more
+        // than f IDs.  Their f smallest keys give the first cut directly; only those f IDs enter the buffer.
+        if (rem > 256) nxt = load_block(p + 256, rem - 256, lane);
+        const uint32_t u[5] = {head_u, cur.x, cur.y, cur.z, cur.w};
+        uint32_t k[5];
+        unsigned long long vm[5];
+        vm[0] = low_lanes(head);
+#pragma unroll
+        for (int e = 1; e < 5; ++e) vm[e] = block_lanes(count0, e - 1);
+#pragma unroll
+        for (int e = 0; e < 5; ++e) k[e] = key32(lo, hi, u[e]);
+        s.cut = uni(kth_key_threshold<5>(k, vm, f, head + count0));
+        s.open = false;
+        s.cnt = f;
+        const unsigned long long me = 1ull << lane;
+        unsigned long long m[5];
+        int rank = 0;
+#pragma unroll
+        for (int e = 0; e < 5; ++e) m[e] = ballot64(k[e] <= s.cut) & vm[e];
+        if (m[0] & me) buf[lanes_below(m[0], lane)] = u[0];
+        rank = __popcll(m[0]);
+#pragma unroll
+        for (int e = 1; e < 5; ++e) rank += lanes_below(m[e], lane);
+#pragma unroll
+        for (int e = 1; e < 5; ++e)
+            if (m[e] & me) buf[rank++] = u[e];
+        cur = nxt;
+        c0 = 1;
+    } else if (head > 0) {
+        const uint32_t u[4] = {head_u, 0u, 0u, 0u};
+        const uint32_t k[4] = {key32(lo, hi, u[0]), 0u, 0u, 0u};
+        const unsigned long long vm[4] = {low_lanes(head), 0ull, 0ull, 0ull};
+        append_block<CAP>(u, k, vm, f, lo, hi, lane, buf, s);
+    }
+    for (int c = c0; c < n_blocks; ++c) {
+        const int left = rem - c * 256;                          // IDs left, this block included
+        if (left > 256) nxt = load_block(p + (c + 1) * 256, left - 256, lane);
+        if (left >= 256) stream_block<CAP, true>(cur, 256, f, lo, hi, lane, buf, s);
+        else stream_block<CAP, false>(cur, left, f, lo, hi, lane, buf, s);
+        cur = nxt;
+    }
     __syncthreads();
     if (s.cnt > f) (void)prune_buffer<CAP>(buf, s.cnt, f, lo, hi, lane);
 }
@@ -226,23 +351,23 @@ __device__ __forceinline__ void sample_long_row(const int32_t *__restrict__ row,
 // `first` holds row[lane] for lane < len.
 template <int CAP, bool MARK>
 __device__ __forceinline__ void sample_row(const int32_t *__restrict__ row, int len, uint32_t first, int f, uint32_t lo, uint32_t hi, int lane,
-                                           uint32_t *buf, int32_t *__restrict__ out, uint32_t *__restrict__ seen_b, uint32_t *__restrict__ fresh_b)
+                                           uint32_t *buf, int32_t *__restrict__ out, uint32_t *__restrict__ reached_b)
 {
     if (len <= 64) {
         const uint32_t u[1] = {first};
-        sample_registers<1, MARK>(u, len, f, lo, hi, lane, out, seen_b, fresh_b);
+        sample_registers<1, MARK>(u, len, f, lo, hi, lane, out, reached_b);
     } else if (len <= 256) {
         uint32_t u[4];
         u[0] = first;
 #pragma unroll
         for (int e = 1; e < 4; ++e) u[e] = e * 64 + lane < len ? (uint32_t)row[e * 64 + lane] : 0u;
-        sample_registers<4, MARK>(u, len, f, lo, hi, lane, out, seen_b, fresh_b);
+        sample_registers<4, MARK>(u, len, f, lo, hi, lane, out, reached_b);
     } else {
-        sample_long_row<CAP>(row, len, first, f, lo, hi, lane, buf);
+        sample_long_row<CAP>(row, len, f, lo, hi, lane, buf);
         for (int j = lane; j < f; j += 64) {
             const uint32_t u = buf[j];
             out[j] = (int32_t)u;
-            if (MARK) mark_reached(seen_b, fresh_b, u);
+            if (MARK) mark_reached(reached_b, u);
         }
         __syncthreads();      // the buffer is reused by the wave's next row
     }
@@ -255,8 +380,19 @@ struct HopArgs {
     uint32_t fanout;
     const int64_t *samp_off; int32_t *samp_nbr;
     const int64_t *tile_off; int64_t n_tiles; int32_t *tile_out;      // tile j writes tile_out[j * fanout ..)
-    uint32_t *seen; uint32_t *fresh; uint64_t words_per_batch;
+    uint32_t *reached; uint64_t words_per_batch;
+    unsigned long long *next_work;                                     // work items are handed out in order through this counter
 };
+
+// The next unclaimed work item (lane 0 asks, every lane gets the answer).
+__device__ __forceinline__ int64_t grab_work(unsigned long long *counter, int lane)
+{
+    unsigned long long v = 0;
+    if (lane == 0) v = atomicAdd(counter, 1ull);
+    const uint32_t lo = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)v);
+    const uint32_t hi = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)(v >> 32));
+    return (int64_t)(((uint64_t)hi << 32) | lo);
+}
 
 // Position i of the frontier whose tiles contain tile job j: tile_off[i] <= j < tile_off[i + 1].
 __device__ __forceinline__ int64_t node_of_tile(const int64_t *__restrict__ tile_off, int64_t n, int64_t j)
@@ -269,7 +405,7 @@ __device__ __forceinline__ int64_t node_of_tile(const int64_t *__restrict__ tile
     return lo;
 }
 
-// Work items [0, n_tiles) are tiles of long rows (first, so the longest-running work starts first);
+// Work items [0, n_tiles) are tiles of long rows (handed out first, so the longest-running work starts first);
 // item n_tiles + c is the c-th group of 64 consecutive frontier nodes.
 template <int CAP>
 __global__ void __launch_bounds__(64) sample_kernel(HopArgs a)
@@ -279,7 +415,9 @@ __global__ void __launch_bounds__(64) sample_kernel(HopArgs a)
     const int f = (int)a.fanout;
     const int64_t n_groups = (a.n_frontier + 63) >> 6;
     const int64_t n_work = a.n_tiles + n_groups;
-    for (int64_t w = blockIdx.x; w < n_work; w += gridDim.x) {
+    // Waves take work items as they become free, so uneven rows do not leave part of the chip idle at the
+    // end; every wave leaves once the counter has passed the last item.
+    for (int64_t w = grab_work(a.next_work, lane); w < n_work; w = grab_work(a.next_work, lane)) {
         if (w < a.n_tiles) {
             const int64_t i = node_of_tile(a.tile_off, a.n_frontier, w);
             const int64_t T = a.tile_off[i + 1] - a.tile_off[i], t = w - a.tile_off[i];
@@ -288,7 +426,7 @@ __global__ void __launch_bounds__(64) sample_kernel(HopArgs a)
             const uint64_t S = a.rec.state[i];
             const int32_t *row = a.indices + row_begin + first_pos;
             sample_row<CAP, false>(row, (int)(last_pos - first_pos), (uint32_t)row[lane], f, (uint32_t)S, (uint32_t)(S >> 32), lane, buf,
-                                   a.tile_out + w * f, nullptr, nullptr);
+                                   a.tile_out + w * f, nullptr);
             continue;
         }
         const int64_t i_lane = ((w - a.n_tiles) << 6) + lane;
@@ -298,12 +436,12 @@ __global__ void __launch_bounds__(64) sample_kernel(HopArgs a)
         const uint32_t b_lane = in ? a.rec.batch[i_lane] : 0u;
         const int64_t S_lane = in ? (int64_t)a.rec.state[i_lane] : 0;
         const int64_t out_lane = in ? a.samp_off[i_lane] : 0;
-        unsigned long long todo = __ballot(deg_lane > 0 && deg_lane <= BIG_ROW);
+        unsigned long long todo = ballot64(deg_lane > 0 && deg_lane <= BIG_ROW);
         if (todo == 0ull) continue;
         // the first node's leading 64 IDs; from then on the next node's are fetched while the current one is sampled
-        int l = __ffsll((long long)todo) - 1;
+        int l = __builtin_amdgcn_readfirstlane(__ffsll((long long)todo) - 1);
         int64_t rb = bcast64(rb_lane, l);
-        int deg = __shfl(deg_lane, l, 64);
+        int deg = __builtin_amdgcn_readlane(deg_lane, l);
         uint32_t first = lane < deg ? (uint32_t)a.indices[rb + lane] : 0u;
         while (todo != 0ull) {
             todo &= todo - 1ull;
@@ -311,26 +449,25 @@ __global__ void __launch_bounds__(64) sample_kernel(HopArgs a)
             const int64_t crb = rb;
             const uint32_t cfirst = first;
             if (todo != 0ull) {
-                l = __ffsll((long long)todo) - 1;
+                l = __builtin_amdgcn_readfirstlane(__ffsll((long long)todo) - 1);
                 rb = bcast64(rb_lane, l);
-                deg = __shfl(deg_lane, l, 64);
+                deg = __builtin_amdgcn_readlane(deg_lane, l);
                 first = lane < deg ? (uint32_t)a.indices[rb + lane] : 0u;
             }
-            const uint32_t b = (uint32_t)__shfl((int)b_lane, cl, 64);
-            uint32_t *seen_b = a.seen + (uint64_t)b * a.words_per_batch;
-            uint32_t *fresh_b = a.fresh + (uint64_t)b * a.words_per_batch;
+            const uint32_t b = (uint32_t)__builtin_amdgcn_readlane((int)b_lane, cl);
+            uint32_t *reached_b = a.reached + (uint64_t)b * a.words_per_batch;
             const int32_t *row = a.indices + crb;
             int32_t *out = a.samp_nbr + bcast64(out_lane, cl);
             if (cdeg <= f) {                  // the whole row is the sample
-                if (lane < cdeg) { out[lane] = (int32_t)cfirst; mark_reached(seen_b, fresh_b, cfirst); }
+                if (lane < cdeg) { out[lane] = (int32_t)cfirst; mark_reached(reached_b, cfirst); }
                 for (int j = 64 + lane; j < cdeg; j += 64) {
                     const int32_t u = row[j];
                     out[j] = u;
-                    mark_reached(seen_b, fresh_b, (uint32_t)u);
+                    mark_reached(reached_b, (uint32_t)u);
                 }
             } else {
                 const uint64_t S = (uint64_t)bcast64(S_lane, cl);
-                sample_row<CAP, true>(row, cdeg, cfirst, f, (uint32_t)S, (uint32_t)(S >> 32), lane, buf, out, seen_b, fresh_b);
+                sample_row<CAP, true>(row, cdeg, cfirst, f, (uint32_t)S, (uint32_t)(S >> 32), lane, buf, out, reached_b);
             }
         }
     }
@@ -353,7 +490,7 @@ __global__ void __launch_bounds__(64) sample_merge_kernel(HopArgs a)
         const int32_t *row = a.tile_out + w * f;
         const int len = (int)(T * f);
         sample_row<CAP, true>(row, len, lane < len ? (uint32_t)row[lane] : 0u, f, (uint32_t)S, (uint32_t)(S >> 32), lane, buf,
-                              a.samp_nbr + a.samp_off[i], a.seen + (uint64_t)b * a.words_per_batch, a.fresh + (uint64_t)b * a.words_per_batch);
+                              a.samp_nbr + a.samp_off[i], a.reached + (uint64_t)b * a.words_per_batch);
     }
 }
 
@@ -364,9 +501,9 @@ static void launch_hop(const HopArgs &a, unsigned grid, unsigned merge_grid, hip
     if (a.n_tiles > 0) hipLaunchKernelGGL(sample_merge_kernel<CAP>, dim3(merge_grid), dim3(64), 0, st, a);
 }
 
-// Samples hop `hop` of every batch: fills cur.samp_off / samp_nbr / n_samples and marks seen / fresh.
+// Samples hop `hop` of every batch: fills cur.samp_off / samp_nbr / n_samples and marks the reached-ID bitmaps.
 rg_status sample_hop(const rg_graph *g, HopData &cur, uint32_t beta, const uint64_t *batch_seed, uint32_t hop, uint32_t fanout,
-                     uint32_t *seen, uint32_t *fresh, uint64_t words_per_batch, Arena &keep, Arena &tmp, int n_cu, hipStream_t st)
+                     uint32_t *reached, uint64_t words_per_batch, Arena &keep, Arena &tmp, int n_cu, hipStream_t st)
 {
     const int64_t n_cur = cur.off_host[beta];
     int32_t *cnt = nullptr, *tiles = nullptr;
@@ -399,10 +536,13 @@ rg_status sample_hop(const rg_graph *g, HopData &cur, uint32_t beta, const uint6
     RG_TRY(tmp.dev_n<int32_t>((uint64_t)n_tiles * fanout, &tile_out));
 
     if (fanout > 0 && n_cur > 0) {
-        HopArgs a{g->indices, cur.ids, n_cur, rec, fanout, cur.samp_off, cur.samp_nbr, tile_off, n_tiles, tile_out, seen, fresh, words_per_batch};
+        unsigned long long *next_work = nullptr;
+        RG_TRY(tmp.dev_n<unsigned long long>(1, &next_work));
+        RG_HIP(hipMemsetAsync(next_work, 0, sizeof(unsigned long long), st));
+        HopArgs a{g->indices, cur.ids, n_cur, rec, fanout, cur.samp_off, cur.samp_nbr, tile_off, n_tiles, tile_out, reached, words_per_batch, next_work};
         ScopedTimer tm(KG_SAMPLER, st);
         const int64_t n_work = n_tiles + (n_cur + 63) / 64;
-        const unsigned grid = (unsigned)std::max<int64_t>(1, std::min<int64_t>(n_work, (int64_t)n_cu * 64));
+        const unsigned grid = (unsigned)std::max<int64_t>(1, std::min<int64_t>(n_work, (int64_t)n_cu * 32));     // as many waves as fit on the chip
         const unsigned merge_grid = (unsigned)std::max<int64_t>(1, std::min<int64_t>(n_tiles, (int64_t)n_cu * 64));
         const uint32_t need = fanout + 64;
         if (need <= 128) launch_hop<128>(a, grid, merge_grid, st);

@@ -4,9 +4,9 @@
 // Layout in HBM.  Batches are independent, so a hop is one launch over the
 // concatenated frontiers of every batch.  Per batch the library keeps two
 // bitmaps of n_nodes bits for the duration of the build: `seen` (members of
-// the current frontier) and `fresh` (IDs first reached in this hop).  Reading
-// the fresh bitmap in word order yields the new IDs already deduplicated and
-// in ascending order, which is the canonical frontier order; no sort or hash
+// the current frontier) and `reached` (IDs sampled in this hop).  Reading
+// reached & ~seen in word order yields the new IDs already deduplicated and in
+// ascending order, which is the canonical frontier order; no sort or hash
 // table is involved and the result does not depend on the order in which
 // waves mark bits.
 #include "rg_internal.h"
@@ -18,7 +18,7 @@
 namespace rg {
 
 rg_status sample_hop(const rg_graph *g, HopData &cur, uint32_t beta, const uint64_t *batch_seed, uint32_t hop, uint32_t fanout,
-                     uint32_t *seen, uint32_t *fresh, uint64_t words_per_batch, Arena &keep, Arena &tmp, int n_cu, hipStream_t st);
+                     uint32_t *reached, uint64_t words_per_batch, Arena &keep, Arena &tmp, int n_cu, hipStream_t st);
 
 // ---------------------------------------------------------------- a1/a2: seeds, shuffle keys
 __global__ void batch_seeds_kernel(uint64_t s0, uint32_t worker, uint32_t epoch, uint32_t n_batches, uint64_t *__restrict__ seeds)
@@ -113,19 +113,20 @@ constexpr int FR_THREADS = 256;
 constexpr int FR_WORDS_PER_THREAD = 8;
 constexpr int FR_CHUNK_WORDS = FR_THREADS * FR_WORDS_PER_THREAD;     // 2048 words = 65536 node IDs per block
 
-// cnt[b * chunks + c] = number of fresh IDs of batch b in chunk c
-__global__ void __launch_bounds__(FR_THREADS) fresh_count_kernel(const uint32_t *__restrict__ fresh, uint64_t words_per_batch, uint32_t chunks,
-                                                                 int32_t *__restrict__ cnt)
+// cnt[b * chunks + c] = number of fresh IDs (reached and not yet seen) of batch b in chunk c
+__global__ void __launch_bounds__(FR_THREADS) fresh_count_kernel(const uint32_t *__restrict__ reached, const uint32_t *__restrict__ seen,
+                                                                 uint64_t words_per_batch, uint32_t chunks, int32_t *__restrict__ cnt)
 {
     __shared__ int red[FR_THREADS / 64];
     const uint32_t c = blockIdx.x, b = blockIdx.y;
-    const uint32_t *base = fresh + (uint64_t)b * words_per_batch;
     const uint64_t w0 = (uint64_t)c * FR_CHUNK_WORDS + (uint64_t)threadIdx.x * FR_WORDS_PER_THREAD;
     int n = 0;
     if (w0 < words_per_batch) {      // words_per_batch is a multiple of FR_WORDS_PER_THREAD
-        const uint4 a = *reinterpret_cast<const uint4 *>(base + w0);
-        const uint4 d = *reinterpret_cast<const uint4 *>(base + w0 + 4);
-        n = __popc(a.x) + __popc(a.y) + __popc(a.z) + __popc(a.w) + __popc(d.x) + __popc(d.y) + __popc(d.z) + __popc(d.w);
+        const uint64_t at = (uint64_t)b * words_per_batch + w0;
+        const uint4 r0 = *reinterpret_cast<const uint4 *>(reached + at), r1 = *reinterpret_cast<const uint4 *>(reached + at + 4);
+        const uint4 s0 = *reinterpret_cast<const uint4 *>(seen + at), s1 = *reinterpret_cast<const uint4 *>(seen + at + 4);
+        n = __popc(r0.x & ~s0.x) + __popc(r0.y & ~s0.y) + __popc(r0.z & ~s0.z) + __popc(r0.w & ~s0.w) +
+            __popc(r1.x & ~s1.x) + __popc(r1.y & ~s1.y) + __popc(r1.z & ~s1.z) + __popc(r1.w & ~s1.w);
     }
     for (int o = 32; o > 0; o >>= 1) n += __shfl_down(n, o, 64);
     if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = n;
@@ -150,31 +151,37 @@ __global__ void copy_prefix_kernel(const int32_t *__restrict__ cur, const int64_
     next[next_off[b] + (i - cur_off[b])] = cur[i];
 }
 
-// Writes the fresh IDs of (batch, chunk) in ascending order behind the batch's old frontier
-// and clears the words it consumed, leaving `fresh` all-zero for the next hop.
-__global__ void __launch_bounds__(FR_THREADS) fresh_emit_kernel(uint32_t *__restrict__ fresh, uint64_t words_per_batch, uint32_t chunks,
-                                                                const int64_t *__restrict__ fresh_scan, const int64_t *__restrict__ cur_off,
-                                                                int32_t *__restrict__ next)
+// Writes the fresh IDs of (batch, chunk) in ascending order behind the batch's old frontier, adds
+// the reached IDs to `seen` and clears `reached` for the next hop.
+__global__ void __launch_bounds__(FR_THREADS) fresh_emit_kernel(uint32_t *__restrict__ reached, uint32_t *__restrict__ seen, uint64_t words_per_batch,
+                                                                uint32_t chunks, const int64_t *__restrict__ fresh_scan,
+                                                                const int64_t *__restrict__ cur_off, int32_t *__restrict__ next)
 {
     __shared__ int wave_tot[FR_THREADS / 64];
     const uint32_t c = blockIdx.x, b = blockIdx.y;
     const int64_t scan_here = fresh_scan[(uint64_t)b * chunks + c];
-    if (fresh_scan[(uint64_t)b * chunks + c + 1] == scan_here) return;       // nothing fresh in this chunk (block-uniform)
-    uint32_t *base = fresh + (uint64_t)b * words_per_batch;
+    const bool any_fresh = fresh_scan[(uint64_t)b * chunks + c + 1] != scan_here;      // block-uniform
     const uint64_t w0 = (uint64_t)c * FR_CHUNK_WORDS + (uint64_t)threadIdx.x * FR_WORDS_PER_THREAD;
     uint32_t w[FR_WORDS_PER_THREAD] = {0, 0, 0, 0, 0, 0, 0, 0};
     int n = 0;
     if (w0 < words_per_batch) {
-        const uint4 a = *reinterpret_cast<const uint4 *>(base + w0);
-        const uint4 d = *reinterpret_cast<const uint4 *>(base + w0 + 4);
-        w[0] = a.x; w[1] = a.y; w[2] = a.z; w[3] = a.w; w[4] = d.x; w[5] = d.y; w[6] = d.z; w[7] = d.w;
+        const uint64_t at = (uint64_t)b * words_per_batch + w0;
+        const uint4 r0 = *reinterpret_cast<const uint4 *>(reached + at), r1 = *reinterpret_cast<const uint4 *>(reached + at + 4);
+        if ((r0.x | r0.y | r0.z | r0.w | r1.x | r1.y | r1.z | r1.w) != 0u) {
+            const uint4 s0 = *reinterpret_cast<const uint4 *>(seen + at), s1 = *reinterpret_cast<const uint4 *>(seen + at + 4);
+            w[0] = r0.x & ~s0.x; w[1] = r0.y & ~s0.y; w[2] = r0.z & ~s0.z; w[3] = r0.w & ~s0.w;
+            w[4] = r1.x & ~s1.x; w[5] = r1.y & ~s1.y; w[6] = r1.z & ~s1.z; w[7] = r1.w & ~s1.w;
 #pragma unroll
-        for (int k = 0; k < FR_WORDS_PER_THREAD; ++k) n += __popc(w[k]);
-        if (n) {
-            *reinterpret_cast<uint4 *>(base + w0) = make_uint4(0, 0, 0, 0);
-            *reinterpret_cast<uint4 *>(base + w0 + 4) = make_uint4(0, 0, 0, 0);
+            for (int k = 0; k < FR_WORDS_PER_THREAD; ++k) n += __popc(w[k]);
+            if (n) {
+                *reinterpret_cast<uint4 *>(seen + at) = make_uint4(s0.x | r0.x, s0.y | r0.y, s0.z | r0.z, s0.w | r0.w);
+                *reinterpret_cast<uint4 *>(seen + at + 4) = make_uint4(s1.x | r1.x, s1.y | r1.y, s1.z | r1.z, s1.w | r1.w);
+            }
+            *reinterpret_cast<uint4 *>(reached + at) = make_uint4(0, 0, 0, 0);
+            *reinterpret_cast<uint4 *>(reached + at + 4) = make_uint4(0, 0, 0, 0);
         }
     }
+    if (!any_fresh) return;
     // exclusive scan of n over the block
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     int incl = n;
@@ -271,11 +278,11 @@ static rg_status build_schedule_impl(const rg_graph *g, const int32_t *train, ui
     // ---- bitmaps (n_nodes bits per batch, rounded up to whole 8-word groups)
     const uint64_t wpb = (((uint64_t)g->n_nodes + 31) / 32 + FR_WORDS_PER_THREAD - 1) / FR_WORDS_PER_THREAD * FR_WORDS_PER_THREAD;
     const uint32_t chunks = (uint32_t)((wpb + FR_CHUNK_WORDS - 1) / FR_CHUNK_WORDS);
-    uint32_t *seen = nullptr, *fresh = nullptr;
+    uint32_t *seen = nullptr, *reached = nullptr;
     RG_TRY(tmp.dev_n<uint32_t>(wpb * beta, &seen));
-    RG_TRY(tmp.dev_n<uint32_t>(wpb * beta, &fresh));
+    RG_TRY(tmp.dev_n<uint32_t>(wpb * beta, &reached));
     RG_HIP(hipMemsetAsync(seen, 0, wpb * beta * sizeof(uint32_t), st));
-    RG_HIP(hipMemsetAsync(fresh, 0, wpb * beta * sizeof(uint32_t), st));
+    RG_HIP(hipMemsetAsync(reached, 0, wpb * beta * sizeof(uint32_t), st));
     {
         ScopedTimer tm(KG_FRONTIER, st);
         hipLaunchKernelGGL(mark_seeds_kernel, dim3((unsigned)((T + 255) / 256)), dim3(256), 0, st, h0.ids, T, B, seen, wpb);
@@ -295,14 +302,14 @@ static rg_status build_schedule_impl(const rg_graph *g, const int32_t *train, ui
         HopData &nxt = s->hop[l + 1];
         const int64_t n_cur = cur.off_host[beta];
 
-        // a3: the samples of this hop; reached IDs are marked in seen / fresh as they are written
-        RG_TRY(sample_hop(g, cur, beta, batch_seed, l, fanout[l], seen, fresh, wpb, s->arena, tmp, n_cu, st));
+        // a3: the samples of this hop; sampled IDs are marked in `reached` as they are written
+        RG_TRY(sample_hop(g, cur, beta, batch_seed, l, fanout[l], reached, wpb, s->arena, tmp, n_cu, st));
 
         // a4: fresh IDs per (batch, chunk) -> positions -> next frontier
         RG_TRY(s->arena.dev_n<int64_t>((uint64_t)beta + 1, &nxt.off_dev));
         {
             ScopedTimer tm(KG_FRONTIER, st);
-            hipLaunchKernelGGL(fresh_count_kernel, dim3(chunks, beta), dim3(FR_THREADS), 0, st, fresh, wpb, chunks, fresh_cnt);
+            hipLaunchKernelGGL(fresh_count_kernel, dim3(chunks, beta), dim3(FR_THREADS), 0, st, reached, seen, wpb, chunks, fresh_cnt);
             RG_TRY(scan_i32_to_i64(fresh_cnt, fresh_scan, (int64_t)n_cells, tmp, st));
             hipLaunchKernelGGL(next_offsets_kernel, dim3((beta + 1 + 255) / 256), dim3(256), 0, st, cur.off_dev, fresh_scan, beta, chunks, nxt.off_dev);
         }
@@ -314,7 +321,7 @@ static rg_status build_schedule_impl(const rg_graph *g, const int32_t *train, ui
         {
             ScopedTimer tm(KG_FRONTIER, st);
             hipLaunchKernelGGL(copy_prefix_kernel, dim3((unsigned)((n_cur + 255) / 256)), dim3(256), 0, st, cur.ids, cur.off_dev, nxt.off_dev, beta, n_cur, nxt.ids);
-            hipLaunchKernelGGL(fresh_emit_kernel, dim3(chunks, beta), dim3(FR_THREADS), 0, st, fresh, wpb, chunks, fresh_scan, cur.off_dev, nxt.ids);
+            hipLaunchKernelGGL(fresh_emit_kernel, dim3(chunks, beta), dim3(FR_THREADS), 0, st, reached, seen, wpb, chunks, fresh_scan, cur.off_dev, nxt.ids);
         }
         RG_HIP(hipGetLastError());
     }
