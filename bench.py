@@ -103,6 +103,19 @@ def cpu_baseline(W, indptr_h, indices_h, train_h, budget_s=15.0):
                        f"frequency, TopHot, cache fill and gather of those batches (single thread); {dt:.1f} s")
 
 
+def measured_traffic(workload, kernel):
+    """HBM bytes per launch of `kernel` on `workload` from the committed rocprofv3 --pmc runs
+    (profiles/*_traffic.md says how they were taken), or None when there is no such measurement."""
+    path = os.path.join(ROOT, "paper_2509_05207_amd", "measured_traffic.json")
+    try:
+        with open(path) as fh:
+            table = json.load(fh)
+    except (OSError, ValueError):
+        return None
+    rec = table.get(f"{workload}:{kernel}")
+    return rec.get("hbm_bytes_per_launch") if rec else None
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -111,6 +124,9 @@ def main():
     ap.add_argument("--workload", default="medium", choices=sorted(synth.CONFIGS))
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-pcie-pass", action="store_true")
+    ap.add_argument("--pmc-probe", action="store_true",
+                    help="also run one plain elementwise kernel of known size (1 GiB read + 1 GiB written), the yardstick "
+                         "that rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE readings of the library's kernels are scaled by")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on ONE GPU only (no collectives, no sharding); use --gpus 1")
@@ -122,13 +138,12 @@ def main():
     torch.cuda.set_device(0)
     cfg = synth.CONFIGS[args.workload]
     t0 = time.perf_counter()
-    W = synth.make_workload(cfg, device="cuda", feature_device="cuda", pin_remote=not args.no_pcie_pass)
+    W = synth.make_workload(cfg, device="cuda", feature_device="cuda", remote_device="cuda")
     torch.cuda.synchronize()
     log(f"[bench] workload {cfg.name}: {W.n_nodes} nodes, {W.indices.numel()} edges, K={W.K}, generated in {time.perf_counter() - t0:.1f} s")
     assert rg.rg_graph_validate(W.indptr, W.indices) == 0
 
-    remote_hbm = W.remote_rows.cuda()
-    feat_hbm = rg.make_features(W.is_local, W.row_of, W.local_rows, remote_hbm, W.row_bytes)
+    feat_hbm = rg.make_features(W.is_local, W.row_of, W.local_rows, W.remote_rows, W.row_bytes)
     side = torch.cuda.Stream()
 
     # sizes and algorithmic bytes from one untimed pass
@@ -175,6 +190,7 @@ def main():
                     avg_launch_ms=samp_ms / max(1, prof["sampler"]["launches"] // args.steps),
                     algorithmic_bytes_per_step=samp_bytes)
     roof["dominant_group_by_time"] = dominant
+    roof["traffic"] = measured_traffic(cfg.name, roof["kernel"])
 
     result = {
         "metric": METRIC, "value": value, "unit": "sampled edges/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
@@ -194,7 +210,8 @@ def main():
     }
 
     if not args.no_pcie_pass:
-        feat_pin = rg.make_features(W.is_local, W.row_of, W.local_rows, W.remote_rows, W.row_bytes)
+        remote_pinned = synth.pinned_copy(W.remote_rows)
+        feat_pin = rg.make_features(W.is_local, W.row_of, W.local_rows, remote_pinned, W.row_bytes)
         steps2 = max(1, min(args.steps, 2))
         dt2, prof2 = timed(rg, W, feat_pin, out_buf, W.stride_bytes, m_max, side, steps2, 1)
         miss_ms = prof2["gather_miss"]["ms"] / steps2
@@ -204,6 +221,13 @@ def main():
                                     "note": "remote feature table in pinned host memory; misses and the cache fill cross the host link"}
         log(f"[bench] pinned-host remote table: {dt2 / steps2 * 1e3:.2f} ms/step (miss pull {miss_ms:.2f} ms, cache fill {fill_ms:.2f} ms)")
     rg.rg_profile_enable(False)
+
+    if args.pmc_probe:
+        a = torch.ones(1 << 28, dtype=torch.int32, device="cuda")
+        b = torch.empty_like(a)
+        torch.add(a, 1, out=b)
+        torch.cuda.synchronize()
+        log("[bench] pmc probe: one elementwise kernel read 1 GiB and wrote 1 GiB")
 
     if not args.no_cpu_baseline:
         t0 = time.perf_counter()

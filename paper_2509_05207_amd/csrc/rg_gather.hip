@@ -127,6 +127,10 @@ rg_status launch_gather(const int64_t *entries, int64_t n_rows, const int32_t *l
     const uint64_t per_block = (uint64_t)GATHER_THREADS * CHUNKS_IN_FLIGHT;
     uint64_t blocks = ((uint64_t)n_work * cpt + per_block - 1) / per_block;
     blocks = std::max<uint64_t>(1, std::min<uint64_t>(blocks, (uint64_t)n_cu * 32));
+    if (blocks < (uint64_t)n_cu * 8) {        // a small block of rows: spread it over the chip rather than fill each thread's pipeline
+        const uint64_t by_thread = ((uint64_t)n_work * cpt + GATHER_THREADS - 1) / GATHER_THREADS;
+        blocks = std::max<uint64_t>(blocks, std::min<uint64_t>(by_thread, (uint64_t)n_cu * 8));
+    }
     ScopedTimer tm(group, st);
     switch (vec) {
     case 16: hipLaunchKernelGGL(gather_rows_kernel<16>, dim3((unsigned)blocks), dim3(GATHER_THREADS), 0, st, entries, n_rows, list, n_list, mode, src, row_bytes, out, out_stride); break;

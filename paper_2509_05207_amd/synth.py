@@ -177,13 +177,14 @@ def make_graph(cfg: Config, device="cpu"):
     return indptr, indices, is_local
 
 
-def make_workload(name_or_cfg, device="cpu", feature_device=None, pin_remote=False) -> Workload:
+def make_workload(name_or_cfg, device="cpu", feature_device=None, pin_remote=False, remote_device=None) -> Workload:
     """Build every input of one configuration.
 
     device: where the graph arrays are produced and left.  feature_device:
-    where the local table is left (default: same).  The remote table is left
-    on the host (pinned if pin_remote) when feature_device is a GPU, standing
-    in for the other partitions' memory.
+    where the local table is left (default: same).  remote_device: where the
+    remote table is produced and left; by default the host (pinned if
+    pin_remote) when feature_device is a GPU, standing in for the other
+    partitions' memory.  pinned_copy() moves a table made on the GPU there.
     """
     cfg = CONFIGS[name_or_cfg] if isinstance(name_or_cfg, str) else name_or_cfg
     dev = torch.device(device)
@@ -224,10 +225,17 @@ def make_workload(name_or_cfg, device="cpu", feature_device=None, pin_remote=Fal
                 hi = min(rows, lo + step)
                 t[lo:hi] = torch.randn((hi - lo, se), generator=g, dtype=torch.float32).to(dt)
             return t
-        return torch.randn((rows, se), generator=g, device=where, dtype=torch.float32).to(dt)
+        t = torch.empty((rows, se), dtype=dt, device=where)
+        step = max(1, (1 << 30) // max(se, 1))
+        for lo in range(0, rows, step):
+            hi = min(rows, lo + step)
+            t[lo:hi] = torch.randn((hi - lo, se), generator=g, device=where, dtype=torch.float32).to(dt)
+        return t
 
     local_rows = table(n_local, 1, fdev, False)
-    if fdev.type == "cpu":
+    if remote_device is not None:
+        remote_rows = table(n_remote, 2, torch.device(remote_device), False)
+    elif fdev.type == "cpu":
         remote_rows = table(n_remote, 2, fdev, False)
     else:
         remote_rows = table(n_remote, 2, torch.device("cpu"), pin_remote)
@@ -235,6 +243,14 @@ def make_workload(name_or_cfg, device="cpu", feature_device=None, pin_remote=Fal
     K = cfg.cache_k if cfg.cache_k is not None else int(cfg.cache_frac * n_remote)
     return Workload(cfg, indptr, indices, train, is_local, row_of, local_rows, remote_rows,
                     row_bytes, stride_bytes, K, dict(n_local=n_local, n_remote=n_remote))
+
+
+def pinned_copy(t: torch.Tensor, chunk_rows: int = 1 << 22) -> torch.Tensor:
+    """A pinned host copy of a (device) table, made in chunks."""
+    out = torch.empty(t.shape, dtype=t.dtype, pin_memory=True)
+    for lo in range(0, t.shape[0], chunk_rows):
+        out[lo:lo + chunk_rows].copy_(t[lo:lo + chunk_rows])
+    return out
 
 
 def integer_graph(n: int, deg_lo: int, deg_hi: int, seed: int):
