@@ -190,8 +190,12 @@ rg_status rg_gather_batch(const rg_schedule *s, const rg_cache *c, const rg_feat
                           void *out, uint64_t out_stride, uint64_t out_capacity_rows,
                           void *stream, void *side_stream, rg_gather_stats *stats);
 
+/* Both wait for the device to go idle (kernels may still be reading the handle), then release the
+ * handle.  With the default allocator the device blocks go to a per-process cache that later builds
+ * draw from; rg_trim_memory() hands the cached blocks back to the driver. */
 void rg_schedule_destroy(rg_schedule *s);
 void rg_cache_destroy(rg_cache *c);
+void rg_trim_memory(void);
 
 /* Timing aid for benchmarks: sums, since the last reset, the device time spent
  * in the named kernel group when profiling is enabled (HIP events around each

@@ -20,7 +20,7 @@ KERNEL_GROUPS = ("sampler", "frontier", "shuffle_sort", "histogram", "topk", "pl
 
 EXPORTS = ("rg_last_error", "rg_graph_validate", "rg_build_schedule", "rg_schedule_info", "rg_schedule_frontier",
            "rg_schedule_samples", "rg_build_cache", "rg_cache_view", "rg_gather_batch", "rg_schedule_destroy",
-           "rg_cache_destroy", "rg_profile_enable", "rg_profile_reset", "rg_profile_read")
+           "rg_cache_destroy", "rg_trim_memory", "rg_profile_enable", "rg_profile_reset", "rg_profile_read")
 
 
 class RgError(RuntimeError):
@@ -74,6 +74,7 @@ def lib():
         L.rg_gather_batch.argtypes = [vp, vp, P(rg_features), u32, vp, u64, u64, vp, vp, P(rg_gather_stats)]
         L.rg_schedule_destroy.argtypes = [vp]; L.rg_schedule_destroy.restype = None
         L.rg_cache_destroy.argtypes = [vp]; L.rg_cache_destroy.restype = None
+        L.rg_trim_memory.argtypes = []; L.rg_trim_memory.restype = None
         L.rg_profile_enable.argtypes = [C.c_int]; L.rg_profile_enable.restype = None
         L.rg_profile_reset.argtypes = []; L.rg_profile_reset.restype = None
         L.rg_profile_read.argtypes = [P(C.c_double), P(u64)]
@@ -229,6 +230,11 @@ def rg_gather_batch(s, c, features, batch, out, out_stride=None, out_capacity_ro
                                  int(out_stride), int(out_capacity_rows), _stream_ptr(stream), side,
                                  C.byref(st) if want_stats else None))
     return dict(n_rows=st.n_rows, n_local=st.n_local, n_hit=st.n_hit, n_miss=st.n_miss) if want_stats else None
+
+
+def rg_trim_memory():
+    """Return the library's cached device blocks to the driver."""
+    lib().rg_trim_memory()
 
 
 def rg_profile_enable(on=True):

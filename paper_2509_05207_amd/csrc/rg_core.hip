@@ -5,6 +5,7 @@
 #include <atomic>
 #include <cstdarg>
 #include <cstdio>
+#include <map>
 #include <mutex>
 
 namespace rg {
@@ -19,6 +20,77 @@ void set_error(const char *fmt, ...)
     vsnprintf(g_err, sizeof(g_err), fmt, ap);
     va_end(ap);
 }
+
+// ---------------------------------------------------------------- device block cache
+// hipMalloc / hipFree cost tens of microseconds to milliseconds each and hipFree synchronises the
+// device.  An epoch's build allocates a few dozen buffers whose sizes repeat from epoch to epoch, so
+// released blocks are kept (per device) and handed out again to requests of nearly the same size.
+// Blocks only come back here after the work that used them has completed: the build calls drain their
+// stream before releasing scratch, and the destroy calls synchronise the device first.
+// rg_trim_memory() returns everything to the driver.
+namespace {
+struct BlockCache {
+    std::mutex mu;
+    std::multimap<std::pair<int, uint64_t>, void *> free_blocks;      // (device, bytes) -> block
+    std::map<void *, std::pair<int, uint64_t>> live;                  // blocks handed out
+    uint64_t cached_bytes = 0;
+
+    static uint64_t round_up(uint64_t bytes)
+    {
+        if (bytes <= 4096) return 4096;
+        if (bytes < (1ull << 20)) { uint64_t r = 4096; while (r < bytes) r <<= 1; return r; }
+        return (bytes + (1ull << 20) - 1) >> 20 << 20;
+    }
+
+    void *take(uint64_t bytes, hipError_t *err)
+    {
+        int dev = 0;
+        (void)hipGetDevice(&dev);
+        const uint64_t want = round_up(bytes);
+        {
+            std::lock_guard<std::mutex> lk(mu);
+            auto it = free_blocks.lower_bound({dev, want});
+            if (it != free_blocks.end() && it->first.first == dev && it->first.second <= want + want / 8 + (1ull << 20)) {
+                void *p = it->second;
+                live[p] = it->first;
+                cached_bytes -= it->first.second;
+                free_blocks.erase(it);
+                return p;
+            }
+        }
+        void *p = nullptr;
+        hipError_t e = hipMalloc(&p, want);
+        if (e != hipSuccess) {                       // give the cache back to the driver and try once more
+            (void)hipGetLastError();
+            trim();
+            e = hipMalloc(&p, want);
+        }
+        if (e != hipSuccess) { (void)hipGetLastError(); *err = e; return nullptr; }
+        std::lock_guard<std::mutex> lk(mu);
+        live[p] = {dev, want};
+        return p;
+    }
+
+    void give(void *p)
+    {
+        std::lock_guard<std::mutex> lk(mu);
+        auto it = live.find(p);
+        if (it == live.end()) { (void)hipFree(p); return; }
+        free_blocks.insert({it->second, p});
+        cached_bytes += it->second.second;
+        live.erase(it);
+    }
+
+    void trim()
+    {
+        std::lock_guard<std::mutex> lk(mu);
+        for (auto &kv : free_blocks) (void)hipFree(kv.second);
+        free_blocks.clear();
+        cached_bytes = 0;
+    }
+};
+BlockCache g_blocks;
+}  // namespace
 
 // ---------------------------------------------------------------- arena
 Arena::Arena(const rg_allocator *a)
@@ -37,9 +109,9 @@ rg_status Arena::dev(uint64_t bytes, void **out)
         p = a_.alloc(want, 1, a_.ctx);
         if (!p) { set_error("allocator callback returned NULL for %llu device bytes", (unsigned long long)want); return RG_ENOMEM; }
     } else {
-        hipError_t e = hipMalloc(&p, want);
-        if (e != hipSuccess) {
-            (void)hipGetLastError();
+        hipError_t e = hipSuccess;
+        p = g_blocks.take(want, &e);
+        if (!p) {
             set_error("hipMalloc(%llu) failed: %s", (unsigned long long)want, hipGetErrorString(e));
             return RG_ENOMEM;
         }
@@ -77,7 +149,7 @@ void Arena::free_one(void *p)
     for (size_t i = 0; i < items_.size(); ++i) {
         if (items_[i].p == p) {
             if (custom_) a_.free(p, items_[i].kind, a_.ctx);
-            else if (items_[i].kind == 1) (void)hipFree(p);
+            else if (items_[i].kind == 1) g_blocks.give(p);
             else (void)hipHostFree(p);
             in_use_ -= items_[i].bytes;
             items_[i] = items_.back();
@@ -91,7 +163,7 @@ void Arena::release_all()
 {
     for (auto &it : items_) {
         if (custom_) a_.free(it.p, it.kind, a_.ctx);
-        else if (it.kind == 1) (void)hipFree(it.p);
+        else if (it.kind == 1) g_blocks.give(it.p);
         else (void)hipHostFree(it.p);
     }
     items_.clear();
@@ -103,6 +175,7 @@ static std::atomic<int> g_prof_on{0};
 static std::mutex g_prof_mu;
 struct Pending { int group; hipEvent_t e0, e1; };
 static std::vector<Pending> g_pending;
+static std::vector<hipEvent_t> g_free_events;
 static double g_ms[RG_N_KERNEL_GROUPS];
 static uint64_t g_launches[RG_N_KERNEL_GROUPS];
 
@@ -111,7 +184,14 @@ bool profiling_on() { return g_prof_on.load(std::memory_order_relaxed) != 0; }
 ScopedTimer::ScopedTimer(int g, hipStream_t s) : group(g), st(s)
 {
     if (!profiling_on()) return;
-    if (hipEventCreate(&e0) != hipSuccess || hipEventCreate(&e1) != hipSuccess) { e0 = e1 = nullptr; return; }
+    {
+        std::lock_guard<std::mutex> lk(g_prof_mu);
+        if (g_free_events.size() >= 2) {
+            e0 = g_free_events.back(); g_free_events.pop_back();
+            e1 = g_free_events.back(); g_free_events.pop_back();
+        }
+    }
+    if (!e0 && (hipEventCreate(&e0) != hipSuccess || hipEventCreate(&e1) != hipSuccess)) { e0 = e1 = nullptr; return; }
     (void)hipEventRecord(e0, st);
 }
 
@@ -131,8 +211,8 @@ static void drain_pending_locked()
             g_ms[p.group] += ms;
             g_launches[p.group] += 1;
         }
-        (void)hipEventDestroy(p.e0);
-        (void)hipEventDestroy(p.e1);
+        g_free_events.push_back(p.e0);
+        g_free_events.push_back(p.e1);
     }
     g_pending.clear();
 }
@@ -350,11 +430,19 @@ rg_status rg_cache_view(const rg_cache *c, uint64_t *K_eff, const int32_t **cach
     return RG_OK;
 }
 
-void rg_schedule_destroy(rg_schedule *s) { delete s; }
+void rg_schedule_destroy(rg_schedule *s)
+{
+    if (!s) return;
+    (void)hipDeviceSynchronize();          // kernels that still read the schedule must finish before its blocks are reused
+    delete s;
+}
+
+void rg_trim_memory(void) { g_blocks.trim(); }
 
 void rg_cache_destroy(rg_cache *c)
 {
     if (!c) return;
+    (void)hipDeviceSynchronize();
     if (c->ev_fork) (void)hipEventDestroy(c->ev_fork);
     if (c->ev_join) (void)hipEventDestroy(c->ev_join);
     delete c;
