@@ -336,8 +336,8 @@ __device__ __forceinline__ void sample_long_row(const int32_t *__restrict__ row,
         const unsigned long long vm[4] = {low_lanes(head), 0ull, 0ull, 0ull};
         append_block<CAP>(u, k, vm, f, lo, hi, lane, buf, s);
     }
-    for (int c = c0; c < n_blocks; ++c) {
-        const int left = rem - c * 256;                          // IDs left, this block included
+    for (int c = uni(c0); c < n_blocks; c = uni(c + 1)) {
+        const int left = uni(rem - c * 256);                     // IDs left, this block included
         if (left > 256) nxt = load_block(p + (c + 1) * 256, left - 256, lane);
         if (left >= 256) stream_block<CAP, true>(cur, 256, f, lo, hi, lane, buf, s);
         else stream_block<CAP, false>(cur, left, f, lo, hi, lane, buf, s);
