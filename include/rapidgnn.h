@@ -197,6 +197,67 @@ void rg_schedule_destroy(rg_schedule *s);
 void rg_cache_destroy(rg_cache *c);
 void rg_trim_memory(void);
 
+/* ------------------------------------------------------------------------
+ * Double-buffered cache (Sec. 3 "Precomputation and scheduling": a secondary
+ * cache C_sec is built from the next epoch's schedule while the current epoch
+ * runs and swapped in at the boundary; Alg. 1: "Parallel: build C_sec from
+ * B_{e+1}", "if C_sec ready: C_s <- C_sec"; Sec. 4 par. (6)).  Device bytes of
+ * the two tables never exceed 2 * n_hot * row stride (Sec. 3, memory bound).
+ *
+ *   rg_cache_pair_create      builds C_s from `first_epoch` (as rg_build_cache with one epoch)
+ *   rg_cache_pair_begin_next  starts building C_sec from `next_epoch` on a stream and a host
+ *                             thread of the pair's own and returns at once; `next_epoch` and
+ *                             the feature tables must stay alive until the swap (or destroy).
+ *                             RG_EINVAL while a build is still running.
+ *   rg_cache_pair_swap        at the epoch boundary.  wait == 0: swaps only if C_sec is ready,
+ *                             otherwise C_s keeps serving (gathers of the new epoch then
+ *                             classify on the fly: same bytes, more misses).  wait != 0: waits
+ *                             for the build.  *swapped (host, may be NULL) says what happened.
+ *                             The old C_s is released after the device has gone idle.
+ *                             Returns the build's error if it failed.
+ *   rg_cache_pair_primary     the current C_s: valid until the next successful swap
+ *   rg_cache_pair_table_bytes device bytes held by C_s's table plus a finished C_sec's
+ * One host thread drives a pair; the calls are not re-entrant. */
+typedef struct rg_cache_pair rg_cache_pair;
+rg_status rg_cache_pair_create(const rg_schedule *first_epoch, const rg_features *f, uint64_t K,
+                               const rg_allocator *a, void *stream, rg_cache_pair **out);
+rg_status rg_cache_pair_begin_next(rg_cache_pair *p, const rg_schedule *next_epoch);
+rg_status rg_cache_pair_swap(rg_cache_pair *p, int wait, int *swapped);
+const rg_cache *rg_cache_pair_primary(const rg_cache_pair *p);
+uint64_t rg_cache_pair_table_bytes(const rg_cache_pair *p);
+void rg_cache_pair_destroy(rg_cache_pair *p);
+
+/* ------------------------------------------------------------------------
+ * Rolling prefetch queue of depth Q (Sec. 3 "Rolling prefetch and execution";
+ * Alg. 1 "Parallel: prefetch features for next Q batches"; Sec. 4 par. (4),
+ * (7)): feature blocks of upcoming batches are staged, in schedule order, into
+ * Q caller-owned device buffers by gathers on a stream of the prefetcher's
+ * own; the consumer takes them in order.  Device memory for staged blocks is
+ * Q * slot_capacity_rows * out_stride (the Q * m_max * d term of the bound).
+ *
+ *   slot_buffers   host array of Q device pointers, each slot_capacity_rows * out_stride bytes
+ *   rg_prefetcher_fill     stages batches until staged + held slots == Q or the epoch ends
+ *                          (back-pressure); asynchronous when `c` was built from `s`
+ *   rg_prefetcher_acquire  the next batch in order: *out is its slot.  If it was staged,
+ *                          consumer_stream is made to wait for the data (*was_staged = 1);
+ *                          if not, it is gathered now on consumer_stream -- the default path
+ *                          of Sec. 3 -- and *was_staged = 0.  RG_EINVAL if Q slots are held,
+ *                          RG_ERANGE past the last batch.
+ *   rg_prefetcher_release  the consumer's work queued so far on consumer_stream is the last
+ *                          use of the oldest held slot; it may be refilled after that.
+ * RG_ERANGE at create if a batch has more rows than a slot.  One host thread
+ * drives a prefetcher; s, c and the feature tables are borrowed. */
+typedef struct rg_prefetcher rg_prefetcher;
+rg_status rg_prefetcher_create(const rg_schedule *s, const rg_cache *c, const rg_features *f, uint32_t Q,
+                               void *const *slot_buffers, uint64_t out_stride, uint64_t slot_capacity_rows,
+                               rg_prefetcher **out);
+rg_status rg_prefetcher_fill(rg_prefetcher *p, uint32_t *issued /* host or NULL */);
+rg_status rg_prefetcher_acquire(rg_prefetcher *p, void *consumer_stream, uint32_t *batch, void **out,
+                                rg_gather_stats *stats, int *was_staged);
+rg_status rg_prefetcher_release(rg_prefetcher *p, void *consumer_stream);
+rg_status rg_prefetcher_depth(const rg_prefetcher *p, uint32_t *staged_not_acquired, uint32_t *held);
+void rg_prefetcher_destroy(rg_prefetcher *p);
+
 /* Timing aid for benchmarks: sums, since the last reset, the device time spent
  * in the named kernel group when profiling is enabled (HIP events around each
  * launch on the launch stream; adds a little latency).  Groups: 0 sampler

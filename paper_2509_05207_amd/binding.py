@@ -20,7 +20,11 @@ KERNEL_GROUPS = ("sampler", "frontier", "shuffle_sort", "histogram", "topk", "pl
 
 EXPORTS = ("rg_last_error", "rg_graph_validate", "rg_build_schedule", "rg_schedule_info", "rg_schedule_frontier",
            "rg_schedule_samples", "rg_build_cache", "rg_cache_view", "rg_gather_batch", "rg_schedule_destroy",
-           "rg_cache_destroy", "rg_trim_memory", "rg_profile_enable", "rg_profile_reset", "rg_profile_read")
+           "rg_cache_destroy", "rg_trim_memory", "rg_profile_enable", "rg_profile_reset", "rg_profile_read",
+           "rg_cache_pair_create", "rg_cache_pair_begin_next", "rg_cache_pair_swap", "rg_cache_pair_primary",
+           "rg_cache_pair_table_bytes", "rg_cache_pair_destroy",
+           "rg_prefetcher_create", "rg_prefetcher_fill", "rg_prefetcher_acquire", "rg_prefetcher_release",
+           "rg_prefetcher_depth", "rg_prefetcher_destroy")
 
 
 class RgError(RuntimeError):
@@ -78,8 +82,23 @@ def lib():
         L.rg_profile_enable.argtypes = [C.c_int]; L.rg_profile_enable.restype = None
         L.rg_profile_reset.argtypes = []; L.rg_profile_reset.restype = None
         L.rg_profile_read.argtypes = [P(C.c_double), P(u64)]
+        L.rg_cache_pair_create.argtypes = [vp, P(rg_features), u64, P(rg_allocator), vp, P(vp)]
+        L.rg_cache_pair_begin_next.argtypes = [vp, vp]
+        L.rg_cache_pair_swap.argtypes = [vp, C.c_int, P(C.c_int)]
+        L.rg_cache_pair_primary.argtypes = [vp]; L.rg_cache_pair_primary.restype = vp
+        L.rg_cache_pair_table_bytes.argtypes = [vp]; L.rg_cache_pair_table_bytes.restype = u64
+        L.rg_cache_pair_destroy.argtypes = [vp]; L.rg_cache_pair_destroy.restype = None
+        L.rg_prefetcher_create.argtypes = [vp, vp, P(rg_features), u32, P(vp), u64, u64, P(vp)]
+        L.rg_prefetcher_fill.argtypes = [vp, P(u32)]
+        L.rg_prefetcher_acquire.argtypes = [vp, vp, P(u32), P(vp), P(rg_gather_stats), P(C.c_int)]
+        L.rg_prefetcher_release.argtypes = [vp, vp]
+        L.rg_prefetcher_depth.argtypes = [vp, P(u32), P(u32)]
+        L.rg_prefetcher_destroy.argtypes = [vp]; L.rg_prefetcher_destroy.restype = None
         for name in ("rg_graph_validate", "rg_build_schedule", "rg_schedule_info", "rg_schedule_frontier", "rg_schedule_samples",
-                     "rg_build_cache", "rg_cache_view", "rg_gather_batch", "rg_profile_read"):
+                     "rg_build_cache", "rg_cache_view", "rg_gather_batch", "rg_profile_read",
+                     "rg_cache_pair_create", "rg_cache_pair_begin_next", "rg_cache_pair_swap",
+                     "rg_prefetcher_create", "rg_prefetcher_fill", "rg_prefetcher_acquire", "rg_prefetcher_release",
+                     "rg_prefetcher_depth"):
             getattr(L, name).restype = C.c_int32
         _lib = L
     return _lib
@@ -230,6 +249,106 @@ def rg_gather_batch(s, c, features, batch, out, out_stride=None, out_capacity_ro
                                  int(out_stride), int(out_capacity_rows), _stream_ptr(stream), side,
                                  C.byref(st) if want_stats else None))
     return dict(n_rows=st.n_rows, n_local=st.n_local, n_hit=st.n_hit, n_miss=st.n_miss) if want_stats else None
+
+
+class _BorrowedCache:
+    """A cache handle owned by something else (a cache pair)."""
+
+    def __init__(self, handle, owner):
+        self.h = C.c_void_p(handle)
+        self._owner = owner
+
+
+class CachePair:
+    def __init__(self, handle, keep):
+        self.h = C.c_void_p(handle)
+        self._keep = list(keep)
+
+    def __del__(self):
+        if getattr(self, "h", None) and _lib is not None:
+            _lib.rg_cache_pair_destroy(self.h)
+            self.h = None
+
+
+def rg_cache_pair_create(first_epoch, features, K, allocator=None, stream=None):
+    out = C.c_void_p()
+    _check(lib().rg_cache_pair_create(first_epoch.h, C.byref(features), int(K),
+                                      C.byref(allocator) if allocator is not None else None, _stream_ptr(stream), C.byref(out)))
+    return CachePair(out.value, (features, first_epoch, allocator))
+
+
+def rg_cache_pair_begin_next(p, next_epoch):
+    p._keep.append(next_epoch)
+    _check(lib().rg_cache_pair_begin_next(p.h, next_epoch.h))
+
+
+def rg_cache_pair_swap(p, wait=False):
+    """True if C_sec was swapped in."""
+    sw = C.c_int(0)
+    _check(lib().rg_cache_pair_swap(p.h, 1 if wait else 0, C.byref(sw)))
+    return bool(sw.value)
+
+
+def rg_cache_pair_primary(p):
+    return _BorrowedCache(lib().rg_cache_pair_primary(p.h), p)
+
+
+def rg_cache_pair_table_bytes(p):
+    return int(lib().rg_cache_pair_table_bytes(p.h))
+
+
+class Prefetcher:
+    def __init__(self, handle, keep, slots, out_stride):
+        self.h = C.c_void_p(handle)
+        self._keep = keep
+        self.slots = slots
+        self.out_stride = out_stride
+        self._by_ptr = {t.data_ptr(): i for i, t in enumerate(slots)}
+
+    def __del__(self):
+        if getattr(self, "h", None) and _lib is not None:
+            _lib.rg_prefetcher_destroy(self.h)
+            self.h = None
+
+
+def rg_prefetcher_create(s, c, features, slots, out_stride=None, slot_capacity_rows=None):
+    """`slots`: list of Q equally sized contiguous device tensors, one staged feature block each."""
+    Q = len(slots)
+    assert all(t.is_cuda and t.is_contiguous() for t in slots)
+    if out_stride is None:
+        out_stride = slots[0].stride(0) * slots[0].element_size()
+    if slot_capacity_rows is None:
+        slot_capacity_rows = min(t.numel() * t.element_size() for t in slots) // out_stride
+    ptrs = (C.c_void_p * max(Q, 1))(*[t.data_ptr() for t in slots])
+    out = C.c_void_p()
+    _check(lib().rg_prefetcher_create(s.h, c.h if c is not None else None, C.byref(features), Q, ptrs, int(out_stride),
+                                      int(slot_capacity_rows), C.byref(out)))
+    return Prefetcher(out.value, (s, c, features), list(slots), int(out_stride))
+
+
+def rg_prefetcher_fill(p):
+    n = C.c_uint32(0)
+    _check(lib().rg_prefetcher_fill(p.h, C.byref(n)))
+    return n.value
+
+
+def rg_prefetcher_acquire(p, stream=None):
+    """(batch, slot tensor, stats dict, was_staged) of the next batch in schedule order."""
+    b, out, st, staged = C.c_uint32(), C.c_void_p(), rg_gather_stats(), C.c_int(0)
+    _check(lib().rg_prefetcher_acquire(p.h, _stream_ptr(stream), C.byref(b), C.byref(out), C.byref(st), C.byref(staged)))
+    stats = dict(n_rows=st.n_rows, n_local=st.n_local, n_hit=st.n_hit, n_miss=st.n_miss)
+    return b.value, p.slots[p._by_ptr[out.value]], stats, bool(staged.value)
+
+
+def rg_prefetcher_release(p, stream=None):
+    _check(lib().rg_prefetcher_release(p.h, _stream_ptr(stream)))
+
+
+def rg_prefetcher_depth(p):
+    """(staged and not yet acquired, held by the consumer)."""
+    a, h = C.c_uint32(), C.c_uint32()
+    _check(lib().rg_prefetcher_depth(p.h, C.byref(a), C.byref(h)))
+    return a.value, h.value
 
 
 def rg_trim_memory():

@@ -1,0 +1,193 @@
+"""GPU tests of the runtime around the three calls: the double-buffered cache (C_s / C_sec) and the
+rolling prefetch queue of depth Q (Alg. 1, Sec. 3 "Rolling prefetch and execution"), against the oracle.
+
+Every gathered byte must equal the oracle's whatever the pipeline state: staged or not, swapped or not."""
+import numpy as np
+import pytest
+import torch
+
+from paper_2509_05207_amd import synth
+from test_gpu_parity import Case
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def rg():
+    from paper_2509_05207_amd import binding
+    binding.lib()
+    assert torch.cuda.is_available(), "GPU tests need a GPU"
+    return binding
+
+
+@pytest.fixture(scope="module", params=["small", "mid_bf16"])
+def case(request, orc, rg):
+    return Case(request.param, orc, rg, s0=11, worker=1, epoch=0, pinned_remote=(request.param == "small"))
+
+
+def oracle_cache(orc, case, osched):
+    w = case.w
+    freq = orc.frequency([osched], w.n_nodes)
+    ids, slot = orc.top_hot(freq, w.is_local.numpy(), w.K)
+    return ids, slot
+
+
+def slots_for(case, Q, out_stride):
+    _, off = case.osched.input_nodes()
+    m_max = int(np.diff(off).max())
+    return [torch.full(((m_max + 1) * out_stride,), 0xCD, dtype=torch.uint8, device="cuda") for _ in range(Q)], m_max
+
+
+@pytest.mark.parametrize("Q", [1, 3, 64])
+def test_prefetch_queue_delivers_every_batch_in_order(case, rg, orc, Q):
+    w = case.w
+    out_stride = (w.row_bytes + 15) // 16 * 16
+    cache = rg.rg_build_cache([case.gsched], case.gfeat, w.K)
+    _, slot = oracle_cache(orc, case, case.osched)
+    slots, m_max = slots_for(case, Q, out_stride)
+    pf = rg.rg_prefetcher_create(case.gsched, cache, case.gfeat, slots, out_stride=out_stride, slot_capacity_rows=m_max + 1)
+    nb = case.gsched.n_batches
+    consumer = torch.cuda.Stream()
+    for b in range(nb):
+        issued = rg.rg_prefetcher_fill(pf)
+        staged, held = rg.rg_prefetcher_depth(pf)
+        assert held == 0 and staged == min(Q, nb - b), "back-pressure: the queue holds min(Q, remaining) batches"
+        assert issued == (min(Q, nb) if b == 0 else (1 if b + Q <= nb else 0))
+        got_b, buf, st, was_staged = rg.rg_prefetcher_acquire(pf, stream=consumer)
+        assert got_b == b and was_staged
+        with torch.cuda.stream(consumer):
+            block = buf.clone()                  # the consumer's use of the slot, ordered on its own stream
+        rg.rg_prefetcher_release(pf, stream=consumer)
+        consumer.synchronize()
+        ref = orc.gather_batch(case.osched, b, case.ofeat, out_stride=out_stride, fill=0xCD)
+        m = ref.shape[0]
+        assert np.array_equal(block.cpu().numpy().reshape(-1, out_stride)[:m, :w.row_bytes], ref[:, :w.row_bytes]), f"batch {b}"
+        assert st == orc.batch_stats(case.osched, b, w.is_local.numpy(), slot)
+    with pytest.raises(rg.RgError) as e:
+        rg.rg_prefetcher_acquire(pf)
+    assert e.value.status == rg.RG_ERANGE
+
+
+def test_unstaged_batches_take_the_default_path(case, rg, orc):
+    """The consumer overtakes the prefetcher: the batch is gathered on the spot, same bytes (Sec. 3, race)."""
+    w = case.w
+    out_stride = w.row_bytes
+    cache = rg.rg_build_cache([case.gsched], case.gfeat, w.K)
+    slots, m_max = slots_for(case, 2, out_stride)
+    pf = rg.rg_prefetcher_create(case.gsched, cache, case.gfeat, slots, out_stride=out_stride, slot_capacity_rows=m_max + 1)
+    nb = case.gsched.n_batches
+    flags = []
+    for b in range(nb):
+        if b % 3 == 1:
+            rg.rg_prefetcher_fill(pf)            # only now and then: some batches arrive staged, others do not
+        got_b, buf, st, was_staged = rg.rg_prefetcher_acquire(pf)
+        flags.append(was_staged)
+        torch.cuda.synchronize()
+        ref = orc.gather_batch(case.osched, b, case.ofeat, out_stride=out_stride, fill=0xCD)
+        m = ref.shape[0]
+        assert got_b == b
+        assert np.array_equal(buf.cpu().numpy().reshape(-1, out_stride)[:m], ref), f"batch {b}"
+        rg.rg_prefetcher_release(pf)
+    assert not flags[0] and any(flags) and not all(flags)
+
+
+def test_holding_more_than_q_slots_is_refused(case, rg):
+    w = case.w
+    slots, m_max = slots_for(case, 2, w.row_bytes)
+    pf = rg.rg_prefetcher_create(case.gsched, None, case.gfeat, slots, out_stride=w.row_bytes, slot_capacity_rows=m_max + 1)
+    if case.gsched.n_batches < 3:
+        pytest.skip("needs three batches")
+    rg.rg_prefetcher_acquire(pf)
+    rg.rg_prefetcher_acquire(pf)
+    with pytest.raises(rg.RgError) as e:
+        rg.rg_prefetcher_acquire(pf)
+    assert e.value.status == rg.RG_EINVAL
+    assert rg.rg_prefetcher_fill(pf) == 0                      # nothing can be staged while both slots are held
+    rg.rg_prefetcher_release(pf)
+    assert rg.rg_prefetcher_fill(pf) == 1
+    torch.cuda.synchronize()
+    rg.rg_prefetcher_release(pf)
+    with pytest.raises(rg.RgError):
+        rg.rg_prefetcher_release(pf)                           # nothing is held any more
+
+
+def test_slots_smaller_than_the_largest_batch_are_refused(case, rg):
+    w = case.w
+    slots, m_max = slots_for(case, 2, w.row_bytes)
+    with pytest.raises(rg.RgError) as e:
+        rg.rg_prefetcher_create(case.gsched, None, case.gfeat, slots, out_stride=w.row_bytes, slot_capacity_rows=m_max - 1)
+    assert e.value.status == rg.RG_ERANGE
+
+
+def test_double_buffered_cache_follows_the_epochs(case, rg, orc):
+    """C_sec built from B_{e+1} while epoch e gathers; after the swap it equals the oracle's cache of epoch e+1."""
+    w = case.w
+    n_epochs = 3
+    osch = [case.osched] + [orc.Schedule(w.indptr.numpy(), w.indices.numpy(), w.train.numpy(), w.cfg.batch_size, w.cfg.fanout,
+                                         case.s0, case.worker, e, n_threads=8) for e in range(1, n_epochs)]
+    gsch = [case.gsched] + [rg.rg_build_schedule(case.indptr, case.indices, case.train, w.cfg.batch_size, w.cfg.fanout,
+                                                 case.s0, case.worker, e) for e in range(1, n_epochs)]
+    out_stride = w.row_bytes
+    _, off = case.osched.input_nodes()
+    m_cap = max(int(np.diff(o.input_nodes()[1]).max()) for o in osch)
+    out = torch.empty(m_cap * out_stride, dtype=torch.uint8, device="cuda")
+    pair = rg.rg_cache_pair_create(gsch[0], case.gfeat, w.K)
+    table_stride = (w.row_bytes + 15) // 16 * 16
+    for e in range(n_epochs):
+        ids, slot = oracle_cache(orc, case, osch[e])
+        cur = rg.rg_cache_pair_primary(pair)
+        v = rg.rg_cache_view(cur, w.n_nodes)
+        assert np.array_equal(v["cache_ids"].cpu().numpy(), ids), f"epoch {e}: C_s is not the top-K of this epoch's schedule"
+        if e + 1 < n_epochs:
+            rg.rg_cache_pair_begin_next(pair, gsch[e + 1])     # runs beside the gathers below
+        for b in range(gsch[e].n_batches):
+            out.fill_(0xCD)
+            st = rg.rg_gather_batch(gsch[e], cur, case.gfeat, b, out, out_stride=out_stride, out_capacity_rows=m_cap)
+            torch.cuda.synchronize()
+            ref = orc.gather_batch(osch[e], b, case.ofeat, out_stride=out_stride, fill=0xCD)
+            assert np.array_equal(out.cpu().numpy().reshape(m_cap, out_stride)[:ref.shape[0]], ref), f"epoch {e} batch {b}"
+            assert st == orc.batch_stats(osch[e], b, w.is_local.numpy(), slot)
+            assert rg.rg_cache_pair_table_bytes(pair) <= 2 * w.K * table_stride, "memory bound 2 * n_hot * d"
+        if e + 1 < n_epochs:
+            assert rg.rg_cache_pair_swap(pair, wait=True)
+    assert not rg.rg_cache_pair_swap(pair, wait=True)          # nothing pending: C_s stays
+
+
+def test_an_unswapped_cache_still_serves_the_next_epoch_exactly(case, rg, orc):
+    """"If C_sec ready" fails: the old C_s serves epoch e+1; hits are those of the old cache, bytes are unchanged."""
+    w = case.w
+    o1 = orc.Schedule(w.indptr.numpy(), w.indices.numpy(), w.train.numpy(), w.cfg.batch_size, w.cfg.fanout, case.s0, case.worker, 1,
+                      n_threads=8)
+    g1 = rg.rg_build_schedule(case.indptr, case.indices, case.train, w.cfg.batch_size, w.cfg.fanout, case.s0, case.worker, 1)
+    pair = rg.rg_cache_pair_create(case.gsched, case.gfeat, w.K)
+    _, slot0 = oracle_cache(orc, case, case.osched)
+    cur = rg.rg_cache_pair_primary(pair)                       # no begin_next: nothing to swap
+    assert not rg.rg_cache_pair_swap(pair, wait=False)
+    m_cap = int(np.diff(o1.input_nodes()[1]).max())
+    out = torch.empty(m_cap * w.row_bytes, dtype=torch.uint8, device="cuda")
+    for b in range(0, g1.n_batches, max(1, g1.n_batches // 4)):
+        st = rg.rg_gather_batch(g1, cur, case.gfeat, b, out, out_stride=w.row_bytes, out_capacity_rows=m_cap)
+        torch.cuda.synchronize()
+        ref = orc.gather_batch(o1, b, case.ofeat, out_stride=w.row_bytes, fill=0xCD)
+        assert np.array_equal(out.cpu().numpy().reshape(m_cap, w.row_bytes)[:ref.shape[0]], ref)
+        assert st == orc.batch_stats(o1, b, w.is_local.numpy(), slot0)
+
+
+def test_begin_next_twice_without_swap_replaces_the_pending_cache(case, rg, orc):
+    w = case.w
+    g1 = rg.rg_build_schedule(case.indptr, case.indices, case.train, w.cfg.batch_size, w.cfg.fanout, case.s0, case.worker, 1)
+    g2 = rg.rg_build_schedule(case.indptr, case.indices, case.train, w.cfg.batch_size, w.cfg.fanout, case.s0, case.worker, 2)
+    o2 = orc.Schedule(w.indptr.numpy(), w.indices.numpy(), w.train.numpy(), w.cfg.batch_size, w.cfg.fanout, case.s0, case.worker, 2,
+                      n_threads=8)
+    pair = rg.rg_cache_pair_create(case.gsched, case.gfeat, w.K)
+    rg.rg_cache_pair_begin_next(pair, g1)
+    while True:                                                # a second begin is refused while the first build runs
+        try:
+            rg.rg_cache_pair_begin_next(pair, g2)
+            break
+        except rg.RgError as e:
+            assert e.status == rg.RG_EINVAL
+    assert rg.rg_cache_pair_swap(pair, wait=True)
+    ids, _ = oracle_cache(orc, case, o2)
+    v = rg.rg_cache_view(rg.rg_cache_pair_primary(pair), w.n_nodes)
+    assert np.array_equal(v["cache_ids"].cpu().numpy(), ids)
