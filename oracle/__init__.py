@@ -54,6 +54,7 @@ def lib():
         L.orc_schedule_samples_size.restype = i64; L.orc_schedule_samples_size.argtypes = [vp, u32]
         L.orc_schedule_get_frontier.restype = None; L.orc_schedule_get_frontier.argtypes = [vp, u32, vp, vp]
         L.orc_schedule_get_samples.restype = None; L.orc_schedule_get_samples.argtypes = [vp, u32, vp, vp]
+        L.orc_schedule_get_block.restype = C.c_int; L.orc_schedule_get_block.argtypes = [vp, u32, vp]
         L.orc_frequency.restype = None; L.orc_frequency.argtypes = [vp, u32, i64, vp]
         L.orc_top_hot.restype = i64; L.orc_top_hot.argtypes = [vp, vp, i64, u64, vp, vp]
         L.orc_cache_fill.restype = None
@@ -141,6 +142,15 @@ class Schedule:
         nbr = np.empty(m, np.int32)
         lib().orc_schedule_get_samples(self.h, hop, _p(off), _p(nbr))
         return off, nbr
+
+    def block(self, hop):
+        """src_pos: position in the batch's U_{hop+1} of every sampled neighbour of hop `hop`."""
+        if not 0 <= hop < self.L:
+            raise RuntimeError(f"block of hop {hop}: the schedule has hops 0..{self.L - 1}")
+        pos = np.empty(lib().orc_schedule_samples_size(self.h, hop), np.int32)
+        if lib().orc_schedule_get_block(self.h, hop, _p(pos)) != 0:
+            raise RuntimeError("orc_schedule_get_block failed")
+        return pos
 
     def seeds(self):
         return self.frontier(0)

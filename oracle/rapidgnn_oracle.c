@@ -438,6 +438,38 @@ void orc_schedule_get_samples(const orc_schedule *s, uint32_t hop, int64_t *samp
 }
 
 /* ------------------------------------------------------------------ */
+/* Computation block of hop l, batch b (Sec. 4 par. (8): the sampled   */
+/* subgraph handed to the trainer).  Destination nodes are U_l of the  */
+/* batch, source nodes are U_{l+1} of the batch; since U_{l+1} starts  */
+/* with U_l, destination j is also source j.  The block's edges are    */
+/* the hop's samples with every neighbour ID replaced by its position  */
+/* in the batch's U_{l+1}: src_pos[k] = p  <=>  U_{l+1,b}[p] = nbr[k]. */
+/* Returns 0, or -1 if a sampled ID is missing from U_{l+1} (never,    */
+/* for a schedule built above) or memory ran out.                      */
+/* ------------------------------------------------------------------ */
+int orc_schedule_get_block(const orc_schedule *s, uint32_t hop, int32_t *src_pos)
+{
+    if (hop >= s->L) return -1;
+    int32_t *where = (int32_t *)malloc(((size_t)s->n_nodes + 1) * sizeof(int32_t));
+    if (!where) return -1;
+    for (int64_t v = 0; v < s->n_nodes; ++v) where[v] = -1;
+    int err = 0;
+    for (uint32_t b = 0; b < s->n_batches && !err; ++b) {
+        const int64_t u0 = s->fr_off[hop + 1][b], u1 = s->fr_off[hop + 1][b + 1];
+        for (int64_t j = u0; j < u1; ++j) where[s->fr_ids[hop + 1][j]] = (int32_t)(j - u0);
+        const int64_t k0 = s->samp_off[hop][s->fr_off[hop][b]], k1 = s->samp_off[hop][s->fr_off[hop][b + 1]];
+        for (int64_t k = k0; k < k1; ++k) {
+            const int32_t p = where[s->samp_nbr[hop][k]];
+            if (p < 0) err = 1;
+            src_pos[k] = p;
+        }
+        for (int64_t j = u0; j < u1; ++j) where[s->fr_ids[hop + 1][j]] = -1;
+    }
+    free(where);
+    return err ? -1 : 0;
+}
+
+/* ------------------------------------------------------------------ */
 /* freq(v) = number of batches whose input set N_i^e contains v        */
 /* (a feature is fetched once per batch that needs it), over all the   */
 /* epochs given.  Tallied for every ID; the remote filter is applied   */
