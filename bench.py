@@ -72,6 +72,51 @@ def timed(rg, W, feat, out_buf, out_stride, cap_rows, side, steps, warmup):
     return dt, rg.rg_profile_read()
 
 
+def runtime_leg(rg, W, feat, epochs=3, Q=4):
+    """The rows after the three calls: E epochs with the double-buffered cache and the depth-Q prefetch queue,
+    and the computation blocks of one epoch.  Reported beside the headline figure, never part of it."""
+    cfg = W.cfg
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    scheds = [rg.rg_build_schedule(W.indptr, W.indices, W.train, cfg.batch_size, cfg.fanout, cfg.s0, cfg.worker, cfg.epoch + e)
+              for e in range(epochs)]
+    t_sched = time.perf_counter() - t0
+    m_cap = max(int(np.diff(rg.rg_schedule_frontier(s, s.L)[2]).max()) for s in scheds)
+    slots = [torch.empty(m_cap * W.stride_bytes, dtype=torch.uint8, device="cuda") for _ in range(Q)]
+    pair = rg.rg_cache_pair_create(scheds[0], feat, W.K)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    staged = total = 0
+    for e in range(epochs):
+        if e + 1 < epochs:
+            rg.rg_cache_pair_begin_next(pair, scheds[e + 1])
+        pf = rg.rg_prefetcher_create(scheds[e], rg.rg_cache_pair_primary(pair), feat, slots, out_stride=W.stride_bytes,
+                                     slot_capacity_rows=m_cap)
+        for _ in range(scheds[e].n_batches):
+            rg.rg_prefetcher_fill(pf)
+            _, _, _, was = rg.rg_prefetcher_acquire(pf)
+            rg.rg_prefetcher_release(pf)
+            staged += int(was)
+            total += 1
+        del pf
+        if e + 1 < epochs:
+            assert rg.rg_cache_pair_swap(pair, wait=True)
+    torch.cuda.synchronize()
+    t_run = time.perf_counter() - t0
+    table_bytes = rg.rg_cache_pair_table_bytes(pair)
+    del pair
+    rg.rg_profile_reset()
+    t0 = time.perf_counter()
+    rg.rg_schedule_build_blocks(scheds[0])
+    t_blk = time.perf_counter() - t0
+    blk = rg.rg_profile_read()["blocks"]
+    n_samp = sum(rg.rg_schedule_block(scheds[0], h).numel() for h in range(scheds[0].L))
+    return {"epochs": epochs, "Q": Q, "schedule_build_ms_per_epoch": t_sched / epochs * 1e3,
+            "gather_epoch_ms_with_next_cache_built_alongside": t_run / epochs * 1e3, "staged_fraction": staged / max(1, total),
+            "cache_table_bytes": table_bytes, "staging_bytes": Q * m_cap * W.stride_bytes,
+            "blocks_ms_per_epoch": t_blk * 1e3, "blocks_kernel_ms": blk["ms"], "block_edges": n_samp}
+
+
 def cpu_baseline(W, indptr_h, indices_h, train_h, budget_s=15.0):
     """The oracle, as it stands, on a bounded prefix of the epoch's batches."""
     import oracle
@@ -124,6 +169,7 @@ def main():
     ap.add_argument("--workload", default="medium", choices=sorted(synth.CONFIGS))
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-pcie-pass", action="store_true")
+    ap.add_argument("--no-runtime-leg", action="store_true", help="skip the multi-epoch cache-pair / prefetch-queue / blocks leg")
     ap.add_argument("--pmc-probe", action="store_true",
                     help="also run one plain elementwise kernel of known size (1 GiB read + 1 GiB written), the yardstick "
                          "that rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE readings of the library's kernels are scaled by")
@@ -220,6 +266,9 @@ def main():
                                     "steps": steps2, "miss_pull_ms_per_step": miss_ms, "cache_fill_ms_per_step": fill_ms,
                                     "note": "remote feature table in pinned host memory; misses and the cache fill cross the host link"}
         log(f"[bench] pinned-host remote table: {dt2 / steps2 * 1e3:.2f} ms/step (miss pull {miss_ms:.2f} ms, cache fill {fill_ms:.2f} ms)")
+    if not args.no_runtime_leg:
+        result["runtime"] = runtime_leg(rg, W, feat_hbm)
+        log(f"[bench] runtime leg: {result['runtime']}")
     rg.rg_profile_enable(False)
 
     if args.pmc_probe:

@@ -198,6 +198,24 @@ void rg_cache_destroy(rg_cache *c);
 void rg_trim_memory(void);
 
 /* ------------------------------------------------------------------------
+ * Computation blocks (Sec. 4 par. (8): the subgraph information of a batch is
+ * gathered into the block the trainer runs on).  Block of hop l, batch b:
+ *   destinations = U_l of the batch, sources = U_{l+1} of the batch (U_{l+1}
+ *   starts with U_l, so destination j is source j), edges = the hop's samples.
+ * rg_schedule_build_blocks computes, for every hop, src_pos[k] = the position
+ * of samp_nbr[k] in its batch's U_{l+1}.  With samp_off (rg_schedule_samples)
+ * this is the block's CSR in block-local indices; rows of the gathered feature
+ * block (rg_gather_batch) are in source order of the outermost block.
+ *   workspace_limit_bytes  device scratch for position tables, 4 * n_nodes
+ *                          bytes per batch processed together; 0 = 4 GiB.
+ *                          At least one batch's table is always allocated.
+ * Waits for `stream`.  A second call is a no-op.  rg_schedule_block returns
+ * RG_EINVAL before the blocks are built, RG_ERANGE for hop >= L.
+ *   src_pos_dev  dev int32 [n_samples of the hop], owned by the schedule */
+rg_status rg_schedule_build_blocks(rg_schedule *s, uint64_t workspace_limit_bytes, void *stream);
+rg_status rg_schedule_block(const rg_schedule *s, uint32_t hop, const int32_t **src_pos_dev);
+
+/* ------------------------------------------------------------------------
  * Double-buffered cache (Sec. 3 "Precomputation and scheduling": a secondary
  * cache C_sec is built from the next epoch's schedule while the current epoch
  * runs and swapped in at the boundary; Alg. 1: "Parallel: build C_sec from
@@ -263,8 +281,9 @@ void rg_prefetcher_destroy(rg_prefetcher *p);
  * launch on the launch stream; adds a little latency).  Groups: 0 sampler
  * (the per-node sampling kernel alone), 1 frontier (mark/scan/emit), 2 shuffle
  * sort, 3 histogram, 4 top-K, 5 plan, 6 cache fill, 7 gather (HBM sources),
- * 8 gather (miss pull), 9 sample sizes and their prefix sum. */
-#define RG_N_KERNEL_GROUPS 10
+ * 8 gather (miss pull), 9 sample sizes and their prefix sum, 10 computation
+ * blocks. */
+#define RG_N_KERNEL_GROUPS 11
 void rg_profile_enable(int on);
 void rg_profile_reset(void);
 rg_status rg_profile_read(double *ms /* host, [RG_N_KERNEL_GROUPS] */, uint64_t *launches /* host, same */);

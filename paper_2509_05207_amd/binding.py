@@ -16,7 +16,7 @@ _LIB_PATH = os.path.join(_HERE, "librapidgnn_hip.so")
 
 RG_OK, RG_EINVAL, RG_ENOMEM, RG_EHIP, RG_ERANGE = 0, -1, -2, -3, -4
 RG_MAX_HOPS, RG_MAX_FANOUT = 8, 1984
-KERNEL_GROUPS = ("sampler", "frontier", "shuffle_sort", "histogram", "topk", "plan", "cache_fill", "gather", "gather_miss", "sample_offsets")
+KERNEL_GROUPS = ("sampler", "frontier", "shuffle_sort", "histogram", "topk", "plan", "cache_fill", "gather", "gather_miss", "sample_offsets", "blocks")
 
 EXPORTS = ("rg_last_error", "rg_graph_validate", "rg_build_schedule", "rg_schedule_info", "rg_schedule_frontier",
            "rg_schedule_samples", "rg_build_cache", "rg_cache_view", "rg_gather_batch", "rg_schedule_destroy",
@@ -24,7 +24,7 @@ EXPORTS = ("rg_last_error", "rg_graph_validate", "rg_build_schedule", "rg_schedu
            "rg_cache_pair_create", "rg_cache_pair_begin_next", "rg_cache_pair_swap", "rg_cache_pair_primary",
            "rg_cache_pair_table_bytes", "rg_cache_pair_destroy",
            "rg_prefetcher_create", "rg_prefetcher_fill", "rg_prefetcher_acquire", "rg_prefetcher_release",
-           "rg_prefetcher_depth", "rg_prefetcher_destroy")
+           "rg_prefetcher_depth", "rg_prefetcher_destroy", "rg_schedule_build_blocks", "rg_schedule_block")
 
 
 class RgError(RuntimeError):
@@ -82,6 +82,8 @@ def lib():
         L.rg_profile_enable.argtypes = [C.c_int]; L.rg_profile_enable.restype = None
         L.rg_profile_reset.argtypes = []; L.rg_profile_reset.restype = None
         L.rg_profile_read.argtypes = [P(C.c_double), P(u64)]
+        L.rg_schedule_build_blocks.argtypes = [vp, u64, vp]
+        L.rg_schedule_block.argtypes = [vp, u32, P(vp)]
         L.rg_cache_pair_create.argtypes = [vp, P(rg_features), u64, P(rg_allocator), vp, P(vp)]
         L.rg_cache_pair_begin_next.argtypes = [vp, vp]
         L.rg_cache_pair_swap.argtypes = [vp, C.c_int, P(C.c_int)]
@@ -98,7 +100,7 @@ def lib():
                      "rg_build_cache", "rg_cache_view", "rg_gather_batch", "rg_profile_read",
                      "rg_cache_pair_create", "rg_cache_pair_begin_next", "rg_cache_pair_swap",
                      "rg_prefetcher_create", "rg_prefetcher_fill", "rg_prefetcher_acquire", "rg_prefetcher_release",
-                     "rg_prefetcher_depth"):
+                     "rg_prefetcher_depth", "rg_schedule_build_blocks", "rg_schedule_block"):
             getattr(L, name).restype = C.c_int32
         _lib = L
     return _lib
@@ -203,6 +205,18 @@ def rg_schedule_samples(s, hop):
     _check(lib().rg_schedule_samples(s.h, int(hop), C.byref(so), C.byref(sn), C.byref(ns)))
     _, _, off_host = rg_schedule_frontier(s, hop)
     return _view(so.value, int(off_host[-1]) + 1, "<i8", s), _view(sn.value, ns.value, "<i4", s)
+
+
+def rg_schedule_build_blocks(s, workspace_limit_bytes=0, stream=None):
+    _check(lib().rg_schedule_build_blocks(s.h, int(workspace_limit_bytes), _stream_ptr(stream)))
+
+
+def rg_schedule_block(s, hop):
+    """src_pos device tensor: block-local source index of every sample of the hop."""
+    p, ns = C.c_void_p(), C.c_int64()
+    _check(lib().rg_schedule_block(s.h, int(hop), C.byref(p)))
+    _check(lib().rg_schedule_samples(s.h, int(hop), None, None, C.byref(ns)))
+    return _view(p.value, ns.value, "<i4", s)
 
 
 def make_features(is_local, row_of, local_rows, remote_rows, row_bytes, local_stride=None, remote_stride=None):

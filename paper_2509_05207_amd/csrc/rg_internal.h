@@ -62,7 +62,7 @@ class Arena {
 // ---------------------------------------------------------------- profiling
 enum KernelGroup {
     KG_SAMPLER = 0, KG_FRONTIER = 1, KG_SORT = 2, KG_HIST = 3, KG_TOPK = 4,
-    KG_PLAN = 5, KG_FILL = 6, KG_GATHER = 7, KG_MISS = 8, KG_OFFSETS = 9
+    KG_PLAN = 5, KG_FILL = 6, KG_GATHER = 7, KG_MISS = 8, KG_OFFSETS = 9, KG_BLOCKS = 10
 };
 bool profiling_on();
 // Records an event pair around a launch when profiling is enabled.
@@ -80,6 +80,7 @@ struct HopData {
     int64_t *samp_off = nullptr;     // dev, [|U_l| + 1]  (hops 0..L-1)
     int32_t *samp_nbr = nullptr;     // dev
     int64_t n_samples = 0;
+    int32_t *src_pos = nullptr;      // dev, [n_samples]: block-local source index of every sample (after rg_schedule_build_blocks)
 };
 
 }  // namespace rg
@@ -91,6 +92,7 @@ struct rg_schedule {
     uint64_t T = 0;
     uint64_t uid = 0;                // identity for plan lookup (pointers can be reused)
     std::vector<rg::HopData> hop;    // L + 1 entries
+    bool blocks_built = false;
     explicit rg_schedule(const rg_allocator *a) : arena(a) {}
 };
 

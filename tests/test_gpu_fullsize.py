@@ -66,6 +66,9 @@ def test_medium_whole_epoch(rg, orc):
         so, nb = o.samples(hop)
         gso, gnb = rg.rg_schedule_samples(s, hop)
         assert np.array_equal(host(gso), so) and np.array_equal(host(gnb), nb), f"samples {hop}"
+    rg.rg_schedule_build_blocks(s)
+    for hop in range(o.L):
+        assert np.array_equal(host(rg.rg_schedule_block(s, hop)), o.block(hop)), f"block {hop}"
 
     is_local = host(W.is_local)
     remote = W.remote_rows.cuda()

@@ -81,6 +81,25 @@ def test_schedule_is_reproducible_and_seed_dependent(case, rg):
     assert not torch.equal(a, c)
 
 
+@pytest.mark.parametrize("workspace", [0, 1, "two_batches"])
+def test_blocks_match_oracle(case, rg, workspace):
+    """Computation blocks: block-local source index of every sample, whatever the workspace grouping."""
+    w = case.w
+    s = rg.rg_build_schedule(case.indptr, case.indices, case.train, w.cfg.batch_size, w.cfg.fanout, case.s0, case.worker, case.epoch)
+    with pytest.raises(rg.RgError) as e:
+        rg.rg_schedule_block(s, 0)
+    assert e.value.status == (rg.RG_EINVAL if s.L > 0 else rg.RG_ERANGE)
+    limit = 2 * 4 * w.n_nodes if workspace == "two_batches" else workspace      # 1 byte: one batch at a time
+    rg.rg_schedule_build_blocks(s, workspace_limit_bytes=limit)
+    rg.rg_schedule_build_blocks(s)                                               # a second call changes nothing
+    for hop in range(s.L):
+        got = rg.rg_schedule_block(s, hop).cpu().numpy()
+        assert np.array_equal(got, case.osched.block(hop)), f"block of hop {hop} differs"
+    with pytest.raises(rg.RgError) as e:
+        rg.rg_schedule_block(s, s.L)
+    assert e.value.status == rg.RG_ERANGE
+
+
 @pytest.mark.parametrize("kmode", ["config", "zero", "all", "one"])
 def test_cache_matches_oracle(case, rg, orc, kmode):
     w = case.w
