@@ -190,6 +190,13 @@ rg_status rg_gather_batch(const rg_schedule *s, const rg_cache *c, const rg_feat
                           void *out, uint64_t out_stride, uint64_t out_capacity_rows,
                           void *stream, void *side_stream, rg_gather_stats *stats);
 
+/* The counts of rg_gather_batch without the copy (Alg. 1 inner loop: the miss
+ * set M_i^e and rpc_e += |M_i^e|): what a cache-size sweep needs.  From the
+ * prepared plan when `c` was built from `s` (no device work), otherwise one
+ * classification kernel on `stream` and a wait.  stats: host, required. */
+rg_status rg_classify_batch(const rg_schedule *s, const rg_cache *c, const rg_features *f, uint32_t batch,
+                            void *stream, rg_gather_stats *stats);
+
 /* Both wait for the device to go idle (kernels may still be reading the handle), then release the
  * handle.  With the default allocator the device blocks go to a per-process cache that later builds
  * draw from; rg_trim_memory() hands the cached blocks back to the driver. */

@@ -24,7 +24,8 @@ EXPORTS = ("rg_last_error", "rg_graph_validate", "rg_build_schedule", "rg_schedu
            "rg_cache_pair_create", "rg_cache_pair_begin_next", "rg_cache_pair_swap", "rg_cache_pair_primary",
            "rg_cache_pair_table_bytes", "rg_cache_pair_destroy",
            "rg_prefetcher_create", "rg_prefetcher_fill", "rg_prefetcher_acquire", "rg_prefetcher_release",
-           "rg_prefetcher_depth", "rg_prefetcher_destroy", "rg_schedule_build_blocks", "rg_schedule_block")
+           "rg_prefetcher_depth", "rg_prefetcher_destroy", "rg_schedule_build_blocks", "rg_schedule_block",
+           "rg_classify_batch")
 
 
 class RgError(RuntimeError):
@@ -82,6 +83,7 @@ def lib():
         L.rg_profile_enable.argtypes = [C.c_int]; L.rg_profile_enable.restype = None
         L.rg_profile_reset.argtypes = []; L.rg_profile_reset.restype = None
         L.rg_profile_read.argtypes = [P(C.c_double), P(u64)]
+        L.rg_classify_batch.argtypes = [vp, vp, P(rg_features), u32, vp, P(rg_gather_stats)]
         L.rg_schedule_build_blocks.argtypes = [vp, u64, vp]
         L.rg_schedule_block.argtypes = [vp, u32, P(vp)]
         L.rg_cache_pair_create.argtypes = [vp, P(rg_features), u64, P(rg_allocator), vp, P(vp)]
@@ -100,7 +102,8 @@ def lib():
                      "rg_build_cache", "rg_cache_view", "rg_gather_batch", "rg_profile_read",
                      "rg_cache_pair_create", "rg_cache_pair_begin_next", "rg_cache_pair_swap",
                      "rg_prefetcher_create", "rg_prefetcher_fill", "rg_prefetcher_acquire", "rg_prefetcher_release",
-                     "rg_prefetcher_depth", "rg_schedule_build_blocks", "rg_schedule_block"):
+                     "rg_prefetcher_depth", "rg_schedule_build_blocks", "rg_schedule_block",
+           "rg_classify_batch"):
             getattr(L, name).restype = C.c_int32
         _lib = L
     return _lib
@@ -263,6 +266,13 @@ def rg_gather_batch(s, c, features, batch, out, out_stride=None, out_capacity_ro
                                  int(out_stride), int(out_capacity_rows), _stream_ptr(stream), side,
                                  C.byref(st) if want_stats else None))
     return dict(n_rows=st.n_rows, n_local=st.n_local, n_hit=st.n_hit, n_miss=st.n_miss) if want_stats else None
+
+
+def rg_classify_batch(s, c, features, batch, stream=None):
+    """The batch's counts (rows, local, hits, misses) without gathering."""
+    st = rg_gather_stats()
+    _check(lib().rg_classify_batch(s.h, c.h if c is not None else None, C.byref(features), int(batch), _stream_ptr(stream), C.byref(st)))
+    return dict(n_rows=st.n_rows, n_local=st.n_local, n_hit=st.n_hit, n_miss=st.n_miss)
 
 
 class _BorrowedCache:

@@ -29,46 +29,55 @@ template <> struct VecT<4> { using type = uint32_t; };
 template <> struct VecT<2> { using type = uint16_t; };
 template <> struct VecT<1> { using type = uint8_t; };
 
-template <int W>
+// A piece of W bytes at an address that is only known to be a multiple of A bytes.  Global memory takes
+// vector accesses at any dword-aligned address, so rows whose base and stride are multiples of 4 (any
+// fp32 width, even bf16/fp16 widths) are copied with 16-byte vectors whatever their 16-byte phase.
+template <int W, int A> struct PieceT { typedef typename VecT<W>::type type __attribute__((aligned(A < W ? A : W))); };
+
+template <int W, int A>
 __device__ __forceinline__ void copy_piece(const uint8_t *src, uint8_t *dst)
 {
-    using T = typename VecT<W>::type;
-    *reinterpret_cast<T *>(dst) = *reinterpret_cast<const T *>(src);
+    using P = typename PieceT<W, A>::type;
+    *reinterpret_cast<P *>(dst) = *reinterpret_cast<const P *>(src);
 }
 
-template <int VEC>
+template <int VEC, int A>
 __device__ __forceinline__ void copy_tail(const uint8_t *src, uint8_t *dst, uint32_t tail)
 {
-    // tail < VEC; pieces of decreasing power-of-two width stay aligned because the offset so far is a multiple of VEC
-    if constexpr (VEC > 8) { if (tail & 8u) { copy_piece<8>(src, dst); src += 8; dst += 8; } }
-    if constexpr (VEC > 4) { if (tail & 4u) { copy_piece<4>(src, dst); src += 4; dst += 4; } }
-    if constexpr (VEC > 2) { if (tail & 2u) { copy_piece<2>(src, dst); src += 2; dst += 2; } }
-    if constexpr (VEC > 1) { if (tail & 1u) { copy_piece<1>(src, dst); } }
+    // tail < VEC, at an offset that is a multiple of VEC; pieces of decreasing power-of-two width
+    if constexpr (VEC > 8) { if (tail & 8u) { copy_piece<8, A>(src, dst); src += 8; dst += 8; } }
+    if constexpr (VEC > 4) { if (tail & 4u) { copy_piece<4, A>(src, dst); src += 4; dst += 4; } }
+    if constexpr (VEC > 2) { if (tail & 2u) { copy_piece<2, A>(src, dst); src += 2; dst += 2; } }
+    if constexpr (VEC > 1) { if (tail & 1u) { copy_piece<1, A>(src, dst); } }
 }
 
 constexpr int GATHER_THREADS = 256;
 constexpr int CHUNKS_IN_FLIGHT = 8;
 
-template <int VEC>
+template <int VEC, int A>
 __global__ void __launch_bounds__(GATHER_THREADS) gather_rows_kernel(const int64_t *__restrict__ entries, int64_t n_rows,
                                                                      const int32_t *__restrict__ list, int64_t n_list, int mode,
                                                                      RowSources src, uint32_t row_bytes,
-                                                                     uint8_t *__restrict__ out, uint64_t out_stride)
+                                                                     uint8_t *__restrict__ out, uint64_t out_stride, int chunks)
 {
     using T = typename VecT<VEC>::type;
+    using P = typename PieceT<VEC, A>::type;
     const uint32_t cpr = row_bytes / VEC, tail = row_bytes % VEC;
     const uint32_t cpt = cpr + (tail ? 1u : 0u);                  // pieces per row: full vectors, then the tail piece
     const uint64_t n_work = (uint64_t)(list ? n_list : n_rows);
     const uint64_t total = n_work * cpt;
-    const uint64_t n_threads = (uint64_t)gridDim.x * GATHER_THREADS;
-    // flat index -> (work item, piece); advanced by n_threads without dividing again
-    const uint64_t dq = n_threads / cpt;
-    const uint32_t dr = (uint32_t)(n_threads - dq * cpt);
-    uint64_t idx = (uint64_t)blockIdx.x * GATHER_THREADS + threadIdx.x;
-    uint64_t w = idx / cpt;
-    uint32_t c = (uint32_t)(idx - w * cpt);
+    // A workgroup takes GATHER_THREADS * chunks consecutive pieces per round (chunks <= CHUNKS_IN_FLIGHT, fewer for
+    // a block of rows too small to fill the chip otherwise): one contiguous span of the output, 32 KB with 16-byte
+    // pieces.  Within a round the flat index -> (work item, piece) pair is advanced by GATHER_THREADS without
+    // dividing again.
+    const uint32_t ROUND = GATHER_THREADS * (uint32_t)chunks;
+    const uint32_t dq = GATHER_THREADS / cpt;
+    const uint32_t dr = GATHER_THREADS - dq * cpt;
 
-    while (idx < total) {
+    for (uint64_t base = (uint64_t)blockIdx.x * ROUND + threadIdx.x; base < total; base += (uint64_t)gridDim.x * ROUND) {
+        uint64_t idx = base;
+        uint64_t w = idx / cpt;
+        uint32_t c = (uint32_t)(idx - w * cpt);
         T v[CHUNKS_IN_FLIGHT];
         const uint8_t *sp[CHUNKS_IN_FLIGHT];
         uint8_t *dp[CHUNKS_IN_FLIGHT];
@@ -77,7 +86,7 @@ __global__ void __launch_bounds__(GATHER_THREADS) gather_rows_kernel(const int64
         for (int k = 0; k < CHUNKS_IN_FLIGHT; ++k) {
             kind[k] = 0;
             sp[k] = nullptr; dp[k] = nullptr;
-            if (idx < total) {
+            if (k < chunks && idx < total) {
                 const int64_t r = list ? (int64_t)list[w] : (int64_t)w;
                 const int64_t e = entries[r];
                 const int64_t tag = entry_tag(e), row = entry_row(e);
@@ -88,18 +97,18 @@ __global__ void __launch_bounds__(GATHER_THREADS) gather_rows_kernel(const int64
                     sp[k] = base + (uint64_t)c * VEC;
                     dp[k] = out + (uint64_t)r * out_stride + (uint64_t)c * VEC;
                     kind[k] = c < cpr ? 1 : 2;
-                    if (kind[k] == 1) v[k] = *reinterpret_cast<const T *>(sp[k]);
+                    if (kind[k] == 1) v[k] = *reinterpret_cast<const P *>(sp[k]);
                 }
             }
-            idx += n_threads;
+            idx += GATHER_THREADS;
             w += dq;
             c += dr;
             if (c >= cpt) { c -= cpt; ++w; }
         }
 #pragma unroll
         for (int k = 0; k < CHUNKS_IN_FLIGHT; ++k) {
-            if (kind[k] == 1) __builtin_nontemporal_store(v[k], reinterpret_cast<T *>(dp[k]));
-            else if (kind[k] == 2) copy_tail<VEC>(sp[k], dp[k], tail);
+            if (kind[k] == 1) __builtin_nontemporal_store(v[k], reinterpret_cast<P *>(dp[k]));
+            else if (kind[k] == 2) copy_tail<VEC, A>(sp[k], dp[k], tail);
         }
     }
 }
@@ -119,25 +128,30 @@ rg_status launch_gather(const int64_t *entries, int64_t n_rows, const int32_t *l
 {
     const int64_t n_work = list ? n_list : n_rows;
     if (n_work <= 0) return RG_OK;
-    const int vec = common_alignment(src, out, out_stride);
+    const int align = common_alignment(src, out, out_stride);
+    const int vec = align >= 4 ? 16 : 1;                        // dword-aligned rows take 16-byte vectors, anything else goes byte by byte
     const uint64_t cpt = row_bytes / (uint32_t)vec + (row_bytes % (uint32_t)vec ? 1 : 0);
     int dev = 0, n_cu = 256;
     RG_HIP(hipGetDevice(&dev));
     RG_HIP(hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, dev));
-    const uint64_t per_block = (uint64_t)GATHER_THREADS * CHUNKS_IN_FLIGHT;
-    uint64_t blocks = ((uint64_t)n_work * cpt + per_block - 1) / per_block;
-    blocks = std::max<uint64_t>(1, std::min<uint64_t>(blocks, (uint64_t)n_cu * 32));
-    if (blocks < (uint64_t)n_cu * 8) {        // a small block of rows: spread it over the chip rather than fill each thread's pipeline
-        const uint64_t by_thread = ((uint64_t)n_work * cpt + GATHER_THREADS - 1) / GATHER_THREADS;
-        blocks = std::max<uint64_t>(blocks, std::min<uint64_t>(by_thread, (uint64_t)n_cu * 8));
-    }
+    // pieces per thread and round: as many as stay in flight, fewer when that would leave compute units without a workgroup
+    const uint64_t total = (uint64_t)n_work * cpt;
+    const uint64_t want_blocks = (uint64_t)n_cu * 8;
+    int chunks = CHUNKS_IN_FLIGHT;
+    while (chunks > 1 && (total + (uint64_t)GATHER_THREADS * chunks - 1) / ((uint64_t)GATHER_THREADS * chunks) < want_blocks) --chunks;
+    const uint64_t per_block = (uint64_t)GATHER_THREADS * chunks;
+    const uint64_t blocks = std::max<uint64_t>(1, std::min<uint64_t>((total + per_block - 1) / per_block, (uint64_t)n_cu * 32));
     ScopedTimer tm(group, st);
-    switch (vec) {
-    case 16: hipLaunchKernelGGL(gather_rows_kernel<16>, dim3((unsigned)blocks), dim3(GATHER_THREADS), 0, st, entries, n_rows, list, n_list, mode, src, row_bytes, out, out_stride); break;
-    case 8:  hipLaunchKernelGGL(gather_rows_kernel<8>, dim3((unsigned)blocks), dim3(GATHER_THREADS), 0, st, entries, n_rows, list, n_list, mode, src, row_bytes, out, out_stride); break;
-    case 4:  hipLaunchKernelGGL(gather_rows_kernel<4>, dim3((unsigned)blocks), dim3(GATHER_THREADS), 0, st, entries, n_rows, list, n_list, mode, src, row_bytes, out, out_stride); break;
-    default: hipLaunchKernelGGL(gather_rows_kernel<1>, dim3((unsigned)blocks), dim3(GATHER_THREADS), 0, st, entries, n_rows, list, n_list, mode, src, row_bytes, out, out_stride); break;
+#define RG_GATHER_LAUNCH(V, AL)                                                                                                         \
+    hipLaunchKernelGGL((gather_rows_kernel<V, AL>), dim3((unsigned)blocks), dim3(GATHER_THREADS), 0, st, entries, n_rows, list, n_list, mode, \
+                       src, row_bytes, out, out_stride, chunks)
+    switch (align) {
+    case 16: RG_GATHER_LAUNCH(16, 16); break;
+    case 8:  RG_GATHER_LAUNCH(16, 8); break;
+    case 4:  RG_GATHER_LAUNCH(16, 4); break;
+    default: RG_GATHER_LAUNCH(1, 1); break;
     }
+#undef RG_GATHER_LAUNCH
     RG_HIP(hipGetLastError());
     return RG_OK;
 }
@@ -252,5 +266,38 @@ extern "C" rg_status rg_gather_batch(const rg_schedule *s, const rg_cache *c, co
     RG_HIP(hipMemcpyAsync(hc, counts, sizeof(hc), hipMemcpyDeviceToHost, st));
     RG_HIP(hipStreamSynchronize(st));
     if (stats) { stats->n_rows = (uint64_t)m; stats->n_local = hc[0]; stats->n_hit = hc[1]; stats->n_miss = hc[2]; }
+    return RG_OK;
+}
+
+// The batch's counts alone: a9 without the copy (Alg. 1 inner loop, rpc_e += |M_i^e|).
+extern "C" rg_status rg_classify_batch(const rg_schedule *s, const rg_cache *c, const rg_features *f, uint32_t batch, void *stream,
+                                       rg_gather_stats *stats)
+{
+    if (!s || !f || !stats) { set_error("rg_classify_batch: null argument"); return RG_EINVAL; }
+    if (batch >= s->n_batches) { set_error("rg_classify_batch: batch %u >= n_batches = %u", batch, s->n_batches); return RG_ERANGE; }
+    if (c && c->n_nodes != s->n_nodes) { set_error("rg_classify_batch: cache does not match the schedule"); return RG_EINVAL; }
+    if (c)
+        for (const Plan &p : c->plans)
+            if (p.schedule_uid == s->uid) { *stats = p.stats[batch]; return RG_OK; }
+    const HopData &h = s->hop[s->L];
+    const int64_t off = h.off_host[batch], m = h.off_host[batch + 1] - off;
+    hipStream_t st = as_stream(stream);
+    Arena tmp(nullptr);
+    int64_t *entry = nullptr;
+    unsigned long long *counts = nullptr;
+    RG_TRY(tmp.dev_n<int64_t>((uint64_t)m, &entry));
+    RG_TRY(tmp.dev_n<unsigned long long>(3, &counts));
+    RG_HIP(hipMemsetAsync(counts, 0, 3 * sizeof(unsigned long long), st));
+    if (m > 0) {
+        ScopedTimer tm(KG_PLAN, st);
+        hipLaunchKernelGGL(route_batch_kernel, dim3((unsigned)((m + 255) / 256)), dim3(256), 0, st, h.ids + off, m, f->is_local, f->row_of,
+                           c ? c->slot_of : nullptr, entry, counts);
+    }
+    unsigned long long hc[3] = {0, 0, 0};
+    hipError_t e1 = hipGetLastError();
+    hipError_t e2 = hipMemcpyAsync(hc, counts, sizeof(hc), hipMemcpyDeviceToHost, st);
+    hipError_t e3 = hipStreamSynchronize(st);                    // also before `tmp` is released
+    if (e1 != hipSuccess || e2 != hipSuccess || e3 != hipSuccess) { set_error("rg_classify_batch: HIP call failed"); return RG_EHIP; }
+    stats->n_rows = (uint64_t)m; stats->n_local = hc[0]; stats->n_hit = hc[1]; stats->n_miss = hc[2];
     return RG_OK;
 }

@@ -300,14 +300,16 @@ def test_torch_backed_allocator(rg, orc):
 
 
 def test_rows_of_odd_width_and_alignment(rg, orc):
-    """Row widths that force the 8-, 4- and 1-byte paths and the tail pieces."""
+    """Row widths and strides at 16-, 8-, 4-, 2- and 1-byte alignment: 16-byte vectors at every dword phase, every
+    tail length, and the byte path."""
     w, indptr, indices, train = small_graph()
     ip, ix, tr = w.indptr.numpy(), w.indices.numpy(), w.train.numpy()
     o = orc.Schedule(ip, ix, tr, 100, [5, 3], 3, 0, 0)
     g = rg.rg_build_schedule(indptr, indices, train, 100, [5, 3], 3, 0, 0)
     n_local, n_remote = w.extra["n_local"], w.extra["n_remote"]
     rng = np.random.default_rng(5)
-    for row_bytes, stride in ((2408, 2416), (2408, 2408), (100, 100), (7, 7), (33, 36), (1, 1), (24, 32), (30, 30)):
+    for row_bytes, stride in ((2408, 2416), (2408, 2408), (2404, 2404), (1204, 1204), (100, 100), (7, 7), (33, 36), (1, 1), (24, 32),
+                              (30, 30), (12, 12), (20, 20), (44, 52), (63, 64)):
         loc = rng.integers(0, 256, (n_local, stride), dtype=np.uint8)
         rem = rng.integers(0, 256, (n_remote, stride), dtype=np.uint8)
         of = orc.Features(w.is_local.numpy(), w.row_of.numpy(), loc, stride, rem, stride, row_bytes)

@@ -191,3 +191,54 @@ def test_begin_next_twice_without_swap_replaces_the_pending_cache(case, rg, orc)
     ids, _ = oracle_cache(orc, case, o2)
     v = rg.rg_cache_view(rg.rg_cache_pair_primary(pair), w.n_nodes)
     assert np.array_equal(v["cache_ids"].cpu().numpy(), ids)
+
+
+def test_classification_alone_matches_the_oracle_and_the_sweep_law(case, rg, orc):
+    """rg_classify_batch: the counts of a gather without the copy, from the plan or on the fly; summed over an epoch
+    they equal the oracle's for every cache size, and fall as the cache grows."""
+    from paper_2509_05207_amd import sweep
+    w = case.w
+    is_local = w.is_local.numpy()
+    freq = orc.frequency([case.osched], w.n_nodes)
+    n_remote = int(((is_local == 0) & (freq > 0)).sum())
+    o1 = orc.Schedule(w.indptr.numpy(), w.indices.numpy(), w.train.numpy(), w.cfg.batch_size, w.cfg.fanout, case.s0, case.worker, 1,
+                      n_threads=8)
+    g1 = rg.rg_build_schedule(case.indptr, case.indices, case.train, w.cfg.batch_size, w.cfg.fanout, case.s0, case.worker, 1)
+    last = None
+    for K in (0, 3, n_remote // 5, n_remote):
+        _, slot = orc.top_hot(freq, is_local, K)
+        c = rg.rg_build_cache([case.gsched], case.gfeat, K)
+        total = 0
+        for b in range(case.gsched.n_batches):
+            st = rg.rg_classify_batch(case.gsched, c, case.gfeat, b)            # from the prepared plan
+            assert st == orc.batch_stats(case.osched, b, is_local, slot)
+            total += st["n_miss"]
+        for b in range(g1.n_batches):
+            assert rg.rg_classify_batch(g1, c, case.gfeat, b) == orc.batch_stats(o1, b, is_local, slot)   # on the fly
+        assert last is None or total <= last
+        last = total
+    assert last == 0
+    for b in range(0, case.gsched.n_batches, 3):
+        assert rg.rg_classify_batch(case.gsched, None, case.gfeat, b) == orc.batch_stats(case.osched, b, is_local, None)
+
+    # the sweep script's own figures for this workload, against the oracle
+    class W:
+        pass
+    W.cfg, W.indptr, W.indices, W.train = w.cfg, case.indptr, case.indices, case.train
+    W.is_local, W.row_of, W.local_rows, W.remote_rows = case.is_local, case.row_of, case.local_rows, case.remote_rows
+    W.row_bytes, W.n_nodes = w.row_bytes, w.n_nodes
+    res = sweep.sweep(rg, W, 2, [0.0, 0.25, 1.0], log=lambda *a: None)
+    os_ = [orc.Schedule(w.indptr.numpy(), w.indices.numpy(), w.train.numpy(), w.cfg.batch_size, w.cfg.fanout, w.cfg.s0, w.cfg.worker,
+                        w.cfg.epoch + e, n_threads=8) for e in range(2)]
+    fr = [orc.frequency([o], w.n_nodes) for o in os_]
+    nr = int(((is_local == 0) & (fr[0] > 0)).sum())
+    assert res["n_remote_first_epoch"] == nr
+    for row, frac in zip(res["rows"], (0.0, 0.25, 1.0)):
+        K = int(round(frac * nr))
+        assert row["K"] == K
+        fresh = stale = 0
+        slots = [orc.top_hot(f, is_local, K)[1] for f in fr]
+        for e, o in enumerate(os_):
+            fresh += sum(orc.batch_stats(o, b, is_local, slots[e])["n_miss"] for b in range(o.n_batches))
+        stale = sum(orc.batch_stats(os_[1], b, is_local, slots[0])["n_miss"] for b in range(os_[1].n_batches))
+        assert row["fetches_per_epoch"] == fresh / 2 and row["fetches_per_epoch_stale_cache"] == stale

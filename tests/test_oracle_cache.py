@@ -146,3 +146,35 @@ def test_stats_are_the_set_arithmetic(orc, wl, name):
                 assert st["n_miss"] == len(N_i - local_set)                # on-demand baseline: all remote
         if K == 10 ** 9:
             assert tot_miss == 0                                           # everything touched is cached
+
+
+def test_fetches_fall_with_cache_size_and_equal_the_uncached_frequency_mass(orc):
+    """Remote fetches of an epoch = sum of freq over the remote nodes left out of the cache (a node is fetched once
+    per batch that needs it); so they fall monotonically in n_hot, from the whole remote mass to zero, and TopHot's
+    choice is the best one for its size (Eq. 2)."""
+    w = synth.make_workload("small")
+    s = orc.Schedule(w.indptr.numpy(), w.indices.numpy(), w.train.numpy(), w.cfg.batch_size, w.cfg.fanout, 9, 0, 0)
+    is_local = w.is_local.numpy()
+    freq = orc.frequency([s], w.n_nodes)
+    remote = (is_local == 0) & (freq > 0)
+    n_remote = int(remote.sum())
+    rng = np.random.default_rng(3)
+    last = None
+    for K in (0, 1, 7, n_remote // 10, n_remote // 3, n_remote - 1, n_remote, n_remote + 50):
+        ids, slot = orc.top_hot(freq, is_local, K)
+        misses = sum(orc.batch_stats(s, b, is_local, slot)["n_miss"] for b in range(s.n_batches))
+        uncached = remote.copy()
+        uncached[ids] = False
+        assert misses == int(freq[uncached].sum())
+        if last is not None:
+            assert misses <= last
+        last = misses
+        if K == 0:
+            assert misses == int(freq[remote].sum())
+        if K >= n_remote:
+            assert misses == 0
+        if 0 < K < n_remote:
+            other = rng.choice(np.nonzero(remote)[0], size=K, replace=False)
+            alt = remote.copy()
+            alt[other] = False
+            assert int(freq[alt].sum()) >= misses
