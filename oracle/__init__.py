@@ -47,6 +47,11 @@ def lib():
         L.orc_sample_row.restype = u32; L.orc_sample_row.argtypes = [vp, i64, u32, u64, vp, vp]
         L.orc_build_schedule.restype = vp
         L.orc_build_schedule.argtypes = [i64, vp, vp, vp, u64, u32, vp, u32, u64, u32, u32, u32, u32, C.c_int]
+        L.orc_build_schedule_with.restype = vp
+        L.orc_build_schedule_with.argtypes = [i64, vp, vp, vp, u64, u32, vp, u32, u64, u32, u32, u32, u32, C.c_int, C.c_int]
+        L.orc_feistel.restype = u64; L.orc_feistel.argtypes = [u64, u32, u64]
+        L.orc_draw_positions.restype = None; L.orc_draw_positions.argtypes = [i64, u32, u64, vp]
+        L.orc_sample_row_positions.restype = u32; L.orc_sample_row_positions.argtypes = [vp, i64, u32, u64, vp, vp]
         L.orc_schedule_destroy.restype = None; L.orc_schedule_destroy.argtypes = [vp]
         L.orc_schedule_n_batches.restype = u32; L.orc_schedule_n_batches.argtypes = [vp]
         L.orc_schedule_hops.restype = u32; L.orc_schedule_hops.argtypes = [vp]
@@ -104,20 +109,39 @@ def sample_row(row, f, s):
     return out[:m].copy()
 
 
+def feistel(x, n_bits, s): return lib().orc_feistel(int(x), int(n_bits), int(s) & (2**64 - 1))
+
+
+def draw_positions(deg, f, s):
+    """f distinct positions in [0, deg), deg > f, in draw order (the O(f) alternative sampler)."""
+    assert deg > f >= 1
+    pos = np.empty(f, np.int64)
+    lib().orc_draw_positions(int(deg), int(f), int(s) & (2**64 - 1), _p(pos))
+    return pos
+
+
+def sample_row_positions(row, f, s):
+    row = _arr(row, np.int32)
+    out = np.empty(max(min(row.size, f), 1), np.int32)
+    pos = np.empty(max(f, 1), np.int64)
+    m = lib().orc_sample_row_positions(_p(row), row.size, int(f), int(s) & (2**64 - 1), _p(pos), _p(out))
+    return out[:m].copy()
+
+
 class Schedule:
     """One epoch's schedule: seeds, frontiers U_0..U_L and per-hop samples."""
 
     def __init__(self, indptr, indices, train, batch_size, fanout, s0=0, worker=0, epoch=0,
-                 batch_lo=0, batch_hi=0, n_threads=1):
+                 batch_lo=0, batch_hi=0, n_threads=1, sampler="keys"):
         self.indptr = _arr(indptr, np.int64)
         self.indices = _arr(indices, np.int32)
         train = _arr(train, np.int32)
         fan = _arr(fanout, np.uint32)
         self.n_nodes = self.indptr.size - 1
-        self.h = lib().orc_build_schedule(self.n_nodes, _p(self.indptr), _p(self.indices), _p(train),
-                                          train.size, int(batch_size), _p(fan), fan.size, int(s0),
-                                          int(worker), int(epoch), int(batch_lo), int(batch_hi),
-                                          int(n_threads))
+        self.h = lib().orc_build_schedule_with(self.n_nodes, _p(self.indptr), _p(self.indices), _p(train),
+                                               train.size, int(batch_size), _p(fan), fan.size, int(s0),
+                                               int(worker), int(epoch), int(batch_lo), int(batch_hi),
+                                               int(n_threads), {"keys": 0, "positions": 1}[sampler])
         if not self.h:
             raise RuntimeError("orc_build_schedule failed")
         self.n_batches = lib().orc_schedule_n_batches(self.h)

@@ -35,6 +35,10 @@
  *     subset / size / no-duplicate invariants, Prop. 1(a) inclusion
  *     frequencies and pairwise inclusion, Prop. 1(b) decorrelation across
  *     (e, i, w, hop), row-permutation invariance.
+ *   - position sampler (the O(f) alternative): the permutation property by
+ *     enumeration, distinctness and range, the selection branch against a
+ *     python re-statement with an explicit list of free positions, inclusion
+ *     and pairwise-inclusion frequencies on both branches.
  *   - batching: the paper's worked example ceil(153431/1000) = 154.
  *   - frontier, freq, TopHot, gather, stats: python set / Counter / full
  *     lexsort / fancy indexing on the same inputs.
@@ -206,6 +210,85 @@ uint32_t orc_sample_row(const int32_t *row, int64_t deg, uint32_t f, uint64_t s,
 }
 
 /* ------------------------------------------------------------------ */
+/* Alternative SAMPLE for deg >> f: draw positions, read only those.   */
+/* (The paper fixes the law -- uniform, without replacement -- not the */
+/* procedure; this second reading costs O(f) per node instead of       */
+/* O(deg).)  With deg > f, the sample is row[p_0], ..., row[p_{f-1}]   */
+/* in draw order, where p_0.. are f distinct positions in [0, deg):    */
+/*                                                                     */
+/*  deg <= 64: sequential selection.  Draw t takes r_t uniform in      */
+/*    [0, deg - t) (top 32 bits of mix64(s + (t+1)G), scaled by        */
+/*    multiply-high) and picks the r_t-th position not picked before.  */
+/*    Exactly uniform given uniform r_t.                               */
+/*  deg > 64: p_t = pi_s(t), pi_s a keyed permutation of [0, deg):     */
+/*    an alternating Feistel network on n = bitlen(deg-1) bits (left   */
+/*    part n - n/2 bits, right part n/2 bits, six rounds, round value  */
+/*    = top 32 bits of mix64((s ^ other half) + (r+1)G)), walked       */
+/*    along its cycle until the value falls below deg.  A permutation  */
+/*    restricted this way is a permutation of [0, deg); its first f    */
+/*    images are distinct, and uniform as far as pi_s is random.       */
+/* With deg <= f the whole row is the sample, in row order.            */
+/* ------------------------------------------------------------------ */
+static uint32_t draw32(uint64_t s, uint64_t t)
+{
+    return (uint32_t)(orc_mix64(s + (t + 1) * ORC_G64) >> 32);
+}
+
+uint64_t orc_feistel(uint64_t x, uint32_t n_bits, uint64_t s)
+{
+    const uint32_t hb = n_bits / 2, ha = n_bits - hb;
+    const uint64_t mask_a = (1ull << ha) - 1, mask_b = (1ull << hb) - 1;
+    uint64_t a = x >> hb, b = x & mask_b;
+    for (uint32_t r = 0; r < 6; ++r) {
+        if (r % 2 == 0) a ^= (orc_mix64((s ^ b) + (uint64_t)(r + 1) * ORC_G64) >> 32) & mask_a;
+        else            b ^= (orc_mix64((s ^ a) + (uint64_t)(r + 1) * ORC_G64) >> 32) & mask_b;
+    }
+    return (a << hb) | b;
+}
+
+/* pos: f entries.  Requires deg > f >= 1. */
+void orc_draw_positions(int64_t deg, uint32_t f, uint64_t s, int64_t *pos)
+{
+    if (deg <= 64) {
+        uint8_t taken[64];
+        memset(taken, 0, sizeof taken);
+        for (uint32_t t = 0; t < f; ++t) {
+            uint64_t r = ((uint64_t)draw32(s, t) * (uint64_t)(deg - t)) >> 32;
+            int64_t p = 0;
+            for (;; ++p) {
+                if (taken[p]) continue;
+                if (r == 0) break;
+                --r;
+            }
+            taken[p] = 1;
+            pos[t] = p;
+        }
+        return;
+    }
+    uint32_t n_bits = 0;
+    while (((uint64_t)1 << n_bits) < (uint64_t)deg) ++n_bits;
+    for (uint32_t t = 0; t < f; ++t) {
+        uint64_t x = orc_feistel(t, n_bits, s);
+        while (x >= (uint64_t)deg) x = orc_feistel(x, n_bits, s);
+        pos[t] = (int64_t)x;
+    }
+}
+
+/* pos_scratch: f entries.  Returns the number written to out. */
+uint32_t orc_sample_row_positions(const int32_t *row, int64_t deg, uint32_t f, uint64_t s,
+                                  int64_t *pos_scratch, int32_t *out)
+{
+    if (f == 0 || deg <= 0) return 0;
+    if (deg <= (int64_t)f) {
+        for (int64_t j = 0; j < deg; ++j) out[j] = row[j];
+        return (uint32_t)deg;
+    }
+    orc_draw_positions(deg, f, s, pos_scratch);
+    for (uint32_t t = 0; t < f; ++t) out[t] = row[pos_scratch[t]];
+    return f;
+}
+
+/* ------------------------------------------------------------------ */
 /* Schedule of one epoch.                                              */
 /*   U_0 = the batch's seeds in shuffle order.                         */
 /*   hop l: every v in U_l is sampled with fanout[l] (fan-outs count   */
@@ -269,14 +352,15 @@ typedef struct {
 static void build_one_batch(int64_t n_nodes, const int64_t *indptr, const int32_t *indices,
                             const int32_t *seeds, int64_t n_seeds, const uint32_t *fanout,
                             uint32_t L, uint64_t batch_seed, uint8_t *present,
-                            batch_out *o)
+                            int sampler, batch_out *o)
 {
     (void)n_nodes;
     uint32_t fmax = 1;
     for (uint32_t l = 0; l < L; ++l) if (fanout[l] > fmax) fmax = fanout[l];
     uint64_t *heap = (uint64_t *)malloc((size_t)fmax * sizeof(uint64_t));
     int32_t *tmp = (int32_t *)malloc((size_t)fmax * sizeof(int32_t));
-    if (!heap || !tmp) { o->err = -1; free(heap); free(tmp); return; }
+    int64_t *pos = (int64_t *)malloc((size_t)fmax * sizeof(int64_t));
+    if (!heap || !tmp || !pos) { o->err = -1; free(heap); free(tmp); free(pos); return; }
 
     for (int64_t j = 0; j < n_seeds; ++j) {
         if (v32_push(&o->fr[0], seeds[j])) o->err = -1;
@@ -289,7 +373,9 @@ static void build_one_batch(int64_t n_nodes, const int64_t *indptr, const int32_
         for (int64_t j = 0; j < U->n; ++j) {
             int32_t v = U->p[j];
             int64_t b = indptr[v], deg = indptr[v + 1] - b;
-            uint32_t m = orc_sample_row(indices + b, deg, fanout[l], orc_node_state(hs, v), heap, tmp);
+            uint64_t sv = orc_node_state(hs, v);
+            uint32_t m = sampler == 1 ? orc_sample_row_positions(indices + b, deg, fanout[l], sv, pos, tmp)
+                                      : orc_sample_row(indices + b, deg, fanout[l], sv, heap, tmp);
             if (v64_push(&o->soff[l], (int64_t)m)) o->err = -1;
             for (uint32_t k = 0; k < m; ++k) {
                 if (v32_push(&o->snbr[l], tmp[k])) o->err = -1;
@@ -309,6 +395,7 @@ static void build_one_batch(int64_t n_nodes, const int64_t *indptr, const int32_
         for (int64_t j = 0; j < o->fr[l].n; ++j) present[o->fr[l].p[j]] = 0;
     free(heap);
     free(tmp);
+    free(pos);
 }
 
 void orc_schedule_destroy(orc_schedule *s)
@@ -327,11 +414,13 @@ void orc_schedule_destroy(orc_schedule *s)
  * all); used to check sampled batches of big workloads and that a batch built
  * alone equals the same batch built inside the epoch.  n_threads: batches are
  * independent, so they may be built by several threads; results do not depend
- * on it. */
-orc_schedule *orc_build_schedule(int64_t n_nodes, const int64_t *indptr, const int32_t *indices,
-                                 const int32_t *train, uint64_t T, uint32_t batch_size,
-                                 const uint32_t *fanout, uint32_t L, uint64_t s0, uint32_t worker,
-                                 uint32_t epoch, uint32_t batch_lo, uint32_t batch_hi, int n_threads)
+ * on it.  sampler: 0 = the f smallest keys of the row (the main reading),
+ * 1 = drawn positions (the O(f) alternative above). */
+orc_schedule *orc_build_schedule_with(int64_t n_nodes, const int64_t *indptr, const int32_t *indices,
+                                      const int32_t *train, uint64_t T, uint32_t batch_size,
+                                      const uint32_t *fanout, uint32_t L, uint64_t s0, uint32_t worker,
+                                      uint32_t epoch, uint32_t batch_lo, uint32_t batch_hi, int n_threads,
+                                      int sampler)
 {
     if (batch_size == 0 && T > 0) return NULL;
     orc_schedule *s = (orc_schedule *)calloc(1, sizeof(orc_schedule));
@@ -365,7 +454,7 @@ orc_schedule *orc_build_schedule(int64_t n_nodes, const int64_t *indptr, const i
             uint64_t lo = gi * batch_size, hi = lo + batch_size;
             if (hi > T) hi = T;
             build_one_batch(n_nodes, indptr, indices, all_seeds + lo, (int64_t)(hi - lo), fanout, L,
-                            orc_batch_seed(s0, worker, epoch, (uint32_t)gi), present, &bo[b]);
+                            orc_batch_seed(s0, worker, epoch, (uint32_t)gi), present, sampler, &bo[b]);
         }
         free(present);
     }
@@ -416,6 +505,15 @@ orc_schedule *orc_build_schedule(int64_t n_nodes, const int64_t *indptr, const i
     free(all_seeds);
     if (err) { orc_schedule_destroy(s); return NULL; }
     return s;
+}
+
+orc_schedule *orc_build_schedule(int64_t n_nodes, const int64_t *indptr, const int32_t *indices,
+                                 const int32_t *train, uint64_t T, uint32_t batch_size,
+                                 const uint32_t *fanout, uint32_t L, uint64_t s0, uint32_t worker,
+                                 uint32_t epoch, uint32_t batch_lo, uint32_t batch_hi, int n_threads)
+{
+    return orc_build_schedule_with(n_nodes, indptr, indices, train, T, batch_size, fanout, L, s0, worker, epoch,
+                                   batch_lo, batch_hi, n_threads, 0);
 }
 
 uint32_t orc_schedule_n_batches(const orc_schedule *s) { return s->n_batches; }
