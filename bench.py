@@ -111,7 +111,25 @@ def runtime_leg(rg, W, feat, epochs=3, Q=4):
     t_blk = time.perf_counter() - t0
     blk = rg.rg_profile_read()["blocks"]
     n_samp = sum(rg.rg_schedule_block(scheds[0], h).numel() for h in range(scheds[0].L))
+    # the O(f) alternative sampler on the same epoch (a different, equally distributed sample: never the headline figure)
+    del scheds
+    rg.rg_build_schedule_with(W.indptr, W.indices, W.train, cfg.batch_size, cfg.fanout, cfg.s0, cfg.worker, cfg.epoch,
+                              sampler=rg.RG_SAMPLER_POSITIONS)
+    torch.cuda.synchronize()
+    rg.rg_profile_reset()
+    reps = 3
+    t0 = time.perf_counter()
+    for _ in range(reps):
+        sp = rg.rg_build_schedule_with(W.indptr, W.indices, W.train, cfg.batch_size, cfg.fanout, cfg.s0, cfg.worker, cfg.epoch,
+                                       sampler=rg.RG_SAMPLER_POSITIONS)
+    torch.cuda.synchronize()
+    t_pos = (time.perf_counter() - t0) / reps
+    pos_kernel_ms = rg.rg_profile_read()["sampler"]["ms"] / reps
+    pos_edges = sum(rg.rg_schedule_samples(sp, h)[1].numel() for h in range(sp.L))
+    del sp
     return {"epochs": epochs, "Q": Q, "schedule_build_ms_per_epoch": t_sched / epochs * 1e3,
+            "position_sampler": {"schedule_build_ms": t_pos * 1e3, "sampler_kernel_ms": pos_kernel_ms, "sampled_edges": pos_edges,
+                                 "edges_per_s_kernel": pos_edges / (pos_kernel_ms * 1e-3) if pos_kernel_ms else None},
             "gather_epoch_ms_with_next_cache_built_alongside": t_run / epochs * 1e3, "staged_fraction": staged / max(1, total),
             "cache_table_bytes": table_bytes, "staging_bytes": Q * m_cap * W.stride_bytes,
             "blocks_ms_per_epoch": t_blk * 1e3, "blocks_kernel_ms": blk["ms"], "block_edges": n_samp}

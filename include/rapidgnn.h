@@ -102,6 +102,25 @@ rg_status rg_build_schedule(const rg_graph *g, const int32_t *train_nodes, uint6
                             uint64_t s0, uint32_t worker, uint32_t epoch,
                             const rg_allocator *a, void *stream, rg_schedule **out);
 
+/* The same with a choice of SAMPLE's procedure.  The paper fixes the law of
+ * SAMPLE (uniform, without replacement; Prop. 1(a)), not how it is drawn:
+ *   RG_SAMPLER_KEYS       the f neighbours with the smallest hash keys, emitted
+ *                         in row order; reads every row in full (O(deg)).
+ *                         This is what rg_build_schedule uses.
+ *   RG_SAMPLER_POSITIONS  f distinct positions of the row are drawn from the
+ *                         node's state (selection without replacement for rows
+ *                         up to 64, a keyed permutation of [0, deg) beyond) and
+ *                         only those are read (O(f)); emitted in draw order.
+ * Seeds, shuffle, frontier rule, counts and every other contract are the same;
+ * the two procedures give different (equally distributed) samples.
+ * RG_EINVAL for any other value. */
+#define RG_SAMPLER_KEYS       0u
+#define RG_SAMPLER_POSITIONS  1u
+rg_status rg_build_schedule_with(const rg_graph *g, const int32_t *train_nodes, uint64_t T,
+                                 uint32_t batch_size, const uint32_t *fanout, uint32_t L,
+                                 uint64_t s0, uint32_t worker, uint32_t epoch, uint32_t sampler,
+                                 const rg_allocator *a, void *stream, rg_schedule **out);
+
 /* Read-only views ("metadata blocks": ordered batches, arrays N_i^e, offsets;
  * Sec. 4 par. (3)).  Device pointers stay valid until rg_schedule_destroy. */
 rg_status rg_schedule_info(const rg_schedule *s, uint32_t *n_batches, uint32_t *L, int64_t *n_nodes);

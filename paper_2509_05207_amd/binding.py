@@ -25,7 +25,7 @@ EXPORTS = ("rg_last_error", "rg_graph_validate", "rg_build_schedule", "rg_schedu
            "rg_cache_pair_table_bytes", "rg_cache_pair_destroy",
            "rg_prefetcher_create", "rg_prefetcher_fill", "rg_prefetcher_acquire", "rg_prefetcher_release",
            "rg_prefetcher_depth", "rg_prefetcher_destroy", "rg_schedule_build_blocks", "rg_schedule_block",
-           "rg_classify_batch")
+           "rg_classify_batch", "rg_build_schedule_with")
 
 
 class RgError(RuntimeError):
@@ -71,6 +71,7 @@ def lib():
         L.rg_last_error.restype = C.c_char_p
         L.rg_graph_validate.argtypes = [P(rg_graph), vp, P(u64)]
         L.rg_build_schedule.argtypes = [P(rg_graph), vp, u64, u32, P(u32), u32, u64, u32, u32, P(rg_allocator), vp, P(vp)]
+        L.rg_build_schedule_with.argtypes = [P(rg_graph), vp, u64, u32, P(u32), u32, u64, u32, u32, u32, P(rg_allocator), vp, P(vp)]
         L.rg_schedule_info.argtypes = [vp, P(u32), P(u32), P(i64)]
         L.rg_schedule_frontier.argtypes = [vp, u32, P(vp), P(vp), P(vp)]
         L.rg_schedule_samples.argtypes = [vp, u32, P(vp), P(vp), P(i64)]
@@ -103,7 +104,7 @@ def lib():
                      "rg_cache_pair_create", "rg_cache_pair_begin_next", "rg_cache_pair_swap",
                      "rg_prefetcher_create", "rg_prefetcher_fill", "rg_prefetcher_acquire", "rg_prefetcher_release",
                      "rg_prefetcher_depth", "rg_schedule_build_blocks", "rg_schedule_block",
-           "rg_classify_batch"):
+           "rg_classify_batch", "rg_build_schedule_with"):
             getattr(L, name).restype = C.c_int32
         _lib = L
     return _lib
@@ -182,6 +183,9 @@ class Cache:
             self.h = None
 
 
+RG_SAMPLER_KEYS, RG_SAMPLER_POSITIONS = 0, 1
+
+
 def rg_build_schedule(indptr, indices, train_nodes, batch_size, fanout, s0=0, worker=0, epoch=0, allocator=None, stream=None):
     g = _graph_struct(indptr, indices)
     fan = (C.c_uint32 * max(len(fanout), 1))(*[int(x) for x in fanout])
@@ -190,6 +194,18 @@ def rg_build_schedule(indptr, indices, train_nodes, batch_size, fanout, s0=0, wo
     _check(lib().rg_build_schedule(C.byref(g), _dev_ptr(train_nodes, torch.int32) if T else None, T, int(batch_size), fan,
                                    len(fanout), int(s0), int(worker), int(epoch),
                                    C.byref(allocator) if allocator is not None else None, _stream_ptr(stream), C.byref(out)))
+    return Schedule(out.value)
+
+
+def rg_build_schedule_with(indptr, indices, train_nodes, batch_size, fanout, s0=0, worker=0, epoch=0, sampler=RG_SAMPLER_KEYS,
+                           allocator=None, stream=None):
+    g = _graph_struct(indptr, indices)
+    fan = (C.c_uint32 * max(len(fanout), 1))(*[int(x) for x in fanout])
+    out = C.c_void_p()
+    T = train_nodes.numel()
+    _check(lib().rg_build_schedule_with(C.byref(g), _dev_ptr(train_nodes, torch.int32) if T else None, T, int(batch_size), fan,
+                                        len(fanout), int(s0), int(worker), int(epoch), int(sampler),
+                                        C.byref(allocator) if allocator is not None else None, _stream_ptr(stream), C.byref(out)))
     return Schedule(out.value)
 
 

@@ -37,6 +37,62 @@ __device__ __forceinline__ uint32_t key32(uint32_t lo, uint32_t hi, uint32_t u)
     return x;
 }
 
+// ---------------------------------------------------------------- drawn positions (the O(f) sampler)
+// Position p_t of draw t among the deg > f slots of a row, for a node state s; p_0, p_1, ... are distinct.
+//   deg <= 64: selection without replacement.  Draw k takes r_k = floor(u_k * (deg - k)), u_k the top 32 bits of
+//              mix64(s + (k + 1) G) read as a fraction, and picks the r_k-th slot not picked by draws 0 .. k-1.
+//              The lane of draw t replays draws 0 .. t over a 64-bit mask of taken slots.
+//   deg > 64:  p_t = pi_s(t), pi_s a permutation of [0, deg): an alternating Feistel network on
+//              n = bitlen(deg - 1) bits (left part n - n/2 bits, right part n/2 bits, six rounds, round value =
+//              top 32 bits of mix64((s ^ other part) + (r + 1) G)), walked along its cycle until the value is
+//              below deg.  The walk ends: the cycle through t comes back to t < deg.
+__device__ __forceinline__ uint32_t draw32(uint64_t s, uint32_t k) { return (uint32_t)(mix64(s + (uint64_t)(k + 1u) * HG64) >> 32); }
+
+__device__ __forceinline__ uint32_t feistel(uint32_t x, uint32_t n_bits, uint64_t s)
+{
+    const uint32_t hb = n_bits >> 1, ha = n_bits - hb;
+    const uint32_t mask_a = (1u << ha) - 1u, mask_b = (1u << hb) - 1u;        // n_bits <= 31: both parts below 32 bits
+    uint32_t a = x >> hb, b = x & mask_b;
+#pragma unroll
+    for (uint32_t r = 0; r < 6; ++r) {
+        if ((r & 1u) == 0) a ^= (uint32_t)(mix64((s ^ (uint64_t)b) + (uint64_t)(r + 1u) * HG64) >> 32) & mask_a;
+        else               b ^= (uint32_t)(mix64((s ^ (uint64_t)a) + (uint64_t)(r + 1u) * HG64) >> 32) & mask_b;
+    }
+    return (a << hb) | b;
+}
+
+// The r-th (from 0) set bit of m; m has more than r set bits.
+__device__ __forceinline__ uint32_t nth_set_bit(uint64_t m, uint32_t r)
+{
+    uint32_t p = 0;
+#pragma unroll
+    for (uint32_t w = 32; w >= 1; w >>= 1) {
+        const uint32_t c = (uint32_t)__popcll((m >> p) & ((1ull << w) - 1ull));
+        if (r >= c) { r -= c; p += w; }
+    }
+    return p;
+}
+
+// Requires 1 <= deg, t < deg.
+__device__ __forceinline__ uint32_t draw_position(uint32_t deg, uint32_t t, uint64_t s)
+{
+    if (deg <= 64u) {
+        const uint64_t all = deg == 64u ? ~0ull : (1ull << deg) - 1ull;
+        uint64_t taken = 0;
+        uint32_t p = 0;
+        for (uint32_t k = 0; k <= t; ++k) {
+            const uint32_t r = __umulhi(draw32(s, k), deg - k);
+            p = nth_set_bit(all & ~taken, r);
+            taken |= 1ull << p;
+        }
+        return p;
+    }
+    const uint32_t n_bits = 32u - (uint32_t)__clz((int)(deg - 1u));
+    uint32_t x = feistel(t, n_bits, s);
+    while (x >= deg) x = feistel(x, n_bits, s);
+    return x;
+}
+
 // ---------------------------------------------------------------- batch lookup
 // Batch of flat frontier position i: the b with off[b] <= i < off[b+1].
 __device__ __forceinline__ uint32_t batch_of(const int64_t *__restrict__ off, uint32_t n_batches, int64_t i)

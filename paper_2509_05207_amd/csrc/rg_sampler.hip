@@ -501,9 +501,39 @@ static void launch_hop(const HopArgs &a, unsigned grid, unsigned merge_grid, hip
     if (a.n_tiles > 0) hipLaunchKernelGGL(sample_merge_kernel<CAP>, dim3(merge_grid), dim3(64), 0, st, a);
 }
 
+// The O(f) sampler: one lane per sampled edge.  A node with deg <= f copies its row; otherwise lane t reads the
+// row at its drawn position (rg_device.h) and nothing else of the row.  Lanes of a workgroup are dealt to
+// (node, draw) pairs: 256 / f nodes per round when f < 256, one node per round otherwise.
+constexpr int POS_THREADS = 256;
+__global__ void __launch_bounds__(POS_THREADS) sample_positions_kernel(const int32_t *__restrict__ indices, NodeRecs rec, int64_t n_cur, uint32_t f,
+                                                                       const int64_t *__restrict__ samp_off, int32_t *__restrict__ samp_nbr,
+                                                                       uint32_t *__restrict__ reached, uint64_t words_per_batch)
+{
+    const uint32_t per_round = f >= POS_THREADS ? 1u : POS_THREADS / f;       // nodes per workgroup round
+    const uint32_t sub = f >= POS_THREADS ? 0u : threadIdx.x / f;              // this lane's node within the round
+    const uint32_t t0 = f >= POS_THREADS ? threadIdx.x : threadIdx.x - sub * f;
+    const uint32_t step = f >= POS_THREADS ? POS_THREADS : f;                  // a lane's next draw of the same node
+    if (sub >= per_round) return;
+    for (int64_t i = (int64_t)blockIdx.x * per_round + sub; i < n_cur; i += (int64_t)gridDim.x * per_round) {
+        const uint32_t deg = (uint32_t)rec.deg[i];
+        const uint32_t cnt = deg < f ? deg : f;
+        if (t0 >= cnt) continue;
+        const int32_t *row = indices + rec.row_begin[i];
+        const uint64_t S = rec.state[i];
+        int32_t *out = samp_nbr + samp_off[i];
+        uint32_t *reached_b = reached + (uint64_t)rec.batch[i] * words_per_batch;
+        for (uint32_t t = t0; t < cnt; t += step) {
+            const uint32_t p = deg <= f ? t : draw_position(deg, t, S);
+            const int32_t u = row[p];
+            out[t] = u;
+            mark_reached(reached_b, (uint32_t)u);
+        }
+    }
+}
+
 // Samples hop `hop` of every batch: fills cur.samp_off / samp_nbr / n_samples and marks the reached-ID bitmaps.
 rg_status sample_hop(const rg_graph *g, HopData &cur, uint32_t beta, const uint64_t *batch_seed, uint32_t hop, uint32_t fanout,
-                     uint32_t *reached, uint64_t words_per_batch, Arena &keep, Arena &tmp, int n_cu, hipStream_t st)
+                     uint32_t sampler, uint32_t *reached, uint64_t words_per_batch, Arena &keep, Arena &tmp, int n_cu, hipStream_t st)
 {
     const int64_t n_cur = cur.off_host[beta];
     int32_t *cnt = nullptr, *tiles = nullptr;
@@ -531,6 +561,17 @@ rg_status sample_hop(const rg_graph *g, HopData &cur, uint32_t beta, const uint6
     tmp.free_one(cnt);
     tmp.free_one(tiles);
     RG_TRY(keep.dev_n<int32_t>((uint64_t)cur.n_samples, &cur.samp_nbr));
+    if (sampler == RG_SAMPLER_POSITIONS) {
+        if (fanout > 0 && n_cur > 0) {
+            ScopedTimer tm(KG_SAMPLER, st);
+            const int64_t per_round = fanout >= (uint32_t)POS_THREADS ? 1 : POS_THREADS / fanout;
+            const unsigned grid = (unsigned)std::max<int64_t>(1, std::min<int64_t>((n_cur + per_round - 1) / per_round, (int64_t)n_cu * 64));
+            hipLaunchKernelGGL(sample_positions_kernel, dim3(grid), dim3(POS_THREADS), 0, st, g->indices, rec, n_cur, fanout, cur.samp_off, cur.samp_nbr,
+                               reached, words_per_batch);
+            RG_HIP(hipGetLastError());
+        }
+        return RG_OK;
+    }
     if (fanout == 0) n_tiles = 0;             // nothing is drawn; every sample is empty
     int32_t *tile_out = nullptr;
     RG_TRY(tmp.dev_n<int32_t>((uint64_t)n_tiles * fanout, &tile_out));

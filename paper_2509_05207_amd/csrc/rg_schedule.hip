@@ -17,7 +17,7 @@
 
 namespace rg {
 
-rg_status sample_hop(const rg_graph *g, HopData &cur, uint32_t beta, const uint64_t *batch_seed, uint32_t hop, uint32_t fanout,
+rg_status sample_hop(const rg_graph *g, HopData &cur, uint32_t beta, const uint64_t *batch_seed, uint32_t hop, uint32_t fanout, uint32_t sampler,
                      uint32_t *reached, uint64_t words_per_batch, Arena &keep, Arena &tmp, int n_cu, hipStream_t st);
 
 // ---------------------------------------------------------------- a1/a2: seeds, shuffle keys
@@ -225,7 +225,7 @@ static rg_status sort_keypos(KeyPos *kp, uint64_t n_pad, hipStream_t st)
 }
 
 static rg_status build_schedule_impl(const rg_graph *g, const int32_t *train, uint64_t T, uint32_t B, const uint32_t *fanout,
-                                     uint32_t L, uint64_t s0, uint32_t worker, uint32_t epoch, const rg_allocator *a, hipStream_t st, rg_schedule *s)
+                                     uint32_t L, uint64_t s0, uint32_t worker, uint32_t epoch, uint32_t sampler, const rg_allocator *a, hipStream_t st, rg_schedule *s)
 {
     const uint32_t beta = (uint32_t)(B ? (T + B - 1) / B : 0);
     s->n_nodes = g->n_nodes;
@@ -303,7 +303,7 @@ static rg_status build_schedule_impl(const rg_graph *g, const int32_t *train, ui
         const int64_t n_cur = cur.off_host[beta];
 
         // a3: the samples of this hop; sampled IDs are marked in `reached` as they are written
-        RG_TRY(sample_hop(g, cur, beta, batch_seed, l, fanout[l], reached, wpb, s->arena, tmp, n_cu, st));
+        RG_TRY(sample_hop(g, cur, beta, batch_seed, l, fanout[l], sampler, reached, wpb, s->arena, tmp, n_cu, st));
 
         // a4: fresh IDs per (batch, chunk) -> positions -> next frontier
         RG_TRY(s->arena.dev_n<int64_t>((uint64_t)beta + 1, &nxt.off_dev));
@@ -337,6 +337,14 @@ extern "C" rg_status rg_build_schedule(const rg_graph *g, const int32_t *train_n
                                        const uint32_t *fanout, uint32_t L, uint64_t s0, uint32_t worker, uint32_t epoch,
                                        const rg_allocator *a, void *stream, rg_schedule **out)
 {
+    return rg_build_schedule_with(g, train_nodes, T, batch_size, fanout, L, s0, worker, epoch, RG_SAMPLER_KEYS, a, stream, out);
+}
+
+extern "C" rg_status rg_build_schedule_with(const rg_graph *g, const int32_t *train_nodes, uint64_t T, uint32_t batch_size,
+                                            const uint32_t *fanout, uint32_t L, uint64_t s0, uint32_t worker, uint32_t epoch,
+                                            uint32_t sampler, const rg_allocator *a, void *stream, rg_schedule **out)
+{
+    if (sampler != RG_SAMPLER_KEYS && sampler != RG_SAMPLER_POSITIONS) { set_error("rg_build_schedule: unknown sampler %u", sampler); return RG_EINVAL; }
     if (!g || !out) { set_error("rg_build_schedule: null graph or output pointer"); return RG_EINVAL; }
     if (g->n_nodes < 0 || g->n_nodes >= ((int64_t)1 << 31)) { set_error("rg_build_schedule: n_nodes %lld outside [0, 2^31)", (long long)g->n_nodes); return RG_ERANGE; }
     if (!g->indptr) { set_error("rg_build_schedule: null indptr"); return RG_EINVAL; }
@@ -351,7 +359,7 @@ extern "C" rg_status rg_build_schedule(const rg_graph *g, const int32_t *train_n
 
     rg_schedule *s = new (std::nothrow) rg_schedule(a);
     if (!s) { set_error("rg_build_schedule: out of host memory"); return RG_ENOMEM; }
-    rg_status rc = build_schedule_impl(g, train_nodes, T, batch_size, fanout, L, s0, worker, epoch, a, as_stream(stream), s);
+    rg_status rc = build_schedule_impl(g, train_nodes, T, batch_size, fanout, L, s0, worker, epoch, sampler, a, as_stream(stream), s);
     if (rc != RG_OK) {
         (void)hipStreamSynchronize(as_stream(stream));
         delete s;

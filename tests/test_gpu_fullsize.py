@@ -146,3 +146,22 @@ def test_sampled_batches_and_epoch_properties(rg, orc, name, batches):
     assert torch.equal(out[:, :W.row_bytes], ref[:, :W.row_bytes])
     assert st["n_rows"] == seg.numel() and st["n_local"] == int(is_loc.sum().item())
     assert st["n_hit"] == int((sel[seg] & ~is_loc).sum().item()) and st["n_miss"] == st["n_rows"] - st["n_local"] - st["n_hit"]
+
+
+def test_medium_whole_epoch_position_sampler(rg, orc):
+    """The O(f) sampler at the benchmark's size: the oracle draws positions too, so the whole epoch is compared."""
+    cfg = synth.CONFIGS["medium"]
+    W = synth.make_workload(cfg, device="cuda", feature_device="cuda")
+    s = rg.rg_build_schedule_with(W.indptr, W.indices, W.train, cfg.batch_size, cfg.fanout, cfg.s0, cfg.worker, cfg.epoch,
+                                  sampler=rg.RG_SAMPLER_POSITIONS)
+    o = orc.Schedule(host(W.indptr), host(W.indices), host(W.train), cfg.batch_size, cfg.fanout, cfg.s0, cfg.worker, cfg.epoch,
+                     n_threads=16, sampler="positions")
+    assert s.n_batches == o.n_batches
+    for hop in range(o.L + 1):
+        ids, off = o.frontier(hop)
+        gids, _, goff = rg.rg_schedule_frontier(s, hop)
+        assert np.array_equal(goff, off) and np.array_equal(host(gids), ids), f"frontier {hop}"
+    for hop in range(o.L):
+        so, nb = o.samples(hop)
+        gso, gnb = rg.rg_schedule_samples(s, hop)
+        assert np.array_equal(host(gso), so) and np.array_equal(host(gnb), nb), f"samples {hop}"

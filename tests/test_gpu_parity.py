@@ -323,3 +323,44 @@ def test_rows_of_odd_width_and_alignment(rg, orc):
             torch.cuda.synchronize()
             ref = orc.gather_batch(o, 1, of, out_stride=out_stride, fill=0xEE)
             assert np.array_equal(out.cpu().numpy()[: ref.size].reshape(ref.shape), ref), (row_bytes, stride, out_stride)
+
+
+# ------------------------------------------------------------------ the O(f) alternative sampler
+@pytest.mark.parametrize("fanout", [None, (300, 3), (70, 2), (1, 1), (64, 63)])
+def test_position_sampler_matches_oracle(case, rg, orc, fanout):
+    """RG_SAMPLER_POSITIONS against the oracle's position sampler: every frontier, sample and block, bit for bit;
+    fan-outs on both sides of the workgroup width and of the 64-slot selection branch."""
+    w = case.w
+    fan = list(fanout) if fanout else list(w.cfg.fanout)
+    if fanout and case.name not in ("small", "mid"):
+        pytest.skip("fan-out variants run on two graphs")
+    o = orc.Schedule(w.indptr.numpy(), w.indices.numpy(), w.train.numpy(), w.cfg.batch_size, fan, case.s0, case.worker, case.epoch,
+                     n_threads=8, sampler="positions")
+    g = rg.rg_build_schedule_with(case.indptr, case.indices, case.train, w.cfg.batch_size, fan, case.s0, case.worker, case.epoch,
+                                  sampler=rg.RG_SAMPLER_POSITIONS)
+    assert_schedules_equal(rg, g, o)
+    rg.rg_schedule_build_blocks(g)
+    for hop in range(g.L):
+        assert np.array_equal(rg.rg_schedule_block(g, hop).cpu().numpy(), o.block(hop))
+    if fanout is None:
+        # the cache and the gather do not care which sampler built the schedule
+        freq = orc.frequency([o], w.n_nodes)
+        ids, slot = orc.top_hot(freq, w.is_local.numpy(), w.K)
+        c = rg.rg_build_cache([g], case.gfeat, w.K)
+        assert np.array_equal(rg.rg_cache_view(c, w.n_nodes)["cache_ids"].cpu().numpy(), ids)
+        _, off = o.input_nodes()
+        m_max = int(np.diff(off).max())
+        out = torch.empty(m_max * w.row_bytes, dtype=torch.uint8, device="cuda")
+        for b in (0, g.n_batches - 1):
+            st = rg.rg_gather_batch(g, c, case.gfeat, b, out, out_stride=w.row_bytes, out_capacity_rows=m_max)
+            torch.cuda.synchronize()
+            ref = orc.gather_batch(o, b, case.ofeat, out_stride=w.row_bytes, fill=0)
+            assert np.array_equal(out.cpu().numpy()[:ref.size].reshape(ref.shape), ref)
+            assert st == orc.batch_stats(o, b, w.is_local.numpy(), slot)
+
+
+def test_unknown_sampler_is_refused(case, rg):
+    w = case.w
+    with pytest.raises(rg.RgError) as e:
+        rg.rg_build_schedule_with(case.indptr, case.indices, case.train, w.cfg.batch_size, w.cfg.fanout, 0, 0, 0, sampler=7)
+    assert e.value.status == rg.RG_EINVAL
