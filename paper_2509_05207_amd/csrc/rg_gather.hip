@@ -54,7 +54,11 @@ __device__ __forceinline__ void copy_tail(const uint8_t *src, uint8_t *dst, uint
 constexpr int GATHER_THREADS = 256;
 constexpr int CHUNKS_IN_FLIGHT = 8;
 
-template <int VEC, int A>
+// TAILPIECE = false: every piece is a full vector.  Either row_bytes is a multiple of VEC, or the last piece of a
+// row is the vector that ENDS at the row's end and overlaps its predecessor (both write the same bytes there), so
+// that no lane leaves the vector path.  TAILPIECE = true (row widths that are no multiple of 4, or below VEC): the
+// last piece is copied in 8/4/2/1-byte parts.
+template <int VEC, int A, bool TAILPIECE>
 __global__ void __launch_bounds__(GATHER_THREADS) gather_rows_kernel(const int64_t *__restrict__ entries, int64_t n_rows,
                                                                      const int32_t *__restrict__ list, int64_t n_list, int mode,
                                                                      RowSources src, uint32_t row_bytes,
@@ -63,7 +67,8 @@ __global__ void __launch_bounds__(GATHER_THREADS) gather_rows_kernel(const int64
     using T = typename VecT<VEC>::type;
     using P = typename PieceT<VEC, A>::type;
     const uint32_t cpr = row_bytes / VEC, tail = row_bytes % VEC;
-    const uint32_t cpt = cpr + (tail ? 1u : 0u);                  // pieces per row: full vectors, then the tail piece
+    const uint32_t cpt = cpr + (tail ? 1u : 0u);                  // pieces per row: full vectors, then the last piece
+    const uint32_t last_off = TAILPIECE ? cpr * VEC : row_bytes - VEC;     // where the piece after the full vectors starts
     const uint64_t n_work = (uint64_t)(list ? n_list : n_rows);
     const uint64_t total = n_work * cpt;
     // A workgroup takes GATHER_THREADS * chunks consecutive pieces per round (chunks <= CHUNKS_IN_FLIGHT, fewer for
@@ -81,7 +86,7 @@ __global__ void __launch_bounds__(GATHER_THREADS) gather_rows_kernel(const int64
         T v[CHUNKS_IN_FLIGHT];
         const uint8_t *sp[CHUNKS_IN_FLIGHT];
         uint8_t *dp[CHUNKS_IN_FLIGHT];
-        int kind[CHUNKS_IN_FLIGHT];                                // 0 nothing, 1 full vector, 2 tail piece
+        int kind[CHUNKS_IN_FLIGHT];                                // 0 nothing, 1 full vector, 2 last piece in parts
 #pragma unroll
         for (int k = 0; k < CHUNKS_IN_FLIGHT; ++k) {
             kind[k] = 0;
@@ -94,9 +99,10 @@ __global__ void __launch_bounds__(GATHER_THREADS) gather_rows_kernel(const int64
                     const uint8_t *base = tag == TAG_LOCAL ? src.local_rows + (uint64_t)row * src.local_stride
                                         : tag == TAG_CACHE ? src.cache_rows + (uint64_t)row * src.cache_stride
                                                            : src.remote_rows + (uint64_t)row * src.remote_stride;
-                    sp[k] = base + (uint64_t)c * VEC;
-                    dp[k] = out + (uint64_t)r * out_stride + (uint64_t)c * VEC;
-                    kind[k] = c < cpr ? 1 : 2;
+                    const uint32_t o = c < cpr ? c * VEC : last_off;
+                    sp[k] = base + o;
+                    dp[k] = out + (uint64_t)r * out_stride + o;
+                    kind[k] = (!TAILPIECE || c < cpr) ? 1 : 2;
                     if (kind[k] == 1) v[k] = *reinterpret_cast<const P *>(sp[k]);
                 }
             }
@@ -108,7 +114,7 @@ __global__ void __launch_bounds__(GATHER_THREADS) gather_rows_kernel(const int64
 #pragma unroll
         for (int k = 0; k < CHUNKS_IN_FLIGHT; ++k) {
             if (kind[k] == 1) __builtin_nontemporal_store(v[k], reinterpret_cast<P *>(dp[k]));
-            else if (kind[k] == 2) copy_tail<VEC, A>(sp[k], dp[k], tail);
+            else if (TAILPIECE && kind[k] == 2) copy_tail<VEC, A>(sp[k], dp[k], tail);
         }
     }
 }
@@ -128,9 +134,15 @@ rg_status launch_gather(const int64_t *entries, int64_t n_rows, const int32_t *l
 {
     const int64_t n_work = list ? n_list : n_rows;
     if (n_work <= 0) return RG_OK;
-    const int align = common_alignment(src, out, out_stride);
+    int align = common_alignment(src, out, out_stride);
     const int vec = align >= 4 ? 16 : 1;                        // dword-aligned rows take 16-byte vectors, anything else goes byte by byte
-    const uint64_t cpt = row_bytes / (uint32_t)vec + (row_bytes % (uint32_t)vec ? 1 : 0);
+    const uint32_t tail = row_bytes % (uint32_t)vec;
+    // A row that ends between vectors: if its width is a multiple of 4 and at least one vector, the last piece is the
+    // vector ending at the row's end, at the alignment the width leaves; otherwise the last piece goes in parts.
+    const bool overlap_last = vec == 16 && tail != 0 && row_bytes >= 16 && row_bytes % 4 == 0;
+    const bool tailpiece = tail != 0 && !overlap_last;
+    if (overlap_last) align = std::min(align, (row_bytes % 8 == 0) ? 8 : 4);
+    const uint64_t cpt = row_bytes / (uint32_t)vec + (tail ? 1 : 0);
     int dev = 0, n_cu = 256;
     RG_HIP(hipGetDevice(&dev));
     RG_HIP(hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, dev));
@@ -142,9 +154,15 @@ rg_status launch_gather(const int64_t *entries, int64_t n_rows, const int32_t *l
     const uint64_t per_block = (uint64_t)GATHER_THREADS * chunks;
     const uint64_t blocks = std::max<uint64_t>(1, std::min<uint64_t>((total + per_block - 1) / per_block, (uint64_t)n_cu * 32));
     ScopedTimer tm(group, st);
-#define RG_GATHER_LAUNCH(V, AL)                                                                                                         \
-    hipLaunchKernelGGL((gather_rows_kernel<V, AL>), dim3((unsigned)blocks), dim3(GATHER_THREADS), 0, st, entries, n_rows, list, n_list, mode, \
-                       src, row_bytes, out, out_stride, chunks)
+#define RG_GATHER_LAUNCH(V, AL)                                                                                                               \
+    do {                                                                                                                                      \
+        if (tailpiece)                                                                                                                        \
+            hipLaunchKernelGGL((gather_rows_kernel<V, AL, true>), dim3((unsigned)blocks), dim3(GATHER_THREADS), 0, st, entries, n_rows, list,   \
+                               n_list, mode, src, row_bytes, out, out_stride, chunks);                                                        \
+        else                                                                                                                                  \
+            hipLaunchKernelGGL((gather_rows_kernel<V, AL, false>), dim3((unsigned)blocks), dim3(GATHER_THREADS), 0, st, entries, n_rows, list,  \
+                               n_list, mode, src, row_bytes, out, out_stride, chunks);                                                        \
+    } while (0)
     switch (align) {
     case 16: RG_GATHER_LAUNCH(16, 16); break;
     case 8:  RG_GATHER_LAUNCH(16, 8); break;
