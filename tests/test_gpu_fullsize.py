@@ -32,7 +32,8 @@ def np_bytes(t):
 
 def build(rg, name):
     cfg = synth.CONFIGS[name]
-    W = synth.make_workload(cfg, device="cuda", feature_device="cuda")
+    # the largest configuration's remote table (tens of GB) is produced on the device, as bench.py does
+    W = synth.make_workload(cfg, device="cuda", feature_device="cuda", remote_device="cuda" if name == "partition_share" else None)
     s = rg.rg_build_schedule(W.indptr, W.indices, W.train, cfg.batch_size, cfg.fanout, cfg.s0, cfg.worker, cfg.epoch)
     return cfg, W, s
 
@@ -96,7 +97,7 @@ def test_medium_whole_epoch(rg, orc):
         assert st == orc.batch_stats(o, b, is_local, slot)
 
 
-@pytest.mark.parametrize("name,batches", [("large_sparse", (0, 97, 195)), ("fanout_stress", (0, 48))])
+@pytest.mark.parametrize("name,batches", [("large_sparse", (0, 97, 195)), ("fanout_stress", (0, 48)), ("partition_share", (0, 146))])
 def test_sampled_batches_and_epoch_properties(rg, orc, name, batches):
     cfg, W, s = build(rg, name)
     indptr, indices, train = host(W.indptr), host(W.indices), host(W.train)
