@@ -193,18 +193,19 @@ typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 // Appends the block's candidates to the buffer in row order.  If they do not fit, the buffer is
 // pruned first (which tightens the cut and may drop some of them); if they still do not fit, the
 // block goes in four quarters of 64 consecutive IDs.
-template <int CAP>
+// MAYBE_OPEN = false: the caller knows a cut is in force (s.open is false), which takes the test out of the loop.
+template <int CAP, bool MAYBE_OPEN = true>
 __device__ __forceinline__ void append_block(const uint32_t (&u)[4], const uint32_t (&k)[4], const unsigned long long (&vm)[4], int f, uint32_t lo,
                                              uint32_t hi, int lane, uint32_t *buf, Stream &s)
 {
     f = uni(f); lo = uni(lo); hi = uni(hi);
-    s.cnt = uni(s.cnt); s.open = uni(s.open); s.cut = uni(s.cut);
+    s.cnt = uni(s.cnt); s.open = MAYBE_OPEN ? uni(s.open) : false; s.cut = uni(s.cut);
     const unsigned long long me = 1ull << lane;
     unsigned long long m[4];
     int total = 0;
 #pragma unroll
     for (int e = 0; e < 4; ++e) {
-        m[e] = s.open ? vm[e] : (ballot64(k[e] <= s.cut) & vm[e]);
+        m[e] = (MAYBE_OPEN && s.open) ? vm[e] : (ballot64(k[e] <= s.cut) & vm[e]);
         total += __popcll(m[e]);
     }
     if (total == 0) return;
@@ -242,7 +243,7 @@ __device__ __forceinline__ void append_block(const uint32_t (&u)[4], const uint3
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
             mq[e] = m[e] & quarter;
-            if (!s.open) mq[e] &= ballot64(k[e] <= s.cut);
+            if (!(MAYBE_OPEN && s.open)) mq[e] &= ballot64(k[e] <= s.cut);
             rank += lanes_below(mq[e], lane);
             sub += __popcll(mq[e]);
         }
@@ -268,7 +269,7 @@ __device__ __forceinline__ u32x4 load_block(const int32_t *__restrict__ p, int l
 // Valid lanes of ID e of a block that holds `count` IDs: 4 * lane + e < count.
 __device__ __forceinline__ unsigned long long block_lanes(int count, int e) { return low_lanes((count - e + 3) >> 2); }
 
-template <int CAP, bool FULL>
+template <int CAP, bool FULL, bool MAYBE_OPEN = true>
 __device__ __forceinline__ void stream_block(const u32x4 &blk, int count, int f, uint32_t lo, uint32_t hi, int lane, uint32_t *buf, Stream &s)
 {
     count = uni(count); f = uni(f); lo = uni(lo); hi = uni(hi);
@@ -280,7 +281,7 @@ __device__ __forceinline__ void stream_block(const u32x4 &blk, int count, int f,
         k[e] = key32(lo, hi, u[e]);
         vm[e] = FULL ? ~0ull : block_lanes(count, e);
     }
-    append_block<CAP>(u, k, vm, f, lo, hi, lane, buf, s);
+    append_block<CAP, MAYBE_OPEN>(u, k, vm, f, lo, hi, lane, buf, s);
 }
 
 // Row of len > 256 IDs streamed once; on return buf[0..f) is the sample in row order.  The IDs in
@@ -291,17 +292,28 @@ template <int CAP>
 __device__ __forceinline__ void sample_long_row(const int32_t *__restrict__ row, int len, int f, uint32_t lo, uint32_t hi, int lane, uint32_t *buf)
 {
     len = uni(len); f = uni(f); lo = uni(lo); hi = uni(hi);
-    Stream s{0, true, 0u};
     int head = uni((32 - (int)(((uintptr_t)row >> 2) & 31)) & 31);
     if (head > len) head = len;
     const int32_t *p = row + head;
     const int rem = len - head;                                  // > 0: len > 256 and head < 32
     const int n_blocks = (rem + 255) >> 8;
     const uint32_t head_u = lane < head ? (uint32_t)row[lane] : 0u;
+    // First attempt with a guessed cut.  Keys are uniform 32-bit words, so about lambda = f + 4 sqrt(f) + 8 of the
+    // row's keys fall below lambda / len: streaming with that cut from the start collects the few IDs that can be in
+    // the sample and skips the first cut and the prunes of the exact procedure.  The guess never changes the result:
+    // every ID with a key up to the cut is kept, so if at least f turn up, the f smallest keys of the row are among
+    // them; if fewer do (once in thousands of rows), the row is streamed again with the exact procedure.
+    const float lambda = (float)f + 4.0f * __fsqrt_rn((float)f) + 8.0f;
+    const bool can_guess = uni(lambda * 4.0f <= (float)len);
+    const uint32_t guessed_cut = (uint32_t)(fminf(lambda / (float)len, 0.5f) * 4294967296.0f);
+    Stream s{0, true, 0u};
+  for (int attempt = uni(can_guess ? 0 : 1); attempt < 2; attempt = uni(attempt + 1)) {
+    const bool guess = attempt == 0;
+    s = guess ? Stream{0, false, guessed_cut} : Stream{0, true, 0u};
     u32x4 cur = load_block(p, rem, lane), nxt = {0u, 0u, 0u, 0u};
     int c0 = 0;
     const int count0 = rem < 256 ? rem : 256;
-    if (head + count0 > f) {
+    if (!guess && head + count0 > f) {
         // The usual case: the head and the first block (up to 287 IDs, all in registers) already hold more
         // than f IDs.  Their f smallest keys give the first cut directly; only those f IDs enter the buffer.
         if (rem > 256) nxt = load_block(p + 256, rem - 256, lane);
@@ -339,11 +351,15 @@ __device__ __forceinline__ void sample_long_row(const int32_t *__restrict__ row,
     for (int c = uni(c0); c < n_blocks; c = uni(c + 1)) {
         const int left = uni(rem - c * 256);                     // IDs left, this block included
         if (left > 256) nxt = load_block(p + (c + 1) * 256, left - 256, lane);
-        if (left >= 256) stream_block<CAP, true>(cur, 256, f, lo, hi, lane, buf, s);
-        else stream_block<CAP, false>(cur, left, f, lo, hi, lane, buf, s);
+        if (left >= 256) {
+            if (guess) stream_block<CAP, true, false>(cur, 256, f, lo, hi, lane, buf, s);
+            else stream_block<CAP, true, true>(cur, 256, f, lo, hi, lane, buf, s);
+        } else stream_block<CAP, false>(cur, left, f, lo, hi, lane, buf, s);
         cur = nxt;
     }
     __syncthreads();
+    if (s.cnt >= f) break;                                       // (always, in the exact attempt: len > f)
+  }
     if (s.cnt > f) (void)prune_buffer<CAP>(buf, s.cnt, f, lo, hi, lane);
 }
 
