@@ -71,7 +71,15 @@ __global__ void node_records_kernel(const int64_t *__restrict__ indptr, const in
     tiles[i] = (int32_t)tiles_of(deg);
 }
 
-__device__ __forceinline__ int lanes_below(unsigned long long m, int lane) { return __popcll(m & ((1ull << lane) - 1ull)); }
+// Number of set bits of m below this lane's bit (m wave-uniform): the two mbcnt instructions.
+__device__ __forceinline__ int lanes_below(unsigned long long m, int lane)
+{
+    (void)lane;
+    return (int)__builtin_amdgcn_mbcnt_hi((uint32_t)(m >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)m, 0u));
+}
+
+// This lane's bit of a wave-uniform mask, as a condition the vector unit takes straight from the scalar pair.
+__device__ __forceinline__ bool my_bit(unsigned long long m) { return __builtin_amdgcn_inverse_ballot_w64(m); }
 
 // The lane mask of a predicate, taken straight from the compare.
 __device__ __forceinline__ unsigned long long ballot64(bool p) { return __builtin_amdgcn_ballot_w64(p); }
@@ -200,7 +208,6 @@ __device__ __forceinline__ void append_block(const uint32_t (&u)[4], const uint3
 {
     f = uni(f); lo = uni(lo); hi = uni(hi);
     s.cnt = uni(s.cnt); s.open = MAYBE_OPEN ? uni(s.open) : false; s.cut = uni(s.cut);
-    const unsigned long long me = 1ull << lane;
     unsigned long long m[4];
     int total = 0;
 #pragma unroll
@@ -222,12 +229,22 @@ __device__ __forceinline__ void append_block(const uint32_t (&u)[4], const uint3
         if (total == 0) return;
     }
     if (s.cnt + total <= CAP) {
+        const unsigned long long any = m[0] | m[1] | m[2] | m[3];
+        if (__popcll(any) == total) {
+            // The usual event: no lane holds two candidates, so lane order is row order: one rank, one store.
+            if (my_bit(any)) {
+                const uint32_t v = my_bit(m[0]) ? u[0] : my_bit(m[1]) ? u[1] : my_bit(m[2]) ? u[2] : u[3];
+                buf[s.cnt + lanes_below(any, lane)] = v;
+            }
+            s.cnt += total;
+            return;
+        }
         int rank = s.cnt;
 #pragma unroll
         for (int e = 0; e < 4; ++e) rank += lanes_below(m[e], lane);
 #pragma unroll
         for (int e = 0; e < 4; ++e)
-            if (m[e] & me) buf[rank++] = u[e];
+            if (my_bit(m[e])) buf[rank++] = u[e];
         s.cnt += total;
         return;
     }
@@ -249,7 +266,7 @@ __device__ __forceinline__ void append_block(const uint32_t (&u)[4], const uint3
         }
 #pragma unroll
         for (int e = 0; e < 4; ++e)
-            if (mq[e] & me) buf[rank++] = u[e];
+            if (my_bit(mq[e])) buf[rank++] = u[e];
         s.cnt += sub;
     }
 }
@@ -328,18 +345,17 @@ __device__ __forceinline__ void sample_long_row(const int32_t *__restrict__ row,
         s.cut = uni(kth_key_threshold<5>(k, vm, f, head + count0));
         s.open = false;
         s.cnt = f;
-        const unsigned long long me = 1ull << lane;
-        unsigned long long m[5];
+            unsigned long long m[5];
         int rank = 0;
 #pragma unroll
         for (int e = 0; e < 5; ++e) m[e] = ballot64(k[e] <= s.cut) & vm[e];
-        if (m[0] & me) buf[lanes_below(m[0], lane)] = u[0];
+        if (my_bit(m[0])) buf[lanes_below(m[0], lane)] = u[0];
         rank = __popcll(m[0]);
 #pragma unroll
         for (int e = 1; e < 5; ++e) rank += lanes_below(m[e], lane);
 #pragma unroll
         for (int e = 1; e < 5; ++e)
-            if (m[e] & me) buf[rank++] = u[e];
+            if (my_bit(m[e])) buf[rank++] = u[e];
         cur = nxt;
         c0 = 1;
     } else if (head > 0) {

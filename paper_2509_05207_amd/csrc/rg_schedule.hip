@@ -124,9 +124,11 @@ __global__ void __launch_bounds__(FR_THREADS) fresh_count_kernel(const uint32_t 
     if (w0 < words_per_batch) {      // words_per_batch is a multiple of FR_WORDS_PER_THREAD
         const uint64_t at = (uint64_t)b * words_per_batch + w0;
         const uint4 r0 = *reinterpret_cast<const uint4 *>(reached + at), r1 = *reinterpret_cast<const uint4 *>(reached + at + 4);
-        const uint4 s0 = *reinterpret_cast<const uint4 *>(seen + at), s1 = *reinterpret_cast<const uint4 *>(seen + at + 4);
-        n = __popc(r0.x & ~s0.x) + __popc(r0.y & ~s0.y) + __popc(r0.z & ~s0.z) + __popc(r0.w & ~s0.w) +
-            __popc(r1.x & ~s1.x) + __popc(r1.y & ~s1.y) + __popc(r1.z & ~s1.z) + __popc(r1.w & ~s1.w);
+        if ((r0.x | r0.y | r0.z | r0.w | r1.x | r1.y | r1.z | r1.w) != 0u) {      // on big graphs most words were not reached: `seen` stays unread
+            const uint4 s0 = *reinterpret_cast<const uint4 *>(seen + at), s1 = *reinterpret_cast<const uint4 *>(seen + at + 4);
+            n = __popc(r0.x & ~s0.x) + __popc(r0.y & ~s0.y) + __popc(r0.z & ~s0.z) + __popc(r0.w & ~s0.w) +
+                __popc(r1.x & ~s1.x) + __popc(r1.y & ~s1.y) + __popc(r1.z & ~s1.z) + __popc(r1.w & ~s1.w);
+        }
     }
     for (int o = 32; o > 0; o >>= 1) n += __shfl_down(n, o, 64);
     if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = n;
