@@ -10,6 +10,8 @@ its misses cross the host link.
 
 Prints ONE JSON line.  `value` is sampled edges per second over whole steps;
 the gathered-feature rate and the per-kernel roofline figures ride along.
+Gathers stage --gather-group batches per launch (default 8: the feature blocks of
+the next eight batches back to back in one staging buffer, rg_gather_batches).
 """
 import argparse
 import json
@@ -48,31 +50,36 @@ def algorithmic_bytes(rg, sched, indptr, fanout):
     return out
 
 
-def run_step(rg, W, feat, out_buf, out_stride, cap_rows, side):
+def run_step(rg, W, feat, out_buf, out_stride, cap_rows, side, group=1):
     cfg = W.cfg
     s = rg.rg_build_schedule(W.indptr, W.indices, W.train, cfg.batch_size, cfg.fanout, cfg.s0, cfg.worker, cfg.epoch)
     c = rg.rg_build_cache([s], feat, W.K)
-    for b in range(s.n_batches):
-        rg.rg_gather_batch(s, c, feat, b, out_buf, out_stride=out_stride, out_capacity_rows=cap_rows, side_stream=side,
-                           want_stats=False)
+    if group <= 1:
+        for b in range(s.n_batches):
+            rg.rg_gather_batch(s, c, feat, b, out_buf, out_stride=out_stride, out_capacity_rows=cap_rows, side_stream=side,
+                               want_stats=False)
+    else:
+        for b in range(0, s.n_batches, group):
+            rg.rg_gather_batches(s, c, feat, b, min(group, s.n_batches - b), out_buf, out_stride=out_stride, out_capacity_rows=cap_rows,
+                                 side_stream=side, want_stats=False)
     return s, c
 
 
-def timed(rg, W, feat, out_buf, out_stride, cap_rows, side, steps, warmup):
+def timed(rg, W, feat, out_buf, out_stride, cap_rows, side, steps, warmup, group=1):
     for _ in range(warmup):
-        run_step(rg, W, feat, out_buf, out_stride, cap_rows, side)
+        run_step(rg, W, feat, out_buf, out_stride, cap_rows, side, group)
     torch.cuda.synchronize()
     rg.rg_profile_reset()
     t0 = time.perf_counter()
     for _ in range(steps):
-        s, c = run_step(rg, W, feat, out_buf, out_stride, cap_rows, side)
+        s, c = run_step(rg, W, feat, out_buf, out_stride, cap_rows, side, group)
         del s, c
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
     return dt, rg.rg_profile_read()
 
 
-def overlapped_leg(rg, W, feat, out_stride, epochs=6):
+def overlapped_leg(rg, W, feat, out_stride, epochs=6, group=1):
     """E epochs end to end with the precompute of epoch e+1 (schedule, tally, TopHot, cache, plan: compute- and
     cache-bound) running on a second host thread and stream beside the gathers of epoch e (HBM-bound), as Alg. 1
     arranges it.  Every epoch's whole hot path runs inside the timed region."""
@@ -109,12 +116,13 @@ def overlapped_leg(rg, W, feat, out_stride, epochs=6):
             raise errors[0]
         s, c = item
         off_L = rg.rg_schedule_frontier(s, s.L)[2]
-        need = int(np.diff(off_L).max())
+        need = max(int(off_L[min(b + group, s.n_batches)] - off_L[b]) for b in range(0, s.n_batches, group))
         if m_cap is None or need > m_cap:
             m_cap = need + need // 8
             outs = [torch.empty(m_cap * out_stride, dtype=torch.uint8, device="cuda") for _ in range(2)]
-        for b in range(s.n_batches):
-            rg.rg_gather_batch(s, c, feat, b, outs[b & 1], out_stride=out_stride, out_capacity_rows=m_cap, want_stats=False)
+        for i, b in enumerate(range(0, s.n_batches, group)):
+            rg.rg_gather_batches(s, c, feat, b, min(group, s.n_batches - b), outs[i & 1], out_stride=out_stride, out_capacity_rows=m_cap,
+                                 want_stats=False)
         edges += sum(rg.rg_schedule_samples(s, h)[1].numel() for h in range(s.L))
         torch.cuda.current_stream().synchronize()      # the epoch's gathers are done before its handles go
         del s, c
@@ -239,6 +247,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=1)
     ap.add_argument("--workload", default="medium", choices=sorted(synth.CONFIGS))
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--gather-group", type=int, default=8,
+                    help="batches whose feature blocks one gather launch stages back to back (rg_gather_batches); 1 = one launch per batch")
     ap.add_argument("--no-pcie-pass", action="store_true")
     ap.add_argument("--no-runtime-leg", action="store_true", help="skip the multi-epoch cache-pair / prefetch-queue / blocks leg")
     ap.add_argument("--pmc-probe", action="store_true",
@@ -276,11 +286,14 @@ def main():
     n_batches = s.n_batches
     del s, c
     sampled_edges = sum(h["sampled"] for h in hops)
+    G = max(1, args.gather_group)
+    if G > 1:       # the staging buffer holds the largest group of G consecutive batches
+        m_max = max(int(off_L[min(b + G, n_batches)] - off_L[b]) for b in range(0, n_batches, G))
     out_buf = torch.empty(m_max * W.stride_bytes, dtype=torch.uint8, device="cuda")
     log(f"[bench] {n_batches} batches, {sampled_edges} sampled edges/epoch, {rows_per_epoch} gathered rows/epoch, K_eff={k_eff}, batch0 {stats[0]}")
 
     rg.rg_profile_enable(True)
-    dt, prof = timed(rg, W, feat_hbm, out_buf, W.stride_bytes, m_max, side, args.steps, args.warmup)
+    dt, prof = timed(rg, W, feat_hbm, out_buf, W.stride_bytes, m_max, side, args.steps, args.warmup, G)
     ms_per_step = dt / args.steps * 1e3
     value = sampled_edges * args.steps / dt
     log(f"[bench] HBM-resident: {ms_per_step:.2f} ms/step; kernel groups: " +
@@ -315,7 +328,7 @@ def main():
         "data": "synthetic",
         "config": {"workload": f"{cfg.name}: {W.n_nodes} nodes, {W.indices.numel()} edges (Chung-Lu, exponent {cfg.gamma}), "
                                f"{cfg.feat_dtype} features dim {cfg.feat_dim}, fanout {cfg.fanout}, batch {cfg.batch_size}, "
-                               f"{cfg.n_train} train nodes, K={W.K}, remote table in HBM",
+                               f"{cfg.n_train} train nodes, K={W.K}, remote table in HBM, {G} batch(es) per gather launch",
                    "n_batches": n_batches, "sampled_edges_per_epoch": sampled_edges, "gathered_rows_per_epoch": rows_per_epoch,
                    "K_eff": int(k_eff)},
         "roofline": roof,
@@ -330,7 +343,7 @@ def main():
         remote_pinned = synth.pinned_copy(W.remote_rows)
         feat_pin = rg.make_features(W.is_local, W.row_of, W.local_rows, remote_pinned, W.row_bytes)
         steps2 = max(1, min(args.steps, 2))
-        dt2, prof2 = timed(rg, W, feat_pin, out_buf, W.stride_bytes, m_max, side, steps2, 1)
+        dt2, prof2 = timed(rg, W, feat_pin, out_buf, W.stride_bytes, m_max, side, steps2, 1, G)
         miss_ms = prof2["gather_miss"]["ms"] / steps2
         fill_ms = prof2["cache_fill"]["ms"] / steps2
         result["pcie_inclusive"] = {"value": sampled_edges * steps2 / dt2, "unit": "sampled edges/s", "ms_per_step": dt2 / steps2 * 1e3,
@@ -342,7 +355,7 @@ def main():
         log(f"[bench] runtime leg: {result['runtime']}")
     rg.rg_profile_enable(False)
     if not args.no_runtime_leg:
-        result["overlapped"] = overlapped_leg(rg, W, feat_hbm, W.stride_bytes)
+        result["overlapped"] = overlapped_leg(rg, W, feat_hbm, W.stride_bytes, group=G)
         log(f"[bench] overlapped epochs: {result['overlapped']}")
 
     if args.pmc_probe:

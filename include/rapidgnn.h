@@ -209,6 +209,22 @@ rg_status rg_gather_batch(const rg_schedule *s, const rg_cache *c, const rg_feat
                           void *out, uint64_t out_stride, uint64_t out_capacity_rows,
                           void *stream, void *side_stream, rg_gather_stats *stats);
 
+/*
+ * rg_gather_batches -- the blocks of batches [first_batch, first_batch + n_batches)
+ * back to back: the block of batch b starts at row off[b] - off[first_batch] of
+ * `out`, off being the batch offsets of rg_schedule_frontier(s, L).  Same bytes
+ * as n_batches calls of rg_gather_batch (the prefetcher's "next Q batches" in
+ * one go, Sec. 3 "Rolling prefetch and execution").  With a cache built from
+ * `s` the range is one launch (plus one per batch with misses when the remote
+ * table is pinned host memory); otherwise it runs batch by batch.
+ *   stats  host, [n_batches], or NULL
+ * RG_ERANGE if the range leaves the schedule or its rows exceed
+ * out_capacity_rows (nothing is written).
+ */
+rg_status rg_gather_batches(const rg_schedule *s, const rg_cache *c, const rg_features *f, uint32_t first_batch,
+                            uint32_t n_batches, void *out, uint64_t out_stride, uint64_t out_capacity_rows,
+                            void *stream, void *side_stream, rg_gather_stats *stats);
+
 /* The counts of rg_gather_batch without the copy (Alg. 1 inner loop: the miss
  * set M_i^e and rpc_e += |M_i^e|): what a cache-size sweep needs.  From the
  * prepared plan when `c` was built from `s` (no device work), otherwise one

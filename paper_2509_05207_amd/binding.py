@@ -25,7 +25,7 @@ EXPORTS = ("rg_last_error", "rg_graph_validate", "rg_build_schedule", "rg_schedu
            "rg_cache_pair_table_bytes", "rg_cache_pair_destroy",
            "rg_prefetcher_create", "rg_prefetcher_fill", "rg_prefetcher_acquire", "rg_prefetcher_release",
            "rg_prefetcher_depth", "rg_prefetcher_destroy", "rg_schedule_build_blocks", "rg_schedule_block",
-           "rg_classify_batch", "rg_build_schedule_with")
+           "rg_classify_batch", "rg_build_schedule_with", "rg_gather_batches")
 
 
 class RgError(RuntimeError):
@@ -84,6 +84,7 @@ def lib():
         L.rg_profile_enable.argtypes = [C.c_int]; L.rg_profile_enable.restype = None
         L.rg_profile_reset.argtypes = []; L.rg_profile_reset.restype = None
         L.rg_profile_read.argtypes = [P(C.c_double), P(u64)]
+        L.rg_gather_batches.argtypes = [vp, vp, P(rg_features), u32, u32, vp, u64, u64, vp, vp, P(rg_gather_stats)]
         L.rg_classify_batch.argtypes = [vp, vp, P(rg_features), u32, vp, P(rg_gather_stats)]
         L.rg_schedule_build_blocks.argtypes = [vp, u64, vp]
         L.rg_schedule_block.argtypes = [vp, u32, P(vp)]
@@ -104,7 +105,7 @@ def lib():
                      "rg_cache_pair_create", "rg_cache_pair_begin_next", "rg_cache_pair_swap",
                      "rg_prefetcher_create", "rg_prefetcher_fill", "rg_prefetcher_acquire", "rg_prefetcher_release",
                      "rg_prefetcher_depth", "rg_schedule_build_blocks", "rg_schedule_block",
-           "rg_classify_batch", "rg_build_schedule_with"):
+           "rg_classify_batch", "rg_build_schedule_with", "rg_gather_batches"):
             getattr(L, name).restype = C.c_int32
         _lib = L
     return _lib
@@ -282,6 +283,24 @@ def rg_gather_batch(s, c, features, batch, out, out_stride=None, out_capacity_ro
                                  int(out_stride), int(out_capacity_rows), _stream_ptr(stream), side,
                                  C.byref(st) if want_stats else None))
     return dict(n_rows=st.n_rows, n_local=st.n_local, n_hit=st.n_hit, n_miss=st.n_miss) if want_stats else None
+
+
+def rg_gather_batches(s, c, features, first_batch, n_batches, out, out_stride=None, out_capacity_rows=None, stream=None,
+                      side_stream=None, want_stats=True):
+    """Blocks of batches [first_batch, first_batch + n_batches) back to back in `out`; returns the list of stats dicts."""
+    assert out.is_cuda and out.is_contiguous()
+    if out_stride is None:
+        out_stride = out.stride(0) * out.element_size()
+    if out_capacity_rows is None:
+        out_capacity_rows = out.numel() * out.element_size() // out_stride
+    st = (rg_gather_stats * max(int(n_batches), 1))()
+    side = _stream_ptr(side_stream) if side_stream is not None else None
+    _check(lib().rg_gather_batches(s.h, c.h if c is not None else None, C.byref(features), int(first_batch), int(n_batches),
+                                   C.c_void_p(out.data_ptr()), int(out_stride), int(out_capacity_rows), _stream_ptr(stream), side,
+                                   st if want_stats else None))
+    if not want_stats:
+        return None
+    return [dict(n_rows=x.n_rows, n_local=x.n_local, n_hit=x.n_hit, n_miss=x.n_miss) for x in st[:int(n_batches)]]
 
 
 def rg_classify_batch(s, c, features, batch, stream=None):

@@ -287,6 +287,81 @@ extern "C" rg_status rg_gather_batch(const rg_schedule *s, const rg_cache *c, co
     return RG_OK;
 }
 
+// Blocks of consecutive batches, back to back in one output buffer.  A schedule keeps the frontiers of its batches
+// concatenated, and so does a plan its routing entries: a range of batches is a range of rows, and one launch
+// copies it (fewer, larger launches: the ramp and tail of a launch are paid once per range, not once per batch).
+extern "C" rg_status rg_gather_batches(const rg_schedule *s, const rg_cache *c, const rg_features *f, uint32_t first_batch,
+                                       uint32_t n_batches, void *out, uint64_t out_stride, uint64_t out_capacity_rows, void *stream,
+                                       void *side_stream, rg_gather_stats *stats)
+{
+    if (!s || !f) { set_error("rg_gather_batches: null schedule or features"); return RG_EINVAL; }
+    if ((uint64_t)first_batch + n_batches > s->n_batches) {
+        set_error("rg_gather_batches: batches [%u, %u + %u) beyond n_batches = %u", first_batch, first_batch, n_batches, s->n_batches);
+        return RG_ERANGE;
+    }
+    if (n_batches == 0) return RG_OK;
+    const HopData &h = s->hop[s->L];
+    const int64_t off0 = h.off_host[first_batch];
+    const int64_t m = h.off_host[first_batch + n_batches] - off0;
+    if ((uint64_t)m > out_capacity_rows) {
+        set_error("rg_gather_batches: %u batches from %u have %lld rows, output holds %llu", n_batches, first_batch, (long long)m,
+                  (unsigned long long)out_capacity_rows);
+        return RG_ERANGE;
+    }
+    const Plan *plan = nullptr;
+    if (c)
+        for (const Plan &p : c->plans)
+            if (p.schedule_uid == s->uid) { plan = &p; break; }
+    if (!plan || n_batches == 1) {
+        // no prepared routing for this schedule: batch by batch (each call classifies on the fly and waits for its counts)
+        for (uint32_t k = 0; k < n_batches; ++k) {
+            const uint32_t b = first_batch + k;
+            const int64_t at = h.off_host[b] - off0;
+            RG_TRY(rg_gather_batch(s, c, f, b, (uint8_t *)out + (uint64_t)at * out_stride, out_stride, out_capacity_rows - (uint64_t)at, stream,
+                                   side_stream, stats ? stats + k : nullptr));
+        }
+        return RG_OK;
+    }
+    if (f->row_bytes == 0 || out_stride < f->row_bytes || f->local_stride < f->row_bytes || f->remote_stride < f->row_bytes) {
+        set_error("rg_gather_batches: row_bytes = %u with strides out %llu local %llu remote %llu", f->row_bytes,
+                  (unsigned long long)out_stride, (unsigned long long)f->local_stride, (unsigned long long)f->remote_stride);
+        return RG_EINVAL;
+    }
+    if (c->n_nodes != s->n_nodes || c->row_bytes != f->row_bytes) { set_error("rg_gather_batches: cache does not match schedule / features"); return RG_EINVAL; }
+    if (m > 0 && !out) { set_error("rg_gather_batches: null output"); return RG_EINVAL; }
+    hipStream_t st = as_stream(stream);
+    hipStream_t side = side_stream ? as_stream(side_stream) : st;
+    RowSources src{(const uint8_t *)f->local_rows, f->local_stride, (const uint8_t *)c->rows, c->stride, (const uint8_t *)f->remote_rows, f->remote_stride};
+    const int64_t n_miss = plan->miss_off[first_batch + n_batches] - plan->miss_off[first_batch];
+    const int64_t *entries = plan->entry + off0;
+    const bool remote_in_hbm = n_miss > 0 && (f->remote_rows == c->remote_rows_seen ? c->remote_is_device : is_device_memory(f->remote_rows));
+    if (n_miss == 0 || remote_in_hbm) {
+        RG_TRY(launch_gather(entries, m, nullptr, 0, 1, src, f->row_bytes, (uint8_t *)out, out_stride, st, KG_GATHER));
+    } else {
+        // rows with HBM sources in one launch; every batch's miss list (row indices within its own block) in a launch of its own
+        if (side != st) {
+            RG_HIP(hipEventRecord(c->ev_fork, st));
+            RG_HIP(hipStreamWaitEvent(side, c->ev_fork, 0));
+        }
+        RG_TRY(launch_gather(entries, m, nullptr, 0, 0, src, f->row_bytes, (uint8_t *)out, out_stride, st, KG_GATHER));
+        for (uint32_t k = 0; k < n_batches; ++k) {
+            const uint32_t b = first_batch + k;
+            const int64_t nm = plan->miss_off[b + 1] - plan->miss_off[b];
+            if (nm == 0) continue;
+            const int64_t at = h.off_host[b] - off0, mb = h.off_host[b + 1] - h.off_host[b];
+            RG_TRY(launch_gather(plan->entry + h.off_host[b], mb, plan->miss_rows + plan->miss_off[b], nm, 1, src, f->row_bytes,
+                                 (uint8_t *)out + (uint64_t)at * out_stride, out_stride, side, KG_MISS));
+        }
+        if (side != st) {
+            RG_HIP(hipEventRecord(c->ev_join, side));
+            RG_HIP(hipStreamWaitEvent(st, c->ev_join, 0));
+        }
+    }
+    if (stats)
+        for (uint32_t k = 0; k < n_batches; ++k) stats[k] = plan->stats[first_batch + k];
+    return RG_OK;
+}
+
 // The batch's counts alone: a9 without the copy (Alg. 1 inner loop, rpc_e += |M_i^e|).
 extern "C" rg_status rg_classify_batch(const rg_schedule *s, const rg_cache *c, const rg_features *f, uint32_t batch, void *stream,
                                        rg_gather_stats *stats)

@@ -95,6 +95,22 @@ def test_medium_whole_epoch(rg, orc):
         got = host(out)[: ref.size].reshape(ref.shape)
         assert np.array_equal(got[:, :W.row_bytes], ref[:, :W.row_bytes]), f"gathered rows of batch {b}"
         assert st == orc.batch_stats(o, b, is_local, slot)
+    # the launch shape the benchmark times: eight batches per launch, staged back to back
+    G = 8
+    for first in (0, 144):                                      # a whole group and the ragged last one
+        n = min(G, s.n_batches - first)
+        rows = int(off[first + n] - off[first])
+        big = torch.empty(rows * W.stride_bytes, dtype=torch.uint8, device="cuda")
+        stats = rg.rg_gather_batches(s, c, feat, first, n, big, out_stride=W.stride_bytes, out_capacity_rows=rows, side_stream=side)
+        torch.cuda.synchronize()
+        got = host(big).reshape(rows, W.stride_bytes)
+        for k in range(n):
+            b = first + k
+            ref = orc.gather_batch(o, b, ofeat, out_stride=W.stride_bytes)
+            at = int(off[b] - off[first])
+            assert np.array_equal(got[at:at + ref.shape[0], :W.row_bytes], ref[:, :W.row_bytes]), f"group at {first}, batch {b}"
+            assert stats[k] == orc.batch_stats(o, b, is_local, slot)
+        del big
 
 
 @pytest.mark.parametrize("name,batches", [("large_sparse", (0, 97, 195)), ("fanout_stress", (0, 48)), ("partition_share", (0, 146))])

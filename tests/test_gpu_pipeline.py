@@ -242,3 +242,37 @@ def test_classification_alone_matches_the_oracle_and_the_sweep_law(case, rg, orc
             fresh += sum(orc.batch_stats(o, b, is_local, slots[e])["n_miss"] for b in range(o.n_batches))
         stale = sum(orc.batch_stats(os_[1], b, is_local, slots[0])["n_miss"] for b in range(os_[1].n_batches))
         assert row["fetches_per_epoch"] == fresh / 2 and row["fetches_per_epoch_stale_cache"] == stale
+
+
+@pytest.mark.parametrize("planned", [True, False])
+def test_ranges_of_batches_gathered_back_to_back(case, rg, orc, planned):
+    """rg_gather_batches: same bytes and stats as one call per batch, blocks packed at the schedule's row offsets."""
+    w = case.w
+    nb = case.gsched.n_batches
+    cache = rg.rg_build_cache([case.gsched], case.gfeat, w.K) if planned else None
+    _, slot = oracle_cache(orc, case, case.osched) if planned else (None, None)
+    _, off = case.osched.input_nodes()
+    out_stride = w.row_bytes + 4
+    side = torch.cuda.Stream()
+    for first, n in ((0, nb), (1, min(3, nb - 1)), (nb - 1, 1), (2, 0)):
+        rows = int(off[first + n] - off[first])
+        out = torch.full(((rows + 2) * out_stride,), 0xCD, dtype=torch.uint8, device="cuda")
+        stats = rg.rg_gather_batches(case.gsched, cache, case.gfeat, first, n, out, out_stride=out_stride, out_capacity_rows=rows + 2,
+                                     side_stream=side)
+        torch.cuda.synchronize()
+        got = out.cpu().numpy().reshape(rows + 2, out_stride)
+        assert len(stats) == n
+        for k in range(n):
+            b = first + k
+            ref = orc.gather_batch(case.osched, b, case.ofeat, out_stride=out_stride, fill=0xCD)
+            at = int(off[b] - off[first])
+            assert np.array_equal(got[at:at + ref.shape[0]], ref), f"range ({first}, {n}) batch {b}"
+            assert stats[k] == orc.batch_stats(case.osched, b, w.is_local.numpy(), slot)
+        assert np.all(got[rows:] == 0xCD), "rows beyond the range were written"
+    with pytest.raises(rg.RgError) as e:
+        rg.rg_gather_batches(case.gsched, cache, case.gfeat, nb - 1, 2, out, out_stride=out_stride, out_capacity_rows=10 ** 9)
+    assert e.value.status == rg.RG_ERANGE
+    small = torch.empty(8 * out_stride, dtype=torch.uint8, device="cuda")
+    with pytest.raises(rg.RgError) as e:
+        rg.rg_gather_batches(case.gsched, cache, case.gfeat, 0, nb, small, out_stride=out_stride, out_capacity_rows=8)
+    assert e.value.status == rg.RG_ERANGE
