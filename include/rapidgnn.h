@@ -96,6 +96,9 @@ typedef struct rg_cache rg_cache;
  *   a            allocator or NULL
  *   out          receives the handle
  * Scratch: two bitmaps of n_batches * n_nodes bits for the duration of the call.
+ * Environment: RAPIDGNN_SPARSE_FRONTIER=1 / 0 forces / forbids the frontier
+ * passes tuned for graphs of 10^7 nodes and more (default: chosen from
+ * n_nodes); the result is the same either way.
  */
 rg_status rg_build_schedule(const rg_graph *g, const int32_t *train_nodes, uint64_t T,
                             uint32_t batch_size, const uint32_t *fanout, uint32_t L,

@@ -265,7 +265,7 @@ extern "C" rg_status rg_gather_batch(const rg_schedule *s, const rg_cache *c, co
     }
 
     // No prepared plan: classify this batch now, copy every row on `stream`, wait for the counts.
-    Arena tmp(nullptr);
+    Arena tmp(s->arena.allocator());     // scratch from the allocator the schedule was built with
     int64_t *entry = nullptr;
     unsigned long long *counts = nullptr;
     RG_TRY(tmp.dev_n<int64_t>((uint64_t)m, &entry));
@@ -375,7 +375,7 @@ extern "C" rg_status rg_classify_batch(const rg_schedule *s, const rg_cache *c, 
     const HopData &h = s->hop[s->L];
     const int64_t off = h.off_host[batch], m = h.off_host[batch + 1] - off;
     hipStream_t st = as_stream(stream);
-    Arena tmp(nullptr);
+    Arena tmp(s->arena.allocator());     // scratch from the allocator the schedule was built with
     int64_t *entry = nullptr;
     unsigned long long *counts = nullptr;
     RG_TRY(tmp.dev_n<int64_t>((uint64_t)m, &entry));

@@ -50,6 +50,8 @@ class Arena {
     void free_one(void *p);     // early release of a single buffer
     void release_all();
     uint64_t bytes_in_use() const { return in_use_; }
+    // The allocator this arena draws from (NULL = the library's own), for scratch that should come from the same place.
+    const rg_allocator *allocator() const { return custom_ ? &a_ : nullptr; }
 
   private:
     struct Item { void *p; int kind; uint64_t bytes; };

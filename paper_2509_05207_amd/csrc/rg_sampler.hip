@@ -134,7 +134,7 @@ __device__ __forceinline__ uint32_t kth_key_threshold(const uint32_t (&k)[E], co
 // sampled and written to out in row order.
 template <int E, bool MARK>
 __device__ __forceinline__ void sample_registers(const uint32_t (&u)[E], int len, int f, uint32_t lo, uint32_t hi, int lane,
-                                                 int32_t *__restrict__ out, uint32_t *__restrict__ reached_b)
+                                                 int32_t *__restrict__ out, const ReachedOfBatch &reached_b)
 {
     len = uni(len); f = uni(f); lo = uni(lo); hi = uni(hi);
     uint32_t k[E];
@@ -383,7 +383,7 @@ __device__ __forceinline__ void sample_long_row(const int32_t *__restrict__ row,
 // `first` holds row[lane] for lane < len.
 template <int CAP, bool MARK>
 __device__ __forceinline__ void sample_row(const int32_t *__restrict__ row, int len, uint32_t first, int f, uint32_t lo, uint32_t hi, int lane,
-                                           uint32_t *buf, int32_t *__restrict__ out, uint32_t *__restrict__ reached_b)
+                                           uint32_t *buf, int32_t *__restrict__ out, const ReachedOfBatch &reached_b)
 {
     if (len <= 64) {
         const uint32_t u[1] = {first};
@@ -412,7 +412,7 @@ struct HopArgs {
     uint32_t fanout;
     const int64_t *samp_off; int32_t *samp_nbr;
     const int64_t *tile_off; int64_t n_tiles; int32_t *tile_out;      // tile j writes tile_out[j * fanout ..)
-    uint32_t *reached; uint64_t words_per_batch;
+    ReachedMaps reached;
     unsigned long long *next_work;                                     // work items are handed out in order through this counter
 };
 
@@ -458,7 +458,7 @@ __global__ void __launch_bounds__(64) sample_kernel(HopArgs a)
             const uint64_t S = a.rec.state[i];
             const int32_t *row = a.indices + row_begin + first_pos;
             sample_row<CAP, false>(row, (int)(last_pos - first_pos), (uint32_t)row[lane], f, (uint32_t)S, (uint32_t)(S >> 32), lane, buf,
-                                   a.tile_out + w * f, nullptr);
+                                   a.tile_out + w * f, ReachedOfBatch{nullptr, nullptr});
             continue;
         }
         const int64_t i_lane = ((w - a.n_tiles) << 6) + lane;
@@ -487,7 +487,7 @@ __global__ void __launch_bounds__(64) sample_kernel(HopArgs a)
                 first = lane < deg ? (uint32_t)a.indices[rb + lane] : 0u;
             }
             const uint32_t b = (uint32_t)__builtin_amdgcn_readlane((int)b_lane, cl);
-            uint32_t *reached_b = a.reached + (uint64_t)b * a.words_per_batch;
+            const ReachedOfBatch reached_b = reached_of(a.reached, b);
             const int32_t *row = a.indices + crb;
             int32_t *out = a.samp_nbr + bcast64(out_lane, cl);
             if (cdeg <= f) {                  // the whole row is the sample
@@ -522,7 +522,7 @@ __global__ void __launch_bounds__(64) sample_merge_kernel(HopArgs a)
         const int32_t *row = a.tile_out + w * f;
         const int len = (int)(T * f);
         sample_row<CAP, true>(row, len, lane < len ? (uint32_t)row[lane] : 0u, f, (uint32_t)S, (uint32_t)(S >> 32), lane, buf,
-                              a.samp_nbr + a.samp_off[i], a.reached + (uint64_t)b * a.words_per_batch);
+                              a.samp_nbr + a.samp_off[i], reached_of(a.reached, b));
     }
 }
 
@@ -539,7 +539,7 @@ static void launch_hop(const HopArgs &a, unsigned grid, unsigned merge_grid, hip
 constexpr int POS_THREADS = 256;
 __global__ void __launch_bounds__(POS_THREADS) sample_positions_kernel(const int32_t *__restrict__ indices, NodeRecs rec, int64_t n_cur, uint32_t f,
                                                                        const int64_t *__restrict__ samp_off, int32_t *__restrict__ samp_nbr,
-                                                                       uint32_t *__restrict__ reached, uint64_t words_per_batch)
+                                                                       ReachedMaps reached)
 {
     const uint32_t per_round = f >= POS_THREADS ? 1u : POS_THREADS / f;       // nodes per workgroup round
     const uint32_t sub = f >= POS_THREADS ? 0u : threadIdx.x / f;              // this lane's node within the round
@@ -553,7 +553,7 @@ __global__ void __launch_bounds__(POS_THREADS) sample_positions_kernel(const int
         const int32_t *row = indices + rec.row_begin[i];
         const uint64_t S = rec.state[i];
         int32_t *out = samp_nbr + samp_off[i];
-        uint32_t *reached_b = reached + (uint64_t)rec.batch[i] * words_per_batch;
+        const ReachedOfBatch reached_b = reached_of(reached, rec.batch[i]);
         for (uint32_t t = t0; t < cnt; t += step) {
             const uint32_t p = deg <= f ? t : draw_position(deg, t, S);
             const int32_t u = row[p];
@@ -565,7 +565,7 @@ __global__ void __launch_bounds__(POS_THREADS) sample_positions_kernel(const int
 
 // Samples hop `hop` of every batch: fills cur.samp_off / samp_nbr / n_samples and marks the reached-ID bitmaps.
 rg_status sample_hop(const rg_graph *g, HopData &cur, uint32_t beta, const uint64_t *batch_seed, uint32_t hop, uint32_t fanout,
-                     uint32_t sampler, uint32_t *reached, uint64_t words_per_batch, Arena &keep, Arena &tmp, int n_cu, hipStream_t st)
+                     uint32_t sampler, const ReachedMaps &reached, Arena &keep, Arena &tmp, int n_cu, hipStream_t st)
 {
     const int64_t n_cur = cur.off_host[beta];
     int32_t *cnt = nullptr, *tiles = nullptr;
@@ -599,7 +599,7 @@ rg_status sample_hop(const rg_graph *g, HopData &cur, uint32_t beta, const uint6
             const int64_t per_round = fanout >= (uint32_t)POS_THREADS ? 1 : POS_THREADS / fanout;
             const unsigned grid = (unsigned)std::max<int64_t>(1, std::min<int64_t>((n_cur + per_round - 1) / per_round, (int64_t)n_cu * 64));
             hipLaunchKernelGGL(sample_positions_kernel, dim3(grid), dim3(POS_THREADS), 0, st, g->indices, rec, n_cur, fanout, cur.samp_off, cur.samp_nbr,
-                               reached, words_per_batch);
+                               reached);
             RG_HIP(hipGetLastError());
         }
         return RG_OK;
@@ -612,7 +612,7 @@ rg_status sample_hop(const rg_graph *g, HopData &cur, uint32_t beta, const uint6
         unsigned long long *next_work = nullptr;
         RG_TRY(tmp.dev_n<unsigned long long>(1, &next_work));
         RG_HIP(hipMemsetAsync(next_work, 0, sizeof(unsigned long long), st));
-        HopArgs a{g->indices, cur.ids, n_cur, rec, fanout, cur.samp_off, cur.samp_nbr, tile_off, n_tiles, tile_out, reached, words_per_batch, next_work};
+        HopArgs a{g->indices, cur.ids, n_cur, rec, fanout, cur.samp_off, cur.samp_nbr, tile_off, n_tiles, tile_out, reached, next_work};
         ScopedTimer tm(KG_SAMPLER, st);
         const int64_t n_work = n_tiles + (n_cur + 63) / 64;
         const unsigned grid = (unsigned)std::max<int64_t>(1, std::min<int64_t>(n_work, (int64_t)n_cu * 32));     // as many waves as fit on the chip

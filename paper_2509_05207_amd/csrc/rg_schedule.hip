@@ -12,13 +12,15 @@
 #include "rg_internal.h"
 #include "rg_device.h"
 
+#include <cstdlib>
+
 #include <algorithm>
 #include <atomic>
 
 namespace rg {
 
 rg_status sample_hop(const rg_graph *g, HopData &cur, uint32_t beta, const uint64_t *batch_seed, uint32_t hop, uint32_t fanout, uint32_t sampler,
-                     uint32_t *reached, uint64_t words_per_batch, Arena &keep, Arena &tmp, int n_cu, hipStream_t st);
+                     const ReachedMaps &reached, Arena &keep, Arena &tmp, int n_cu, hipStream_t st);
 
 // ---------------------------------------------------------------- a1/a2: seeds, shuffle keys
 __global__ void batch_seeds_kernel(uint64_t s0, uint32_t worker, uint32_t epoch, uint32_t n_batches, uint64_t *__restrict__ seeds)
@@ -114,17 +116,18 @@ constexpr int FR_WORDS_PER_THREAD = 8;
 constexpr int FR_CHUNK_WORDS = FR_THREADS * FR_WORDS_PER_THREAD;     // 2048 words = 65536 node IDs per block
 
 // cnt[b * chunks + c] = number of fresh IDs (reached and not yet seen) of batch b in chunk c
-__global__ void __launch_bounds__(FR_THREADS) fresh_count_kernel(const uint32_t *__restrict__ reached, const uint32_t *__restrict__ seen,
-                                                                 uint64_t words_per_batch, uint32_t chunks, int32_t *__restrict__ cnt)
+__global__ void __launch_bounds__(FR_THREADS) fresh_count_kernel(const uint32_t *__restrict__ reached, const uint8_t *__restrict__ flags,
+                                                                 const uint32_t *__restrict__ seen, uint64_t words_per_batch, uint32_t chunks,
+                                                                 int32_t *__restrict__ cnt)
 {
     __shared__ int red[FR_THREADS / 64];
     const uint32_t c = blockIdx.x, b = blockIdx.y;
     const uint64_t w0 = (uint64_t)c * FR_CHUNK_WORDS + (uint64_t)threadIdx.x * FR_WORDS_PER_THREAD;
     int n = 0;
-    if (w0 < words_per_batch) {      // words_per_batch is a multiple of FR_WORDS_PER_THREAD
+    if (w0 < words_per_batch) {      // words_per_batch is a multiple of FR_WORDS_PER_THREAD; a thread's words are one flag's group
         const uint64_t at = (uint64_t)b * words_per_batch + w0;
-        const uint4 r0 = *reinterpret_cast<const uint4 *>(reached + at), r1 = *reinterpret_cast<const uint4 *>(reached + at + 4);
-        if ((r0.x | r0.y | r0.z | r0.w | r1.x | r1.y | r1.z | r1.w) != 0u) {      // on big graphs most words were not reached: `seen` stays unread
+        if (flags[at >> 3]) {        // on big graphs most groups were not reached: neither bitmap is read there
+            const uint4 r0 = *reinterpret_cast<const uint4 *>(reached + at), r1 = *reinterpret_cast<const uint4 *>(reached + at + 4);
             const uint4 s0 = *reinterpret_cast<const uint4 *>(seen + at), s1 = *reinterpret_cast<const uint4 *>(seen + at + 4);
             n = __popc(r0.x & ~s0.x) + __popc(r0.y & ~s0.y) + __popc(r0.z & ~s0.z) + __popc(r0.w & ~s0.w) +
                 __popc(r1.x & ~s1.x) + __popc(r1.y & ~s1.y) + __popc(r1.z & ~s1.z) + __popc(r1.w & ~s1.w);
@@ -155,8 +158,8 @@ __global__ void copy_prefix_kernel(const int32_t *__restrict__ cur, const int64_
 
 // Writes the fresh IDs of (batch, chunk) in ascending order behind the batch's old frontier, adds
 // the reached IDs to `seen` and clears `reached` for the next hop.
-__global__ void __launch_bounds__(FR_THREADS) fresh_emit_kernel(uint32_t *__restrict__ reached, uint32_t *__restrict__ seen, uint64_t words_per_batch,
-                                                                uint32_t chunks, const int64_t *__restrict__ fresh_scan,
+__global__ void __launch_bounds__(FR_THREADS) fresh_emit_kernel(uint32_t *__restrict__ reached, uint8_t *__restrict__ flags, uint32_t *__restrict__ seen,
+                                                                uint64_t words_per_batch, uint32_t chunks, const int64_t *__restrict__ fresh_scan,
                                                                 const int64_t *__restrict__ cur_off, int32_t *__restrict__ next)
 {
     __shared__ int wave_tot[FR_THREADS / 64];
@@ -168,8 +171,8 @@ __global__ void __launch_bounds__(FR_THREADS) fresh_emit_kernel(uint32_t *__rest
     int n = 0;
     if (w0 < words_per_batch) {
         const uint64_t at = (uint64_t)b * words_per_batch + w0;
-        const uint4 r0 = *reinterpret_cast<const uint4 *>(reached + at), r1 = *reinterpret_cast<const uint4 *>(reached + at + 4);
-        if ((r0.x | r0.y | r0.z | r0.w | r1.x | r1.y | r1.z | r1.w) != 0u) {
+        if (flags[at >> 3]) {
+            const uint4 r0 = *reinterpret_cast<const uint4 *>(reached + at), r1 = *reinterpret_cast<const uint4 *>(reached + at + 4);
             const uint4 s0 = *reinterpret_cast<const uint4 *>(seen + at), s1 = *reinterpret_cast<const uint4 *>(seen + at + 4);
             w[0] = r0.x & ~s0.x; w[1] = r0.y & ~s0.y; w[2] = r0.z & ~s0.z; w[3] = r0.w & ~s0.w;
             w[4] = r1.x & ~s1.x; w[5] = r1.y & ~s1.y; w[6] = r1.z & ~s1.z; w[7] = r1.w & ~s1.w;
@@ -181,6 +184,7 @@ __global__ void __launch_bounds__(FR_THREADS) fresh_emit_kernel(uint32_t *__rest
             }
             *reinterpret_cast<uint4 *>(reached + at) = make_uint4(0, 0, 0, 0);
             *reinterpret_cast<uint4 *>(reached + at + 4) = make_uint4(0, 0, 0, 0);
+            flags[at >> 3] = 0;
         }
     }
     if (!any_fresh) return;
@@ -207,6 +211,111 @@ __global__ void __launch_bounds__(FR_THREADS) fresh_emit_kernel(uint32_t *__rest
             next[pos++] = (int32_t)(id0 + bit);
         }
     }
+}
+
+// The same two passes for graphs so large that almost every group of a batch's bitmap is untouched (10^8 nodes:
+// a batch reaches a few 10^4 IDs out of 3.5 M words).  A thread owns eight consecutive groups, i.e. one 8-byte
+// load of flags; a cell is 16,384 words, so the grid is eight times smaller and an untouched cell costs one
+// flag load per thread.  Flagged groups are read twice (count, then emit): they are few.
+constexpr int FRS_GROUPS = 8;                                            // groups per thread
+constexpr int FRS_WORDS_PER_THREAD = FR_WORDS_PER_THREAD * FRS_GROUPS;   // 64
+constexpr int FRS_CHUNK_WORDS = FR_THREADS * FRS_WORDS_PER_THREAD;       // 16384; words_per_batch is a multiple of 64
+
+__device__ __forceinline__ int fresh_in_group(const uint32_t *__restrict__ reached, const uint32_t *__restrict__ seen, uint64_t at, uint32_t (&w)[8])
+{
+    const uint4 r0 = *reinterpret_cast<const uint4 *>(reached + at), r1 = *reinterpret_cast<const uint4 *>(reached + at + 4);
+    const uint4 s0 = *reinterpret_cast<const uint4 *>(seen + at), s1 = *reinterpret_cast<const uint4 *>(seen + at + 4);
+    w[0] = r0.x & ~s0.x; w[1] = r0.y & ~s0.y; w[2] = r0.z & ~s0.z; w[3] = r0.w & ~s0.w;
+    w[4] = r1.x & ~s1.x; w[5] = r1.y & ~s1.y; w[6] = r1.z & ~s1.z; w[7] = r1.w & ~s1.w;
+    int n = 0;
+#pragma unroll
+    for (int k = 0; k < 8; ++k) n += __popc(w[k]);
+    return n;
+}
+
+__global__ void __launch_bounds__(FR_THREADS) fresh_count_sparse_kernel(const uint32_t *__restrict__ reached, const uint8_t *__restrict__ flags,
+                                                                        const uint32_t *__restrict__ seen, uint64_t words_per_batch,
+                                                                        uint32_t chunks, int32_t *__restrict__ cnt)
+{
+    __shared__ int red[FR_THREADS / 64];
+    const uint32_t c = blockIdx.x, b = blockIdx.y;
+    const uint64_t w0 = (uint64_t)c * FRS_CHUNK_WORDS + (uint64_t)threadIdx.x * FRS_WORDS_PER_THREAD;
+    int n = 0;
+    if (w0 < words_per_batch) {
+        const uint64_t at = (uint64_t)b * words_per_batch + w0;
+        const unsigned long long fl = *reinterpret_cast<const unsigned long long *>(flags + (at >> 3));
+        if (fl != 0ull) {
+            for (int g = 0; g < FRS_GROUPS; ++g)
+                if ((fl >> (8 * g)) & 0xFFull) {
+                    uint32_t w[8];
+                    n += fresh_in_group(reached, seen, at + 8 * g, w);
+                }
+        }
+    }
+    for (int o = 32; o > 0; o >>= 1) n += __shfl_down(n, o, 64);
+    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = n;
+    __syncthreads();
+    if (threadIdx.x == 0) cnt[(uint64_t)b * chunks + c] = red[0] + red[1] + red[2] + red[3];
+}
+
+__global__ void __launch_bounds__(FR_THREADS) fresh_emit_sparse_kernel(uint32_t *__restrict__ reached, uint8_t *__restrict__ flags,
+                                                                       uint32_t *__restrict__ seen, uint64_t words_per_batch, uint32_t chunks,
+                                                                       const int64_t *__restrict__ fresh_scan, const int64_t *__restrict__ cur_off,
+                                                                       int32_t *__restrict__ next)
+{
+    __shared__ int wave_tot[FR_THREADS / 64];
+    const uint32_t c = blockIdx.x, b = blockIdx.y;
+    const int64_t scan_here = fresh_scan[(uint64_t)b * chunks + c];
+    const bool any_fresh = fresh_scan[(uint64_t)b * chunks + c + 1] != scan_here;      // block-uniform
+    const uint64_t w0 = (uint64_t)c * FRS_CHUNK_WORDS + (uint64_t)threadIdx.x * FRS_WORDS_PER_THREAD;
+    const bool mine = w0 < words_per_batch;
+    const uint64_t at = (uint64_t)b * words_per_batch + w0;
+    const unsigned long long fl = mine ? *reinterpret_cast<const unsigned long long *>(flags + (at >> 3)) : 0ull;
+    int n = 0;
+    if (any_fresh && fl != 0ull) {
+        for (int g = 0; g < FRS_GROUPS; ++g)
+            if ((fl >> (8 * g)) & 0xFFull) {
+                uint32_t w[8];
+                n += fresh_in_group(reached, seen, at + 8 * g, w);
+            }
+    }
+    int before = 0;
+    if (any_fresh) {                          // exclusive scan of n over the block
+        const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+        int incl = n;
+        for (int d = 1; d < 64; d <<= 1) {
+            const int y = __shfl_up(incl, d, 64);
+            if (lane >= d) incl += y;
+        }
+        if (lane == 63) wave_tot[wave] = incl;
+        __syncthreads();
+        before = incl - n;
+        for (int k = 0; k < wave; ++k) before += wave_tot[k];
+    }
+    if (fl == 0ull) return;
+    int64_t pos = cur_off[b + 1] + scan_here + before;
+    for (int g = 0; g < FRS_GROUPS; ++g) {
+        if (!((fl >> (8 * g)) & 0xFFull)) continue;
+        const uint64_t ag = at + 8 * g;
+        uint32_t w[8];
+        const int ng = fresh_in_group(reached, seen, ag, w);
+        if (ng) {
+#pragma unroll
+            for (int k = 0; k < 8; ++k) {
+                uint32_t x = w[k];
+                const uint32_t id0 = (uint32_t)((w0 + 8 * g + k) << 5);
+                while (x) {
+                    const int bit = __ffs((int)x) - 1;
+                    x &= x - 1;
+                    next[pos++] = (int32_t)(id0 + bit);
+                }
+                seen[ag + k] |= w[k];
+            }
+        }
+        *reinterpret_cast<uint4 *>(reached + ag) = make_uint4(0, 0, 0, 0);
+        *reinterpret_cast<uint4 *>(reached + ag + 4) = make_uint4(0, 0, 0, 0);
+    }
+    *reinterpret_cast<unsigned long long *>(flags + (at >> 3)) = 0ull;
 }
 
 static std::atomic<uint64_t> g_next_uid{1};
@@ -278,13 +387,20 @@ static rg_status build_schedule_impl(const rg_graph *g, const int32_t *train, ui
     if (L == 0 || beta == 0) { RG_HIP(hipStreamSynchronize(st)); return RG_OK; }
 
     // ---- bitmaps (n_nodes bits per batch, rounded up to whole 8-word groups)
-    const uint64_t wpb = (((uint64_t)g->n_nodes + 31) / 32 + FR_WORDS_PER_THREAD - 1) / FR_WORDS_PER_THREAD * FR_WORDS_PER_THREAD;
-    const uint32_t chunks = (uint32_t)((wpb + FR_CHUNK_WORDS - 1) / FR_CHUNK_WORDS);
+    const uint64_t wpb = (((uint64_t)g->n_nodes + 31) / 32 + FRS_WORDS_PER_THREAD - 1) / FRS_WORDS_PER_THREAD * FRS_WORDS_PER_THREAD;
+    bool sparse_maps = wpb >= (uint64_t)FRS_CHUNK_WORDS * 16;                // 8.4 M nodes and up: a batch leaves most groups untouched
+    if (const char *force = getenv("RAPIDGNN_SPARSE_FRONTIER")) sparse_maps = force[0] == '1';   // same results either way; for tests and tuning
+    const uint32_t chunk_words = sparse_maps ? FRS_CHUNK_WORDS : FR_CHUNK_WORDS;
+    const uint32_t chunks = (uint32_t)((wpb + chunk_words - 1) / chunk_words);
     uint32_t *seen = nullptr, *reached = nullptr;
+    uint8_t *reached_flags = nullptr;                  // one byte per 8-word group of `reached`
     RG_TRY(tmp.dev_n<uint32_t>(wpb * beta, &seen));
     RG_TRY(tmp.dev_n<uint32_t>(wpb * beta, &reached));
+    RG_TRY(tmp.dev_n<uint8_t>(wpb / FR_WORDS_PER_THREAD * beta, &reached_flags));
     RG_HIP(hipMemsetAsync(seen, 0, wpb * beta * sizeof(uint32_t), st));
     RG_HIP(hipMemsetAsync(reached, 0, wpb * beta * sizeof(uint32_t), st));
+    RG_HIP(hipMemsetAsync(reached_flags, 0, wpb / FR_WORDS_PER_THREAD * beta, st));
+    const ReachedMaps maps{reached, reached_flags, wpb};
     {
         ScopedTimer tm(KG_FRONTIER, st);
         hipLaunchKernelGGL(mark_seeds_kernel, dim3((unsigned)((T + 255) / 256)), dim3(256), 0, st, h0.ids, T, B, seen, wpb);
@@ -305,13 +421,16 @@ static rg_status build_schedule_impl(const rg_graph *g, const int32_t *train, ui
         const int64_t n_cur = cur.off_host[beta];
 
         // a3: the samples of this hop; sampled IDs are marked in `reached` as they are written
-        RG_TRY(sample_hop(g, cur, beta, batch_seed, l, fanout[l], sampler, reached, wpb, s->arena, tmp, n_cu, st));
+        RG_TRY(sample_hop(g, cur, beta, batch_seed, l, fanout[l], sampler, maps, s->arena, tmp, n_cu, st));
 
         // a4: fresh IDs per (batch, chunk) -> positions -> next frontier
         RG_TRY(s->arena.dev_n<int64_t>((uint64_t)beta + 1, &nxt.off_dev));
         {
             ScopedTimer tm(KG_FRONTIER, st);
-            hipLaunchKernelGGL(fresh_count_kernel, dim3(chunks, beta), dim3(FR_THREADS), 0, st, reached, seen, wpb, chunks, fresh_cnt);
+            if (sparse_maps)
+                hipLaunchKernelGGL(fresh_count_sparse_kernel, dim3(chunks, beta), dim3(FR_THREADS), 0, st, reached, reached_flags, seen, wpb, chunks, fresh_cnt);
+            else
+                hipLaunchKernelGGL(fresh_count_kernel, dim3(chunks, beta), dim3(FR_THREADS), 0, st, reached, reached_flags, seen, wpb, chunks, fresh_cnt);
             RG_TRY(scan_i32_to_i64(fresh_cnt, fresh_scan, (int64_t)n_cells, tmp, st));
             hipLaunchKernelGGL(next_offsets_kernel, dim3((beta + 1 + 255) / 256), dim3(256), 0, st, cur.off_dev, fresh_scan, beta, chunks, nxt.off_dev);
         }
@@ -323,7 +442,10 @@ static rg_status build_schedule_impl(const rg_graph *g, const int32_t *train, ui
         {
             ScopedTimer tm(KG_FRONTIER, st);
             hipLaunchKernelGGL(copy_prefix_kernel, dim3((unsigned)((n_cur + 255) / 256)), dim3(256), 0, st, cur.ids, cur.off_dev, nxt.off_dev, beta, n_cur, nxt.ids);
-            hipLaunchKernelGGL(fresh_emit_kernel, dim3(chunks, beta), dim3(FR_THREADS), 0, st, reached, seen, wpb, chunks, fresh_scan, cur.off_dev, nxt.ids);
+            if (sparse_maps)
+                hipLaunchKernelGGL(fresh_emit_sparse_kernel, dim3(chunks, beta), dim3(FR_THREADS), 0, st, reached, reached_flags, seen, wpb, chunks, fresh_scan, cur.off_dev, nxt.ids);
+            else
+                hipLaunchKernelGGL(fresh_emit_kernel, dim3(chunks, beta), dim3(FR_THREADS), 0, st, reached, reached_flags, seen, wpb, chunks, fresh_scan, cur.off_dev, nxt.ids);
         }
         RG_HIP(hipGetLastError());
     }

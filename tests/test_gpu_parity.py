@@ -364,3 +364,14 @@ def test_unknown_sampler_is_refused(case, rg):
     with pytest.raises(rg.RgError) as e:
         rg.rg_build_schedule_with(case.indptr, case.indices, case.train, w.cfg.batch_size, w.cfg.fanout, 0, 0, 0, sampler=7)
     assert e.value.status == rg.RG_EINVAL
+
+
+@pytest.mark.parametrize("force", ["1", "0"])
+def test_both_frontier_variants_give_the_same_schedule(case, rg, force, monkeypatch):
+    """The frontier passes for very large graphs (eight flag groups per thread, two-pass emit) forced onto small ones."""
+    monkeypatch.setenv("RAPIDGNN_SPARSE_FRONTIER", force)
+    w = case.w
+    g = rg.rg_build_schedule(case.indptr, case.indices, case.train, w.cfg.batch_size, w.cfg.fanout, case.s0, case.worker, case.epoch)
+    assert_schedules_equal(rg, g, case.osched)
+    g2 = rg.rg_build_schedule(case.indptr, case.indices, case.train, w.cfg.batch_size, w.cfg.fanout, case.s0, case.worker, case.epoch)
+    assert_schedules_equal(rg, g2, case.osched)          # bitmaps and flags come back clean from the block cache
