@@ -196,21 +196,24 @@ __device__ __forceinline__ uint32_t batch_of_pos(const int64_t *__restrict__ off
     return lo;
 }
 
-// route[v] = (tag << 62) | row for every node ID: where a request for v's feature row is served from.
-__global__ void route_table_kernel(int64_t n, const uint8_t *__restrict__ is_local, const int32_t *__restrict__ row_of,
-                                   const int32_t *__restrict__ slot_of, int64_t *__restrict__ route)
+// Where a request for v's feature row is served from: (tag << 62) | row.
+struct RouteSources {
+    const uint8_t *is_local;
+    const int32_t *row_of;
+    const int32_t *slot_of;
+};
+__device__ __forceinline__ int64_t route_of(const RouteSources &r, int64_t v)
+{
+    if (r.is_local[v]) return make_entry(TAG_LOCAL, r.row_of[v]);
+    const int32_t slot = r.slot_of[v];
+    return slot >= 0 ? make_entry(TAG_CACHE, slot) : make_entry(TAG_REMOTE, r.row_of[v]);
+}
+
+// route[v] for every node ID: worth building when the epochs list far more input nodes than the graph has nodes.
+__global__ void route_table_kernel(int64_t n, RouteSources r, int64_t *__restrict__ route)
 {
     const int64_t stride = (int64_t)gridDim.x * blockDim.x;
-    for (int64_t v = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; v < n; v += stride) {
-        int64_t tag, row;
-        if (is_local[v]) { tag = TAG_LOCAL; row = row_of[v]; }
-        else {
-            const int32_t slot = slot_of[v];
-            if (slot >= 0) { tag = TAG_CACHE; row = slot; }
-            else { tag = TAG_REMOTE; row = row_of[v]; }
-        }
-        route[v] = make_entry(tag, row);
-    }
+    for (int64_t v = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; v < n; v += stride) route[v] = route_of(r, v);
 }
 
 // entry[j] = route[ids[j]] for every listed input node, the miss flag (for the miss-list scan) and
@@ -221,7 +224,8 @@ constexpr int PLAN_PER_THREAD = 4;
 constexpr int PLAN_TILE = PLAN_THREADS * PLAN_PER_THREAD;
 
 __global__ void __launch_bounds__(PLAN_THREADS) plan_kernel(const int32_t *__restrict__ ids, int64_t n, const int64_t *__restrict__ batch_off, uint32_t n_batches,
-                                                            const int64_t *__restrict__ route, int64_t *__restrict__ entry, int32_t *__restrict__ miss_flag,
+                                                            const int64_t *__restrict__ route /* or NULL: look the three arrays up */, RouteSources rs,
+                                                            int64_t *__restrict__ entry, int32_t *__restrict__ miss_flag,
                                                             unsigned long long *__restrict__ counts /* [n_batches][2]: local, hit */)
 {
     __shared__ unsigned int red[2][PLAN_THREADS / 64];
@@ -234,7 +238,7 @@ __global__ void __launch_bounds__(PLAN_THREADS) plan_kernel(const int32_t *__res
     for (int k = 0; k < PLAN_PER_THREAD; ++k) {
         const int64_t j = tile0 + (int64_t)k * PLAN_THREADS + threadIdx.x;
         if (j < n) {
-            const int64_t e = route[ids[j]];
+            const int64_t e = route ? route[ids[j]] : route_of(rs, ids[j]);
             const int64_t tag = entry_tag(e);
             entry[j] = e;
             miss_flag[j] = tag == TAG_REMOTE ? 1 : 0;
@@ -275,7 +279,7 @@ __global__ void miss_offsets_kernel(const int64_t *__restrict__ miss_scan, const
 
 // Routing entries, miss lists and counts of one schedule from the per-node route table.  What the
 // plan keeps lives in `keep`; scratch in `tmp`.
-rg_status build_plan(const rg_schedule *s, const int64_t *route, Arena &keep, Arena &tmp, hipStream_t st, Plan *plan)
+rg_status build_plan(const rg_schedule *s, const int64_t *route, const RouteSources &rs, Arena &keep, Arena &tmp, hipStream_t st, Plan *plan)
 {
     const uint32_t beta = s->n_batches;
     const HopData &h = s->hop[s->L];
@@ -298,7 +302,7 @@ rg_status build_plan(const rg_schedule *s, const int64_t *route, Arena &keep, Ar
         ScopedTimer tm(KG_PLAN, st);
         if (n > 0)
             hipLaunchKernelGGL(plan_kernel, dim3((unsigned)((n + PLAN_TILE - 1) / PLAN_TILE)), dim3(PLAN_THREADS), 0, st, h.ids, n, h.off_dev, beta,
-                               route, plan->entry, miss_flag, counts);
+                               route, rs, plan->entry, miss_flag, counts);
         RG_TRY(scan_i32_to_i64(miss_flag, miss_scan, n, tmp, st));
         hipLaunchKernelGGL(miss_offsets_kernel, dim3((beta + 1 + 255) / 256), dim3(256), 0, st, miss_scan, h.off_dev, beta, miss_off_dev);
     }
@@ -410,14 +414,17 @@ static rg_status build_cache_impl(const rg_schedule *const *epochs, uint32_t n_e
 
     // ---- a5/a9: plans, miss lists and counts for every batch of every epoch
     c->plans.resize(n_epochs);
+    const RouteSources rs{f->is_local, f->row_of, c->slot_of};
+    int64_t listed = 0;                                   // input nodes over all epochs
+    for (uint32_t e = 0; e < n_epochs; ++e) listed += epochs[e]->hop[epochs[e]->L].off_host[epochs[e]->n_batches];
     int64_t *route = nullptr;
-    RG_TRY(tmp.dev_n<int64_t>((uint64_t)n, &route));
-    if (n > 0) {
+    if (n > 0 && listed >= n / 4) {                       // else three lookups per listed node cost less than a pass over every node
+        RG_TRY(tmp.dev_n<int64_t>((uint64_t)n, &route));
         ScopedTimer tm(KG_PLAN, st);
         const unsigned grid = (unsigned)std::max<int64_t>(1, std::min<int64_t>((n + 255) / 256, (int64_t)n_cu * 16));
-        hipLaunchKernelGGL(route_table_kernel, dim3(grid), dim3(256), 0, st, n, f->is_local, f->row_of, c->slot_of, route);
+        hipLaunchKernelGGL(route_table_kernel, dim3(grid), dim3(256), 0, st, n, rs, route);
     }
-    for (uint32_t e = 0; e < n_epochs; ++e) RG_TRY(build_plan(epochs[e], route, c->arena, tmp, st, &c->plans[e]));
+    for (uint32_t e = 0; e < n_epochs; ++e) RG_TRY(build_plan(epochs[e], route, rs, c->arena, tmp, st, &c->plans[e]));
     RG_HIP(hipStreamSynchronize(st));
     return RG_OK;
 }

@@ -375,3 +375,29 @@ def test_both_frontier_variants_give_the_same_schedule(case, rg, force, monkeypa
     assert_schedules_equal(rg, g, case.osched)
     g2 = rg.rg_build_schedule(case.indptr, case.indices, case.train, w.cfg.batch_size, w.cfg.fanout, case.s0, case.worker, case.epoch)
     assert_schedules_equal(rg, g2, case.osched)          # bitmaps and flags come back clean from the block cache
+
+
+def test_few_listed_nodes_plan_without_the_route_table(case, rg, orc):
+    """An epoch that lists far fewer input nodes than the graph has nodes is planned by direct lookups."""
+    w = case.w
+    if w.n_nodes < 2000:
+        pytest.skip("needs a graph much larger than the epoch's input sets")
+    train = case.train[:20].contiguous()
+    fan = [3, 2]
+    o = orc.Schedule(w.indptr.numpy(), w.indices.numpy(), w.train.numpy()[:20], 7, fan, 5, 0, 0)
+    g = rg.rg_build_schedule(case.indptr, case.indices, train, 7, fan, 5, 0, 0)
+    assert_schedules_equal(rg, g, o)
+    _, off = o.input_nodes()
+    assert off[-1] < w.n_nodes // 4
+    freq = orc.frequency([o], w.n_nodes)
+    ids, slot = orc.top_hot(freq, w.is_local.numpy(), 5)
+    c = rg.rg_build_cache([g], case.gfeat, 5)
+    assert np.array_equal(rg.rg_cache_view(c, w.n_nodes)["cache_ids"].cpu().numpy(), ids)
+    m_max = int(np.diff(off).max())
+    out = torch.empty(m_max * w.row_bytes, dtype=torch.uint8, device="cuda")
+    for b in range(g.n_batches):
+        st = rg.rg_gather_batch(g, c, case.gfeat, b, out, out_stride=w.row_bytes, out_capacity_rows=m_max)
+        torch.cuda.synchronize()
+        ref = orc.gather_batch(o, b, case.ofeat, out_stride=w.row_bytes, fill=0)
+        assert np.array_equal(out.cpu().numpy()[:ref.size].reshape(ref.shape), ref)
+        assert st == orc.batch_stats(o, b, w.is_local.numpy(), slot)
