@@ -401,3 +401,47 @@ def test_few_listed_nodes_plan_without_the_route_table(case, rg, orc):
         ref = orc.gather_batch(o, b, case.ofeat, out_stride=w.row_bytes, fill=0)
         assert np.array_equal(out.cpu().numpy()[:ref.size].reshape(ref.shape), ref)
         assert st == orc.batch_stats(o, b, w.is_local.numpy(), slot)
+
+
+def test_rows_built_to_defeat_the_guessed_cut(rg, orc):
+    """Long rows are first streamed with a cut guessed from the key distribution.  Rows made of IDs whose keys (under
+    the node's own state) all lie above that cut, or with exactly f - 1, f and f + 1 keys below it, force the
+    fallback to the exact procedure and both sides of its trigger."""
+    n, f, deg = 20000, 10, 1500
+    s0, wk, ep = 21, 0, 3
+    specials = [11, 222, 3333, 4444]                     # seeds, all in batch 0 (one batch)
+    below = [0, f - 1, f, f + 1]                         # keys below the guessed cut in each special row
+    hs = orc.hop_state(orc.batch_seed(s0, wk, ep, 0), 0)
+    lam = f + 4.0 * np.sqrt(np.float32(f)) + 8.0
+    cut = int(np.float32(lam) / np.float32(deg) * np.float32(4294967296.0))
+    rng = np.random.default_rng(77)
+    rows = [np.unique(rng.integers(0, n, 6)).astype(np.int32) for _ in range(n)]
+    for v, nb in zip(specials, below):
+        S = orc.node_state(hs, v)
+        keys = np.array([orc.key32(S, u) for u in range(n)], dtype=np.uint64)
+        cand = np.arange(n)
+        cand = cand[cand != v]
+        lo_ids = cand[keys[cand] < cut // 2]             # safely below the cut
+        hi_ids = cand[keys[cand] > (1 << 31)]            # far above it
+        assert lo_ids.size >= nb and hi_ids.size >= deg
+        row = np.concatenate([rng.permutation(lo_ids)[:nb], rng.permutation(hi_ids)[:deg - nb]])
+        rows[v] = np.sort(row).astype(np.int32)
+    indptr = np.zeros(n + 1, np.int64)
+    indptr[1:] = np.cumsum([r.size for r in rows])
+    indices = np.concatenate(rows)
+    train = np.array(specials + [5, 6, 7], dtype=np.int32)
+    dp, dx, dt = torch.from_numpy(indptr).cuda(), torch.from_numpy(indices).cuda(), torch.from_numpy(train).cuda()
+    assert rg.rg_graph_validate(dp, dx) == 0
+    g = rg.rg_build_schedule(dp, dx, dt, 100, [f], s0, wk, ep)
+    o = orc.Schedule(indptr, indices, train, 100, [f], s0, wk, ep)
+    assert_schedules_equal(rg, g, o)
+    # the construction did what it set out to do: the oracle's sample of each special row has the planned number of
+    # keys below the guessed cut
+    ids, off = o.frontier(0)
+    so, nbr = o.samples(0)
+    for v, nb in zip(specials, below):
+        j = int(np.nonzero(ids == v)[0][0])
+        S = orc.node_state(hs, v)
+        got = nbr[so[j]:so[j + 1]]
+        assert got.size == f
+        assert sum(orc.key32(S, int(u)) <= cut for u in got) == min(nb, f)
