@@ -172,6 +172,18 @@ def runtime_leg(rg, W, feat, epochs=3, Q=4):
     t_blk = time.perf_counter() - t0
     blk = rg.rg_profile_read()["blocks"]
     n_samp = sum(rg.rg_schedule_block(scheds[0], h).numel() for h in range(scheds[0].L))
+    # the metadata block through a file and back
+    import tempfile
+    with tempfile.TemporaryDirectory() as td:
+        path = os.path.join(td, "epoch.rgsched")
+        t0 = time.perf_counter()
+        rg.rg_schedule_save(scheds[0], path)
+        t_save = time.perf_counter() - t0
+        file_bytes = os.path.getsize(path)
+        t0 = time.perf_counter()
+        loaded = rg.rg_schedule_load(path)
+        t_load = time.perf_counter() - t0
+        del loaded
     # the O(f) alternative sampler on the same epoch (a different, equally distributed sample: never the headline figure)
     del scheds
     rg.rg_build_schedule_with(W.indptr, W.indices, W.train, cfg.batch_size, cfg.fanout, cfg.s0, cfg.worker, cfg.epoch,
@@ -189,6 +201,7 @@ def runtime_leg(rg, W, feat, epochs=3, Q=4):
     pos_edges = sum(rg.rg_schedule_samples(sp, h)[1].numel() for h in range(sp.L))
     del sp
     return {"epochs": epochs, "Q": Q, "schedule_build_ms_per_epoch": t_sched / epochs * 1e3,
+            "schedule_file": {"bytes": file_bytes, "save_ms": t_save * 1e3, "load_ms": t_load * 1e3},
             "position_sampler": {"schedule_build_ms": t_pos * 1e3, "sampler_kernel_ms": pos_kernel_ms, "sampled_edges": pos_edges,
                                  "edges_per_s_kernel": pos_edges / (pos_kernel_ms * 1e-3) if pos_kernel_ms else None},
             "gather_epoch_ms_with_next_cache_built_alongside": t_run / epochs * 1e3, "staged_fraction": staged / max(1, total),

@@ -40,6 +40,7 @@ typedef int32_t rg_status;
 #define RG_ENOMEM   (-2)   /* an allocation failed */
 #define RG_EHIP     (-3)   /* a HIP runtime call failed */
 #define RG_ERANGE   (-4)   /* a size is beyond a documented limit, or an output buffer is too small */
+#define RG_EIO      (-5)   /* a schedule file cannot be opened, read or written, or its contents are not a schedule */
 
 #define RG_MAX_HOPS    8u      /* L <= 8 */
 #define RG_MAX_FANOUT  1984u   /* every fanout[l] <= 1984 */
@@ -139,6 +140,19 @@ rg_status rg_schedule_frontier(const rg_schedule *s, uint32_t hop, const int32_t
  * samp_nbr_dev[samp_off[j] .. samp_off[j+1]).  *n_samples = samp_off[|U_hop|]. */
 rg_status rg_schedule_samples(const rg_schedule *s, uint32_t hop, const int64_t **samp_off_dev,
                               const int32_t **samp_nbr_dev, int64_t *n_samples);
+
+/* The metadata block on storage (Sec. 4 par. (3): the precomputed schedule --
+ * ordered batches, the arrays N_i^e, offsets, per-hop samples; no features --
+ * is written out once and streamed back).  rg_schedule_save writes `s` to
+ * `path` (device arrays pass through a 64 MiB pinned staging buffer, `stream`
+ * is waited on); rg_schedule_load reads such a file into a new handle that
+ * behaves like the schedule that was saved (computation blocks are rebuilt on
+ * request, not stored).  A file is checked while it is read -- magic, header
+ * ranges, offsets monotone and consistent between hops, every node ID inside
+ * [0, n_nodes), exact length -- and refused with RG_EIO otherwise; nothing
+ * is written through `out` then. */
+rg_status rg_schedule_save(const rg_schedule *s, const char *path, void *stream);
+rg_status rg_schedule_load(const char *path, const rg_allocator *a, void *stream, rg_schedule **out);
 
 /* Feature storage, as byte rows (any element type): X[v] is
  * local_rows + row_of[v] * local_stride when is_local[v], else

@@ -14,7 +14,7 @@ import torch
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB_PATH = os.path.join(_HERE, "librapidgnn_hip.so")
 
-RG_OK, RG_EINVAL, RG_ENOMEM, RG_EHIP, RG_ERANGE = 0, -1, -2, -3, -4
+RG_OK, RG_EINVAL, RG_ENOMEM, RG_EHIP, RG_ERANGE, RG_EIO = 0, -1, -2, -3, -4, -5
 RG_MAX_HOPS, RG_MAX_FANOUT = 8, 1984
 KERNEL_GROUPS = ("sampler", "frontier", "shuffle_sort", "histogram", "topk", "plan", "cache_fill", "gather", "gather_miss", "sample_offsets", "blocks")
 
@@ -25,7 +25,8 @@ EXPORTS = ("rg_last_error", "rg_graph_validate", "rg_build_schedule", "rg_schedu
            "rg_cache_pair_table_bytes", "rg_cache_pair_destroy",
            "rg_prefetcher_create", "rg_prefetcher_fill", "rg_prefetcher_acquire", "rg_prefetcher_release",
            "rg_prefetcher_depth", "rg_prefetcher_destroy", "rg_schedule_build_blocks", "rg_schedule_block",
-           "rg_classify_batch", "rg_build_schedule_with", "rg_gather_batches")
+           "rg_classify_batch", "rg_build_schedule_with", "rg_gather_batches",
+           "rg_schedule_save", "rg_schedule_load")
 
 
 class RgError(RuntimeError):
@@ -84,6 +85,8 @@ def lib():
         L.rg_profile_enable.argtypes = [C.c_int]; L.rg_profile_enable.restype = None
         L.rg_profile_reset.argtypes = []; L.rg_profile_reset.restype = None
         L.rg_profile_read.argtypes = [P(C.c_double), P(u64)]
+        L.rg_schedule_save.argtypes = [vp, C.c_char_p, vp]
+        L.rg_schedule_load.argtypes = [C.c_char_p, P(rg_allocator), vp, P(vp)]
         L.rg_gather_batches.argtypes = [vp, vp, P(rg_features), u32, u32, vp, u64, u64, vp, vp, P(rg_gather_stats)]
         L.rg_classify_batch.argtypes = [vp, vp, P(rg_features), u32, vp, P(rg_gather_stats)]
         L.rg_schedule_build_blocks.argtypes = [vp, u64, vp]
@@ -105,7 +108,8 @@ def lib():
                      "rg_cache_pair_create", "rg_cache_pair_begin_next", "rg_cache_pair_swap",
                      "rg_prefetcher_create", "rg_prefetcher_fill", "rg_prefetcher_acquire", "rg_prefetcher_release",
                      "rg_prefetcher_depth", "rg_schedule_build_blocks", "rg_schedule_block",
-           "rg_classify_batch", "rg_build_schedule_with", "rg_gather_batches"):
+           "rg_classify_batch", "rg_build_schedule_with", "rg_gather_batches",
+           "rg_schedule_save", "rg_schedule_load"):
             getattr(L, name).restype = C.c_int32
         _lib = L
     return _lib
@@ -207,6 +211,17 @@ def rg_build_schedule_with(indptr, indices, train_nodes, batch_size, fanout, s0=
     _check(lib().rg_build_schedule_with(C.byref(g), _dev_ptr(train_nodes, torch.int32) if T else None, T, int(batch_size), fan,
                                         len(fanout), int(s0), int(worker), int(epoch), int(sampler),
                                         C.byref(allocator) if allocator is not None else None, _stream_ptr(stream), C.byref(out)))
+    return Schedule(out.value)
+
+
+def rg_schedule_save(s, path, stream=None):
+    _check(lib().rg_schedule_save(s.h, os.fsencode(path), _stream_ptr(stream)))
+
+
+def rg_schedule_load(path, allocator=None, stream=None):
+    out = C.c_void_p()
+    _check(lib().rg_schedule_load(os.fsencode(path), C.byref(allocator) if allocator is not None else None, _stream_ptr(stream),
+                                  C.byref(out)))
     return Schedule(out.value)
 
 

@@ -318,7 +318,7 @@ __global__ void __launch_bounds__(FR_THREADS) fresh_emit_sparse_kernel(uint32_t 
     *reinterpret_cast<unsigned long long *>(flags + (at >> 3)) = 0ull;
 }
 
-static std::atomic<uint64_t> g_next_uid{1};
+std::atomic<uint64_t> g_next_schedule_uid{1};        // also taken by schedules loaded from a file
 
 static rg_status sort_keypos(KeyPos *kp, uint64_t n_pad, hipStream_t st)
 {
@@ -343,7 +343,7 @@ static rg_status build_schedule_impl(const rg_graph *g, const int32_t *train, ui
     s->n_batches = beta;
     s->L = L;
     s->T = T;
-    s->uid = g_next_uid.fetch_add(1);
+    s->uid = g_next_schedule_uid.fetch_add(1);
     s->hop.resize(L + 1);
     Arena tmp(a);             // build-time scratch, released when this function returns
 

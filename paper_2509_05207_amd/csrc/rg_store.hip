@@ -1,0 +1,196 @@
+// The metadata block of one epoch on storage (Sec. 4 par. (3): the precomputed schedule -- ordered batches, the
+// arrays N_i^e, offsets -- is written out and streamed back by the prefetcher; no features in it).
+//
+// rg_schedule_save writes a schedule to a file, rg_schedule_load reads one back into HBM.  Layout, little endian:
+//   "RGSCHED1", n_nodes i64, T u64, n_batches u32, L u32,
+//   for hop 0..L:   batch_off i64[n_batches + 1], ids i32[batch_off[n_batches]]
+//   for hop 0..L-1: samp_off i64[|U_hop| + 1],    samp_nbr i32[samp_off[|U_hop|]]   (after that hop's ids)
+// Device arrays go through a pinned staging buffer in pieces, so neither side needs the whole schedule in host
+// memory.  A loaded file is checked before anything on the device depends on it: offsets monotone and consistent,
+// every ID inside [0, n_nodes).
+#include "rg_internal.h"
+
+#include <algorithm>
+#include <atomic>
+#include <cstdio>
+#include <cstring>
+
+namespace rg {
+
+extern std::atomic<uint64_t> g_next_schedule_uid;      // rg_schedule.hip
+
+static const char MAGIC[8] = {'R', 'G', 'S', 'C', 'H', 'E', 'D', '1'};
+constexpr uint64_t STAGE_BYTES = (uint64_t)64 << 20;
+
+struct File {
+    FILE *f = nullptr;
+    ~File() { if (f) fclose(f); }
+};
+
+static rg_status write_all(FILE *f, const void *p, uint64_t n)
+{
+    if (n && fwrite(p, 1, n, f) != n) { set_error("rg_schedule_save: write failed"); return RG_EIO; }
+    return RG_OK;
+}
+
+static rg_status read_all(FILE *f, void *p, uint64_t n)
+{
+    if (n && fread(p, 1, n, f) != n) { set_error("rg_schedule_load: file is truncated"); return RG_EIO; }
+    return RG_OK;
+}
+
+static rg_status device_to_file(FILE *f, const void *dev, uint64_t bytes, void *stage, hipStream_t st)
+{
+    for (uint64_t at = 0; at < bytes; at += STAGE_BYTES) {
+        const uint64_t n = std::min<uint64_t>(STAGE_BYTES, bytes - at);
+        RG_HIP(hipMemcpyAsync(stage, (const uint8_t *)dev + at, n, hipMemcpyDeviceToHost, st));
+        RG_HIP(hipStreamSynchronize(st));
+        RG_TRY(write_all(f, stage, n));
+    }
+    return RG_OK;
+}
+
+// check(piece, count, first_index) is called on every piece before it goes to the device
+template <typename T, typename Check>
+static rg_status file_to_device(FILE *f, void *dev, uint64_t count, void *stage, hipStream_t st, Check check)
+{
+    const uint64_t per = STAGE_BYTES / sizeof(T);
+    for (uint64_t at = 0; at < count; at += per) {
+        const uint64_t n = std::min<uint64_t>(per, count - at);
+        RG_TRY(read_all(f, stage, n * sizeof(T)));
+        RG_TRY(check((const T *)stage, n, at));
+        RG_HIP(hipMemcpyAsync((T *)dev + at, stage, n * sizeof(T), hipMemcpyHostToDevice, st));
+        RG_HIP(hipStreamSynchronize(st));            // the staging buffer is reused by the next piece
+    }
+    return RG_OK;
+}
+
+}  // namespace rg
+
+using namespace rg;
+
+extern "C" {
+
+rg_status rg_schedule_save(const rg_schedule *s, const char *path, void *stream)
+{
+    if (!s || !path) { set_error("rg_schedule_save: null argument"); return RG_EINVAL; }
+    hipStream_t st = as_stream(stream);
+    File file;
+    file.f = fopen(path, "wb");
+    if (!file.f) { set_error("rg_schedule_save: cannot open %s for writing", path); return RG_EIO; }
+    Arena tmp(s->arena.allocator());
+    void *stage = nullptr;
+    RG_TRY(tmp.pinned(STAGE_BYTES, &stage));
+    RG_TRY(write_all(file.f, MAGIC, 8));
+    const int64_t n_nodes = s->n_nodes;
+    const uint64_t T = s->T;
+    const uint32_t nb = s->n_batches, L = s->L;
+    RG_TRY(write_all(file.f, &n_nodes, 8));
+    RG_TRY(write_all(file.f, &T, 8));
+    RG_TRY(write_all(file.f, &nb, 4));
+    RG_TRY(write_all(file.f, &L, 4));
+    for (uint32_t l = 0; l <= L; ++l) {
+        const HopData &h = s->hop[l];
+        RG_TRY(write_all(file.f, h.off_host.data(), ((uint64_t)nb + 1) * sizeof(int64_t)));
+        const uint64_t n = (uint64_t)h.off_host[nb];
+        RG_TRY(device_to_file(file.f, h.ids, n * sizeof(int32_t), stage, st));
+        if (l < L) {
+            RG_TRY(device_to_file(file.f, h.samp_off, (n + 1) * sizeof(int64_t), stage, st));
+            RG_TRY(device_to_file(file.f, h.samp_nbr, (uint64_t)h.n_samples * sizeof(int32_t), stage, st));
+        }
+    }
+    if (fflush(file.f) != 0) { set_error("rg_schedule_save: flush failed"); return RG_EIO; }
+    return RG_OK;
+}
+
+rg_status rg_schedule_load(const char *path, const rg_allocator *a, void *stream, rg_schedule **out)
+{
+    if (!path || !out) { set_error("rg_schedule_load: null argument"); return RG_EINVAL; }
+    hipStream_t st = as_stream(stream);
+    File file;
+    file.f = fopen(path, "rb");
+    if (!file.f) { set_error("rg_schedule_load: cannot open %s", path); return RG_EIO; }
+    // Sizes read from the file are trusted only as far as the file is long: nothing is allocated for data that is not there.
+    if (fseek(file.f, 0, SEEK_END) != 0) { set_error("rg_schedule_load: cannot seek in %s", path); return RG_EIO; }
+    const long end_pos = ftell(file.f);
+    if (end_pos < 0 || fseek(file.f, 0, SEEK_SET) != 0) { set_error("rg_schedule_load: cannot seek in %s", path); return RG_EIO; }
+    const uint64_t file_bytes = (uint64_t)end_pos;
+    auto fits = [&](uint64_t count, uint64_t elem) -> bool {
+        const long at = ftell(file.f);
+        return at >= 0 && count <= (file_bytes - (uint64_t)at) / elem;
+    };
+    char magic[8];
+    int64_t n_nodes = 0;
+    uint64_t T = 0;
+    uint32_t nb = 0, L = 0;
+    RG_TRY(read_all(file.f, magic, 8));
+    if (memcmp(magic, MAGIC, 8) != 0) { set_error("rg_schedule_load: %s is not a schedule file", path); return RG_EIO; }
+    RG_TRY(read_all(file.f, &n_nodes, 8));
+    RG_TRY(read_all(file.f, &T, 8));
+    RG_TRY(read_all(file.f, &nb, 4));
+    RG_TRY(read_all(file.f, &L, 4));
+    if (n_nodes < 0 || n_nodes >= ((int64_t)1 << 31) || L > RG_MAX_HOPS || nb > 0x7FFFFFFFu) {
+        set_error("rg_schedule_load: header out of range (n_nodes %lld, L %u, n_batches %u)", (long long)n_nodes, L, nb);
+        return RG_EIO;
+    }
+    if (!fits(((uint64_t)nb + 1) * ((uint64_t)L + 1), sizeof(int64_t))) { set_error("rg_schedule_load: file is truncated"); return RG_EIO; }
+    rg_schedule *s = new (std::nothrow) rg_schedule(a);
+    if (!s) { set_error("rg_schedule_load: out of host memory"); return RG_ENOMEM; }
+    struct Guard { rg_schedule *s; hipStream_t st; ~Guard() { if (s) { (void)hipStreamSynchronize(st); delete s; } } } guard{s, st};
+    s->n_nodes = n_nodes; s->T = T; s->n_batches = nb; s->L = L;
+    s->uid = g_next_schedule_uid.fetch_add(1);
+    s->hop.resize((size_t)L + 1);
+    Arena tmp(a);
+    void *stage = nullptr;
+    RG_TRY(tmp.pinned(STAGE_BYTES, &stage));
+
+    auto ids_in_range = [n_nodes](const int32_t *p, uint64_t n, uint64_t) -> rg_status {
+        for (uint64_t i = 0; i < n; ++i)
+            if (p[i] < 0 || (int64_t)p[i] >= n_nodes) { set_error("rg_schedule_load: node ID %d outside [0, %lld)", p[i], (long long)n_nodes); return RG_EIO; }
+        return RG_OK;
+    };
+    for (uint32_t l = 0; l <= L; ++l) {
+        HopData &h = s->hop[l];
+        h.off_host.resize((size_t)nb + 1);
+        RG_TRY(read_all(file.f, h.off_host.data(), ((uint64_t)nb + 1) * sizeof(int64_t)));
+        if (h.off_host[0] != 0) { set_error("rg_schedule_load: batch offsets of hop %u do not start at 0", l); return RG_EIO; }
+        for (uint32_t b = 0; b < nb; ++b)
+            if (h.off_host[b + 1] < h.off_host[b]) { set_error("rg_schedule_load: batch offsets of hop %u decrease", l); return RG_EIO; }
+        if (l > 0)
+            for (uint32_t b = 0; b < nb; ++b)
+                if (h.off_host[b + 1] - h.off_host[b] < s->hop[l - 1].off_host[b + 1] - s->hop[l - 1].off_host[b]) {
+                    set_error("rg_schedule_load: frontier of hop %u, batch %u is smaller than the one before", l, b);
+                    return RG_EIO;
+                }
+        const uint64_t n = (uint64_t)h.off_host[nb];
+        if (!fits(n, sizeof(int32_t))) { set_error("rg_schedule_load: file is truncated (frontier of hop %u)", l); return RG_EIO; }
+        RG_TRY(s->arena.dev_n<int64_t>((uint64_t)nb + 1, &h.off_dev));
+        RG_HIP(hipMemcpyAsync(h.off_dev, h.off_host.data(), ((uint64_t)nb + 1) * sizeof(int64_t), hipMemcpyHostToDevice, st));
+        RG_TRY(s->arena.dev_n<int32_t>(n, &h.ids));
+        RG_TRY((file_to_device<int32_t>(file.f, h.ids, n, stage, st, ids_in_range)));
+        if (l < L) {
+            if (!fits(n + 1, sizeof(int64_t))) { set_error("rg_schedule_load: file is truncated (sample offsets of hop %u)", l); return RG_EIO; }
+            RG_TRY(s->arena.dev_n<int64_t>(n + 1, &h.samp_off));
+            int64_t last = 0;              // running check: starts at 0, never decreases
+            auto offsets_ok = [&last](const int64_t *p, uint64_t cnt, uint64_t first) -> rg_status {
+                for (uint64_t i = 0; i < cnt; ++i) {
+                    if ((first + i == 0 && p[i] != 0) || p[i] < last) { set_error("rg_schedule_load: sample offsets are not a prefix sum"); return RG_EIO; }
+                    last = p[i];
+                }
+                return RG_OK;
+            };
+            RG_TRY((file_to_device<int64_t>(file.f, h.samp_off, n + 1, stage, st, offsets_ok)));
+            h.n_samples = last;
+            if (!fits((uint64_t)h.n_samples, sizeof(int32_t))) { set_error("rg_schedule_load: file is truncated (samples of hop %u)", l); return RG_EIO; }
+            RG_TRY(s->arena.dev_n<int32_t>((uint64_t)h.n_samples, &h.samp_nbr));
+            RG_TRY((file_to_device<int32_t>(file.f, h.samp_nbr, (uint64_t)h.n_samples, stage, st, ids_in_range)));
+        }
+    }
+    if (fgetc(file.f) != EOF) { set_error("rg_schedule_load: trailing bytes after the schedule"); return RG_EIO; }
+    RG_HIP(hipStreamSynchronize(st));
+    guard.s = nullptr;
+    *out = s;
+    return RG_OK;
+}
+
+}  // extern "C"

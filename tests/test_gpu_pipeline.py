@@ -276,3 +276,79 @@ def test_ranges_of_batches_gathered_back_to_back(case, rg, orc, planned):
     with pytest.raises(rg.RgError) as e:
         rg.rg_gather_batches(case.gsched, cache, case.gfeat, 0, nb, small, out_stride=out_stride, out_capacity_rows=8)
     assert e.value.status == rg.RG_ERANGE
+
+
+def test_schedule_survives_a_round_trip_through_a_file(case, rg, orc, tmp_path):
+    """The metadata block on storage: saved, loaded into a new handle, equal to the oracle's schedule, and as good
+    as the original for the cache, the plan, the gathers and the blocks."""
+    w = case.w
+    path = tmp_path / "epoch0.rgsched"
+    rg.rg_schedule_save(case.gsched, path)
+    # what the format says the file holds: header 32 bytes, then per hop offsets + ids (+ sample offsets + samples)
+    want = 32
+    for hop in range(case.osched.L + 1):
+        ids, off = case.osched.frontier(hop)
+        want += off.size * 8 + ids.size * 4
+        if hop < case.osched.L:
+            so, nb = case.osched.samples(hop)
+            want += so.size * 8 + nb.size * 4
+    assert path.stat().st_size == want
+    g = rg.rg_schedule_load(path)
+    from test_gpu_parity import assert_schedules_equal
+    assert_schedules_equal(rg, g, case.osched)
+    ids, slot = oracle_cache(orc, case, case.osched)
+    c = rg.rg_build_cache([g], case.gfeat, w.K)
+    assert np.array_equal(rg.rg_cache_view(c, w.n_nodes)["cache_ids"].cpu().numpy(), ids)
+    _, off = case.osched.input_nodes()
+    rows = int(off[-1])
+    out = torch.empty(rows * w.row_bytes, dtype=torch.uint8, device="cuda")
+    stats = rg.rg_gather_batches(g, c, case.gfeat, 0, g.n_batches, out, out_stride=w.row_bytes, out_capacity_rows=rows)
+    torch.cuda.synchronize()
+    got = out.cpu().numpy().reshape(rows, w.row_bytes)
+    for b in range(g.n_batches):
+        ref = orc.gather_batch(case.osched, b, case.ofeat, out_stride=w.row_bytes, fill=0)
+        assert np.array_equal(got[off[b]:off[b + 1]], ref)
+        assert stats[b] == orc.batch_stats(case.osched, b, w.is_local.numpy(), slot)
+    rg.rg_schedule_build_blocks(g)
+    for hop in range(g.L):
+        assert np.array_equal(rg.rg_schedule_block(g, hop).cpu().numpy(), case.osched.block(hop))
+
+
+def test_damaged_schedule_files_are_refused(case, rg, tmp_path):
+    path = tmp_path / "epoch0.rgsched"
+    rg.rg_schedule_save(case.gsched, path)
+    good = path.read_bytes()
+
+    def refused(data, name):
+        p = tmp_path / name
+        p.write_bytes(data)
+        with pytest.raises(rg.RgError) as e:
+            rg.rg_schedule_load(p)
+        assert e.value.status == rg.RG_EIO, name
+
+    refused(b"", "empty")
+    refused(b"NOTASCHD" + good[8:], "magic")
+    refused(good[:40], "header_only")
+    refused(good[: len(good) // 2], "half")
+    refused(good[:-1], "one_byte_short")
+    refused(good + b"\\0", "trailing")
+    bad = bytearray(good)
+    bad[8:16] = (2**31).to_bytes(8, "little")                  # n_nodes out of range
+    refused(bytes(bad), "n_nodes")
+    bad = bytearray(good)
+    bad[24:28] = (2**31 - 1).to_bytes(4, "little")             # far more batches than the file can hold
+    refused(bytes(bad), "n_batches")
+    bad = bytearray(good)
+    first_ids = 32 + (case.gsched.n_batches + 1) * 8           # first seed ID
+    bad[first_ids:first_ids + 4] = (case.w.n_nodes).to_bytes(4, "little")
+    refused(bytes(bad), "id_out_of_range")
+    bad = bytearray(good)
+    bad[32 + 8:32 + 16] = (2**62).to_bytes(8, "little")        # a batch offset beyond everything
+    refused(bytes(bad), "offset")
+    with pytest.raises(rg.RgError) as e:
+        rg.rg_schedule_load(tmp_path / "does_not_exist")
+    assert e.value.status == rg.RG_EIO
+    with pytest.raises(rg.RgError) as e:
+        rg.rg_schedule_save(case.gsched, tmp_path / "no_such_dir" / "x")
+    assert e.value.status == rg.RG_EIO
+    rg.rg_schedule_load(path)                                  # and the good file still loads
