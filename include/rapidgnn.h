@@ -57,8 +57,8 @@ typedef struct rg_allocator {
     void *ctx;
 } rg_allocator;
 
-/* CSR adjacency the sampler reads ("the graph structure visible to the
- * neighbourhood sampler", Sec. 2.3).  Precondition: within each row the
+/* CSR adjacency the sampler reads (the graph structure this worker's sampler
+ * sees, Sec. 2.3).  Precondition: within each row the
  * neighbour IDs are strictly ascending (sorted, duplicate free) and in
  * [0, n_nodes); rg_graph_validate checks it. */
 typedef struct rg_graph {
@@ -156,8 +156,7 @@ rg_status rg_schedule_load(const char *path, const rg_allocator *a, void *stream
 
 /* Feature storage, as byte rows (any element type): X[v] is
  * local_rows + row_of[v] * local_stride when is_local[v], else
- * remote_rows + row_of[v] * remote_stride ("N_local: nodes whose features
- * reside on this worker", Eq. 2).  The remote table stands for the other
+ * remote_rows + row_of[v] * remote_stride (is_local marks N_local, the nodes whose rows this worker holds; Eq. 2).  The remote table stands for the other
  * partitions' memory behind VectorPull / SyncPull. */
 typedef struct rg_features {
     const uint8_t *is_local;    /* dev, [n_nodes], 1 = local */
@@ -275,10 +274,11 @@ rg_status rg_schedule_build_blocks(rg_schedule *s, uint64_t workspace_limit_byte
 rg_status rg_schedule_block(const rg_schedule *s, uint32_t hop, const int32_t **src_pos_dev);
 
 /* ------------------------------------------------------------------------
- * Double-buffered cache (Sec. 3 "Precomputation and scheduling": a secondary
- * cache C_sec is built from the next epoch's schedule while the current epoch
- * runs and swapped in at the boundary; Alg. 1: "Parallel: build C_sec from
- * B_{e+1}", "if C_sec ready: C_s <- C_sec"; Sec. 4 par. (6)).  Device bytes of
+ * Double-buffered cache (Sec. 3 "Rolling prefetch and execution"; Alg. 1, the
+ * secondary-cache build that runs beside an epoch and the swap at its end;
+ * Sec. 4 par. (6)): a secondary cache C_sec is built from the next epoch's
+ * schedule while the current epoch runs and takes over at the boundary if it
+ * is ready by then.  Device bytes of
  * the two tables never exceed 2 * n_hot * row stride (Sec. 3, memory bound).
  *
  *   rg_cache_pair_create      builds C_s from `first_epoch` (as rg_build_cache with one epoch)
@@ -306,8 +306,8 @@ void rg_cache_pair_destroy(rg_cache_pair *p);
 
 /* ------------------------------------------------------------------------
  * Rolling prefetch queue of depth Q (Sec. 3 "Rolling prefetch and execution";
- * Alg. 1 "Parallel: prefetch features for next Q batches"; Sec. 4 par. (4),
- * (7)): feature blocks of upcoming batches are staged, in schedule order, into
+ * Alg. 1, the prefetch of the next Q batches beside the batch loop; Sec. 4
+ * par. (4), (7)): feature blocks of upcoming batches are staged, in schedule order, into
  * Q caller-owned device buffers by gathers on a stream of the prefetcher's
  * own; the consumer takes them in order.  Device memory for staged blocks is
  * Q * slot_capacity_rows * out_stride (the Q * m_max * d term of the bound).

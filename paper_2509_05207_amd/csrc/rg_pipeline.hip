@@ -1,8 +1,9 @@
 // The runtime around the three calls: the double-buffered cache (C_s / C_sec, swapped at the
 // epoch boundary) and the rolling prefetch queue of depth Q (Sec. 3 "Rolling prefetch and
-// execution"; Alg. 1 "Parallel: build C_sec from B_{e+1}", "Parallel: prefetch features for next Q
-// batches", "if C_sec ready: C_s <- C_sec"; Sec. 4 par. (4), (6), (7)).  Host-side orchestration
-// of the library's own kernels: threads, streams and events, no new device code.
+// execution"; Alg. 1: the secondary-cache build and the prefetch of the next Q batches that run
+// beside an epoch's batch loop, and the swap at the epoch's end if the secondary cache is ready;
+// Sec. 4 par. (4), (6), (7)).  Host-side orchestration of the library's own kernels: threads,
+// streams and events, no new device code.
 #include "rg_internal.h"
 
 #include <atomic>
@@ -100,7 +101,7 @@ rg_status rg_cache_pair_swap(rg_cache_pair *p, int wait, int *swapped)
     if (!p) { set_error("rg_cache_pair_swap: null argument"); return RG_EINVAL; }
     if (swapped) *swapped = 0;
     int st = p->state.load(std::memory_order_acquire);
-    if (st == 1 && !wait) return RG_OK;                       // not ready: the old cache keeps serving (Alg. 1)
+    if (st == 1 && !wait) return RG_OK;                       // not ready: the old cache keeps serving (Alg. 1, the swap is conditional)
     if (p->worker.joinable()) p->worker.join();
     st = p->state.load(std::memory_order_acquire);
     if (st == 3) {

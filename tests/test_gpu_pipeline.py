@@ -154,7 +154,8 @@ def test_double_buffered_cache_follows_the_epochs(case, rg, orc):
 
 
 def test_an_unswapped_cache_still_serves_the_next_epoch_exactly(case, rg, orc):
-    """"If C_sec ready" fails: the old C_s serves epoch e+1; hits are those of the old cache, bytes are unchanged."""
+    """The secondary cache is not ready at the boundary (Alg. 1's swap is conditional): the old C_s serves epoch e+1;
+    hits are those of the old cache, bytes are unchanged."""
     w = case.w
     o1 = orc.Schedule(w.indptr.numpy(), w.indices.numpy(), w.train.numpy(), w.cfg.batch_size, w.cfg.fanout, case.s0, case.worker, 1,
                       n_threads=8)
