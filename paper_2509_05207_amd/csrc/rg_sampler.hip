@@ -111,14 +111,16 @@ __device__ __forceinline__ unsigned long long low_lanes(int n)
 // the lanes of vm[e]; `total` >= keep keys are valid in all.  Bisection on the key value: the
 // keep-th smallest key stays inside [lo, lo + 2^(bit+1)), and the search stops as soon as the
 // number of keys below the bracket's upper end is exactly `keep` -- after about log2(total)
-// steps for spread-out keys, 32 at most (keys are distinct).
+// steps for spread-out keys, 32 at most (keys are distinct).  `upper` is a bound no valid key exceeds (the cut the keys
+// were collected under, else 2^32 - 1): the search starts at its leading bit instead of bit 31.
 template <int E>
-__device__ __forceinline__ uint32_t kth_key_threshold(const uint32_t (&k)[E], const unsigned long long (&vm)[E], int keep, int total)
+__device__ __forceinline__ uint32_t kth_key_threshold(const uint32_t (&k)[E], const unsigned long long (&vm)[E], int keep, int total,
+                                                      uint32_t upper = 0xFFFFFFFFu)
 {
     keep = uni(keep);
     uint32_t lo = 0;
     int below_hi = uni(total);
-    int bit = 31;
+    int bit = uni(31 - __clz((int)(upper | 1u)));
     while (below_hi != keep) {
         const uint32_t trial = lo | (1u << bit);
         int below = 0;
@@ -161,7 +163,7 @@ __device__ __forceinline__ void sample_registers(const uint32_t (&u)[E], int len
 // exactly those entries' keys do not exceed.
 // Precondition: cnt > keep >= 1, cnt <= CAP.
 template <int CAP>
-__device__ __forceinline__ uint32_t prune_buffer(uint32_t *buf, int cnt, int keep, uint32_t lo, uint32_t hi, int lane)
+__device__ __forceinline__ uint32_t prune_buffer(uint32_t *buf, int cnt, int keep, uint32_t lo, uint32_t hi, int lane, uint32_t upper)
 {
     constexpr int E = CAP / 64;
     cnt = uni(cnt); keep = uni(keep); lo = uni(lo); hi = uni(hi);
@@ -174,7 +176,7 @@ __device__ __forceinline__ uint32_t prune_buffer(uint32_t *buf, int cnt, int kee
         u[e] = idx < cnt ? buf[idx] : 0u;
         k[e] = key32(lo, hi, u[e]);
     }
-    const uint32_t cut = uni(kth_key_threshold<E>(k, vm, keep, cnt));
+    const uint32_t cut = uni(kth_key_threshold<E>(k, vm, keep, cnt, uni(upper)));
     __syncthreads();          // every lane has read its entries before any is overwritten
     int base = 0;
 #pragma unroll
@@ -217,7 +219,7 @@ __device__ __forceinline__ void append_block(const uint32_t (&u)[4], const uint3
     }
     if (total == 0) return;
     if (s.cnt + total > CAP && s.cnt > f) {
-        s.cut = prune_buffer<CAP>(buf, s.cnt, f, lo, hi, lane);
+        s.cut = prune_buffer<CAP>(buf, s.cnt, f, lo, hi, lane, ((MAYBE_OPEN && s.open) ? 0xFFFFFFFFu : s.cut));
         s.cnt = f;
         s.open = false;
         total = 0;
@@ -250,7 +252,7 @@ __device__ __forceinline__ void append_block(const uint32_t (&u)[4], const uint3
     }
     for (int q = 0; q < 4; ++q) {             // lanes 16q .. 16q+15 hold 64 consecutive IDs
         if (s.cnt > CAP - 64) {
-            s.cut = prune_buffer<CAP>(buf, s.cnt, f, lo, hi, lane);
+            s.cut = prune_buffer<CAP>(buf, s.cnt, f, lo, hi, lane, ((MAYBE_OPEN && s.open) ? 0xFFFFFFFFu : s.cut));
             s.cnt = f;
             s.open = false;
         }
@@ -376,7 +378,7 @@ __device__ __forceinline__ void sample_long_row(const int32_t *__restrict__ row,
     __syncthreads();
     if (s.cnt >= f) break;                                       // (always, in the exact attempt: len > f)
   }
-    if (s.cnt > f) (void)prune_buffer<CAP>(buf, s.cnt, f, lo, hi, lane);
+    if (s.cnt > f) (void)prune_buffer<CAP>(buf, s.cnt, f, lo, hi, lane, s.open ? 0xFFFFFFFFu : s.cut);
 }
 
 // SAMPLE of a row of len > f IDs into out (row order), marking the bitmaps when MARK.
