@@ -288,6 +288,28 @@ __device__ __forceinline__ u32x4 load_block(const int32_t *__restrict__ p, int l
 // Valid lanes of ID e of a block that holds `count` IDs: 4 * lane + e < count.
 __device__ __forceinline__ unsigned long long block_lanes(int count, int e) { return low_lanes((count - e + 3) >> 2); }
 
+// A long row is read as its head (the IDs in front of the first 128-byte boundary, fewer than 32) and aligned blocks.
+__device__ __forceinline__ int row_head(const int32_t *row, int len)
+{
+    const int head = (32 - (int)(((uintptr_t)row >> 2) & 31)) & 31;
+    return head > len ? len : head;
+}
+// What a row of len > 64 IDs needs besides its leading 64, fetched ahead of the row's turn: for len <= 256 the IDs
+// row[64 + lane], row[128 + lane], row[192 + lane] (x, y, z; 0 past the end), for longer rows the first aligned block.
+__device__ __forceinline__ u32x4 row_ahead(const int32_t *__restrict__ row, int len, int lane)
+{
+    len = uni(len);
+    if (len <= 256) {
+        u32x4 r = {0u, 0u, 0u, 0u};
+        if (64 + lane < len) r.x = (uint32_t)row[64 + lane];
+        if (128 + lane < len) r.y = (uint32_t)row[128 + lane];
+        if (192 + lane < len) r.z = (uint32_t)row[192 + lane];
+        return r;
+    }
+    const int head = uni(row_head(row, len));
+    return load_block(row + head, len - head, lane);
+}
+
 template <int CAP, bool FULL, bool MAYBE_OPEN = true>
 __device__ __forceinline__ void stream_block(const u32x4 &blk, int count, int f, uint32_t lo, uint32_t hi, int lane, uint32_t *buf, Stream &s)
 {
@@ -307,12 +329,13 @@ __device__ __forceinline__ void stream_block(const u32x4 &blk, int count, int f,
 // front of the first 128-byte boundary go first (one per lane); from there on the row is read in
 // blocks of 1 KB, one aligned 16-byte load per lane, so no two loads of a wave share a cache line,
 // and the next block's load is in flight while the current block's keys are computed.
+// blk0 = row_ahead(row, len, lane), loaded by the caller.
 template <int CAP>
-__device__ __forceinline__ void sample_long_row(const int32_t *__restrict__ row, int len, int f, uint32_t lo, uint32_t hi, int lane, uint32_t *buf)
+__device__ __forceinline__ void sample_long_row(const int32_t *__restrict__ row, int len, int f, uint32_t lo, uint32_t hi, int lane, uint32_t *buf,
+                                                const u32x4 &blk0)
 {
     len = uni(len); f = uni(f); lo = uni(lo); hi = uni(hi);
-    int head = uni((32 - (int)(((uintptr_t)row >> 2) & 31)) & 31);
-    if (head > len) head = len;
+    const int head = uni(row_head(row, len));
     const int32_t *p = row + head;
     const int rem = len - head;                                  // > 0: len > 256 and head < 32
     const int n_blocks = (rem + 255) >> 8;
@@ -326,10 +349,11 @@ __device__ __forceinline__ void sample_long_row(const int32_t *__restrict__ row,
     const bool can_guess = uni(lambda * 4.0f <= (float)len);
     const uint32_t guessed_cut = (uint32_t)(fminf(lambda / (float)len, 0.5f) * 4294967296.0f);
     Stream s{0, true, 0u};
-  for (int attempt = uni(can_guess ? 0 : 1); attempt < 2; attempt = uni(attempt + 1)) {
+    const int first_attempt = uni(can_guess ? 0 : 1);
+  for (int attempt = first_attempt; attempt < 2; attempt = uni(attempt + 1)) {
     const bool guess = attempt == 0;
     s = guess ? Stream{0, false, guessed_cut} : Stream{0, true, 0u};
-    u32x4 cur = load_block(p, rem, lane), nxt = {0u, 0u, 0u, 0u};
+    u32x4 cur = attempt == first_attempt ? blk0 : load_block(p, rem, lane), nxt = {0u, 0u, 0u, 0u};
     int c0 = 0;
     const int count0 = rem < 256 ? rem : 256;
     if (!guess && head + count0 > f) {
@@ -382,22 +406,19 @@ __device__ __forceinline__ void sample_long_row(const int32_t *__restrict__ row,
 }
 
 // SAMPLE of a row of len > f IDs into out (row order), marking the bitmaps when MARK.
-// `first` holds row[lane] for lane < len.
+// `first` holds row[lane] for lane < len; ahead = row_ahead(row, len, lane) when len > 64 (unused otherwise).
 template <int CAP, bool MARK>
-__device__ __forceinline__ void sample_row(const int32_t *__restrict__ row, int len, uint32_t first, int f, uint32_t lo, uint32_t hi, int lane,
-                                           uint32_t *buf, int32_t *__restrict__ out, const ReachedOfBatch &reached_b)
+__device__ __forceinline__ void sample_row(const int32_t *__restrict__ row, int len, uint32_t first, const u32x4 &ahead, int f, uint32_t lo, uint32_t hi,
+                                           int lane, uint32_t *buf, int32_t *__restrict__ out, const ReachedOfBatch &reached_b)
 {
     if (len <= 64) {
         const uint32_t u[1] = {first};
         sample_registers<1, MARK>(u, len, f, lo, hi, lane, out, reached_b);
     } else if (len <= 256) {
-        uint32_t u[4];
-        u[0] = first;
-#pragma unroll
-        for (int e = 1; e < 4; ++e) u[e] = e * 64 + lane < len ? (uint32_t)row[e * 64 + lane] : 0u;
+        const uint32_t u[4] = {first, ahead.x, ahead.y, ahead.z};
         sample_registers<4, MARK>(u, len, f, lo, hi, lane, out, reached_b);
     } else {
-        sample_long_row<CAP>(row, len, f, lo, hi, lane, buf);
+        sample_long_row<CAP>(row, len, f, lo, hi, lane, buf, ahead);
         for (int j = lane; j < f; j += 64) {
             const uint32_t u = buf[j];
             out[j] = (int32_t)u;
@@ -442,7 +463,7 @@ __device__ __forceinline__ int64_t node_of_tile(const int64_t *__restrict__ tile
 // Work items [0, n_tiles) are tiles of long rows (handed out first, so the longest-running work starts first);
 // item n_tiles + c is the c-th group of 64 consecutive frontier nodes.
 template <int CAP>
-__global__ void __launch_bounds__(64) sample_kernel(HopArgs a)
+__global__ void __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(CAP <= 256 ? 7 : 1))) sample_kernel(HopArgs a)
 {
     __shared__ uint32_t buf[CAP];
     const int lane = threadIdx.x;
@@ -459,7 +480,8 @@ __global__ void __launch_bounds__(64) sample_kernel(HopArgs a)
             const int64_t first_pos = t * deg / T, last_pos = (t + 1) * deg / T;     // near-equal tiles, each longer than 2 * RG_MAX_FANOUT
             const uint64_t S = a.rec.state[i];
             const int32_t *row = a.indices + row_begin + first_pos;
-            sample_row<CAP, false>(row, (int)(last_pos - first_pos), (uint32_t)row[lane], f, (uint32_t)S, (uint32_t)(S >> 32), lane, buf,
+            const int len = (int)(last_pos - first_pos);
+            sample_row<CAP, false>(row, len, (uint32_t)row[lane], row_ahead(row, len, lane), f, (uint32_t)S, (uint32_t)(S >> 32), lane, buf,
                                    a.tile_out + w * f, ReachedOfBatch{nullptr, nullptr});
             continue;
         }
@@ -477,16 +499,20 @@ __global__ void __launch_bounds__(64) sample_kernel(HopArgs a)
         int64_t rb = bcast64(rb_lane, l);
         int deg = __builtin_amdgcn_readlane(deg_lane, l);
         uint32_t first = lane < deg ? (uint32_t)a.indices[rb + lane] : 0u;
+        u32x4 ahead = {0u, 0u, 0u, 0u};
+        if (deg > 64 && deg > f) ahead = row_ahead(a.indices + rb, deg, lane);
         while (todo != 0ull) {
             todo &= todo - 1ull;
             const int cl = l, cdeg = deg;
             const int64_t crb = rb;
             const uint32_t cfirst = first;
+            const u32x4 cahead = ahead;
             if (todo != 0ull) {
                 l = __builtin_amdgcn_readfirstlane(__ffsll((long long)todo) - 1);
                 rb = bcast64(rb_lane, l);
                 deg = __builtin_amdgcn_readlane(deg_lane, l);
                 first = lane < deg ? (uint32_t)a.indices[rb + lane] : 0u;
+                if (deg > 64 && deg > f) ahead = row_ahead(a.indices + rb, deg, lane);
             }
             const uint32_t b = (uint32_t)__builtin_amdgcn_readlane((int)b_lane, cl);
             const ReachedOfBatch reached_b = reached_of(a.reached, b);
@@ -501,7 +527,7 @@ __global__ void __launch_bounds__(64) sample_kernel(HopArgs a)
                 }
             } else {
                 const uint64_t S = (uint64_t)bcast64(S_lane, cl);
-                sample_row<CAP, true>(row, cdeg, cfirst, f, (uint32_t)S, (uint32_t)(S >> 32), lane, buf, out, reached_b);
+                sample_row<CAP, true>(row, cdeg, cfirst, cahead, f, (uint32_t)S, (uint32_t)(S >> 32), lane, buf, out, reached_b);
             }
         }
     }
@@ -523,7 +549,9 @@ __global__ void __launch_bounds__(64) sample_merge_kernel(HopArgs a)
         const uint64_t S = a.rec.state[i];
         const int32_t *row = a.tile_out + w * f;
         const int len = (int)(T * f);
-        sample_row<CAP, true>(row, len, lane < len ? (uint32_t)row[lane] : 0u, f, (uint32_t)S, (uint32_t)(S >> 32), lane, buf,
+        u32x4 ahead = {0u, 0u, 0u, 0u};
+        if (len > 64) ahead = row_ahead(row, len, lane);
+        sample_row<CAP, true>(row, len, lane < len ? (uint32_t)row[lane] : 0u, ahead, f, (uint32_t)S, (uint32_t)(S >> 32), lane, buf,
                               a.samp_nbr + a.samp_off[i], reached_of(a.reached, b));
     }
 }
