@@ -121,7 +121,7 @@ __device__ __forceinline__ uint32_t kth_key_threshold(const uint32_t (&k)[E], co
     uint32_t lo = 0;
     int below_hi = uni(total);
     int bit = uni(31 - __clz((int)(upper | 1u)));
-    while (below_hi != keep) {
+    while (below_hi != keep && bit >= 0) {     // (bit >= 0 always holds for distinct keys; it bounds the loop whatever the input)
         const uint32_t trial = lo | (1u << bit);
         int below = 0;
 #pragma unroll
@@ -428,13 +428,38 @@ __device__ __forceinline__ void sample_row(const int32_t *__restrict__ row, int 
     }
 }
 
+// Per tile job j: the frontier position i whose row it belongs to (tile_off[i] <= j < tile_off[i + 1]), where its piece of
+// the row starts in `indices` and how long it is (near-equal pieces, each longer than 2 * RG_MAX_FANOUT).  Written by the
+// nodes that have tiles, so that a wave finds its piece with one load instead of a search through tile_off.
+struct TileRecs {
+    int64_t *node;
+    int64_t *begin;
+    int32_t *len;
+};
+__global__ void tile_records_kernel(const int64_t *__restrict__ tile_off, const int64_t *__restrict__ row_begin, const int32_t *__restrict__ deg,
+                                    int64_t n, TileRecs r)
+{
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= n) return;
+    const int64_t d = deg[i];
+    const int64_t T = tiles_of(d);            // the count tile_off was summed from
+    if (T == 0) return;
+    const int64_t first = tile_off[i], b0 = row_begin[i];
+    for (int64_t t = 0; t < T; ++t) {
+        const int64_t first_pos = t * d / T, last_pos = (t + 1) * d / T;
+        r.node[first + t] = i;
+        r.begin[first + t] = b0 + first_pos;
+        r.len[first + t] = (int32_t)(last_pos - first_pos);
+    }
+}
+
 struct HopArgs {
     const int32_t *indices;
     const int32_t *frontier; int64_t n_frontier;
     NodeRecs rec;
     uint32_t fanout;
     const int64_t *samp_off; int32_t *samp_nbr;
-    const int64_t *tile_off; int64_t n_tiles; int32_t *tile_out;      // tile j writes tile_out[j * fanout ..)
+    const int64_t *tile_off; TileRecs tile; int64_t n_tiles; int32_t *tile_out;      // tile j writes tile_out[j * fanout ..)
     ReachedMaps reached;
     unsigned long long *next_work;                                     // work items are handed out in order through this counter
 };
@@ -447,17 +472,6 @@ __device__ __forceinline__ int64_t grab_work(unsigned long long *counter, int la
     const uint32_t lo = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)v);
     const uint32_t hi = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)(v >> 32));
     return (int64_t)(((uint64_t)hi << 32) | lo);
-}
-
-// Position i of the frontier whose tiles contain tile job j: tile_off[i] <= j < tile_off[i + 1].
-__device__ __forceinline__ int64_t node_of_tile(const int64_t *__restrict__ tile_off, int64_t n, int64_t j)
-{
-    int64_t lo = 0, hi = n;
-    while (hi - lo > 1) {
-        const int64_t mid = (lo + hi) >> 1;
-        if (tile_off[mid] <= j) lo = mid; else hi = mid;
-    }
-    return lo;
 }
 
 // Work items [0, n_tiles) are tiles of long rows (handed out first, so the longest-running work starts first);
@@ -474,13 +488,9 @@ __global__ void __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(CAP <= 
     // end; every wave leaves once the counter has passed the last item.
     for (int64_t w = grab_work(a.next_work, lane); w < n_work; w = grab_work(a.next_work, lane)) {
         if (w < a.n_tiles) {
-            const int64_t i = node_of_tile(a.tile_off, a.n_frontier, w);
-            const int64_t T = a.tile_off[i + 1] - a.tile_off[i], t = w - a.tile_off[i];
-            const int64_t row_begin = a.rec.row_begin[i], deg = a.rec.deg[i];
-            const int64_t first_pos = t * deg / T, last_pos = (t + 1) * deg / T;     // near-equal tiles, each longer than 2 * RG_MAX_FANOUT
-            const uint64_t S = a.rec.state[i];
-            const int32_t *row = a.indices + row_begin + first_pos;
-            const int len = (int)(last_pos - first_pos);
+            const int32_t *row = a.indices + a.tile.begin[w];
+            const int len = a.tile.len[w];
+            const uint64_t S = a.rec.state[a.tile.node[w]];
             sample_row<CAP, false>(row, len, (uint32_t)row[lane], row_ahead(row, len, lane), f, (uint32_t)S, (uint32_t)(S >> 32), lane, buf,
                                    a.tile_out + w * f, ReachedOfBatch{nullptr, nullptr});
             continue;
@@ -542,7 +552,7 @@ __global__ void __launch_bounds__(64) sample_merge_kernel(HopArgs a)
     const int lane = threadIdx.x;
     const int f = (int)a.fanout;
     for (int64_t w = blockIdx.x; w < a.n_tiles; w += gridDim.x) {
-        const int64_t i = node_of_tile(a.tile_off, a.n_frontier, w);
+        const int64_t i = a.tile.node[w];
         if (a.tile_off[i] != w) continue;
         const int64_t T = a.tile_off[i + 1] - a.tile_off[i];
         const uint32_t b = a.rec.batch[i];
@@ -636,13 +646,21 @@ rg_status sample_hop(const rg_graph *g, HopData &cur, uint32_t beta, const uint6
     }
     if (fanout == 0) n_tiles = 0;             // nothing is drawn; every sample is empty
     int32_t *tile_out = nullptr;
+    TileRecs tile{nullptr, nullptr, nullptr};
     RG_TRY(tmp.dev_n<int32_t>((uint64_t)n_tiles * fanout, &tile_out));
+    RG_TRY(tmp.dev_n<int64_t>((uint64_t)n_tiles, &tile.node));
+    RG_TRY(tmp.dev_n<int64_t>((uint64_t)n_tiles, &tile.begin));
+    RG_TRY(tmp.dev_n<int32_t>((uint64_t)n_tiles, &tile.len));
+    if (n_tiles > 0) {
+        ScopedTimer tm(KG_OFFSETS, st);
+        hipLaunchKernelGGL(tile_records_kernel, dim3((unsigned)((n_cur + 255) / 256)), dim3(256), 0, st, tile_off, rec.row_begin, rec.deg, n_cur, tile);
+    }
 
     if (fanout > 0 && n_cur > 0) {
         unsigned long long *next_work = nullptr;
         RG_TRY(tmp.dev_n<unsigned long long>(1, &next_work));
         RG_HIP(hipMemsetAsync(next_work, 0, sizeof(unsigned long long), st));
-        HopArgs a{g->indices, cur.ids, n_cur, rec, fanout, cur.samp_off, cur.samp_nbr, tile_off, n_tiles, tile_out, reached, next_work};
+        HopArgs a{g->indices, cur.ids, n_cur, rec, fanout, cur.samp_off, cur.samp_nbr, tile_off, tile, n_tiles, tile_out, reached, next_work};
         ScopedTimer tm(KG_SAMPLER, st);
         const int64_t n_work = n_tiles + (n_cur + 63) / 64;
         const unsigned grid = (unsigned)std::max<int64_t>(1, std::min<int64_t>(n_work, (int64_t)n_cu * 32));     // as many waves as fit on the chip
