@@ -329,17 +329,17 @@ __device__ __forceinline__ void stream_block(const u32x4 &blk, int count, int f,
 // front of the first 128-byte boundary go first (one per lane); from there on the row is read in
 // blocks of 1 KB, one aligned 16-byte load per lane, so no two loads of a wave share a cache line,
 // and the next block's load is in flight while the current block's keys are computed.
-// blk0 = row_ahead(row, len, lane), loaded by the caller.
+// first = row[lane] and blk0 = row_ahead(row, len, lane), loaded by the caller.
 template <int CAP>
-__device__ __forceinline__ void sample_long_row(const int32_t *__restrict__ row, int len, int f, uint32_t lo, uint32_t hi, int lane, uint32_t *buf,
-                                                const u32x4 &blk0)
+__device__ __forceinline__ void sample_long_row(const int32_t *__restrict__ row, int len, uint32_t first, int f, uint32_t lo, uint32_t hi, int lane,
+                                                uint32_t *buf, const u32x4 &blk0)
 {
     len = uni(len); f = uni(f); lo = uni(lo); hi = uni(hi);
     const int head = uni(row_head(row, len));
     const int32_t *p = row + head;
     const int rem = len - head;                                  // > 0: len > 256 and head < 32
     const int n_blocks = (rem + 255) >> 8;
-    const uint32_t head_u = lane < head ? (uint32_t)row[lane] : 0u;
+    const uint32_t head_u = lane < head ? first : 0u;          // the head is part of the row's leading 64 IDs, which the caller holds
     // First attempt with a guessed cut.  Keys are uniform 32-bit words, so about lambda = f + 4 sqrt(f) + 8 of the
     // row's keys fall below lambda / len: streaming with that cut from the start collects the few IDs that can be in
     // the sample and skips the first cut and the prunes of the exact procedure.  The guess never changes the result:
@@ -402,7 +402,11 @@ __device__ __forceinline__ void sample_long_row(const int32_t *__restrict__ row,
     __syncthreads();
     if (s.cnt >= f) break;                                       // (always, in the exact attempt: len > f)
   }
-    if (s.cnt > f) (void)prune_buffer<CAP>(buf, s.cnt, f, lo, hi, lane, s.open ? 0xFFFFFFFFu : s.cut);
+    if (s.cnt > f) {
+        const uint32_t upper = s.open ? 0xFFFFFFFFu : s.cut;
+        if (CAP > 64 && s.cnt <= 64) (void)prune_buffer<64>(buf, s.cnt, f, lo, hi, lane, upper);     // the usual case after a guessed cut: one ID per lane
+        else (void)prune_buffer<CAP>(buf, s.cnt, f, lo, hi, lane, upper);
+    }
 }
 
 // SAMPLE of a row of len > f IDs into out (row order), marking the bitmaps when MARK.
@@ -418,7 +422,7 @@ __device__ __forceinline__ void sample_row(const int32_t *__restrict__ row, int 
         const uint32_t u[4] = {first, ahead.x, ahead.y, ahead.z};
         sample_registers<4, MARK>(u, len, f, lo, hi, lane, out, reached_b);
     } else {
-        sample_long_row<CAP>(row, len, f, lo, hi, lane, buf, ahead);
+        sample_long_row<CAP>(row, len, first, f, lo, hi, lane, buf, ahead);
         for (int j = lane; j < f; j += 64) {
             const uint32_t u = buf[j];
             out[j] = (int32_t)u;
