@@ -325,6 +325,38 @@ __device__ __forceinline__ void stream_block(const u32x4 &blk, int count, int f,
     append_block<CAP, MAYBE_OPEN>(u, k, vm, f, lo, hi, lane, buf, s);
 }
 
+// A full block while a cut is in force, the common outcomes only: no candidate, or candidates that fit the buffer.
+// Returns false, with nothing done, when they do not fit; the caller then takes the block through append_block.
+template <int CAP>
+__device__ __forceinline__ bool stream_full_block_fast(const u32x4 &blk, uint32_t lo, uint32_t hi, int lane, uint32_t *buf, Stream &s)
+{
+    const uint32_t u[4] = {blk.x, blk.y, blk.z, blk.w};
+    const uint32_t cut = uni(s.cut);
+    s.cnt = uni(s.cnt);
+    unsigned long long m[4];
+#pragma unroll
+    for (int e = 0; e < 4; ++e) m[e] = ballot64(key32(lo, hi, u[e]) <= cut);
+    const unsigned long long any = m[0] | m[1] | m[2] | m[3];
+    if (any == 0ull) return true;
+    const int total = __popcll(m[0]) + __popcll(m[1]) + __popcll(m[2]) + __popcll(m[3]);
+    if (s.cnt + total > CAP) return false;
+    if (__popcll(any) == total) {
+        if (my_bit(any)) {
+            const uint32_t v = my_bit(m[0]) ? u[0] : my_bit(m[1]) ? u[1] : my_bit(m[2]) ? u[2] : u[3];
+            buf[s.cnt + lanes_below(any, lane)] = v;
+        }
+    } else {
+        int rank = s.cnt;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) rank += lanes_below(m[e], lane);
+#pragma unroll
+        for (int e = 0; e < 4; ++e)
+            if (my_bit(m[e])) buf[rank++] = u[e];
+    }
+    s.cnt += total;
+    return true;
+}
+
 // Row of len > 256 IDs streamed once; on return buf[0..f) is the sample in row order.  The IDs in
 // front of the first 128-byte boundary go first (one per lane); from there on the row is read in
 // blocks of 1 KB, one aligned 16-byte load per lane, so no two loads of a wave share a cache line,
@@ -389,6 +421,37 @@ __device__ __forceinline__ void sample_long_row(const int32_t *__restrict__ row,
         const uint32_t k[4] = {key32(lo, hi, u[0]), 0u, 0u, 0u};
         const unsigned long long vm[4] = {low_lanes(head), 0ull, 0ull, 0ull};
         append_block<CAP>(u, k, vm, f, lo, hi, lane, buf, s);
+    }
+    if (guess && rem >= 256) {
+        // The full blocks under the guessed cut, two in flight behind the one whose keys are computed: block j lives in
+        // register quartet j mod 3 and the loop is unrolled by three, so no block is copied from one quartet to another
+        // (a copy would have to wait for a load that has only just been issued).  Leaves at the first block it does not
+        // take -- the partial last one, or a full one whose candidates do not fit -- which the loop below picks up.
+        const int n_full = rem >> 8;
+        auto load = [&](int j) {                                                                   // block j < n_blocks
+            if (j < n_full) return *reinterpret_cast<const u32x4 *>(p + j * 256 + 4 * lane);
+            return load_block(p + j * 256, rem - j * 256, lane);
+        };
+        u32x4 r0 = cur, r1 = {0u, 0u, 0u, 0u}, r2 = {0u, 0u, 0u, 0u};
+        if (1 < n_blocks) r1 = load(1);
+        int c = 0;
+        for (;;) {
+            if (c + 2 < n_blocks) r2 = load(c + 2);
+            if (!stream_full_block_fast<CAP>(r0, lo, hi, lane, buf, s)) break;
+            c = uni(c + 1);
+            if (c >= n_full) break;
+            if (c + 2 < n_blocks) r0 = load(c + 2);
+            if (!stream_full_block_fast<CAP>(r1, lo, hi, lane, buf, s)) break;
+            c = uni(c + 1);
+            if (c >= n_full) break;
+            if (c + 2 < n_blocks) r1 = load(c + 2);
+            if (!stream_full_block_fast<CAP>(r2, lo, hi, lane, buf, s)) break;
+            c = uni(c + 1);
+            if (c >= n_full) break;
+        }
+        c0 = c;
+        const int which = c % 3;
+        cur = which == 0 ? r0 : which == 1 ? r1 : r2;            // (unused when c == n_blocks)
     }
     for (int c = uni(c0); c < n_blocks; c = uni(c + 1)) {
         const int left = uni(rem - c * 256);                     // IDs left, this block included
