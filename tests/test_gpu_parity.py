@@ -403,6 +403,47 @@ def test_few_listed_nodes_plan_without_the_route_table(case, rg, orc):
         assert st == orc.batch_stats(o, b, w.is_local.numpy(), slot)
 
 
+def test_rows_that_overflow_the_candidate_buffer_under_the_guessed_cut(rg, orc):
+    """Under the guessed cut a long row is expected to yield a few dozen candidates.  Rows built from IDs whose keys
+    (under the node's own state) lie below that cut by the hundred overflow the candidate buffer instead: at the very
+    first block, in the middle of the row, in its last blocks only, and by accumulation one past the buffer's size,
+    so the fast block loop is left at each of its three steps and the general path prunes and goes on."""
+    n, f, deg = 200000, 10, 1200
+    s0, wk, ep = 5, 0, 1
+    hs = orc.hop_state(orc.batch_seed(s0, wk, ep, 0), 0)
+    lam = f + 4.0 * np.sqrt(np.float32(f)) + 8.0
+    cut = int(np.float32(lam) / np.float32(deg) * np.float32(4294967296.0))
+    # (seed, number of low keys, ID range the low-key IDs come from)
+    plans = [(17, deg, (0, n)), (1234, 200, (150000, n)), (50001, 300, (80000, 120000)), (77777, 129, (0, n)), (99999, 128, (0, n)),
+             (31, 600, (0, 60000))]
+    rng = np.random.default_rng(5)
+    rows = [np.unique(rng.integers(0, n, 4)).astype(np.int32) for _ in range(n)]
+    for v, n_low, (a, b) in plans:
+        S = orc.node_state(hs, v)
+        keys = np.array([orc.key32(S, u) for u in range(n)], dtype=np.uint64)
+        cand = np.arange(n)
+        cand = cand[cand != v]
+        low = cand[(keys[cand] < cut // 2) & (cand >= a) & (cand < b)]
+        high = cand[(keys[cand] > (1 << 31)) & ((cand < a) | (cand >= b) | (b - a == n))]
+        assert low.size >= n_low and high.size >= deg - n_low, (v, low.size, high.size)
+        row = np.concatenate([rng.permutation(low)[:n_low], rng.permutation(high)[:deg - n_low]])
+        rows[v] = np.sort(row).astype(np.int32)
+        assert rows[v].size == deg
+    indptr = np.zeros(n + 1, np.int64)
+    indptr[1:] = np.cumsum([r.size for r in rows])
+    indices = np.concatenate(rows)
+    train = np.array([p[0] for p in plans] + [8, 9], dtype=np.int32)
+    dp, dx, dt = torch.from_numpy(indptr).cuda(), torch.from_numpy(indices).cuda(), torch.from_numpy(train).cuda()
+    assert rg.rg_graph_validate(dp, dx) == 0
+    g = rg.rg_build_schedule(dp, dx, dt, 100, [f], s0, wk, ep)
+    o = orc.Schedule(indptr, indices, train, 100, [f], s0, wk, ep)
+    assert_schedules_equal(rg, g, o)
+    # the rows are what they were built to be: far more keys below the guessed cut than the buffer holds
+    for v, n_low, _ in plans:
+        S = orc.node_state(hs, v)
+        assert sum(orc.key32(S, int(u)) <= cut for u in rows[v]) == n_low
+
+
 def test_rows_built_to_defeat_the_guessed_cut(rg, orc):
     """Long rows are first streamed with a cut guessed from the key distribution.  Rows made of IDs whose keys (under
     the node's own state) all lie above that cut, or with exactly f - 1, f and f + 1 keys below it, force the
