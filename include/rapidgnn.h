@@ -96,10 +96,14 @@ typedef struct rg_cache rg_cache;
  *   fanout       host, [L]; L <= RG_MAX_HOPS, fanout[l] <= RG_MAX_FANOUT; L may be 0
  *   a            allocator or NULL
  *   out          receives the handle
- * Scratch: two bitmaps of n_batches * n_nodes bits for the duration of the call.
+ * Scratch, for the duration of the call: a bitmap of n_batches * n_nodes bits and
+ * a map of the IDs a hop reaches, n_batches * n_nodes bytes if that is at most
+ * 2 GiB (marks are then plain stores), else as many bits (marks are atomic ORs).
  * Environment: RAPIDGNN_SPARSE_FRONTIER=1 / 0 forces / forbids the frontier
  * passes tuned for graphs of 10^7 nodes and more (default: chosen from
- * n_nodes); the result is the same either way.
+ * n_nodes); RAPIDGNN_BYTE_MAPS=1 / 0 forces / forbids the byte form of the
+ * reached map (never used together with those passes).  The result is the
+ * same in every case.
  */
 rg_status rg_build_schedule(const rg_graph *g, const int32_t *train_nodes, uint64_t T,
                             uint32_t batch_size, const uint32_t *fanout, uint32_t L,

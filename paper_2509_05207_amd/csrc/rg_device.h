@@ -105,28 +105,44 @@ __device__ __forceinline__ uint32_t batch_of(const int64_t *__restrict__ off, ui
     return lo;
 }
 
-// ---------------------------------------------------------------- reached-ID bitmaps
-// Every sampled ID sets its bit in the batch's `reached` bitmap.  The OR needs no return value, so
-// the wave never waits for it; which of the reached IDs are new to the batch is decided afterwards,
-// word by word, against the batch's `seen` bitmap.  Beside the bitmap there is one flag byte per
-// eight words (256 IDs): the frontier passes read the flags and touch only the flagged words, which
-// on a graph of 10^8 nodes is a few per cent of the bitmap.
-struct ReachedMaps {
+// ---------------------------------------------------------------- reached-ID maps
+// Every sampled ID is marked in the batch's `reached` map; which of the reached IDs are new to the batch is decided
+// afterwards, group by group, against the batch's `seen` bitmap.  The map comes in two forms.  As a byte per node ID,
+// where a mark is a plain store of 1: nothing is read, nothing is atomic, and the memory system takes three to five
+// times as many of them per second as of the other form -- but the map is eight times as large and its scattered
+// stores reach memory as whole lines.  As a bit per node ID, where a mark is an atomic OR without return value.  The
+// wave waits for neither; a hop uses the form that suits its traffic (see sample_hop).  Beside the map there is one
+// flag byte per 256 IDs: the frontier passes read the flags and touch only the flagged groups, which on a graph of
+// 10^8 nodes is a few per cent of the map.
+constexpr int MARK_NONE = 0, MARK_BITS = 1, MARK_BYTES = 2;     // what a kernel does with a sampled ID (a template argument)
+struct ReachedForms {             // host side: the forms a schedule build holds
     uint32_t *words;              // [n_batches * words_per_batch]
+    uint8_t *bytes;               // [n_batches * words_per_batch * 32]; NULL until the first hop that wants it
     uint8_t *flags;               // [n_batches * words_per_batch / 8]
     uint64_t words_per_batch;     // a multiple of 8
+    bool bytes_allowed;           // the byte form is small enough to be worth having
+};
+struct ReachedMaps {              // the form one hop marks
+    void *map;
+    uint8_t *flags;
+    uint64_t words_per_batch;
 };
 struct ReachedOfBatch {
-    uint32_t *words;
+    void *map;
     uint8_t *flags;
 };
+template <int MARK>
 __device__ __forceinline__ ReachedOfBatch reached_of(const ReachedMaps &m, uint32_t batch)
 {
-    return ReachedOfBatch{m.words + (uint64_t)batch * m.words_per_batch, m.flags + (uint64_t)batch * (m.words_per_batch >> 3)};
+    const uint64_t step = MARK == MARK_BYTES ? m.words_per_batch << 5 : m.words_per_batch << 2;       // bytes per batch
+    return ReachedOfBatch{static_cast<uint8_t *>(m.map) + (uint64_t)batch * step, m.flags + (uint64_t)batch * (m.words_per_batch >> 3)};
 }
+template <int MARK>
 __device__ __forceinline__ void mark_reached(const ReachedOfBatch &r, uint32_t u)
 {
-    (void)__hip_atomic_fetch_or(&r.words[u >> 5], 1u << (u & 31), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    if (MARK == MARK_NONE) return;
+    if (MARK == MARK_BYTES) static_cast<uint8_t *>(r.map)[u] = 1;
+    else (void)__hip_atomic_fetch_or(static_cast<uint32_t *>(r.map) + (u >> 5), 1u << (u & 31), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     r.flags[u >> 8] = 1;
 }
 

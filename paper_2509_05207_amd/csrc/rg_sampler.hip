@@ -71,6 +71,18 @@ __global__ void node_records_kernel(const int64_t *__restrict__ indptr, const in
     tiles[i] = (int32_t)tiles_of(deg);
 }
 
+// total += sum of deg[0..n): what the hop will read of the adjacency, in IDs
+__global__ void __launch_bounds__(256) sum_degrees_kernel(const int32_t *__restrict__ deg, int64_t n, unsigned long long *__restrict__ total)
+{
+    __shared__ unsigned long long part[4];
+    unsigned long long acc = 0;
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (int64_t)gridDim.x * blockDim.x) acc += (unsigned long long)(uint32_t)deg[i];
+    for (int o = 32; o > 0; o >>= 1) acc += __shfl_down(acc, o, 64);
+    if ((threadIdx.x & 63) == 0) part[threadIdx.x >> 6] = acc;
+    __syncthreads();
+    if (threadIdx.x == 0) atomicAdd(total, part[0] + part[1] + part[2] + part[3]);
+}
+
 // Number of set bits of m below this lane's bit (m wave-uniform): the two mbcnt instructions.
 __device__ __forceinline__ int lanes_below(unsigned long long m, int lane)
 {
@@ -134,7 +146,7 @@ __device__ __forceinline__ uint32_t kth_key_threshold(const uint32_t (&k)[E], co
 
 // Row of f < len <= 64 * E IDs held in registers (u[e] of lane l is row[e * 64 + l]),
 // sampled and written to out in row order.
-template <int E, bool MARK>
+template <int E, int MARK>
 __device__ __forceinline__ void sample_registers(const uint32_t (&u)[E], int len, int f, uint32_t lo, uint32_t hi, int lane,
                                                  int32_t *__restrict__ out, const ReachedOfBatch &reached_b)
 {
@@ -153,7 +165,7 @@ __device__ __forceinline__ void sample_registers(const uint32_t (&u)[E], int len
         const unsigned long long m = ballot64(k[e] <= cut) & vm[e];
         if (e * 64 + lane < len && k[e] <= cut) {
             out[base + lanes_below(m, lane)] = (int32_t)u[e];
-            if (MARK) mark_reached(reached_b, u[e]);
+            mark_reached<MARK>(reached_b, u[e]);
         }
         base += __popcll(m);
     }
@@ -472,9 +484,9 @@ __device__ __forceinline__ void sample_long_row(const int32_t *__restrict__ row,
     }
 }
 
-// SAMPLE of a row of len > f IDs into out (row order), marking the bitmaps when MARK.
+// SAMPLE of a row of len > f IDs into out (row order), marking the sampled IDs as MARK says.
 // `first` holds row[lane] for lane < len; ahead = row_ahead(row, len, lane) when len > 64 (unused otherwise).
-template <int CAP, bool MARK>
+template <int CAP, int MARK>
 __device__ __forceinline__ void sample_row(const int32_t *__restrict__ row, int len, uint32_t first, const u32x4 &ahead, int f, uint32_t lo, uint32_t hi,
                                            int lane, uint32_t *buf, int32_t *__restrict__ out, const ReachedOfBatch &reached_b)
 {
@@ -489,7 +501,7 @@ __device__ __forceinline__ void sample_row(const int32_t *__restrict__ row, int 
         for (int j = lane; j < f; j += 64) {
             const uint32_t u = buf[j];
             out[j] = (int32_t)u;
-            if (MARK) mark_reached(reached_b, u);
+            mark_reached<MARK>(reached_b, u);
         }
         __syncthreads();      // the buffer is reused by the wave's next row
     }
@@ -543,7 +555,7 @@ __device__ __forceinline__ int64_t grab_work(unsigned long long *counter, int la
 
 // Work items [0, n_tiles) are tiles of long rows (handed out first, so the longest-running work starts first);
 // item n_tiles + c is the c-th group of 64 consecutive frontier nodes.
-template <int CAP>
+template <int CAP, int MARK>
 __global__ void __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(CAP <= 256 ? 7 : 1))) sample_kernel(HopArgs a)
 {
     __shared__ uint32_t buf[CAP];
@@ -558,8 +570,8 @@ __global__ void __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(CAP <= 
             const int32_t *row = a.indices + a.tile.begin[w];
             const int len = a.tile.len[w];
             const uint64_t S = a.rec.state[a.tile.node[w]];
-            sample_row<CAP, false>(row, len, (uint32_t)row[lane], row_ahead(row, len, lane), f, (uint32_t)S, (uint32_t)(S >> 32), lane, buf,
-                                   a.tile_out + w * f, ReachedOfBatch{nullptr, nullptr});
+            sample_row<CAP, MARK_NONE>(row, len, (uint32_t)row[lane], row_ahead(row, len, lane), f, (uint32_t)S, (uint32_t)(S >> 32), lane, buf,
+                                       a.tile_out + w * f, ReachedOfBatch{nullptr, nullptr});
             continue;
         }
         const int64_t i_lane = ((w - a.n_tiles) << 6) + lane;
@@ -592,19 +604,19 @@ __global__ void __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(CAP <= 
                 if (deg > 64 && deg > f) ahead = row_ahead(a.indices + rb, deg, lane);
             }
             const uint32_t b = (uint32_t)__builtin_amdgcn_readlane((int)b_lane, cl);
-            const ReachedOfBatch reached_b = reached_of(a.reached, b);
+            const ReachedOfBatch reached_b = reached_of<MARK>(a.reached, b);
             const int32_t *row = a.indices + crb;
             int32_t *out = a.samp_nbr + bcast64(out_lane, cl);
             if (cdeg <= f) {                  // the whole row is the sample
-                if (lane < cdeg) { out[lane] = (int32_t)cfirst; mark_reached(reached_b, cfirst); }
+                if (lane < cdeg) { out[lane] = (int32_t)cfirst; mark_reached<MARK>(reached_b, cfirst); }
                 for (int j = 64 + lane; j < cdeg; j += 64) {
                     const int32_t u = row[j];
                     out[j] = u;
-                    mark_reached(reached_b, (uint32_t)u);
+                    mark_reached<MARK>(reached_b, (uint32_t)u);
                 }
             } else {
                 const uint64_t S = (uint64_t)bcast64(S_lane, cl);
-                sample_row<CAP, true>(row, cdeg, cfirst, cahead, f, (uint32_t)S, (uint32_t)(S >> 32), lane, buf, out, reached_b);
+                sample_row<CAP, MARK>(row, cdeg, cfirst, cahead, f, (uint32_t)S, (uint32_t)(S >> 32), lane, buf, out, reached_b);
             }
         }
     }
@@ -612,7 +624,7 @@ __global__ void __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(CAP <= 
 
 // One wave per tile job; the wave that holds a long row's first tile samples the row's
 // concatenated tile results (T * f IDs, row order, all distinct) into the final output.
-template <int CAP>
+template <int CAP, int MARK>
 __global__ void __launch_bounds__(64) sample_merge_kernel(HopArgs a)
 {
     __shared__ uint32_t buf[CAP];
@@ -628,22 +640,23 @@ __global__ void __launch_bounds__(64) sample_merge_kernel(HopArgs a)
         const int len = (int)(T * f);
         u32x4 ahead = {0u, 0u, 0u, 0u};
         if (len > 64) ahead = row_ahead(row, len, lane);
-        sample_row<CAP, true>(row, len, lane < len ? (uint32_t)row[lane] : 0u, ahead, f, (uint32_t)S, (uint32_t)(S >> 32), lane, buf,
-                              a.samp_nbr + a.samp_off[i], reached_of(a.reached, b));
+        sample_row<CAP, MARK>(row, len, lane < len ? (uint32_t)row[lane] : 0u, ahead, f, (uint32_t)S, (uint32_t)(S >> 32), lane, buf,
+                              a.samp_nbr + a.samp_off[i], reached_of<MARK>(a.reached, b));
     }
 }
 
-template <int CAP>
+template <int CAP, int MARK>
 static void launch_hop(const HopArgs &a, unsigned grid, unsigned merge_grid, hipStream_t st)
 {
-    hipLaunchKernelGGL(sample_kernel<CAP>, dim3(grid), dim3(64), 0, st, a);
-    if (a.n_tiles > 0) hipLaunchKernelGGL(sample_merge_kernel<CAP>, dim3(merge_grid), dim3(64), 0, st, a);
+    hipLaunchKernelGGL((sample_kernel<CAP, MARK>), dim3(grid), dim3(64), 0, st, a);
+    if (a.n_tiles > 0) hipLaunchKernelGGL((sample_merge_kernel<CAP, MARK>), dim3(merge_grid), dim3(64), 0, st, a);
 }
 
 // The O(f) sampler: one lane per sampled edge.  A node with deg <= f copies its row; otherwise lane t reads the
 // row at its drawn position (rg_device.h) and nothing else of the row.  Lanes of a workgroup are dealt to
 // (node, draw) pairs: 256 / f nodes per round when f < 256, one node per round otherwise.
 constexpr int POS_THREADS = 256;
+template <int MARK>
 __global__ void __launch_bounds__(POS_THREADS) sample_positions_kernel(const int32_t *__restrict__ indices, NodeRecs rec, int64_t n_cur, uint32_t f,
                                                                        const int64_t *__restrict__ samp_off, int32_t *__restrict__ samp_nbr,
                                                                        ReachedMaps reached)
@@ -660,19 +673,23 @@ __global__ void __launch_bounds__(POS_THREADS) sample_positions_kernel(const int
         const int32_t *row = indices + rec.row_begin[i];
         const uint64_t S = rec.state[i];
         int32_t *out = samp_nbr + samp_off[i];
-        const ReachedOfBatch reached_b = reached_of(reached, rec.batch[i]);
+        const ReachedOfBatch reached_b = reached_of<MARK>(reached, rec.batch[i]);
         for (uint32_t t = t0; t < cnt; t += step) {
             const uint32_t p = deg <= f ? t : draw_position(deg, t, S);
             const int32_t u = row[p];
             out[t] = u;
-            mark_reached(reached_b, (uint32_t)u);
+            mark_reached<MARK>(reached_b, (uint32_t)u);
         }
     }
 }
 
 // Samples hop `hop` of every batch: fills cur.samp_off / samp_nbr / n_samples and marks the reached-ID bitmaps.
+// Where `maps` allows the reached map's byte form, the hop marks into whichever form suits it (see below; the byte
+// map is allocated, clear, by the first hop that wants it) and *marked_bytes says which, so that the frontier pass
+// reads the right one.
 rg_status sample_hop(const rg_graph *g, HopData &cur, uint32_t beta, const uint64_t *batch_seed, uint32_t hop, uint32_t fanout,
-                     uint32_t sampler, const ReachedMaps &reached, Arena &keep, Arena &tmp, int n_cu, hipStream_t st)
+                     uint32_t sampler, ReachedForms &maps, int prefer_bytes, bool *marked_bytes, Arena &keep, Arena &tmp, int n_cu,
+                     hipStream_t st)
 {
     const int64_t n_cur = cur.off_host[beta];
     int32_t *cnt = nullptr, *tiles = nullptr;
@@ -694,9 +711,32 @@ rg_status sample_hop(const rg_graph *g, HopData &cur, uint32_t beta, const uint6
         RG_TRY(scan_i32_to_i64(tiles, tile_off, n_cur, tmp, st));
     }
     int64_t n_tiles = 0;
+    unsigned long long sum_deg = 0, *sum_deg_dev = nullptr;
+    // (the byte-marking kernels exist for fan-outs up to 192: the two smaller candidate buffers)
+    const bool can_bytes = maps.bytes_allowed && (sampler == RG_SAMPLER_POSITIONS || fanout + 64 <= 256);
+    if (can_bytes && prefer_bytes < 0) {
+        RG_TRY(tmp.dev_n<unsigned long long>(1, &sum_deg_dev));
+        RG_HIP(hipMemsetAsync(sum_deg_dev, 0, sizeof(unsigned long long), st));
+        if (n_cur > 0)
+            hipLaunchKernelGGL(sum_degrees_kernel, dim3((unsigned)std::min<int64_t>((n_cur + 255) / 256, 1024)), dim3(256), 0, st, rec.deg, n_cur, sum_deg_dev);
+        RG_HIP(hipMemcpyAsync(&sum_deg, sum_deg_dev, sizeof(unsigned long long), hipMemcpyDeviceToHost, st));
+    }
     RG_HIP(hipMemcpyAsync(&cur.n_samples, cur.samp_off + n_cur, sizeof(int64_t), hipMemcpyDeviceToHost, st));
     RG_HIP(hipMemcpyAsync(&n_tiles, tile_off + n_cur, sizeof(int64_t), hipMemcpyDeviceToHost, st));
     RG_HIP(hipStreamSynchronize(st));
+    // Which form of the reached map this hop marks.  A byte store is several times cheaper than an atomic OR, but the
+    // byte map is 8 times the size and its scattered stores reach memory as whole lines; that pays where marks are a
+    // large part of the hop's traffic (rows mostly no longer than the fan-out: one mark per ID read), and costs a
+    // little where long rows are scanned for a few samples (measured: at one mark per 20 IDs read nothing is gained,
+    // at one per 10 the hop is a quarter faster).  Threshold: one mark per 14 IDs read.
+    const bool use_bytes = can_bytes && (prefer_bytes >= 0 ? prefer_bytes != 0 : (unsigned long long)cur.n_samples * 14ull >= sum_deg);
+    if (use_bytes && !maps.bytes) {
+        const uint64_t map_bytes = maps.words_per_batch * 32 * (uint64_t)beta;
+        RG_TRY(tmp.dev_n<uint8_t>(map_bytes, &maps.bytes));
+        RG_HIP(hipMemsetAsync(maps.bytes, 0, map_bytes, st));
+    }
+    *marked_bytes = use_bytes;
+    const ReachedMaps reached{use_bytes ? (void *)maps.bytes : (void *)maps.words, maps.flags, maps.words_per_batch};
     tmp.free_one(cnt);
     tmp.free_one(tiles);
     RG_TRY(keep.dev_n<int32_t>((uint64_t)cur.n_samples, &cur.samp_nbr));
@@ -705,8 +745,12 @@ rg_status sample_hop(const rg_graph *g, HopData &cur, uint32_t beta, const uint6
             ScopedTimer tm(KG_SAMPLER, st);
             const int64_t per_round = fanout >= (uint32_t)POS_THREADS ? 1 : POS_THREADS / fanout;
             const unsigned grid = (unsigned)std::max<int64_t>(1, std::min<int64_t>((n_cur + per_round - 1) / per_round, (int64_t)n_cu * 64));
-            hipLaunchKernelGGL(sample_positions_kernel, dim3(grid), dim3(POS_THREADS), 0, st, g->indices, rec, n_cur, fanout, cur.samp_off, cur.samp_nbr,
-                               reached);
+            if (use_bytes)
+                hipLaunchKernelGGL(sample_positions_kernel<MARK_BYTES>, dim3(grid), dim3(POS_THREADS), 0, st, g->indices, rec, n_cur, fanout, cur.samp_off,
+                                   cur.samp_nbr, reached);
+            else
+                hipLaunchKernelGGL(sample_positions_kernel<MARK_BITS>, dim3(grid), dim3(POS_THREADS), 0, st, g->indices, rec, n_cur, fanout, cur.samp_off,
+                                   cur.samp_nbr, reached);
             RG_HIP(hipGetLastError());
         }
         return RG_OK;
@@ -733,11 +777,11 @@ rg_status sample_hop(const rg_graph *g, HopData &cur, uint32_t beta, const uint6
         const unsigned grid = (unsigned)std::max<int64_t>(1, std::min<int64_t>(n_work, (int64_t)n_cu * 32));     // as many waves as fit on the chip
         const unsigned merge_grid = (unsigned)std::max<int64_t>(1, std::min<int64_t>(n_tiles, (int64_t)n_cu * 64));
         const uint32_t need = fanout + 64;
-        if (need <= 128) launch_hop<128>(a, grid, merge_grid, st);
-        else if (need <= 256) launch_hop<256>(a, grid, merge_grid, st);
-        else if (need <= 512) launch_hop<512>(a, grid, merge_grid, st);
-        else if (need <= 1024) launch_hop<1024>(a, grid, merge_grid, st);
-        else launch_hop<2048>(a, grid, merge_grid, st);
+        if (need <= 128) { if (use_bytes) launch_hop<128, MARK_BYTES>(a, grid, merge_grid, st); else launch_hop<128, MARK_BITS>(a, grid, merge_grid, st); }
+        else if (need <= 256) { if (use_bytes) launch_hop<256, MARK_BYTES>(a, grid, merge_grid, st); else launch_hop<256, MARK_BITS>(a, grid, merge_grid, st); }
+        else if (need <= 512) launch_hop<512, MARK_BITS>(a, grid, merge_grid, st);
+        else if (need <= 1024) launch_hop<1024, MARK_BITS>(a, grid, merge_grid, st);
+        else launch_hop<2048, MARK_BITS>(a, grid, merge_grid, st);
         RG_HIP(hipGetLastError());
     }
     return RG_OK;

@@ -20,7 +20,7 @@
 namespace rg {
 
 rg_status sample_hop(const rg_graph *g, HopData &cur, uint32_t beta, const uint64_t *batch_seed, uint32_t hop, uint32_t fanout, uint32_t sampler,
-                     const ReachedMaps &reached, Arena &keep, Arena &tmp, int n_cu, hipStream_t st);
+                     ReachedForms &maps, int prefer_bytes, bool *marked_bytes, Arena &keep, Arena &tmp, int n_cu, hipStream_t st);
 
 // ---------------------------------------------------------------- a1/a2: seeds, shuffle keys
 __global__ void batch_seeds_kernel(uint64_t s0, uint32_t worker, uint32_t epoch, uint32_t n_batches, uint64_t *__restrict__ seeds)
@@ -115,8 +115,46 @@ constexpr int FR_THREADS = 256;
 constexpr int FR_WORDS_PER_THREAD = 8;
 constexpr int FR_CHUNK_WORDS = FR_THREADS * FR_WORDS_PER_THREAD;     // 2048 words = 65536 node IDs per block
 
+// The reached bits of one group of 256 IDs (eight words).  BYTES: from the byte map, where every ID has a byte that
+// is 0 or 1: four such bytes in a dword d become four bits by one multiply ((d * 0x00204081) >> 21 puts byte k's bit
+// at position k; the partial products below bit 21 sum to less than 2^17, so nothing carries in).
+template <bool BYTES>
+__device__ __forceinline__ void load_reached_group(const void *reached, uint64_t at, uint32_t (&r)[8])
+{
+    if (!BYTES) {
+        const uint32_t *p = static_cast<const uint32_t *>(reached) + at;
+        const uint4 r0 = *reinterpret_cast<const uint4 *>(p), r1 = *reinterpret_cast<const uint4 *>(p + 4);
+        r[0] = r0.x; r[1] = r0.y; r[2] = r0.z; r[3] = r0.w; r[4] = r1.x; r[5] = r1.y; r[6] = r1.z; r[7] = r1.w;
+    } else {
+        const uint4 *p = reinterpret_cast<const uint4 *>(static_cast<const uint8_t *>(reached) + (at << 5));       // 256 bytes
+#pragma unroll
+        for (int k = 0; k < 8; ++k) {
+            const uint4 a = p[2 * k], b = p[2 * k + 1];
+            const uint32_t d[8] = {a.x, a.y, a.z, a.w, b.x, b.y, b.z, b.w};
+            uint32_t w = 0;
+#pragma unroll
+            for (int q = 0; q < 8; ++q) w |= ((d[q] * 0x00204081u >> 21) & 0xFu) << (4 * q);
+            r[k] = w;
+        }
+    }
+}
+template <bool BYTES>
+__device__ __forceinline__ void clear_reached_group(void *reached, uint64_t at)
+{
+    if (!BYTES) {
+        uint32_t *p = static_cast<uint32_t *>(reached) + at;
+        *reinterpret_cast<uint4 *>(p) = make_uint4(0, 0, 0, 0);
+        *reinterpret_cast<uint4 *>(p + 4) = make_uint4(0, 0, 0, 0);
+    } else {
+        uint4 *p = reinterpret_cast<uint4 *>(static_cast<uint8_t *>(reached) + (at << 5));
+#pragma unroll
+        for (int k = 0; k < 16; ++k) p[k] = make_uint4(0, 0, 0, 0);
+    }
+}
+
 // cnt[b * chunks + c] = number of fresh IDs (reached and not yet seen) of batch b in chunk c
-__global__ void __launch_bounds__(FR_THREADS) fresh_count_kernel(const uint32_t *__restrict__ reached, const uint8_t *__restrict__ flags,
+template <bool BYTES>
+__global__ void __launch_bounds__(FR_THREADS) fresh_count_kernel(const void *__restrict__ reached, const uint8_t *__restrict__ flags,
                                                                  const uint32_t *__restrict__ seen, uint64_t words_per_batch, uint32_t chunks,
                                                                  int32_t *__restrict__ cnt)
 {
@@ -126,11 +164,12 @@ __global__ void __launch_bounds__(FR_THREADS) fresh_count_kernel(const uint32_t 
     int n = 0;
     if (w0 < words_per_batch) {      // words_per_batch is a multiple of FR_WORDS_PER_THREAD; a thread's words are one flag's group
         const uint64_t at = (uint64_t)b * words_per_batch + w0;
-        if (flags[at >> 3]) {        // on big graphs most groups were not reached: neither bitmap is read there
-            const uint4 r0 = *reinterpret_cast<const uint4 *>(reached + at), r1 = *reinterpret_cast<const uint4 *>(reached + at + 4);
+        if (flags[at >> 3]) {        // on big graphs most groups were not reached: neither map is read there
+            uint32_t r[8];
+            load_reached_group<BYTES>(reached, at, r);
             const uint4 s0 = *reinterpret_cast<const uint4 *>(seen + at), s1 = *reinterpret_cast<const uint4 *>(seen + at + 4);
-            n = __popc(r0.x & ~s0.x) + __popc(r0.y & ~s0.y) + __popc(r0.z & ~s0.z) + __popc(r0.w & ~s0.w) +
-                __popc(r1.x & ~s1.x) + __popc(r1.y & ~s1.y) + __popc(r1.z & ~s1.z) + __popc(r1.w & ~s1.w);
+            n = __popc(r[0] & ~s0.x) + __popc(r[1] & ~s0.y) + __popc(r[2] & ~s0.z) + __popc(r[3] & ~s0.w) +
+                __popc(r[4] & ~s1.x) + __popc(r[5] & ~s1.y) + __popc(r[6] & ~s1.z) + __popc(r[7] & ~s1.w);
         }
     }
     for (int o = 32; o > 0; o >>= 1) n += __shfl_down(n, o, 64);
@@ -158,7 +197,8 @@ __global__ void copy_prefix_kernel(const int32_t *__restrict__ cur, const int64_
 
 // Writes the fresh IDs of (batch, chunk) in ascending order behind the batch's old frontier, adds
 // the reached IDs to `seen` and clears `reached` for the next hop.
-__global__ void __launch_bounds__(FR_THREADS) fresh_emit_kernel(uint32_t *__restrict__ reached, uint8_t *__restrict__ flags, uint32_t *__restrict__ seen,
+template <bool BYTES>
+__global__ void __launch_bounds__(FR_THREADS) fresh_emit_kernel(void *__restrict__ reached, uint8_t *__restrict__ flags, uint32_t *__restrict__ seen,
                                                                 uint64_t words_per_batch, uint32_t chunks, const int64_t *__restrict__ fresh_scan,
                                                                 const int64_t *__restrict__ cur_off, int32_t *__restrict__ next)
 {
@@ -172,18 +212,18 @@ __global__ void __launch_bounds__(FR_THREADS) fresh_emit_kernel(uint32_t *__rest
     if (w0 < words_per_batch) {
         const uint64_t at = (uint64_t)b * words_per_batch + w0;
         if (flags[at >> 3]) {
-            const uint4 r0 = *reinterpret_cast<const uint4 *>(reached + at), r1 = *reinterpret_cast<const uint4 *>(reached + at + 4);
+            uint32_t r[8];
+            load_reached_group<BYTES>(reached, at, r);
             const uint4 s0 = *reinterpret_cast<const uint4 *>(seen + at), s1 = *reinterpret_cast<const uint4 *>(seen + at + 4);
-            w[0] = r0.x & ~s0.x; w[1] = r0.y & ~s0.y; w[2] = r0.z & ~s0.z; w[3] = r0.w & ~s0.w;
-            w[4] = r1.x & ~s1.x; w[5] = r1.y & ~s1.y; w[6] = r1.z & ~s1.z; w[7] = r1.w & ~s1.w;
+            w[0] = r[0] & ~s0.x; w[1] = r[1] & ~s0.y; w[2] = r[2] & ~s0.z; w[3] = r[3] & ~s0.w;
+            w[4] = r[4] & ~s1.x; w[5] = r[5] & ~s1.y; w[6] = r[6] & ~s1.z; w[7] = r[7] & ~s1.w;
 #pragma unroll
             for (int k = 0; k < FR_WORDS_PER_THREAD; ++k) n += __popc(w[k]);
             if (n) {
-                *reinterpret_cast<uint4 *>(seen + at) = make_uint4(s0.x | r0.x, s0.y | r0.y, s0.z | r0.z, s0.w | r0.w);
-                *reinterpret_cast<uint4 *>(seen + at + 4) = make_uint4(s1.x | r1.x, s1.y | r1.y, s1.z | r1.z, s1.w | r1.w);
+                *reinterpret_cast<uint4 *>(seen + at) = make_uint4(s0.x | r[0], s0.y | r[1], s0.z | r[2], s0.w | r[3]);
+                *reinterpret_cast<uint4 *>(seen + at + 4) = make_uint4(s1.x | r[4], s1.y | r[5], s1.z | r[6], s1.w | r[7]);
             }
-            *reinterpret_cast<uint4 *>(reached + at) = make_uint4(0, 0, 0, 0);
-            *reinterpret_cast<uint4 *>(reached + at + 4) = make_uint4(0, 0, 0, 0);
+            clear_reached_group<BYTES>(reached, at);
             flags[at >> 3] = 0;
         }
     }
@@ -392,15 +432,24 @@ static rg_status build_schedule_impl(const rg_graph *g, const int32_t *train, ui
     if (const char *force = getenv("RAPIDGNN_SPARSE_FRONTIER")) sparse_maps = force[0] == '1';   // same results either way; for tests and tuning
     const uint32_t chunk_words = sparse_maps ? FRS_CHUNK_WORDS : FR_CHUNK_WORDS;
     const uint32_t chunks = (uint32_t)((wpb + chunk_words - 1) / chunk_words);
-    uint32_t *seen = nullptr, *reached = nullptr;
-    uint8_t *reached_flags = nullptr;                  // one byte per 8-word group of `reached`
+    // `reached` always as a bit per ID; where a byte per ID stays within the last-level cache's size (256 MB) a hop
+    // may mark that form instead (sample_hop decides, and allocates it at the first such hop).  Both start out clear
+    // and every hop's frontier pass clears what the hop marked.
+    bool byte_map = !sparse_maps && wpb * 32 * (uint64_t)beta <= ((uint64_t)256 << 20);
+    int prefer_bytes = -1;                             // -1: by the hop's own figures
+    if (const char *force = getenv("RAPIDGNN_BYTE_MAPS")) {     // same results either way; for tests and tuning
+        prefer_bytes = force[0] == '1';
+        byte_map = prefer_bytes && !sparse_maps;
+    }
+    uint32_t *seen = nullptr, *reached_words = nullptr;
+    uint8_t *reached_flags = nullptr;                  // one byte per group of 256 IDs of `reached`
     RG_TRY(tmp.dev_n<uint32_t>(wpb * beta, &seen));
-    RG_TRY(tmp.dev_n<uint32_t>(wpb * beta, &reached));
-    RG_TRY(tmp.dev_n<uint8_t>(wpb / FR_WORDS_PER_THREAD * beta, &reached_flags));
     RG_HIP(hipMemsetAsync(seen, 0, wpb * beta * sizeof(uint32_t), st));
-    RG_HIP(hipMemsetAsync(reached, 0, wpb * beta * sizeof(uint32_t), st));
+    RG_TRY(tmp.dev_n<uint32_t>(wpb * beta, &reached_words));
+    RG_HIP(hipMemsetAsync(reached_words, 0, wpb * beta * sizeof(uint32_t), st));
+    RG_TRY(tmp.dev_n<uint8_t>(wpb / FR_WORDS_PER_THREAD * beta, &reached_flags));
     RG_HIP(hipMemsetAsync(reached_flags, 0, wpb / FR_WORDS_PER_THREAD * beta, st));
-    const ReachedMaps maps{reached, reached_flags, wpb};
+    ReachedForms maps{reached_words, nullptr, reached_flags, wpb, byte_map};
     {
         ScopedTimer tm(KG_FRONTIER, st);
         hipLaunchKernelGGL(mark_seeds_kernel, dim3((unsigned)((T + 255) / 256)), dim3(256), 0, st, h0.ids, T, B, seen, wpb);
@@ -421,16 +470,20 @@ static rg_status build_schedule_impl(const rg_graph *g, const int32_t *train, ui
         const int64_t n_cur = cur.off_host[beta];
 
         // a3: the samples of this hop; sampled IDs are marked in `reached` as they are written
-        RG_TRY(sample_hop(g, cur, beta, batch_seed, l, fanout[l], sampler, maps, s->arena, tmp, n_cu, st));
+        bool marked_bytes = false;
+        RG_TRY(sample_hop(g, cur, beta, batch_seed, l, fanout[l], sampler, maps, prefer_bytes, &marked_bytes, s->arena, tmp, n_cu, st));
+        void *reached = marked_bytes ? (void *)maps.bytes : (void *)reached_words;
 
         // a4: fresh IDs per (batch, chunk) -> positions -> next frontier
         RG_TRY(s->arena.dev_n<int64_t>((uint64_t)beta + 1, &nxt.off_dev));
         {
             ScopedTimer tm(KG_FRONTIER, st);
             if (sparse_maps)
-                hipLaunchKernelGGL(fresh_count_sparse_kernel, dim3(chunks, beta), dim3(FR_THREADS), 0, st, reached, reached_flags, seen, wpb, chunks, fresh_cnt);
+                hipLaunchKernelGGL(fresh_count_sparse_kernel, dim3(chunks, beta), dim3(FR_THREADS), 0, st, reached_words, reached_flags, seen, wpb, chunks, fresh_cnt);
+            else if (marked_bytes)
+                hipLaunchKernelGGL(fresh_count_kernel<true>, dim3(chunks, beta), dim3(FR_THREADS), 0, st, reached, reached_flags, seen, wpb, chunks, fresh_cnt);
             else
-                hipLaunchKernelGGL(fresh_count_kernel, dim3(chunks, beta), dim3(FR_THREADS), 0, st, reached, reached_flags, seen, wpb, chunks, fresh_cnt);
+                hipLaunchKernelGGL(fresh_count_kernel<false>, dim3(chunks, beta), dim3(FR_THREADS), 0, st, reached, reached_flags, seen, wpb, chunks, fresh_cnt);
             RG_TRY(scan_i32_to_i64(fresh_cnt, fresh_scan, (int64_t)n_cells, tmp, st));
             hipLaunchKernelGGL(next_offsets_kernel, dim3((beta + 1 + 255) / 256), dim3(256), 0, st, cur.off_dev, fresh_scan, beta, chunks, nxt.off_dev);
         }
@@ -443,9 +496,11 @@ static rg_status build_schedule_impl(const rg_graph *g, const int32_t *train, ui
             ScopedTimer tm(KG_FRONTIER, st);
             hipLaunchKernelGGL(copy_prefix_kernel, dim3((unsigned)((n_cur + 255) / 256)), dim3(256), 0, st, cur.ids, cur.off_dev, nxt.off_dev, beta, n_cur, nxt.ids);
             if (sparse_maps)
-                hipLaunchKernelGGL(fresh_emit_sparse_kernel, dim3(chunks, beta), dim3(FR_THREADS), 0, st, reached, reached_flags, seen, wpb, chunks, fresh_scan, cur.off_dev, nxt.ids);
+                hipLaunchKernelGGL(fresh_emit_sparse_kernel, dim3(chunks, beta), dim3(FR_THREADS), 0, st, reached_words, reached_flags, seen, wpb, chunks, fresh_scan, cur.off_dev, nxt.ids);
+            else if (marked_bytes)
+                hipLaunchKernelGGL(fresh_emit_kernel<true>, dim3(chunks, beta), dim3(FR_THREADS), 0, st, reached, reached_flags, seen, wpb, chunks, fresh_scan, cur.off_dev, nxt.ids);
             else
-                hipLaunchKernelGGL(fresh_emit_kernel, dim3(chunks, beta), dim3(FR_THREADS), 0, st, reached, reached_flags, seen, wpb, chunks, fresh_scan, cur.off_dev, nxt.ids);
+                hipLaunchKernelGGL(fresh_emit_kernel<false>, dim3(chunks, beta), dim3(FR_THREADS), 0, st, reached, reached_flags, seen, wpb, chunks, fresh_scan, cur.off_dev, nxt.ids);
         }
         RG_HIP(hipGetLastError());
     }

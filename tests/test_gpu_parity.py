@@ -377,6 +377,22 @@ def test_both_frontier_variants_give_the_same_schedule(case, rg, force, monkeypa
     assert_schedules_equal(rg, g2, case.osched)          # bitmaps and flags come back clean from the block cache
 
 
+@pytest.mark.parametrize("force", ["1", "0"])
+@pytest.mark.parametrize("sampler", ["keys", "positions"])
+def test_both_forms_of_the_reached_map_give_the_same_schedule(case, rg, orc, force, sampler, monkeypatch):
+    """Marks as plain byte stores into a byte per ID, and as atomic ORs into a bit per ID (what graphs too large for
+    the byte form get), each forced; both samplers mark through the same call."""
+    monkeypatch.setenv("RAPIDGNN_BYTE_MAPS", force)
+    w = case.w
+    code = rg.RG_SAMPLER_KEYS if sampler == "keys" else rg.RG_SAMPLER_POSITIONS
+    o = case.osched if sampler == "keys" else orc.Schedule(w.indptr.numpy(), w.indices.numpy(), w.train.numpy(), w.cfg.batch_size, w.cfg.fanout,
+                                                           case.s0, case.worker, case.epoch, sampler="positions")
+    for _ in range(2):                                  # the second build finds the maps' memory used before
+        g = rg.rg_build_schedule_with(case.indptr, case.indices, case.train, w.cfg.batch_size, w.cfg.fanout, case.s0, case.worker, case.epoch,
+                                      sampler=code)
+        assert_schedules_equal(rg, g, o)
+
+
 def test_few_listed_nodes_plan_without_the_route_table(case, rg, orc):
     """An epoch that lists far fewer input nodes than the graph has nodes is planned by direct lookups."""
     w = case.w
