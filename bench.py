@@ -240,6 +240,22 @@ def cpu_baseline(W, indptr_h, indices_h, train_h, budget_s=15.0):
                        f"frequency, TopHot, cache fill and gather of those batches (single thread); {dt:.1f} s")
 
 
+def device_copy_gbps(n_bytes=1 << 30, reps=5):
+    """Read + write rate of a plain device-to-device copy of n_bytes on this GPU: the yardstick beside the 8 TB/s peak."""
+    a = torch.empty(n_bytes, dtype=torch.uint8, device="cuda")
+    b = torch.empty_like(a)
+    a.fill_(1)
+    b.copy_(a)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    e0.record()
+    for _ in range(reps):
+        b.copy_(a)
+    e1.record()
+    torch.cuda.synchronize()
+    return 2.0 * n_bytes * reps / (e0.elapsed_time(e1) * 1e-3) / 1e9
+
+
 def measured_traffic(workload, kernel):
     """HBM bytes per launch of `kernel` on `workload` from the committed rocprofv3 --pmc runs
     (profiles/*_traffic.md says how they were taken), or None when there is no such measurement."""
@@ -334,6 +350,10 @@ def main():
                     algorithmic_bytes_per_step=samp_bytes)
     roof["dominant_group_by_time"] = dominant
     roof["traffic"] = measured_traffic(cfg.name, roof["kernel"])
+    copy_gbps = device_copy_gbps()
+    roof["device_copy_GBps"] = copy_gbps                       # a 1 GiB device-to-device copy on this machine, read + write
+    roof["achieved_over_device_copy"] = roof["achieved"] / copy_gbps
+    log(f"[bench] plain device-to-device copy of 1 GiB: {copy_gbps:.0f} GB/s read+write; {roof['kernel']} reaches {roof['achieved']:.0f} GB/s")
 
     result = {
         "metric": METRIC, "value": value, "unit": "sampled edges/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
