@@ -311,8 +311,25 @@ def main():
     c = rg.rg_build_cache([s], feat_hbm, W.K)
     stats = [rg.rg_gather_batch(s, c, feat_hbm, b, torch.empty(m_max * W.stride_bytes, dtype=torch.uint8, device="cuda"),
                                 out_stride=W.stride_bytes, out_capacity_rows=m_max) for b in (0,)]
-    k_eff = rg.rg_cache_view(c, W.n_nodes)["K_eff"]
+    view = rg.rg_cache_view(c, W.n_nodes)
+    k_eff = view["K_eff"]
     n_batches = s.n_batches
+    # how the epoch's accesses to remote features are distributed, and what the cache saves (reported, not timed)
+    remote_freq = view["freq"][~W.is_local.bool()]
+    touched = remote_freq[remote_freq > 0]
+    cls = [rg.rg_classify_batch(s, c, feat_hbm, b) for b in range(n_batches)]
+    remote_rows = sum(x["n_hit"] + x["n_miss"] for x in cls)
+    fetched_rows = sum(x["n_miss"] for x in cls)
+    access_stats = {
+        "touched_remote_nodes": int(touched.numel()),
+        "share_accessed_once": float((touched == 1).sum().item()) / max(1, touched.numel()),
+        "max_frequency": int(touched.max().item()) if touched.numel() else 0,
+        "remote_rows_in_input_sets": int(remote_rows), "remote_rows_fetched_with_cache": int(fetched_rows),
+        "fetch_reduction": remote_rows / fetched_rows if fetched_rows else None,
+        "note": "context, not parity: the paper's Evaluation section reports 45.3 % of nodes accessed exactly once and a maximum "
+                "frequency of 66 for an OGBN-Products epoch, and 9.70-15.39x less time in remote fetches (a time ratio on other "
+                "graphs and machines; this is a row-count ratio on the synthetic graph)"}
+    del view, remote_freq, touched
     del s, c
     sampled_edges = sum(h["sampled"] for h in hops)
     G = max(1, args.gather_group)
@@ -365,6 +382,7 @@ def main():
                    "n_batches": n_batches, "sampled_edges_per_epoch": sampled_edges, "gathered_rows_per_epoch": rows_per_epoch,
                    "K_eff": int(k_eff)},
         "roofline": roof,
+        "access_stats": access_stats,
         "sampler": {"edges_per_s_kernel": sampled_edges / (samp_ms * 1e-3) if samp_ms else None, "GBps": samp_gbps,
                     "frac_hbm": samp_gbps / HBM_PEAK_GBPS, "ms_per_step": samp_ms, "scanned_row_entries": sum(h["sum_deg"] for h in hops)},
         "gather": {"GBps": gath_gbps, "frac_hbm": gath_gbps / HBM_PEAK_GBPS, "ms_per_step": gath_ms,
