@@ -223,21 +223,30 @@ def cpu_baseline(W, indptr_h, indices_h, train_h, budget_s=15.0):
         t0 = time.perf_counter()
         s = oracle.Schedule(indptr_h, indices_h, train_h, cfg.batch_size, cfg.fanout, cfg.s0, cfg.worker, cfg.epoch,
                             batch_lo=0, batch_hi=nb, n_threads=threads)
+        t1 = time.perf_counter()
         freq = oracle.frequency([s], W.n_nodes)
         ids, _ = oracle.top_hot(freq, feats.is_local, W.K)
         oracle.cache_fill(ids, feats, table_stride=W.stride_bytes)
+        t2 = time.perf_counter()
         for b in range(s.n_batches):
             oracle.gather_batch(s, b, feats, out_stride=W.stride_bytes)
-        dt = time.perf_counter() - t0
+        t3 = time.perf_counter()
         edges = sum(int(s.samples(h)[1].size) for h in range(s.L))
-        return dt, edges
-    dt1, _ = one(min(threads, beta))
+        return t3 - t0, edges, {"schedule": t1 - t0, "cache": t2 - t1, "gather": t3 - t2}
+    dt1, _, _ = one(min(threads, beta))
     nb = int(max(threads, min(beta, threads * max(1.0, budget_s / max(dt1, 1e-3)))))
     nb = min(beta, nb // threads * threads if nb >= threads else nb)
-    dt, edges = one(nb)
+    dt, edges, phases = one(nb)
+    model = ""
+    try:
+        with open("/proc/cpuinfo") as fh:
+            model = next((ln.split(":", 1)[1].strip() for ln in fh if ln.startswith("model name")), "")
+    except OSError:
+        pass
     return dict(value=edges / dt, unit="sampled edges/s", cores=threads, kind="oracle",
                 sample=f"first {nb} of {beta} batches of the epoch: schedule ({threads} threads, one batch per thread), "
-                       f"frequency, TopHot, cache fill and gather of those batches (single thread); {dt:.1f} s")
+                       f"frequency, TopHot, cache fill and gather of those batches (single thread); {dt:.1f} s",
+                seconds={k: round(v, 3) for k, v in phases.items()}, cpu_model=model, host_cpus=os.cpu_count())
 
 
 def device_copy_gbps(n_bytes=1 << 30, reps=5):
