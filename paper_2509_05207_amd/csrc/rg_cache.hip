@@ -14,6 +14,13 @@ __global__ void tally_kernel(const int32_t *__restrict__ ids, int64_t n, uint32_
     for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride) atomicAdd(&freq[ids[i]], 1u);
 }
 
+// freq += the frequencies an epoch's schedule already holds (computed from its bitmaps when it was built)
+__global__ void add_epoch_freq_kernel(const uint32_t *__restrict__ epoch_freq, int64_t n, uint32_t *__restrict__ freq)
+{
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) freq[i] += epoch_freq[i];
+}
+
 // ---------------------------------------------------------------- a7: TopHot
 // Candidates: remote IDs with freq > 0.  The K-th largest frequency t is found
 // by a most-significant-digit-first radix select over the candidates' freq
@@ -358,6 +365,10 @@ static rg_status build_cache_impl(const rg_schedule *const *epochs, uint32_t n_e
         const int64_t m = h.off_host[s->n_batches];
         if (m == 0) continue;
         ScopedTimer tm(KG_HIST, st);
+        if (s->epoch_freq) {
+            hipLaunchKernelGGL(add_epoch_freq_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, s->epoch_freq, n, c->freq);
+            continue;
+        }
         const unsigned grid = (unsigned)std::min<int64_t>((m + 255) / 256, (int64_t)n_cu * 32);
         hipLaunchKernelGGL(tally_kernel, dim3(grid), dim3(256), 0, st, h.ids, m, c->freq);
     }

@@ -95,6 +95,7 @@ struct rg_schedule {
     uint64_t uid = 0;                // identity for plan lookup (pointers can be reused)
     std::vector<rg::HopData> hop;    // L + 1 entries
     bool blocks_built = false;
+    uint32_t *epoch_freq = nullptr;  // dev, [n_nodes]: in how many of the epoch's input sets each node is, or NULL (then the lists are tallied)
     explicit rg_schedule(const rg_allocator *a) : arena(a) {}
 };
 

@@ -110,6 +110,39 @@ __global__ void mark_seeds_kernel(const int32_t *__restrict__ seeds, uint64_t T,
     atomicOr(&seen[(t / batch_size) * words_per_batch + (v >> 5)], 1u << (v & 31));
 }
 
+// ---------------------------------------------------------------- a6 (first half): freq(v) of the epoch as column sums
+// After the last hop a batch's `seen` bitmap is exactly its input set N_i^e, so freq(v) = in how many batches' bitmaps
+// bit v is set: the sum of a column of a bit matrix of n_batches rows.  A thread owns one word position (32 node IDs)
+// and adds the batches' words into 16 bit-sliced counters (plane k holds bit k of all 32 counts; adding a word is a
+// ripple of AND/XOR through the planes), so the whole tally reads every bitmap once, coalesced, and has no atomics.
+constexpr int FREQ_PLANES = 16;          // counts up to 65,535 batches
+__global__ void epoch_freq_kernel(const uint32_t *__restrict__ seen, uint64_t words_per_batch, uint32_t n_batches, int64_t n_nodes,
+                                  uint32_t *__restrict__ freq)
+{
+    const uint64_t i = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= words_per_batch) return;
+    uint32_t plane[FREQ_PLANES];
+#pragma unroll
+    for (int k = 0; k < FREQ_PLANES; ++k) plane[k] = 0;
+    for (uint32_t b = 0; b < n_batches; ++b) {
+        uint32_t carry = seen[(uint64_t)b * words_per_batch + i];
+#pragma unroll
+        for (int k = 0; k < FREQ_PLANES; ++k) {
+            const uint32_t t = plane[k] & carry;
+            plane[k] ^= carry;
+            carry = t;
+        }
+    }
+    const int64_t v0 = (int64_t)(i << 5);
+#pragma unroll 4
+    for (int j = 0; j < 32; ++j) {
+        uint32_t c = 0;
+#pragma unroll
+        for (int k = 0; k < FREQ_PLANES; ++k) c |= ((plane[k] >> j) & 1u) << k;
+        if (v0 + j < n_nodes) freq[v0 + j] = c;
+    }
+}
+
 // ---------------------------------------------------------------- a4: frontier from the fresh bitmap
 constexpr int FR_THREADS = 256;
 constexpr int FR_WORDS_PER_THREAD = 8;
@@ -502,6 +535,13 @@ static rg_status build_schedule_impl(const rg_graph *g, const int32_t *train, ui
             else
                 hipLaunchKernelGGL(fresh_emit_kernel<false>, dim3(chunks, beta), dim3(FR_THREADS), 0, st, reached, reached_flags, seen, wpb, chunks, fresh_scan, cur.off_dev, nxt.ids);
         }
+        RG_HIP(hipGetLastError());
+    }
+    // a6, first half: where the bitmaps are smaller than the lists of input nodes, the epoch's frequencies come from them
+    if (!sparse_maps && beta < (1u << FREQ_PLANES) && wpb * (uint64_t)beta <= (uint64_t)s->hop[L].off_host[beta]) {
+        RG_TRY(s->arena.dev_n<uint32_t>((uint64_t)g->n_nodes, &s->epoch_freq));
+        ScopedTimer tm(KG_HIST, st);
+        hipLaunchKernelGGL(epoch_freq_kernel, dim3((unsigned)((wpb + 255) / 256)), dim3(256), 0, st, seen, wpb, beta, (int64_t)g->n_nodes, s->epoch_freq);
         RG_HIP(hipGetLastError());
     }
     RG_HIP(hipStreamSynchronize(st));
