@@ -145,9 +145,9 @@ __device__ __forceinline__ uint32_t kth_key_threshold(const uint32_t (&k)[E], co
 }
 
 // Row of f < len <= 64 * E IDs held in registers (u[e] of lane l is row[e * 64 + l]),
-// sampled and written to out in row order.
+// sampled and written to out in row order.  buf: scratch of at least 64 entries (used when E > 1).
 template <int E, int MARK>
-__device__ __forceinline__ void sample_registers(const uint32_t (&u)[E], int len, int f, uint32_t lo, uint32_t hi, int lane,
+__device__ __forceinline__ void sample_registers(const uint32_t (&u)[E], int len, int f, uint32_t lo, uint32_t hi, int lane, uint32_t *buf,
                                                  int32_t *__restrict__ out, const ReachedOfBatch &reached_b)
 {
     len = uni(len); f = uni(f); lo = uni(lo); hi = uni(hi);
@@ -158,7 +158,41 @@ __device__ __forceinline__ void sample_registers(const uint32_t (&u)[E], int len
         vm[e] = low_lanes(len - e * 64);
         k[e] = key32(lo, hi, u[e]);
     }
-    const uint32_t cut = kth_key_threshold<E>(k, vm, f, len);
+    uint32_t cut = 0;
+    bool have_cut = false;
+    if (E > 1) {
+        // As for long rows, a cut guessed from the key distribution first: about lambda of the row's keys lie below
+        // lambda / len.  If between f and 64 do, the threshold is searched among those alone, one key per lane and
+        // from the guessed cut's leading bit down, instead of among all E registers from bit 31; the f smallest keys of the
+        // row are among them, so the result is the same.  Otherwise (or for rows too short to guess) the search below.
+        const float lambda = (float)f + 4.0f * __fsqrt_rn((float)f) + 8.0f;
+        if (uni(lambda * 2.0f <= (float)len)) {
+            const uint32_t guessed = uni((uint32_t)(lambda / (float)len * 4294967296.0f));
+            unsigned long long m[E];
+            int total = 0;
+#pragma unroll
+            for (int e = 0; e < E; ++e) {
+                m[e] = ballot64(k[e] <= guessed) & vm[e];
+                total += __popcll(m[e]);
+            }
+            if (total >= f && total <= 64) {
+                int base = 0;
+#pragma unroll
+                for (int e = 0; e < E; ++e) {
+                    if (my_bit(m[e])) buf[base + lanes_below(m[e], lane)] = k[e];
+                    base += __popcll(m[e]);
+                }
+                __syncthreads();
+                const uint32_t ck[1] = {lane < total ? buf[lane] : 0u};
+                const unsigned long long cvm[1] = {low_lanes(total)};
+                cut = kth_key_threshold<1>(ck, cvm, f, total, guessed);
+                if (cut > guessed) cut = guessed;      // (the search may answer with the end of its bracket: keys above the guess are no candidates)
+                have_cut = true;
+                __syncthreads();      // the scratch is free again
+            }
+        }
+    }
+    if (!have_cut) cut = kth_key_threshold<E>(k, vm, f, len);
     int base = 0;
 #pragma unroll
     for (int e = 0; e < E; ++e) {
@@ -492,10 +526,10 @@ __device__ __forceinline__ void sample_row(const int32_t *__restrict__ row, int 
 {
     if (len <= 64) {
         const uint32_t u[1] = {first};
-        sample_registers<1, MARK>(u, len, f, lo, hi, lane, out, reached_b);
+        sample_registers<1, MARK>(u, len, f, lo, hi, lane, buf, out, reached_b);
     } else if (len <= 256) {
         const uint32_t u[4] = {first, ahead.x, ahead.y, ahead.z};
-        sample_registers<4, MARK>(u, len, f, lo, hi, lane, out, reached_b);
+        sample_registers<4, MARK>(u, len, f, lo, hi, lane, buf, out, reached_b);
     } else {
         sample_long_row<CAP>(row, len, first, f, lo, hi, lane, buf, ahead);
         for (int j = lane; j < f; j += 64) {

@@ -460,14 +460,15 @@ def test_rows_that_overflow_the_candidate_buffer_under_the_guessed_cut(rg, orc):
         assert sum(orc.key32(S, int(u)) <= cut for u in rows[v]) == n_low
 
 
-def test_rows_built_to_defeat_the_guessed_cut(rg, orc):
-    """Long rows are first streamed with a cut guessed from the key distribution.  Rows made of IDs whose keys (under
-    the node's own state) all lie above that cut, or with exactly f - 1, f and f + 1 keys below it, force the
-    fallback to the exact procedure and both sides of its trigger."""
-    n, f, deg = 20000, 10, 1500
+@pytest.mark.parametrize("deg", [1500, 200])
+def test_rows_built_to_defeat_the_guessed_cut(rg, orc, deg):
+    """Long rows (and rows of 65-256 IDs, which are held in registers) are first taken with a cut guessed from the
+    key distribution.  Rows made of IDs whose keys (under the node's own state) all lie above that cut, or with exactly
+    f - 1, f and f + 1 keys below it, force the fallback to the exact procedure and both sides of its trigger."""
+    n, f = 20000, 10
     s0, wk, ep = 21, 0, 3
-    specials = [11, 222, 3333, 4444]                     # seeds, all in batch 0 (one batch)
-    below = [0, f - 1, f, f + 1]                         # keys below the guessed cut in each special row
+    specials = [11, 222, 3333, 4444, 5555]               # seeds, all in batch 0 (one batch)
+    below = [0, f - 1, f, f + 1, 100]                    # keys below the guessed cut in each special row (100: more than a wave holds)
     hs = orc.hop_state(orc.batch_seed(s0, wk, ep, 0), 0)
     lam = f + 4.0 * np.sqrt(np.float32(f)) + 8.0
     cut = int(np.float32(lam) / np.float32(deg) * np.float32(4294967296.0))
