@@ -314,9 +314,12 @@ rg_status build_plan(const rg_schedule *s, const int64_t *route, const RouteSour
         hipLaunchKernelGGL(miss_offsets_kernel, dim3((beta + 1 + 255) / 256), dim3(256), 0, st, miss_scan, h.off_dev, beta, miss_off_dev);
     }
     std::vector<unsigned long long> hc(2 * (size_t)beta);
-    RG_HIP(hipMemcpyAsync(plan->miss_off.data(), miss_off_dev, ((size_t)beta + 1) * sizeof(int64_t), hipMemcpyDeviceToHost, st));
-    RG_HIP(hipMemcpyAsync(hc.data(), counts, hc.size() * sizeof(unsigned long long), hipMemcpyDeviceToHost, st));
-    RG_HIP(hipStreamSynchronize(st));
+    {
+        Readback rb(st);
+        RG_TRY(rb.add(plan->miss_off.data(), miss_off_dev, ((size_t)beta + 1) * sizeof(int64_t)));
+        RG_TRY(rb.add(hc.data(), counts, hc.size() * sizeof(unsigned long long)));
+        RG_TRY(rb.wait());
+    }
     const int64_t n_miss = plan->miss_off[beta];
     RG_TRY(keep.dev_n<int32_t>((uint64_t)n_miss, &plan->miss_rows));
     if (n_miss > 0) {
@@ -401,8 +404,11 @@ static rg_status build_cache_impl(const rg_schedule *const *epochs, uint32_t n_e
         }
     }
     SelectState hs;
-    RG_HIP(hipMemcpyAsync(&hs, stp, sizeof(SelectState), hipMemcpyDeviceToHost, st));
-    RG_HIP(hipStreamSynchronize(st));
+    {
+        Readback rb(st);
+        RG_TRY(rb.add(&hs, stp, sizeof(SelectState)));
+        RG_TRY(rb.wait());
+    }
     c->K_eff = hs.k_eff;
     RG_TRY(c->arena.dev_n<int32_t>(c->K_eff, &c->cache_ids));
     if (sel_blocks > 0) {

@@ -2,6 +2,8 @@
 // graph validation and the handle accessors.
 #include "rg_internal.h"
 
+#include <cstring>
+
 #include <atomic>
 #include <cstdarg>
 #include <cstdio>
@@ -91,6 +93,54 @@ struct BlockCache {
 };
 BlockCache g_blocks;
 }  // namespace
+
+// ---------------------------------------------------------------- small readbacks
+namespace {
+constexpr size_t STAGE_BYTES = 8192;
+struct StagePool {
+    std::mutex mu;
+    std::vector<uint8_t *> free_blocks;
+    uint8_t *take()
+    {
+        {
+            std::lock_guard<std::mutex> lk(mu);
+            if (!free_blocks.empty()) { uint8_t *p = free_blocks.back(); free_blocks.pop_back(); return p; }
+        }
+        void *p = nullptr;
+        if (hipHostMalloc(&p, STAGE_BYTES, hipHostMallocDefault) != hipSuccess) { (void)hipGetLastError(); return nullptr; }
+        return static_cast<uint8_t *>(p);
+    }
+    void give(uint8_t *p) { std::lock_guard<std::mutex> lk(mu); free_blocks.push_back(p); }
+};
+StagePool g_stages;
+}  // namespace
+
+Readback::Readback(hipStream_t st) : st_(st) {}
+Readback::~Readback() { if (stage_) g_stages.give(stage_); }
+
+rg_status Readback::add(void *host_dst, const void *dev_src, size_t bytes)
+{
+    if (bytes == 0) return RG_OK;
+    if (!stage_) stage_ = g_stages.take();
+    const size_t at = (used_ + 15) & ~(size_t)15;
+    if (!stage_ || at + bytes > STAGE_BYTES) {           // too large for the block (or no pinned memory to be had): straight to the destination
+        RG_HIP(hipMemcpyAsync(host_dst, dev_src, bytes, hipMemcpyDeviceToHost, st_));
+        return RG_OK;
+    }
+    RG_HIP(hipMemcpyAsync(stage_ + at, dev_src, bytes, hipMemcpyDeviceToHost, st_));
+    parts_.push_back({host_dst, at, bytes});
+    used_ = at + bytes;
+    return RG_OK;
+}
+
+rg_status Readback::wait()
+{
+    RG_HIP(hipStreamSynchronize(st_));
+    for (const Part &p : parts_) memcpy(p.dst, stage_ + p.at, p.bytes);
+    parts_.clear();
+    used_ = 0;
+    return RG_OK;
+}
 
 // ---------------------------------------------------------------- arena
 Arena::Arena(const rg_allocator *a)

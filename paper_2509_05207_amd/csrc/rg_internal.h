@@ -154,6 +154,25 @@ rg_status launch_gather(const int64_t *entries, int64_t n_rows, const int32_t *l
                         const RowSources &src, uint32_t row_bytes, uint8_t *out, uint64_t out_stride,
                         hipStream_t st, int group);
 
+// A few small values read back from the device behind one stream synchronisation.  They travel through a pinned
+// staging block (kept in a pool for the life of the process): a copy into pageable memory costs the runtime
+// about 8 us more, and the builds read back a dozen such values per epoch.
+class Readback {
+  public:
+    explicit Readback(hipStream_t st);
+    ~Readback();
+    Readback(const Readback &) = delete;
+    Readback &operator=(const Readback &) = delete;
+    rg_status add(void *host_dst, const void *dev_src, size_t bytes);    // queues the copy
+    rg_status wait();                                                    // synchronises the stream; the destinations are valid afterwards
+  private:
+    struct Part { void *dst; size_t at, bytes; };
+    hipStream_t st_;
+    uint8_t *stage_ = nullptr;
+    size_t used_ = 0;
+    std::vector<Part> parts_;
+};
+
 // True when p is device memory on the current device (false for pinned host memory).
 bool is_device_memory(const void *p);
 

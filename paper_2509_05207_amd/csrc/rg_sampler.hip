@@ -753,11 +753,14 @@ rg_status sample_hop(const rg_graph *g, HopData &cur, uint32_t beta, const uint6
         RG_HIP(hipMemsetAsync(sum_deg_dev, 0, sizeof(unsigned long long), st));
         if (n_cur > 0)
             hipLaunchKernelGGL(sum_degrees_kernel, dim3((unsigned)std::min<int64_t>((n_cur + 255) / 256, 1024)), dim3(256), 0, st, rec.deg, n_cur, sum_deg_dev);
-        RG_HIP(hipMemcpyAsync(&sum_deg, sum_deg_dev, sizeof(unsigned long long), hipMemcpyDeviceToHost, st));
     }
-    RG_HIP(hipMemcpyAsync(&cur.n_samples, cur.samp_off + n_cur, sizeof(int64_t), hipMemcpyDeviceToHost, st));
-    RG_HIP(hipMemcpyAsync(&n_tiles, tile_off + n_cur, sizeof(int64_t), hipMemcpyDeviceToHost, st));
-    RG_HIP(hipStreamSynchronize(st));
+    {
+        Readback rb(st);
+        if (sum_deg_dev) RG_TRY(rb.add(&sum_deg, sum_deg_dev, sizeof(unsigned long long)));
+        RG_TRY(rb.add(&cur.n_samples, cur.samp_off + n_cur, sizeof(int64_t)));
+        RG_TRY(rb.add(&n_tiles, tile_off + n_cur, sizeof(int64_t)));
+        RG_TRY(rb.wait());
+    }
     // Which form of the reached map this hop marks.  A byte store is several times cheaper than an atomic OR, but the
     // byte map is 8 times the size and its scattered stores reach memory as whole lines; that pays where marks are a
     // large part of the hop's traffic (rows mostly no longer than the fan-out: one mark per ID read), and costs a

@@ -521,8 +521,11 @@ static rg_status build_schedule_impl(const rg_graph *g, const int32_t *train, ui
             hipLaunchKernelGGL(next_offsets_kernel, dim3((beta + 1 + 255) / 256), dim3(256), 0, st, cur.off_dev, fresh_scan, beta, chunks, nxt.off_dev);
         }
         nxt.off_host.resize((size_t)beta + 1);
-        RG_HIP(hipMemcpyAsync(nxt.off_host.data(), nxt.off_dev, ((size_t)beta + 1) * sizeof(int64_t), hipMemcpyDeviceToHost, st));
-        RG_HIP(hipStreamSynchronize(st));
+        {
+            Readback rb(st);
+            RG_TRY(rb.add(nxt.off_host.data(), nxt.off_dev, ((size_t)beta + 1) * sizeof(int64_t)));
+            RG_TRY(rb.wait());
+        }
         const int64_t n_next = nxt.off_host[beta];
         RG_TRY(s->arena.dev_n<int32_t>((uint64_t)n_next, &nxt.ids));
         {
