@@ -379,16 +379,25 @@ def test_both_frontier_variants_give_the_same_schedule(case, rg, force, monkeypa
 
 @pytest.mark.parametrize("force", ["1", "0"])
 @pytest.mark.parametrize("sampler", ["keys", "positions"])
-def test_both_forms_of_the_reached_map_give_the_same_schedule(case, rg, orc, force, sampler, monkeypatch):
+@pytest.mark.parametrize("fanout", [None, (300, 3)])
+def test_both_forms_of_the_reached_map_give_the_same_schedule(case, rg, orc, force, sampler, fanout, monkeypatch):
     """Marks as plain byte stores into a byte per ID, and as atomic ORs into a bit per ID (what graphs too large for
-    the byte form get), each forced; both samplers mark through the same call."""
+    the byte form get), each forced; both samplers mark through the same call.  With fan-outs (300, 3) and the byte
+    form forced, the key sampler's first hop still marks bits (its byte-marking kernels stop at a fan-out of 192)
+    and its second hop bytes: both forms within one build."""
     monkeypatch.setenv("RAPIDGNN_BYTE_MAPS", force)
     w = case.w
+    if fanout and case.name not in ("small", "mid"):
+        pytest.skip("fan-out variants run on two graphs")
+    fan = list(fanout) if fanout else list(w.cfg.fanout)
     code = rg.RG_SAMPLER_KEYS if sampler == "keys" else rg.RG_SAMPLER_POSITIONS
-    o = case.osched if sampler == "keys" else orc.Schedule(w.indptr.numpy(), w.indices.numpy(), w.train.numpy(), w.cfg.batch_size, w.cfg.fanout,
-                                                           case.s0, case.worker, case.epoch, sampler="positions")
+    if sampler == "keys" and not fanout:
+        o = case.osched
+    else:
+        o = orc.Schedule(w.indptr.numpy(), w.indices.numpy(), w.train.numpy(), w.cfg.batch_size, fan, case.s0, case.worker, case.epoch,
+                         n_threads=8, sampler=sampler)
     for _ in range(2):                                  # the second build finds the maps' memory used before
-        g = rg.rg_build_schedule_with(case.indptr, case.indices, case.train, w.cfg.batch_size, w.cfg.fanout, case.s0, case.worker, case.epoch,
+        g = rg.rg_build_schedule_with(case.indptr, case.indices, case.train, w.cfg.batch_size, fan, case.s0, case.worker, case.epoch,
                                       sampler=code)
         assert_schedules_equal(rg, g, o)
 
