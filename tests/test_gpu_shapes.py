@@ -58,8 +58,10 @@ SHAPES = [
 
 
 @pytest.mark.parametrize("shape", range(len(SHAPES)))
-@pytest.mark.parametrize("sampler", ["keys", "positions"])
-def test_random_shape(rg, orc, shape, sampler):
+@pytest.mark.parametrize("sampler,maps", [("keys", "auto"), ("keys", "bytes"), ("keys", "bits"), ("positions", "auto")])
+def test_random_shape(rg, orc, shape, sampler, maps, monkeypatch):
+    if maps != "auto":                                   # the form of the reached-ID map, forced (chosen per hop otherwise)
+        monkeypatch.setenv("RAPIDGNN_BYTE_MAPS", "1" if maps == "bytes" else "0")
     n, classes, fanout, batch, n_train = SHAPES[shape]
     rng = np.random.default_rng(4000 + shape)
     indptr, indices = random_graph(rng, n, classes)
