@@ -59,6 +59,15 @@ class rg_allocator(C.Structure):
 _lib = None
 
 
+def use_library(path):
+    """Load another build of the same library (the profiling build with phase timers) instead of the default one.
+    Must be called before the first call of lib()."""
+    global _LIB_PATH
+    if _lib is not None:
+        raise RuntimeError("the library is already loaded")
+    _LIB_PATH = os.path.abspath(path)
+
+
 def lib():
     """The loaded library; raises if it has not been built (python -m paper_2509_05207_amd.build)."""
     global _lib

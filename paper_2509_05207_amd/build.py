@@ -21,19 +21,26 @@ def stale():
     return any(os.path.getmtime(p) > t for p in SOURCES + HEADERS)
 
 
-def build(force=True, verbose=False):
-    if not force and not stale():
+def stale_against(lib_path):
+    t = os.path.getmtime(lib_path)
+    return any(os.path.getmtime(p) > t for p in SOURCES + HEADERS)
+
+
+def build(force=True, verbose=False, out=None, defines=()):
+    """Builds the library; `out` and `defines` make another build of the same sources (the profiling build)."""
+    if out is None and not force and not stale():
         return LIB
+    out = out or LIB
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
     cmd = [hipcc, "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
            "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",      # no packed-fp32 code generation
-           "-Wall", "-Wno-unused-command-line-argument",
+           "-Wall", "-Wno-unused-command-line-argument"] + ["-D" + d for d in defines] + [
            "-I", os.path.join(ROOT, "include"), "-I", os.path.join(HERE, "csrc"),
-           "-o", LIB] + SOURCES
+           "-o", out] + SOURCES
     if verbose:
         print(" ".join(cmd))
     subprocess.check_call(cmd)
-    return LIB
+    return out
 
 
 if __name__ == "__main__":

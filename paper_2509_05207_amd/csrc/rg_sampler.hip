@@ -41,6 +41,27 @@
 
 namespace rg {
 
+// ---------------------------------------------------------------- optional phase timers
+// Built with -DRG_PHASE_TIMERS (python -m paper_2509_05207_amd.phase_timers does that, into a library of its own), the
+// sampling kernel reads the cycle counter around each of its phases and sums the differences over all waves; the
+// ordinary build contains none of this.  One wave per workgroup, so the accumulators are simply in LDS.
+#ifdef RG_PHASE_TIMERS
+enum Phase { PH_WAVE = 0, PH_TILES, PH_GROUP_SETUP, PH_ROWS_64, PH_ROWS_256, PH_LONG_ROWS, PH_LONG_ENTRY, PH_LONG_LOOP, PH_LONG_FINAL_CUT,
+             PH_LONG_OUTPUT, PH_N_LONG_ROWS, PH_N_BLOCKS, PH_N_CANDIDATES, PH_N_ROWS_64, PH_N_ROWS_256, PH_NODE_LOOP, PH_COPY_ROWS,
+             PH_N_COPY_ROWS, PH_N_NODES, PH_WORK_COUNTER, PH_COUNT };
+__device__ unsigned long long g_phase[PH_COUNT];
+__shared__ unsigned long long phase_acc[PH_COUNT];
+#define RG_T0(name) const unsigned long long name = (unsigned long long)__builtin_readcyclecounter()
+#define RG_TSET(name) name = (unsigned long long)__builtin_readcyclecounter()
+#define RG_TADD(k, t0) do { if (threadIdx.x == 0) phase_acc[k] += (unsigned long long)__builtin_readcyclecounter() - (t0); } while (0)
+#define RG_TCNT(k, n) do { if (threadIdx.x == 0) phase_acc[k] += (unsigned long long)(n); } while (0)
+#else
+#define RG_T0(name) do { } while (0)
+#define RG_TSET(name) do { } while (0)
+#define RG_TADD(k, t0) do { } while (0)
+#define RG_TCNT(k, n) do { } while (0)
+#endif
+
 constexpr int BIG_ROW = 16384;           // rows longer than this are sampled tile by tile
 
 __device__ __host__ __forceinline__ int64_t tiles_of(int64_t deg) { return deg > BIG_ROW ? (deg + BIG_ROW - 1) / BIG_ROW : 0; }
@@ -412,6 +433,7 @@ template <int CAP>
 __device__ __forceinline__ void sample_long_row(const int32_t *__restrict__ row, int len, uint32_t first, int f, uint32_t lo, uint32_t hi, int lane,
                                                 uint32_t *buf, const u32x4 &blk0)
 {
+    RG_T0(t_entry);
     len = uni(len); f = uni(f); lo = uni(lo); hi = uni(hi);
     const int head = uni(row_head(row, len));
     const int32_t *p = row + head;
@@ -468,6 +490,9 @@ __device__ __forceinline__ void sample_long_row(const int32_t *__restrict__ row,
         const unsigned long long vm[4] = {low_lanes(head), 0ull, 0ull, 0ull};
         append_block<CAP>(u, k, vm, f, lo, hi, lane, buf, s);
     }
+    RG_TADD(PH_LONG_ENTRY, t_entry);
+    RG_T0(t_loop);
+    RG_TCNT(PH_N_BLOCKS, n_blocks);
     if (guess && rem >= 256) {
         // The full blocks under the guessed cut, two in flight behind the one whose keys are computed: block j lives in
         // register quartet j mod 3 and the loop is unrolled by three, so no block is copied from one quartet to another
@@ -509,13 +534,17 @@ __device__ __forceinline__ void sample_long_row(const int32_t *__restrict__ row,
         cur = nxt;
     }
     __syncthreads();
+    RG_TADD(PH_LONG_LOOP, t_loop);
     if (s.cnt >= f) break;                                       // (always, in the exact attempt: len > f)
   }
+    RG_T0(t_cut);
+    RG_TCNT(PH_N_CANDIDATES, s.cnt);
     if (s.cnt > f) {
         const uint32_t upper = s.open ? 0xFFFFFFFFu : s.cut;
         if (CAP > 64 && s.cnt <= 64) (void)prune_buffer<64>(buf, s.cnt, f, lo, hi, lane, upper);     // the usual case after a guessed cut: one ID per lane
         else (void)prune_buffer<CAP>(buf, s.cnt, f, lo, hi, lane, upper);
     }
+    RG_TADD(PH_LONG_FINAL_CUT, t_cut);
 }
 
 // SAMPLE of a row of len > f IDs into out (row order), marking the sampled IDs as MARK says.
@@ -524,20 +553,26 @@ template <int CAP, int MARK>
 __device__ __forceinline__ void sample_row(const int32_t *__restrict__ row, int len, uint32_t first, const u32x4 &ahead, int f, uint32_t lo, uint32_t hi,
                                            int lane, uint32_t *buf, int32_t *__restrict__ out, const ReachedOfBatch &reached_b)
 {
+    RG_T0(t_row);
     if (len <= 64) {
         const uint32_t u[1] = {first};
         sample_registers<1, MARK>(u, len, f, lo, hi, lane, buf, out, reached_b);
+        RG_TADD(PH_ROWS_64, t_row); RG_TCNT(PH_N_ROWS_64, 1);
     } else if (len <= 256) {
         const uint32_t u[4] = {first, ahead.x, ahead.y, ahead.z};
         sample_registers<4, MARK>(u, len, f, lo, hi, lane, buf, out, reached_b);
+        RG_TADD(PH_ROWS_256, t_row); RG_TCNT(PH_N_ROWS_256, 1);
     } else {
         sample_long_row<CAP>(row, len, first, f, lo, hi, lane, buf, ahead);
+        RG_T0(t_out);
         for (int j = lane; j < f; j += 64) {
             const uint32_t u = buf[j];
             out[j] = (int32_t)u;
             mark_reached<MARK>(reached_b, u);
         }
         __syncthreads();      // the buffer is reused by the wave's next row
+        RG_TADD(PH_LONG_OUTPUT, t_out);
+        RG_TADD(PH_LONG_ROWS, t_row); RG_TCNT(PH_N_LONG_ROWS, 1);
     }
 }
 
@@ -597,17 +632,29 @@ __global__ void __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(CAP <= 
     const int f = (int)a.fanout;
     const int64_t n_groups = (a.n_frontier + 63) >> 6;
     const int64_t n_work = a.n_tiles + n_groups;
+#ifdef RG_PHASE_TIMERS
+    if (lane < PH_COUNT) phase_acc[lane] = 0;
+    __syncthreads();
+    RG_T0(t_wave);
+    unsigned long long t_ask;
+    RG_TSET(t_ask);
+#endif
     // Waves take work items as they become free, so uneven rows do not leave part of the chip idle at the
     // end; every wave leaves once the counter has passed the last item.
     for (int64_t w = grab_work(a.next_work, lane); w < n_work; w = grab_work(a.next_work, lane)) {
+        RG_TADD(PH_WORK_COUNTER, t_ask);
         if (w < a.n_tiles) {
+            RG_T0(t_tile);
             const int32_t *row = a.indices + a.tile.begin[w];
             const int len = a.tile.len[w];
             const uint64_t S = a.rec.state[a.tile.node[w]];
             sample_row<CAP, MARK_NONE>(row, len, (uint32_t)row[lane], row_ahead(row, len, lane), f, (uint32_t)S, (uint32_t)(S >> 32), lane, buf,
                                        a.tile_out + w * f, ReachedOfBatch{nullptr, nullptr});
+            RG_TADD(PH_TILES, t_tile);
+            RG_TSET(t_ask);
             continue;
         }
+        RG_T0(t_group);
         const int64_t i_lane = ((w - a.n_tiles) << 6) + lane;
         const bool in = i_lane < a.n_frontier;
         const int64_t rb_lane = in ? a.rec.row_begin[i_lane] : 0;
@@ -616,7 +663,7 @@ __global__ void __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(CAP <= 
         const int64_t S_lane = in ? (int64_t)a.rec.state[i_lane] : 0;
         const int64_t out_lane = in ? a.samp_off[i_lane] : 0;
         unsigned long long todo = ballot64(deg_lane > 0 && deg_lane <= BIG_ROW);
-        if (todo == 0ull) continue;
+        if (todo == 0ull) { RG_TSET(t_ask); continue; }
         // the first node's leading 64 IDs; from then on the next node's are fetched while the current one is sampled
         int l = __builtin_amdgcn_readfirstlane(__ffsll((long long)todo) - 1);
         int64_t rb = bcast64(rb_lane, l);
@@ -624,7 +671,10 @@ __global__ void __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(CAP <= 
         uint32_t first = lane < deg ? (uint32_t)a.indices[rb + lane] : 0u;
         u32x4 ahead = {0u, 0u, 0u, 0u};
         if (deg > 64 && deg > f) ahead = row_ahead(a.indices + rb, deg, lane);
+        RG_TADD(PH_GROUP_SETUP, t_group);
         while (todo != 0ull) {
+            RG_T0(t_node);
+            RG_TCNT(PH_N_NODES, 1);
             todo &= todo - 1ull;
             const int cl = l, cdeg = deg;
             const int64_t crb = rb;
@@ -641,19 +691,28 @@ __global__ void __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(CAP <= 
             const ReachedOfBatch reached_b = reached_of<MARK>(a.reached, b);
             const int32_t *row = a.indices + crb;
             int32_t *out = a.samp_nbr + bcast64(out_lane, cl);
+            RG_TADD(PH_NODE_LOOP, t_node);
             if (cdeg <= f) {                  // the whole row is the sample
+                RG_T0(t_copy);
                 if (lane < cdeg) { out[lane] = (int32_t)cfirst; mark_reached<MARK>(reached_b, cfirst); }
                 for (int j = 64 + lane; j < cdeg; j += 64) {
                     const int32_t u = row[j];
                     out[j] = u;
                     mark_reached<MARK>(reached_b, (uint32_t)u);
                 }
+                RG_TADD(PH_COPY_ROWS, t_copy); RG_TCNT(PH_N_COPY_ROWS, 1);
             } else {
                 const uint64_t S = (uint64_t)bcast64(S_lane, cl);
                 sample_row<CAP, MARK>(row, cdeg, cfirst, cahead, f, (uint32_t)S, (uint32_t)(S >> 32), lane, buf, out, reached_b);
             }
         }
+        RG_TSET(t_ask);
     }
+#ifdef RG_PHASE_TIMERS
+    RG_TADD(PH_WAVE, t_wave);
+    __syncthreads();
+    if (lane < PH_COUNT) atomicAdd(&g_phase[lane], phase_acc[lane]);
+#endif
 }
 
 // One wave per tile job; the wave that holds a long row's first tile samples the row's
@@ -825,3 +884,17 @@ rg_status sample_hop(const rg_graph *g, HopData &cur, uint32_t beta, const uint6
 }
 
 }  // namespace rg
+
+#ifdef RG_PHASE_TIMERS
+// Sums of the phase timers since the last reset (host array of PH_COUNT values), for the profiling build only.
+extern "C" int rg_phase_timers_read(unsigned long long *out, int n, int reset)
+{
+    if (n != rg::PH_COUNT || hipDeviceSynchronize() != hipSuccess) return -1;
+    if (hipMemcpyFromSymbol(out, HIP_SYMBOL(rg::g_phase), sizeof(unsigned long long) * rg::PH_COUNT) != hipSuccess) return -2;
+    if (reset) {
+        unsigned long long zero[rg::PH_COUNT] = {0};
+        if (hipMemcpyToSymbol(HIP_SYMBOL(rg::g_phase), zero, sizeof(zero)) != hipSuccess) return -3;
+    }
+    return 0;
+}
+#endif
