@@ -141,11 +141,14 @@ __device__ __forceinline__ unsigned long long low_lanes(int n)
 // is scalar work that the vector unit never sees.
 
 // A threshold that exactly `keep` of the keys held in registers do not exceed.  k[e] is valid in
-// the lanes of vm[e]; `total` >= keep keys are valid in all.  Bisection on the key value: the
+// the lanes of vm[e]; `total` >= keep keys are valid in all.  Search on the key value: the
 // keep-th smallest key stays inside [lo, lo + 2^(bit+1)), and the search stops as soon as the
 // number of keys below the bracket's upper end is exactly `keep` -- after about log2(total)
-// steps for spread-out keys, 32 at most (keys are distinct).  `upper` is a bound no valid key exceeds (the cut the keys
-// were collected under, else 2^32 - 1): the search starts at its leading bit instead of bit 31.
+// bits for spread-out keys, 32 at most (keys are distinct).  Two bits are decided per step: the three
+// inner quarter points are compared at once (independent compares and counts), which halves the
+// number of dependent compare -> count -> decide chains a wave has to sit through; the outcome is
+// that of two halving steps.  `upper` is a bound no valid key exceeds (the cut the keys were
+// collected under, else 2^32 - 1): the search starts at its leading bit instead of bit 31.
 template <int E>
 __device__ __forceinline__ uint32_t kth_key_threshold(const uint32_t (&k)[E], const unsigned long long (&vm)[E], int keep, int total,
                                                       uint32_t upper = 0xFFFFFFFFu)
@@ -154,13 +157,29 @@ __device__ __forceinline__ uint32_t kth_key_threshold(const uint32_t (&k)[E], co
     uint32_t lo = 0;
     int below_hi = uni(total);
     int bit = uni(31 - __clz((int)(upper | 1u)));
-    while (below_hi != keep && bit >= 0) {     // (bit >= 0 always holds for distinct keys; it bounds the loop whatever the input)
-        const uint32_t trial = lo | (1u << bit);
+    while (below_hi != keep && bit >= 1) {
+        const uint32_t q = 1u << (bit - 1);
+        const uint32_t t1 = lo | q, t2 = lo | (q << 1), t3 = t2 | q;
+        int c1 = 0, c2 = 0, c3 = 0;
+#pragma unroll
+        for (int e = 0; e < E; ++e) {
+            c1 += __popcll(ballot64(k[e] < t1) & vm[e]);
+            c2 += __popcll(ballot64(k[e] < t2) & vm[e]);
+            c3 += __popcll(ballot64(k[e] < t3) & vm[e]);
+        }
+        if (c1 >= keep) below_hi = c1;                           // first quarter
+        else if (c2 >= keep) { lo = t1; below_hi = c2; }
+        else if (c3 >= keep) { lo = t2; below_hi = c3; }
+        else lo = t3;                                            // last quarter: the count below its upper end is unchanged
+        bit -= 2;
+    }
+    if (below_hi != keep && bit == 0) {                          // a single bit left
+        const uint32_t trial = lo | 1u;
         int below = 0;
 #pragma unroll
         for (int e = 0; e < E; ++e) below += __popcll(ballot64(k[e] < trial) & vm[e]);
         if (below < keep) lo = trial; else below_hi = below;
-        --bit;
+        bit = -1;
     }
     return lo + (uint32_t)((((uint64_t)1) << (bit + 1)) - 1u);
 }
