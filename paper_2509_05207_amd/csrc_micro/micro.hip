@@ -1,6 +1,8 @@
 // Micro-benchmarks behind figures quoted beside the library's kernels: what the memory system gives for the access
 // patterns alone.  Built and run by `python -m paper_2509_05207_amd.microbench`; not part of librapidgnn_hip.so.
 //   mb_copy    a plain streaming copy (16-byte loads and stores, four or eight per thread in flight)
+//   mb_fill    stores alone (16-byte, plain or nontemporal) and mb_read, loads alone: the one-directional rates a copy's
+//              two halves are held to
 //   mb_marks   the sampler's marking traffic alone: atomic ORs into per-batch bitmaps against byte stores into
 //              per-batch byte maps, each with the flag byte per 256 IDs
 //   mb_stream  the sampler's row reads alone: one wave per frontier node streams the node's adjacency row in aligned
@@ -26,6 +28,31 @@ __global__ void __launch_bounds__(256) copy_kernel(const u32x4 *__restrict__ a, 
 #pragma unroll
         for (int k = 0; k < U; ++k) { const size_t i = base + k * nt; if (i < n) b[i] = v[k]; }
     }
+}
+
+template <bool NT>
+__global__ void __launch_bounds__(256) fill_kernel(u32x4 *__restrict__ b, size_t n, uint32_t x)
+{
+    const size_t nt = (size_t)gridDim.x * 256;
+    const u32x4 v = {x, x + 1u, x + 2u, x + 3u};
+    for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n; i += nt) {
+        if (NT) __builtin_nontemporal_store(v, b + i);
+        else b[i] = v;
+    }
+}
+
+__global__ void __launch_bounds__(256) read_kernel(const u32x4 *__restrict__ a, size_t n, uint32_t *__restrict__ out)
+{
+    const size_t nt = (size_t)gridDim.x * 256;
+    uint32_t acc = 0;
+    for (size_t base = (size_t)blockIdx.x * 256 + threadIdx.x; base < n; base += nt * 4) {
+        u32x4 v[4];
+#pragma unroll
+        for (int k = 0; k < 4; ++k) { const size_t i = base + k * nt; v[k] = i < n ? a[i] : u32x4{0u, 0u, 0u, 0u}; }
+#pragma unroll
+        for (int k = 0; k < 4; ++k) acc ^= v[k].x ^ v[k].y ^ v[k].z ^ v[k].w;
+    }
+    if (acc == 0x12345678u) out[0] = acc;        // keeps the loads alive; practically never stores
 }
 
 // IDs with a power-law bias (popular nodes are hit often, like sampled neighbours); consecutive marks share a batch.
@@ -132,6 +159,21 @@ float mb_copy(const void *a, void *b, uint64_t bytes, int unroll, int grid, int 
     const size_t n = bytes / 16;
     if (unroll == 8) return timed([&] { hipLaunchKernelGGL(copy_kernel<8>, dim3(grid), dim3(256), 0, 0, (const u32x4 *)a, (u32x4 *)b, n); }, iters);
     return timed([&] { hipLaunchKernelGGL(copy_kernel<4>, dim3(grid), dim3(256), 0, 0, (const u32x4 *)a, (u32x4 *)b, n); }, iters);
+}
+
+// b: device buffer of `bytes` bytes (a multiple of 16); nontemporal != 0: stores that bypass the caches
+float mb_fill(void *b, uint64_t bytes, int nontemporal, int grid, int iters)
+{
+    const size_t n = bytes / 16;
+    if (nontemporal) return timed([&] { hipLaunchKernelGGL(fill_kernel<true>, dim3(grid), dim3(256), 0, 0, (u32x4 *)b, n, 7u); }, iters);
+    return timed([&] { hipLaunchKernelGGL(fill_kernel<false>, dim3(grid), dim3(256), 0, 0, (u32x4 *)b, n, 7u); }, iters);
+}
+
+// a: device buffer of `bytes` bytes (a multiple of 16); out: one uint32
+float mb_read(const void *a, uint64_t bytes, void *out, int grid, int iters)
+{
+    const size_t n = bytes / 16;
+    return timed([&] { hipLaunchKernelGGL(read_kernel, dim3(grid), dim3(256), 0, 0, (const u32x4 *)a, n, (uint32_t *)out); }, iters);
 }
 
 // words: n_batches * wpb uint32; flags: n_batches * wpb / 8 bytes; bytes: n_batches * wpb * 32 bytes; wpb = words per batch,

@@ -1,6 +1,6 @@
 """Micro-benchmarks of the access patterns alone (csrc_micro/micro.hip), the yardsticks quoted beside the kernels:
 
-  * a plain streaming copy, and the runtime's own device-to-device copy;
+  * a plain streaming copy, the runtime's own device-to-device copy, and stores alone / loads alone;
   * the sampler's marking traffic alone: atomic ORs into bitmaps against byte stores into byte maps;
   * the sampler's row reads alone on a workload's real frontiers: every row streamed once, keys computed, minimum kept.
 
@@ -43,7 +43,9 @@ def main():
         sys.exit("microbench: built " + LIB + "; no GPU visible to run it on")
     mb = C.CDLL(LIB)
     vp, u64, u32, i64 = C.c_void_p, C.c_uint64, C.c_uint32, C.c_int64
-    mb.mb_copy.restype = mb.mb_marks.restype = mb.mb_stream.restype = C.c_float
+    mb.mb_copy.restype = mb.mb_marks.restype = mb.mb_stream.restype = mb.mb_fill.restype = mb.mb_read.restype = C.c_float
+    mb.mb_fill.argtypes = [vp, u64, C.c_int, C.c_int, C.c_int]
+    mb.mb_read.argtypes = [vp, u64, vp, C.c_int, C.c_int]
     mb.mb_copy.argtypes = [vp, vp, u64, C.c_int, C.c_int, C.c_int]
     mb.mb_marks.argtypes = [vp, vp, vp, u64, u32, u32, u64, C.c_int, C.c_int]
     mb.mb_stream.argtypes = [vp, vp, vp, i64, vp, C.c_int, C.c_int, C.c_int]
@@ -71,6 +73,16 @@ def main():
         torch.cuda.synchronize()
         ms = e0.elapsed_time(e1) / 10
         print(f"| the runtime's device-to-device copy (torch `copy_`) | {nbytes} | {ms * 1e3:.1f} | {2 * nbytes / ms / 1e6:.0f} |")
+        one = torch.zeros(1, dtype=torch.int32, device="cuda")
+        for name, call in (("stores alone, plain", lambda g: mb.mb_fill(b.data_ptr(), nbytes, 0, g, 10)),
+                           ("stores alone, nontemporal", lambda g: mb.mb_fill(b.data_ptr(), nbytes, 1, g, 10)),
+                           ("loads alone", lambda g: mb.mb_read(a.data_ptr(), nbytes, one.data_ptr(), g, 10))):
+            best = None
+            for grid in (4096, 8192, 16384):
+                ms = call(grid)
+                assert ms > 0, ms
+                best = ms if best is None else min(best, ms)
+            print(f"| {name} (16 bytes per lane, best of three grids; one direction, bytes counted once) | {nbytes} | {best * 1e3:.1f} | {nbytes / best / 1e6:.0f} |")
         del a, b
 
     print("\n## Marks alone (IDs with a power-law bias, consecutive marks share a batch)\n")
