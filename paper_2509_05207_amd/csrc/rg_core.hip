@@ -116,7 +116,12 @@ StagePool g_stages;
 }  // namespace
 
 Readback::Readback(hipStream_t st) : st_(st) {}
-Readback::~Readback() { if (stage_) g_stages.give(stage_); }
+Readback::~Readback()
+{
+    if (!stage_) return;
+    if (!parts_.empty()) (void)hipStreamSynchronize(st_);      // left without wait() (an error path): copies into the block may still be in flight
+    g_stages.give(stage_);
+}
 
 rg_status Readback::add(void *host_dst, const void *dev_src, size_t bytes)
 {

@@ -596,15 +596,17 @@ __device__ __forceinline__ void sample_row(const int32_t *__restrict__ row, int 
 }
 
 // Per tile job j: the frontier position i whose row it belongs to (tile_off[i] <= j < tile_off[i + 1]), where its piece of
-// the row starts in `indices` and how long it is (near-equal pieces, each longer than 2 * RG_MAX_FANOUT).  Written by the
-// nodes that have tiles, so that a wave finds its piece with one load instead of a search through tile_off.
+// the row starts in `indices`, how long it is (near-equal pieces, each longer than 2 * RG_MAX_FANOUT) and the node's
+// stream S_v.  Written by the nodes that have tiles, so that a wave finds everything about its piece in one round of
+// loads instead of a search through tile_off and a second round for the node's record.
 struct TileRecs {
     int64_t *node;
     int64_t *begin;
     int32_t *len;
+    uint64_t *state;
 };
 __global__ void tile_records_kernel(const int64_t *__restrict__ tile_off, const int64_t *__restrict__ row_begin, const int32_t *__restrict__ deg,
-                                    int64_t n, TileRecs r)
+                                    const uint64_t *__restrict__ state, int64_t n, TileRecs r)
 {
     const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (i >= n) return;
@@ -617,6 +619,7 @@ __global__ void tile_records_kernel(const int64_t *__restrict__ tile_off, const 
         r.node[first + t] = i;
         r.begin[first + t] = b0 + first_pos;
         r.len[first + t] = (int32_t)(last_pos - first_pos);
+        r.state[first + t] = state[i];
     }
 }
 
@@ -641,8 +644,8 @@ __device__ __forceinline__ int64_t grab_work(unsigned long long *counter, int la
     return (int64_t)(((uint64_t)hi << 32) | lo);
 }
 
-// Work items [0, n_tiles) are tiles of long rows (handed out first, so the longest-running work starts first);
-// item n_tiles + c is the c-th group of 64 consecutive frontier nodes.
+// The work of a hop: n_tiles tiles of long rows (done first, so the longest-running work starts first) and the groups
+// of 64 consecutive frontier nodes.
 template <int CAP, int MARK>
 __global__ void __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(CAP <= 256 ? 7 : 1))) sample_kernel(HopArgs a)
 {
@@ -650,7 +653,6 @@ __global__ void __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(CAP <= 
     const int lane = threadIdx.x;
     const int f = (int)a.fanout;
     const int64_t n_groups = (a.n_frontier + 63) >> 6;
-    const int64_t n_work = a.n_tiles + n_groups;
 #ifdef RG_PHASE_TIMERS
     if (lane < PH_COUNT) phase_acc[lane] = 0;
     __syncthreads();
@@ -658,23 +660,37 @@ __global__ void __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(CAP <= 
     unsigned long long t_ask;
     RG_TSET(t_ask);
 #endif
-    // Waves take work items as they become free, so uneven rows do not leave part of the chip idle at the
-    // end; every wave leaves once the counter has passed the last item.
-    for (int64_t w = grab_work(a.next_work, lane); w < n_work; w = grab_work(a.next_work, lane)) {
-        RG_TADD(PH_WORK_COUNTER, t_ask);
-        if (w < a.n_tiles) {
+    // Tiles first, dealt out in turn (workgroup k takes tiles k, k + grid, ...): they are all of about the same
+    // length, the whole grid is resident (see launch_hop), and with the next tile known in advance its record is
+    // fetched while the current one is streamed -- no wave waits for a counter or a record between tiles.
+    {
+        int64_t w = blockIdx.x;
+        int64_t nb = 0; int nl = 0; uint64_t nS = 0;
+        if (w < a.n_tiles) { nb = a.tile.begin[w]; nl = a.tile.len[w]; nS = a.tile.state[w]; }
+        while (w < a.n_tiles) {
             RG_T0(t_tile);
-            const int32_t *row = a.indices + a.tile.begin[w];
-            const int len = a.tile.len[w];
-            const uint64_t S = a.rec.state[a.tile.node[w]];
-            sample_row<CAP, MARK_NONE>(row, len, (uint32_t)row[lane], row_ahead(row, len, lane), f, (uint32_t)S, (uint32_t)(S >> 32), lane, buf,
-                                       a.tile_out + w * f, ReachedOfBatch{nullptr, nullptr});
+            const int32_t *row = a.indices + nb;
+            const int len = nl;
+            const uint64_t S = nS;
+            const uint32_t first = (uint32_t)row[lane];
+            const u32x4 ahead = row_ahead(row, len, lane);
+            const int64_t w_next = w + gridDim.x;
+            if (w_next < a.n_tiles) { nb = a.tile.begin[w_next]; nl = a.tile.len[w_next]; nS = a.tile.state[w_next]; }
+            sample_row<CAP, MARK_NONE>(row, len, first, ahead, f, (uint32_t)S, (uint32_t)(S >> 32), lane, buf, a.tile_out + w * f,
+                                       ReachedOfBatch{nullptr, nullptr});
+            w = w_next;
             RG_TADD(PH_TILES, t_tile);
-            RG_TSET(t_ask);
-            continue;
         }
+    }
+#ifdef RG_PHASE_TIMERS
+    RG_TSET(t_ask);
+#endif
+    // Then the groups of 64 consecutive frontier nodes, taken as waves become free, so that uneven rows do not leave
+    // part of the chip idle at the end; every wave leaves once the counter has passed the last group.
+    for (int64_t w = grab_work(a.next_work, lane); w < n_groups; w = grab_work(a.next_work, lane)) {
+        RG_TADD(PH_WORK_COUNTER, t_ask);
         RG_T0(t_group);
-        const int64_t i_lane = ((w - a.n_tiles) << 6) + lane;
+        const int64_t i_lane = (w << 6) + lane;
         const bool in = i_lane < a.n_frontier;
         const int64_t rb_lane = in ? a.rec.row_begin[i_lane] : 0;
         const int deg_lane = in ? a.rec.deg[i_lane] : 0;
@@ -757,11 +773,22 @@ __global__ void __launch_bounds__(64) sample_merge_kernel(HopArgs a)
     }
 }
 
+// Every workgroup of the sampling launch must be resident from the start (tiles are dealt out by workgroup index), so
+// the grid is what the chip holds of this kernel, or the amount of work if that is less.
 template <int CAP, int MARK>
-static void launch_hop(const HopArgs &a, unsigned grid, unsigned merge_grid, hipStream_t st)
+static rg_status launch_hop(const HopArgs &a, int n_cu, unsigned merge_grid, hipStream_t st)
 {
+    static int per_cu = 0;                    // the same answer every time; asked once
+    if (per_cu == 0) {
+        int v = 0;
+        RG_HIP(hipOccupancyMaxActiveBlocksPerMultiprocessor(&v, sample_kernel<CAP, MARK>, 64, 0));
+        per_cu = v > 0 ? v : 1;
+    }
+    const int64_t n_work = a.n_tiles + (a.n_frontier + 63) / 64;
+    const unsigned grid = (unsigned)std::max<int64_t>(1, std::min<int64_t>(n_work, (int64_t)n_cu * per_cu));
     hipLaunchKernelGGL((sample_kernel<CAP, MARK>), dim3(grid), dim3(64), 0, st, a);
     if (a.n_tiles > 0) hipLaunchKernelGGL((sample_merge_kernel<CAP, MARK>), dim3(merge_grid), dim3(64), 0, st, a);
+    return RG_OK;
 }
 
 // The O(f) sampler: one lane per sampled edge.  A node with deg <= f copies its row; otherwise lane t reads the
@@ -872,14 +899,15 @@ rg_status sample_hop(const rg_graph *g, HopData &cur, uint32_t beta, const uint6
     }
     if (fanout == 0) n_tiles = 0;             // nothing is drawn; every sample is empty
     int32_t *tile_out = nullptr;
-    TileRecs tile{nullptr, nullptr, nullptr};
+    TileRecs tile{nullptr, nullptr, nullptr, nullptr};
     RG_TRY(tmp.dev_n<int32_t>((uint64_t)n_tiles * fanout, &tile_out));
     RG_TRY(tmp.dev_n<int64_t>((uint64_t)n_tiles, &tile.node));
     RG_TRY(tmp.dev_n<int64_t>((uint64_t)n_tiles, &tile.begin));
     RG_TRY(tmp.dev_n<int32_t>((uint64_t)n_tiles, &tile.len));
+    RG_TRY(tmp.dev_n<uint64_t>((uint64_t)n_tiles, &tile.state));
     if (n_tiles > 0) {
         ScopedTimer tm(KG_OFFSETS, st);
-        hipLaunchKernelGGL(tile_records_kernel, dim3((unsigned)((n_cur + 255) / 256)), dim3(256), 0, st, tile_off, rec.row_begin, rec.deg, n_cur, tile);
+        hipLaunchKernelGGL(tile_records_kernel, dim3((unsigned)((n_cur + 255) / 256)), dim3(256), 0, st, tile_off, rec.row_begin, rec.deg, rec.state, n_cur, tile);
     }
 
     if (fanout > 0 && n_cur > 0) {
@@ -888,15 +916,13 @@ rg_status sample_hop(const rg_graph *g, HopData &cur, uint32_t beta, const uint6
         RG_HIP(hipMemsetAsync(next_work, 0, sizeof(unsigned long long), st));
         HopArgs a{g->indices, cur.ids, n_cur, rec, fanout, cur.samp_off, cur.samp_nbr, tile_off, tile, n_tiles, tile_out, reached, next_work};
         ScopedTimer tm(KG_SAMPLER, st);
-        const int64_t n_work = n_tiles + (n_cur + 63) / 64;
-        const unsigned grid = (unsigned)std::max<int64_t>(1, std::min<int64_t>(n_work, (int64_t)n_cu * 32));     // as many waves as fit on the chip
         const unsigned merge_grid = (unsigned)std::max<int64_t>(1, std::min<int64_t>(n_tiles, (int64_t)n_cu * 64));
         const uint32_t need = fanout + 64;
-        if (need <= 128) { if (use_bytes) launch_hop<128, MARK_BYTES>(a, grid, merge_grid, st); else launch_hop<128, MARK_BITS>(a, grid, merge_grid, st); }
-        else if (need <= 256) { if (use_bytes) launch_hop<256, MARK_BYTES>(a, grid, merge_grid, st); else launch_hop<256, MARK_BITS>(a, grid, merge_grid, st); }
-        else if (need <= 512) launch_hop<512, MARK_BITS>(a, grid, merge_grid, st);
-        else if (need <= 1024) launch_hop<1024, MARK_BITS>(a, grid, merge_grid, st);
-        else launch_hop<2048, MARK_BITS>(a, grid, merge_grid, st);
+        if (need <= 128) { if (use_bytes) RG_TRY((launch_hop<128, MARK_BYTES>(a, n_cu, merge_grid, st))); else RG_TRY((launch_hop<128, MARK_BITS>(a, n_cu, merge_grid, st))); }
+        else if (need <= 256) { if (use_bytes) RG_TRY((launch_hop<256, MARK_BYTES>(a, n_cu, merge_grid, st))); else RG_TRY((launch_hop<256, MARK_BITS>(a, n_cu, merge_grid, st))); }
+        else if (need <= 512) RG_TRY((launch_hop<512, MARK_BITS>(a, n_cu, merge_grid, st)));
+        else if (need <= 1024) RG_TRY((launch_hop<1024, MARK_BITS>(a, n_cu, merge_grid, st)));
+        else RG_TRY((launch_hop<2048, MARK_BITS>(a, n_cu, merge_grid, st)));
         RG_HIP(hipGetLastError());
     }
     return RG_OK;
