@@ -31,6 +31,8 @@
 //    launch samples the concatenation of a row's tile results, which is the
 //    row's sample: the f smallest keys of the row are among the f smallest of
 //    each tile.  This bounds the work of one wave whatever the degree skew.
+//    Tiles are dealt out by workgroup index and done before the groups of
+//    nodes, which the waves then take from a counter as they become free.
 //
 // No step sorts anything.  While a wave writes a sample it also marks the
 // batch's reached-ID bitmaps, so frontier dedup costs no extra pass.
