@@ -40,6 +40,7 @@
 #include "rg_device.h"
 
 #include <algorithm>
+#include <atomic>
 
 namespace rg {
 
@@ -780,11 +781,13 @@ __global__ void __launch_bounds__(64) sample_merge_kernel(HopArgs a)
 template <int CAP, int MARK>
 static rg_status launch_hop(const HopArgs &a, int n_cu, unsigned merge_grid, hipStream_t st)
 {
-    static int per_cu = 0;                    // the same answer every time; asked once
+    static std::atomic<int> asked{0};         // the same answer every time; asked once (schedules may be built from several threads)
+    int per_cu = asked.load(std::memory_order_relaxed);
     if (per_cu == 0) {
         int v = 0;
         RG_HIP(hipOccupancyMaxActiveBlocksPerMultiprocessor(&v, sample_kernel<CAP, MARK>, 64, 0));
         per_cu = v > 0 ? v : 1;
+        asked.store(per_cu, std::memory_order_relaxed);
     }
     const int64_t n_work = a.n_tiles + (a.n_frontier + 63) / 64;
     const unsigned grid = (unsigned)std::max<int64_t>(1, std::min<int64_t>(n_work, (int64_t)n_cu * per_cu));
