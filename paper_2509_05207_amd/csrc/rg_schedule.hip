@@ -34,8 +34,13 @@ __global__ void batch_seeds_kernel(uint64_t s0, uint32_t worker, uint32_t epoch,
     seeds[i] = h;
 }
 
-// Shuffle: train position t gets key combine(P_e, t); the epoch's order is
-// ascending (key, t).  Entries beyond T are padding that sorts last.
+// Shuffle: train position t gets key combine(P_e, t); the epoch's order is ascending (key, t).
+//
+// The keys are hash values, so their top bits spread them evenly: the positions are dealt into buckets by the top
+// bits of their keys (a count, a prefix sum, a scatter), and one workgroup per bucket then places each of its
+// bucket's entries by rank -- the number of entries of the bucket that precede it in (key, t) order -- which for a
+// hundred-odd entries per bucket is less work than any sorting network and takes a bucket of any size (its entries
+// pass through LDS a tile at a time).  Four launches and a prefix sum, whatever T.
 struct KeyPos { uint64_t key; uint64_t pos; };
 
 __device__ __forceinline__ bool kp_less(const KeyPos &a, const KeyPos &b)
@@ -43,63 +48,58 @@ __device__ __forceinline__ bool kp_less(const KeyPos &a, const KeyPos &b)
     return a.key < b.key || (a.key == b.key && a.pos < b.pos);
 }
 
-__global__ void shuffle_keys_kernel(uint64_t s0, uint32_t worker, uint32_t epoch, uint64_t T, uint64_t n_pad, KeyPos *__restrict__ kp)
+__device__ __forceinline__ uint64_t shuffle_key(uint64_t s0, uint32_t worker, uint32_t epoch, uint64_t t)
 {
-    const uint64_t t = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (t >= n_pad) return;
     uint64_t P = mix64(s0 ^ HG64);
     P = combine(P, worker);
     P = combine(P, ((uint64_t)1 << 32) + epoch);
-    KeyPos x;
-    if (t < T) { x.key = combine(P, t); x.pos = t; }
-    else { x.key = ~0ull; x.pos = ~0ull; }
-    kp[t] = x;
+    return combine(P, t);
 }
+__device__ __forceinline__ uint32_t bucket_of_key(uint64_t key, uint32_t bucket_bits) { return bucket_bits ? (uint32_t)(key >> (64u - bucket_bits)) : 0u; }
 
-// Bitonic network.  Stages whose partner distance is < SORT_TILE/2 run in LDS.
-constexpr int SORT_THREADS = 256;
-constexpr int SORT_TILE = 2048;     // elements per block in the LDS kernels (32 KB of KeyPos)
-
-__global__ void __launch_bounds__(SORT_THREADS) bitonic_global_step(KeyPos *__restrict__ kp, uint64_t n_pad, uint64_t k, uint64_t j)
-{
-    const uint64_t t = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x;      // one compare-exchange per thread
-    if (t >= n_pad / 2) return;
-    const uint64_t i = ((t & ~(j - 1)) << 1) | (t & (j - 1));                // index with bit j clear
-    const uint64_t l = i | j;
-    const bool up = (i & k) == 0;
-    KeyPos a = kp[i], b = kp[l];
-    if (kp_less(b, a) == up) { kp[i] = b; kp[l] = a; }
-}
-
-// Runs, inside LDS, every stage (k, j) with k in [k_first, k_last] and j <= min(k/2, SORT_TILE/2);
-// for k > SORT_TILE only the tail j = SORT_TILE/2 .. 1 of that k (k_first == k_last then).
-__global__ void __launch_bounds__(SORT_THREADS) bitonic_lds_steps(KeyPos *__restrict__ kp, uint64_t k_first, uint64_t k_last)
-{
-    __shared__ KeyPos tile[SORT_TILE];
-    const uint64_t base = (uint64_t)blockIdx.x * SORT_TILE;
-    for (int e = threadIdx.x; e < SORT_TILE; e += SORT_THREADS) tile[e] = kp[base + e];
-    __syncthreads();
-    for (uint64_t k = k_first; k <= k_last; k <<= 1) {
-        uint64_t j0 = k >> 1;
-        if (j0 > SORT_TILE / 2) j0 = SORT_TILE / 2;
-        for (uint64_t j = j0; j >= 1; j >>= 1) {
-            for (int t = threadIdx.x; t < SORT_TILE / 2; t += SORT_THREADS) {
-                const uint32_t i = (uint32_t)(((t & ~(j - 1)) << 1) | (t & (j - 1)));
-                const uint32_t l = i | (uint32_t)j;
-                const bool up = ((base + i) & k) == 0;
-                KeyPos a = tile[i], b = tile[l];
-                if (kp_less(b, a) == up) { tile[i] = b; tile[l] = a; }
-            }
-            __syncthreads();
-        }
-    }
-    for (int e = threadIdx.x; e < SORT_TILE; e += SORT_THREADS) kp[base + e] = tile[e];
-}
-
-__global__ void apply_shuffle_kernel(const KeyPos *__restrict__ kp, const int32_t *__restrict__ train, uint64_t T, int32_t *__restrict__ seeds)
+__global__ void shuffle_count_kernel(uint64_t s0, uint32_t worker, uint32_t epoch, uint64_t T, uint32_t bucket_bits, int32_t *__restrict__ bucket_cnt)
 {
     const uint64_t t = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (t < T) seeds[t] = train[kp[t].pos];
+    if (t < T) atomicAdd(&bucket_cnt[bucket_of_key(shuffle_key(s0, worker, epoch, t), bucket_bits)], 1);
+}
+
+// bucket_cnt is counted down again, so every slot of a bucket is handed out once; the order inside a bucket is
+// whatever the atomics give, the ranks below do not depend on it.
+__global__ void shuffle_scatter_kernel(uint64_t s0, uint32_t worker, uint32_t epoch, uint64_t T, uint32_t bucket_bits,
+                                       const int64_t *__restrict__ bucket_off, int32_t *__restrict__ bucket_cnt, KeyPos *__restrict__ kp)
+{
+    const uint64_t t = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (t >= T) return;
+    const uint64_t key = shuffle_key(s0, worker, epoch, t);
+    const uint32_t b = bucket_of_key(key, bucket_bits);
+    const int32_t left = atomicSub(&bucket_cnt[b], 1);                 // count .. 1
+    kp[bucket_off[b] + left - 1] = KeyPos{key, t};
+}
+
+constexpr int RANK_THREADS = 256;
+constexpr int RANK_TILE = 1024;      // entries of a bucket in LDS at a time (16 KB)
+
+// One workgroup per bucket: seeds[first + rank(x)] = train[x.pos] for every entry x of the bucket.
+__global__ void __launch_bounds__(RANK_THREADS) shuffle_rank_kernel(const KeyPos *__restrict__ kp, const int64_t *__restrict__ bucket_off,
+                                                                    const int32_t *__restrict__ train, int32_t *__restrict__ seeds)
+{
+    __shared__ KeyPos tile[RANK_TILE];
+    const int64_t first = bucket_off[blockIdx.x], n = bucket_off[blockIdx.x + 1] - first;
+    for (int64_t e0 = 0; e0 < n; e0 += RANK_THREADS) {                 // the entries this round's threads place (uniform trip count)
+        const int64_t e = e0 + threadIdx.x;
+        const bool have = e < n;
+        KeyPos mine = have ? kp[first + e] : KeyPos{0, 0};
+        int64_t rank = 0;
+        for (int64_t j0 = 0; j0 < n; j0 += RANK_TILE) {
+            const int m = (int)(n - j0 < RANK_TILE ? n - j0 : RANK_TILE);
+            __syncthreads();                                           // the previous tile has been read by everyone
+            for (int j = threadIdx.x; j < m; j += RANK_THREADS) tile[j] = kp[first + j0 + j];
+            __syncthreads();
+            if (have)
+                for (int j = 0; j < m; ++j) rank += kp_less(tile[j], mine) ? 1 : 0;
+        }
+        if (have) seeds[first + rank] = train[mine.pos];
+    }
 }
 
 __global__ void mark_seeds_kernel(const int32_t *__restrict__ seeds, uint64_t T, uint32_t batch_size, uint32_t *__restrict__ seen, uint64_t words_per_batch)
@@ -393,21 +393,6 @@ __global__ void __launch_bounds__(FR_THREADS) fresh_emit_sparse_kernel(uint32_t 
 
 std::atomic<uint64_t> g_next_schedule_uid{1};        // also taken by schedules loaded from a file
 
-static rg_status sort_keypos(KeyPos *kp, uint64_t n_pad, hipStream_t st)
-{
-    // n_pad is a power of two >= SORT_TILE
-    const unsigned lds_blocks = (unsigned)(n_pad / SORT_TILE);
-    const unsigned g_blocks = (unsigned)((n_pad / 2 + SORT_THREADS - 1) / SORT_THREADS);
-    hipLaunchKernelGGL(bitonic_lds_steps, dim3(lds_blocks), dim3(SORT_THREADS), 0, st, kp, (uint64_t)2, (uint64_t)SORT_TILE);
-    for (uint64_t k = (uint64_t)SORT_TILE * 2; k <= n_pad; k <<= 1) {
-        for (uint64_t j = k >> 1; j > SORT_TILE / 2; j >>= 1)
-            hipLaunchKernelGGL(bitonic_global_step, dim3(g_blocks), dim3(SORT_THREADS), 0, st, kp, n_pad, k, j);
-        hipLaunchKernelGGL(bitonic_lds_steps, dim3(lds_blocks), dim3(SORT_THREADS), 0, st, kp, k, k);
-    }
-    RG_HIP(hipGetLastError());
-    return RG_OK;
-}
-
 static rg_status build_schedule_impl(const rg_graph *g, const int32_t *train, uint64_t T, uint32_t B, const uint32_t *fanout,
                                      uint32_t L, uint64_t s0, uint32_t worker, uint32_t epoch, uint32_t sampler, const rg_allocator *a, hipStream_t st, rg_schedule *s)
 {
@@ -433,15 +418,24 @@ static rg_status build_schedule_impl(const rg_graph *g, const int32_t *train, ui
     for (uint32_t b = 0; b <= beta; ++b) h0.off_host[b] = (int64_t)std::min<uint64_t>((uint64_t)b * B, T);
     RG_HIP(hipMemcpyAsync(h0.off_dev, h0.off_host.data(), ((size_t)beta + 1) * sizeof(int64_t), hipMemcpyHostToDevice, st));
     if (T > 0) {
-        uint64_t n_pad = SORT_TILE;
-        while (n_pad < T) n_pad <<= 1;
+        // about a hundred positions per bucket, a power of two of buckets
+        uint32_t bucket_bits = 0;
+        while (bucket_bits < 20 && ((uint64_t)128 << bucket_bits) < T) ++bucket_bits;
+        const uint64_t n_buckets = (uint64_t)1 << bucket_bits;
         KeyPos *kp = nullptr;
-        RG_TRY(tmp.dev_n<KeyPos>(n_pad, &kp));
+        int32_t *bucket_cnt = nullptr;
+        int64_t *bucket_off = nullptr;
+        RG_TRY(tmp.dev_n<KeyPos>(T, &kp));
+        RG_TRY(tmp.dev_n<int32_t>(n_buckets, &bucket_cnt));
+        RG_TRY(tmp.dev_n<int64_t>(n_buckets + 1, &bucket_off));
+        RG_HIP(hipMemsetAsync(bucket_cnt, 0, n_buckets * sizeof(int32_t), st));
         {
             ScopedTimer tm(KG_SORT, st);
-            hipLaunchKernelGGL(shuffle_keys_kernel, dim3((unsigned)((n_pad + 255) / 256)), dim3(256), 0, st, s0, worker, epoch, T, n_pad, kp);
-            RG_TRY(sort_keypos(kp, n_pad, st));
-            hipLaunchKernelGGL(apply_shuffle_kernel, dim3((unsigned)((T + 255) / 256)), dim3(256), 0, st, kp, train, T, h0.ids);
+            const unsigned blocks = (unsigned)((T + 255) / 256);
+            hipLaunchKernelGGL(shuffle_count_kernel, dim3(blocks), dim3(256), 0, st, s0, worker, epoch, T, bucket_bits, bucket_cnt);
+            RG_TRY(scan_i32_to_i64(bucket_cnt, bucket_off, (int64_t)n_buckets, tmp, st));
+            hipLaunchKernelGGL(shuffle_scatter_kernel, dim3(blocks), dim3(256), 0, st, s0, worker, epoch, T, bucket_bits, bucket_off, bucket_cnt, kp);
+            hipLaunchKernelGGL(shuffle_rank_kernel, dim3((unsigned)n_buckets), dim3(RANK_THREADS), 0, st, kp, bucket_off, train, h0.ids);
         }
         RG_HIP(hipGetLastError());
     }
