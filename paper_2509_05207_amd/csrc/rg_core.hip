@@ -273,8 +273,9 @@ static void drain_pending_locked()
 }
 
 // ---------------------------------------------------------------- prefix sum
-// Three launches: per-block totals, one block scanning the totals, per-block
-// local scan plus base.  Each block covers SCAN_TILE consecutive elements.
+// Per-block totals, then per-block local scans plus the sum of the totals in front: one launch for a single block,
+// two while a block can add up its predecessors' totals itself, three (with a scan of the totals between) beyond.
+// Each block covers SCAN_TILE consecutive elements.
 constexpr int SCAN_THREADS = 256;
 constexpr int SCAN_PER_THREAD = 16;
 constexpr int SCAN_TILE = SCAN_THREADS * SCAN_PER_THREAD;
@@ -331,10 +332,19 @@ __global__ void __launch_bounds__(SCAN_THREADS) scan_of_totals(int64_t *__restri
     if (threadIdx.x == 0) *grand_total = carry;
 }
 
+// FUSED: block_base is the raw per-block totals; the block adds up the totals in front of its own (a few thousand
+// at most, see scan_i32_to_i64) instead of reading a scanned table, and the last block writes the grand total.
+template <bool FUSED>
 __global__ void __launch_bounds__(SCAN_THREADS) scan_apply(const int32_t *__restrict__ in, int64_t n, const int64_t *__restrict__ block_base,
                                                            int64_t *__restrict__ out)
 {
     __shared__ int64_t lds[SCAN_THREADS / 64 + 1];
+    int64_t base;
+    if (FUSED) {
+        int64_t part = 0;
+        for (int64_t j = threadIdx.x; j < (int64_t)blockIdx.x; j += SCAN_THREADS) part += block_base[j];
+        (void)block_exclusive_scan_i64(part, &base, lds);
+    } else base = block_base[blockIdx.x];
     // thread t owns SCAN_PER_THREAD consecutive elements so one block scan suffices
     const int64_t first = (int64_t)blockIdx.x * SCAN_TILE + (int64_t)threadIdx.x * SCAN_PER_THREAD;
     int32_t v[SCAN_PER_THREAD];
@@ -345,24 +355,35 @@ __global__ void __launch_bounds__(SCAN_THREADS) scan_apply(const int32_t *__rest
         s += v[k];
     }
     int64_t tot;
-    int64_t run = block_base[blockIdx.x] + block_exclusive_scan_i64(s, &tot, lds);
+    int64_t run = base + block_exclusive_scan_i64(s, &tot, lds);
     for (int k = 0; k < SCAN_PER_THREAD; ++k) {
         int64_t i = first + k;
         if (i < n) out[i] = run;
         run += v[k];
     }
+    if (FUSED && blockIdx.x == gridDim.x - 1 && threadIdx.x == 0) out[n] = base + tot;
 }
+
+constexpr int64_t SCAN_FUSED_BLOCKS = 4096;      // up to here a block adds up its predecessors' totals itself (16 M elements)
 
 rg_status scan_i32_to_i64(const int32_t *in, int64_t *out, int64_t n, Arena &tmp, hipStream_t st)
 {
     const int64_t n_blocks = (n + SCAN_TILE - 1) / SCAN_TILE;
+    if (n_blocks <= 1) {
+        // one block: nothing in front of it, its own total is the grand total (n = 0 writes out[0] = 0)
+        hipLaunchKernelGGL(scan_apply<true>, dim3(1), dim3(SCAN_THREADS), 0, st, in, n, (const int64_t *)nullptr, out);
+        RG_HIP(hipGetLastError());
+        return RG_OK;
+    }
     int64_t *block_tot = nullptr;
-    RG_TRY(tmp.dev_n<int64_t>((uint64_t)(n_blocks > 0 ? n_blocks : 1), &block_tot));
-    if (n_blocks > 0)
-        hipLaunchKernelGGL(scan_block_totals, dim3((unsigned)n_blocks), dim3(SCAN_THREADS), 0, st, in, n, block_tot);
-    hipLaunchKernelGGL(scan_of_totals, dim3(1), dim3(SCAN_THREADS), 0, st, block_tot, n_blocks, out + n);
-    if (n_blocks > 0)
-        hipLaunchKernelGGL(scan_apply, dim3((unsigned)n_blocks), dim3(SCAN_THREADS), 0, st, in, n, block_tot, out);
+    RG_TRY(tmp.dev_n<int64_t>((uint64_t)n_blocks, &block_tot));
+    hipLaunchKernelGGL(scan_block_totals, dim3((unsigned)n_blocks), dim3(SCAN_THREADS), 0, st, in, n, block_tot);
+    if (n_blocks <= SCAN_FUSED_BLOCKS) {
+        hipLaunchKernelGGL(scan_apply<true>, dim3((unsigned)n_blocks), dim3(SCAN_THREADS), 0, st, in, n, block_tot, out);
+    } else {
+        hipLaunchKernelGGL(scan_of_totals, dim3(1), dim3(SCAN_THREADS), 0, st, block_tot, n_blocks, out + n);
+        hipLaunchKernelGGL(scan_apply<false>, dim3((unsigned)n_blocks), dim3(SCAN_THREADS), 0, st, in, n, block_tot, out);
+    }
     RG_HIP(hipGetLastError());
     return RG_OK;
 }

@@ -512,3 +512,19 @@ def test_rows_built_to_defeat_the_guessed_cut(rg, orc, deg):
         got = nbr[so[j]:so[j + 1]]
         assert got.size == f
         assert sum(orc.key32(S, int(u)) <= cut for u in got) == min(nb, f)
+
+
+@pytest.mark.parametrize("T", [1, 2, 127, 128, 129, 255, 257, 1000, 4097, 50000])
+def test_epoch_shuffle_at_the_bucket_bounds(rg, orc, T):
+    """The shuffled order of the train nodes alone (no hops), for sizes on both sides of every change in the number
+    of buckets the device shuffle uses, against the oracle's sort by (key, position)."""
+    rng = np.random.default_rng(T)
+    train = rng.permutation(200000)[:T].astype(np.int32)
+    indptr = torch.zeros(200001, dtype=torch.int64, device="cuda")
+    indices = torch.empty(0, dtype=torch.int32, device="cuda")
+    for s0, worker, epoch in ((0, 0, 0), (12345, 3, 7)):
+        g = rg.rg_build_schedule(indptr, indices, torch.from_numpy(train).cuda(), 100, [], s0, worker, epoch)
+        want = orc.epoch_seeds(train, s0, worker, epoch)
+        got, _, off = rg.rg_schedule_frontier(g, 0)
+        assert np.array_equal(got.cpu().numpy(), want), f"T = {T}: shuffled order differs"
+        assert off[-1] == T and len(off) == (T + 99) // 100 + 1
