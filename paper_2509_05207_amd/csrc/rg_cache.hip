@@ -43,6 +43,9 @@ constexpr int TOPK_THREADS = 256;
 constexpr int DIGIT_BITS = 8;
 constexpr int DIGIT_BINS = 1 << DIGIT_BITS;
 
+// QUADS: a lane takes four consecutive nodes per round (one 16-byte and one 4-byte load; is_local must be 4-byte
+// aligned), the few nodes after the last whole quad one by one.
+template <bool QUADS>
 __global__ void __launch_bounds__(TOPK_THREADS) digit_histogram_kernel(const uint32_t *__restrict__ freq, const uint8_t *__restrict__ is_local, int64_t n,
                                                                        const SelectState *__restrict__ stp, int shift,
                                                                        unsigned long long *__restrict__ bins)
@@ -53,10 +56,21 @@ __global__ void __launch_bounds__(TOPK_THREADS) digit_histogram_kernel(const uin
     const uint32_t prefix = stp->prefix, pmask = stp->prefix_mask;
     if (stp->take_all) return;
     const int64_t stride = (int64_t)gridDim.x * blockDim.x;
-    for (int64_t v = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; v < n; v += stride) {
-        const uint32_t fv = freq[v];
-        if (fv != 0 && !is_local[v] && (fv & pmask) == prefix) atomicAdd(&h[(fv >> shift) & (DIGIT_BINS - 1)], 1u);
+    const int64_t t0 = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    auto count = [&](uint32_t fv, uint32_t local) {
+        if (fv != 0 && !local && (fv & pmask) == prefix) atomicAdd(&h[(fv >> shift) & (DIGIT_BINS - 1)], 1u);
+    };
+    int64_t done = 0;
+    if (QUADS) {
+        const int64_t n_quads = n >> 2;
+        for (int64_t q = t0; q < n_quads; q += stride) {
+            const uint4 fv = reinterpret_cast<const uint4 *>(freq)[q];
+            const uint32_t loc = reinterpret_cast<const uint32_t *>(is_local)[q];
+            count(fv.x, loc & 0xFFu); count(fv.y, (loc >> 8) & 0xFFu); count(fv.z, (loc >> 16) & 0xFFu); count(fv.w, loc >> 24);
+        }
+        done = n_quads << 2;
     }
+    for (int64_t v = done + t0; v < n; v += stride) count(freq[v], is_local[v]);
     __syncthreads();
     for (int k = threadIdx.x; k < DIGIT_BINS; k += TOPK_THREADS)
         if (h[k]) atomicAdd(&bins[k], (unsigned long long)h[k]);
@@ -102,6 +116,27 @@ __device__ __forceinline__ uint64_t classify_node(uint32_t fv, uint8_t local, co
 constexpr int SEL_PER_THREAD = 8;
 constexpr int SEL_TILE = TOPK_THREADS * SEL_PER_THREAD;
 
+// The eight consecutive nodes of a thread, classified.  ALIGNED8 (is_local 8-byte aligned; freq always is, and a
+// thread's first node is a multiple of eight): two 16-byte loads and one 8-byte load when all eight exist.
+template <bool ALIGNED8>
+__device__ __forceinline__ void classify_eight(const uint32_t *__restrict__ freq, const uint8_t *__restrict__ is_local, int64_t first, int64_t n,
+                                               const SelectState &st, uint64_t c[SEL_PER_THREAD])
+{
+    if (ALIGNED8 && first + SEL_PER_THREAD <= n) {
+        const uint4 a = *reinterpret_cast<const uint4 *>(freq + first), b = *reinterpret_cast<const uint4 *>(freq + first + 4);
+        const uint64_t loc = *reinterpret_cast<const uint64_t *>(is_local + first);
+        const uint32_t fv[SEL_PER_THREAD] = {a.x, a.y, a.z, a.w, b.x, b.y, b.z, b.w};
+#pragma unroll
+        for (int k = 0; k < SEL_PER_THREAD; ++k) c[k] = classify_node(fv[k], (uint8_t)(loc >> (8 * k)), st);
+        return;
+    }
+#pragma unroll
+    for (int k = 0; k < SEL_PER_THREAD; ++k) {
+        const int64_t v = first + k;
+        c[k] = v < n ? classify_node(freq[v], is_local[v], st) : 0;
+    }
+}
+
 __device__ __forceinline__ uint64_t block_exclusive_scan_u64(uint64_t x, uint64_t *total, uint64_t *lds)
 {
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -123,36 +158,45 @@ __device__ __forceinline__ uint64_t block_exclusive_scan_u64(uint64_t x, uint64_
     return base + incl - x;
 }
 
+template <bool ALIGNED8>
 __global__ void __launch_bounds__(TOPK_THREADS) select_block_totals(const uint32_t *__restrict__ freq, const uint8_t *__restrict__ is_local, int64_t n,
                                                                     const SelectState *__restrict__ stp, uint64_t *__restrict__ block_tot)
 {
     __shared__ uint64_t lds[TOPK_THREADS / 64];
     const SelectState st = *stp;
     const int64_t first = (int64_t)blockIdx.x * SEL_TILE + (int64_t)threadIdx.x * SEL_PER_THREAD;
+    uint64_t c[SEL_PER_THREAD];
+    classify_eight<ALIGNED8>(freq, is_local, first, n, st, c);
     uint64_t s = 0;
-    for (int k = 0; k < SEL_PER_THREAD; ++k) {
-        const int64_t v = first + k;
-        if (v < n) s += classify_node(freq[v], is_local[v], st);
-    }
+#pragma unroll
+    for (int k = 0; k < SEL_PER_THREAD; ++k) s += c[k];
     uint64_t tot;
     (void)block_exclusive_scan_u64(s, &tot, lds);
     if (threadIdx.x == 0) block_tot[blockIdx.x] = tot;
 }
 
+// One workgroup; a thread takes eight consecutive totals per round.
 __global__ void __launch_bounds__(TOPK_THREADS) select_scan_totals(uint64_t *__restrict__ block_tot, int64_t n_blocks)
 {
     __shared__ uint64_t lds[TOPK_THREADS / 64];
     uint64_t carry = 0;
-    for (int64_t base = 0; base < n_blocks; base += TOPK_THREADS) {
-        const int64_t i = base + threadIdx.x;
-        const uint64_t x = i < n_blocks ? block_tot[i] : 0;
+    for (int64_t base = 0; base < n_blocks; base += (int64_t)TOPK_THREADS * 8) {
+        const int64_t i0 = base + (int64_t)threadIdx.x * 8;
+        uint64_t x[8], sum = 0;
+#pragma unroll
+        for (int k = 0; k < 8; ++k) { x[k] = i0 + k < n_blocks ? block_tot[i0 + k] : 0; sum += x[k]; }
         uint64_t tot;
-        const uint64_t ex = block_exclusive_scan_u64(x, &tot, lds);
-        if (i < n_blocks) block_tot[i] = carry + ex;
+        uint64_t run = carry + block_exclusive_scan_u64(sum, &tot, lds);
+#pragma unroll
+        for (int k = 0; k < 8; ++k) {
+            if (i0 + k < n_blocks) block_tot[i0 + k] = run;
+            run += x[k];
+        }
         carry += tot;
     }
 }
 
+template <bool ALIGNED8>
 __global__ void __launch_bounds__(TOPK_THREADS) select_emit_kernel(const uint32_t *__restrict__ freq, const uint8_t *__restrict__ is_local, int64_t n,
                                                                    const SelectState *__restrict__ stp, const uint64_t *__restrict__ block_base,
                                                                    int32_t *__restrict__ cache_ids, int32_t *__restrict__ slot_of)
@@ -161,27 +205,32 @@ __global__ void __launch_bounds__(TOPK_THREADS) select_emit_kernel(const uint32_
     const SelectState st = *stp;
     const int64_t first = (int64_t)blockIdx.x * SEL_TILE + (int64_t)threadIdx.x * SEL_PER_THREAD;
     uint64_t c[SEL_PER_THREAD];
+    classify_eight<ALIGNED8>(freq, is_local, first, n, st, c);
     uint64_t s = 0;
-    for (int k = 0; k < SEL_PER_THREAD; ++k) {
-        const int64_t v = first + k;
-        c[k] = v < n ? classify_node(freq[v], is_local[v], st) : 0;
-        s += c[k];
-    }
+#pragma unroll
+    for (int k = 0; k < SEL_PER_THREAD; ++k) s += c[k];
     uint64_t tot;
     uint64_t run = block_base[blockIdx.x] + block_exclusive_scan_u64(s, &tot, lds);
+    int32_t slots[SEL_PER_THREAD];
+#pragma unroll
     for (int k = 0; k < SEL_PER_THREAD; ++k) {
         const int64_t v = first + k;
-        if (v < n) {
-            const uint64_t gt_before = run >> 32, eq_before = run & 0xFFFFFFFFull;
-            const bool sel = (c[k] >> 32) != 0 || (c[k] == 1 && eq_before < st.r);
-            int32_t slot = -1;
-            if (sel) {
-                slot = (int32_t)(gt_before + (eq_before < st.r ? eq_before : st.r));
-                cache_ids[slot] = (int32_t)v;
-            }
-            slot_of[v] = slot;
+        const uint64_t gt_before = run >> 32, eq_before = run & 0xFFFFFFFFull;
+        const bool sel = v < n && ((c[k] >> 32) != 0 || (c[k] == 1 && eq_before < st.r));
+        slots[k] = -1;
+        if (sel) {
+            slots[k] = (int32_t)(gt_before + (eq_before < st.r ? eq_before : st.r));
+            cache_ids[slots[k]] = (int32_t)v;
         }
         run += c[k];
+    }
+    if (first + SEL_PER_THREAD <= n) {                     // slot_of is the library's own array: 16-byte aligned at a multiple of eight
+        *reinterpret_cast<int4 *>(slot_of + first) = make_int4(slots[0], slots[1], slots[2], slots[3]);
+        *reinterpret_cast<int4 *>(slot_of + first + 4) = make_int4(slots[4], slots[5], slots[6], slots[7]);
+    } else {
+#pragma unroll
+        for (int k = 0; k < SEL_PER_THREAD; ++k)
+            if (first + k < n) slot_of[first + k] = slots[k];
     }
 }
 
@@ -387,6 +436,7 @@ static rg_status build_cache_impl(const rg_schedule *const *epochs, uint32_t n_e
     int bits = 1;
     while (bits < 32 && (max_freq >> bits) != 0) ++bits;
     const int passes = (bits + DIGIT_BITS - 1) / DIGIT_BITS;
+    const bool local4 = ((uintptr_t)f->is_local & 3) == 0, local8 = ((uintptr_t)f->is_local & 7) == 0;      // the caller's array: wide loads only if it allows them
     const int64_t sel_blocks = (n + SEL_TILE - 1) / SEL_TILE;
     uint64_t *block_tot = nullptr;
     RG_TRY(tmp.dev_n<uint64_t>((uint64_t)(sel_blocks ? sel_blocks : 1), &block_tot));
@@ -395,11 +445,13 @@ static rg_status build_cache_impl(const rg_schedule *const *epochs, uint32_t n_e
         const unsigned grid = (unsigned)std::max<int64_t>(1, std::min<int64_t>((n + TOPK_THREADS - 1) / TOPK_THREADS, (int64_t)n_cu * 16));
         for (int p = 0; p < passes; ++p) {
             const int shift = (passes - 1 - p) * DIGIT_BITS;
-            hipLaunchKernelGGL(digit_histogram_kernel, dim3(grid), dim3(TOPK_THREADS), 0, st, c->freq, f->is_local, n, stp, shift, bins);
+            if (local4) hipLaunchKernelGGL(digit_histogram_kernel<true>, dim3(grid), dim3(TOPK_THREADS), 0, st, c->freq, f->is_local, n, stp, shift, bins);
+            else hipLaunchKernelGGL(digit_histogram_kernel<false>, dim3(grid), dim3(TOPK_THREADS), 0, st, c->freq, f->is_local, n, stp, shift, bins);
             hipLaunchKernelGGL(choose_digit_kernel, dim3(1), dim3(64), 0, st, stp, bins, shift, p == 0 ? 1 : 0, K);
         }
         if (sel_blocks > 0) {
-            hipLaunchKernelGGL(select_block_totals, dim3((unsigned)sel_blocks), dim3(TOPK_THREADS), 0, st, c->freq, f->is_local, n, stp, block_tot);
+            if (local8) hipLaunchKernelGGL(select_block_totals<true>, dim3((unsigned)sel_blocks), dim3(TOPK_THREADS), 0, st, c->freq, f->is_local, n, stp, block_tot);
+            else hipLaunchKernelGGL(select_block_totals<false>, dim3((unsigned)sel_blocks), dim3(TOPK_THREADS), 0, st, c->freq, f->is_local, n, stp, block_tot);
             hipLaunchKernelGGL(select_scan_totals, dim3(1), dim3(TOPK_THREADS), 0, st, block_tot, sel_blocks);
         }
     }
@@ -413,8 +465,10 @@ static rg_status build_cache_impl(const rg_schedule *const *epochs, uint32_t n_e
     RG_TRY(c->arena.dev_n<int32_t>(c->K_eff, &c->cache_ids));
     if (sel_blocks > 0) {
         ScopedTimer tm(KG_TOPK, st);
-        hipLaunchKernelGGL(select_emit_kernel, dim3((unsigned)sel_blocks), dim3(TOPK_THREADS), 0, st, c->freq, f->is_local, n, stp, block_tot,
-                           c->cache_ids, c->slot_of);
+        if (local8) hipLaunchKernelGGL(select_emit_kernel<true>, dim3((unsigned)sel_blocks), dim3(TOPK_THREADS), 0, st, c->freq, f->is_local, n, stp, block_tot,
+                                       c->cache_ids, c->slot_of);
+        else hipLaunchKernelGGL(select_emit_kernel<false>, dim3((unsigned)sel_blocks), dim3(TOPK_THREADS), 0, st, c->freq, f->is_local, n, stp, block_tot,
+                                c->cache_ids, c->slot_of);
     }
     RG_HIP(hipGetLastError());
 

@@ -528,3 +528,21 @@ def test_epoch_shuffle_at_the_bucket_bounds(rg, orc, T):
         got, _, off = rg.rg_schedule_frontier(g, 0)
         assert np.array_equal(got.cpu().numpy(), want), f"T = {T}: shuffled order differs"
         assert off[-1] == T and len(off) == (T + 99) // 100 + 1
+
+
+def test_top_hot_with_an_unaligned_locality_array(case, rg, orc):
+    """TopHot reads is_local with wide loads when its address allows them: the same array at an odd address (the
+    one-by-one path) selects the same cache."""
+    w = case.w
+    shifted = torch.empty(w.n_nodes + 1, dtype=torch.uint8, device="cuda")
+    shifted[1:] = case.is_local
+    odd = shifted[1:]
+    assert odd.data_ptr() % 2 == 1
+    feat = rg.make_features(odd, case.row_of, case.local_rows, case.remote_rows, w.row_bytes)
+    a = rg.rg_cache_view(rg.rg_build_cache([case.gsched], case.gfeat, w.K), w.n_nodes)
+    b = rg.rg_cache_view(rg.rg_build_cache([case.gsched], feat, w.K), w.n_nodes)
+    ids, slot = orc.top_hot(orc.frequency([case.osched], w.n_nodes), w.is_local.numpy(), w.K)
+    for v in (a, b):
+        assert v["K_eff"] == ids.size
+        assert np.array_equal(v["cache_ids"].cpu().numpy(), ids)
+        assert np.array_equal(v["slot_of"].cpu().numpy(), slot)
