@@ -506,6 +506,11 @@ __device__ __forceinline__ void sample_long_row(const int32_t *__restrict__ row,
             if (my_bit(m[e])) buf[rank++] = u[e];
         cur = nxt;
         c0 = 1;
+    } else if (guess && head > 0) {
+        // under the guessed cut the head's candidates (at most 31, into an empty buffer) need no more than a rank
+        const unsigned long long m = ballot64(key32(lo, hi, head_u) <= s.cut) & low_lanes(head);
+        if (my_bit(m)) buf[lanes_below(m, lane)] = head_u;
+        s.cnt = __popcll(m);
     } else if (head > 0) {
         const uint32_t u[4] = {head_u, 0u, 0u, 0u};
         const uint32_t k[4] = {key32(lo, hi, u[0]), 0u, 0u, 0u};
