@@ -321,9 +321,12 @@ __global__ void __launch_bounds__(PLAN_THREADS) plan_kernel(const int32_t *__res
 __global__ void miss_list_kernel(const int32_t *__restrict__ miss_flag, const int64_t *__restrict__ miss_scan, int64_t n,
                                  const int64_t *__restrict__ batch_off, uint32_t n_batches, int32_t *__restrict__ miss_rows)
 {
-    const int64_t j = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const int64_t j0 = (int64_t)blockIdx.x * blockDim.x, j = j0 + threadIdx.x;
+    // almost every workgroup lies inside one batch: its first row's batch then serves all of its rows
+    const uint32_t b_first = batch_of_pos(batch_off, n_batches, j0);
+    const int64_t end_first = batch_off[b_first + 1];
     if (j >= n || !miss_flag[j]) return;
-    const uint32_t b = batch_of_pos(batch_off, n_batches, j);
+    const uint32_t b = j < end_first ? b_first : batch_of_pos(batch_off, n_batches, j);
     miss_rows[miss_scan[j]] = (int32_t)(j - batch_off[b]);
 }
 
