@@ -40,6 +40,7 @@
 #include "rg_device.h"
 
 #include <algorithm>
+#include <cstdlib>
 #include <atomic>
 
 namespace rg {
@@ -95,16 +96,24 @@ __global__ void node_records_kernel(const int64_t *__restrict__ indptr, const in
     tiles[i] = (int32_t)tiles_of(deg);
 }
 
-// total += sum of deg[0..n): what the hop will read of the adjacency, in IDs
+// total[0] += sum of deg[0..n): what the hop will read of the adjacency, in IDs; total[1] += the part of it in rows of
+// up to BIG_ROW IDs (the rows that are sampled inside the groups of nodes, not as tiles)
 __global__ void __launch_bounds__(256) sum_degrees_kernel(const int32_t *__restrict__ deg, int64_t n, unsigned long long *__restrict__ total)
 {
-    __shared__ unsigned long long part[4];
-    unsigned long long acc = 0;
-    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (int64_t)gridDim.x * blockDim.x) acc += (unsigned long long)(uint32_t)deg[i];
-    for (int o = 32; o > 0; o >>= 1) acc += __shfl_down(acc, o, 64);
-    if ((threadIdx.x & 63) == 0) part[threadIdx.x >> 6] = acc;
+    __shared__ unsigned long long part[2][4];
+    unsigned long long acc = 0, acc_groups = 0;
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (int64_t)gridDim.x * blockDim.x) {
+        const unsigned long long d = (unsigned long long)(uint32_t)deg[i];
+        acc += d;
+        if (d <= (unsigned long long)BIG_ROW) acc_groups += d;
+    }
+    for (int o = 32; o > 0; o >>= 1) { acc += __shfl_down(acc, o, 64); acc_groups += __shfl_down(acc_groups, o, 64); }
+    if ((threadIdx.x & 63) == 0) { part[0][threadIdx.x >> 6] = acc; part[1][threadIdx.x >> 6] = acc_groups; }
     __syncthreads();
-    if (threadIdx.x == 0) atomicAdd(total, part[0] + part[1] + part[2] + part[3]);
+    if (threadIdx.x == 0) {
+        atomicAdd(total, part[0][0] + part[0][1] + part[0][2] + part[0][3]);
+        atomicAdd(total + 1, part[1][0] + part[1][1] + part[1][2] + part[1][3]);
+    }
 }
 
 // Number of set bits of m below this lane's bit (m wave-uniform): the two mbcnt instructions.
@@ -634,6 +643,7 @@ __global__ void tile_records_kernel(const int64_t *__restrict__ tile_off, const 
 struct HopArgs {
     const int32_t *indices;
     const int32_t *frontier; int64_t n_frontier;
+    int64_t n_full_groups, n_units;                                    // set by launch_hop: see there
     NodeRecs rec;
     uint32_t fanout;
     const int64_t *samp_off; int32_t *samp_nbr;
@@ -660,7 +670,6 @@ __global__ void __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(CAP <= 
     __shared__ uint32_t buf[CAP];
     const int lane = threadIdx.x;
     const int f = (int)a.fanout;
-    const int64_t n_groups = (a.n_frontier + 63) >> 6;
 #ifdef RG_PHASE_TIMERS
     if (lane < PH_COUNT) phase_acc[lane] = 0;
     __syncthreads();
@@ -694,12 +703,15 @@ __global__ void __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(CAP <= 
     RG_TSET(t_ask);
 #endif
     // Then the groups of 64 consecutive frontier nodes, taken as waves become free, so that uneven rows do not leave
-    // part of the chip idle at the end; every wave leaves once the counter has passed the last group.
-    for (int64_t w = grab_work(a.next_work, lane); w < n_groups; w = grab_work(a.next_work, lane)) {
+    // part of the chip idle at the end -- and for the same reason the launch's last nodes come in groups of 16 (a group
+    // of 64 nodes with long rows is a sizeable part of a launch's whole duration); every wave leaves once the counter
+    // has passed the last group.
+    for (int64_t w = grab_work(a.next_work, lane); w < a.n_units; w = grab_work(a.next_work, lane)) {
         RG_TADD(PH_WORK_COUNTER, t_ask);
         RG_T0(t_group);
-        const int64_t i_lane = (w << 6) + lane;
-        const bool in = i_lane < a.n_frontier;
+        const bool full = w < a.n_full_groups;                  // 64 nodes, or 16 of the launch's last nodes
+        const int64_t i_lane = (full ? w << 6 : (a.n_full_groups << 6) + ((w - a.n_full_groups) << 4)) + lane;
+        const bool in = (full || lane < 16) && i_lane < a.n_frontier;
         const int64_t rb_lane = in ? a.rec.row_begin[i_lane] : 0;
         const int deg_lane = in ? a.rec.deg[i_lane] : 0;
         const uint32_t b_lane = in ? a.rec.batch[i_lane] : 0u;
@@ -784,8 +796,9 @@ __global__ void __launch_bounds__(64) sample_merge_kernel(HopArgs a)
 // Every workgroup of the sampling launch must be resident from the start (tiles are dealt out by workgroup index), so
 // the grid is what the chip holds of this kernel, or the amount of work if that is less.
 template <int CAP, int MARK>
-static rg_status launch_hop(const HopArgs &a, int n_cu, unsigned merge_grid, hipStream_t st)
+static rg_status launch_hop(const HopArgs &args, int n_cu, unsigned merge_grid, bool fine_tail, hipStream_t st)
 {
+    HopArgs a = args;
     static std::atomic<int> asked{0};         // the same answer every time; asked once (schedules may be built from several threads)
     int per_cu = asked.load(std::memory_order_relaxed);
     if (per_cu == 0) {
@@ -794,8 +807,14 @@ static rg_status launch_hop(const HopArgs &a, int n_cu, unsigned merge_grid, hip
         per_cu = v > 0 ? v : 1;
         asked.store(per_cu, std::memory_order_relaxed);
     }
-    const int64_t n_work = a.n_tiles + (a.n_frontier + 63) / 64;
-    const unsigned grid = (unsigned)std::max<int64_t>(1, std::min<int64_t>(n_work, (int64_t)n_cu * per_cu));
+    // Groups of 64 nodes, except that with fine_tail the last 128 nodes per resident wave (and always what is left of
+    // the frontier after the last whole group) are handed out 16 at a time.
+    const int64_t resident = (int64_t)n_cu * per_cu;
+    const int64_t tail_nodes = fine_tail ? std::min<int64_t>(a.n_frontier, resident * 128) : 0;
+    a.n_full_groups = (a.n_frontier - tail_nodes) / 64;
+    a.n_units = a.n_full_groups + (a.n_frontier - a.n_full_groups * 64 + 15) / 16;
+    const int64_t n_work = a.n_tiles + a.n_units;
+    const unsigned grid = (unsigned)std::max<int64_t>(1, std::min<int64_t>(n_work, resident));
     hipLaunchKernelGGL((sample_kernel<CAP, MARK>), dim3(grid), dim3(64), 0, st, a);
     if (a.n_tiles > 0) hipLaunchKernelGGL((sample_merge_kernel<CAP, MARK>), dim3(merge_grid), dim3(64), 0, st, a);
     return RG_OK;
@@ -860,18 +879,18 @@ rg_status sample_hop(const rg_graph *g, HopData &cur, uint32_t beta, const uint6
         RG_TRY(scan_i32_to_i64(tiles, tile_off, n_cur, tmp, st));
     }
     int64_t n_tiles = 0;
-    unsigned long long sum_deg = 0, *sum_deg_dev = nullptr;
+    unsigned long long sums[2] = {0, 0}, *sum_deg_dev = nullptr;       // IDs in all rows of the frontier, IDs in its rows outside tiles
     // (the byte-marking kernels exist for fan-outs up to 192: the two smaller candidate buffers)
     const bool can_bytes = maps.bytes_allowed && (sampler == RG_SAMPLER_POSITIONS || fanout + 64 <= 256);
-    if (can_bytes && prefer_bytes < 0) {
-        RG_TRY(tmp.dev_n<unsigned long long>(1, &sum_deg_dev));
-        RG_HIP(hipMemsetAsync(sum_deg_dev, 0, sizeof(unsigned long long), st));
+    {
+        RG_TRY(tmp.dev_n<unsigned long long>(2, &sum_deg_dev));
+        RG_HIP(hipMemsetAsync(sum_deg_dev, 0, 2 * sizeof(unsigned long long), st));
         if (n_cur > 0)
             hipLaunchKernelGGL(sum_degrees_kernel, dim3((unsigned)std::min<int64_t>((n_cur + 255) / 256, 1024)), dim3(256), 0, st, rec.deg, n_cur, sum_deg_dev);
     }
     {
         Readback rb(st);
-        if (sum_deg_dev) RG_TRY(rb.add(&sum_deg, sum_deg_dev, sizeof(unsigned long long)));
+        if (sum_deg_dev) RG_TRY(rb.add(sums, sum_deg_dev, sizeof(sums)));
         RG_TRY(rb.add(&cur.n_samples, cur.samp_off + n_cur, sizeof(int64_t)));
         RG_TRY(rb.add(&n_tiles, tile_off + n_cur, sizeof(int64_t)));
         RG_TRY(rb.wait());
@@ -881,6 +900,7 @@ rg_status sample_hop(const rg_graph *g, HopData &cur, uint32_t beta, const uint6
     // large part of the hop's traffic (rows mostly no longer than the fan-out: one mark per ID read), and costs a
     // little where long rows are scanned for a few samples (measured: at one mark per 20 IDs read nothing is gained,
     // at one per 10 the hop is a quarter faster).  Threshold: one mark per 14 IDs read.
+    const unsigned long long sum_deg = sums[0];
     const bool use_bytes = can_bytes && (prefer_bytes >= 0 ? prefer_bytes != 0 : (unsigned long long)cur.n_samples * 14ull >= sum_deg);
     if (use_bytes && !maps.bytes) {
         const uint64_t map_bytes = maps.words_per_batch * 32 * (uint64_t)beta;
@@ -924,15 +944,19 @@ rg_status sample_hop(const rg_graph *g, HopData &cur, uint32_t beta, const uint6
         unsigned long long *next_work = nullptr;
         RG_TRY(tmp.dev_n<unsigned long long>(1, &next_work));
         RG_HIP(hipMemsetAsync(next_work, 0, sizeof(unsigned long long), st));
-        HopArgs a{g->indices, cur.ids, n_cur, rec, fanout, cur.samp_off, cur.samp_nbr, tile_off, tile, n_tiles, tile_out, reached, next_work};
+        HopArgs a{g->indices, cur.ids, n_cur, 0, 0, rec, fanout, cur.samp_off, cur.samp_nbr, tile_off, tile, n_tiles, tile_out, reached, next_work};
         ScopedTimer tm(KG_SAMPLER, st);
         const unsigned merge_grid = (unsigned)std::max<int64_t>(1, std::min<int64_t>(n_tiles, (int64_t)n_cu * 64));
+        // worth it where a group is long work: rows of a thousand IDs on average, tiles aside (short rows finish a
+        // group of 64 in no time, and four times the requests to the work counter then cost more than the tail does;
+        // measured: Medium, 2,500 IDs per row, 4 % faster; large_sparse and partition_share, a few hundred, 1-8 % slower)
+        const bool fine_tail = sums[1] >= 1024ull * (unsigned long long)n_cur;
         const uint32_t need = fanout + 64;
-        if (need <= 128) { if (use_bytes) RG_TRY((launch_hop<128, MARK_BYTES>(a, n_cu, merge_grid, st))); else RG_TRY((launch_hop<128, MARK_BITS>(a, n_cu, merge_grid, st))); }
-        else if (need <= 256) { if (use_bytes) RG_TRY((launch_hop<256, MARK_BYTES>(a, n_cu, merge_grid, st))); else RG_TRY((launch_hop<256, MARK_BITS>(a, n_cu, merge_grid, st))); }
-        else if (need <= 512) RG_TRY((launch_hop<512, MARK_BITS>(a, n_cu, merge_grid, st)));
-        else if (need <= 1024) RG_TRY((launch_hop<1024, MARK_BITS>(a, n_cu, merge_grid, st)));
-        else RG_TRY((launch_hop<2048, MARK_BITS>(a, n_cu, merge_grid, st)));
+        if (need <= 128) { if (use_bytes) RG_TRY((launch_hop<128, MARK_BYTES>(a, n_cu, merge_grid, fine_tail, st))); else RG_TRY((launch_hop<128, MARK_BITS>(a, n_cu, merge_grid, fine_tail, st))); }
+        else if (need <= 256) { if (use_bytes) RG_TRY((launch_hop<256, MARK_BYTES>(a, n_cu, merge_grid, fine_tail, st))); else RG_TRY((launch_hop<256, MARK_BITS>(a, n_cu, merge_grid, fine_tail, st))); }
+        else if (need <= 512) RG_TRY((launch_hop<512, MARK_BITS>(a, n_cu, merge_grid, fine_tail, st)));
+        else if (need <= 1024) RG_TRY((launch_hop<1024, MARK_BITS>(a, n_cu, merge_grid, fine_tail, st)));
+        else RG_TRY((launch_hop<2048, MARK_BITS>(a, n_cu, merge_grid, fine_tail, st)));
         RG_HIP(hipGetLastError());
     }
     return RG_OK;
