@@ -796,7 +796,7 @@ __global__ void __launch_bounds__(64) sample_merge_kernel(HopArgs a)
 // Every workgroup of the sampling launch must be resident from the start (tiles are dealt out by workgroup index), so
 // the grid is what the chip holds of this kernel, or the amount of work if that is less.
 template <int CAP, int MARK>
-static rg_status launch_hop(const HopArgs &args, int n_cu, unsigned merge_grid, bool fine_tail, hipStream_t st)
+static rg_status launch_hop(const HopArgs &args, int n_cu, unsigned merge_grid, bool fine_tail, bool fine_if_few, hipStream_t st)
 {
     HopArgs a = args;
     static std::atomic<int> asked{0};         // the same answer every time; asked once (schedules may be built from several threads)
@@ -810,7 +810,8 @@ static rg_status launch_hop(const HopArgs &args, int n_cu, unsigned merge_grid, 
     // Groups of 64 nodes, except that with fine_tail the last 128 nodes per resident wave (and always what is left of
     // the frontier after the last whole group) are handed out 16 at a time.
     const int64_t resident = (int64_t)n_cu * per_cu;
-    const int64_t tail_nodes = fine_tail ? std::min<int64_t>(a.n_frontier, resident * 128) : 0;
+    int64_t tail_nodes = fine_tail ? std::min<int64_t>(a.n_frontier, resident * 128) : 0;
+    if (fine_if_few && a.n_frontier < resident * 64) tail_nodes = a.n_frontier;       // fewer groups of 64 than waves: sixteens throughout
     a.n_full_groups = (a.n_frontier - tail_nodes) / 64;
     a.n_units = a.n_full_groups + (a.n_frontier - a.n_full_groups * 64 + 15) / 16;
     const int64_t n_work = a.n_tiles + a.n_units;
@@ -951,12 +952,14 @@ rg_status sample_hop(const rg_graph *g, HopData &cur, uint32_t beta, const uint6
         // group of 64 in no time, and four times the requests to the work counter then cost more than the tail does;
         // measured: Medium, 2,500 IDs per row, 4 % faster; large_sparse and partition_share, a few hundred, 1-8 % slower)
         const bool fine_tail = sums[1] >= 1024ull * (unsigned long long)n_cur;
+        // a frontier that does not give every resident wave a group of 64 (the seed hop) is split finer from rows of 256 IDs on
+        const bool fine_if_few = sums[1] >= 256ull * (unsigned long long)n_cur;
         const uint32_t need = fanout + 64;
-        if (need <= 128) { if (use_bytes) RG_TRY((launch_hop<128, MARK_BYTES>(a, n_cu, merge_grid, fine_tail, st))); else RG_TRY((launch_hop<128, MARK_BITS>(a, n_cu, merge_grid, fine_tail, st))); }
-        else if (need <= 256) { if (use_bytes) RG_TRY((launch_hop<256, MARK_BYTES>(a, n_cu, merge_grid, fine_tail, st))); else RG_TRY((launch_hop<256, MARK_BITS>(a, n_cu, merge_grid, fine_tail, st))); }
-        else if (need <= 512) RG_TRY((launch_hop<512, MARK_BITS>(a, n_cu, merge_grid, fine_tail, st)));
-        else if (need <= 1024) RG_TRY((launch_hop<1024, MARK_BITS>(a, n_cu, merge_grid, fine_tail, st)));
-        else RG_TRY((launch_hop<2048, MARK_BITS>(a, n_cu, merge_grid, fine_tail, st)));
+        if (need <= 128) { if (use_bytes) RG_TRY((launch_hop<128, MARK_BYTES>(a, n_cu, merge_grid, fine_tail, fine_if_few, st))); else RG_TRY((launch_hop<128, MARK_BITS>(a, n_cu, merge_grid, fine_tail, fine_if_few, st))); }
+        else if (need <= 256) { if (use_bytes) RG_TRY((launch_hop<256, MARK_BYTES>(a, n_cu, merge_grid, fine_tail, fine_if_few, st))); else RG_TRY((launch_hop<256, MARK_BITS>(a, n_cu, merge_grid, fine_tail, fine_if_few, st))); }
+        else if (need <= 512) RG_TRY((launch_hop<512, MARK_BITS>(a, n_cu, merge_grid, fine_tail, fine_if_few, st)));
+        else if (need <= 1024) RG_TRY((launch_hop<1024, MARK_BITS>(a, n_cu, merge_grid, fine_tail, fine_if_few, st)));
+        else RG_TRY((launch_hop<2048, MARK_BITS>(a, n_cu, merge_grid, fine_tail, fine_if_few, st)));
         RG_HIP(hipGetLastError());
     }
     return RG_OK;
