@@ -114,7 +114,9 @@ __device__ __forceinline__ uint32_t batch_of(const int64_t *__restrict__ off, ui
 // wave waits for neither; a hop uses the form that suits its traffic (see sample_hop).  Beside the map there is one
 // flag byte per 256 IDs: the frontier passes read the flags and touch only the flagged groups, which on a graph of
 // 10^8 nodes is a few per cent of the map.
-constexpr int MARK_NONE = 0, MARK_BITS = 1, MARK_BYTES = 2;     // what a kernel does with a sampled ID (a template argument)
+// What a kernel does with a sampled ID (a template argument).  MARK_BYTES_ALL: the byte form without the flag store,
+// for a hop that reaches nearly every group anyway; its caller sets every flag instead.
+constexpr int MARK_NONE = 0, MARK_BITS = 1, MARK_BYTES = 2, MARK_BYTES_ALL = 3;
 struct ReachedForms {             // host side: the forms a schedule build holds
     uint32_t *words;              // [n_batches * words_per_batch]
     uint8_t *bytes;               // [n_batches * words_per_batch * 32]; NULL until the first hop that wants it
@@ -134,13 +136,14 @@ struct ReachedOfBatch {
 template <int MARK>
 __device__ __forceinline__ ReachedOfBatch reached_of(const ReachedMaps &m, uint32_t batch)
 {
-    const uint64_t step = MARK == MARK_BYTES ? m.words_per_batch << 5 : m.words_per_batch << 2;       // bytes per batch
+    const uint64_t step = (MARK == MARK_BYTES || MARK == MARK_BYTES_ALL) ? m.words_per_batch << 5 : m.words_per_batch << 2;       // bytes per batch
     return ReachedOfBatch{static_cast<uint8_t *>(m.map) + (uint64_t)batch * step, m.flags + (uint64_t)batch * (m.words_per_batch >> 3)};
 }
 template <int MARK>
 __device__ __forceinline__ void mark_reached(const ReachedOfBatch &r, uint32_t u)
 {
     if (MARK == MARK_NONE) return;
+    if (MARK == MARK_BYTES_ALL) { static_cast<uint8_t *>(r.map)[u] = 1; return; }
     if (MARK == MARK_BYTES) static_cast<uint8_t *>(r.map)[u] = 1;
     else (void)__hip_atomic_fetch_or(static_cast<uint32_t *>(r.map) + (u >> 5), 1u << (u & 31), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     r.flags[u >> 8] = 1;
