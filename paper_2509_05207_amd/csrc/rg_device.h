@@ -114,9 +114,9 @@ __device__ __forceinline__ uint32_t batch_of(const int64_t *__restrict__ off, ui
 // wave waits for neither; a hop uses the form that suits its traffic (see sample_hop).  Beside the map there is one
 // flag byte per 256 IDs: the frontier passes read the flags and touch only the flagged groups, which on a graph of
 // 10^8 nodes is a few per cent of the map.
-// What a kernel does with a sampled ID (a template argument).  MARK_BYTES_ALL: the byte form without the flag store,
-// for a hop that reaches nearly every group anyway; its caller sets every flag instead.
-constexpr int MARK_NONE = 0, MARK_BITS = 1, MARK_BYTES = 2, MARK_BYTES_ALL = 3;
+// What a kernel does with a sampled ID (a template argument).  MARK_BYTES_ALL, MARK_BITS_ALL: the same forms without
+// the flag store, for a hop that reaches nearly every group anyway; its caller sets every flag instead.
+constexpr int MARK_NONE = 0, MARK_BITS = 1, MARK_BYTES = 2, MARK_BYTES_ALL = 3, MARK_BITS_ALL = 4;
 struct ReachedForms {             // host side: the forms a schedule build holds
     uint32_t *words;              // [n_batches * words_per_batch]
     uint8_t *bytes;               // [n_batches * words_per_batch * 32]; NULL until the first hop that wants it
@@ -146,7 +146,7 @@ __device__ __forceinline__ void mark_reached(const ReachedOfBatch &r, uint32_t u
     if (MARK == MARK_BYTES_ALL) { static_cast<uint8_t *>(r.map)[u] = 1; return; }
     if (MARK == MARK_BYTES) static_cast<uint8_t *>(r.map)[u] = 1;
     else (void)__hip_atomic_fetch_or(static_cast<uint32_t *>(r.map) + (u >> 5), 1u << (u & 31), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    r.flags[u >> 8] = 1;
+    if (MARK != MARK_BITS_ALL) r.flags[u >> 8] = 1;
 }
 
 }  // namespace rg

@@ -912,7 +912,7 @@ rg_status sample_hop(const rg_graph *g, HopData &cur, uint32_t beta, const uint6
     // A hop that marks many times more IDs than the maps have groups reaches nearly every group: the per-mark flag
     // store (a third of the hop's scattered stores) is replaced by setting every flag once.
     const uint64_t flag_bytes = maps.words_per_batch / 8 * (uint64_t)beta;
-    const bool all_flags = use_bytes && sampler == RG_SAMPLER_KEYS && fanout > 0 && (uint64_t)cur.n_samples >= 16 * flag_bytes;
+    const bool all_flags = sampler == RG_SAMPLER_KEYS && fanout > 0 && fanout + 64 <= 256 && (uint64_t)cur.n_samples >= 16 * flag_bytes;
     if (all_flags) RG_HIP(hipMemsetAsync(maps.flags, 1, flag_bytes, st));
     const ReachedMaps reached{use_bytes ? (void *)maps.bytes : (void *)maps.words, maps.flags, maps.words_per_batch};
     tmp.free_one(cnt);
@@ -961,11 +961,13 @@ rg_status sample_hop(const rg_graph *g, HopData &cur, uint32_t beta, const uint6
         const bool fine_if_few = sums[1] >= 256ull * (unsigned long long)n_cur;
         const uint32_t need = fanout + 64;
         if (need <= 128) {
-            if (all_flags) RG_TRY((launch_hop<128, MARK_BYTES_ALL>(a, n_cu, merge_grid, fine_tail, fine_if_few, st)));
+            if (all_flags && use_bytes) RG_TRY((launch_hop<128, MARK_BYTES_ALL>(a, n_cu, merge_grid, fine_tail, fine_if_few, st)));
+            else if (all_flags) RG_TRY((launch_hop<128, MARK_BITS_ALL>(a, n_cu, merge_grid, fine_tail, fine_if_few, st)));
             else if (use_bytes) RG_TRY((launch_hop<128, MARK_BYTES>(a, n_cu, merge_grid, fine_tail, fine_if_few, st)));
             else RG_TRY((launch_hop<128, MARK_BITS>(a, n_cu, merge_grid, fine_tail, fine_if_few, st)));
         } else if (need <= 256) {
-            if (all_flags) RG_TRY((launch_hop<256, MARK_BYTES_ALL>(a, n_cu, merge_grid, fine_tail, fine_if_few, st)));
+            if (all_flags && use_bytes) RG_TRY((launch_hop<256, MARK_BYTES_ALL>(a, n_cu, merge_grid, fine_tail, fine_if_few, st)));
+            else if (all_flags) RG_TRY((launch_hop<256, MARK_BITS_ALL>(a, n_cu, merge_grid, fine_tail, fine_if_few, st)));
             else if (use_bytes) RG_TRY((launch_hop<256, MARK_BYTES>(a, n_cu, merge_grid, fine_tail, fine_if_few, st)));
             else RG_TRY((launch_hop<256, MARK_BITS>(a, n_cu, merge_grid, fine_tail, fine_if_few, st)));
         }
