@@ -10,8 +10,9 @@ its misses cross the host link.
 
 Prints ONE JSON line.  `value` is sampled edges per second over whole steps;
 the gathered-feature rate and the per-kernel roofline figures ride along.
-Gathers stage --gather-group batches per launch (default 8: the feature blocks of
-the next eight batches back to back in one staging buffer, rg_gather_batches).
+Gathers stage --gather-group batches per launch (default: the feature blocks of
+the next eight batches back to back in one staging buffer, rg_gather_batches;
+more, up to 64, while that would be less than 512 MB per launch).
 """
 import argparse
 import json
@@ -285,8 +286,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=1)
     ap.add_argument("--workload", default="medium", choices=sorted(synth.CONFIGS))
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--gather-group", type=int, default=8,
-                    help="batches whose feature blocks one gather launch stages back to back (rg_gather_batches); 1 = one launch per batch")
+    ap.add_argument("--gather-group", type=int, default=0,
+                    help="batches whose feature blocks one gather launch stages back to back (rg_gather_batches, the prefetcher's Q); "
+                         "1 = one launch per batch; 0 = eight, doubled up to 64 while a launch would stage less than 512 MB")
     ap.add_argument("--no-pcie-pass", action="store_true")
     ap.add_argument("--no-runtime-leg", action="store_true", help="skip the multi-epoch cache-pair / prefetch-queue / blocks leg")
     ap.add_argument("--pmc-probe", action="store_true",
@@ -341,7 +343,11 @@ def main():
     del view, remote_freq, touched
     del s, c
     sampled_edges = sum(h["sampled"] for h in hops)
-    G = max(1, args.gather_group)
+    G = args.gather_group
+    if G <= 0:      # small batches: more of them per launch, so that a launch is long enough to run at the memory system's rate
+        G = 8
+        while G < 64 and G < n_batches and rows_per_epoch / n_batches * G * W.stride_bytes < (512 << 20):
+            G *= 2
     if G > 1:       # the staging buffer holds the largest group of G consecutive batches
         m_max = max(int(off_L[min(b + G, n_batches)] - off_L[b]) for b in range(0, n_batches, G))
     out_buf = torch.empty(m_max * W.stride_bytes, dtype=torch.uint8, device="cuda")
