@@ -40,7 +40,6 @@
 #include "rg_device.h"
 
 #include <algorithm>
-#include <cstdlib>
 #include <atomic>
 
 namespace rg {
