@@ -44,6 +44,7 @@ typedef int32_t rg_status;
 
 #define RG_MAX_HOPS    8u      /* L <= 8 */
 #define RG_MAX_FANOUT  1984u   /* every fanout[l] <= 1984 */
+#define RG_MAX_BATCHES 65535u  /* ceil(T / batch_size) <= 65535 batches per epoch */
 
 const char *rg_last_error(void);
 
@@ -91,8 +92,8 @@ typedef struct rg_cache rg_cache;
  * arguments: it does not depend on launch shape or timing.
  *
  *   g            graph (struct on host, arrays on device)
- *   train_nodes  dev, [T], distinct node IDs
- *   batch_size   > 0 (unless T == 0)
+ *   train_nodes  dev, [T], distinct node IDs in [0, n_nodes); checked on the device, RG_EINVAL otherwise
+ *   batch_size   > 0 (unless T == 0); ceil(T / batch_size) <= RG_MAX_BATCHES, RG_ERANGE otherwise
  *   fanout       host, [L]; L <= RG_MAX_HOPS, fanout[l] <= RG_MAX_FANOUT; L may be 0
  *   a            allocator or NULL
  *   out          receives the handle
@@ -138,6 +139,10 @@ rg_status rg_schedule_info(const rg_schedule *s, uint32_t *n_batches, uint32_t *
  * n_batches + 1 entries and is given both on the device and on the host. */
 rg_status rg_schedule_frontier(const rg_schedule *s, uint32_t hop, const int32_t **ids_dev,
                                const int64_t **batch_off_dev, const int64_t **batch_off_host);
+
+/* The epoch's shuffled seeds (Sec. 3 "Seeding and reproducibility": the batches' seed nodes in the order the
+ * epoch's stream puts them) and the batch offsets, [n_batches + 1]: the frontier of hop 0 under its own name. */
+rg_status rg_schedule_seeds(const rg_schedule *s, const int32_t **seeds_dev, const int64_t **batch_off_dev);
 
 /* Samples of hop in [0, L): samp_off_dev has |U_hop| + 1 entries indexed by
  * position in frontier(hop); node at position j drew
@@ -252,9 +257,12 @@ rg_status rg_gather_batches(const rg_schedule *s, const rg_cache *c, const rg_fe
 rg_status rg_classify_batch(const rg_schedule *s, const rg_cache *c, const rg_features *f, uint32_t batch,
                             void *stream, rg_gather_stats *stats);
 
-/* Both wait for the device to go idle (kernels may still be reading the handle), then release the
- * handle.  With the default allocator the device blocks go to a per-process cache that later builds
- * draw from; rg_trim_memory() hands the cached blocks back to the driver. */
+/* Release a handle.  Neither waits for the device: a handle that gathers enqueued by rg_gather_batch /
+ * rg_gather_batches still read is released once exactly those have finished -- with a caller-supplied
+ * allocator the call waits for them (and for nothing else), with the default allocator it returns at
+ * once and a later library call lets go of the memory.  The device blocks then go to a per-process cache
+ * that later builds draw from; rg_trim_memory() waits for every handle released so far and hands the
+ * cached blocks back to the driver. */
 void rg_schedule_destroy(rg_schedule *s);
 void rg_cache_destroy(rg_cache *c);
 void rg_trim_memory(void);
@@ -294,10 +302,11 @@ rg_status rg_schedule_block(const rg_schedule *s, uint32_t hop, const int32_t **
  *                             otherwise C_s keeps serving (gathers of the new epoch then
  *                             classify on the fly: same bytes, more misses).  wait != 0: waits
  *                             for the build.  *swapped (host, may be NULL) says what happened.
- *                             The old C_s is released after the device has gone idle.
+ *                             The old C_s is released once the gathers that still read it have
+ *                             finished; the call does not wait for them (staged blocks stay valid).
  *                             Returns the build's error if it failed.
  *   rg_cache_pair_primary     the current C_s: valid until the next successful swap
- *   rg_cache_pair_table_bytes device bytes held by C_s's table plus a finished C_sec's
+ *   rg_cache_pair_table_bytes device bytes held by C_s's table plus C_sec's, finished or under construction
  * One host thread drives a pair; the calls are not re-entrant. */
 typedef struct rg_cache_pair rg_cache_pair;
 rg_status rg_cache_pair_create(const rg_schedule *first_epoch, const rg_features *f, uint64_t K,

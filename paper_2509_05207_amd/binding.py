@@ -15,7 +15,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB_PATH = os.path.join(_HERE, "librapidgnn_hip.so")
 
 RG_OK, RG_EINVAL, RG_ENOMEM, RG_EHIP, RG_ERANGE, RG_EIO = 0, -1, -2, -3, -4, -5
-RG_MAX_HOPS, RG_MAX_FANOUT = 8, 1984
+RG_MAX_HOPS, RG_MAX_FANOUT, RG_MAX_BATCHES = 8, 1984, 65535
 KERNEL_GROUPS = ("sampler", "frontier", "shuffle_sort", "histogram", "topk", "plan", "cache_fill", "gather", "gather_miss", "sample_offsets", "blocks")
 
 EXPORTS = ("rg_last_error", "rg_graph_validate", "rg_build_schedule", "rg_schedule_info", "rg_schedule_frontier",
@@ -26,7 +26,7 @@ EXPORTS = ("rg_last_error", "rg_graph_validate", "rg_build_schedule", "rg_schedu
            "rg_prefetcher_create", "rg_prefetcher_fill", "rg_prefetcher_acquire", "rg_prefetcher_release",
            "rg_prefetcher_depth", "rg_prefetcher_destroy", "rg_schedule_build_blocks", "rg_schedule_block",
            "rg_classify_batch", "rg_build_schedule_with", "rg_gather_batches",
-           "rg_schedule_save", "rg_schedule_load")
+           "rg_schedule_save", "rg_schedule_load", "rg_schedule_seeds")
 
 
 class RgError(RuntimeError):
@@ -85,6 +85,7 @@ def lib():
         L.rg_schedule_info.argtypes = [vp, P(u32), P(u32), P(i64)]
         L.rg_schedule_frontier.argtypes = [vp, u32, P(vp), P(vp), P(vp)]
         L.rg_schedule_samples.argtypes = [vp, u32, P(vp), P(vp), P(i64)]
+        L.rg_schedule_seeds.argtypes = [vp, P(vp), P(vp)]
         L.rg_build_cache.argtypes = [P(vp), u32, P(rg_features), u64, P(rg_allocator), vp, P(vp)]
         L.rg_cache_view.argtypes = [vp, P(u64), P(vp), P(vp), P(vp), P(vp), P(u64)]
         L.rg_gather_batch.argtypes = [vp, vp, P(rg_features), u32, vp, u64, u64, vp, vp, P(rg_gather_stats)]
@@ -118,7 +119,7 @@ def lib():
                      "rg_prefetcher_create", "rg_prefetcher_fill", "rg_prefetcher_acquire", "rg_prefetcher_release",
                      "rg_prefetcher_depth", "rg_schedule_build_blocks", "rg_schedule_block",
            "rg_classify_batch", "rg_build_schedule_with", "rg_gather_batches",
-           "rg_schedule_save", "rg_schedule_load"):
+           "rg_schedule_save", "rg_schedule_load", "rg_schedule_seeds"):
             getattr(L, name).restype = C.c_int32
         _lib = L
     return _lib
@@ -174,8 +175,9 @@ def rg_graph_validate(indptr, indices, stream=None):
 
 
 class Schedule:
-    def __init__(self, handle):
+    def __init__(self, handle, keep=None):
         self.h = C.c_void_p(handle)
+        self._keep = keep            # the allocator the handle's memory came from must outlive the handle
         nb, L, nn = C.c_uint32(), C.c_uint32(), C.c_int64()
         _check(lib().rg_schedule_info(self.h, C.byref(nb), C.byref(L), C.byref(nn)))
         self.n_batches, self.L, self.n_nodes = nb.value, L.value, nn.value
@@ -208,7 +210,7 @@ def rg_build_schedule(indptr, indices, train_nodes, batch_size, fanout, s0=0, wo
     _check(lib().rg_build_schedule(C.byref(g), _dev_ptr(train_nodes, torch.int32) if T else None, T, int(batch_size), fan,
                                    len(fanout), int(s0), int(worker), int(epoch),
                                    C.byref(allocator) if allocator is not None else None, _stream_ptr(stream), C.byref(out)))
-    return Schedule(out.value)
+    return Schedule(out.value, allocator)
 
 
 def rg_build_schedule_with(indptr, indices, train_nodes, batch_size, fanout, s0=0, worker=0, epoch=0, sampler=RG_SAMPLER_KEYS,
@@ -220,7 +222,7 @@ def rg_build_schedule_with(indptr, indices, train_nodes, batch_size, fanout, s0=
     _check(lib().rg_build_schedule_with(C.byref(g), _dev_ptr(train_nodes, torch.int32) if T else None, T, int(batch_size), fan,
                                         len(fanout), int(s0), int(worker), int(epoch), int(sampler),
                                         C.byref(allocator) if allocator is not None else None, _stream_ptr(stream), C.byref(out)))
-    return Schedule(out.value)
+    return Schedule(out.value, allocator)
 
 
 def rg_schedule_save(s, path, stream=None):
@@ -231,7 +233,7 @@ def rg_schedule_load(path, allocator=None, stream=None):
     out = C.c_void_p()
     _check(lib().rg_schedule_load(os.fsencode(path), C.byref(allocator) if allocator is not None else None, _stream_ptr(stream),
                                   C.byref(out)))
-    return Schedule(out.value)
+    return Schedule(out.value, allocator)
 
 
 def rg_schedule_frontier(s, hop):
@@ -241,6 +243,14 @@ def rg_schedule_frontier(s, hop):
     off_host = np.ctypeslib.as_array(C.cast(offh, C.POINTER(C.c_int64)), shape=(s.n_batches + 1,)).copy()
     n = int(off_host[-1])
     return _view(ids.value, n, "<i4", s), _view(offd.value, s.n_batches + 1, "<i8", s), off_host
+
+
+def rg_schedule_seeds(s):
+    """(seeds device tensor: the shuffled train nodes; batch offsets device tensor [n_batches + 1])."""
+    ids, offd = C.c_void_p(), C.c_void_p()
+    _check(lib().rg_schedule_seeds(s.h, C.byref(ids), C.byref(offd)))
+    off = _view(offd.value, s.n_batches + 1, "<i8", s)
+    return _view(ids.value, int(off[-1].item()) if s.n_batches else 0, "<i4", s), off
 
 
 def rg_schedule_samples(s, hop):

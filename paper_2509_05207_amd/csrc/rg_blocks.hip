@@ -60,7 +60,7 @@ rg_status rg_schedule_build_blocks(rg_schedule *s, uint64_t workspace_limit_byte
     const uint64_t per_batch = (uint64_t)std::max<int64_t>(s->n_nodes, 1) * sizeof(int32_t);
     if (workspace_limit_bytes == 0) workspace_limit_bytes = (uint64_t)4 << 30;
     const uint32_t group = (uint32_t)std::max<uint64_t>(1, std::min<uint64_t>(s->n_batches, workspace_limit_bytes / per_batch));
-    Arena tmp(s->arena.allocator());     // scratch from the allocator the schedule was built with
+    Arena tmp(s->arena.allocator(), st);     // scratch from the allocator the schedule was built with
     int32_t *table = nullptr;
     if (s->n_batches > 0) RG_TRY(tmp.dev((uint64_t)group * per_batch, (void **)&table));
     for (uint32_t l = 0; l < s->L; ++l)           // every allocation before the first launch: no early return with kernels in flight
@@ -79,6 +79,7 @@ rg_status rg_schedule_build_blocks(rg_schedule *s, uint64_t workspace_limit_byte
     }
     RG_HIP(hipGetLastError());
     RG_HIP(hipStreamSynchronize(st));            // the table is released below
+    tmp.drained();
     s->blocks_built = true;
     return RG_OK;
 }

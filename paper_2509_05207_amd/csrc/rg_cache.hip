@@ -6,6 +6,8 @@
 
 namespace rg {
 
+thread_local std::atomic<uint64_t> *tls_table_bytes_sink = nullptr;
+
 // ---------------------------------------------------------------- a6: freq(v)
 // Every batch's input set is duplicate free, so each listed ID adds one.
 __global__ void tally_kernel(const int32_t *__restrict__ ids, int64_t n, uint32_t *__restrict__ freq)
@@ -399,7 +401,7 @@ static rg_status build_cache_impl(const rg_schedule *const *epochs, uint32_t n_e
     c->stride = ((uint64_t)f->row_bytes + 15) / 16 * 16;
     c->remote_rows_seen = f->remote_rows;
     c->remote_is_device = is_device_memory(f->remote_rows);
-    Arena tmp(a);
+    Arena tmp(a, st);
     RG_HIP(hipEventCreateWithFlags(&c->ev_fork, hipEventDisableTiming));
     RG_HIP(hipEventCreateWithFlags(&c->ev_join, hipEventDisableTiming));
 
@@ -477,6 +479,7 @@ static rg_status build_cache_impl(const rg_schedule *const *epochs, uint32_t n_e
 
     // ---- a8: VectorPull -- one bulk gather of the selected rows out of the remote table
     RG_TRY(c->arena.dev(c->K_eff * c->stride, &c->rows));
+    if (tls_table_bytes_sink) tls_table_bytes_sink->store(c->K_eff * c->stride, std::memory_order_release);
     if (c->K_eff > 0) {
         int64_t *fill_entries = nullptr;
         RG_TRY(tmp.dev_n<int64_t>(c->K_eff, &fill_entries));
@@ -500,6 +503,7 @@ static rg_status build_cache_impl(const rg_schedule *const *epochs, uint32_t n_e
     }
     for (uint32_t e = 0; e < n_epochs; ++e) RG_TRY(build_plan(epochs[e], route, rs, c->arena, tmp, st, &c->plans[e]));
     RG_HIP(hipStreamSynchronize(st));
+    tmp.drained();
     return RG_OK;
 }
 

@@ -27,9 +27,9 @@ void set_error(const char *fmt, ...)
 // hipMalloc / hipFree cost tens of microseconds to milliseconds each and hipFree synchronises the
 // device.  An epoch's build allocates a few dozen buffers whose sizes repeat from epoch to epoch, so
 // released blocks are kept (per device) and handed out again to requests of nearly the same size.
-// Blocks only come back here after the work that used them has completed: the build calls drain their
-// stream before releasing scratch, and the destroy calls synchronise the device first.
-// rg_trim_memory() returns everything to the driver.
+// Blocks only come back here after the work that used them has completed: a call's scratch arena drains
+// the call's stream before it lets go (on every way out of the call), and a handle is released only once
+// the gathers that read it have finished (UseLog).  rg_trim_memory() returns everything to the driver.
 namespace {
 struct BlockCache {
     std::mutex mu;
@@ -62,8 +62,9 @@ struct BlockCache {
         }
         void *p = nullptr;
         hipError_t e = hipMalloc(&p, want);
-        if (e != hipSuccess) {                       // give the cache back to the driver and try once more
+        if (e != hipSuccess) {                       // release what waits for its readers, give the cache back to the driver, try once more
             (void)hipGetLastError();
+            reap_retired(true);
             trim();
             e = hipMalloc(&p, want);
         }
@@ -154,6 +155,12 @@ Arena::Arena(const rg_allocator *a)
     if (custom_) a_ = *a; else a_ = rg_allocator{nullptr, nullptr, nullptr};
 }
 
+Arena::Arena(const rg_allocator *a, hipStream_t st) : Arena(a)
+{
+    drain_ = true;
+    drain_stream_ = st;
+}
+
 Arena::~Arena() { release_all(); }
 
 rg_status Arena::dev(uint64_t bytes, void **out)
@@ -216,6 +223,8 @@ void Arena::free_one(void *p)
 
 void Arena::release_all()
 {
+    if (drain_ && !items_.empty()) (void)hipStreamSynchronize(drain_stream_);     // kernels of the call that owns this scratch may still run
+    drain_ = false;
     for (auto &it : items_) {
         if (custom_) a_.free(it.p, it.kind, a_.ctx);
         else if (it.kind == 1) g_blocks.give(it.p);
@@ -223,6 +232,86 @@ void Arena::release_all()
     }
     items_.clear();
     in_use_ = 0;
+}
+
+// ---------------------------------------------------------------- last uses, retired handles
+UseLog::~UseLog()
+{
+    for (Use &u : uses_) (void)hipEventDestroy(u.ev);
+}
+
+void UseLog::note(hipStream_t st)
+{
+    std::lock_guard<std::mutex> lk(mu_);
+    for (Use &u : uses_)
+        if (u.st == st) {
+            if (hipEventRecord(u.ev, st) != hipSuccess) { (void)hipGetLastError(); lost_ = true; }
+            return;
+        }
+    hipEvent_t ev = nullptr;
+    if (hipEventCreateWithFlags(&ev, hipEventDisableTiming) != hipSuccess) { (void)hipGetLastError(); lost_ = true; return; }
+    if (hipEventRecord(ev, st) != hipSuccess) { (void)hipGetLastError(); (void)hipEventDestroy(ev); lost_ = true; return; }
+    uses_.push_back({st, ev});
+}
+
+bool UseLog::idle()
+{
+    std::lock_guard<std::mutex> lk(mu_);
+    if (lost_) return false;
+    for (Use &u : uses_) {
+        const hipError_t e = hipEventQuery(u.ev);
+        if (e == hipErrorNotReady) return false;
+        if (e != hipSuccess) { (void)hipGetLastError(); return false; }
+    }
+    return true;
+}
+
+void UseLog::wait()
+{
+    std::lock_guard<std::mutex> lk(mu_);
+    if (lost_) { (void)hipDeviceSynchronize(); lost_ = false; return; }
+    for (Use &u : uses_)
+        if (hipEventSynchronize(u.ev) != hipSuccess) { (void)hipGetLastError(); (void)hipDeviceSynchronize(); return; }
+}
+
+namespace {
+struct Retired {
+    std::mutex mu;
+    std::vector<rg_schedule *> schedules;
+    std::vector<rg_cache *> caches;
+};
+Retired &retired() { static Retired *r = new Retired(); return *r; }     // (never destructed: no HIP calls at process exit)
+
+template <typename H> void reap_list(std::vector<H *> &list, bool wait)
+{
+    size_t kept = 0;
+    for (H *h : list) {
+        if (wait) h->uses.wait();
+        if (wait || h->uses.idle()) delete h;
+        else list[kept++] = h;
+    }
+    list.resize(kept);
+}
+
+// A handle leaves: at once when nothing reads it any more; with a caller's allocator after a wait for its own
+// readers (the allocator may not outlive the call); otherwise it is parked until a later call finds it idle.
+template <typename H> void retire(H *h, std::vector<H *> Retired::*list)
+{
+    reap_retired(false);
+    if (h->arena.allocator()) h->uses.wait();
+    if (h->arena.allocator() || h->uses.idle()) { delete h; return; }
+    Retired &r = retired();
+    std::lock_guard<std::mutex> lk(r.mu);
+    (r.*list).push_back(h);
+}
+}  // namespace
+
+void reap_retired(bool wait)
+{
+    Retired &r = retired();
+    std::lock_guard<std::mutex> lk(r.mu);
+    reap_list(r.schedules, wait);
+    reap_list(r.caches, wait);
 }
 
 // ---------------------------------------------------------------- profiling
@@ -411,6 +500,12 @@ __global__ void validate_rows(int64_t n_nodes, const int64_t *__restrict__ indpt
 
 }  // namespace rg
 
+rg_cache::~rg_cache()
+{
+    if (ev_fork) (void)hipEventDestroy(ev_fork);
+    if (ev_join) (void)hipEventDestroy(ev_join);
+}
+
 using namespace rg;
 
 extern "C" {
@@ -481,6 +576,12 @@ rg_status rg_schedule_frontier(const rg_schedule *s, uint32_t hop, const int32_t
     return RG_OK;
 }
 
+rg_status rg_schedule_seeds(const rg_schedule *s, const int32_t **seeds_dev, const int64_t **batch_off_dev)
+{
+    if (!s) { set_error("rg_schedule_seeds: null schedule"); return RG_EINVAL; }
+    return rg_schedule_frontier(s, 0, seeds_dev, batch_off_dev, nullptr);
+}
+
 rg_status rg_schedule_samples(const rg_schedule *s, uint32_t hop, const int64_t **samp_off_dev,
                               const int32_t **samp_nbr_dev, int64_t *n_samples)
 {
@@ -508,20 +609,18 @@ rg_status rg_cache_view(const rg_cache *c, uint64_t *K_eff, const int32_t **cach
 
 void rg_schedule_destroy(rg_schedule *s)
 {
-    if (!s) return;
-    (void)hipDeviceSynchronize();          // kernels that still read the schedule must finish before its blocks are reused
-    delete s;
+    if (s) retire(s, &Retired::schedules);
 }
 
-void rg_trim_memory(void) { g_blocks.trim(); }
+void rg_trim_memory(void)
+{
+    reap_retired(true);
+    g_blocks.trim();
+}
 
 void rg_cache_destroy(rg_cache *c)
 {
-    if (!c) return;
-    (void)hipDeviceSynchronize();
-    if (c->ev_fork) (void)hipEventDestroy(c->ev_fork);
-    if (c->ev_join) (void)hipEventDestroy(c->ev_join);
-    delete c;
+    if (c) retire(c, &Retired::caches);
 }
 
 }  // extern "C"

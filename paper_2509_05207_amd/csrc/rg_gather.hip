@@ -260,12 +260,14 @@ extern "C" rg_status rg_gather_batch(const rg_schedule *s, const rg_cache *c, co
             RG_TRY(launch_gather(entries, m, nullptr, 0, 0, src, f->row_bytes, (uint8_t *)out, out_stride, st, KG_GATHER));
             RG_TRY(launch_gather(entries, m, plan->miss_rows + plan->miss_off[batch], n_miss, 1, src, f->row_bytes, (uint8_t *)out, out_stride, st, KG_MISS));
         }
+        s->uses.note(st);                                      // the launches above read the schedule's and the cache's arrays after this call returns
+        c->uses.note(st);
         if (stats) *stats = plan->stats[batch];
         return RG_OK;
     }
 
     // No prepared plan: classify this batch now, copy every row on `stream`, wait for the counts.
-    Arena tmp(s->arena.allocator());     // scratch from the allocator the schedule was built with
+    Arena tmp(s->arena.allocator(), st);     // scratch from the allocator the schedule was built with
     int64_t *entry = nullptr;
     unsigned long long *counts = nullptr;
     RG_TRY(tmp.dev_n<int64_t>((uint64_t)m, &entry));
@@ -283,6 +285,7 @@ extern "C" rg_status rg_gather_batch(const rg_schedule *s, const rg_cache *c, co
     unsigned long long hc[3] = {0, 0, 0};
     RG_HIP(hipMemcpyAsync(hc, counts, sizeof(hc), hipMemcpyDeviceToHost, st));
     RG_HIP(hipStreamSynchronize(st));
+    tmp.drained();
     if (stats) { stats->n_rows = (uint64_t)m; stats->n_local = hc[0]; stats->n_hit = hc[1]; stats->n_miss = hc[2]; }
     return RG_OK;
 }
@@ -357,6 +360,8 @@ extern "C" rg_status rg_gather_batches(const rg_schedule *s, const rg_cache *c, 
             RG_HIP(hipStreamWaitEvent(st, c->ev_join, 0));
         }
     }
+    s->uses.note(st);
+    c->uses.note(st);
     if (stats)
         for (uint32_t k = 0; k < n_batches; ++k) stats[k] = plan->stats[first_batch + k];
     return RG_OK;
@@ -375,7 +380,7 @@ extern "C" rg_status rg_classify_batch(const rg_schedule *s, const rg_cache *c, 
     const HopData &h = s->hop[s->L];
     const int64_t off = h.off_host[batch], m = h.off_host[batch + 1] - off;
     hipStream_t st = as_stream(stream);
-    Arena tmp(s->arena.allocator());     // scratch from the allocator the schedule was built with
+    Arena tmp(s->arena.allocator(), st);     // scratch from the allocator the schedule was built with
     int64_t *entry = nullptr;
     unsigned long long *counts = nullptr;
     RG_TRY(tmp.dev_n<int64_t>((uint64_t)m, &entry));
@@ -390,6 +395,7 @@ extern "C" rg_status rg_classify_batch(const rg_schedule *s, const rg_cache *c, 
     hipError_t e1 = hipGetLastError();
     hipError_t e2 = hipMemcpyAsync(hc, counts, sizeof(hc), hipMemcpyDeviceToHost, st);
     hipError_t e3 = hipStreamSynchronize(st);                    // also before `tmp` is released
+    if (e3 == hipSuccess) tmp.drained();
     if (e1 != hipSuccess || e2 != hipSuccess || e3 != hipSuccess) { set_error("rg_classify_batch: HIP call failed"); return RG_EHIP; }
     stats->n_rows = (uint64_t)m; stats->n_local = hc[0]; stats->n_hit = hc[1]; stats->n_miss = hc[2];
     return RG_OK;

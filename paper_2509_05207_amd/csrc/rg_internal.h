@@ -5,6 +5,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 #include <stddef.h>
+#include <atomic>
+#include <mutex>
 #include <string>
 #include <vector>
 #include <utility>
@@ -38,6 +40,11 @@ void set_error(const char *fmt, ...);
 class Arena {
   public:
     explicit Arena(const rg_allocator *a);
+    // Scratch of a call that launches kernels on `st`: the stream is drained before the buffers go back (they may be
+    // handed to another thread's build at once), on every way out of the call -- unless the call has waited for the
+    // stream itself and says so with drained().
+    Arena(const rg_allocator *a, hipStream_t st);
+    void drained() { drain_ = false; }
     ~Arena();
     Arena(const Arena &) = delete;
     Arena &operator=(const Arena &) = delete;
@@ -59,6 +66,28 @@ class Arena {
     bool custom_;
     std::vector<Item> items_;
     uint64_t in_use_ = 0;
+    bool drain_ = false;
+    hipStream_t drain_stream_ = nullptr;
+};
+
+// ---------------------------------------------------------------- last uses of a handle
+// A gather served from a prepared plan returns while its kernels still read the schedule and the cache.  Each such
+// call records, per stream, an event behind its last launch; a destroy call then knows exactly what it has to wait
+// for (that handle's own readers), not for the whole device.
+class UseLog {
+  public:
+    UseLog() = default;
+    ~UseLog();
+    UseLog(const UseLog &) = delete;
+    UseLog &operator=(const UseLog &) = delete;
+    void note(hipStream_t st);      // work just enqueued on st reads the handle
+    bool idle();                    // every noted use has completed
+    void wait();                    // blocks until idle
+  private:
+    struct Use { hipStream_t st; hipEvent_t ev; };
+    std::mutex mu_;
+    std::vector<Use> uses_;
+    bool lost_ = false;             // an event could not be created or recorded: only a device-wide wait is safe
 };
 
 // ---------------------------------------------------------------- profiling
@@ -96,6 +125,7 @@ struct rg_schedule {
     std::vector<rg::HopData> hop;    // L + 1 entries
     bool blocks_built = false;
     uint32_t *epoch_freq = nullptr;  // dev, [n_nodes]: in how many of the epoch's input sets each node is, or NULL (then the lists are tallied)
+    mutable rg::UseLog uses;         // gathers in flight that read this schedule
     explicit rg_schedule(const rg_allocator *a) : arena(a) {}
 };
 
@@ -133,7 +163,9 @@ struct rg_cache {
     hipEvent_t ev_fork = nullptr, ev_join = nullptr;
     const void *remote_rows_seen = nullptr;   // the remote table the cache was built over ...
     bool remote_is_device = false;            // ... and whether it is device memory
+    mutable rg::UseLog uses;                  // gathers in flight that read this cache
     explicit rg_cache(const rg_allocator *a) : arena(a) {}
+    ~rg_cache();
 };
 
 namespace rg {
@@ -172,6 +204,14 @@ class Readback {
     size_t used_ = 0;
     std::vector<Part> parts_;
 };
+
+// Handles whose destroy call found readers still in flight wait here (default allocator only); they are released by
+// a later library call once their readers have finished.  reap_retired(true) waits for all of them.
+void reap_retired(bool wait);
+
+// Where a cache build on this thread reports the bytes of its table as soon as the table is allocated (NULL: nowhere).
+// The double-buffered cache sets it on its build thread so that the memory bound counts a C_sec under construction.
+extern thread_local std::atomic<uint64_t> *tls_table_bytes_sink;
 
 // True when p is device memory on the current device (false for pinned host memory).
 bool is_device_memory(const void *p);

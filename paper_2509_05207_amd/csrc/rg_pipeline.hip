@@ -22,6 +22,7 @@ struct rg_cache_pair {
     hipStream_t build_stream = nullptr;
     std::thread worker;
     std::atomic<int> state{0};         // 0 idle, 1 building, 2 ready, 3 failed
+    std::atomic<uint64_t> building_bytes{0};   // table bytes of the C_sec under construction, once its table exists
     rg_status worker_status = RG_OK;
     std::string worker_error;
 };
@@ -33,7 +34,10 @@ static void build_secondary(rg_cache_pair *p, const rg_schedule *next)
     (void)hipSetDevice(p->device);
     rg_cache *c = nullptr;
     const rg_schedule *eps[1] = {next};
+    tls_table_bytes_sink = &p->building_bytes;
     rg_status rc = rg_build_cache(eps, 1, &p->feat, p->K, p->has_alloc ? &p->alloc : nullptr, p->build_stream, &c);
+    tls_table_bytes_sink = nullptr;
+    if (rc != RG_OK) p->building_bytes.store(0, std::memory_order_release);
     if (rc == RG_OK) {
         p->secondary = c;
         p->worker_status = RG_OK;
@@ -85,6 +89,7 @@ rg_status rg_cache_pair_begin_next(rg_cache_pair *p, const rg_schedule *next_epo
     if (st == 1) { set_error("rg_cache_pair_begin_next: a secondary build is already running"); return RG_EINVAL; }
     if (p->worker.joinable()) p->worker.join();
     if (p->secondary) { rg_cache_destroy(p->secondary); p->secondary = nullptr; }      // an unused C_sec is dropped
+    p->building_bytes.store(0, std::memory_order_release);
     p->state.store(1, std::memory_order_release);
     try {
         p->worker = std::thread(build_secondary, p, next_epoch);
@@ -114,7 +119,7 @@ rg_status rg_cache_pair_swap(rg_cache_pair *p, int wait, int *swapped)
     p->primary = p->secondary;
     p->secondary = nullptr;
     p->state.store(0, std::memory_order_release);
-    rg_cache_destroy(old);                                    // waits for gathers that still read the old table
+    rg_cache_destroy(old);                                    // released once the gathers that still read the old table have finished; nothing waits here
     if (swapped) *swapped = 1;
     return RG_OK;
 }
@@ -126,7 +131,9 @@ uint64_t rg_cache_pair_table_bytes(const rg_cache_pair *p)
     if (!p) return 0;
     uint64_t b = 0;
     if (p->primary) b += p->primary->K_eff * p->primary->stride;
-    if (p->state.load(std::memory_order_acquire) == 2 && p->secondary) b += p->secondary->K_eff * p->secondary->stride;
+    const int st = p->state.load(std::memory_order_acquire);
+    if (st == 2 && p->secondary) b += p->secondary->K_eff * p->secondary->stride;
+    else if (st == 1) b += p->building_bytes.load(std::memory_order_acquire);       // a C_sec whose table is already allocated
     return b;
 }
 

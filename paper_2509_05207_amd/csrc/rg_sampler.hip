@@ -44,26 +44,6 @@
 
 namespace rg {
 
-// ---------------------------------------------------------------- optional phase timers
-// Built with -DRG_PHASE_TIMERS (python -m paper_2509_05207_amd.phase_timers does that, into a library of its own), the
-// sampling kernel reads the cycle counter around each of its phases and sums the differences over all waves; the
-// ordinary build contains none of this.  One wave per workgroup, so the accumulators are simply in LDS.
-#ifdef RG_PHASE_TIMERS
-enum Phase { PH_WAVE = 0, PH_TILES, PH_GROUP_SETUP, PH_ROWS_64, PH_ROWS_256, PH_LONG_ROWS, PH_LONG_ENTRY, PH_LONG_LOOP, PH_LONG_FINAL_CUT,
-             PH_LONG_OUTPUT, PH_N_LONG_ROWS, PH_N_BLOCKS, PH_N_CANDIDATES, PH_N_ROWS_64, PH_N_ROWS_256, PH_NODE_LOOP, PH_COPY_ROWS,
-             PH_N_COPY_ROWS, PH_N_NODES, PH_WORK_COUNTER, PH_COUNT };
-__device__ unsigned long long g_phase[PH_COUNT];
-__shared__ unsigned long long phase_acc[PH_COUNT];
-#define RG_T0(name) const unsigned long long name = (unsigned long long)__builtin_readcyclecounter()
-#define RG_TSET(name) name = (unsigned long long)__builtin_readcyclecounter()
-#define RG_TADD(k, t0) do { if (threadIdx.x == 0) phase_acc[k] += (unsigned long long)__builtin_readcyclecounter() - (t0); } while (0)
-#define RG_TCNT(k, n) do { if (threadIdx.x == 0) phase_acc[k] += (unsigned long long)(n); } while (0)
-#else
-#define RG_T0(name) do { } while (0)
-#define RG_TSET(name) do { } while (0)
-#define RG_TADD(k, t0) do { } while (0)
-#define RG_TCNT(k, n) do { } while (0)
-#endif
 
 constexpr int BIG_ROW = 16384;           // rows longer than this are sampled tile by tile
 
@@ -79,13 +59,14 @@ struct NodeRecs {
 
 __global__ void node_records_kernel(const int64_t *__restrict__ indptr, const int32_t *__restrict__ frontier, int64_t n,
                                     const int64_t *__restrict__ batch_off, uint32_t n_batches, const uint64_t *__restrict__ batch_seed,
-                                    uint32_t hop, uint32_t fanout, NodeRecs r, int32_t *__restrict__ cnt, int32_t *__restrict__ tiles)
+                                    uint32_t hop, uint32_t fanout, NodeRecs r, int32_t *__restrict__ cnt, int32_t *__restrict__ tiles, int64_t n_nodes)
 {
     const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (i >= n) return;
     const int32_t v = frontier[i];
-    const int64_t b0 = indptr[v];
-    const int64_t deg = indptr[v + 1] - b0;
+    const bool known = v >= 0 && (int64_t)v < n_nodes;      // (a seed out of range is refused by the host at the hop's readback; until then it has no row)
+    const int64_t b0 = known ? indptr[v] : 0;
+    const int64_t deg = known ? indptr[v + 1] - b0 : 0;
     const uint32_t b = batch_of(batch_off, n_batches, i);
     r.row_begin[i] = b0;
     r.deg[i] = (int32_t)deg;
@@ -463,7 +444,6 @@ template <int CAP>
 __device__ __forceinline__ void sample_long_row(const int32_t *__restrict__ row, int len, uint32_t first, int f, uint32_t lo, uint32_t hi, int lane,
                                                 uint32_t *buf, const u32x4 &blk0)
 {
-    RG_T0(t_entry);
     len = uni(len); f = uni(f); lo = uni(lo); hi = uni(hi);
     const int head = uni(row_head(row, len));
     const int32_t *p = row + head;
@@ -525,9 +505,6 @@ __device__ __forceinline__ void sample_long_row(const int32_t *__restrict__ row,
         const unsigned long long vm[4] = {low_lanes(head), 0ull, 0ull, 0ull};
         append_block<CAP>(u, k, vm, f, lo, hi, lane, buf, s);
     }
-    RG_TADD(PH_LONG_ENTRY, t_entry);
-    RG_T0(t_loop);
-    RG_TCNT(PH_N_BLOCKS, n_blocks);
     if (guess && rem >= 256) {
         // The full blocks under the guessed cut, two in flight behind the one whose keys are computed: block j lives in
         // register quartet j mod 3 and the loop is unrolled by three, so no block is copied from one quartet to another
@@ -569,17 +546,13 @@ __device__ __forceinline__ void sample_long_row(const int32_t *__restrict__ row,
         cur = nxt;
     }
     __syncthreads();
-    RG_TADD(PH_LONG_LOOP, t_loop);
     if (s.cnt >= f) break;                                       // (always, in the exact attempt: len > f)
   }
-    RG_T0(t_cut);
-    RG_TCNT(PH_N_CANDIDATES, s.cnt);
     if (s.cnt > f) {
         const uint32_t upper = s.open ? 0xFFFFFFFFu : s.cut;
         if (CAP > 64 && s.cnt <= 64) (void)prune_buffer<64>(buf, s.cnt, f, lo, hi, lane, upper);     // the usual case after a guessed cut: one ID per lane
         else (void)prune_buffer<CAP>(buf, s.cnt, f, lo, hi, lane, upper);
     }
-    RG_TADD(PH_LONG_FINAL_CUT, t_cut);
 }
 
 // SAMPLE of a row of len > f IDs into out (row order), marking the sampled IDs as MARK says.
@@ -588,26 +561,20 @@ template <int CAP, int MARK>
 __device__ __forceinline__ void sample_row(const int32_t *__restrict__ row, int len, uint32_t first, const u32x4 &ahead, int f, uint32_t lo, uint32_t hi,
                                            int lane, uint32_t *buf, int32_t *__restrict__ out, const ReachedOfBatch &reached_b)
 {
-    RG_T0(t_row);
     if (len <= 64) {
         const uint32_t u[1] = {first};
         sample_registers<1, MARK>(u, len, f, lo, hi, lane, buf, out, reached_b);
-        RG_TADD(PH_ROWS_64, t_row); RG_TCNT(PH_N_ROWS_64, 1);
     } else if (len <= 256) {
         const uint32_t u[4] = {first, ahead.x, ahead.y, ahead.z};
         sample_registers<4, MARK>(u, len, f, lo, hi, lane, buf, out, reached_b);
-        RG_TADD(PH_ROWS_256, t_row); RG_TCNT(PH_N_ROWS_256, 1);
     } else {
         sample_long_row<CAP>(row, len, first, f, lo, hi, lane, buf, ahead);
-        RG_T0(t_out);
         for (int j = lane; j < f; j += 64) {
             const uint32_t u = buf[j];
             out[j] = (int32_t)u;
             mark_reached<MARK>(reached_b, u);
         }
         __syncthreads();      // the buffer is reused by the wave's next row
-        RG_TADD(PH_LONG_OUTPUT, t_out);
-        RG_TADD(PH_LONG_ROWS, t_row); RG_TCNT(PH_N_LONG_ROWS, 1);
     }
 }
 
@@ -669,13 +636,6 @@ __global__ void __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(CAP <= 
     __shared__ uint32_t buf[CAP];
     const int lane = threadIdx.x;
     const int f = (int)a.fanout;
-#ifdef RG_PHASE_TIMERS
-    if (lane < PH_COUNT) phase_acc[lane] = 0;
-    __syncthreads();
-    RG_T0(t_wave);
-    unsigned long long t_ask;
-    RG_TSET(t_ask);
-#endif
     // Tiles first, dealt out in turn (workgroup k takes tiles k, k + grid, ...): they are all of about the same
     // length, the whole grid is resident (see launch_hop), and with the next tile known in advance its record is
     // fetched while the current one is streamed -- no wave waits for a counter or a record between tiles.
@@ -684,7 +644,6 @@ __global__ void __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(CAP <= 
         int64_t nb = 0; int nl = 0; uint64_t nS = 0;
         if (w < a.n_tiles) { nb = a.tile.begin[w]; nl = a.tile.len[w]; nS = a.tile.state[w]; }
         while (w < a.n_tiles) {
-            RG_T0(t_tile);
             const int32_t *row = a.indices + nb;
             const int len = nl;
             const uint64_t S = nS;
@@ -695,19 +654,13 @@ __global__ void __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(CAP <= 
             sample_row<CAP, MARK_NONE>(row, len, first, ahead, f, (uint32_t)S, (uint32_t)(S >> 32), lane, buf, a.tile_out + w * f,
                                        ReachedOfBatch{nullptr, nullptr});
             w = w_next;
-            RG_TADD(PH_TILES, t_tile);
         }
     }
-#ifdef RG_PHASE_TIMERS
-    RG_TSET(t_ask);
-#endif
     // Then the groups of 64 consecutive frontier nodes, taken as waves become free, so that uneven rows do not leave
     // part of the chip idle at the end -- and for the same reason the launch's last nodes come in groups of 16 (a group
     // of 64 nodes with long rows is a sizeable part of a launch's whole duration); every wave leaves once the counter
     // has passed the last group.
     for (int64_t w = grab_work(a.next_work, lane); w < a.n_units; w = grab_work(a.next_work, lane)) {
-        RG_TADD(PH_WORK_COUNTER, t_ask);
-        RG_T0(t_group);
         const bool full = w < a.n_full_groups;                  // 64 nodes, or 16 of the launch's last nodes
         const int64_t i_lane = (full ? w << 6 : (a.n_full_groups << 6) + ((w - a.n_full_groups) << 4)) + lane;
         const bool in = (full || lane < 16) && i_lane < a.n_frontier;
@@ -717,7 +670,7 @@ __global__ void __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(CAP <= 
         const int64_t S_lane = in ? (int64_t)a.rec.state[i_lane] : 0;
         const int64_t out_lane = in ? a.samp_off[i_lane] : 0;
         unsigned long long todo = ballot64(deg_lane > 0 && deg_lane <= BIG_ROW);
-        if (todo == 0ull) { RG_TSET(t_ask); continue; }
+        if (todo == 0ull) continue;
         // the first node's leading 64 IDs; from then on the next node's are fetched while the current one is sampled
         int l = __builtin_amdgcn_readfirstlane(__ffsll((long long)todo) - 1);
         int64_t rb = bcast64(rb_lane, l);
@@ -725,10 +678,7 @@ __global__ void __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(CAP <= 
         uint32_t first = lane < deg ? (uint32_t)a.indices[rb + lane] : 0u;
         u32x4 ahead = {0u, 0u, 0u, 0u};
         if (deg > 64 && deg > f) ahead = row_ahead(a.indices + rb, deg, lane);
-        RG_TADD(PH_GROUP_SETUP, t_group);
         while (todo != 0ull) {
-            RG_T0(t_node);
-            RG_TCNT(PH_N_NODES, 1);
             todo &= todo - 1ull;
             const int cl = l, cdeg = deg;
             const int64_t crb = rb;
@@ -745,28 +695,19 @@ __global__ void __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(CAP <= 
             const ReachedOfBatch reached_b = reached_of<MARK>(a.reached, b);
             const int32_t *row = a.indices + crb;
             int32_t *out = a.samp_nbr + bcast64(out_lane, cl);
-            RG_TADD(PH_NODE_LOOP, t_node);
             if (cdeg <= f) {                  // the whole row is the sample
-                RG_T0(t_copy);
                 if (lane < cdeg) { out[lane] = (int32_t)cfirst; mark_reached<MARK>(reached_b, cfirst); }
                 for (int j = 64 + lane; j < cdeg; j += 64) {
                     const int32_t u = row[j];
                     out[j] = u;
                     mark_reached<MARK>(reached_b, (uint32_t)u);
                 }
-                RG_TADD(PH_COPY_ROWS, t_copy); RG_TCNT(PH_N_COPY_ROWS, 1);
             } else {
                 const uint64_t S = (uint64_t)bcast64(S_lane, cl);
                 sample_row<CAP, MARK>(row, cdeg, cfirst, cahead, f, (uint32_t)S, (uint32_t)(S >> 32), lane, buf, out, reached_b);
             }
         }
-        RG_TSET(t_ask);
     }
-#ifdef RG_PHASE_TIMERS
-    RG_TADD(PH_WAVE, t_wave);
-    __syncthreads();
-    if (lane < PH_COUNT) atomicAdd(&g_phase[lane], phase_acc[lane]);
-#endif
 }
 
 // One wave per tile job; the wave that holds a long row's first tile samples the row's
@@ -852,12 +793,14 @@ __global__ void __launch_bounds__(POS_THREADS) sample_positions_kernel(const int
 }
 
 // Samples hop `hop` of every batch: fills cur.samp_off / samp_nbr / n_samples and marks the reached-ID bitmaps.
+// also_read_dev (or NULL): one more device value copied to *also_read_host behind the hop's own readback; if it
+// comes back non-zero the hop stops there (the caller is about to refuse its input).
 // Where `maps` allows the reached map's byte form, the hop marks into whichever form suits it (see below; the byte
 // map is allocated, clear, by the first hop that wants it) and *marked_bytes says which, so that the frontier pass
 // reads the right one.
 rg_status sample_hop(const rg_graph *g, HopData &cur, uint32_t beta, const uint64_t *batch_seed, uint32_t hop, uint32_t fanout,
                      uint32_t sampler, ReachedForms &maps, int prefer_bytes, bool *marked_bytes, Arena &keep, Arena &tmp, int n_cu,
-                     hipStream_t st)
+                     hipStream_t st, const unsigned long long *also_read_dev, unsigned long long *also_read_host)
 {
     const int64_t n_cur = cur.off_host[beta];
     int32_t *cnt = nullptr, *tiles = nullptr;
@@ -874,7 +817,7 @@ rg_status sample_hop(const rg_graph *g, HopData &cur, uint32_t beta, const uint6
     {
         ScopedTimer tm(KG_OFFSETS, st);
         hipLaunchKernelGGL(node_records_kernel, dim3((unsigned)((n_cur + 255) / 256)), dim3(256), 0, st, g->indptr, cur.ids, n_cur, cur.off_dev, beta,
-                           batch_seed, hop, fanout, rec, cnt, tiles);
+                           batch_seed, hop, fanout, rec, cnt, tiles, (int64_t)g->n_nodes);
         RG_TRY(scan_i32_to_i64(cnt, cur.samp_off, n_cur, tmp, st));
         RG_TRY(scan_i32_to_i64(tiles, tile_off, n_cur, tmp, st));
     }
@@ -893,7 +836,9 @@ rg_status sample_hop(const rg_graph *g, HopData &cur, uint32_t beta, const uint6
         if (sum_deg_dev) RG_TRY(rb.add(sums, sum_deg_dev, sizeof(sums)));
         RG_TRY(rb.add(&cur.n_samples, cur.samp_off + n_cur, sizeof(int64_t)));
         RG_TRY(rb.add(&n_tiles, tile_off + n_cur, sizeof(int64_t)));
+        if (also_read_dev) RG_TRY(rb.add(also_read_host, also_read_dev, sizeof(unsigned long long)));     // a value the caller wants behind the same wait
         RG_TRY(rb.wait());
+        if (also_read_dev && *also_read_host != 0) return RG_OK;        // the caller refuses the build: nothing more to launch
     }
     // Which form of the reached map this hop marks.  A byte store is several times cheaper than an atomic OR, but the
     // byte map is 8 times the size and its scattered stores reach memory as whole lines; that pays where marks are a
@@ -980,16 +925,3 @@ rg_status sample_hop(const rg_graph *g, HopData &cur, uint32_t beta, const uint6
 
 }  // namespace rg
 
-#ifdef RG_PHASE_TIMERS
-// Sums of the phase timers since the last reset (host array of PH_COUNT values), for the profiling build only.
-extern "C" int rg_phase_timers_read(unsigned long long *out, int n, int reset)
-{
-    if (n != rg::PH_COUNT || hipDeviceSynchronize() != hipSuccess) return -1;
-    if (hipMemcpyFromSymbol(out, HIP_SYMBOL(rg::g_phase), sizeof(unsigned long long) * rg::PH_COUNT) != hipSuccess) return -2;
-    if (reset) {
-        unsigned long long zero[rg::PH_COUNT] = {0};
-        if (hipMemcpyToSymbol(HIP_SYMBOL(rg::g_phase), zero, sizeof(zero)) != hipSuccess) return -3;
-    }
-    return 0;
-}
-#endif

@@ -20,7 +20,8 @@
 namespace rg {
 
 rg_status sample_hop(const rg_graph *g, HopData &cur, uint32_t beta, const uint64_t *batch_seed, uint32_t hop, uint32_t fanout, uint32_t sampler,
-                     ReachedForms &maps, int prefer_bytes, bool *marked_bytes, Arena &keep, Arena &tmp, int n_cu, hipStream_t st);
+                     ReachedForms &maps, int prefer_bytes, bool *marked_bytes, Arena &keep, Arena &tmp, int n_cu, hipStream_t st,
+                     const unsigned long long *also_read_dev, unsigned long long *also_read_host);
 
 // ---------------------------------------------------------------- a1/a2: seeds, shuffle keys
 __global__ void batch_seeds_kernel(uint64_t s0, uint32_t worker, uint32_t epoch, uint32_t n_batches, uint64_t *__restrict__ seeds)
@@ -102,11 +103,30 @@ __global__ void __launch_bounds__(RANK_THREADS) shuffle_rank_kernel(const KeyPos
     }
 }
 
-__global__ void mark_seeds_kernel(const int32_t *__restrict__ seeds, uint64_t T, uint32_t batch_size, uint32_t *__restrict__ seen, uint64_t words_per_batch)
+// The precondition on train_nodes, checked on the device: *n_bad += the IDs outside [0, n_nodes) and the IDs that
+// occurred before (`once`: a bit per node ID, clear on entry).  Until the host has seen the count (at the build's
+// first readback), the kernels that index by a seed's value skip values out of range.
+__global__ void check_train_kernel(const int32_t *__restrict__ train, uint64_t T, int64_t n_nodes, uint32_t *__restrict__ once,
+                                   unsigned long long *__restrict__ n_bad)
+{
+    const uint64_t t = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    bool bad = false;
+    if (t < T) {
+        const int64_t v = train[t];
+        if (v < 0 || v >= n_nodes) bad = true;
+        else bad = (atomicOr(&once[v >> 5], 1u << (v & 31)) >> (v & 31)) & 1u;
+    }
+    const unsigned long long m = __ballot(bad);
+    if (m != 0ull && (threadIdx.x & 63) == 0) atomicAdd(n_bad, (unsigned long long)__popcll(m));
+}
+
+__global__ void mark_seeds_kernel(const int32_t *__restrict__ seeds, uint64_t T, uint32_t batch_size, uint32_t *__restrict__ seen, uint64_t words_per_batch,
+                                  int64_t n_nodes)
 {
     const uint64_t t = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (t >= T) return;
     const uint32_t v = (uint32_t)seeds[t];
+    if ((int64_t)v >= n_nodes) return;          // (refused by the host as soon as it has read check_train_kernel's count)
     atomicOr(&seen[(t / batch_size) * words_per_batch + (v >> 5)], 1u << (v & 31));
 }
 
@@ -403,7 +423,7 @@ static rg_status build_schedule_impl(const rg_graph *g, const int32_t *train, ui
     s->T = T;
     s->uid = g_next_schedule_uid.fetch_add(1);
     s->hop.resize(L + 1);
-    Arena tmp(a);             // build-time scratch, released when this function returns
+    Arena tmp(a, st);         // build-time scratch, released (behind a drained stream) when this function returns
 
     // ---- a1: batch seeds
     uint64_t *batch_seed = nullptr;
@@ -417,6 +437,21 @@ static rg_status build_schedule_impl(const rg_graph *g, const int32_t *train, ui
     h0.off_host.resize((size_t)beta + 1);
     for (uint32_t b = 0; b <= beta; ++b) h0.off_host[b] = (int64_t)std::min<uint64_t>((uint64_t)b * B, T);
     RG_HIP(hipMemcpyAsync(h0.off_dev, h0.off_host.data(), ((size_t)beta + 1) * sizeof(int64_t), hipMemcpyHostToDevice, st));
+    unsigned long long *n_bad_train = nullptr, n_bad_host = 0;
+    RG_TRY(tmp.dev_n<unsigned long long>(1, &n_bad_train));
+    RG_HIP(hipMemsetAsync(n_bad_train, 0, sizeof(unsigned long long), st));
+    if (T > 0) {
+        uint32_t *once = nullptr;
+        const uint64_t once_words = ((uint64_t)g->n_nodes + 31) / 32;
+        RG_TRY(tmp.dev_n<uint32_t>(once_words, &once));
+        RG_HIP(hipMemsetAsync(once, 0, once_words * sizeof(uint32_t), st));
+        hipLaunchKernelGGL(check_train_kernel, dim3((unsigned)((T + 255) / 256)), dim3(256), 0, st, train, T, (int64_t)g->n_nodes, once, n_bad_train);
+    }
+    auto refuse_bad_train = [&]() -> rg_status {
+        if (n_bad_host == 0) return RG_OK;
+        set_error("rg_build_schedule: %llu of the %llu train nodes are outside [0, n_nodes) or repeated", n_bad_host, (unsigned long long)T);
+        return RG_EINVAL;
+    };
     if (T > 0) {
         // about a hundred positions per bucket, a power of two of buckets
         uint32_t bucket_bits = 0;
@@ -451,7 +486,13 @@ static rg_status build_schedule_impl(const rg_graph *g, const int32_t *train, ui
             nx.off_host.assign(1, 0);
         }
     }
-    if (L == 0 || beta == 0) { RG_HIP(hipStreamSynchronize(st)); return RG_OK; }
+    if (L == 0 || beta == 0) {
+        Readback rb(st);
+        RG_TRY(rb.add(&n_bad_host, n_bad_train, sizeof(n_bad_host)));
+        RG_TRY(rb.wait());
+        tmp.drained();
+        return refuse_bad_train();
+    }
 
     // ---- bitmaps (n_nodes bits per batch, rounded up to whole 8-word groups)
     const uint64_t wpb = (((uint64_t)g->n_nodes + 31) / 32 + FRS_WORDS_PER_THREAD - 1) / FRS_WORDS_PER_THREAD * FRS_WORDS_PER_THREAD;
@@ -479,7 +520,7 @@ static rg_status build_schedule_impl(const rg_graph *g, const int32_t *train, ui
     ReachedForms maps{reached_words, nullptr, reached_flags, wpb, byte_map};
     {
         ScopedTimer tm(KG_FRONTIER, st);
-        hipLaunchKernelGGL(mark_seeds_kernel, dim3((unsigned)((T + 255) / 256)), dim3(256), 0, st, h0.ids, T, B, seen, wpb);
+        hipLaunchKernelGGL(mark_seeds_kernel, dim3((unsigned)((T + 255) / 256)), dim3(256), 0, st, h0.ids, T, B, seen, wpb, (int64_t)g->n_nodes);
     }
     int32_t *fresh_cnt = nullptr;
     int64_t *fresh_scan = nullptr;
@@ -498,7 +539,9 @@ static rg_status build_schedule_impl(const rg_graph *g, const int32_t *train, ui
 
         // a3: the samples of this hop; sampled IDs are marked in `reached` as they are written
         bool marked_bytes = false;
-        RG_TRY(sample_hop(g, cur, beta, batch_seed, l, fanout[l], sampler, maps, prefer_bytes, &marked_bytes, s->arena, tmp, n_cu, st));
+        RG_TRY(sample_hop(g, cur, beta, batch_seed, l, fanout[l], sampler, maps, prefer_bytes, &marked_bytes, s->arena, tmp, n_cu, st,
+                          l == 0 ? n_bad_train : nullptr, &n_bad_host));
+        if (l == 0) RG_TRY(refuse_bad_train());
         void *reached = marked_bytes ? (void *)maps.bytes : (void *)reached_words;
 
         // a4: fresh IDs per (batch, chunk) -> positions -> next frontier
@@ -542,6 +585,7 @@ static rg_status build_schedule_impl(const rg_graph *g, const int32_t *train, ui
         RG_HIP(hipGetLastError());
     }
     RG_HIP(hipStreamSynchronize(st));
+    tmp.drained();
     return RG_OK;
 }
 
@@ -571,7 +615,10 @@ extern "C" rg_status rg_build_schedule_with(const rg_graph *g, const int32_t *tr
     if (L > 0 && !fanout) { set_error("rg_build_schedule: null fanout with L > 0"); return RG_EINVAL; }
     for (uint32_t l = 0; l < L; ++l)
         if (fanout[l] > RG_MAX_FANOUT) { set_error("rg_build_schedule: fanout[%u] = %u exceeds RG_MAX_FANOUT = %u", l, fanout[l], RG_MAX_FANOUT); return RG_ERANGE; }
-    if (T > 0 && (T + batch_size - 1) / batch_size > 0xFFFFFFFFull / 2) { set_error("rg_build_schedule: too many batches"); return RG_ERANGE; }
+    if (T > 0 && (T + batch_size - 1) / batch_size > RG_MAX_BATCHES) {
+        set_error("rg_build_schedule: %llu batches exceed RG_MAX_BATCHES = %u", (unsigned long long)((T + batch_size - 1) / batch_size), RG_MAX_BATCHES);
+        return RG_ERANGE;
+    }
 
     rg_schedule *s = new (std::nothrow) rg_schedule(a);
     if (!s) { set_error("rg_build_schedule: out of host memory"); return RG_ENOMEM; }

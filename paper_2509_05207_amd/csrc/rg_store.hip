@@ -78,7 +78,7 @@ rg_status rg_schedule_save(const rg_schedule *s, const char *path, void *stream)
     File file;
     file.f = fopen(path, "wb");
     if (!file.f) { set_error("rg_schedule_save: cannot open %s for writing", path); return RG_EIO; }
-    Arena tmp(s->arena.allocator());
+    Arena tmp(s->arena.allocator(), st);      // the staging block goes back only behind a drained stream
     void *stage = nullptr;
     RG_TRY(tmp.pinned(STAGE_BYTES, &stage));
     RG_TRY(write_all(file.f, MAGIC, 8));
@@ -129,7 +129,7 @@ rg_status rg_schedule_load(const char *path, const rg_allocator *a, void *stream
     RG_TRY(read_all(file.f, &T, 8));
     RG_TRY(read_all(file.f, &nb, 4));
     RG_TRY(read_all(file.f, &L, 4));
-    if (n_nodes < 0 || n_nodes >= ((int64_t)1 << 31) || L > RG_MAX_HOPS || nb > 0x7FFFFFFFu) {
+    if (n_nodes < 0 || n_nodes >= ((int64_t)1 << 31) || L > RG_MAX_HOPS || nb > RG_MAX_BATCHES) {
         set_error("rg_schedule_load: header out of range (n_nodes %lld, L %u, n_batches %u)", (long long)n_nodes, L, nb);
         return RG_EIO;
     }
@@ -140,7 +140,7 @@ rg_status rg_schedule_load(const char *path, const rg_allocator *a, void *stream
     s->n_nodes = n_nodes; s->T = T; s->n_batches = nb; s->L = L;
     s->uid = g_next_schedule_uid.fetch_add(1);
     s->hop.resize((size_t)L + 1);
-    Arena tmp(a);
+    Arena tmp(a, st);      // the staging block goes back only behind a drained stream
     void *stage = nullptr;
     RG_TRY(tmp.pinned(STAGE_BYTES, &stage));
 

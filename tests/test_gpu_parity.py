@@ -299,6 +299,62 @@ def test_torch_backed_allocator(rg, orc):
     assert len(alloc.live) == 0                                  # everything handed back
 
 
+def test_a_schedule_keeps_its_allocator_alive(rg, orc):
+    """The allocator object is dropped before the schedule: the handle must hold on to it (its memory is the
+    allocator's tensors, and destroy calls back into it)."""
+    import gc
+    w, indptr, indices, train = small_graph()
+    alloc = rg.TorchAllocator()
+    live = alloc.live
+    g = rg.rg_build_schedule(indptr, indices, train, w.cfg.batch_size, w.cfg.fanout, 2, 0, 0, allocator=alloc.struct)
+    del alloc
+    gc.collect()
+    torch.empty(1 << 24, dtype=torch.uint8, device="cuda").fill_(0x5A)      # would land on freed blocks
+    torch.cuda.synchronize()
+    o = orc.Schedule(w.indptr.numpy(), w.indices.numpy(), w.train.numpy(), w.cfg.batch_size, w.cfg.fanout, 2, 0, 0)
+    assert_schedules_equal(rg, g, o)
+    rg.rg_schedule_build_blocks(g)                                           # scratch from the same allocator
+    assert np.array_equal(rg.rg_schedule_block(g, 0).cpu().numpy(), o.block(0))
+    assert len(live) > 0
+    del g
+    gc.collect()
+    assert len(live) == 0
+
+
+def test_train_nodes_are_checked(rg):
+    w, indptr, indices, train = small_graph()
+    n = w.n_nodes
+    for bad_value, fanout in ((n, [3, 2]), (-1, [3, 2]), (2**31 - 1, [3]), (n, [])):
+        bad = train.clone()
+        bad[17] = bad_value
+        with pytest.raises(rg.RgError) as e:
+            rg.rg_build_schedule(indptr, indices, bad, 100, fanout)
+        assert e.value.status == rg.RG_EINVAL and "train nodes" in str(e.value)
+    dup = train.clone()
+    dup[5] = dup[400]                                                        # the same ID twice, in different batches
+    for fanout in ([3, 2], []):
+        with pytest.raises(rg.RgError) as e:
+            rg.rg_build_schedule(indptr, indices, dup, 100, fanout)
+        assert e.value.status == rg.RG_EINVAL
+    torch.cuda.synchronize()
+    rg.rg_build_schedule(indptr, indices, train, 100, [3, 2])                # and the good input still builds
+
+
+def test_more_batches_than_the_limit_are_refused(rg):
+    w, indptr, indices, train = small_graph()
+    T = rg.RG_MAX_BATCHES + 1
+    many = torch.arange(T, dtype=torch.int32, device="cuda") % w.n_nodes     # (never looked at: the count is refused first)
+    with pytest.raises(rg.RgError) as e:
+        rg.rg_build_schedule(indptr, indices, many, 1, [2])
+    assert e.value.status == rg.RG_ERANGE and "RG_MAX_BATCHES" in str(e.value)
+
+
+def test_seeds_view_is_the_first_frontier(case, rg):
+    seeds, off = rg.rg_schedule_seeds(case.gsched)
+    ids, ooff = case.osched.seeds()
+    assert np.array_equal(seeds.cpu().numpy(), ids) and np.array_equal(off.cpu().numpy(), ooff)
+
+
 def test_rows_of_odd_width_and_alignment(rg, orc):
     """Row widths and strides at 16-, 8-, 4-, 2- and 1-byte alignment: 16-byte vectors at every dword phase, every
     tail length, and the byte path."""

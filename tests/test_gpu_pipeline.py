@@ -153,6 +153,41 @@ def test_double_buffered_cache_follows_the_epochs(case, rg, orc):
     assert not rg.rg_cache_pair_swap(pair, wait=True)          # nothing pending: C_s stays
 
 
+def test_swap_while_staged_gathers_are_in_flight(case, rg, orc):
+    """The swap at the epoch boundary releases the old C_s without draining the device: blocks that the prefetcher
+    staged from it just before -- their kernels possibly still running -- must arrive intact, and the memory bound
+    counts the table that is being built."""
+    w = case.w
+    o1 = orc.Schedule(w.indptr.numpy(), w.indices.numpy(), w.train.numpy(), w.cfg.batch_size, w.cfg.fanout, case.s0, case.worker, 1,
+                      n_threads=8)
+    g1 = rg.rg_build_schedule(case.indptr, case.indices, case.train, w.cfg.batch_size, w.cfg.fanout, case.s0, case.worker, 1)
+    out_stride = (w.row_bytes + 15) // 16 * 16
+    Q = min(3, case.gsched.n_batches)
+    slots, m_max = slots_for(case, Q, out_stride)
+    _, slot0 = oracle_cache(orc, case, case.osched)
+    ids1, _ = oracle_cache(orc, case, o1)
+    for _ in range(3):                                           # several boundaries in a row, memory reused in between
+        pair = rg.rg_cache_pair_create(case.gsched, case.gfeat, w.K)
+        pf = rg.rg_prefetcher_create(case.gsched, rg.rg_cache_pair_primary(pair), case.gfeat, slots, out_stride=out_stride,
+                                     slot_capacity_rows=m_max + 1)
+        rg.rg_cache_pair_begin_next(pair, g1)
+        assert rg.rg_prefetcher_fill(pf) == Q                    # Q gathers enqueued from the old C_s ...
+        assert rg.rg_cache_pair_swap(pair, wait=True)            # ... and the old C_s is released under them
+        assert rg.rg_cache_pair_table_bytes(pair) <= 2 * w.K * out_stride
+        junk = rg.rg_build_cache([g1], case.gfeat, w.K)          # a build right behind the swap draws from the same block cache
+        for b in range(Q):
+            got_b, buf, st, was_staged = rg.rg_prefetcher_acquire(pf)
+            assert got_b == b and was_staged
+            torch.cuda.current_stream().synchronize()
+            ref = orc.gather_batch(case.osched, b, case.ofeat, out_stride=out_stride, fill=0xCD)
+            assert np.array_equal(buf.cpu().numpy().reshape(-1, out_stride)[:ref.shape[0], :w.row_bytes], ref[:, :w.row_bytes]), f"batch {b}"
+            assert st == orc.batch_stats(case.osched, b, w.is_local.numpy(), slot0)
+            rg.rg_prefetcher_release(pf)
+        v = rg.rg_cache_view(rg.rg_cache_pair_primary(pair), w.n_nodes)
+        assert np.array_equal(v["cache_ids"].cpu().numpy(), ids1)
+        del pf, junk, pair, v
+
+
 def test_an_unswapped_cache_still_serves_the_next_epoch_exactly(case, rg, orc):
     """The secondary cache is not ready at the boundary (Alg. 1's swap is conditional): the old C_s serves epoch e+1;
     hits are those of the old cache, bytes are unchanged."""
