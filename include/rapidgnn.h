@@ -250,6 +250,33 @@ rg_status rg_gather_batches(const rg_schedule *s, const rg_cache *c, const rg_fe
                             uint32_t n_batches, void *out, uint64_t out_stride, uint64_t out_capacity_rows,
                             void *stream, void *side_stream, rg_gather_stats *stats);
 
+/*
+ * rg_gather_batch_noalloc -- rg_gather_batch for callers that cannot allocate:
+ * code under HIP graph capture, tight serving loops, harnesses that forbid
+ * hipMalloc.  Same result as rg_gather_batch when the cache holds no prepared
+ * plan for `s`: the batch's rows are classified on the fly (c == NULL: every
+ * remote row is a miss) and every row is copied by one launch on `stream`,
+ * remote rows read in place.  The routing entries and counters that
+ * rg_gather_batch takes from an allocation live in a fixed array inside the
+ * library's image instead, RG_NOALLOC_SCRATCH_BYTES per GPU the library runs
+ * on, held until the process ends.  The call makes no hipMalloc / hipFree and
+ * uses no allocator, block cache or event timer.
+ *
+ *   stats  host or NULL.  NULL: the call only enqueues kernels on `stream` (it
+ *          may be recorded into a graph), and `s` and `c` must stay alive
+ *          until that work has finished.  Otherwise the counts are copied back
+ *          and the call waits for `stream`.
+ * RG_ERANGE, with nothing written, if the batch has more than
+ * RG_NOALLOC_MAX_ROWS rows, more than out_capacity_rows, or batch >= n_batches.
+ * Every call on a GPU uses that GPU's one scratch array: calls on the same GPU
+ * must be ordered (same stream, or otherwise serialised); two that overlap race.
+ */
+#define RG_NOALLOC_MAX_ROWS      ((uint64_t)1 << 22)                       /* 4,194,304 rows per batch */
+#define RG_NOALLOC_SCRATCH_BYTES (256u + 8u * RG_NOALLOC_MAX_ROWS)         /* 32 MiB + 256 B */
+rg_status rg_gather_batch_noalloc(const rg_schedule *s, const rg_cache *c, const rg_features *f, uint32_t batch,
+                                  void *out, uint64_t out_stride, uint64_t out_capacity_rows, void *stream,
+                                  rg_gather_stats *stats);
+
 /* The counts of rg_gather_batch without the copy (Alg. 1 inner loop: the miss
  * set M_i^e and rpc_e += |M_i^e|): what a cache-size sweep needs.  From the
  * prepared plan when `c` was built from `s` (no device work), otherwise one

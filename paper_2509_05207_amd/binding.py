@@ -26,7 +26,7 @@ EXPORTS = ("rg_last_error", "rg_graph_validate", "rg_build_schedule", "rg_schedu
            "rg_prefetcher_create", "rg_prefetcher_fill", "rg_prefetcher_acquire", "rg_prefetcher_release",
            "rg_prefetcher_depth", "rg_prefetcher_destroy", "rg_schedule_build_blocks", "rg_schedule_block",
            "rg_classify_batch", "rg_build_schedule_with", "rg_gather_batches",
-           "rg_schedule_save", "rg_schedule_load", "rg_schedule_seeds")
+           "rg_schedule_save", "rg_schedule_load", "rg_gather_batch_noalloc", "rg_schedule_seeds")
 
 
 class RgError(RuntimeError):
@@ -89,6 +89,7 @@ def lib():
         L.rg_build_cache.argtypes = [P(vp), u32, P(rg_features), u64, P(rg_allocator), vp, P(vp)]
         L.rg_cache_view.argtypes = [vp, P(u64), P(vp), P(vp), P(vp), P(vp), P(u64)]
         L.rg_gather_batch.argtypes = [vp, vp, P(rg_features), u32, vp, u64, u64, vp, vp, P(rg_gather_stats)]
+        L.rg_gather_batch_noalloc.argtypes = [vp, vp, P(rg_features), u32, vp, u64, u64, vp, P(rg_gather_stats)]
         L.rg_schedule_destroy.argtypes = [vp]; L.rg_schedule_destroy.restype = None
         L.rg_cache_destroy.argtypes = [vp]; L.rg_cache_destroy.restype = None
         L.rg_trim_memory.argtypes = []; L.rg_trim_memory.restype = None
@@ -119,7 +120,7 @@ def lib():
                      "rg_prefetcher_create", "rg_prefetcher_fill", "rg_prefetcher_acquire", "rg_prefetcher_release",
                      "rg_prefetcher_depth", "rg_schedule_build_blocks", "rg_schedule_block",
            "rg_classify_batch", "rg_build_schedule_with", "rg_gather_batches",
-           "rg_schedule_save", "rg_schedule_load", "rg_schedule_seeds"):
+           "rg_schedule_save", "rg_schedule_load", "rg_gather_batch_noalloc", "rg_schedule_seeds"):
             getattr(L, name).restype = C.c_int32
         _lib = L
     return _lib
@@ -316,6 +317,22 @@ def rg_gather_batch(s, c, features, batch, out, out_stride=None, out_capacity_ro
     _check(lib().rg_gather_batch(s.h, c.h if c is not None else None, C.byref(features), int(batch), C.c_void_p(out.data_ptr()),
                                  int(out_stride), int(out_capacity_rows), _stream_ptr(stream), side,
                                  C.byref(st) if want_stats else None))
+    return dict(n_rows=st.n_rows, n_local=st.n_local, n_hit=st.n_hit, n_miss=st.n_miss) if want_stats else None
+
+
+RG_NOALLOC_MAX_ROWS = 1 << 22
+
+
+def rg_gather_batch_noalloc(s, c, features, batch, out, out_stride=None, out_capacity_rows=None, stream=None, want_stats=True):
+    """rg_gather_batch through the entry point that allocates nothing; returns the stats dict (None without stats)."""
+    assert out.is_cuda and out.is_contiguous()
+    if out_stride is None:
+        out_stride = out.stride(0) * out.element_size()
+    if out_capacity_rows is None:
+        out_capacity_rows = out.numel() * out.element_size() // out_stride
+    st = rg_gather_stats()
+    _check(lib().rg_gather_batch_noalloc(s.h, c.h if c is not None else None, C.byref(features), int(batch), C.c_void_p(out.data_ptr()),
+                                         int(out_stride), int(out_capacity_rows), _stream_ptr(stream), C.byref(st) if want_stats else None))
     return dict(n_rows=st.n_rows, n_local=st.n_local, n_hit=st.n_hit, n_miss=st.n_miss) if want_stats else None
 
 

@@ -327,7 +327,7 @@ bool profiling_on() { return g_prof_on.load(std::memory_order_relaxed) != 0; }
 
 ScopedTimer::ScopedTimer(int g, hipStream_t s) : group(g), st(s)
 {
-    if (!profiling_on()) return;
+    if (g < 0 || !profiling_on()) return;       // group -1: a launch that is never timed
     {
         std::lock_guard<std::mutex> lk(g_prof_mu);
         if (g_free_events.size() >= 2) {

@@ -16,6 +16,7 @@
 #include "rg_internal.h"
 
 #include <algorithm>
+#include <mutex>
 
 namespace rg {
 
@@ -208,9 +209,91 @@ __global__ void route_batch_kernel(const int32_t *__restrict__ ids, int64_t n, c
     }
 }
 
+// ---------------------------------------------------------------- the entry point that allocates nothing
+// Its scratch -- the three counters and one routing entry per row of the batch -- lives in the library's image: one
+// copy per GPU, at an address of that GPU's own, which the host asks for once per device.  The array's name is only a
+// stand-in on the host; kernels and copies get the pointer kept here.
+constexpr uint64_t NOALLOC_HEAD_BYTES = 256;                       // the counters, in front of the entries
+static __device__ __align__(256) unsigned char scratch[NOALLOC_HEAD_BYTES + RG_NOALLOC_MAX_ROWS * sizeof(int64_t)];
+
+constexpr int MAX_DEVICES = 64;
+static std::mutex g_scratch_mu;
+static void *g_scratch_ptr[MAX_DEVICES];                           // per device; NULL until asked for
+
+// The current device's copy of `scratch`.
+static rg_status scratch_of_current_device(unsigned char **out)
+{
+    int dev = 0;
+    RG_HIP(hipGetDevice(&dev));
+    if (dev < 0 || dev >= MAX_DEVICES) { set_error("rg_gather_batch_noalloc: device %d beyond the %d this build keeps scratch for", dev, MAX_DEVICES); return RG_ERANGE; }
+    std::lock_guard<std::mutex> lk(g_scratch_mu);
+    if (!g_scratch_ptr[dev]) {
+        void *p = nullptr;
+        RG_HIP(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+        if (!p) { set_error("rg_gather_batch_noalloc: no address for the scratch array on device %d", dev); return RG_EHIP; }
+        g_scratch_ptr[dev] = p;
+    }
+    *out = static_cast<unsigned char *>(g_scratch_ptr[dev]);
+    return RG_OK;
+}
+
+// (a fill kernel, not hipMemsetAsync: the call may be recorded into a graph)
+__global__ void clear_counts_kernel(unsigned long long *__restrict__ counts)
+{
+    if (threadIdx.x < 3) counts[threadIdx.x] = 0ull;
+}
+
 }  // namespace rg
 
 using namespace rg;
+
+extern "C" rg_status rg_gather_batch_noalloc(const rg_schedule *s, const rg_cache *c, const rg_features *f, uint32_t batch, void *out,
+                                             uint64_t out_stride, uint64_t out_capacity_rows, void *stream, rg_gather_stats *stats)
+{
+    if (!s || !f) { set_error("rg_gather_batch_noalloc: null schedule or features"); return RG_EINVAL; }
+    if (batch >= s->n_batches) { set_error("rg_gather_batch_noalloc: batch %u >= n_batches = %u", batch, s->n_batches); return RG_ERANGE; }
+    if (f->row_bytes == 0 || out_stride < f->row_bytes || f->local_stride < f->row_bytes || f->remote_stride < f->row_bytes) {
+        set_error("rg_gather_batch_noalloc: row_bytes = %u with strides out %llu local %llu remote %llu", f->row_bytes,
+                  (unsigned long long)out_stride, (unsigned long long)f->local_stride, (unsigned long long)f->remote_stride);
+        return RG_EINVAL;
+    }
+    if (c && (c->n_nodes != s->n_nodes || c->row_bytes != f->row_bytes)) { set_error("rg_gather_batch_noalloc: cache does not match schedule / features"); return RG_EINVAL; }
+    const HopData &h = s->hop[s->L];
+    const int64_t off = h.off_host[batch];
+    const int64_t m = h.off_host[batch + 1] - off;
+    if ((uint64_t)m > RG_NOALLOC_MAX_ROWS) {
+        set_error("rg_gather_batch_noalloc: batch %u has %lld rows, the built-in scratch holds RG_NOALLOC_MAX_ROWS = %llu", batch, (long long)m,
+                  (unsigned long long)RG_NOALLOC_MAX_ROWS);
+        return RG_ERANGE;
+    }
+    if ((uint64_t)m > out_capacity_rows) {
+        set_error("rg_gather_batch_noalloc: batch %u has %lld rows, output holds %llu", batch, (long long)m, (unsigned long long)out_capacity_rows);
+        return RG_ERANGE;
+    }
+    if (m > 0 && !out) { set_error("rg_gather_batch_noalloc: null output"); return RG_EINVAL; }
+    unsigned char *base = nullptr;
+    RG_TRY(scratch_of_current_device(&base));
+    unsigned long long *counts = reinterpret_cast<unsigned long long *>(base);
+    int64_t *entry = reinterpret_cast<int64_t *>(base + NOALLOC_HEAD_BYTES);
+    hipStream_t st = as_stream(stream);
+    RowSources src{(const uint8_t *)f->local_rows, f->local_stride, c ? (const uint8_t *)c->rows : (const uint8_t *)f->local_rows,
+                   c ? c->stride : f->local_stride, (const uint8_t *)f->remote_rows, f->remote_stride};
+    hipLaunchKernelGGL(clear_counts_kernel, dim3(1), dim3(64), 0, st, counts);
+    if (m > 0) {
+        hipLaunchKernelGGL(route_batch_kernel, dim3((unsigned)((m + 255) / 256)), dim3(256), 0, st, h.ids + off, m, f->is_local, f->row_of,
+                           c ? c->slot_of : nullptr, entry, counts);
+        RG_HIP(hipGetLastError());
+        RG_TRY(launch_gather(entry, m, nullptr, 0, 1, src, f->row_bytes, (uint8_t *)out, out_stride, st, -1));      // (group -1: no event timers, they are created on demand)
+    }
+    RG_HIP(hipGetLastError());
+    if (stats) {
+        unsigned long long hc[3] = {0, 0, 0};
+        RG_HIP(hipMemcpyAsync(hc, counts, sizeof(hc), hipMemcpyDeviceToHost, st));
+        RG_HIP(hipStreamSynchronize(st));
+        stats->n_rows = (uint64_t)m; stats->n_local = hc[0]; stats->n_hit = hc[1]; stats->n_miss = hc[2];
+    }
+    return RG_OK;
+}
 
 extern "C" rg_status rg_gather_batch(const rg_schedule *s, const rg_cache *c, const rg_features *f, uint32_t batch, void *out,
                                      uint64_t out_stride, uint64_t out_capacity_rows, void *stream, void *side_stream,
