@@ -245,9 +245,39 @@ def make_workload(name_or_cfg, device="cpu", feature_device=None, pin_remote=Fal
                     row_bytes, stride_bytes, K, dict(n_local=n_local, n_remote=n_remote))
 
 
+_hip = None
+
+
+def pinned_empty(shape, dtype) -> torch.Tensor:
+    """An uninitialised tensor in pinned host memory of exactly the size asked for, straight from hipHostMalloc.
+    (torch's pinned allocator rounds a request up to the next power of two, which for a table of tens of GB goes
+    past what a box lets a process pin.)  The memory is freed when the last tensor or array over it is gone."""
+    import ctypes
+    import weakref
+    global _hip
+    if _hip is None:
+        torch.cuda.init()
+        _hip = ctypes.CDLL("libamdhip64.so")
+        _hip.hipHostMalloc.argtypes = [ctypes.POINTER(ctypes.c_void_p), ctypes.c_size_t, ctypes.c_uint]
+        _hip.hipHostFree.argtypes = [ctypes.c_void_p]
+    n = 1
+    for d in shape:
+        n *= int(d)
+    nbytes = n * torch.empty(0, dtype=dtype).element_size()
+    if nbytes == 0:
+        return torch.empty(shape, dtype=dtype, pin_memory=True)
+    p = ctypes.c_void_p()
+    rc = _hip.hipHostMalloc(ctypes.byref(p), nbytes, 0)
+    if rc != 0 or not p.value:
+        raise MemoryError(f"hipHostMalloc of {nbytes} bytes failed with status {rc}")
+    buf = (ctypes.c_uint8 * nbytes).from_address(p.value)
+    weakref.finalize(buf, _hip.hipHostFree, p)
+    return torch.frombuffer(buf, dtype=dtype).view(*shape)
+
+
 def pinned_copy(t: torch.Tensor, chunk_rows: int = 1 << 22) -> torch.Tensor:
     """A pinned host copy of a (device) table, made in chunks."""
-    out = torch.empty(t.shape, dtype=t.dtype, pin_memory=True)
+    out = pinned_empty(tuple(t.shape), t.dtype)
     for lo in range(0, t.shape[0], chunk_rows):
         out[lo:lo + chunk_rows].copy_(t[lo:lo + chunk_rows])
     return out

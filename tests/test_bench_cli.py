@@ -14,12 +14,13 @@ def test_more_than_one_gpu_is_refused_with_a_message():
 
 def test_measured_traffic_table_is_well_formed():
     import json
-    with open(os.path.join(ROOT, "paper_2509_05207_amd", "measured_traffic.json")) as fh:
+    with open(os.path.join(ROOT, "profiles", "measured_traffic.json")) as fh:
         t = json.load(fh)
     for key, rec in t.items():
         if key.startswith("_"):
             continue
         workload, kernel = key.split(":")
         assert workload and kernel
-        assert rec["hbm_bytes_per_launch"] > 0
-        assert abs(rec["fetch_bytes"] + rec["write_bytes"] - rec["hbm_bytes_per_launch"]) <= 0.01 * rec["hbm_bytes_per_launch"]
+        assert rec["hbm_bytes_per_step"] > 0 and rec["launches_per_step"] > 0
+        assert abs(rec["fetch_bytes_per_step"] + rec["write_bytes_per_step"] - rec["hbm_bytes_per_step"]) <= 0.01 * rec["hbm_bytes_per_step"]
+        assert os.path.exists(os.path.join(ROOT, rec["source"]))

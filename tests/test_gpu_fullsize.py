@@ -1,10 +1,23 @@
-"""GPU parity at the benchmark's full sizes, in the launch configuration bench.py times.
+"""GPU parity at the benchmark's full sizes, every stage against the CPU oracle.
 
-medium (the benchmarked workload): the whole epoch against the oracle (16 host threads build the
-oracle's schedule), every frontier, sample, count, cache member and slot, plus the gathered bytes and
-stats of sampled batches.  large_sparse and fanout_stress: sampled batches, which the oracle builds one
-by one (a batch built alone equals the batch inside the epoch), plus size-independent properties of
-the whole epoch."""
+For medium, large_sparse, fanout_stress and partition_share the oracle builds the WHOLE epoch (one host thread per
+batch) and everything the library produces is compared with it bit for bit: every frontier, batch offset and
+sample of every hop; freq of every node; the TopHot set, its slots and the cache table; the counts of every
+batch; and the gathered bytes of a spread of batches (first, last = ragged, some in between), one batch per
+launch and in the launch shape the benchmark times (several batches staged back to back by rg_gather_batches).
+Nothing here is checked against the library's own outputs.
+
+Memory placement: large_sparse and partition_share keep the remote table in pinned host memory, as their
+configuration says (VectorPull and SyncPull cross the host link); medium and fanout_stress keep it in HBM.
+Every workload also builds a second cache whose K lies below the number of candidates, so that the radix select and
+the id-ascending tie-break at the threshold frequency run at full size (partition_share's own K covers every
+touched remote row) and so that misses exist to be pulled.
+
+The tiny configuration's whole epoch is covered by test_gpu_parity.py.
+"""
+import sys
+import time
+
 import numpy as np
 import pytest
 import torch
@@ -13,13 +26,31 @@ from paper_2509_05207_amd import synth
 
 pytestmark = pytest.mark.gpu
 
+PINNED_REMOTE = {"medium": False, "large_sparse": True, "fanout_stress": False, "partition_share": True}
+ORACLE_THREADS = 16
+
+
+_capture = None
+
 
 @pytest.fixture(scope="module")
-def rg():
+def rg(request):
     from paper_2509_05207_amd import binding
     binding.lib()
     assert torch.cuda.is_available(), "GPU tests need a GPU"
+    global _capture
+    _capture = request.config.pluginmanager.getplugin("capturemanager")
     return binding
+
+
+def note(msg):
+    """A progress line past pytest's capture (these tests run for a while, and a silent run looks hung from outside)."""
+    line = f"[fullsize {time.strftime('%H:%M:%S')}] {msg}"
+    if _capture is not None:
+        with _capture.global_and_fixture_disabled():
+            print(line, file=sys.stderr, flush=True)
+    else:
+        print(line, file=sys.stderr, flush=True)
 
 
 def host(t):
@@ -30,139 +61,150 @@ def np_bytes(t):
     return t.contiguous().view(torch.uint8).cpu().numpy()
 
 
-def build(rg, name):
-    cfg = synth.CONFIGS[name]
-    # the largest configuration's remote table (tens of GB) is produced on the device, as bench.py does
-    W = synth.make_workload(cfg, device="cuda", feature_device="cuda", remote_device="cuda" if name == "partition_share" else None)
-    s = rg.rg_build_schedule(W.indptr, W.indices, W.train, cfg.batch_size, cfg.fanout, cfg.s0, cfg.worker, cfg.epoch)
-    return cfg, W, s
+class Epoch:
+    """One workload at full size: the library's schedule on the device, the oracle's on the host, both feature views."""
+
+    def __init__(self, name, rg, orc):
+        t0 = time.perf_counter()
+        self.name = name
+        cfg = self.cfg = synth.CONFIGS[name]
+        W = self.W = synth.make_workload(cfg, device="cuda", feature_device="cuda", remote_device="cuda")
+        torch.cuda.synchronize()
+        note(f"{name}: inputs generated ({time.perf_counter() - t0:.1f} s)")
+        self.s = rg.rg_build_schedule(W.indptr, W.indices, W.train, cfg.batch_size, cfg.fanout, cfg.s0, cfg.worker, cfg.epoch)
+        self.o = orc.Schedule(host(W.indptr), host(W.indices), host(W.train), cfg.batch_size, cfg.fanout, cfg.s0, cfg.worker, cfg.epoch,
+                              n_threads=ORACLE_THREADS)
+        note(f"{name}: oracle schedule of {self.o.n_batches} batches built ({time.perf_counter() - t0:.1f} s)")
+        self.is_local = host(W.is_local)
+        if PINNED_REMOTE[name]:
+            self.remote = synth.pinned_copy(W.remote_rows)        # the other partitions' memory: pinned host
+            W.remote_rows = None                                   # (the device copy is not needed any more)
+            remote_np = self.remote.view(torch.uint8).numpy()     # the oracle reads the very same host bytes
+            note(f"{name}: remote table of {remote_np.nbytes / 1e9:.1f} GB in pinned host memory ({time.perf_counter() - t0:.1f} s)")
+        else:
+            self.remote = W.remote_rows
+            remote_np = np_bytes(W.remote_rows)
+        self.feat = rg.make_features(W.is_local, W.row_of, W.local_rows, self.remote, W.row_bytes)
+        self.ofeat = orc.Features(self.is_local, host(W.row_of), np_bytes(W.local_rows), W.stride_bytes, remote_np, W.stride_bytes,
+                                  W.row_bytes)
+        self.freq = orc.frequency([self.o], W.n_nodes)
+        self.n_candidates = int(((self.is_local == 0) & (self.freq > 0)).sum())
+        _, self.off = self.o.input_nodes()
+        note(f"{name}: ready ({time.perf_counter() - t0:.1f} s); {int(self.off[-1])} input nodes, {self.n_candidates} candidates, K = {W.K}")
+
+    def spread(self):
+        """First, last (ragged) and a few batches in between."""
+        nb = self.o.n_batches
+        return sorted({0, 1, nb // 3, nb // 2, (2 * nb) // 3, nb - 2, nb - 1})
+
+    def group_size(self):
+        """Batches per gather launch, as bench.py chooses it."""
+        nb, rows = self.o.n_batches, int(self.off[-1])
+        G = 8
+        while G < 64 and G < nb and rows / nb * G * self.W.stride_bytes < (512 << 20):
+            G *= 2
+        return G
 
 
-def compare_batch(rg, s, o_one, b):
-    """Batch b of the GPU schedule against the oracle's schedule that holds only that batch."""
-    for hop in range(s.L + 1):
-        gids, _, goff = rg.rg_schedule_frontier(s, hop)
-        ids, _ = o_one.frontier(hop)
-        assert np.array_equal(host(gids[goff[b]:goff[b + 1]]), ids), f"batch {b} frontier {hop}"
-    for hop in range(s.L):
-        _, _, goff = rg.rg_schedule_frontier(s, hop)
-        gso, gnb = rg.rg_schedule_samples(s, hop)
-        so, nb = o_one.samples(hop)
-        lo, hi = int(goff[b]), int(goff[b + 1])
-        seg_off = host(gso[lo:hi + 1])
-        assert np.array_equal(seg_off - seg_off[0], so), f"batch {b} sample offsets {hop}"
-        assert np.array_equal(host(gnb[int(seg_off[0]):int(seg_off[-1])]), nb), f"batch {b} samples {hop}"
+@pytest.fixture(scope="module", params=["medium", "large_sparse", "fanout_stress", "partition_share"])
+def ep(request, rg, orc):
+    e = Epoch(request.param, rg, orc)
+    yield e
+    del e
+    rg.rg_trim_memory()
+    torch.cuda.empty_cache()
 
 
-def test_medium_whole_epoch(rg, orc):
-    cfg, W, s = build(rg, "medium")
-    indptr, indices, train = host(W.indptr), host(W.indices), host(W.train)
-    o = orc.Schedule(indptr, indices, train, cfg.batch_size, cfg.fanout, cfg.s0, cfg.worker, cfg.epoch, n_threads=16)
-    assert s.n_batches == o.n_batches == 147
+def test_every_frontier_and_sample(ep, rg):
+    s, o = ep.s, ep.o
+    assert s.n_batches == o.n_batches and s.L == o.L
     for hop in range(o.L + 1):
         ids, off = o.frontier(hop)
-        gids, _, goff = rg.rg_schedule_frontier(s, hop)
-        assert np.array_equal(goff, off) and np.array_equal(host(gids), ids), f"frontier {hop}"
+        gids, goff_dev, goff = rg.rg_schedule_frontier(s, hop)
+        assert np.array_equal(goff, off), f"{ep.name}: batch offsets of hop {hop}"
+        assert np.array_equal(host(goff_dev), off)
+        assert np.array_equal(host(gids), ids), f"{ep.name}: frontier {hop}"
     for hop in range(o.L):
         so, nb = o.samples(hop)
         gso, gnb = rg.rg_schedule_samples(s, hop)
-        assert np.array_equal(host(gso), so) and np.array_equal(host(gnb), nb), f"samples {hop}"
-    rg.rg_schedule_build_blocks(s)
-    for hop in range(o.L):
-        assert np.array_equal(host(rg.rg_schedule_block(s, hop)), o.block(hop)), f"block {hop}"
+        assert np.array_equal(host(gso), so), f"{ep.name}: sample offsets of hop {hop}"
+        assert np.array_equal(host(gnb), nb), f"{ep.name}: samples of hop {hop}"
+        del so, nb, gso, gnb
+    note(f"{ep.name}: every frontier and sample equal")
+    if ep.name == "medium":        # computation blocks of a whole epoch at full size (test_gpu_parity.py covers the other shapes)
+        rg.rg_schedule_build_blocks(s)
+        for hop in range(o.L):
+            assert np.array_equal(host(rg.rg_schedule_block(s, hop)), o.block(hop)), f"block {hop}"
 
-    is_local = host(W.is_local)
-    remote = W.remote_rows.cuda()
-    feat = rg.make_features(W.is_local, W.row_of, W.local_rows, remote, W.row_bytes)
-    c = rg.rg_build_cache([s], feat, W.K)
-    freq = orc.frequency([o], W.n_nodes)
-    ids, slot = orc.top_hot(freq, is_local, W.K)
+
+def check_cache(ep, rg, orc, c, K, batches, tag):
+    """Everything a cache holds and serves, against the oracle: freq, TopHot set and slots, table, the counts of EVERY
+    batch, the gathered bytes of `batches` one by one and of the groups of batches that contain them."""
+    W, o = ep.W, ep.o
+    ids, slot = orc.top_hot(ep.freq, ep.is_local, K)
     v = rg.rg_cache_view(c, W.n_nodes)
-    assert np.array_equal(host(v["freq"]).view(np.uint32), freq)
-    assert np.array_equal(host(v["cache_ids"]), ids) and np.array_equal(host(v["slot_of"]), slot)
-
-    ofeat = orc.Features(is_local, host(W.row_of), np_bytes(W.local_rows), W.stride_bytes, np_bytes(remote), W.stride_bytes, W.row_bytes)
-    table = orc.cache_fill(ids, ofeat, table_stride=v["stride"])
-    assert np.array_equal(host(v["rows"]).reshape(ids.size, v["stride"])[:, :W.row_bytes], table[:, :W.row_bytes])
-    _, off = o.input_nodes()
+    assert np.array_equal(host(v["freq"]).view(np.uint32), ep.freq), f"{tag}: freq"
+    assert v["K_eff"] == ids.size == min(K, ep.n_candidates), f"{tag}: K_eff"
+    assert np.array_equal(host(v["cache_ids"]), ids), f"{tag}: TopHot set"
+    assert np.array_equal(host(v["slot_of"]), slot), f"{tag}: slots"
+    table = orc.cache_fill(ids, ep.ofeat, table_stride=v["stride"])
+    assert np.array_equal(host(v["rows"]).reshape(ids.size, v["stride"])[:, :W.row_bytes], table[:, :W.row_bytes]), f"{tag}: cache table"
+    del table
+    note(f"{tag}: freq, TopHot ({ids.size} of {ep.n_candidates} candidates) and cache table equal")
+    want = [orc.batch_stats(o, b, ep.is_local, slot) for b in range(o.n_batches)]
+    got = [rg.rg_classify_batch(ep.s, c, ep.feat, b) for b in range(o.n_batches)]
+    assert got == want, f"{tag}: counts of some batch differ"
+    assert sum(x["n_miss"] for x in want) == int(ep.freq[(ep.is_local == 0) & (slot < 0)].sum()), "misses = frequency mass left out of the cache"
+    off = ep.off
     m_max = int(np.diff(off).max())
     out = torch.empty(m_max * W.stride_bytes, dtype=torch.uint8, device="cuda")
     side = torch.cuda.Stream()
-    for b in (0, 73, 146):
-        st = rg.rg_gather_batch(s, c, feat, b, out, out_stride=W.stride_bytes, out_capacity_rows=m_max, side_stream=side)
+    for b in batches:
+        out.fill_(0xCD)
+        st = rg.rg_gather_batch(ep.s, c, ep.feat, b, out, out_stride=W.stride_bytes, out_capacity_rows=m_max, side_stream=side)
         torch.cuda.synchronize()
-        ref = orc.gather_batch(o, b, ofeat, out_stride=W.stride_bytes)
-        got = host(out)[: ref.size].reshape(ref.shape)
-        assert np.array_equal(got[:, :W.row_bytes], ref[:, :W.row_bytes]), f"gathered rows of batch {b}"
-        assert st == orc.batch_stats(o, b, is_local, slot)
-    # the launch shape the benchmark times: eight batches per launch, staged back to back
-    G = 8
-    for first in (0, 144):                                      # a whole group and the ragged last one
-        n = min(G, s.n_batches - first)
+        ref = orc.gather_batch(o, b, ep.ofeat, out_stride=W.stride_bytes, fill=0xCD)
+        assert np.array_equal(host(out)[: ref.size].reshape(ref.shape), ref), f"{tag}: gathered rows of batch {b}"
+        assert st == want[b]
+    del out
+    # the launch shape the benchmark times: G consecutive batches staged back to back by one call
+    G = ep.group_size()
+    firsts = sorted({0, (o.n_batches - 1) // G * G})            # a whole group and the ragged last one
+    for first in firsts:
+        n = min(G, o.n_batches - first)
         rows = int(off[first + n] - off[first])
-        big = torch.empty(rows * W.stride_bytes, dtype=torch.uint8, device="cuda")
-        stats = rg.rg_gather_batches(s, c, feat, first, n, big, out_stride=W.stride_bytes, out_capacity_rows=rows, side_stream=side)
+        big = torch.full((rows * W.stride_bytes,), 0xCD, dtype=torch.uint8, device="cuda")
+        stats = rg.rg_gather_batches(ep.s, c, ep.feat, first, n, big, out_stride=W.stride_bytes, out_capacity_rows=rows, side_stream=side)
         torch.cuda.synchronize()
-        got = host(big).reshape(rows, W.stride_bytes)
+        got_rows = host(big).reshape(rows, W.stride_bytes)
+        del big
         for k in range(n):
             b = first + k
-            ref = orc.gather_batch(o, b, ofeat, out_stride=W.stride_bytes)
+            ref = orc.gather_batch(o, b, ep.ofeat, out_stride=W.stride_bytes, fill=0xCD)
             at = int(off[b] - off[first])
-            assert np.array_equal(got[at:at + ref.shape[0], :W.row_bytes], ref[:, :W.row_bytes]), f"group at {first}, batch {b}"
-            assert stats[k] == orc.batch_stats(o, b, is_local, slot)
-        del big
+            assert np.array_equal(got_rows[at:at + ref.shape[0]], ref), f"{tag}: group of {n} at {first}, batch {b}"
+            assert stats[k] == want[b]
+        del got_rows
+    note(f"{tag}: counts of all {o.n_batches} batches, rows of batches {batches} and of {len(firsts)} groups of {G} equal")
 
 
-@pytest.mark.parametrize("name,batches", [("large_sparse", (0, 97, 195)), ("fanout_stress", (0, 48)), ("partition_share", (0, 146))])
-def test_sampled_batches_and_epoch_properties(rg, orc, name, batches):
-    cfg, W, s = build(rg, name)
-    indptr, indices, train = host(W.indptr), host(W.indices), host(W.train)
-    for b in batches:
-        o_one = orc.Schedule(indptr, indices, train, cfg.batch_size, cfg.fanout, cfg.s0, cfg.worker, cfg.epoch, batch_lo=b, batch_hi=b + 1)
-        compare_batch(rg, s, o_one, b)
-    # properties that hold at any size
-    deg = W.indptr[1:] - W.indptr[:-1]
-    for hop in range(s.L):
-        gids, goff_dev, goff = rg.rg_schedule_frontier(s, hop)
-        gso, gnb = rg.rg_schedule_samples(s, hop)
-        want = torch.clamp(deg[gids.long()], max=cfg.fanout[hop])
-        assert torch.equal(gso[1:] - gso[:-1], want)                          # |sample| = min(deg, fanout)
-        nxt, _, noff = rg.rg_schedule_frontier(s, hop + 1)
-        assert np.all(np.diff(noff) >= np.diff(goff))
-        b = batches[-1]                                                       # prefix property and ascending new part
-        cur_b, nxt_b = gids[goff[b]:goff[b + 1]], nxt[noff[b]:noff[b + 1]]
-        assert torch.equal(nxt_b[: cur_b.numel()], cur_b)
-        new = nxt_b[cur_b.numel():]
-        assert bool((new[1:] > new[:-1]).all())
-        assert torch.unique(nxt_b).numel() == nxt_b.numel()
-    feat = rg.make_features(W.is_local, W.row_of, W.local_rows, W.remote_rows.cuda(), W.row_bytes)
-    c = rg.rg_build_cache([s], feat, W.K)
-    v = rg.rg_cache_view(c, W.n_nodes)
-    ids_L, _, off_L = rg.rg_schedule_frontier(s, s.L)
-    freq = v["freq"]
-    assert int(freq.sum().item()) == ids_L.numel()                            # counts sum to the listed IDs
-    assert torch.equal(freq, torch.bincount(ids_L.long(), minlength=W.n_nodes).to(torch.int32))
-    cand = (W.is_local == 0) & (freq > 0)
-    k_eff = min(W.K, int(cand.sum().item()))
-    assert v["K_eff"] == k_eff
-    sel = v["slot_of"] >= 0
-    assert int(sel.sum().item()) == k_eff and not bool((sel & ~cand).any())
-    if k_eff and int((cand & ~sel).sum().item()):
-        assert int(freq[sel].min().item()) >= int(freq[cand & ~sel].max().item())   # nothing hotter is left out
-    assert torch.equal(v["cache_ids"].long(), torch.nonzero(sel).flatten())
-    # gather of one batch equals direct indexing of the assembled table (device-side reference)
-    b = batches[-1]
-    seg = ids_L[off_L[b]:off_L[b + 1]].long()
-    out = torch.empty((seg.numel(), W.stride_bytes), dtype=torch.uint8, device="cuda")
-    st = rg.rg_gather_batch(s, c, feat, b, out, out_stride=W.stride_bytes, out_capacity_rows=seg.numel())
-    torch.cuda.synchronize()
-    loc = W.local_rows.contiguous().view(torch.uint8).reshape(-1, W.stride_bytes)
-    rem = feat._keep[3].contiguous().view(torch.uint8).reshape(-1, W.stride_bytes)
-    is_loc = W.is_local[seg] == 1
-    ref = torch.where(is_loc[:, None], loc[W.row_of[seg].long() * is_loc], rem[W.row_of[seg].long() * (~is_loc)])
-    assert torch.equal(out[:, :W.row_bytes], ref[:, :W.row_bytes])
-    assert st["n_rows"] == seg.numel() and st["n_local"] == int(is_loc.sum().item())
-    assert st["n_hit"] == int((sel[seg] & ~is_loc).sum().item()) and st["n_miss"] == st["n_rows"] - st["n_local"] - st["n_hit"]
+def test_cache_and_gather_with_the_configured_k(ep, rg, orc):
+    c = rg.rg_build_cache([ep.s], ep.feat, ep.W.K)
+    check_cache(ep, rg, orc, c, ep.W.K, ep.spread(), f"{ep.name}, K = {ep.W.K}")
+
+
+def test_cache_and_gather_with_k_below_the_candidates(ep, rg, orc):
+    """K in the middle of a run of equal frequencies: the select's threshold pass and the id-ascending tie-break decide."""
+    order = np.sort(ep.freq[(ep.is_local == 0) & (ep.freq > 0)].astype(np.int64))[::-1]
+    K = ep.n_candidates // 2
+    t = order[K]
+    run_lo, run_hi = int(np.searchsorted(-order, -t, "left")), int(np.searchsorted(-order, -t, "right"))
+    if run_hi - run_lo >= 3:
+        K = (run_lo + run_hi) // 2                              # strictly inside the tied run
+    assert 0 < K < ep.n_candidates
+    c = rg.rg_build_cache([ep.s], ep.feat, K)
+    nb = ep.o.n_batches
+    check_cache(ep, rg, orc, c, K, [0, nb // 2, nb - 1], f"{ep.name}, K = {K} (threshold frequency {int(t)}, tied run of {run_hi - run_lo})")
 
 
 def test_medium_whole_epoch_position_sampler(rg, orc):
@@ -172,7 +214,7 @@ def test_medium_whole_epoch_position_sampler(rg, orc):
     s = rg.rg_build_schedule_with(W.indptr, W.indices, W.train, cfg.batch_size, cfg.fanout, cfg.s0, cfg.worker, cfg.epoch,
                                   sampler=rg.RG_SAMPLER_POSITIONS)
     o = orc.Schedule(host(W.indptr), host(W.indices), host(W.train), cfg.batch_size, cfg.fanout, cfg.s0, cfg.worker, cfg.epoch,
-                     n_threads=16, sampler="positions")
+                     n_threads=ORACLE_THREADS, sampler="positions")
     assert s.n_batches == o.n_batches
     for hop in range(o.L + 1):
         ids, off = o.frontier(hop)
