@@ -21,6 +21,6 @@ def test_measured_traffic_table_is_well_formed():
             continue
         workload, kernel = key.split(":")
         assert workload and kernel
-        assert rec["hbm_bytes_per_step"] > 0 and rec["launches_per_step"] > 0
+        assert rec["hbm_bytes_per_step"] > 0
         assert abs(rec["fetch_bytes_per_step"] + rec["write_bytes_per_step"] - rec["hbm_bytes_per_step"]) <= 0.01 * rec["hbm_bytes_per_step"]
         assert os.path.exists(os.path.join(ROOT, rec["source"]))
