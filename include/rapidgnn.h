@@ -104,7 +104,9 @@ typedef struct rg_cache rg_cache;
  * passes tuned for graphs of 10^7 nodes and more (default: chosen from
  * n_nodes); RAPIDGNN_BYTE_MAPS=1 / 0 forces / forbids the byte form of the
  * reached map (never used together with those passes).  The result is the
- * same in every case.
+ * same in every case.  The maps are drawn from a pool of blocks known to be
+ * all-zero and handed back to it after the build has cleared what it touched;
+ * RAPIDGNN_CHECK_ZERO_MAPS=1 makes every build verify that on the device first.
  */
 rg_status rg_build_schedule(const rg_graph *g, const int32_t *train_nodes, uint64_t T,
                             uint32_t batch_size, const uint32_t *fanout, uint32_t L,

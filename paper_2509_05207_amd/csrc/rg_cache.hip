@@ -115,28 +115,36 @@ __device__ __forceinline__ uint64_t classify_node(uint32_t fv, uint8_t local, co
     return fv == st.t ? 1ull : 0ull;
 }
 
-constexpr int SEL_PER_THREAD = 8;
+constexpr int SEL_PER_THREAD = 8;         // runs of eight consecutive nodes (sixteen halves the scan of the per-workgroup totals on 10^8 nodes but costs the emit pass as much)
 constexpr int SEL_TILE = TOPK_THREADS * SEL_PER_THREAD;
 
 // The eight consecutive nodes of a thread, classified.  ALIGNED8 (is_local 8-byte aligned; freq always is, and a
 // thread's first node is a multiple of eight): two 16-byte loads and one 8-byte load when all eight exist.
 template <bool ALIGNED8>
 __device__ __forceinline__ void classify_eight(const uint32_t *__restrict__ freq, const uint8_t *__restrict__ is_local, int64_t first, int64_t n,
-                                               const SelectState &st, uint64_t c[SEL_PER_THREAD])
+                                               const SelectState &st, uint64_t *c /* [8] */)
 {
-    if (ALIGNED8 && first + SEL_PER_THREAD <= n) {
+    if (ALIGNED8 && first + 8 <= n) {
         const uint4 a = *reinterpret_cast<const uint4 *>(freq + first), b = *reinterpret_cast<const uint4 *>(freq + first + 4);
         const uint64_t loc = *reinterpret_cast<const uint64_t *>(is_local + first);
-        const uint32_t fv[SEL_PER_THREAD] = {a.x, a.y, a.z, a.w, b.x, b.y, b.z, b.w};
+        const uint32_t fv[8] = {a.x, a.y, a.z, a.w, b.x, b.y, b.z, b.w};
 #pragma unroll
-        for (int k = 0; k < SEL_PER_THREAD; ++k) c[k] = classify_node(fv[k], (uint8_t)(loc >> (8 * k)), st);
+        for (int k = 0; k < 8; ++k) c[k] = classify_node(fv[k], (uint8_t)(loc >> (8 * k)), st);
         return;
     }
 #pragma unroll
-    for (int k = 0; k < SEL_PER_THREAD; ++k) {
+    for (int k = 0; k < 8; ++k) {
         const int64_t v = first + k;
         c[k] = v < n ? classify_node(freq[v], is_local[v], st) : 0;
     }
+}
+// The SEL_PER_THREAD consecutive nodes of a thread.
+template <bool ALIGNED8>
+__device__ __forceinline__ void classify_mine(const uint32_t *__restrict__ freq, const uint8_t *__restrict__ is_local, int64_t first, int64_t n,
+                                              const SelectState &st, uint64_t (&c)[SEL_PER_THREAD])
+{
+#pragma unroll
+    for (int h = 0; h < SEL_PER_THREAD / 8; ++h) classify_eight<ALIGNED8>(freq, is_local, first + 8 * h, n, st, c + 8 * h);
 }
 
 __device__ __forceinline__ uint64_t block_exclusive_scan_u64(uint64_t x, uint64_t *total, uint64_t *lds)
@@ -168,7 +176,7 @@ __global__ void __launch_bounds__(TOPK_THREADS) select_block_totals(const uint32
     const SelectState st = *stp;
     const int64_t first = (int64_t)blockIdx.x * SEL_TILE + (int64_t)threadIdx.x * SEL_PER_THREAD;
     uint64_t c[SEL_PER_THREAD];
-    classify_eight<ALIGNED8>(freq, is_local, first, n, st, c);
+    classify_mine<ALIGNED8>(freq, is_local, first, n, st, c);
     uint64_t s = 0;
 #pragma unroll
     for (int k = 0; k < SEL_PER_THREAD; ++k) s += c[k];
@@ -207,7 +215,7 @@ __global__ void __launch_bounds__(TOPK_THREADS) select_emit_kernel(const uint32_
     const SelectState st = *stp;
     const int64_t first = (int64_t)blockIdx.x * SEL_TILE + (int64_t)threadIdx.x * SEL_PER_THREAD;
     uint64_t c[SEL_PER_THREAD];
-    classify_eight<ALIGNED8>(freq, is_local, first, n, st, c);
+    classify_mine<ALIGNED8>(freq, is_local, first, n, st, c);
     uint64_t s = 0;
 #pragma unroll
     for (int k = 0; k < SEL_PER_THREAD; ++k) s += c[k];
@@ -227,8 +235,9 @@ __global__ void __launch_bounds__(TOPK_THREADS) select_emit_kernel(const uint32_
         run += c[k];
     }
     if (first + SEL_PER_THREAD <= n) {                     // slot_of is the library's own array: 16-byte aligned at a multiple of eight
-        *reinterpret_cast<int4 *>(slot_of + first) = make_int4(slots[0], slots[1], slots[2], slots[3]);
-        *reinterpret_cast<int4 *>(slot_of + first + 4) = make_int4(slots[4], slots[5], slots[6], slots[7]);
+#pragma unroll
+        for (int q = 0; q < SEL_PER_THREAD / 4; ++q)
+            *reinterpret_cast<int4 *>(slot_of + first + 4 * q) = make_int4(slots[4 * q], slots[4 * q + 1], slots[4 * q + 2], slots[4 * q + 3]);
     } else {
 #pragma unroll
         for (int k = 0; k < SEL_PER_THREAD; ++k)

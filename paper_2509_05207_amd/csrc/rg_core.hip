@@ -34,6 +34,7 @@ namespace {
 struct BlockCache {
     std::mutex mu;
     std::multimap<std::pair<int, uint64_t>, void *> free_blocks;      // (device, bytes) -> block
+    std::multimap<std::pair<int, uint64_t>, void *> zero_blocks;      // the same, blocks whose every byte is known to be zero
     std::map<void *, std::pair<int, uint64_t>> live;                  // blocks handed out
     uint64_t cached_bytes = 0;
 
@@ -44,20 +45,31 @@ struct BlockCache {
         return (bytes + (1ull << 20) - 1) >> 20 << 20;
     }
 
-    void *take(uint64_t bytes, hipError_t *err)
+    // zeroed: prefer a block that is known to hold nothing but zero bytes (*was_zero says whether one was found;
+    // otherwise the caller clears what it got).  A request that finds no ordinary block takes a zeroed one.
+    void *take(uint64_t bytes, hipError_t *err, bool zeroed = false, bool *was_zero = nullptr)
     {
         int dev = 0;
         (void)hipGetDevice(&dev);
         const uint64_t want = round_up(bytes);
+        if (was_zero) *was_zero = false;
         {
             std::lock_guard<std::mutex> lk(mu);
-            auto it = free_blocks.lower_bound({dev, want});
-            if (it != free_blocks.end() && it->first.first == dev && it->first.second <= want + want / 8 + (1ull << 20)) {
+            auto fits = [&](std::multimap<std::pair<int, uint64_t>, void *> &pool) -> void * {
+                auto it = pool.lower_bound({dev, want});
+                if (it == pool.end() || it->first.first != dev || it->first.second > want + want / 8 + (1ull << 20)) return nullptr;
                 void *p = it->second;
                 live[p] = it->first;
                 cached_bytes -= it->first.second;
-                free_blocks.erase(it);
+                pool.erase(it);
                 return p;
+            };
+            if (zeroed) {
+                if (void *p = fits(zero_blocks)) { if (was_zero) *was_zero = true; return p; }
+                if (void *p = fits(free_blocks)) return p;
+            } else {
+                if (void *p = fits(free_blocks)) return p;
+                if (void *p = fits(zero_blocks)) return p;
             }
         }
         void *p = nullptr;
@@ -74,12 +86,20 @@ struct BlockCache {
         return p;
     }
 
-    void give(void *p)
+    uint64_t size_of(void *p)
+    {
+        std::lock_guard<std::mutex> lk(mu);
+        auto it = live.find(p);
+        return it == live.end() ? 0 : it->second.second;
+    }
+
+    // all_zero: the caller vouches that every byte of the block is zero and that nothing will write it any more
+    void give(void *p, bool all_zero = false)
     {
         std::lock_guard<std::mutex> lk(mu);
         auto it = live.find(p);
         if (it == live.end()) { (void)hipFree(p); return; }
-        free_blocks.insert({it->second, p});
+        (all_zero ? zero_blocks : free_blocks).insert({it->second, p});
         cached_bytes += it->second.second;
         live.erase(it);
     }
@@ -88,7 +108,9 @@ struct BlockCache {
     {
         std::lock_guard<std::mutex> lk(mu);
         for (auto &kv : free_blocks) (void)hipFree(kv.second);
+        for (auto &kv : zero_blocks) (void)hipFree(kv.second);
         free_blocks.clear();
+        zero_blocks.clear();
         cached_bytes = 0;
     }
 };
@@ -182,6 +204,43 @@ rg_status Arena::dev(uint64_t bytes, void **out)
     in_use_ += want;
     *out = p;
     return RG_OK;
+}
+
+rg_status Arena::dev_zeroed(uint64_t bytes, void **out, hipStream_t st)
+{
+    if (custom_) {
+        RG_TRY(dev(bytes, out));
+        RG_HIP(hipMemsetAsync(*out, 0, bytes ? bytes : 256, st));
+        return RG_OK;
+    }
+    const uint64_t want = bytes ? bytes : 256;
+    hipError_t e = hipSuccess;
+    bool was_zero = false;
+    void *p = g_blocks.take(want, &e, true, &was_zero);
+    if (!p) {
+        set_error("hipMalloc(%llu) failed: %s", (unsigned long long)want, hipGetErrorString(e));
+        return RG_ENOMEM;
+    }
+    items_.push_back({p, 1, want});
+    in_use_ += want;
+    *out = p;
+    if (!was_zero) RG_HIP(hipMemsetAsync(p, 0, g_blocks.size_of(p), st));      // the whole block: it may come back as all-zero for a larger request
+    return RG_OK;
+}
+
+void Arena::free_zeroed(void *p)
+{
+    if (!p) return;
+    for (size_t i = 0; i < items_.size(); ++i) {
+        if (items_[i].p == p) {
+            if (custom_) a_.free(p, items_[i].kind, a_.ctx);
+            else g_blocks.give(p, true);
+            in_use_ -= items_[i].bytes;
+            items_[i] = items_.back();
+            items_.pop_back();
+            return;
+        }
+    }
 }
 
 rg_status Arena::pinned(uint64_t bytes, void **out)

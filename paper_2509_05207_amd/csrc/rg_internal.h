@@ -54,6 +54,12 @@ class Arena {
     rg_status dev(uint64_t bytes, void **out);
     rg_status pinned(uint64_t bytes, void **out);
     template <typename T> rg_status dev_n(uint64_t n, T **out) { return dev(n * sizeof(T), (void **)out); }
+    // Device memory that holds zero bytes: a block that an earlier call handed back as all-zero (free_zeroed), or a
+    // fresh one cleared on `st`.  The big per-batch bitmaps of a schedule build come and go this way, so that an
+    // epoch clears only the parts the epoch before it touched instead of gigabytes.
+    rg_status dev_zeroed(uint64_t bytes, void **out, hipStream_t st);
+    // Hands a buffer back as all-zero: every byte is zero and the work that wrote it has completed.
+    void free_zeroed(void *p);
     void free_one(void *p);     // early release of a single buffer
     void release_all();
     uint64_t bytes_in_use() const { return in_use_; }

@@ -57,42 +57,42 @@ struct NodeRecs {
     uint64_t *state;      // S_v = combine(combine(S_{e,i}, hop + 1), v)
 };
 
-__global__ void node_records_kernel(const int64_t *__restrict__ indptr, const int32_t *__restrict__ frontier, int64_t n,
-                                    const int64_t *__restrict__ batch_off, uint32_t n_batches, const uint64_t *__restrict__ batch_seed,
-                                    uint32_t hop, uint32_t fanout, NodeRecs r, int32_t *__restrict__ cnt, int32_t *__restrict__ tiles, int64_t n_nodes)
-{
-    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (i >= n) return;
-    const int32_t v = frontier[i];
-    const bool known = v >= 0 && (int64_t)v < n_nodes;      // (a seed out of range is refused by the host at the hop's readback; until then it has no row)
-    const int64_t b0 = known ? indptr[v] : 0;
-    const int64_t deg = known ? indptr[v + 1] - b0 : 0;
-    const uint32_t b = batch_of(batch_off, n_batches, i);
-    r.row_begin[i] = b0;
-    r.deg[i] = (int32_t)deg;
-    r.batch[i] = b;
-    r.state[i] = combine(combine(batch_seed[b], (uint64_t)hop + 1u), (uint64_t)(uint32_t)v);
-    cnt[i] = (int32_t)(deg < (int64_t)fanout ? deg : (int64_t)fanout);
-    tiles[i] = (int32_t)tiles_of(deg);
-}
-
-// total[0] += sum of deg[0..n): what the hop will read of the adjacency, in IDs; total[1] += the part of it in rows of
-// up to BIG_ROW IDs (the rows that are sampled inside the groups of nodes, not as tiles)
-__global__ void __launch_bounds__(256) sum_degrees_kernel(const int32_t *__restrict__ deg, int64_t n, unsigned long long *__restrict__ total)
+// Also adds up, over the frontier, what the hop will read of the adjacency: the sum of the degrees (in IDs) and the
+// part of it in rows of up to BIG_ROW IDs (the rows that are sampled inside the groups of nodes, not as tiles).  The
+// sums are spread over DEG_SUM_SLOTS pairs of counters, total[2 * slot] and total[2 * slot + 1], which the host adds up:
+// thousands of workgroups adding to one address would queue up behind each other.
+constexpr int DEG_SUM_SLOTS = 64;
+__global__ void __launch_bounds__(256) node_records_kernel(const int64_t *__restrict__ indptr, const int32_t *__restrict__ frontier, int64_t n,
+                                                           const int64_t *__restrict__ batch_off, uint32_t n_batches, const uint64_t *__restrict__ batch_seed,
+                                                           uint32_t hop, uint32_t fanout, NodeRecs r, int32_t *__restrict__ cnt, int32_t *__restrict__ tiles,
+                                                           int64_t n_nodes, unsigned long long *__restrict__ total)
 {
     __shared__ unsigned long long part[2][4];
     unsigned long long acc = 0, acc_groups = 0;
+    // (a bounded grid, each workgroup striding over the frontier: the sums cost two atomics per workgroup)
     for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (int64_t)gridDim.x * blockDim.x) {
-        const unsigned long long d = (unsigned long long)(uint32_t)deg[i];
-        acc += d;
-        if (d <= (unsigned long long)BIG_ROW) acc_groups += d;
+        const int32_t v = frontier[i];
+        const bool known = v >= 0 && (int64_t)v < n_nodes;      // (a seed out of range is refused by the host at the hop's readback; until then it has no row)
+        const int64_t b0 = known ? indptr[v] : 0;
+        const int64_t deg = known ? indptr[v + 1] - b0 : 0;
+        const uint32_t b = batch_of(batch_off, n_batches, i);
+        r.row_begin[i] = b0;
+        r.deg[i] = (int32_t)deg;
+        r.batch[i] = b;
+        r.state[i] = combine(combine(batch_seed[b], (uint64_t)hop + 1u), (uint64_t)(uint32_t)v);
+        cnt[i] = (int32_t)(deg < (int64_t)fanout ? deg : (int64_t)fanout);
+        tiles[i] = (int32_t)tiles_of(deg);
+        acc += (unsigned long long)deg;
+        if (deg <= (int64_t)BIG_ROW) acc_groups += (unsigned long long)deg;
     }
     for (int o = 32; o > 0; o >>= 1) { acc += __shfl_down(acc, o, 64); acc_groups += __shfl_down(acc_groups, o, 64); }
     if ((threadIdx.x & 63) == 0) { part[0][threadIdx.x >> 6] = acc; part[1][threadIdx.x >> 6] = acc_groups; }
     __syncthreads();
     if (threadIdx.x == 0) {
-        atomicAdd(total, part[0][0] + part[0][1] + part[0][2] + part[0][3]);
-        atomicAdd(total + 1, part[1][0] + part[1][1] + part[1][2] + part[1][3]);
+        const unsigned long long a = part[0][0] + part[0][1] + part[0][2] + part[0][3], g = part[1][0] + part[1][1] + part[1][2] + part[1][3];
+        const unsigned slot = blockIdx.x % DEG_SUM_SLOTS;
+        if (a) atomicAdd(total + 2 * slot, a);
+        if (g) atomicAdd(total + 2 * slot + 1, g);
     }
 }
 
@@ -588,22 +588,26 @@ struct TileRecs {
     int32_t *len;
     uint64_t *state;
 };
+// One thread per tile job: its node is the frontier position i with tile_off[i] <= j < tile_off[i + 1].
 __global__ void tile_records_kernel(const int64_t *__restrict__ tile_off, const int64_t *__restrict__ row_begin, const int32_t *__restrict__ deg,
-                                    const uint64_t *__restrict__ state, int64_t n, TileRecs r)
+                                    const uint64_t *__restrict__ state, int64_t n, int64_t n_tiles, TileRecs r)
 {
-    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (i >= n) return;
+    const int64_t j = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (j >= n_tiles) return;
+    int64_t lo = 0, hi = n;                    // invariant: tile_off[lo] <= j < tile_off[hi]   (tile_off[0] = 0, tile_off[n] = n_tiles)
+    while (hi - lo > 1) {
+        const int64_t mid = (lo + hi) >> 1;
+        if (tile_off[mid] <= j) lo = mid; else hi = mid;
+    }
+    const int64_t i = lo;
     const int64_t d = deg[i];
     const int64_t T = tiles_of(d);            // the count tile_off was summed from
-    if (T == 0) return;
-    const int64_t first = tile_off[i], b0 = row_begin[i];
-    for (int64_t t = 0; t < T; ++t) {
-        const int64_t first_pos = t * d / T, last_pos = (t + 1) * d / T;
-        r.node[first + t] = i;
-        r.begin[first + t] = b0 + first_pos;
-        r.len[first + t] = (int32_t)(last_pos - first_pos);
-        r.state[first + t] = state[i];
-    }
+    const int64_t t = j - tile_off[i];
+    const int64_t first_pos = t * d / T, last_pos = (t + 1) * d / T;
+    r.node[j] = i;
+    r.begin[j] = row_begin[i] + first_pos;
+    r.len[j] = (int32_t)(last_pos - first_pos);
+    r.state[j] = state[i];
 }
 
 struct HopArgs {
@@ -814,30 +818,28 @@ rg_status sample_hop(const rg_graph *g, HopData &cur, uint32_t beta, const uint6
     RG_TRY(tmp.dev_n<uint32_t>((uint64_t)n_cur, &rec.batch));
     RG_TRY(tmp.dev_n<uint64_t>((uint64_t)n_cur, &rec.state));
     RG_TRY(keep.dev_n<int64_t>((uint64_t)n_cur + 1, &cur.samp_off));
+    unsigned long long sums[2] = {0, 0}, *sum_deg_dev = nullptr;       // IDs in all rows of the frontier, IDs in its rows outside tiles
+    unsigned long long sum_parts[2 * DEG_SUM_SLOTS];
+    RG_TRY(tmp.dev_n<unsigned long long>(2 * DEG_SUM_SLOTS, &sum_deg_dev));
+    RG_HIP(hipMemsetAsync(sum_deg_dev, 0, sizeof(sum_parts), st));
     {
         ScopedTimer tm(KG_OFFSETS, st);
-        hipLaunchKernelGGL(node_records_kernel, dim3((unsigned)((n_cur + 255) / 256)), dim3(256), 0, st, g->indptr, cur.ids, n_cur, cur.off_dev, beta,
-                           batch_seed, hop, fanout, rec, cnt, tiles, (int64_t)g->n_nodes);
+        hipLaunchKernelGGL(node_records_kernel, dim3((unsigned)std::max<int64_t>(1, std::min<int64_t>((n_cur + 255) / 256, (int64_t)n_cu * 64))), dim3(256), 0, st, g->indptr, cur.ids, n_cur, cur.off_dev, beta,
+                           batch_seed, hop, fanout, rec, cnt, tiles, (int64_t)g->n_nodes, sum_deg_dev);
         RG_TRY(scan_i32_to_i64(cnt, cur.samp_off, n_cur, tmp, st));
         RG_TRY(scan_i32_to_i64(tiles, tile_off, n_cur, tmp, st));
     }
     int64_t n_tiles = 0;
-    unsigned long long sums[2] = {0, 0}, *sum_deg_dev = nullptr;       // IDs in all rows of the frontier, IDs in its rows outside tiles
     // (the byte-marking kernels exist for fan-outs up to 192: the two smaller candidate buffers)
     const bool can_bytes = maps.bytes_allowed && (sampler == RG_SAMPLER_POSITIONS || fanout + 64 <= 256);
     {
-        RG_TRY(tmp.dev_n<unsigned long long>(2, &sum_deg_dev));
-        RG_HIP(hipMemsetAsync(sum_deg_dev, 0, 2 * sizeof(unsigned long long), st));
-        if (n_cur > 0)
-            hipLaunchKernelGGL(sum_degrees_kernel, dim3((unsigned)std::min<int64_t>((n_cur + 255) / 256, 1024)), dim3(256), 0, st, rec.deg, n_cur, sum_deg_dev);
-    }
-    {
         Readback rb(st);
-        if (sum_deg_dev) RG_TRY(rb.add(sums, sum_deg_dev, sizeof(sums)));
+        RG_TRY(rb.add(sum_parts, sum_deg_dev, sizeof(sum_parts)));
         RG_TRY(rb.add(&cur.n_samples, cur.samp_off + n_cur, sizeof(int64_t)));
         RG_TRY(rb.add(&n_tiles, tile_off + n_cur, sizeof(int64_t)));
         if (also_read_dev) RG_TRY(rb.add(also_read_host, also_read_dev, sizeof(unsigned long long)));     // a value the caller wants behind the same wait
         RG_TRY(rb.wait());
+        for (int k = 0; k < DEG_SUM_SLOTS; ++k) { sums[0] += sum_parts[2 * k]; sums[1] += sum_parts[2 * k + 1]; }
         if (also_read_dev && *also_read_host != 0) return RG_OK;        // the caller refuses the build: nothing more to launch
     }
     // Which form of the reached map this hop marks.  A byte store is several times cheaper than an atomic OR, but the
@@ -849,8 +851,7 @@ rg_status sample_hop(const rg_graph *g, HopData &cur, uint32_t beta, const uint6
     const bool use_bytes = can_bytes && (prefer_bytes >= 0 ? prefer_bytes != 0 : (unsigned long long)cur.n_samples * 14ull >= sum_deg);
     if (use_bytes && !maps.bytes) {
         const uint64_t map_bytes = maps.words_per_batch * 32 * (uint64_t)beta;
-        RG_TRY(tmp.dev_n<uint8_t>(map_bytes, &maps.bytes));
-        RG_HIP(hipMemsetAsync(maps.bytes, 0, map_bytes, st));
+        RG_TRY(tmp.dev_zeroed(map_bytes, (void **)&maps.bytes, st));       // (the caller hands it back as all-zero: the frontier passes clear what a hop marks)
     }
     *marked_bytes = use_bytes;
     // A hop that marks many times more IDs than the maps have groups reaches nearly every group: the per-mark flag
@@ -887,7 +888,7 @@ rg_status sample_hop(const rg_graph *g, HopData &cur, uint32_t beta, const uint6
     RG_TRY(tmp.dev_n<uint64_t>((uint64_t)n_tiles, &tile.state));
     if (n_tiles > 0) {
         ScopedTimer tm(KG_OFFSETS, st);
-        hipLaunchKernelGGL(tile_records_kernel, dim3((unsigned)((n_cur + 255) / 256)), dim3(256), 0, st, tile_off, rec.row_begin, rec.deg, rec.state, n_cur, tile);
+        hipLaunchKernelGGL(tile_records_kernel, dim3((unsigned)((n_tiles + 255) / 256)), dim3(256), 0, st, tile_off, rec.row_begin, rec.deg, rec.state, n_cur, n_tiles, tile);
     }
 
     if (fanout > 0 && n_cur > 0) {

@@ -120,14 +120,16 @@ __global__ void check_train_kernel(const int32_t *__restrict__ train, uint64_t T
     if (m != 0ull && (threadIdx.x & 63) == 0) atomicAdd(n_bad, (unsigned long long)__popcll(m));
 }
 
-__global__ void mark_seeds_kernel(const int32_t *__restrict__ seeds, uint64_t T, uint32_t batch_size, uint32_t *__restrict__ seen, uint64_t words_per_batch,
-                                  int64_t n_nodes)
+__global__ void mark_seeds_kernel(const int32_t *__restrict__ seeds, uint64_t T, uint32_t batch_size, uint32_t *__restrict__ seen,
+                                  uint8_t *__restrict__ seen_flags, uint64_t words_per_batch, int64_t n_nodes)
 {
     const uint64_t t = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (t >= T) return;
     const uint32_t v = (uint32_t)seeds[t];
     if ((int64_t)v >= n_nodes) return;          // (refused by the host as soon as it has read check_train_kernel's count)
-    atomicOr(&seen[(t / batch_size) * words_per_batch + (v >> 5)], 1u << (v & 31));
+    const uint64_t word = (t / batch_size) * words_per_batch + (v >> 5);
+    atomicOr(&seen[word], 1u << (v & 31));
+    seen_flags[word >> 3] = 1;
 }
 
 // ---------------------------------------------------------------- a6 (first half): freq(v) of the epoch as column sums
@@ -252,7 +254,7 @@ __global__ void copy_prefix_kernel(const int32_t *__restrict__ cur, const int64_
 // the reached IDs to `seen` and clears `reached` for the next hop.
 template <bool BYTES>
 __global__ void __launch_bounds__(FR_THREADS) fresh_emit_kernel(void *__restrict__ reached, uint8_t *__restrict__ flags, uint32_t *__restrict__ seen,
-                                                                uint64_t words_per_batch, uint32_t chunks, const int64_t *__restrict__ fresh_scan,
+                                                                uint8_t *__restrict__ seen_flags, uint64_t words_per_batch, uint32_t chunks, const int64_t *__restrict__ fresh_scan,
                                                                 const int64_t *__restrict__ cur_off, int32_t *__restrict__ next)
 {
     __shared__ int wave_tot[FR_THREADS / 64];
@@ -275,6 +277,7 @@ __global__ void __launch_bounds__(FR_THREADS) fresh_emit_kernel(void *__restrict
             if (n) {
                 *reinterpret_cast<uint4 *>(seen + at) = make_uint4(s0.x | r[0], s0.y | r[1], s0.z | r[2], s0.w | r[3]);
                 *reinterpret_cast<uint4 *>(seen + at + 4) = make_uint4(s1.x | r[4], s1.y | r[5], s1.z | r[6], s1.w | r[7]);
+                seen_flags[at >> 3] = 1;
             }
             clear_reached_group<BYTES>(reached, at);
             flags[at >> 3] = 0;
@@ -309,10 +312,15 @@ __global__ void __launch_bounds__(FR_THREADS) fresh_emit_kernel(void *__restrict
 // The same two passes for graphs so large that almost every group of a batch's bitmap is untouched (10^8 nodes:
 // a batch reaches a few 10^4 IDs out of 3.5 M words).  A thread owns eight consecutive groups, i.e. one 8-byte
 // load of flags; a cell is 16,384 words, so the grid is eight times smaller and an untouched cell costs one
-// flag load per thread.  Flagged groups are read twice (count, then emit): they are few.
+// flag load per thread.  The few flagged groups of a wave's 512 are first listed (in ascending order, through
+// LDS) and then dealt out one per lane, so that their loads -- two scattered 32-byte reads each -- are all in
+// flight at once instead of one after another in the lane that happens to own them.  Flagged groups are read
+// twice (count, then emit): they are few.
 constexpr int FRS_GROUPS = 8;                                            // groups per thread
 constexpr int FRS_WORDS_PER_THREAD = FR_WORDS_PER_THREAD * FRS_GROUPS;   // 64
 constexpr int FRS_CHUNK_WORDS = FR_THREADS * FRS_WORDS_PER_THREAD;       // 16384; words_per_batch is a multiple of 64
+constexpr int FRS_WAVE_GROUPS = 64 * FRS_GROUPS;                         // 512 groups per wave
+constexpr int FRS_ROUNDS = FRS_GROUPS;                                   // a lane takes at most eight listed groups
 
 __device__ __forceinline__ int fresh_in_group(const uint32_t *__restrict__ reached, const uint32_t *__restrict__ seen, uint64_t at, uint32_t (&w)[8])
 {
@@ -326,89 +334,160 @@ __device__ __forceinline__ int fresh_in_group(const uint32_t *__restrict__ reach
     return n;
 }
 
+// Lists the wave's flagged groups in ascending order: list[0 .. total) holds their indices within the wave's 512
+// (lane * 8 + g).  fl: this lane's eight flag bytes.  Returns total (wave-uniform).  Ends with a block barrier.
+__device__ __forceinline__ int list_flagged_groups(unsigned long long fl, uint16_t *list /* this wave's [FRS_WAVE_GROUPS] */)
+{
+    const int lane = threadIdx.x & 63;
+    // one bit per flagged group of this lane: a byte is non-zero iff, after OR-folding it onto its lowest bit, that bit is set
+    unsigned long long x = fl;
+    x |= x >> 4; x |= x >> 2; x |= x >> 1;
+    x &= 0x0101010101010101ull;
+    const int nf = __popcll(x);
+    int incl = nf;
+    for (int d = 1; d < 64; d <<= 1) {
+        const int y = __shfl_up(incl, d, 64);
+        if (lane >= d) incl += y;
+    }
+    const int total = __shfl(incl, 63, 64);
+    int at = incl - nf;
+#pragma unroll
+    for (int g = 0; g < FRS_GROUPS; ++g)
+        if ((x >> (8 * g)) & 1ull) list[at++] = (uint16_t)(lane * FRS_GROUPS + g);
+    __syncthreads();
+    return total;
+}
+
 __global__ void __launch_bounds__(FR_THREADS) fresh_count_sparse_kernel(const uint32_t *__restrict__ reached, const uint8_t *__restrict__ flags,
                                                                         const uint32_t *__restrict__ seen, uint64_t words_per_batch,
                                                                         uint32_t chunks, int32_t *__restrict__ cnt)
 {
+    __shared__ uint16_t lists[FR_THREADS / 64][FRS_WAVE_GROUPS];
     __shared__ int red[FR_THREADS / 64];
     const uint32_t c = blockIdx.x, b = blockIdx.y;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const uint64_t w0 = (uint64_t)c * FRS_CHUNK_WORDS + (uint64_t)threadIdx.x * FRS_WORDS_PER_THREAD;
+    const uint64_t at = (uint64_t)b * words_per_batch + w0;
+    const unsigned long long fl = w0 < words_per_batch ? *reinterpret_cast<const unsigned long long *>(flags + (at >> 3)) : 0ull;
+    const int total = list_flagged_groups(fl, lists[wave]);
+    const uint64_t wave_at = (uint64_t)b * words_per_batch + (uint64_t)c * FRS_CHUNK_WORDS + (uint64_t)wave * (FRS_WAVE_GROUPS * FR_WORDS_PER_THREAD);
     int n = 0;
-    if (w0 < words_per_batch) {
-        const uint64_t at = (uint64_t)b * words_per_batch + w0;
-        const unsigned long long fl = *reinterpret_cast<const unsigned long long *>(flags + (at >> 3));
-        if (fl != 0ull) {
-            for (int g = 0; g < FRS_GROUPS; ++g)
-                if ((fl >> (8 * g)) & 0xFFull) {
-                    uint32_t w[8];
-                    n += fresh_in_group(reached, seen, at + 8 * g, w);
-                }
-        }
+    for (int i = lane; i < total; i += 64) {
+        uint32_t w[8];
+        n += fresh_in_group(reached, seen, wave_at + (uint64_t)lists[wave][i] * FR_WORDS_PER_THREAD, w);
     }
     for (int o = 32; o > 0; o >>= 1) n += __shfl_down(n, o, 64);
-    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = n;
+    if (lane == 0) red[wave] = n;
     __syncthreads();
     if (threadIdx.x == 0) cnt[(uint64_t)b * chunks + c] = red[0] + red[1] + red[2] + red[3];
 }
 
 __global__ void __launch_bounds__(FR_THREADS) fresh_emit_sparse_kernel(uint32_t *__restrict__ reached, uint8_t *__restrict__ flags,
-                                                                       uint32_t *__restrict__ seen, uint64_t words_per_batch, uint32_t chunks,
+                                                                       uint32_t *__restrict__ seen, uint8_t *__restrict__ seen_flags,
+                                                                       uint64_t words_per_batch, uint32_t chunks,
                                                                        const int64_t *__restrict__ fresh_scan, const int64_t *__restrict__ cur_off,
                                                                        int32_t *__restrict__ next)
 {
+    __shared__ uint16_t lists[FR_THREADS / 64][FRS_WAVE_GROUPS];
     __shared__ int wave_tot[FR_THREADS / 64];
     const uint32_t c = blockIdx.x, b = blockIdx.y;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int64_t scan_here = fresh_scan[(uint64_t)b * chunks + c];
     const bool any_fresh = fresh_scan[(uint64_t)b * chunks + c + 1] != scan_here;      // block-uniform
     const uint64_t w0 = (uint64_t)c * FRS_CHUNK_WORDS + (uint64_t)threadIdx.x * FRS_WORDS_PER_THREAD;
-    const bool mine = w0 < words_per_batch;
     const uint64_t at = (uint64_t)b * words_per_batch + w0;
-    const unsigned long long fl = mine ? *reinterpret_cast<const unsigned long long *>(flags + (at >> 3)) : 0ull;
-    int n = 0;
-    if (any_fresh && fl != 0ull) {
-        for (int g = 0; g < FRS_GROUPS; ++g)
-            if ((fl >> (8 * g)) & 0xFFull) {
-                uint32_t w[8];
-                n += fresh_in_group(reached, seen, at + 8 * g, w);
-            }
-    }
-    int before = 0;
-    if (any_fresh) {                          // exclusive scan of n over the block
-        const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-        int incl = n;
-        for (int d = 1; d < 64; d <<= 1) {
-            const int y = __shfl_up(incl, d, 64);
-            if (lane >= d) incl += y;
-        }
-        if (lane == 63) wave_tot[wave] = incl;
-        __syncthreads();
-        before = incl - n;
-        for (int k = 0; k < wave; ++k) before += wave_tot[k];
-    }
-    if (fl == 0ull) return;
-    int64_t pos = cur_off[b + 1] + scan_here + before;
-    for (int g = 0; g < FRS_GROUPS; ++g) {
-        if (!((fl >> (8 * g)) & 0xFFull)) continue;
-        const uint64_t ag = at + 8 * g;
-        uint32_t w[8];
-        const int ng = fresh_in_group(reached, seen, ag, w);
-        if (ng) {
+    const unsigned long long fl = w0 < words_per_batch ? *reinterpret_cast<const unsigned long long *>(flags + (at >> 3)) : 0ull;
+    const int total = list_flagged_groups(fl, lists[wave]);
+    const uint64_t wave_w0 = (uint64_t)c * FRS_CHUNK_WORDS + (uint64_t)wave * (FRS_WAVE_GROUPS * FR_WORDS_PER_THREAD);   // first word of the wave's groups within the batch
+    const uint64_t wave_at = (uint64_t)b * words_per_batch + wave_w0;
+    // first round of loads: how many fresh IDs each listed group holds, and from that where each group's IDs go
+    int before[FRS_ROUNDS];            // fresh IDs of the wave's listed groups in front of this lane's group of round r
+    int carry = 0;
+    if (any_fresh) {
 #pragma unroll
-            for (int k = 0; k < 8; ++k) {
-                uint32_t x = w[k];
-                const uint32_t id0 = (uint32_t)((w0 + 8 * g + k) << 5);
-                while (x) {
-                    const int bit = __ffs((int)x) - 1;
-                    x &= x - 1;
-                    next[pos++] = (int32_t)(id0 + bit);
+        for (int r = 0; r < FRS_ROUNDS; ++r) {
+            before[r] = 0;
+            if (r * 64 < total) {                                       // wave-uniform
+                const int i = r * 64 + lane;
+                int n = 0;
+                if (i < total) {
+                    uint32_t w[8];
+                    n = fresh_in_group(reached, seen, wave_at + (uint64_t)lists[wave][i] * FR_WORDS_PER_THREAD, w);
                 }
-                seen[ag + k] |= w[k];
+                int incl = n;
+                for (int d = 1; d < 64; d <<= 1) {
+                    const int y = __shfl_up(incl, d, 64);
+                    if (lane >= d) incl += y;
+                }
+                before[r] = carry + incl - n;
+                carry += __shfl(incl, 63, 64);
             }
         }
-        *reinterpret_cast<uint4 *>(reached + ag) = make_uint4(0, 0, 0, 0);
-        *reinterpret_cast<uint4 *>(reached + ag + 4) = make_uint4(0, 0, 0, 0);
     }
-    *reinterpret_cast<unsigned long long *>(flags + (at >> 3)) = 0ull;
+    if (lane == 0) wave_tot[wave] = carry;
+    __syncthreads();
+    int64_t base = cur_off[b + 1] + scan_here;
+    for (int k = 0; k < wave; ++k) base += wave_tot[k];
+    // second round: write the fresh IDs in ascending order, add them to `seen`, clear `reached`
+#pragma unroll
+    for (int r = 0; r < FRS_ROUNDS; ++r) {
+        const int i = r * 64 + lane;
+        if (i < total) {
+            const uint32_t grp = lists[wave][i];
+            const uint64_t ag = wave_at + (uint64_t)grp * FR_WORDS_PER_THREAD;
+            if (any_fresh) {
+                uint32_t w[8];
+                const int ng = fresh_in_group(reached, seen, ag, w);
+                if (ng) {
+                    int64_t pos = base + before[r];
+#pragma unroll
+                    for (int k = 0; k < 8; ++k) {
+                        uint32_t x = w[k];
+                        if (x) {
+                            const uint32_t id0 = (uint32_t)((wave_w0 + (uint64_t)grp * FR_WORDS_PER_THREAD + k) << 5);
+                            seen[ag + k] |= x;
+                            while (x) {
+                                const int bit = __ffs((int)x) - 1;
+                                x &= x - 1;
+                                next[pos++] = (int32_t)(id0 + bit);
+                            }
+                        }
+                    }
+                    seen_flags[ag >> 3] = 1;
+                }
+            }
+            *reinterpret_cast<uint4 *>(reached + ag) = make_uint4(0, 0, 0, 0);
+            *reinterpret_cast<uint4 *>(reached + ag + 4) = make_uint4(0, 0, 0, 0);
+        }
+    }
+    if (fl != 0ull) *reinterpret_cast<unsigned long long *>(flags + (at >> 3)) = 0ull;
+}
+
+// *n += the non-zero 8-byte words of p[0 .. n_words): the check behind RAPIDGNN_CHECK_ZERO_MAPS
+__global__ void count_nonzero_kernel(const unsigned long long *__restrict__ p, uint64_t n_words, unsigned long long *__restrict__ n)
+{
+    unsigned long long mine = 0;
+    for (uint64_t i = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n_words; i += (uint64_t)gridDim.x * blockDim.x) mine += p[i] != 0ull;
+    for (int o = 32; o > 0; o >>= 1) mine += __shfl_down(mine, o, 64);
+    if ((threadIdx.x & 63) == 0 && mine) atomicAdd(n, mine);
+}
+
+// After the last hop: `seen` back to all-zero by clearing only the groups that hold bits (seen_flags), so that the
+// bitmap can serve the next build without a memset of the whole map.  A thread owns eight groups.
+__global__ void __launch_bounds__(FR_THREADS) clear_seen_kernel(uint32_t *__restrict__ seen, uint8_t *__restrict__ seen_flags, uint64_t n_flag_words)
+{
+    const uint64_t i = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= n_flag_words) return;
+    const unsigned long long fl = reinterpret_cast<const unsigned long long *>(seen_flags)[i];
+    if (fl == 0ull) return;
+#pragma unroll
+    for (int g = 0; g < 8; ++g)
+        if ((fl >> (8 * g)) & 0xFFull) {
+            uint32_t *p = seen + (i * 8 + g) * FR_WORDS_PER_THREAD;
+            *reinterpret_cast<uint4 *>(p) = make_uint4(0, 0, 0, 0);
+            *reinterpret_cast<uint4 *>(p + 4) = make_uint4(0, 0, 0, 0);
+        }
+    reinterpret_cast<unsigned long long *>(seen_flags)[i] = 0ull;
 }
 
 std::atomic<uint64_t> g_next_schedule_uid{1};        // also taken by schedules loaded from a file
@@ -509,18 +588,34 @@ static rg_status build_schedule_impl(const rg_graph *g, const int32_t *train, ui
         prefer_bytes = force[0] == '1';
         byte_map = prefer_bytes && !sparse_maps;
     }
+    // The maps come from the pool of all-zero blocks and go back to it: every hop's frontier pass clears what the hop
+    // marked in `reached` and its flags, and `seen` is cleared at the end group by group (seen_flags says which), so a
+    // build clears what it touched, not n_batches * n_nodes bits (2 GB a map on a graph of 10^8 nodes).
     uint32_t *seen = nullptr, *reached_words = nullptr;
     uint8_t *reached_flags = nullptr;                  // one byte per group of 256 IDs of `reached`
-    RG_TRY(tmp.dev_n<uint32_t>(wpb * beta, &seen));
-    RG_HIP(hipMemsetAsync(seen, 0, wpb * beta * sizeof(uint32_t), st));
-    RG_TRY(tmp.dev_n<uint32_t>(wpb * beta, &reached_words));
-    RG_HIP(hipMemsetAsync(reached_words, 0, wpb * beta * sizeof(uint32_t), st));
-    RG_TRY(tmp.dev_n<uint8_t>(wpb / FR_WORDS_PER_THREAD * beta, &reached_flags));
-    RG_HIP(hipMemsetAsync(reached_flags, 0, wpb / FR_WORDS_PER_THREAD * beta, st));
+    uint8_t *seen_flags = nullptr;                     // the same for `seen`: groups that hold any bit
+    const uint64_t n_groups = wpb / FR_WORDS_PER_THREAD * beta;          // (a multiple of eight: wpb is a multiple of 64)
+    RG_TRY(tmp.dev_zeroed(wpb * beta * sizeof(uint32_t), (void **)&seen, st));
+    RG_TRY(tmp.dev_zeroed(wpb * beta * sizeof(uint32_t), (void **)&reached_words, st));
+    RG_TRY(tmp.dev_zeroed(n_groups, (void **)&reached_flags, st));
+    RG_TRY(tmp.dev_zeroed(n_groups, (void **)&seen_flags, st));
+    if (const char *check = getenv("RAPIDGNN_CHECK_ZERO_MAPS"); check && check[0] == '1') {
+        // for tests: the maps, wherever they came from, really hold nothing but zeros (the pool of all-zero blocks keeps its promise)
+        unsigned long long *n_dev = nullptr, n_host = 0;
+        RG_TRY(tmp.dev_n<unsigned long long>(1, &n_dev));
+        RG_HIP(hipMemsetAsync(n_dev, 0, sizeof(unsigned long long), st));
+        const struct { const void *p; uint64_t bytes; } parts[4] = {{seen, wpb * beta * 4}, {reached_words, wpb * beta * 4}, {reached_flags, n_groups}, {seen_flags, n_groups}};
+        for (const auto &part : parts)
+            hipLaunchKernelGGL(count_nonzero_kernel, dim3(1024), dim3(256), 0, st, (const unsigned long long *)part.p, part.bytes / 8, n_dev);
+        Readback rb(st);
+        RG_TRY(rb.add(&n_host, n_dev, sizeof(n_host)));
+        RG_TRY(rb.wait());
+        if (n_host != 0) { set_error("rg_build_schedule: %llu words of the per-batch maps are not zero at the start of the build", n_host); return RG_EHIP; }
+    }
     ReachedForms maps{reached_words, nullptr, reached_flags, wpb, byte_map};
     {
         ScopedTimer tm(KG_FRONTIER, st);
-        hipLaunchKernelGGL(mark_seeds_kernel, dim3((unsigned)((T + 255) / 256)), dim3(256), 0, st, h0.ids, T, B, seen, wpb, (int64_t)g->n_nodes);
+        hipLaunchKernelGGL(mark_seeds_kernel, dim3((unsigned)((T + 255) / 256)), dim3(256), 0, st, h0.ids, T, B, seen, seen_flags, wpb, (int64_t)g->n_nodes);
     }
     int32_t *fresh_cnt = nullptr;
     int64_t *fresh_scan = nullptr;
@@ -569,11 +664,11 @@ static rg_status build_schedule_impl(const rg_graph *g, const int32_t *train, ui
             ScopedTimer tm(KG_FRONTIER, st);
             hipLaunchKernelGGL(copy_prefix_kernel, dim3((unsigned)((n_cur + 255) / 256)), dim3(256), 0, st, cur.ids, cur.off_dev, nxt.off_dev, beta, n_cur, nxt.ids);
             if (sparse_maps)
-                hipLaunchKernelGGL(fresh_emit_sparse_kernel, dim3(chunks, beta), dim3(FR_THREADS), 0, st, reached_words, reached_flags, seen, wpb, chunks, fresh_scan, cur.off_dev, nxt.ids);
+                hipLaunchKernelGGL(fresh_emit_sparse_kernel, dim3(chunks, beta), dim3(FR_THREADS), 0, st, reached_words, reached_flags, seen, seen_flags, wpb, chunks, fresh_scan, cur.off_dev, nxt.ids);
             else if (marked_bytes)
-                hipLaunchKernelGGL(fresh_emit_kernel<true>, dim3(chunks, beta), dim3(FR_THREADS), 0, st, reached, reached_flags, seen, wpb, chunks, fresh_scan, cur.off_dev, nxt.ids);
+                hipLaunchKernelGGL(fresh_emit_kernel<true>, dim3(chunks, beta), dim3(FR_THREADS), 0, st, reached, reached_flags, seen, seen_flags, wpb, chunks, fresh_scan, cur.off_dev, nxt.ids);
             else
-                hipLaunchKernelGGL(fresh_emit_kernel<false>, dim3(chunks, beta), dim3(FR_THREADS), 0, st, reached, reached_flags, seen, wpb, chunks, fresh_scan, cur.off_dev, nxt.ids);
+                hipLaunchKernelGGL(fresh_emit_kernel<false>, dim3(chunks, beta), dim3(FR_THREADS), 0, st, reached, reached_flags, seen, seen_flags, wpb, chunks, fresh_scan, cur.off_dev, nxt.ids);
         }
         RG_HIP(hipGetLastError());
     }
@@ -584,8 +679,19 @@ static rg_status build_schedule_impl(const rg_graph *g, const int32_t *train, ui
         hipLaunchKernelGGL(epoch_freq_kernel, dim3((unsigned)((wpb + 255) / 256)), dim3(256), 0, st, seen, wpb, beta, (int64_t)g->n_nodes, s->epoch_freq);
         RG_HIP(hipGetLastError());
     }
+    {
+        ScopedTimer tm(KG_FRONTIER, st);
+        hipLaunchKernelGGL(clear_seen_kernel, dim3((unsigned)((n_groups / 8 + FR_THREADS - 1) / FR_THREADS)), dim3(FR_THREADS), 0, st, seen, seen_flags, n_groups / 8);
+        RG_HIP(hipGetLastError());
+    }
     RG_HIP(hipStreamSynchronize(st));
     tmp.drained();
+    // every map is all-zero again and nothing writes them any more
+    tmp.free_zeroed(seen);
+    tmp.free_zeroed(seen_flags);
+    tmp.free_zeroed(reached_words);
+    tmp.free_zeroed(reached_flags);
+    if (maps.bytes) tmp.free_zeroed(maps.bytes);
     return RG_OK;
 }
 
