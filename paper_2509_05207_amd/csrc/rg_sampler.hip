@@ -41,6 +41,7 @@
 
 #include <algorithm>
 #include <atomic>
+#include <cstdlib>
 
 namespace rg {
 
@@ -57,18 +58,21 @@ struct NodeRecs {
     uint64_t *state;      // S_v = combine(combine(S_{e,i}, hop + 1), v)
 };
 
-// Also adds up, over the frontier, what the hop will read of the adjacency: the sum of the degrees (in IDs) and the
-// part of it in rows of up to BIG_ROW IDs (the rows that are sampled inside the groups of nodes, not as tiles).  The
-// sums are spread over DEG_SUM_SLOTS pairs of counters, total[2 * slot] and total[2 * slot + 1], which the host adds up:
-// thousands of workgroups adding to one address would queue up behind each other.
+// Also adds up, over the frontier, what the hop will read of the adjacency: [0] the sum of the degrees (in IDs),
+// [1] the part of it in rows of up to BIG_ROW IDs (the rows that are not sampled as tiles), [2] the number of rows of
+// 1 .. SHORT_ROW IDs and [3] the IDs in them.  The sums are spread over DEG_SUM_SLOTS sets of four counters,
+// total[4 * slot + k], which the host adds up: thousands of workgroups adding to one address would queue up behind
+// each other.
 constexpr int DEG_SUM_SLOTS = 64;
+constexpr int DEG_SUMS = 4;
+constexpr int SHORT_ROW = 64;            // rows of up to this many IDs are sampled four at a time, sixteen lanes each
 __global__ void __launch_bounds__(256) node_records_kernel(const int64_t *__restrict__ indptr, const int32_t *__restrict__ frontier, int64_t n,
                                                            const int64_t *__restrict__ batch_off, uint32_t n_batches, const uint64_t *__restrict__ batch_seed,
                                                            uint32_t hop, uint32_t fanout, NodeRecs r, int32_t *__restrict__ cnt, int32_t *__restrict__ tiles,
                                                            int64_t n_nodes, unsigned long long *__restrict__ total)
 {
-    __shared__ unsigned long long part[2][4];
-    unsigned long long acc = 0, acc_groups = 0;
+    __shared__ unsigned long long part[DEG_SUMS][4];
+    unsigned long long acc[DEG_SUMS] = {0, 0, 0, 0};
     // (a bounded grid, each workgroup striding over the frontier: the sums cost two atomics per workgroup)
     for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (int64_t)gridDim.x * blockDim.x) {
         const int32_t v = frontier[i];
@@ -82,17 +86,19 @@ __global__ void __launch_bounds__(256) node_records_kernel(const int64_t *__rest
         r.state[i] = combine(combine(batch_seed[b], (uint64_t)hop + 1u), (uint64_t)(uint32_t)v);
         cnt[i] = (int32_t)(deg < (int64_t)fanout ? deg : (int64_t)fanout);
         tiles[i] = (int32_t)tiles_of(deg);
-        acc += (unsigned long long)deg;
-        if (deg <= (int64_t)BIG_ROW) acc_groups += (unsigned long long)deg;
+        acc[0] += (unsigned long long)deg;
+        if (deg <= (int64_t)BIG_ROW) acc[1] += (unsigned long long)deg;
+        if (deg > 0 && deg <= (int64_t)SHORT_ROW) { acc[2] += 1; acc[3] += (unsigned long long)deg; }
     }
-    for (int o = 32; o > 0; o >>= 1) { acc += __shfl_down(acc, o, 64); acc_groups += __shfl_down(acc_groups, o, 64); }
-    if ((threadIdx.x & 63) == 0) { part[0][threadIdx.x >> 6] = acc; part[1][threadIdx.x >> 6] = acc_groups; }
+#pragma unroll
+    for (int k = 0; k < DEG_SUMS; ++k) {
+        for (int o = 32; o > 0; o >>= 1) acc[k] += __shfl_down(acc[k], o, 64);
+        if ((threadIdx.x & 63) == 0) part[k][threadIdx.x >> 6] = acc[k];
+    }
     __syncthreads();
-    if (threadIdx.x == 0) {
-        const unsigned long long a = part[0][0] + part[0][1] + part[0][2] + part[0][3], g = part[1][0] + part[1][1] + part[1][2] + part[1][3];
-        const unsigned slot = blockIdx.x % DEG_SUM_SLOTS;
-        if (a) atomicAdd(total + 2 * slot, a);
-        if (g) atomicAdd(total + 2 * slot + 1, g);
+    if (threadIdx.x < DEG_SUMS) {
+        const unsigned long long a = part[threadIdx.x][0] + part[threadIdx.x][1] + part[threadIdx.x][2] + part[threadIdx.x][3];
+        if (a) atomicAdd(total + DEG_SUMS * (blockIdx.x % DEG_SUM_SLOTS) + threadIdx.x, a);
     }
 }
 
@@ -614,6 +620,7 @@ struct HopArgs {
     const int32_t *indices;
     const int32_t *frontier; int64_t n_frontier;
     int64_t n_full_groups, n_units;                                    // set by launch_hop: see there
+    int min_deg;                                                       // rows of up to this many IDs are somebody else's (sample_short_kernel)
     NodeRecs rec;
     uint32_t fanout;
     const int64_t *samp_off; int32_t *samp_nbr;
@@ -673,7 +680,7 @@ __global__ void __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(CAP <= 
         const uint32_t b_lane = in ? a.rec.batch[i_lane] : 0u;
         const int64_t S_lane = in ? (int64_t)a.rec.state[i_lane] : 0;
         const int64_t out_lane = in ? a.samp_off[i_lane] : 0;
-        unsigned long long todo = ballot64(deg_lane > 0 && deg_lane <= BIG_ROW);
+        unsigned long long todo = ballot64(deg_lane > a.min_deg && deg_lane <= BIG_ROW);
         if (todo == 0ull) continue;
         // the first node's leading 64 IDs; from then on the next node's are fetched while the current one is sampled
         int l = __builtin_amdgcn_readfirstlane(__ffsll((long long)todo) - 1);
@@ -735,6 +742,175 @@ __global__ void __launch_bounds__(64) sample_merge_kernel(HopArgs a)
         sample_row<CAP, MARK>(row, len, lane < len ? (uint32_t)row[lane] : 0u, ahead, f, (uint32_t)S, (uint32_t)(S >> 32), lane, buf,
                               a.samp_nbr + a.samp_off[i], reached_of<MARK>(a.reached, b));
     }
+}
+
+
+// ---------------------------------------------------------------- rows of up to SHORT_ROW IDs, four at a time
+// A wave that samples one short row at a time spends its time waiting: a row of 30 IDs is one load and a few dozen
+// instructions, and the next row's load cannot start much earlier than this row's ends.  Here a wave takes 64
+// consecutive frontier nodes, lists the ones with 1 .. SHORT_ROW neighbours -- shortest first, so that rows of a
+// round are of a kind -- and samples four of them at once, one per row of sixteen lanes (lane l of a row holds IDs
+// l, l + 16, l + 32, l + 48 of it), with the next four rows' IDs already on their way.  The f smallest keys of a
+// row: for rows of up to 16 IDs (one key per lane) by rank -- every key is compared with every other key of its row as
+// the register rotates through the sixteen lanes (DPP row rotation, no LDS), and the IDs whose key has fewer than f
+// smaller keys are the sample; for longer rows by the same bisection on the key value as everywhere else, the four
+// rows searching side by side, each lane counting its own row's sixteen bits of every lane mask.  Output positions
+// come from the lane masks, in row order, as in the other kernels.
+struct ShortRec {
+    int64_t row_begin, out;
+    uint64_t state;
+    int32_t deg;
+    uint32_t batch;
+};
+
+template <int R> __device__ __forceinline__ uint32_t rotate16(uint32_t x)      // the value R lanes away within the lane's row of sixteen
+{
+    return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, 0x120 + R, 0xF, 0xF, false);
+}
+
+// The number of keys of the lane's row of sixteen lanes (one key per lane) that are smaller than this lane's.
+__device__ __forceinline__ int count_smaller16(uint32_t k)
+{
+    int cnt = 0;
+#define RG_ROT(R) cnt += rotate16<R>(k) < k ? 1 : 0;
+    RG_ROT(1) RG_ROT(2) RG_ROT(3) RG_ROT(4) RG_ROT(5) RG_ROT(6) RG_ROT(7) RG_ROT(8)
+    RG_ROT(9) RG_ROT(10) RG_ROT(11) RG_ROT(12) RG_ROT(13) RG_ROT(14) RG_ROT(15)
+#undef RG_ROT
+    return cnt;
+}
+
+// This lane's row's sixteen bits of a lane mask, counted.
+__device__ __forceinline__ int popc_of_my_row(unsigned long long m, int lane) { return __popc((uint32_t)(m >> (lane & 48)) & 0xFFFFu); }
+
+// For each row of sixteen lanes on its own: the largest key value `cut` such that exactly f of the row's keys do not
+// exceed it.  k[e], e < E: the row's keys, a missing one stands as 0xFFFFFFFF; deg (> f in the rows that search, same
+// in all lanes of a row): how many there are; rows with searching == false ride along and get an arbitrary answer.
+// Bit by bit from the top, as kth_key_threshold does for a whole wave: the f-th smallest key stays inside
+// [lo, lo + 2^(bit+1)), and a row is done as soon as exactly f keys lie below the bracket's upper end -- for keys
+// spread over 32 bits after about log2(deg) + 2 steps; the loop ends when every row is done.
+template <int E>
+__device__ __forceinline__ uint32_t kth_key_threshold_rows(const uint32_t (&k)[4], int f, int deg, bool searching, int lane)
+{
+    uint32_t lo = 0, cut = 0xFFFFFFFFu;
+    int below_hi = deg;
+    bool done = !searching;
+    for (int bit = 31; bit >= 0; --bit) {
+        if (ballot64(!done) == 0ull) break;
+        const uint32_t t = lo | (1u << bit);
+        int c = 0;
+#pragma unroll
+        for (int e = 0; e < E; ++e) c += popc_of_my_row(ballot64(k[e] < t), lane);
+        if (!done) {
+            if (c >= f) below_hi = c; else lo = t;
+            cut = lo | ((1u << bit) - 1u);
+            done = below_hi == f;
+        }
+    }
+    return cut;
+}
+
+struct ShortArgs {
+    const int32_t *indices;
+    int64_t n_frontier;
+    NodeRecs rec;
+    uint32_t fanout;
+    const int64_t *samp_off; int32_t *samp_nbr;
+    ReachedMaps reached;
+};
+
+template <int MARK>
+__global__ void __launch_bounds__(64) sample_short_kernel(ShortArgs a)
+{
+    __shared__ ShortRec recs[64];
+    const int lane = threadIdx.x, l16 = lane & 15, sg = lane >> 4;
+    const int f = (int)a.fanout;
+    const int64_t n_groups = (a.n_frontier + 63) >> 6;
+    for (int64_t w = blockIdx.x; w < n_groups; w += gridDim.x) {
+        const int64_t i_lane = (w << 6) + lane;
+        const int deg_lane = i_lane < a.n_frontier ? a.rec.deg[i_lane] : 0;
+        const bool mine = deg_lane > 0 && deg_lane <= SHORT_ROW;
+        const unsigned long long short_mask = ballot64(mine);
+        const int count = __popcll(short_mask);
+        if (count == 0) continue;
+        __syncthreads();                                            // the previous group's records have been read by every lane
+        if (mine) {
+            // shortest rows first: by the number of IDs per lane ((deg - 1) / 16), lane order within a kind
+            const int kind = (deg_lane - 1) >> 4;
+            int at = 0;
+#pragma unroll
+            for (int c = 0; c < 4; ++c) {
+                const unsigned long long m = ballot64(mine && ((deg_lane - 1) >> 4) == c);
+                if (c < kind) at += __popcll(m);
+                else if (c == kind) at += lanes_below(m, lane);
+            }
+            recs[at] = ShortRec{a.rec.row_begin[i_lane], a.samp_off[i_lane], a.rec.state[i_lane], deg_lane, a.rec.batch[i_lane]};
+        }
+        __syncthreads();
+        const int n_it = (count + 3) >> 2;
+        // this lane's row of the round, and its IDs (0 where the row has none)
+        auto fetch = [&](int it, ShortRec &r, uint32_t (&u)[4]) {
+            const int slot = it * 4 + sg;
+            r = slot < count ? recs[slot] : ShortRec{0, 0, 0, 0, 0};
+            const int32_t *row = a.indices + r.row_begin;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) u[e] = l16 + 16 * e < r.deg ? (uint32_t)row[l16 + 16 * e] : 0u;
+        };
+        ShortRec r, r_next;
+        uint32_t u[4], u_next[4];
+        fetch(0, r, u);
+        for (int it = 0; it < n_it; ++it) {
+            if (it + 1 < n_it) fetch(it + 1, r_next, u_next);
+            const int deg = r.deg;
+            bool sel[4];
+#pragma unroll
+            for (int e = 0; e < 4; ++e) sel[e] = l16 + 16 * e < deg;
+            const bool searching = deg > f;
+            if (ballot64(searching) != 0ull) {                       // some row of the round is longer than the fan-out
+                const uint32_t slo = (uint32_t)r.state, shi = (uint32_t)(r.state >> 32);
+                uint32_t k[4];
+#pragma unroll
+                for (int e = 0; e < 4; ++e) k[e] = sel[e] ? key32(slo, shi, u[e]) : 0xFFFFFFFFu;     // (a missing key's stand-in is never counted as smaller than anything)
+                if (ballot64(searching && deg > 16) == 0ull) {       // one key per lane: by rank
+                    const int smaller = count_smaller16(k[0]);
+                    if (searching) sel[0] = sel[0] && smaller < f;
+                } else {
+                    uint32_t cut;
+                    if (ballot64(searching && deg > 48) != 0ull) cut = kth_key_threshold_rows<4>(k, f, deg, searching, lane);
+                    else if (ballot64(searching && deg > 32) != 0ull) cut = kth_key_threshold_rows<3>(k, f, deg, searching, lane);
+                    else cut = kth_key_threshold_rows<2>(k, f, deg, searching, lane);
+                    if (searching) {
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) sel[e] = sel[e] && k[e] <= cut;
+                    }
+                }
+            }
+            // row order is ID 0 .. 15 (e = 0), 16 .. 31 (e = 1), ...: a selected ID's place is the number of selected IDs before it
+            const ReachedOfBatch reached_b = reached_of<MARK>(a.reached, r.batch);
+            int32_t *out = a.samp_nbr + r.out;
+            int base = 0;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const uint32_t m16 = (uint32_t)(ballot64(sel[e]) >> (lane & 48)) & 0xFFFFu;       // the selected lanes of this lane's row
+                if (sel[e]) {
+                    out[base + __popc(m16 & ((1u << l16) - 1u))] = (int32_t)u[e];
+                    mark_reached<MARK>(reached_b, u[e]);
+                }
+                base += __popc(m16);
+            }
+            r = r_next;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) u[e] = u_next[e];
+        }
+    }
+}
+
+template <int MARK>
+static rg_status launch_short(const ShortArgs &a, int n_cu, hipStream_t st)
+{
+    const int64_t n_groups = (a.n_frontier + 63) >> 6;
+    const unsigned grid = (unsigned)std::max<int64_t>(1, std::min<int64_t>(n_groups, (int64_t)n_cu * 32));
+    hipLaunchKernelGGL((sample_short_kernel<MARK>), dim3(grid), dim3(64), 0, st, a);
+    return RG_OK;
 }
 
 // Every workgroup of the sampling launch must be resident from the start (tiles are dealt out by workgroup index), so
@@ -818,9 +994,9 @@ rg_status sample_hop(const rg_graph *g, HopData &cur, uint32_t beta, const uint6
     RG_TRY(tmp.dev_n<uint32_t>((uint64_t)n_cur, &rec.batch));
     RG_TRY(tmp.dev_n<uint64_t>((uint64_t)n_cur, &rec.state));
     RG_TRY(keep.dev_n<int64_t>((uint64_t)n_cur + 1, &cur.samp_off));
-    unsigned long long sums[2] = {0, 0}, *sum_deg_dev = nullptr;       // IDs in all rows of the frontier, IDs in its rows outside tiles
-    unsigned long long sum_parts[2 * DEG_SUM_SLOTS];
-    RG_TRY(tmp.dev_n<unsigned long long>(2 * DEG_SUM_SLOTS, &sum_deg_dev));
+    unsigned long long sums[DEG_SUMS] = {0, 0, 0, 0}, *sum_deg_dev = nullptr;       // see node_records_kernel
+    unsigned long long sum_parts[DEG_SUMS * DEG_SUM_SLOTS];
+    RG_TRY(tmp.dev_n<unsigned long long>(DEG_SUMS * DEG_SUM_SLOTS, &sum_deg_dev));
     RG_HIP(hipMemsetAsync(sum_deg_dev, 0, sizeof(sum_parts), st));
     {
         ScopedTimer tm(KG_OFFSETS, st);
@@ -839,7 +1015,8 @@ rg_status sample_hop(const rg_graph *g, HopData &cur, uint32_t beta, const uint6
         RG_TRY(rb.add(&n_tiles, tile_off + n_cur, sizeof(int64_t)));
         if (also_read_dev) RG_TRY(rb.add(also_read_host, also_read_dev, sizeof(unsigned long long)));     // a value the caller wants behind the same wait
         RG_TRY(rb.wait());
-        for (int k = 0; k < DEG_SUM_SLOTS; ++k) { sums[0] += sum_parts[2 * k]; sums[1] += sum_parts[2 * k + 1]; }
+        for (int k = 0; k < DEG_SUM_SLOTS; ++k)
+            for (int q = 0; q < DEG_SUMS; ++q) sums[q] += sum_parts[DEG_SUMS * k + q];
         if (also_read_dev && *also_read_host != 0) return RG_OK;        // the caller refuses the build: nothing more to launch
     }
     // Which form of the reached map this hop marks.  A byte store is several times cheaper than an atomic OR, but the
@@ -892,19 +1069,29 @@ rg_status sample_hop(const rg_graph *g, HopData &cur, uint32_t beta, const uint6
     }
 
     if (fanout > 0 && n_cur > 0) {
+        // Rows of up to SHORT_ROW IDs go to a kernel of their own where the hop marks with plain byte stores (same samples
+        // either way; RAPIDGNN_SHORT_ROWS=1 / 0 forces / forbids it, for tests and tuning).  Measured: fanout_stress
+        // (rows mostly copied whole, byte marks) 4.3 -> 3.8 ms; where marks are atomic ORs the kernel of its own is bound
+        // by their rate (large_sparse: 58 M of them in 2.6 ms, 22 G/s) and the hop as a whole gets slower, 12.3 -> 13.0 ms,
+        // also with the two kernels side by side on two streams (13.1 ms): interleaved with the streaming of long rows in
+        // one kernel the atomics cost less.
+        bool short_rows_apart = sums[2] > 0 && use_bytes;
+        if (const char *force = getenv("RAPIDGNN_SHORT_ROWS")) short_rows_apart = force[0] == '1';
+        const uint32_t need = fanout + 64;
+        const int mark = need > 256 ? MARK_BITS : all_flags && use_bytes ? MARK_BYTES_ALL : all_flags ? MARK_BITS_ALL : use_bytes ? MARK_BYTES : MARK_BITS;
         unsigned long long *next_work = nullptr;
         RG_TRY(tmp.dev_n<unsigned long long>(1, &next_work));
         RG_HIP(hipMemsetAsync(next_work, 0, sizeof(unsigned long long), st));
-        HopArgs a{g->indices, cur.ids, n_cur, 0, 0, rec, fanout, cur.samp_off, cur.samp_nbr, tile_off, tile, n_tiles, tile_out, reached, next_work};
+        HopArgs a{g->indices, cur.ids, n_cur, 0, 0, short_rows_apart ? SHORT_ROW : 0, rec, fanout, cur.samp_off, cur.samp_nbr, tile_off, tile, n_tiles, tile_out, reached, next_work};
         ScopedTimer tm(KG_SAMPLER, st);
         const unsigned merge_grid = (unsigned)std::max<int64_t>(1, std::min<int64_t>(n_tiles, (int64_t)n_cu * 64));
         // worth it where a group is long work: rows of a thousand IDs on average, tiles aside (short rows finish a
         // group of 64 in no time, and four times the requests to the work counter then cost more than the tail does;
         // measured: Medium, 2,500 IDs per row, 4 % faster; large_sparse and partition_share, a few hundred, 1-8 % slower)
-        const bool fine_tail = sums[1] >= 1024ull * (unsigned long long)n_cur;
+        const unsigned long long ids_here = sums[1] - (short_rows_apart ? sums[3] : 0), rows_here = (unsigned long long)n_cur - (short_rows_apart ? sums[2] : 0);
+        const bool fine_tail = ids_here >= 1024ull * rows_here;
         // a frontier that does not give every resident wave a group of 64 (the seed hop) is split finer from rows of 256 IDs on
-        const bool fine_if_few = sums[1] >= 256ull * (unsigned long long)n_cur;
-        const uint32_t need = fanout + 64;
+        const bool fine_if_few = ids_here >= 256ull * rows_here;
         if (need <= 128) {
             if (all_flags && use_bytes) RG_TRY((launch_hop<128, MARK_BYTES_ALL>(a, n_cu, merge_grid, fine_tail, fine_if_few, st)));
             else if (all_flags) RG_TRY((launch_hop<128, MARK_BITS_ALL>(a, n_cu, merge_grid, fine_tail, fine_if_few, st)));
@@ -920,6 +1107,16 @@ rg_status sample_hop(const rg_graph *g, HopData &cur, uint32_t beta, const uint6
         else if (need <= 1024) RG_TRY((launch_hop<1024, MARK_BITS>(a, n_cu, merge_grid, fine_tail, fine_if_few, st)));
         else RG_TRY((launch_hop<2048, MARK_BITS>(a, n_cu, merge_grid, fine_tail, fine_if_few, st)));
         RG_HIP(hipGetLastError());
+        if (short_rows_apart) {
+            const ShortArgs sa{g->indices, n_cur, rec, fanout, cur.samp_off, cur.samp_nbr, reached};
+            switch (mark) {
+            case MARK_BYTES_ALL: RG_TRY(launch_short<MARK_BYTES_ALL>(sa, n_cu, st)); break;
+            case MARK_BITS_ALL: RG_TRY(launch_short<MARK_BITS_ALL>(sa, n_cu, st)); break;
+            case MARK_BYTES: RG_TRY(launch_short<MARK_BYTES>(sa, n_cu, st)); break;
+            default: RG_TRY(launch_short<MARK_BITS>(sa, n_cu, st)); break;
+            }
+            RG_HIP(hipGetLastError());
+        }
     }
     return RG_OK;
 }

@@ -54,14 +54,21 @@ SHAPES = [
     (1200, [(0, 0, 5), (1, 2, 1)], (4, 4), 16, 1200),                                             # almost no edges
     (40000, [(2, 12, 8), (13, 40, 2)], (5, 5, 5), 1024, 5000),
     (900, [(64, 64, 1), (65, 65, 1), (256, 256, 1), (257, 257, 1), (63, 63, 1), (255, 255, 1)], (9, 7), 33, 400),   # the class boundaries
+    (3000, [(1, 16, 2), (17, 32, 2), (33, 48, 2), (49, 64, 2), (0, 0, 1)], (15, 40, 64), 97, 1500),                 # short rows only: every count of IDs per lane, fan-outs around them
+    (1500, [(15, 17, 1), (31, 33, 1), (47, 49, 1), (63, 65, 1)], (16, 1, 63), 64, 1500),                            # the sixteen-lane boundaries
 ]
 
 
 @pytest.mark.parametrize("shape", range(len(SHAPES)))
-@pytest.mark.parametrize("sampler,maps", [("keys", "auto"), ("keys", "bytes"), ("keys", "bits"), ("positions", "auto")])
+@pytest.mark.parametrize("sampler,maps", [("keys", "auto"), ("keys", "bytes"), ("keys", "bits"), ("keys", "one_row_per_wave"), ("keys", "four_short_rows_per_wave"),
+                                          ("positions", "auto")])
 def test_random_shape(rg, orc, shape, sampler, maps, monkeypatch):
-    if maps != "auto":                                   # the form of the reached-ID map, forced (chosen per hop otherwise)
+    if maps in ("bytes", "bits"):                        # the form of the reached-ID map, forced (chosen per hop otherwise)
         monkeypatch.setenv("RAPIDGNN_BYTE_MAPS", "1" if maps == "bytes" else "0")
+    if maps == "one_row_per_wave":                       # without the kernel that samples four short rows at a time ...
+        monkeypatch.setenv("RAPIDGNN_SHORT_ROWS", "0")
+    if maps == "four_short_rows_per_wave":               # ... and with it in every hop (by default: in hops that mark with byte stores)
+        monkeypatch.setenv("RAPIDGNN_SHORT_ROWS", "1")
     n, classes, fanout, batch, n_train = SHAPES[shape]
     rng = np.random.default_rng(4000 + shape)
     indptr, indices = random_graph(rng, n, classes)
