@@ -167,6 +167,15 @@ rg_status rg_schedule_samples(const rg_schedule *s, uint32_t hop, const int64_t 
 rg_status rg_schedule_save(const rg_schedule *s, const char *path, void *stream);
 rg_status rg_schedule_load(const char *path, const rg_allocator *a, void *stream, rg_schedule **out);
 
+/* Streaming the metadata block (Sec. 4 par. (3): blocks are streamed from storage when they exceed memory):
+ * batches [first_batch, first_batch + n_batches) of the schedule in `path` as a handle of their own, batch k of
+ * the handle being batch first_batch + k of the file.  Only those batches' bytes are read (a batch range is a
+ * contiguous slice of every array in the file) and only they occupy device memory, so an epoch that does not fit
+ * is served range after range; caches, gathers and computation blocks take the handle like any other schedule.
+ * Checked like rg_schedule_load (RG_EIO); RG_ERANGE if the range leaves the file's batches. */
+rg_status rg_schedule_load_range(const char *path, uint32_t first_batch, uint32_t n_batches, const rg_allocator *a,
+                                 void *stream, rg_schedule **out);
+
 /* Feature storage, as byte rows (any element type): X[v] is
  * local_rows + row_of[v] * local_stride when is_local[v], else
  * remote_rows + row_of[v] * remote_stride (is_local marks N_local, the nodes whose rows this worker holds; Eq. 2).  The remote table stands for the other

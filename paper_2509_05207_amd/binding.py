@@ -26,7 +26,7 @@ EXPORTS = ("rg_last_error", "rg_graph_validate", "rg_build_schedule", "rg_schedu
            "rg_prefetcher_create", "rg_prefetcher_fill", "rg_prefetcher_acquire", "rg_prefetcher_release",
            "rg_prefetcher_depth", "rg_prefetcher_destroy", "rg_schedule_build_blocks", "rg_schedule_block",
            "rg_classify_batch", "rg_build_schedule_with", "rg_gather_batches",
-           "rg_schedule_save", "rg_schedule_load", "rg_gather_batch_noalloc", "rg_schedule_seeds")
+           "rg_schedule_save", "rg_schedule_load", "rg_gather_batch_noalloc", "rg_schedule_seeds", "rg_schedule_load_range")
 
 
 class RgError(RuntimeError):
@@ -98,6 +98,7 @@ def lib():
         L.rg_profile_read.argtypes = [P(C.c_double), P(u64)]
         L.rg_schedule_save.argtypes = [vp, C.c_char_p, vp]
         L.rg_schedule_load.argtypes = [C.c_char_p, P(rg_allocator), vp, P(vp)]
+        L.rg_schedule_load_range.argtypes = [C.c_char_p, u32, u32, P(rg_allocator), vp, P(vp)]
         L.rg_gather_batches.argtypes = [vp, vp, P(rg_features), u32, u32, vp, u64, u64, vp, vp, P(rg_gather_stats)]
         L.rg_classify_batch.argtypes = [vp, vp, P(rg_features), u32, vp, P(rg_gather_stats)]
         L.rg_schedule_build_blocks.argtypes = [vp, u64, vp]
@@ -120,7 +121,7 @@ def lib():
                      "rg_prefetcher_create", "rg_prefetcher_fill", "rg_prefetcher_acquire", "rg_prefetcher_release",
                      "rg_prefetcher_depth", "rg_schedule_build_blocks", "rg_schedule_block",
            "rg_classify_batch", "rg_build_schedule_with", "rg_gather_batches",
-           "rg_schedule_save", "rg_schedule_load", "rg_gather_batch_noalloc", "rg_schedule_seeds"):
+           "rg_schedule_save", "rg_schedule_load", "rg_gather_batch_noalloc", "rg_schedule_seeds", "rg_schedule_load_range"):
             getattr(L, name).restype = C.c_int32
         _lib = L
     return _lib
@@ -234,6 +235,14 @@ def rg_schedule_load(path, allocator=None, stream=None):
     out = C.c_void_p()
     _check(lib().rg_schedule_load(os.fsencode(path), C.byref(allocator) if allocator is not None else None, _stream_ptr(stream),
                                   C.byref(out)))
+    return Schedule(out.value, allocator)
+
+
+def rg_schedule_load_range(path, first_batch, n_batches, allocator=None, stream=None):
+    """Batches [first_batch, first_batch + n_batches) of a schedule file as a schedule of their own."""
+    out = C.c_void_p()
+    _check(lib().rg_schedule_load_range(os.fsencode(path), int(first_batch), int(n_batches),
+                                        C.byref(allocator) if allocator is not None else None, _stream_ptr(stream), C.byref(out)))
     return Schedule(out.value, allocator)
 
 
@@ -482,13 +491,18 @@ def rg_profile_read():
 
 
 class TorchAllocator:
-    """rg_allocator backed by torch: device buffers from the caching allocator, pinned buffers from pinned tensors."""
+    """rg_allocator backed by torch: device buffers from the caching allocator, pinned buffers from pinned tensors.
+    limit_bytes: requests above it are refused (NULL to the library), as an allocator that has run out would."""
 
-    def __init__(self):
+    def __init__(self, limit_bytes=None):
         self.live = {}
         self.n_alloc = 0
+        self.n_refused = 0
 
         def _alloc(nbytes, kind, _ctx):
+            if limit_bytes is not None and int(nbytes) > limit_bytes:
+                self.n_refused += 1
+                return None
             try:
                 if kind == 1:
                     t = torch.empty(int(nbytes), dtype=torch.uint8, device="cuda")

@@ -321,6 +321,36 @@ def test_a_schedule_keeps_its_allocator_alive(rg, orc):
     assert len(live) == 0
 
 
+def test_an_allocation_that_fails_is_an_error_not_a_crash(rg, orc):
+    """The per-batch maps of a build are n_batches * n_nodes bits each: an allocator that cannot give that much makes
+    the build return RG_ENOMEM with everything it had taken handed back; the same goes for the cache's arrays."""
+    import gc
+    w, indptr, indices, train = small_graph()
+    beta = -(-train.numel() // 16)
+    words_per_batch = ((w.n_nodes + 31) // 32 + 63) // 64 * 64
+    map_bytes = beta * words_per_batch * 4                                   # one bitmap
+    alloc = rg.TorchAllocator(limit_bytes=map_bytes // 2)
+    with pytest.raises(rg.RgError) as e:
+        rg.rg_build_schedule(indptr, indices, train, 16, [3, 2], allocator=alloc.struct)
+    assert e.value.status == rg.RG_ENOMEM and alloc.n_refused >= 1
+    torch.cuda.synchronize()
+    assert len(alloc.live) == 0                                              # nothing kept
+    roomy = rg.TorchAllocator()
+    g = rg.rg_build_schedule(indptr, indices, train, 16, [3, 2], allocator=roomy.struct)
+    o = orc.Schedule(w.indptr.numpy(), w.indices.numpy(), w.train.numpy(), 16, [3, 2])
+    assert_schedules_equal(rg, g, o)
+    f = rg.make_features(w.is_local.cuda(), w.row_of.cuda(), w.local_rows.cuda(), w.remote_rows.cuda(), w.row_bytes)
+    tight = rg.TorchAllocator(limit_bytes=w.n_nodes * 4 - 1)                 # freq and slot_of need n_nodes * 4 bytes each
+    with pytest.raises(rg.RgError) as e:
+        rg.rg_build_cache([g], f, w.K, allocator=tight.struct)
+    assert e.value.status == rg.RG_ENOMEM
+    torch.cuda.synchronize()
+    assert len(tight.live) == 0
+    del g, e                                                                 # (the caught error's traceback holds the schedule too)
+    gc.collect()
+    assert len(roomy.live) == 0
+
+
 def test_train_nodes_are_checked(rg):
     w, indptr, indices, train = small_graph()
     n = w.n_nodes

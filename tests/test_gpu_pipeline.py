@@ -7,7 +7,7 @@ import pytest
 import torch
 
 from paper_2509_05207_amd import synth
-from test_gpu_parity import Case
+from test_gpu_parity import Case, assert_schedules_equal
 
 pytestmark = pytest.mark.gpu
 
@@ -348,6 +348,50 @@ def test_schedule_survives_a_round_trip_through_a_file(case, rg, orc, tmp_path):
     rg.rg_schedule_build_blocks(g)
     for hop in range(g.L):
         assert np.array_equal(rg.rg_schedule_block(g, hop).cpu().numpy(), case.osched.block(hop))
+
+
+def test_an_epoch_streamed_from_its_file_range_by_range(case, rg, orc, tmp_path):
+    """The metadata block streamed back piece by piece: every range of batches of the file equals the oracle's
+    schedule of those batches alone, serves gathers with a cache of its own, and yields its computation blocks."""
+    w = case.w
+    path = tmp_path / "epoch.rgsched"
+    rg.rg_schedule_save(case.gsched, path)
+    nb = case.gsched.n_batches
+    step = max(1, nb // 3)
+    ranges = [(lo, min(step, nb - lo)) for lo in range(0, nb, step)] + [(nb - 1, 1), (0, nb), (1, 0), (nb, 0)]
+    for lo, n in ranges:
+        part = rg.rg_schedule_load_range(path, lo, n)
+        assert part.n_batches == n and part.L == case.gsched.L
+        if n == 0:
+            continue
+        o = orc.Schedule(w.indptr.numpy(), w.indices.numpy(), w.train.numpy(), w.cfg.batch_size, w.cfg.fanout, case.s0, case.worker, case.epoch,
+                         batch_lo=lo, batch_hi=lo + n, n_threads=4)
+        assert_schedules_equal(rg, part, o)
+        rg.rg_schedule_build_blocks(part)
+        for hop in range(o.L):
+            assert np.array_equal(rg.rg_schedule_block(part, hop).cpu().numpy(), o.block(hop))
+        cache = rg.rg_build_cache([part], case.gfeat, w.K)
+        ids, slot = orc.top_hot(orc.frequency([o], w.n_nodes), w.is_local.numpy(), w.K)
+        assert np.array_equal(rg.rg_cache_view(cache, w.n_nodes)["cache_ids"].cpu().numpy(), ids)
+        _, off = o.input_nodes()
+        rows = int(off[-1])
+        out = torch.empty(max(rows, 1) * w.row_bytes, dtype=torch.uint8, device="cuda")
+        stats = rg.rg_gather_batches(part, cache, case.gfeat, 0, n, out, out_stride=w.row_bytes, out_capacity_rows=rows)
+        torch.cuda.synchronize()
+        got = out.cpu().numpy()[: rows * w.row_bytes].reshape(rows, w.row_bytes)
+        for b in range(n):
+            ref = orc.gather_batch(o, b, case.ofeat, out_stride=w.row_bytes)
+            assert np.array_equal(got[off[b]:off[b + 1]], ref), f"range ({lo}, {n}) batch {b}"
+            assert stats[b] == orc.batch_stats(o, b, w.is_local.numpy(), slot)
+    for lo, n in ((nb, 1), (0, nb + 1), (nb + 1, 0)):
+        with pytest.raises(rg.RgError) as e:
+            rg.rg_schedule_load_range(path, lo, n)
+        assert e.value.status == rg.RG_ERANGE
+    data = path.read_bytes()
+    (tmp_path / "short").write_bytes(data[:-4])
+    with pytest.raises(rg.RgError) as e:
+        rg.rg_schedule_load_range(tmp_path / "short", 0, 1)
+    assert e.value.status == rg.RG_EIO
 
 
 def test_damaged_schedule_files_are_refused(case, rg, tmp_path):
