@@ -418,8 +418,6 @@ def test_position_sampler_matches_oracle(case, rg, orc, fanout):
     fan-outs on both sides of the workgroup width and of the 64-slot selection branch."""
     w = case.w
     fan = list(fanout) if fanout else list(w.cfg.fanout)
-    if fanout and case.name not in ("small", "mid"):
-        pytest.skip("fan-out variants run on two graphs")
     o = orc.Schedule(w.indptr.numpy(), w.indices.numpy(), w.train.numpy(), w.cfg.batch_size, fan, case.s0, case.worker, case.epoch,
                      n_threads=8, sampler="positions")
     g = rg.rg_build_schedule_with(case.indptr, case.indices, case.train, w.cfg.batch_size, fan, case.s0, case.worker, case.epoch,
@@ -473,8 +471,6 @@ def test_both_forms_of_the_reached_map_give_the_same_schedule(case, rg, orc, for
     and its second hop bytes: both forms within one build."""
     monkeypatch.setenv("RAPIDGNN_BYTE_MAPS", force)
     w = case.w
-    if fanout and case.name not in ("small", "mid"):
-        pytest.skip("fan-out variants run on two graphs")
     fan = list(fanout) if fanout else list(w.cfg.fanout)
     code = rg.RG_SAMPLER_KEYS if sampler == "keys" else rg.RG_SAMPLER_POSITIONS
     if sampler == "keys" and not fanout:
