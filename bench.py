@@ -217,14 +217,25 @@ def runtime_leg(rg, W, feat, epochs=3, Q=4):
 
 
 def cpu_model_string():
+    """The first processor's entry of /proc/cpuinfo: model name with vendor, family, model and stepping numbers."""
+    want = ("vendor_id", "model name", "cpu family", "model", "stepping")
+    got = {}
     try:
         with open("/proc/cpuinfo") as fh:
             for ln in fh:
-                if ln.startswith("model name"):
-                    return ln.split(":", 1)[1].strip()
+                if ":" not in ln:
+                    if got:
+                        break
+                    continue
+                k, v = (x.strip() for x in ln.split(":", 1))
+                if k in want and k not in got:
+                    got[k] = v
     except OSError:
         pass
-    return ""
+    if not got:
+        return ""
+    return (f"{got.get('model name', '?')} ({got.get('vendor_id', '?')}, family {got.get('cpu family', '?')}, model {got.get('model', '?')}, "
+            f"stepping {got.get('stepping', '?')})")
 
 
 def cpu_baseline(W, remote_host, budget_s=10.0):
