@@ -16,8 +16,9 @@ Prints ONE JSON line.
                   placement: VectorPull and every miss cross the host link (reported, never `value`)
   cpu_baseline    the CPU oracle on a bounded prefix of the epoch, per call, on one thread and on all cores
   other_workloads the remaining configurations, briefly (value, step time, sampler and gather rates)
-Gathers stage --gather-group batches per launch (default: the next eight batches back to back in one staging
-buffer, more, up to 64, while that would be less than 512 MB per launch).
+Gathers stage --gather-group batches per launch (default, accounting.gather_group: the whole epoch if its feature
+blocks together stay under 4 GiB, else the next eight batches back to back in one staging buffer, more, up to 64,
+while that would be less than 512 MiB per launch).
 """
 import argparse
 import json
@@ -368,9 +369,7 @@ def measure(rg, name, args, full):
     sampled_edges = sum(h["sampled"] for h in hops)
     G = args.gather_group
     if G <= 0:      # small batches: more of them per launch, so that a launch is long enough to run at the memory system's rate
-        G = 8
-        while G < 64 and G < n_batches and rows_per_epoch / n_batches * G * W.stride_bytes < (512 << 20):
-            G *= 2
+        G = accounting.gather_group(n_batches, rows_per_epoch, W.stride_bytes)
     if G > 1:       # the staging buffer holds the largest group of G consecutive batches
         m_max = max(int(off_L[min(b + G, n_batches)] - off_L[b]) for b in range(0, n_batches, G))
     out_buf = torch.empty(m_max * W.stride_bytes, dtype=torch.uint8, device="cuda")
@@ -506,7 +505,7 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--gather-group", type=int, default=0,
                     help="batches whose feature blocks one gather launch stages back to back (rg_gather_batches, the prefetcher's Q); "
-                         "1 = one launch per batch; 0 = eight, doubled up to 64 while a launch would stage less than 512 MB")
+                         "1 = one launch per batch; 0 = the whole epoch if it stages under 4 GiB, else eight, doubled up to 64 while a launch would stage less than 512 MiB")
     ap.add_argument("--no-pcie-pass", action="store_true")
     ap.add_argument("--no-runtime-leg", action="store_true", help="skip the multi-epoch cache-pair / prefetch-queue / blocks leg")
     ap.add_argument("--no-other-workloads", action="store_true", help="skip the brief passes over the other configurations")

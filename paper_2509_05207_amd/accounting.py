@@ -21,3 +21,18 @@ def gather_traffic_bytes(n_rows: int, row_bytes: int) -> int:
     """Algorithmic bytes of one feature-block gather: every row read once and
     written once, one 4-byte node ID and one 8-byte routing entry per row."""
     return n_rows * (2 * row_bytes + 4 + 8)
+
+
+def gather_group(n_batches: int, rows_per_epoch: int, stride_bytes: int) -> int:
+    """How many consecutive batches the benchmark stages per gather launch (the prefetcher's "next Q batches" at
+    once, rg_gather_batches): the whole epoch if its feature blocks together stay under 4 GiB, else eight batches,
+    doubled up to 64 while a launch would stage less than 512 MiB.  A launch has to be long enough to run at the
+    memory system's rate: a single small batch is launch-bound."""
+    if n_batches <= 0:
+        return 1
+    if rows_per_epoch * stride_bytes < (4 << 30):
+        return n_batches
+    g = 8
+    while g < 64 and g < n_batches and rows_per_epoch / n_batches * g * stride_bytes < (512 << 20):
+        g *= 2
+    return g

@@ -402,6 +402,8 @@ __global__ void __launch_bounds__(FR_THREADS) fresh_emit_sparse_kernel(uint32_t 
     const uint64_t wave_at = (uint64_t)b * words_per_batch + wave_w0;
     // first round of loads: how many fresh IDs each listed group holds, and from that where each group's IDs go
     int before[FRS_ROUNDS];            // fresh IDs of the wave's listed groups in front of this lane's group of round r
+    uint32_t w_first[8] = {0, 0, 0, 0, 0, 0, 0, 0};       // the fresh words of the first round's group (nearly always the only round): kept for the second pass
+    int n_first = 0;
     int carry = 0;
     if (any_fresh) {
 #pragma unroll
@@ -413,6 +415,11 @@ __global__ void __launch_bounds__(FR_THREADS) fresh_emit_sparse_kernel(uint32_t 
                 if (i < total) {
                     uint32_t w[8];
                     n = fresh_in_group(reached, seen, wave_at + (uint64_t)lists[wave][i] * FR_WORDS_PER_THREAD, w);
+                    if (r == 0) {
+                        n_first = n;
+#pragma unroll
+                        for (int k = 0; k < 8; ++k) w_first[k] = w[k];
+                    }
                 }
                 int incl = n;
                 for (int d = 1; d < 64; d <<= 1) {
@@ -437,7 +444,12 @@ __global__ void __launch_bounds__(FR_THREADS) fresh_emit_sparse_kernel(uint32_t 
             const uint64_t ag = wave_at + (uint64_t)grp * FR_WORDS_PER_THREAD;
             if (any_fresh) {
                 uint32_t w[8];
-                const int ng = fresh_in_group(reached, seen, ag, w);
+                int ng;
+                if (r == 0) {
+                    ng = n_first;
+#pragma unroll
+                    for (int k = 0; k < 8; ++k) w[k] = w_first[k];
+                } else ng = fresh_in_group(reached, seen, ag, w);
                 if (ng) {
                     int64_t pos = base + before[r];
 #pragma unroll

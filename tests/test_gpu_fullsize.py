@@ -99,11 +99,8 @@ class Epoch:
 
     def group_size(self):
         """Batches per gather launch, as bench.py chooses it."""
-        nb, rows = self.o.n_batches, int(self.off[-1])
-        G = 8
-        while G < 64 and G < nb and rows / nb * G * self.W.stride_bytes < (512 << 20):
-            G *= 2
-        return G
+        from paper_2509_05207_amd import accounting
+        return accounting.gather_group(self.o.n_batches, int(self.off[-1]), self.W.stride_bytes)
 
 
 @pytest.fixture(scope="module", params=["medium", "large_sparse", "fanout_stress", "partition_share"])
