@@ -103,9 +103,10 @@ typedef struct rg_cache rg_cache;
  * Environment: RAPIDGNN_SPARSE_FRONTIER=1 / 0 forces / forbids the frontier
  * passes tuned for graphs of 10^7 nodes and more (default: chosen from
  * n_nodes); RAPIDGNN_BYTE_MAPS=1 / 0 forces / forbids the byte form of the
- * reached map (never used together with those passes); RAPIDGNN_SHORT_ROWS=1 / 0
- * forces / forbids the kernel that samples rows of up to 64 IDs four at a time
- * (default: in hops that mark with byte stores).  The result is the
+ * reached map (never used together with those passes); RAPIDGNN_SHORT_ROWS=0 / 1 / 2
+ * makes rows of up to 64 IDs be sampled one per wave / four at a time by a kernel
+ * of their own / four at a time inside the main kernel (default: 1 in hops that
+ * mark with byte stores, 2 in the others).  The result is the
  * same in every case.  The maps are drawn from a pool of blocks known to be
  * all-zero and handed back to it after the build has cleared what it touched;
  * RAPIDGNN_CHECK_ZERO_MAPS=1 makes every build verify that on the device first.

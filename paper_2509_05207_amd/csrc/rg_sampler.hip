@@ -584,6 +584,148 @@ __device__ __forceinline__ void sample_row(const int32_t *__restrict__ row, int 
     }
 }
 
+// ---------------------------------------------------------------- rows of up to SHORT_ROW IDs, four at a time
+// A wave that samples one short row at a time spends its time waiting: a row of 30 IDs is one load and a few dozen
+// instructions, and the next row's load cannot start much earlier than this row's ends.  Here a wave takes 64
+// consecutive frontier nodes, lists the ones with 1 .. SHORT_ROW neighbours -- shortest first, so that rows of a
+// round are of a kind -- and samples four of them at once, one per row of sixteen lanes (lane l of a row holds IDs
+// l, l + 16, l + 32, l + 48 of it), with the next four rows' IDs already on their way.  The f smallest keys of a
+// row: for rows of up to 16 IDs (one key per lane) by rank -- every key is compared with every other key of its row as
+// the register rotates through the sixteen lanes (DPP row rotation, no LDS), and the IDs whose key has fewer than f
+// smaller keys are the sample; for longer rows by the same bisection on the key value as everywhere else, the four
+// rows searching side by side, each lane counting its own row's sixteen bits of every lane mask.  Output positions
+// come from the lane masks, in row order, as in the other kernels.
+struct ShortRec {
+    int64_t row_begin, out;
+    uint64_t state;
+    int32_t deg;
+    uint32_t batch;
+};
+
+template <int R> __device__ __forceinline__ uint32_t rotate16(uint32_t x)      // the value R lanes away within the lane's row of sixteen
+{
+    return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, 0x120 + R, 0xF, 0xF, false);
+}
+
+// The number of keys of the lane's row of sixteen lanes (one key per lane) that are smaller than this lane's.
+__device__ __forceinline__ int count_smaller16(uint32_t k)
+{
+    int cnt = 0;
+#define RG_ROT(R) cnt += rotate16<R>(k) < k ? 1 : 0;
+    RG_ROT(1) RG_ROT(2) RG_ROT(3) RG_ROT(4) RG_ROT(5) RG_ROT(6) RG_ROT(7) RG_ROT(8)
+    RG_ROT(9) RG_ROT(10) RG_ROT(11) RG_ROT(12) RG_ROT(13) RG_ROT(14) RG_ROT(15)
+#undef RG_ROT
+    return cnt;
+}
+
+// This lane's row's sixteen bits of a lane mask, counted.
+__device__ __forceinline__ int popc_of_my_row(unsigned long long m, int lane) { return __popc((uint32_t)(m >> (lane & 48)) & 0xFFFFu); }
+
+// For each row of sixteen lanes on its own: the largest key value `cut` such that exactly f of the row's keys do not
+// exceed it.  k[e], e < E: the row's keys, a missing one stands as 0xFFFFFFFF; deg (> f in the rows that search, same
+// in all lanes of a row): how many there are; rows with searching == false ride along and get an arbitrary answer.
+// Bit by bit from the top, as kth_key_threshold does for a whole wave: the f-th smallest key stays inside
+// [lo, lo + 2^(bit+1)), and a row is done as soon as exactly f keys lie below the bracket's upper end -- for keys
+// spread over 32 bits after about log2(deg) + 2 steps; the loop ends when every row is done.
+template <int E>
+__device__ __forceinline__ uint32_t kth_key_threshold_rows(const uint32_t (&k)[4], int f, int deg, bool searching, int lane)
+{
+    uint32_t lo = 0, cut = 0xFFFFFFFFu;
+    int below_hi = deg;
+    bool done = !searching;
+    for (int bit = 31; bit >= 0; --bit) {
+        if (ballot64(!done) == 0ull) break;
+        const uint32_t t = lo | (1u << bit);
+        int c = 0;
+#pragma unroll
+        for (int e = 0; e < E; ++e) c += popc_of_my_row(ballot64(k[e] < t), lane);
+        if (!done) {
+            if (c >= f) below_hi = c; else lo = t;
+            cut = lo | ((1u << bit) - 1u);
+            done = below_hi == f;
+        }
+    }
+    return cut;
+}
+
+// The listed short rows (recs[0 .. count), shortest first; LDS) sampled four per round.  All 64 lanes call it.
+template <int MARK>
+__device__ __forceinline__ void sample_short_rows(const ShortRec *recs, int count, const int32_t *__restrict__ indices, int f,
+                                                  int32_t *__restrict__ samp_nbr, const ReachedMaps &reached, int lane)
+{
+    const int l16 = lane & 15, sg = lane >> 4;
+    const int n_it = (count + 3) >> 2;
+    // this lane's row of the round, and its IDs (0 where the row has none)
+    auto fetch = [&](int it, ShortRec &r, uint32_t (&u)[4]) {
+        const int slot = it * 4 + sg;
+        r = slot < count ? recs[slot] : ShortRec{0, 0, 0, 0, 0};
+        const int32_t *row = indices + r.row_begin;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) u[e] = l16 + 16 * e < r.deg ? (uint32_t)row[l16 + 16 * e] : 0u;
+    };
+    ShortRec r, r_next;
+    uint32_t u[4], u_next[4];
+    fetch(0, r, u);
+    for (int it = 0; it < n_it; ++it) {
+        if (it + 1 < n_it) fetch(it + 1, r_next, u_next);
+        const int deg = r.deg;
+        bool sel[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) sel[e] = l16 + 16 * e < deg;
+        const bool searching = deg > f;
+        if (ballot64(searching) != 0ull) {                       // some row of the round is longer than the fan-out
+            const uint32_t slo = (uint32_t)r.state, shi = (uint32_t)(r.state >> 32);
+            uint32_t k[4];
+#pragma unroll
+            for (int e = 0; e < 4; ++e) k[e] = sel[e] ? key32(slo, shi, u[e]) : 0xFFFFFFFFu;     // (a missing key's stand-in is never counted as smaller than anything)
+            if (ballot64(searching && deg > 16) == 0ull) {       // one key per lane: by rank
+                const int smaller = count_smaller16(k[0]);
+                if (searching) sel[0] = sel[0] && smaller < f;
+            } else {
+                uint32_t cut;
+                if (ballot64(searching && deg > 48) != 0ull) cut = kth_key_threshold_rows<4>(k, f, deg, searching, lane);
+                else if (ballot64(searching && deg > 32) != 0ull) cut = kth_key_threshold_rows<3>(k, f, deg, searching, lane);
+                else cut = kth_key_threshold_rows<2>(k, f, deg, searching, lane);
+                if (searching) {
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) sel[e] = sel[e] && k[e] <= cut;
+                }
+            }
+        }
+        // row order is ID 0 .. 15 (e = 0), 16 .. 31 (e = 1), ...: a selected ID's place is the number of selected IDs before it
+        const ReachedOfBatch reached_b = reached_of<MARK>(reached, r.batch);
+        int32_t *out = samp_nbr + r.out;
+        int base = 0;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            const uint32_t m16 = (uint32_t)(ballot64(sel[e]) >> (lane & 48)) & 0xFFFFu;       // the selected lanes of this lane's row
+            if (sel[e]) {
+                out[base + __popc(m16 & ((1u << l16) - 1u))] = (int32_t)u[e];
+                mark_reached<MARK>(reached_b, u[e]);
+            }
+            base += __popc(m16);
+        }
+        r = r_next;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) u[e] = u_next[e];
+    }
+}
+
+// Where a lane's short row goes in the list: shortest rows first, by the number of IDs per lane ((deg - 1) / 16), lane
+// order within a kind.  mine: this lane has a row of 1 .. SHORT_ROW IDs.  All 64 lanes call it.
+__device__ __forceinline__ int short_row_slot(bool mine, int deg, int lane)
+{
+    const int kind = mine ? (deg - 1) >> 4 : -1;
+    int at = 0;
+#pragma unroll
+    for (int c = 0; c < 4; ++c) {
+        const unsigned long long m = ballot64(kind == c);
+        if (c < kind) at += __popcll(m);
+        else if (c == kind) at += lanes_below(m, lane);
+    }
+    return at;
+}
+
 // Per tile job j: the frontier position i whose row it belongs to (tile_off[i] <= j < tile_off[i + 1]), where its piece of
 // the row starts in `indices`, how long it is (near-equal pieces, each longer than 2 * RG_MAX_FANOUT) and the node's
 // stream S_v.  Written by the nodes that have tiles, so that a wave finds everything about its piece in one round of
@@ -620,7 +762,8 @@ struct HopArgs {
     const int32_t *indices;
     const int32_t *frontier; int64_t n_frontier;
     int64_t n_full_groups, n_units;                                    // set by launch_hop: see there
-    int min_deg;                                                       // rows of up to this many IDs are somebody else's (sample_short_kernel)
+    int min_deg;                                                       // rows of up to this many IDs are not sampled one per wave ...
+    int short_inline;                                                  // ... but four at a time: 1 = by sample_kernel<.., true>, a group's short rows first; 0 = by sample_short_kernel
     NodeRecs rec;
     uint32_t fanout;
     const int64_t *samp_off; int32_t *samp_nbr;
@@ -641,10 +784,13 @@ __device__ __forceinline__ int64_t grab_work(unsigned long long *counter, int la
 
 // The work of a hop: n_tiles tiles of long rows (done first, so the longest-running work starts first) and the groups
 // of 64 consecutive frontier nodes.
-template <int CAP, int MARK>
+// SHORT_INLINE: each group's rows of up to SHORT_ROW IDs are sampled four at a time before its other rows (an
+// instantiation of its own: the code costs the streaming loop a few registers).
+template <int CAP, int MARK, bool SHORT_INLINE>
 __global__ void __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(CAP <= 256 ? 7 : 1))) sample_kernel(HopArgs a)
 {
     __shared__ uint32_t buf[CAP];
+    __shared__ ShortRec short_recs[SHORT_INLINE ? 64 : 1];
     const int lane = threadIdx.x;
     const int f = (int)a.fanout;
     // Tiles first, dealt out in turn (workgroup k takes tiles k, k + grid, ...): they are all of about the same
@@ -680,6 +826,19 @@ __global__ void __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(CAP <= 
         const uint32_t b_lane = in ? a.rec.batch[i_lane] : 0u;
         const int64_t S_lane = in ? (int64_t)a.rec.state[i_lane] : 0;
         const int64_t out_lane = in ? a.samp_off[i_lane] : 0;
+        if (SHORT_INLINE) {
+            // the group's rows of up to SHORT_ROW IDs first, four at a time (their marks and scattered little reads then
+            // run beside the streaming of the other waves' long rows)
+            const bool mine = in && deg_lane > 0 && deg_lane <= SHORT_ROW;
+            const int count = __popcll(ballot64(mine));
+            if (count != 0) {
+                const int at = short_row_slot(mine, deg_lane, lane);
+                __syncthreads();
+                if (mine) short_recs[at] = ShortRec{rb_lane, out_lane, (uint64_t)S_lane, deg_lane, b_lane};
+                __syncthreads();
+                sample_short_rows<MARK>(short_recs, count, a.indices, f, a.samp_nbr, a.reached, lane);
+            }
+        }
         unsigned long long todo = ballot64(deg_lane > a.min_deg && deg_lane <= BIG_ROW);
         if (todo == 0ull) continue;
         // the first node's leading 64 IDs; from then on the next node's are fetched while the current one is sampled
@@ -745,70 +904,6 @@ __global__ void __launch_bounds__(64) sample_merge_kernel(HopArgs a)
 }
 
 
-// ---------------------------------------------------------------- rows of up to SHORT_ROW IDs, four at a time
-// A wave that samples one short row at a time spends its time waiting: a row of 30 IDs is one load and a few dozen
-// instructions, and the next row's load cannot start much earlier than this row's ends.  Here a wave takes 64
-// consecutive frontier nodes, lists the ones with 1 .. SHORT_ROW neighbours -- shortest first, so that rows of a
-// round are of a kind -- and samples four of them at once, one per row of sixteen lanes (lane l of a row holds IDs
-// l, l + 16, l + 32, l + 48 of it), with the next four rows' IDs already on their way.  The f smallest keys of a
-// row: for rows of up to 16 IDs (one key per lane) by rank -- every key is compared with every other key of its row as
-// the register rotates through the sixteen lanes (DPP row rotation, no LDS), and the IDs whose key has fewer than f
-// smaller keys are the sample; for longer rows by the same bisection on the key value as everywhere else, the four
-// rows searching side by side, each lane counting its own row's sixteen bits of every lane mask.  Output positions
-// come from the lane masks, in row order, as in the other kernels.
-struct ShortRec {
-    int64_t row_begin, out;
-    uint64_t state;
-    int32_t deg;
-    uint32_t batch;
-};
-
-template <int R> __device__ __forceinline__ uint32_t rotate16(uint32_t x)      // the value R lanes away within the lane's row of sixteen
-{
-    return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, 0x120 + R, 0xF, 0xF, false);
-}
-
-// The number of keys of the lane's row of sixteen lanes (one key per lane) that are smaller than this lane's.
-__device__ __forceinline__ int count_smaller16(uint32_t k)
-{
-    int cnt = 0;
-#define RG_ROT(R) cnt += rotate16<R>(k) < k ? 1 : 0;
-    RG_ROT(1) RG_ROT(2) RG_ROT(3) RG_ROT(4) RG_ROT(5) RG_ROT(6) RG_ROT(7) RG_ROT(8)
-    RG_ROT(9) RG_ROT(10) RG_ROT(11) RG_ROT(12) RG_ROT(13) RG_ROT(14) RG_ROT(15)
-#undef RG_ROT
-    return cnt;
-}
-
-// This lane's row's sixteen bits of a lane mask, counted.
-__device__ __forceinline__ int popc_of_my_row(unsigned long long m, int lane) { return __popc((uint32_t)(m >> (lane & 48)) & 0xFFFFu); }
-
-// For each row of sixteen lanes on its own: the largest key value `cut` such that exactly f of the row's keys do not
-// exceed it.  k[e], e < E: the row's keys, a missing one stands as 0xFFFFFFFF; deg (> f in the rows that search, same
-// in all lanes of a row): how many there are; rows with searching == false ride along and get an arbitrary answer.
-// Bit by bit from the top, as kth_key_threshold does for a whole wave: the f-th smallest key stays inside
-// [lo, lo + 2^(bit+1)), and a row is done as soon as exactly f keys lie below the bracket's upper end -- for keys
-// spread over 32 bits after about log2(deg) + 2 steps; the loop ends when every row is done.
-template <int E>
-__device__ __forceinline__ uint32_t kth_key_threshold_rows(const uint32_t (&k)[4], int f, int deg, bool searching, int lane)
-{
-    uint32_t lo = 0, cut = 0xFFFFFFFFu;
-    int below_hi = deg;
-    bool done = !searching;
-    for (int bit = 31; bit >= 0; --bit) {
-        if (ballot64(!done) == 0ull) break;
-        const uint32_t t = lo | (1u << bit);
-        int c = 0;
-#pragma unroll
-        for (int e = 0; e < E; ++e) c += popc_of_my_row(ballot64(k[e] < t), lane);
-        if (!done) {
-            if (c >= f) below_hi = c; else lo = t;
-            cut = lo | ((1u << bit) - 1u);
-            done = below_hi == f;
-        }
-    }
-    return cut;
-}
-
 struct ShortArgs {
     const int32_t *indices;
     int64_t n_frontier;
@@ -822,85 +917,19 @@ template <int MARK>
 __global__ void __launch_bounds__(64) sample_short_kernel(ShortArgs a)
 {
     __shared__ ShortRec recs[64];
-    const int lane = threadIdx.x, l16 = lane & 15, sg = lane >> 4;
-    const int f = (int)a.fanout;
+    const int lane = threadIdx.x;
     const int64_t n_groups = (a.n_frontier + 63) >> 6;
     for (int64_t w = blockIdx.x; w < n_groups; w += gridDim.x) {
         const int64_t i_lane = (w << 6) + lane;
         const int deg_lane = i_lane < a.n_frontier ? a.rec.deg[i_lane] : 0;
         const bool mine = deg_lane > 0 && deg_lane <= SHORT_ROW;
-        const unsigned long long short_mask = ballot64(mine);
-        const int count = __popcll(short_mask);
+        const int count = __popcll(ballot64(mine));
         if (count == 0) continue;
+        const int at = short_row_slot(mine, deg_lane, lane);
         __syncthreads();                                            // the previous group's records have been read by every lane
-        if (mine) {
-            // shortest rows first: by the number of IDs per lane ((deg - 1) / 16), lane order within a kind
-            const int kind = (deg_lane - 1) >> 4;
-            int at = 0;
-#pragma unroll
-            for (int c = 0; c < 4; ++c) {
-                const unsigned long long m = ballot64(mine && ((deg_lane - 1) >> 4) == c);
-                if (c < kind) at += __popcll(m);
-                else if (c == kind) at += lanes_below(m, lane);
-            }
-            recs[at] = ShortRec{a.rec.row_begin[i_lane], a.samp_off[i_lane], a.rec.state[i_lane], deg_lane, a.rec.batch[i_lane]};
-        }
+        if (mine) recs[at] = ShortRec{a.rec.row_begin[i_lane], a.samp_off[i_lane], a.rec.state[i_lane], deg_lane, a.rec.batch[i_lane]};
         __syncthreads();
-        const int n_it = (count + 3) >> 2;
-        // this lane's row of the round, and its IDs (0 where the row has none)
-        auto fetch = [&](int it, ShortRec &r, uint32_t (&u)[4]) {
-            const int slot = it * 4 + sg;
-            r = slot < count ? recs[slot] : ShortRec{0, 0, 0, 0, 0};
-            const int32_t *row = a.indices + r.row_begin;
-#pragma unroll
-            for (int e = 0; e < 4; ++e) u[e] = l16 + 16 * e < r.deg ? (uint32_t)row[l16 + 16 * e] : 0u;
-        };
-        ShortRec r, r_next;
-        uint32_t u[4], u_next[4];
-        fetch(0, r, u);
-        for (int it = 0; it < n_it; ++it) {
-            if (it + 1 < n_it) fetch(it + 1, r_next, u_next);
-            const int deg = r.deg;
-            bool sel[4];
-#pragma unroll
-            for (int e = 0; e < 4; ++e) sel[e] = l16 + 16 * e < deg;
-            const bool searching = deg > f;
-            if (ballot64(searching) != 0ull) {                       // some row of the round is longer than the fan-out
-                const uint32_t slo = (uint32_t)r.state, shi = (uint32_t)(r.state >> 32);
-                uint32_t k[4];
-#pragma unroll
-                for (int e = 0; e < 4; ++e) k[e] = sel[e] ? key32(slo, shi, u[e]) : 0xFFFFFFFFu;     // (a missing key's stand-in is never counted as smaller than anything)
-                if (ballot64(searching && deg > 16) == 0ull) {       // one key per lane: by rank
-                    const int smaller = count_smaller16(k[0]);
-                    if (searching) sel[0] = sel[0] && smaller < f;
-                } else {
-                    uint32_t cut;
-                    if (ballot64(searching && deg > 48) != 0ull) cut = kth_key_threshold_rows<4>(k, f, deg, searching, lane);
-                    else if (ballot64(searching && deg > 32) != 0ull) cut = kth_key_threshold_rows<3>(k, f, deg, searching, lane);
-                    else cut = kth_key_threshold_rows<2>(k, f, deg, searching, lane);
-                    if (searching) {
-#pragma unroll
-                        for (int e = 0; e < 4; ++e) sel[e] = sel[e] && k[e] <= cut;
-                    }
-                }
-            }
-            // row order is ID 0 .. 15 (e = 0), 16 .. 31 (e = 1), ...: a selected ID's place is the number of selected IDs before it
-            const ReachedOfBatch reached_b = reached_of<MARK>(a.reached, r.batch);
-            int32_t *out = a.samp_nbr + r.out;
-            int base = 0;
-#pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                const uint32_t m16 = (uint32_t)(ballot64(sel[e]) >> (lane & 48)) & 0xFFFFu;       // the selected lanes of this lane's row
-                if (sel[e]) {
-                    out[base + __popc(m16 & ((1u << l16) - 1u))] = (int32_t)u[e];
-                    mark_reached<MARK>(reached_b, u[e]);
-                }
-                base += __popc(m16);
-            }
-            r = r_next;
-#pragma unroll
-            for (int e = 0; e < 4; ++e) u[e] = u_next[e];
-        }
+        sample_short_rows<MARK>(recs, count, a.indices, (int)a.fanout, a.samp_nbr, a.reached, lane);
     }
 }
 
@@ -919,13 +948,15 @@ template <int CAP, int MARK>
 static rg_status launch_hop(const HopArgs &args, int n_cu, unsigned merge_grid, bool fine_tail, bool fine_if_few, hipStream_t st)
 {
     HopArgs a = args;
-    static std::atomic<int> asked{0};         // the same answer every time; asked once (schedules may be built from several threads)
-    int per_cu = asked.load(std::memory_order_relaxed);
+    static std::atomic<int> asked[2] = {{0}, {0}};      // the same answer every time; asked once (schedules may be built from several threads)
+    const int which = a.short_inline ? 1 : 0;
+    int per_cu = asked[which].load(std::memory_order_relaxed);
     if (per_cu == 0) {
         int v = 0;
-        RG_HIP(hipOccupancyMaxActiveBlocksPerMultiprocessor(&v, sample_kernel<CAP, MARK>, 64, 0));
+        if (which) RG_HIP(hipOccupancyMaxActiveBlocksPerMultiprocessor(&v, sample_kernel<CAP, MARK, true>, 64, 0));
+        else RG_HIP(hipOccupancyMaxActiveBlocksPerMultiprocessor(&v, sample_kernel<CAP, MARK, false>, 64, 0));
         per_cu = v > 0 ? v : 1;
-        asked.store(per_cu, std::memory_order_relaxed);
+        asked[which].store(per_cu, std::memory_order_relaxed);
     }
     // Groups of 64 nodes, except that with fine_tail the last 128 nodes per resident wave (and always what is left of
     // the frontier after the last whole group) are handed out 16 at a time.
@@ -936,7 +967,8 @@ static rg_status launch_hop(const HopArgs &args, int n_cu, unsigned merge_grid, 
     a.n_units = a.n_full_groups + (a.n_frontier - a.n_full_groups * 64 + 15) / 16;
     const int64_t n_work = a.n_tiles + a.n_units;
     const unsigned grid = (unsigned)std::max<int64_t>(1, std::min<int64_t>(n_work, resident));
-    hipLaunchKernelGGL((sample_kernel<CAP, MARK>), dim3(grid), dim3(64), 0, st, a);
+    if (which) hipLaunchKernelGGL((sample_kernel<CAP, MARK, true>), dim3(grid), dim3(64), 0, st, a);
+    else hipLaunchKernelGGL((sample_kernel<CAP, MARK, false>), dim3(grid), dim3(64), 0, st, a);
     if (a.n_tiles > 0) hipLaunchKernelGGL((sample_merge_kernel<CAP, MARK>), dim3(merge_grid), dim3(64), 0, st, a);
     return RG_OK;
 }
@@ -1069,26 +1101,26 @@ rg_status sample_hop(const rg_graph *g, HopData &cur, uint32_t beta, const uint6
     }
 
     if (fanout > 0 && n_cur > 0) {
-        // Rows of up to SHORT_ROW IDs go to a kernel of their own where the hop marks with plain byte stores (same samples
-        // either way; RAPIDGNN_SHORT_ROWS=1 / 0 forces / forbids it, for tests and tuning).  Measured: fanout_stress
-        // (rows mostly copied whole, byte marks) 4.3 -> 3.8 ms; where marks are atomic ORs the kernel of its own is bound
-        // by their rate (large_sparse: 58 M of them in 2.6 ms, 22 G/s) and the hop as a whole gets slower, 12.3 -> 13.0 ms,
-        // also with the two kernels side by side on two streams (13.1 ms): interleaved with the streaming of long rows in
-        // one kernel the atomics cost less.
-        bool short_rows_apart = sums[2] > 0 && use_bytes;
-        if (const char *force = getenv("RAPIDGNN_SHORT_ROWS")) short_rows_apart = force[0] == '1';
+        // Rows of up to SHORT_ROW IDs are sampled four at a time wherever a frontier has any: by a kernel of their own
+        // where the hop marks with plain byte stores, inside the other kernel (each group's short rows first) where marks are
+        // atomic ORs -- a kernel of nothing but short rows is then bound by the rate of those atomics (large_sparse: 58 M of
+        // them in 2.6 ms, 22 G/s), while between the streaming of long rows they cost next to nothing.  Same samples in
+        // every case; RAPIDGNN_SHORT_ROWS = 0 / 1 / 2 forces one row per wave / the kernel of their own / the inline form.
+        int short_mode = sums[2] == 0 ? 0 : use_bytes ? 1 : 2;
+        if (const char *force = getenv("RAPIDGNN_SHORT_ROWS")) short_mode = force[0] == '1' ? 1 : force[0] == '2' ? 2 : 0;
+        const bool short_rows_apart = short_mode == 1;
         const uint32_t need = fanout + 64;
         const int mark = need > 256 ? MARK_BITS : all_flags && use_bytes ? MARK_BYTES_ALL : all_flags ? MARK_BITS_ALL : use_bytes ? MARK_BYTES : MARK_BITS;
         unsigned long long *next_work = nullptr;
         RG_TRY(tmp.dev_n<unsigned long long>(1, &next_work));
         RG_HIP(hipMemsetAsync(next_work, 0, sizeof(unsigned long long), st));
-        HopArgs a{g->indices, cur.ids, n_cur, 0, 0, short_rows_apart ? SHORT_ROW : 0, rec, fanout, cur.samp_off, cur.samp_nbr, tile_off, tile, n_tiles, tile_out, reached, next_work};
+        HopArgs a{g->indices, cur.ids, n_cur, 0, 0, short_mode != 0 ? SHORT_ROW : 0, short_mode == 2 ? 1 : 0, rec, fanout, cur.samp_off, cur.samp_nbr, tile_off, tile, n_tiles, tile_out, reached, next_work};
         ScopedTimer tm(KG_SAMPLER, st);
         const unsigned merge_grid = (unsigned)std::max<int64_t>(1, std::min<int64_t>(n_tiles, (int64_t)n_cu * 64));
         // worth it where a group is long work: rows of a thousand IDs on average, tiles aside (short rows finish a
         // group of 64 in no time, and four times the requests to the work counter then cost more than the tail does;
         // measured: Medium, 2,500 IDs per row, 4 % faster; large_sparse and partition_share, a few hundred, 1-8 % slower)
-        const unsigned long long ids_here = sums[1] - (short_rows_apart ? sums[3] : 0), rows_here = (unsigned long long)n_cur - (short_rows_apart ? sums[2] : 0);
+        const unsigned long long ids_here = sums[1] - (short_mode != 0 ? sums[3] : 0), rows_here = (unsigned long long)n_cur - (short_mode != 0 ? sums[2] : 0);
         const bool fine_tail = ids_here >= 1024ull * rows_here;
         // a frontier that does not give every resident wave a group of 64 (the seed hop) is split finer from rows of 256 IDs on
         const bool fine_if_few = ids_here >= 256ull * rows_here;

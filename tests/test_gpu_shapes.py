@@ -60,15 +60,17 @@ SHAPES = [
 
 
 @pytest.mark.parametrize("shape", range(len(SHAPES)))
-@pytest.mark.parametrize("sampler,maps", [("keys", "auto"), ("keys", "bytes"), ("keys", "bits"), ("keys", "one_row_per_wave"), ("keys", "four_short_rows_per_wave"),
+@pytest.mark.parametrize("sampler,maps", [("keys", "auto"), ("keys", "bytes"), ("keys", "bits"), ("keys", "one_row_per_wave"), ("keys", "four_short_rows_per_wave"), ("keys", "four_short_rows_inline"),
                                           ("positions", "auto")])
 def test_random_shape(rg, orc, shape, sampler, maps, monkeypatch):
     if maps in ("bytes", "bits"):                        # the form of the reached-ID map, forced (chosen per hop otherwise)
         monkeypatch.setenv("RAPIDGNN_BYTE_MAPS", "1" if maps == "bytes" else "0")
     if maps == "one_row_per_wave":                       # without the kernel that samples four short rows at a time ...
         monkeypatch.setenv("RAPIDGNN_SHORT_ROWS", "0")
-    if maps == "four_short_rows_per_wave":               # ... and with it in every hop (by default: in hops that mark with byte stores)
+    if maps == "four_short_rows_per_wave":               # ... with it in every hop (by default: in hops that mark with byte stores) ...
         monkeypatch.setenv("RAPIDGNN_SHORT_ROWS", "1")
+    if maps == "four_short_rows_inline":                 # ... and with the same done inside the other kernel (by default: in hops that mark with atomic ORs)
+        monkeypatch.setenv("RAPIDGNN_SHORT_ROWS", "2")
     n, classes, fanout, batch, n_train = SHAPES[shape]
     rng = np.random.default_rng(4000 + shape)
     indptr, indices = random_graph(rng, n, classes)
