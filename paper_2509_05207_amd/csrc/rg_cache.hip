@@ -44,6 +44,7 @@ struct SelectState {
 constexpr int TOPK_THREADS = 256;
 constexpr int DIGIT_BITS = 8;
 constexpr int DIGIT_BINS = 1 << DIGIT_BITS;
+constexpr int BIN_COPIES = 64;            // the digit histogram is kept in this many copies, summed when a digit is chosen
 
 // QUADS: a lane takes four consecutive nodes per round (one 16-byte and one 4-byte load; is_local must be 4-byte
 // aligned), the few nodes after the last whole quad one by one.
@@ -57,31 +58,59 @@ __global__ void __launch_bounds__(TOPK_THREADS) digit_histogram_kernel(const uin
     __syncthreads();
     const uint32_t prefix = stp->prefix, pmask = stp->prefix_mask;
     if (stp->take_all) return;
-    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
-    const int64_t t0 = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     auto count = [&](uint32_t fv, uint32_t local) {
         if (fv != 0 && !local && (fv & pmask) == prefix) atomicAdd(&h[(fv >> shift) & (DIGIT_BINS - 1)], 1u);
     };
     int64_t done = 0;
     if (QUADS) {
-        const int64_t n_quads = n >> 2;
-        for (int64_t q = t0; q < n_quads; q += stride) {
-            const uint4 fv = reinterpret_cast<const uint4 *>(freq)[q];
-            const uint32_t loc = reinterpret_cast<const uint32_t *>(is_local)[q];
+        auto count4 = [&](const uint4 fv, uint32_t loc) {
+            if ((fv.x | fv.y | fv.z | fv.w) == 0u) return;                     // most nodes are never listed
             count(fv.x, loc & 0xFFu); count(fv.y, (loc >> 8) & 0xFFu); count(fv.z, (loc >> 16) & 0xFFu); count(fv.w, loc >> 24);
+        };
+        // a workgroup reads one contiguous span of quads, four independent loads of each kind in flight per lane
+        const int64_t n_quads = n >> 2;
+        const int64_t span = (n_quads + gridDim.x - 1) / gridDim.x;
+        const int64_t q_end = min(n_quads, (int64_t)(blockIdx.x + 1) * span);
+        int64_t q = (int64_t)blockIdx.x * span + threadIdx.x;
+        for (; q + 3 * TOPK_THREADS < q_end; q += 4 * TOPK_THREADS) {
+            uint4 fv[4]; uint32_t loc[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) fv[u] = reinterpret_cast<const uint4 *>(freq)[q + u * TOPK_THREADS];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) loc[u] = reinterpret_cast<const uint32_t *>(is_local)[q + u * TOPK_THREADS];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) count4(fv[u], loc[u]);
         }
+        for (; q < q_end; q += TOPK_THREADS) count4(reinterpret_cast<const uint4 *>(freq)[q], reinterpret_cast<const uint32_t *>(is_local)[q]);
         done = n_quads << 2;
     }
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    const int64_t t0 = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     for (int64_t v = done + t0; v < n; v += stride) count(freq[v], is_local[v]);
     __syncthreads();
+    // workgroups spread their adds over BIN_COPIES copies of the bins: few digits are in use, and thousands of adds
+    // to the same few addresses would queue up behind each other
+    unsigned long long *mine = bins + (size_t)(blockIdx.x % BIN_COPIES) * DIGIT_BINS;
     for (int k = threadIdx.x; k < DIGIT_BINS; k += TOPK_THREADS)
-        if (h[k]) atomicAdd(&bins[k], (unsigned long long)h[k]);
+        if (h[k]) atomicAdd(&mine[k], (unsigned long long)h[k]);
 }
 
-// One thread: walk the digit bins from the top until `want` is covered.
-__global__ void choose_digit_kernel(SelectState *__restrict__ stp, unsigned long long *__restrict__ bins, int shift, int first_pass, uint64_t K)
+// One workgroup of DIGIT_BINS threads: sum the copies of each bin (and clear them for the next pass), then one thread
+// walks the bins from the top until `want` is covered.
+__global__ void __launch_bounds__(DIGIT_BINS) choose_digit_kernel(SelectState *__restrict__ stp, unsigned long long *__restrict__ bins_copies, int shift,
+                                                                  int first_pass, uint64_t K)
 {
-    if (threadIdx.x != 0 || blockIdx.x != 0) return;
+    __shared__ unsigned long long bins[DIGIT_BINS];
+    {
+        unsigned long long sum = 0;
+        for (int cpy = 0; cpy < BIN_COPIES; ++cpy) {
+            sum += bins_copies[(size_t)cpy * DIGIT_BINS + threadIdx.x];
+            bins_copies[(size_t)cpy * DIGIT_BINS + threadIdx.x] = 0;
+        }
+        bins[threadIdx.x] = sum;
+    }
+    __syncthreads();
+    if (threadIdx.x != 0) return;
     SelectState st = *stp;
     if (first_pass) {
         uint64_t tot = 0;
@@ -103,7 +132,6 @@ __global__ void choose_digit_kernel(SelectState *__restrict__ stp, unsigned long
         st.prefix_mask |= (uint32_t)(DIGIT_BINS - 1) << shift;
         if (shift == 0) { st.t = st.prefix; st.r = st.want; }
     }
-    for (int k = 0; k < DIGIT_BINS; ++k) bins[k] = 0;
     *stp = st;
 }
 
@@ -147,6 +175,7 @@ __device__ __forceinline__ void classify_mine(const uint32_t *__restrict__ freq,
     for (int h = 0; h < SEL_PER_THREAD / 8; ++h) classify_eight<ALIGNED8>(freq, is_local, first + 8 * h, n, st, c + 8 * h);
 }
 
+template <int THREADS = TOPK_THREADS>
 __device__ __forceinline__ uint64_t block_exclusive_scan_u64(uint64_t x, uint64_t *total, uint64_t *lds)
 {
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -158,7 +187,7 @@ __device__ __forceinline__ uint64_t block_exclusive_scan_u64(uint64_t x, uint64_
     if (lane == 63) lds[wave] = incl;
     __syncthreads();
     uint64_t base = 0, tot = 0;
-    for (int w = 0; w < TOPK_THREADS / 64; ++w) {
+    for (int w = 0; w < THREADS / 64; ++w) {
         const uint64_t s = lds[w];
         if (w < wave) base += s;
         tot += s;
@@ -185,20 +214,21 @@ __global__ void __launch_bounds__(TOPK_THREADS) select_block_totals(const uint32
     if (threadIdx.x == 0) block_tot[blockIdx.x] = tot;
 }
 
-// One workgroup; a thread takes eight consecutive totals per round.
-__global__ void __launch_bounds__(TOPK_THREADS) select_scan_totals(uint64_t *__restrict__ block_tot, int64_t n_blocks)
+// One workgroup of SCAN_THREADS; a thread takes sixteen consecutive totals per round.
+constexpr int SCAN_THREADS = 1024;
+__global__ void __launch_bounds__(SCAN_THREADS) select_scan_totals(uint64_t *__restrict__ block_tot, int64_t n_blocks)
 {
-    __shared__ uint64_t lds[TOPK_THREADS / 64];
+    __shared__ uint64_t lds[SCAN_THREADS / 64];
     uint64_t carry = 0;
-    for (int64_t base = 0; base < n_blocks; base += (int64_t)TOPK_THREADS * 8) {
-        const int64_t i0 = base + (int64_t)threadIdx.x * 8;
-        uint64_t x[8], sum = 0;
+    for (int64_t base = 0; base < n_blocks; base += (int64_t)SCAN_THREADS * 16) {
+        const int64_t i0 = base + (int64_t)threadIdx.x * 16;
+        uint64_t x[16], sum = 0;
 #pragma unroll
-        for (int k = 0; k < 8; ++k) { x[k] = i0 + k < n_blocks ? block_tot[i0 + k] : 0; sum += x[k]; }
+        for (int k = 0; k < 16; ++k) { x[k] = i0 + k < n_blocks ? block_tot[i0 + k] : 0; sum += x[k]; }
         uint64_t tot;
-        uint64_t run = carry + block_exclusive_scan_u64(sum, &tot, lds);
+        uint64_t run = carry + block_exclusive_scan_u64<SCAN_THREADS>(sum, &tot, lds);
 #pragma unroll
-        for (int k = 0; k < 8; ++k) {
+        for (int k = 0; k < 16; ++k) {
             if (i0 + k < n_blocks) block_tot[i0 + k] = run;
             run += x[k];
         }
@@ -444,9 +474,9 @@ static rg_status build_cache_impl(const rg_schedule *const *epochs, uint32_t n_e
     SelectState *stp = nullptr;
     unsigned long long *bins = nullptr;
     RG_TRY(tmp.dev_n<SelectState>(1, &stp));
-    RG_TRY(tmp.dev_n<unsigned long long>(DIGIT_BINS, &bins));
+    RG_TRY(tmp.dev_n<unsigned long long>((uint64_t)BIN_COPIES * DIGIT_BINS, &bins));
     RG_HIP(hipMemsetAsync(stp, 0, sizeof(SelectState), st));
-    RG_HIP(hipMemsetAsync(bins, 0, DIGIT_BINS * sizeof(unsigned long long), st));
+    RG_HIP(hipMemsetAsync(bins, 0, (size_t)BIN_COPIES * DIGIT_BINS * sizeof(unsigned long long), st));
     int bits = 1;
     while (bits < 32 && (max_freq >> bits) != 0) ++bits;
     const int passes = (bits + DIGIT_BITS - 1) / DIGIT_BITS;
@@ -461,12 +491,12 @@ static rg_status build_cache_impl(const rg_schedule *const *epochs, uint32_t n_e
             const int shift = (passes - 1 - p) * DIGIT_BITS;
             if (local4) hipLaunchKernelGGL(digit_histogram_kernel<true>, dim3(grid), dim3(TOPK_THREADS), 0, st, c->freq, f->is_local, n, stp, shift, bins);
             else hipLaunchKernelGGL(digit_histogram_kernel<false>, dim3(grid), dim3(TOPK_THREADS), 0, st, c->freq, f->is_local, n, stp, shift, bins);
-            hipLaunchKernelGGL(choose_digit_kernel, dim3(1), dim3(64), 0, st, stp, bins, shift, p == 0 ? 1 : 0, K);
+            hipLaunchKernelGGL(choose_digit_kernel, dim3(1), dim3(DIGIT_BINS), 0, st, stp, bins, shift, p == 0 ? 1 : 0, K);
         }
         if (sel_blocks > 0) {
             if (local8) hipLaunchKernelGGL(select_block_totals<true>, dim3((unsigned)sel_blocks), dim3(TOPK_THREADS), 0, st, c->freq, f->is_local, n, stp, block_tot);
             else hipLaunchKernelGGL(select_block_totals<false>, dim3((unsigned)sel_blocks), dim3(TOPK_THREADS), 0, st, c->freq, f->is_local, n, stp, block_tot);
-            hipLaunchKernelGGL(select_scan_totals, dim3(1), dim3(TOPK_THREADS), 0, st, block_tot, sel_blocks);
+            hipLaunchKernelGGL(select_scan_totals, dim3(1), dim3(SCAN_THREADS), 0, st, block_tot, sel_blocks);
         }
     }
     SelectState hs;
@@ -486,16 +516,28 @@ static rg_status build_cache_impl(const rg_schedule *const *epochs, uint32_t n_e
     }
     RG_HIP(hipGetLastError());
 
-    // ---- a8: VectorPull -- one bulk gather of the selected rows out of the remote table
+    // ---- a8: VectorPull -- one bulk gather of the selected rows out of the remote table.  It streams rows while the
+    // plans below are bound by dependent lookups, and neither reads what the other writes: the fill goes to the
+    // library's helper stream and runs beside them.
     RG_TRY(c->arena.dev(c->K_eff * c->stride, &c->rows));
     if (tls_table_bytes_sink) tls_table_bytes_sink->store(c->K_eff * c->stride, std::memory_order_release);
+    struct Forked {                                       // declared after `tmp`: on every exit the fill has ended before tmp's blocks go back
+        hipStream_t side = nullptr;
+        ~Forked() { if (side) (void)hipStreamSynchronize(side); }
+    } forked;
     if (c->K_eff > 0) {
         int64_t *fill_entries = nullptr;
         RG_TRY(tmp.dev_n<int64_t>(c->K_eff, &fill_entries));
-        hipLaunchKernelGGL(fill_entries_kernel, dim3((unsigned)((c->K_eff + 255) / 256)), dim3(256), 0, st, c->cache_ids, c->K_eff, f->row_of, fill_entries);
+        hipStream_t side = nullptr;
+        RG_TRY(helper_stream(&side));
+        RG_HIP(hipEventRecord(c->ev_fork, st));
+        RG_HIP(hipStreamWaitEvent(side, c->ev_fork, 0));
+        forked.side = side;
+        hipLaunchKernelGGL(fill_entries_kernel, dim3((unsigned)((c->K_eff + 255) / 256)), dim3(256), 0, side, c->cache_ids, c->K_eff, f->row_of, fill_entries);
         RowSources src{(const uint8_t *)f->local_rows, f->local_stride, (const uint8_t *)c->rows, c->stride,
                        (const uint8_t *)f->remote_rows, f->remote_stride};
-        RG_TRY(launch_gather(fill_entries, (int64_t)c->K_eff, nullptr, 0, 1, src, f->row_bytes, (uint8_t *)c->rows, c->stride, st, KG_FILL));
+        RG_TRY(launch_gather(fill_entries, (int64_t)c->K_eff, nullptr, 0, 1, src, f->row_bytes, (uint8_t *)c->rows, c->stride, side, KG_FILL));
+        RG_HIP(hipEventRecord(c->ev_join, side));
     }
 
     // ---- a5/a9: plans, miss lists and counts for every batch of every epoch
@@ -511,7 +553,9 @@ static rg_status build_cache_impl(const rg_schedule *const *epochs, uint32_t n_e
         hipLaunchKernelGGL(route_table_kernel, dim3(grid), dim3(256), 0, st, n, rs, route);
     }
     for (uint32_t e = 0; e < n_epochs; ++e) RG_TRY(build_plan(epochs[e], route, rs, c->arena, tmp, st, &c->plans[e]));
+    if (forked.side) RG_HIP(hipStreamWaitEvent(st, c->ev_join, 0));
     RG_HIP(hipStreamSynchronize(st));
+    if (forked.side) { RG_HIP(hipStreamSynchronize(forked.side)); forked.side = nullptr; }
     tmp.drained();
     return RG_OK;
 }

@@ -365,6 +365,19 @@ template <typename H> void retire(H *h, std::vector<H *> Retired::*list)
 }
 }  // namespace
 
+rg_status helper_stream(hipStream_t *out)
+{
+    static std::mutex mu;
+    static hipStream_t streams[64] = {};
+    int dev = 0;
+    RG_HIP(hipGetDevice(&dev));
+    if (dev < 0 || dev >= 64) { set_error("helper_stream: device %d out of range", dev); return RG_EINVAL; }
+    std::lock_guard<std::mutex> lk(mu);
+    if (!streams[dev]) RG_HIP(hipStreamCreateWithFlags(&streams[dev], hipStreamNonBlocking));
+    *out = streams[dev];
+    return RG_OK;
+}
+
 void reap_retired(bool wait)
 {
     Retired &r = retired();

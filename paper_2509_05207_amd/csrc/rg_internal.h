@@ -215,6 +215,11 @@ class Readback {
 // a later library call once their readers have finished.  reap_retired(true) waits for all of them.
 void reap_retired(bool wait);
 
+// One non-blocking stream per device, owned by the library and kept until the process ends: a call that has two
+// independent pieces of device work forks the second onto it (event from the caller's stream, event back) so that
+// both run at once.  Calls from several threads share it, which orders their forked pieces but changes no result.
+rg_status helper_stream(hipStream_t *out);
+
 // Where a cache build on this thread reports the bytes of its table as soon as the table is allocated (NULL: nowhere).
 // The double-buffered cache sets it on its build thread so that the memory bound counts a C_sec under construction.
 extern thread_local std::atomic<uint64_t> *tls_table_bytes_sink;

@@ -386,8 +386,9 @@ __global__ void __launch_bounds__(FR_THREADS) fresh_emit_sparse_kernel(uint32_t 
                                                                        uint32_t *__restrict__ seen, uint8_t *__restrict__ seen_flags,
                                                                        uint64_t words_per_batch, uint32_t chunks,
                                                                        const int64_t *__restrict__ fresh_scan, const int64_t *__restrict__ cur_off,
-                                                                       int32_t *__restrict__ next)
+                                                                       int32_t *__restrict__ next, int keep_seen)
 {
+    // keep_seen == 0 (the last hop): nothing reads `seen` again, so the fresh IDs are not added to it
     __shared__ uint16_t lists[FR_THREADS / 64][FRS_WAVE_GROUPS];
     __shared__ int wave_tot[FR_THREADS / 64];
     const uint32_t c = blockIdx.x, b = blockIdx.y;
@@ -457,7 +458,7 @@ __global__ void __launch_bounds__(FR_THREADS) fresh_emit_sparse_kernel(uint32_t 
                         uint32_t x = w[k];
                         if (x) {
                             const uint32_t id0 = (uint32_t)((wave_w0 + (uint64_t)grp * FR_WORDS_PER_THREAD + k) << 5);
-                            seen[ag + k] |= x;
+                            if (keep_seen) seen[ag + k] |= x;
                             while (x) {
                                 const int bit = __ffs((int)x) - 1;
                                 x &= x - 1;
@@ -465,7 +466,7 @@ __global__ void __launch_bounds__(FR_THREADS) fresh_emit_sparse_kernel(uint32_t 
                             }
                         }
                     }
-                    seen_flags[ag >> 3] = 1;
+                    if (keep_seen) seen_flags[ag >> 3] = 1;
                 }
             }
             *reinterpret_cast<uint4 *>(reached + ag) = make_uint4(0, 0, 0, 0);
@@ -676,7 +677,7 @@ static rg_status build_schedule_impl(const rg_graph *g, const int32_t *train, ui
             ScopedTimer tm(KG_FRONTIER, st);
             hipLaunchKernelGGL(copy_prefix_kernel, dim3((unsigned)((n_cur + 255) / 256)), dim3(256), 0, st, cur.ids, cur.off_dev, nxt.off_dev, beta, n_cur, nxt.ids);
             if (sparse_maps)
-                hipLaunchKernelGGL(fresh_emit_sparse_kernel, dim3(chunks, beta), dim3(FR_THREADS), 0, st, reached_words, reached_flags, seen, seen_flags, wpb, chunks, fresh_scan, cur.off_dev, nxt.ids);
+                hipLaunchKernelGGL(fresh_emit_sparse_kernel, dim3(chunks, beta), dim3(FR_THREADS), 0, st, reached_words, reached_flags, seen, seen_flags, wpb, chunks, fresh_scan, cur.off_dev, nxt.ids, l + 1 < L ? 1 : 0);
             else if (marked_bytes)
                 hipLaunchKernelGGL(fresh_emit_kernel<true>, dim3(chunks, beta), dim3(FR_THREADS), 0, st, reached, reached_flags, seen, seen_flags, wpb, chunks, fresh_scan, cur.off_dev, nxt.ids);
             else
@@ -692,9 +693,18 @@ static rg_status build_schedule_impl(const rg_graph *g, const int32_t *train, ui
         RG_HIP(hipGetLastError());
     }
     {
+        // `seen` back to all-zero.  Clearing the flagged groups alone costs about eight times as much per group as a
+        // fill costs per group of the whole map (scattered 32-byte stores against a streaming fill), and a group is
+        // flagged by at least one input node: the fill wins unless fewer than an eighth of the groups can be flagged.
         ScopedTimer tm(KG_FRONTIER, st);
-        hipLaunchKernelGGL(clear_seen_kernel, dim3((unsigned)((n_groups / 8 + FR_THREADS - 1) / FR_THREADS)), dim3(FR_THREADS), 0, st, seen, seen_flags, n_groups / 8);
-        RG_HIP(hipGetLastError());
+        const uint64_t listed = L > 0 ? (uint64_t)s->hop[L].off_host[beta] : T;
+        if (listed > n_groups / 8) {
+            RG_HIP(hipMemsetAsync(seen, 0, n_groups * FR_WORDS_PER_THREAD * sizeof(uint32_t), st));
+            RG_HIP(hipMemsetAsync(seen_flags, 0, n_groups, st));
+        } else {
+            hipLaunchKernelGGL(clear_seen_kernel, dim3((unsigned)((n_groups / 8 + FR_THREADS - 1) / FR_THREADS)), dim3(FR_THREADS), 0, st, seen, seen_flags, n_groups / 8);
+            RG_HIP(hipGetLastError());
+        }
     }
     RG_HIP(hipStreamSynchronize(st));
     tmp.drained();
