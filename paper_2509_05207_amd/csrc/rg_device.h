@@ -123,21 +123,29 @@ struct ReachedForms {             // host side: the forms a schedule build holds
     uint8_t *flags;               // [n_batches * words_per_batch / 8]
     uint64_t words_per_batch;     // a multiple of 8
     bool bytes_allowed;           // the byte form is small enough to be worth having
+    bool paired;                  // `words` holds a 64-byte record per group of 256 IDs: the group's eight words of `reached`,
+                                  // then its eight words of `seen` (see paired_word)
 };
 struct ReachedMaps {              // the form one hop marks
     void *map;
     uint8_t *flags;
     uint64_t words_per_batch;
+    uint32_t paired;              // 1: the bit form in paired records
 };
 struct ReachedOfBatch {
     void *map;
     uint8_t *flags;
+    uint32_t paired;
 };
+// On graphs of 10^8 nodes a batch touches a few per cent of its groups, so the frontier passes read a group's words
+// of `reached` and of `seen` from two unrelated places each time.  Paired, both lie in one 64-byte record: word w of
+// a map that would hold both arrays apart is word paired_word(w) of the records (`seen`: eight words further on).
+__host__ __device__ __forceinline__ uint64_t paired_word(uint64_t w) { return ((w >> 3) << 4) | (w & 7); }
 template <int MARK>
 __device__ __forceinline__ ReachedOfBatch reached_of(const ReachedMaps &m, uint32_t batch)
 {
-    const uint64_t step = (MARK == MARK_BYTES || MARK == MARK_BYTES_ALL) ? m.words_per_batch << 5 : m.words_per_batch << 2;       // bytes per batch
-    return ReachedOfBatch{static_cast<uint8_t *>(m.map) + (uint64_t)batch * step, m.flags + (uint64_t)batch * (m.words_per_batch >> 3)};
+    const uint64_t step = (MARK == MARK_BYTES || MARK == MARK_BYTES_ALL) ? m.words_per_batch << 5 : m.words_per_batch << (2 + m.paired);       // bytes per batch
+    return ReachedOfBatch{static_cast<uint8_t *>(m.map) + (uint64_t)batch * step, m.flags + (uint64_t)batch * (m.words_per_batch >> 3), m.paired};
 }
 template <int MARK>
 __device__ __forceinline__ void mark_reached(const ReachedOfBatch &r, uint32_t u)
@@ -145,7 +153,11 @@ __device__ __forceinline__ void mark_reached(const ReachedOfBatch &r, uint32_t u
     if (MARK == MARK_NONE) return;
     if (MARK == MARK_BYTES_ALL) { static_cast<uint8_t *>(r.map)[u] = 1; return; }
     if (MARK == MARK_BYTES) static_cast<uint8_t *>(r.map)[u] = 1;
-    else (void)__hip_atomic_fetch_or(static_cast<uint32_t *>(r.map) + (u >> 5), 1u << (u & 31), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    else {
+        const uint32_t w = u >> 5;
+        (void)__hip_atomic_fetch_or(static_cast<uint32_t *>(r.map) + (r.paired ? (((w >> 3) << 4) | (w & 7)) : w), 1u << (u & 31), __ATOMIC_RELAXED,
+                                    __HIP_MEMORY_SCOPE_AGENT);
+    }
     if (MARK != MARK_BITS_ALL) r.flags[u >> 8] = 1;
 }
 

@@ -1068,7 +1068,7 @@ rg_status sample_hop(const rg_graph *g, HopData &cur, uint32_t beta, const uint6
     const uint64_t flag_bytes = maps.words_per_batch / 8 * (uint64_t)beta;
     const bool all_flags = sampler == RG_SAMPLER_KEYS && fanout > 0 && fanout + 64 <= 256 && (uint64_t)cur.n_samples >= 16 * flag_bytes;
     if (all_flags) RG_HIP(hipMemsetAsync(maps.flags, 1, flag_bytes, st));
-    const ReachedMaps reached{use_bytes ? (void *)maps.bytes : (void *)maps.words, maps.flags, maps.words_per_batch};
+    const ReachedMaps reached{use_bytes ? (void *)maps.bytes : (void *)maps.words, maps.flags, maps.words_per_batch, (!use_bytes && maps.paired) ? 1u : 0u};
     tmp.free_one(cnt);
     tmp.free_one(tiles);
     RG_TRY(keep.dev_n<int32_t>((uint64_t)cur.n_samples, &cur.samp_nbr));

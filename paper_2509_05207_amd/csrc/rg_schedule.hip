@@ -120,15 +120,16 @@ __global__ void check_train_kernel(const int32_t *__restrict__ train, uint64_t T
     if (m != 0ull && (threadIdx.x & 63) == 0) atomicAdd(n_bad, (unsigned long long)__popcll(m));
 }
 
+// paired: `seen` points at the first group's `seen` half of the paired records (see paired_word)
 __global__ void mark_seeds_kernel(const int32_t *__restrict__ seeds, uint64_t T, uint32_t batch_size, uint32_t *__restrict__ seen,
-                                  uint8_t *__restrict__ seen_flags, uint64_t words_per_batch, int64_t n_nodes)
+                                  uint8_t *__restrict__ seen_flags, uint64_t words_per_batch, int64_t n_nodes, int paired)
 {
     const uint64_t t = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (t >= T) return;
     const uint32_t v = (uint32_t)seeds[t];
     if ((int64_t)v >= n_nodes) return;          // (refused by the host as soon as it has read check_train_kernel's count)
     const uint64_t word = (t / batch_size) * words_per_batch + (v >> 5);
-    atomicOr(&seen[word], 1u << (v & 31));
+    atomicOr(&seen[paired ? paired_word(word) : word], 1u << (v & 31));
     seen_flags[word >> 3] = 1;
 }
 
@@ -313,15 +314,36 @@ __global__ void __launch_bounds__(FR_THREADS) fresh_emit_kernel(void *__restrict
 // a batch reaches a few 10^4 IDs out of 3.5 M words).  A thread owns eight consecutive groups, i.e. one 8-byte
 // load of flags; a cell is 16,384 words, so the grid is eight times smaller and an untouched cell costs one
 // flag load per thread.  The few flagged groups of a wave's 512 are first listed (in ascending order, through
-// LDS) and then dealt out one per lane, so that their loads -- two scattered 32-byte reads each -- are all in
-// flight at once instead of one after another in the lane that happens to own them.  Flagged groups are read
-// twice (count, then emit): they are few.
-constexpr int FRS_GROUPS = 8;                                            // groups per thread
-constexpr int FRS_WORDS_PER_THREAD = FR_WORDS_PER_THREAD * FRS_GROUPS;   // 64
-constexpr int FRS_CHUNK_WORDS = FR_THREADS * FRS_WORDS_PER_THREAD;       // 16384; words_per_batch is a multiple of 64
-constexpr int FRS_WAVE_GROUPS = 64 * FRS_GROUPS;                         // 512 groups per wave
-constexpr int FRS_ROUNDS = FRS_GROUPS;                                   // a lane takes at most eight listed groups
+// LDS) and then dealt out one per lane, so that their loads are all in flight at once instead of one after
+// another in the lane that happens to own them.  Flagged groups are read twice (count, then emit): they are few,
+// but each read lands in a memory page of its own, which is what these passes cost -- so here a group's words of
+// `reached` and of `seen` share one 64-byte record (see paired_word) and a visit is one scattered access, not two.
+constexpr int FRS_GROUPS = 8;                                            // groups per thread (a multiple of eight; 16 and 32 measure the same)
+constexpr int FRS_FLAG_WORDS = FRS_GROUPS / 8;                           // their flags, as 8-byte words
+constexpr int FRS_WORDS_PER_THREAD = FR_WORDS_PER_THREAD * FRS_GROUPS;   // words_per_batch is a multiple of this
+constexpr int FRS_CHUNK_WORDS = FR_THREADS * FRS_WORDS_PER_THREAD;
+constexpr int FRS_WAVE_GROUPS = 64 * FRS_GROUPS;                         // groups per wave
+constexpr int FRS_ROUNDS = FRS_GROUPS;                                   // a lane takes at most this many listed groups
 
+struct FrsFlags { unsigned long long w[FRS_FLAG_WORDS]; };
+
+__device__ __forceinline__ FrsFlags load_frs_flags(const uint8_t *flags, uint64_t first_group, bool inside)
+{
+    FrsFlags f;
+#pragma unroll
+    for (int k = 0; k < FRS_FLAG_WORDS; ++k) f.w[k] = inside ? reinterpret_cast<const unsigned long long *>(flags + first_group)[k] : 0ull;
+    return f;
+}
+
+__device__ __forceinline__ void clear_frs_flags(uint8_t *flags, uint64_t first_group, const FrsFlags &f)
+{
+#pragma unroll
+    for (int k = 0; k < FRS_FLAG_WORDS; ++k)
+        if (f.w[k] != 0ull) reinterpret_cast<unsigned long long *>(flags + first_group)[k] = 0ull;
+}
+
+// The large-graph passes work on paired records (see paired_word): `reached` points at the records, `seen` eight
+// words further on, and `at` is a group's first word in the records (twice its word in a map of its own).
 __device__ __forceinline__ int fresh_in_group(const uint32_t *__restrict__ reached, const uint32_t *__restrict__ seen, uint64_t at, uint32_t (&w)[8])
 {
     const uint4 r0 = *reinterpret_cast<const uint4 *>(reached + at), r1 = *reinterpret_cast<const uint4 *>(reached + at + 4);
@@ -336,14 +358,19 @@ __device__ __forceinline__ int fresh_in_group(const uint32_t *__restrict__ reach
 
 // Lists the wave's flagged groups in ascending order: list[0 .. total) holds their indices within the wave's 512
 // (lane * 8 + g).  fl: this lane's eight flag bytes.  Returns total (wave-uniform).  Ends with a block barrier.
-__device__ __forceinline__ int list_flagged_groups(unsigned long long fl, uint16_t *list /* this wave's [FRS_WAVE_GROUPS] */)
+__device__ __forceinline__ int list_flagged_groups(const FrsFlags &fl, uint16_t *list /* this wave's [FRS_WAVE_GROUPS] */)
 {
     const int lane = threadIdx.x & 63;
     // one bit per flagged group of this lane: a byte is non-zero iff, after OR-folding it onto its lowest bit, that bit is set
-    unsigned long long x = fl;
-    x |= x >> 4; x |= x >> 2; x |= x >> 1;
-    x &= 0x0101010101010101ull;
-    const int nf = __popcll(x);
+    unsigned long long x[FRS_FLAG_WORDS];
+    int nf = 0;
+#pragma unroll
+    for (int k = 0; k < FRS_FLAG_WORDS; ++k) {
+        unsigned long long y = fl.w[k];
+        y |= y >> 4; y |= y >> 2; y |= y >> 1;
+        x[k] = y & 0x0101010101010101ull;
+        nf += __popcll(x[k]);
+    }
     int incl = nf;
     for (int d = 1; d < 64; d <<= 1) {
         const int y = __shfl_up(incl, d, 64);
@@ -353,7 +380,7 @@ __device__ __forceinline__ int list_flagged_groups(unsigned long long fl, uint16
     int at = incl - nf;
 #pragma unroll
     for (int g = 0; g < FRS_GROUPS; ++g)
-        if ((x >> (8 * g)) & 1ull) list[at++] = (uint16_t)(lane * FRS_GROUPS + g);
+        if ((x[g >> 3] >> (8 * (g & 7))) & 1ull) list[at++] = (uint16_t)(lane * FRS_GROUPS + g);
     __syncthreads();
     return total;
 }
@@ -368,13 +395,13 @@ __global__ void __launch_bounds__(FR_THREADS) fresh_count_sparse_kernel(const ui
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const uint64_t w0 = (uint64_t)c * FRS_CHUNK_WORDS + (uint64_t)threadIdx.x * FRS_WORDS_PER_THREAD;
     const uint64_t at = (uint64_t)b * words_per_batch + w0;
-    const unsigned long long fl = w0 < words_per_batch ? *reinterpret_cast<const unsigned long long *>(flags + (at >> 3)) : 0ull;
+    const FrsFlags fl = load_frs_flags(flags, at >> 3, w0 < words_per_batch);
     const int total = list_flagged_groups(fl, lists[wave]);
     const uint64_t wave_at = (uint64_t)b * words_per_batch + (uint64_t)c * FRS_CHUNK_WORDS + (uint64_t)wave * (FRS_WAVE_GROUPS * FR_WORDS_PER_THREAD);
     int n = 0;
     for (int i = lane; i < total; i += 64) {
         uint32_t w[8];
-        n += fresh_in_group(reached, seen, wave_at + (uint64_t)lists[wave][i] * FR_WORDS_PER_THREAD, w);
+        n += fresh_in_group(reached, seen, 2 * (wave_at + (uint64_t)lists[wave][i] * FR_WORDS_PER_THREAD), w);
     }
     for (int o = 32; o > 0; o >>= 1) n += __shfl_down(n, o, 64);
     if (lane == 0) red[wave] = n;
@@ -397,7 +424,7 @@ __global__ void __launch_bounds__(FR_THREADS) fresh_emit_sparse_kernel(uint32_t 
     const bool any_fresh = fresh_scan[(uint64_t)b * chunks + c + 1] != scan_here;      // block-uniform
     const uint64_t w0 = (uint64_t)c * FRS_CHUNK_WORDS + (uint64_t)threadIdx.x * FRS_WORDS_PER_THREAD;
     const uint64_t at = (uint64_t)b * words_per_batch + w0;
-    const unsigned long long fl = w0 < words_per_batch ? *reinterpret_cast<const unsigned long long *>(flags + (at >> 3)) : 0ull;
+    const FrsFlags fl = load_frs_flags(flags, at >> 3, w0 < words_per_batch);
     const int total = list_flagged_groups(fl, lists[wave]);
     const uint64_t wave_w0 = (uint64_t)c * FRS_CHUNK_WORDS + (uint64_t)wave * (FRS_WAVE_GROUPS * FR_WORDS_PER_THREAD);   // first word of the wave's groups within the batch
     const uint64_t wave_at = (uint64_t)b * words_per_batch + wave_w0;
@@ -415,7 +442,7 @@ __global__ void __launch_bounds__(FR_THREADS) fresh_emit_sparse_kernel(uint32_t 
                 int n = 0;
                 if (i < total) {
                     uint32_t w[8];
-                    n = fresh_in_group(reached, seen, wave_at + (uint64_t)lists[wave][i] * FR_WORDS_PER_THREAD, w);
+                    n = fresh_in_group(reached, seen, 2 * (wave_at + (uint64_t)lists[wave][i] * FR_WORDS_PER_THREAD), w);
                     if (r == 0) {
                         n_first = n;
 #pragma unroll
@@ -450,7 +477,7 @@ __global__ void __launch_bounds__(FR_THREADS) fresh_emit_sparse_kernel(uint32_t 
                     ng = n_first;
 #pragma unroll
                     for (int k = 0; k < 8; ++k) w[k] = w_first[k];
-                } else ng = fresh_in_group(reached, seen, ag, w);
+                } else ng = fresh_in_group(reached, seen, 2 * ag, w);
                 if (ng) {
                     int64_t pos = base + before[r];
 #pragma unroll
@@ -458,7 +485,7 @@ __global__ void __launch_bounds__(FR_THREADS) fresh_emit_sparse_kernel(uint32_t 
                         uint32_t x = w[k];
                         if (x) {
                             const uint32_t id0 = (uint32_t)((wave_w0 + (uint64_t)grp * FR_WORDS_PER_THREAD + k) << 5);
-                            if (keep_seen) seen[ag + k] |= x;
+                            if (keep_seen) seen[2 * ag + k] |= x;
                             while (x) {
                                 const int bit = __ffs((int)x) - 1;
                                 x &= x - 1;
@@ -469,11 +496,11 @@ __global__ void __launch_bounds__(FR_THREADS) fresh_emit_sparse_kernel(uint32_t 
                     if (keep_seen) seen_flags[ag >> 3] = 1;
                 }
             }
-            *reinterpret_cast<uint4 *>(reached + ag) = make_uint4(0, 0, 0, 0);
-            *reinterpret_cast<uint4 *>(reached + ag + 4) = make_uint4(0, 0, 0, 0);
+            *reinterpret_cast<uint4 *>(reached + 2 * ag) = make_uint4(0, 0, 0, 0);
+            *reinterpret_cast<uint4 *>(reached + 2 * ag + 4) = make_uint4(0, 0, 0, 0);
         }
     }
-    if (fl != 0ull) *reinterpret_cast<unsigned long long *>(flags + (at >> 3)) = 0ull;
+    clear_frs_flags(flags, at >> 3, fl);
 }
 
 // *n += the non-zero 8-byte words of p[0 .. n_words): the check behind RAPIDGNN_CHECK_ZERO_MAPS
@@ -487,7 +514,7 @@ __global__ void count_nonzero_kernel(const unsigned long long *__restrict__ p, u
 
 // After the last hop: `seen` back to all-zero by clearing only the groups that hold bits (seen_flags), so that the
 // bitmap can serve the next build without a memset of the whole map.  A thread owns eight groups.
-__global__ void __launch_bounds__(FR_THREADS) clear_seen_kernel(uint32_t *__restrict__ seen, uint8_t *__restrict__ seen_flags, uint64_t n_flag_words)
+__global__ void __launch_bounds__(FR_THREADS) clear_seen_kernel(uint32_t *__restrict__ seen, uint8_t *__restrict__ seen_flags, uint64_t n_flag_words, int paired)
 {
     const uint64_t i = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (i >= n_flag_words) return;
@@ -496,7 +523,7 @@ __global__ void __launch_bounds__(FR_THREADS) clear_seen_kernel(uint32_t *__rest
 #pragma unroll
     for (int g = 0; g < 8; ++g)
         if ((fl >> (8 * g)) & 0xFFull) {
-            uint32_t *p = seen + (i * 8 + g) * FR_WORDS_PER_THREAD;
+            uint32_t *p = seen + (i * 8 + g) * (FR_WORDS_PER_THREAD << paired);
             *reinterpret_cast<uint4 *>(p) = make_uint4(0, 0, 0, 0);
             *reinterpret_cast<uint4 *>(p + 4) = make_uint4(0, 0, 0, 0);
         }
@@ -588,7 +615,7 @@ static rg_status build_schedule_impl(const rg_graph *g, const int32_t *train, ui
 
     // ---- bitmaps (n_nodes bits per batch, rounded up to whole 8-word groups)
     const uint64_t wpb = (((uint64_t)g->n_nodes + 31) / 32 + FRS_WORDS_PER_THREAD - 1) / FRS_WORDS_PER_THREAD * FRS_WORDS_PER_THREAD;
-    bool sparse_maps = wpb >= (uint64_t)FRS_CHUNK_WORDS * 16;                // 8.4 M nodes and up: a batch leaves most groups untouched
+    bool sparse_maps = wpb >= ((uint64_t)1 << 18);                           // 8.4 M nodes and up: a batch leaves most groups untouched
     if (const char *force = getenv("RAPIDGNN_SPARSE_FRONTIER")) sparse_maps = force[0] == '1';   // same results either way; for tests and tuning
     const uint32_t chunk_words = sparse_maps ? FRS_CHUNK_WORDS : FR_CHUNK_WORDS;
     const uint32_t chunks = (uint32_t)((wpb + chunk_words - 1) / chunk_words);
@@ -608,8 +635,15 @@ static rg_status build_schedule_impl(const rg_graph *g, const int32_t *train, ui
     uint8_t *reached_flags = nullptr;                  // one byte per group of 256 IDs of `reached`
     uint8_t *seen_flags = nullptr;                     // the same for `seen`: groups that hold any bit
     const uint64_t n_groups = wpb / FR_WORDS_PER_THREAD * beta;          // (a multiple of eight: wpb is a multiple of 64)
-    RG_TRY(tmp.dev_zeroed(wpb * beta * sizeof(uint32_t), (void **)&seen, st));
-    RG_TRY(tmp.dev_zeroed(wpb * beta * sizeof(uint32_t), (void **)&reached_words, st));
+    uint32_t *paired = nullptr;                        // the large-graph form: both maps in one array of records (see paired_word)
+    if (sparse_maps) {
+        RG_TRY(tmp.dev_zeroed(2 * wpb * beta * sizeof(uint32_t), (void **)&paired, st));
+        reached_words = paired;
+        seen = paired + FR_WORDS_PER_THREAD;
+    } else {
+        RG_TRY(tmp.dev_zeroed(wpb * beta * sizeof(uint32_t), (void **)&seen, st));
+        RG_TRY(tmp.dev_zeroed(wpb * beta * sizeof(uint32_t), (void **)&reached_words, st));
+    }
     RG_TRY(tmp.dev_zeroed(n_groups, (void **)&reached_flags, st));
     RG_TRY(tmp.dev_zeroed(n_groups, (void **)&seen_flags, st));
     if (const char *check = getenv("RAPIDGNN_CHECK_ZERO_MAPS"); check && check[0] == '1') {
@@ -617,18 +651,20 @@ static rg_status build_schedule_impl(const rg_graph *g, const int32_t *train, ui
         unsigned long long *n_dev = nullptr, n_host = 0;
         RG_TRY(tmp.dev_n<unsigned long long>(1, &n_dev));
         RG_HIP(hipMemsetAsync(n_dev, 0, sizeof(unsigned long long), st));
-        const struct { const void *p; uint64_t bytes; } parts[4] = {{seen, wpb * beta * 4}, {reached_words, wpb * beta * 4}, {reached_flags, n_groups}, {seen_flags, n_groups}};
+        const struct { const void *p; uint64_t bytes; } parts[4] = {{paired ? nullptr : seen, paired ? 0 : wpb * beta * 4}, {reached_words, wpb * beta * (paired ? 8u : 4u)},
+                                                                    {reached_flags, n_groups}, {seen_flags, n_groups}};
         for (const auto &part : parts)
-            hipLaunchKernelGGL(count_nonzero_kernel, dim3(1024), dim3(256), 0, st, (const unsigned long long *)part.p, part.bytes / 8, n_dev);
+            if (part.bytes)
+                hipLaunchKernelGGL(count_nonzero_kernel, dim3(1024), dim3(256), 0, st, (const unsigned long long *)part.p, part.bytes / 8, n_dev);
         Readback rb(st);
         RG_TRY(rb.add(&n_host, n_dev, sizeof(n_host)));
         RG_TRY(rb.wait());
         if (n_host != 0) { set_error("rg_build_schedule: %llu words of the per-batch maps are not zero at the start of the build", n_host); return RG_EHIP; }
     }
-    ReachedForms maps{reached_words, nullptr, reached_flags, wpb, byte_map};
+    ReachedForms maps{reached_words, nullptr, reached_flags, wpb, byte_map, paired != nullptr};
     {
         ScopedTimer tm(KG_FRONTIER, st);
-        hipLaunchKernelGGL(mark_seeds_kernel, dim3((unsigned)((T + 255) / 256)), dim3(256), 0, st, h0.ids, T, B, seen, seen_flags, wpb, (int64_t)g->n_nodes);
+        hipLaunchKernelGGL(mark_seeds_kernel, dim3((unsigned)((T + 255) / 256)), dim3(256), 0, st, h0.ids, T, B, seen, seen_flags, wpb, (int64_t)g->n_nodes, sparse_maps ? 1 : 0);
     }
     int32_t *fresh_cnt = nullptr;
     int64_t *fresh_scan = nullptr;
@@ -698,20 +734,21 @@ static rg_status build_schedule_impl(const rg_graph *g, const int32_t *train, ui
         // flagged by at least one input node: the fill wins unless fewer than an eighth of the groups can be flagged.
         ScopedTimer tm(KG_FRONTIER, st);
         const uint64_t listed = L > 0 ? (uint64_t)s->hop[L].off_host[beta] : T;
-        if (listed > n_groups / 8) {
-            RG_HIP(hipMemsetAsync(seen, 0, n_groups * FR_WORDS_PER_THREAD * sizeof(uint32_t), st));
+        if (listed > n_groups / (paired ? 4 : 8)) {          // (paired records: the fill covers twice the bytes)
+            if (paired) RG_HIP(hipMemsetAsync(paired, 0, 2 * n_groups * FR_WORDS_PER_THREAD * sizeof(uint32_t), st));
+            else RG_HIP(hipMemsetAsync(seen, 0, n_groups * FR_WORDS_PER_THREAD * sizeof(uint32_t), st));
             RG_HIP(hipMemsetAsync(seen_flags, 0, n_groups, st));
         } else {
-            hipLaunchKernelGGL(clear_seen_kernel, dim3((unsigned)((n_groups / 8 + FR_THREADS - 1) / FR_THREADS)), dim3(FR_THREADS), 0, st, seen, seen_flags, n_groups / 8);
+            hipLaunchKernelGGL(clear_seen_kernel, dim3((unsigned)((n_groups / 8 + FR_THREADS - 1) / FR_THREADS)), dim3(FR_THREADS), 0, st, seen, seen_flags, n_groups / 8, paired ? 1 : 0);
             RG_HIP(hipGetLastError());
         }
     }
     RG_HIP(hipStreamSynchronize(st));
     tmp.drained();
     // every map is all-zero again and nothing writes them any more
-    tmp.free_zeroed(seen);
+    if (paired) tmp.free_zeroed(paired);
+    else { tmp.free_zeroed(seen); tmp.free_zeroed(reached_words); }
     tmp.free_zeroed(seen_flags);
-    tmp.free_zeroed(reached_words);
     tmp.free_zeroed(reached_flags);
     if (maps.bytes) tmp.free_zeroed(maps.bytes);
     return RG_OK;

@@ -134,6 +134,25 @@ def test_every_frontier_and_sample(ep, rg):
             assert np.array_equal(host(rg.rg_schedule_block(s, hop)), o.block(hop)), f"block {hop}"
 
 
+def test_medium_frontier_forms_give_the_same_frontiers(ep, rg, monkeypatch):
+    """The library picks one form of the frontier pass by the graph's size.  At full size, where a batch's map spans
+    several cells of either form, the form it did not pick must give the same frontiers.  (The medium graph builds
+    fast in either form; the small-graph form would scan 2 GB of maps per hop on the 10^8-node graph.)"""
+    if ep.name != "medium":
+        return
+    cfg, W, o = ep.cfg, ep.W, ep.o
+    for force in ("1", "0"):
+        monkeypatch.setenv("RAPIDGNN_SPARSE_FRONTIER", force)
+        for again in range(2):                             # the second build takes the first one's maps back from the pool
+            s = rg.rg_build_schedule(W.indptr, W.indices, W.train, cfg.batch_size, cfg.fanout, cfg.s0, cfg.worker, cfg.epoch)
+            for hop in range(o.L + 1):
+                ids, off = o.frontier(hop)
+                gids, _, goff = rg.rg_schedule_frontier(s, hop)
+                assert np.array_equal(goff, off) and np.array_equal(host(gids), ids), f"forced {force}, build {again}: frontier {hop}"
+            del s
+        note(f"{ep.name}: frontiers equal with RAPIDGNN_SPARSE_FRONTIER={force}")
+
+
 def check_cache(ep, rg, orc, c, K, batches, tag):
     """Everything a cache holds and serves, against the oracle: freq, TopHot set and slots, table, the counts of EVERY
     batch, the gathered bytes of `batches` one by one and of the groups of batches that contain them."""
