@@ -10,17 +10,34 @@ thread_local std::atomic<uint64_t> *tls_table_bytes_sink = nullptr;
 
 // ---------------------------------------------------------------- a6: freq(v)
 // Every batch's input set is duplicate free, so each listed ID adds one.
-__global__ void tally_kernel(const int32_t *__restrict__ ids, int64_t n, uint32_t *__restrict__ freq)
+// The counters are uint32_t, or -- when no frequency can exceed 255 (at most 255 batches over the epochs given) --
+// uint8_t, four to a word: an add of 1 << 8 * (id & 3) to the word can then never carry into the next counter.  A
+// tally of 10^8 nodes is a quarter of the bytes to clear and to read in every later pass, and small enough for
+// its scattered adds to stay in the last-level cache.
+template <typename F>
+__global__ void tally_kernel(const int32_t *__restrict__ ids, int64_t n, F *__restrict__ freq)
 {
     const int64_t stride = (int64_t)gridDim.x * blockDim.x;
-    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride) atomicAdd(&freq[ids[i]], 1u);
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride) {
+        const uint32_t v = (uint32_t)ids[i];
+        if (sizeof(F) == 1) atomicAdd(reinterpret_cast<uint32_t *>(freq) + (v >> 2), 1u << (8 * (v & 3)));
+        else atomicAdd(reinterpret_cast<uint32_t *>(freq) + v, 1u);
+    }
 }
 
 // freq += the frequencies an epoch's schedule already holds (computed from its bitmaps when it was built)
-__global__ void add_epoch_freq_kernel(const uint32_t *__restrict__ epoch_freq, int64_t n, uint32_t *__restrict__ freq)
+template <typename F>
+__global__ void add_epoch_freq_kernel(const uint32_t *__restrict__ epoch_freq, int64_t n, F *__restrict__ freq)
 {
     const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (i < n) freq[i] += epoch_freq[i];
+    if (i < n) freq[i] = (F)(freq[i] + epoch_freq[i]);
+}
+
+// The uint8_t tally as the uint32_t array the cache's view hands out (made when first asked for).
+__global__ void widen_freq_kernel(const uint8_t *__restrict__ freq8, int64_t n, uint32_t *__restrict__ freq)
+{
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride) freq[i] = freq8[i];
 }
 
 // ---------------------------------------------------------------- a7: TopHot
@@ -90,6 +107,56 @@ __global__ void __launch_bounds__(TOPK_THREADS) digit_histogram_kernel(const uin
     __syncthreads();
     // workgroups spread their adds over BIN_COPIES copies of the bins: few digits are in use, and thousands of adds
     // to the same few addresses would queue up behind each other
+    unsigned long long *mine = bins + (size_t)(blockIdx.x % BIN_COPIES) * DIGIT_BINS;
+    for (int k = threadIdx.x; k < DIGIT_BINS; k += TOPK_THREADS)
+        if (h[k]) atomicAdd(&mine[k], (unsigned long long)h[k]);
+}
+
+// The same for the uint8_t tally: one digit, so no prefix to match.  WIDE (is_local 16-byte aligned; the tally always
+// is): a lane takes sixteen consecutive nodes per round, one 16-byte load of each array, and visits only the
+// bytes that are candidates (non-zero count, not local).
+__device__ __forceinline__ uint32_t nonzero_bytes(uint32_t w) { return (w | ((w & 0x7F7F7F7Fu) + 0x7F7F7F7Fu)) & 0x80808080u; }   // bit 7 of every non-zero byte
+
+template <bool WIDE>
+__global__ void __launch_bounds__(TOPK_THREADS) digit_histogram8_kernel(const uint8_t *__restrict__ freq, const uint8_t *__restrict__ is_local, int64_t n,
+                                                                        const SelectState *__restrict__ stp, unsigned long long *__restrict__ bins)
+{
+    __shared__ unsigned int h[DIGIT_BINS];
+    for (int k = threadIdx.x; k < DIGIT_BINS; k += TOPK_THREADS) h[k] = 0;
+    __syncthreads();
+    if (stp->take_all) return;
+    int64_t done = 0;
+    if (WIDE) {
+        auto count_word = [&](uint32_t fw, uint32_t lw) {
+            uint32_t cand = nonzero_bytes(fw) & ~nonzero_bytes(lw);
+            while (cand) {
+                const int top = __ffs((int)cand) - 1;              // bit 7 of the candidate's byte
+                cand &= cand - 1;
+                atomicAdd(&h[(fw >> (top - 7)) & 0xFFu], 1u);
+            }
+        };
+        auto count16 = [&](const uint4 fv, const uint4 lv) {
+            if ((fv.x | fv.y | fv.z | fv.w) == 0u) return;
+            count_word(fv.x, lv.x); count_word(fv.y, lv.y); count_word(fv.z, lv.z); count_word(fv.w, lv.w);
+        };
+        const int64_t n16 = n >> 4;
+        const int64_t span = (n16 + gridDim.x - 1) / gridDim.x;
+        const int64_t q_end = min(n16, (int64_t)(blockIdx.x + 1) * span);
+        int64_t q = (int64_t)blockIdx.x * span + threadIdx.x;
+        for (; q + TOPK_THREADS < q_end; q += 2 * TOPK_THREADS) {
+            const uint4 f0 = reinterpret_cast<const uint4 *>(freq)[q], f1 = reinterpret_cast<const uint4 *>(freq)[q + TOPK_THREADS];
+            const uint4 l0 = reinterpret_cast<const uint4 *>(is_local)[q], l1 = reinterpret_cast<const uint4 *>(is_local)[q + TOPK_THREADS];
+            count16(f0, l0); count16(f1, l1);
+        }
+        for (; q < q_end; q += TOPK_THREADS) count16(reinterpret_cast<const uint4 *>(freq)[q], reinterpret_cast<const uint4 *>(is_local)[q]);
+        done = n16 << 4;
+    }
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    for (int64_t v = done + (int64_t)blockIdx.x * blockDim.x + threadIdx.x; v < n; v += stride) {
+        const uint32_t fv = freq[v];
+        if (fv != 0 && !is_local[v]) atomicAdd(&h[fv], 1u);
+    }
+    __syncthreads();
     unsigned long long *mine = bins + (size_t)(blockIdx.x % BIN_COPIES) * DIGIT_BINS;
     for (int k = threadIdx.x; k < DIGIT_BINS; k += TOPK_THREADS)
         if (h[k]) atomicAdd(&mine[k], (unsigned long long)h[k]);
@@ -166,9 +233,32 @@ __device__ __forceinline__ void classify_eight(const uint32_t *__restrict__ freq
         c[k] = v < n ? classify_node(freq[v], is_local[v], st) : 0;
     }
 }
-// The SEL_PER_THREAD consecutive nodes of a thread.
+// The same over the uint8_t tally: one 8-byte load of each array.
 template <bool ALIGNED8>
-__device__ __forceinline__ void classify_mine(const uint32_t *__restrict__ freq, const uint8_t *__restrict__ is_local, int64_t first, int64_t n,
+__device__ __forceinline__ void classify_eight(const uint8_t *__restrict__ freq, const uint8_t *__restrict__ is_local, int64_t first, int64_t n,
+                                               const SelectState &st, uint64_t *c /* [8] */)
+{
+    if (ALIGNED8 && first + 8 <= n) {
+        const uint64_t fw = *reinterpret_cast<const uint64_t *>(freq + first);
+        if (fw == 0ull) {
+#pragma unroll
+            for (int k = 0; k < 8; ++k) c[k] = 0;
+            return;
+        }
+        const uint64_t loc = *reinterpret_cast<const uint64_t *>(is_local + first);
+#pragma unroll
+        for (int k = 0; k < 8; ++k) c[k] = classify_node((uint32_t)(fw >> (8 * k)) & 0xFFu, (uint8_t)(loc >> (8 * k)), st);
+        return;
+    }
+#pragma unroll
+    for (int k = 0; k < 8; ++k) {
+        const int64_t v = first + k;
+        c[k] = v < n ? classify_node(freq[v], is_local[v], st) : 0;
+    }
+}
+// The SEL_PER_THREAD consecutive nodes of a thread.
+template <bool ALIGNED8, typename F>
+__device__ __forceinline__ void classify_mine(const F *__restrict__ freq, const uint8_t *__restrict__ is_local, int64_t first, int64_t n,
                                               const SelectState &st, uint64_t (&c)[SEL_PER_THREAD])
 {
 #pragma unroll
@@ -197,15 +287,15 @@ __device__ __forceinline__ uint64_t block_exclusive_scan_u64(uint64_t x, uint64_
     return base + incl - x;
 }
 
-template <bool ALIGNED8>
-__global__ void __launch_bounds__(TOPK_THREADS) select_block_totals(const uint32_t *__restrict__ freq, const uint8_t *__restrict__ is_local, int64_t n,
+template <bool ALIGNED8, typename F>
+__global__ void __launch_bounds__(TOPK_THREADS) select_block_totals(const F *__restrict__ freq, const uint8_t *__restrict__ is_local, int64_t n,
                                                                     const SelectState *__restrict__ stp, uint64_t *__restrict__ block_tot)
 {
     __shared__ uint64_t lds[TOPK_THREADS / 64];
     const SelectState st = *stp;
     const int64_t first = (int64_t)blockIdx.x * SEL_TILE + (int64_t)threadIdx.x * SEL_PER_THREAD;
     uint64_t c[SEL_PER_THREAD];
-    classify_mine<ALIGNED8>(freq, is_local, first, n, st, c);
+    classify_mine<ALIGNED8, F>(freq, is_local, first, n, st, c);
     uint64_t s = 0;
 #pragma unroll
     for (int k = 0; k < SEL_PER_THREAD; ++k) s += c[k];
@@ -214,21 +304,41 @@ __global__ void __launch_bounds__(TOPK_THREADS) select_block_totals(const uint32
     if (threadIdx.x == 0) block_tot[blockIdx.x] = tot;
 }
 
-// One workgroup of SCAN_THREADS; a thread takes sixteen consecutive totals per round.
-constexpr int SCAN_THREADS = 1024;
-__global__ void __launch_bounds__(SCAN_THREADS) select_scan_totals(uint64_t *__restrict__ block_tot, int64_t n_blocks)
+// The exclusive scan of the per-workgroup totals, in two levels: every workgroup scans its own SCAN_TILE totals in
+// place and leaves their sum in tile_tot; one workgroup then scans tile_tot (select_scan_totals); the emit pass adds
+// the two.  (10^8 nodes are 54,000 totals: one workgroup alone spends longer walking them than a pass over the nodes' flags takes.)
+constexpr int SCAN_TILE = TOPK_THREADS * 8;
+__global__ void __launch_bounds__(TOPK_THREADS) select_scan_tiles(uint64_t *__restrict__ block_tot, int64_t n_blocks, uint64_t *__restrict__ tile_tot)
 {
-    __shared__ uint64_t lds[SCAN_THREADS / 64];
+    __shared__ uint64_t lds[TOPK_THREADS / 64];
+    const int64_t i0 = (int64_t)blockIdx.x * SCAN_TILE + (int64_t)threadIdx.x * 8;
+    uint64_t x[8], sum = 0;
+#pragma unroll
+    for (int k = 0; k < 8; ++k) { x[k] = i0 + k < n_blocks ? block_tot[i0 + k] : 0; sum += x[k]; }
+    uint64_t tot;
+    uint64_t run = block_exclusive_scan_u64(sum, &tot, lds);
+#pragma unroll
+    for (int k = 0; k < 8; ++k) {
+        if (i0 + k < n_blocks) block_tot[i0 + k] = run;
+        run += x[k];
+    }
+    if (threadIdx.x == 0) tile_tot[blockIdx.x] = tot;
+}
+
+// One workgroup; a thread takes eight consecutive totals per round.
+__global__ void __launch_bounds__(TOPK_THREADS) select_scan_totals(uint64_t *__restrict__ block_tot, int64_t n_blocks)
+{
+    __shared__ uint64_t lds[TOPK_THREADS / 64];
     uint64_t carry = 0;
-    for (int64_t base = 0; base < n_blocks; base += (int64_t)SCAN_THREADS * 16) {
-        const int64_t i0 = base + (int64_t)threadIdx.x * 16;
-        uint64_t x[16], sum = 0;
+    for (int64_t base = 0; base < n_blocks; base += (int64_t)TOPK_THREADS * 8) {
+        const int64_t i0 = base + (int64_t)threadIdx.x * 8;
+        uint64_t x[8], sum = 0;
 #pragma unroll
-        for (int k = 0; k < 16; ++k) { x[k] = i0 + k < n_blocks ? block_tot[i0 + k] : 0; sum += x[k]; }
+        for (int k = 0; k < 8; ++k) { x[k] = i0 + k < n_blocks ? block_tot[i0 + k] : 0; sum += x[k]; }
         uint64_t tot;
-        uint64_t run = carry + block_exclusive_scan_u64<SCAN_THREADS>(sum, &tot, lds);
+        uint64_t run = carry + block_exclusive_scan_u64(sum, &tot, lds);
 #pragma unroll
-        for (int k = 0; k < 16; ++k) {
+        for (int k = 0; k < 8; ++k) {
             if (i0 + k < n_blocks) block_tot[i0 + k] = run;
             run += x[k];
         }
@@ -236,21 +346,23 @@ __global__ void __launch_bounds__(SCAN_THREADS) select_scan_totals(uint64_t *__r
     }
 }
 
-template <bool ALIGNED8>
-__global__ void __launch_bounds__(TOPK_THREADS) select_emit_kernel(const uint32_t *__restrict__ freq, const uint8_t *__restrict__ is_local, int64_t n,
+template <bool ALIGNED8, typename F>
+__global__ void __launch_bounds__(TOPK_THREADS) select_emit_kernel(const F *__restrict__ freq, const uint8_t *__restrict__ is_local, int64_t n,
                                                                    const SelectState *__restrict__ stp, const uint64_t *__restrict__ block_base,
-                                                                   int32_t *__restrict__ cache_ids, int32_t *__restrict__ slot_of)
+                                                                   const uint64_t *__restrict__ tile_base, int32_t *__restrict__ cache_ids, int32_t *__restrict__ slot_of,
+                                                                   const int32_t *__restrict__ row_of, int64_t *__restrict__ fill_entries)
 {
+    // fill_entries[slot]: where VectorPull finds the row of the node in that slot (a8), written here while the node is at hand
     __shared__ uint64_t lds[TOPK_THREADS / 64];
     const SelectState st = *stp;
     const int64_t first = (int64_t)blockIdx.x * SEL_TILE + (int64_t)threadIdx.x * SEL_PER_THREAD;
     uint64_t c[SEL_PER_THREAD];
-    classify_mine<ALIGNED8>(freq, is_local, first, n, st, c);
+    classify_mine<ALIGNED8, F>(freq, is_local, first, n, st, c);
     uint64_t s = 0;
 #pragma unroll
     for (int k = 0; k < SEL_PER_THREAD; ++k) s += c[k];
     uint64_t tot;
-    uint64_t run = block_base[blockIdx.x] + block_exclusive_scan_u64(s, &tot, lds);
+    uint64_t run = block_base[blockIdx.x] + tile_base[blockIdx.x / SCAN_TILE] + block_exclusive_scan_u64(s, &tot, lds);
     int32_t slots[SEL_PER_THREAD];
 #pragma unroll
     for (int k = 0; k < SEL_PER_THREAD; ++k) {
@@ -261,6 +373,7 @@ __global__ void __launch_bounds__(TOPK_THREADS) select_emit_kernel(const uint32_
         if (sel) {
             slots[k] = (int32_t)(gt_before + (eq_before < st.r ? eq_before : st.r));
             cache_ids[slots[k]] = (int32_t)v;
+            fill_entries[slots[k]] = make_entry(TAG_REMOTE, row_of[v]);
         }
         run += c[k];
     }
@@ -273,13 +386,6 @@ __global__ void __launch_bounds__(TOPK_THREADS) select_emit_kernel(const uint32_
         for (int k = 0; k < SEL_PER_THREAD; ++k)
             if (first + k < n) slot_of[first + k] = slots[k];
     }
-}
-
-// ---------------------------------------------------------------- a8: VectorPull entries
-__global__ void fill_entries_kernel(const int32_t *__restrict__ cache_ids, uint64_t k_eff, const int32_t *__restrict__ row_of, int64_t *__restrict__ entries)
-{
-    const uint64_t j = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (j < k_eff) entries[j] = make_entry(TAG_REMOTE, row_of[cache_ids[j]]);
 }
 
 // ---------------------------------------------------------------- a5/a9: routing plan
@@ -431,6 +537,27 @@ rg_status build_plan(const rg_schedule *s, const int64_t *route, const RouteSour
     return RG_OK;
 }
 
+// The tally as uint32_t[n_nodes] for rg_cache_view: the array itself, or -- where the build counted in bytes -- a
+// widened copy made at the first request (device memory from the cache's allocator; the call waits for the copy).
+rg_status cache_freq_view(const rg_cache *cc, const uint32_t **out)
+{
+    rg_cache *c = const_cast<rg_cache *>(cc);
+    std::lock_guard<std::mutex> lk(c->view_mu);
+    if (!c->freq && c->freq8 && c->n_nodes > 0) {
+        hipStream_t side = nullptr;
+        RG_TRY(helper_stream(&side));
+        uint32_t *wide = nullptr;
+        RG_TRY(c->arena.dev_n<uint32_t>((uint64_t)c->n_nodes, &wide));
+        const unsigned grid = (unsigned)std::max<int64_t>(1, std::min<int64_t>((c->n_nodes + 255) / 256, 1 << 16));
+        hipLaunchKernelGGL(widen_freq_kernel, dim3(grid), dim3(256), 0, side, c->freq8, c->n_nodes, wide);
+        RG_HIP(hipGetLastError());
+        RG_HIP(hipStreamSynchronize(side));
+        c->freq = wide;
+    }
+    *out = c->freq;
+    return RG_OK;
+}
+
 static rg_status build_cache_impl(const rg_schedule *const *epochs, uint32_t n_epochs, const rg_features *f, uint64_t K,
                                   const rg_allocator *a, hipStream_t st, rg_cache *c)
 {
@@ -449,24 +576,33 @@ static rg_status build_cache_impl(const rg_schedule *const *epochs, uint32_t n_e
     RG_HIP(hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, dev));
 
     // ---- a6: tally
-    RG_TRY(c->arena.dev_n<uint32_t>((uint64_t)n, &c->freq));
-    RG_TRY(c->arena.dev_n<int32_t>((uint64_t)n, &c->slot_of));
-    RG_HIP(hipMemsetAsync(c->freq, 0, (uint64_t)n * sizeof(uint32_t), st));
     uint64_t max_freq = 0;
+    bool from_bitmaps = false;
+    for (uint32_t e = 0; e < n_epochs; ++e) { max_freq += epochs[e]->n_batches; from_bitmaps = from_bitmaps || epochs[e]->epoch_freq; }
+    bool narrow = max_freq <= 255;                       // byte counters suffice
+    if (const char *force = getenv("RAPIDGNN_NARROW_TALLY"); force && force[0] == '0') narrow = false;      // same results either way; for tests and tuning
+    const uint64_t tally_bytes = narrow ? ((uint64_t)n + 15) / 16 * 16 : (uint64_t)n * sizeof(uint32_t);
+    void *tally = nullptr;
+    RG_TRY(c->arena.dev(tally_bytes ? tally_bytes : 16, &tally));
+    if (narrow) c->freq8 = (uint8_t *)tally; else c->freq = (uint32_t *)tally;
+    RG_TRY(c->arena.dev_n<int32_t>((uint64_t)n, &c->slot_of));
+    RG_HIP(hipMemsetAsync(tally, 0, tally_bytes, st));
     for (uint32_t e = 0; e < n_epochs; ++e) {
         const rg_schedule *s = epochs[e];
-        max_freq += s->n_batches;
         if (s->n_batches == 0) continue;
         const HopData &h = s->hop[s->L];
         const int64_t m = h.off_host[s->n_batches];
         if (m == 0) continue;
         ScopedTimer tm(KG_HIST, st);
         if (s->epoch_freq) {
-            hipLaunchKernelGGL(add_epoch_freq_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, s->epoch_freq, n, c->freq);
+            const dim3 grid((unsigned)((n + 255) / 256));
+            if (narrow) hipLaunchKernelGGL(add_epoch_freq_kernel<uint8_t>, grid, dim3(256), 0, st, s->epoch_freq, n, c->freq8);
+            else hipLaunchKernelGGL(add_epoch_freq_kernel<uint32_t>, grid, dim3(256), 0, st, s->epoch_freq, n, c->freq);
             continue;
         }
         const unsigned grid = (unsigned)std::min<int64_t>((m + 255) / 256, (int64_t)n_cu * 32);
-        hipLaunchKernelGGL(tally_kernel, dim3(grid), dim3(256), 0, st, h.ids, m, c->freq);
+        if (narrow) hipLaunchKernelGGL(tally_kernel<uint8_t>, dim3(grid), dim3(256), 0, st, h.ids, m, c->freq8);
+        else hipLaunchKernelGGL(tally_kernel<uint32_t>, dim3(grid), dim3(256), 0, st, h.ids, m, c->freq);
     }
     RG_HIP(hipGetLastError());
 
@@ -480,23 +616,34 @@ static rg_status build_cache_impl(const rg_schedule *const *epochs, uint32_t n_e
     int bits = 1;
     while (bits < 32 && (max_freq >> bits) != 0) ++bits;
     const int passes = (bits + DIGIT_BITS - 1) / DIGIT_BITS;
-    const bool local4 = ((uintptr_t)f->is_local & 3) == 0, local8 = ((uintptr_t)f->is_local & 7) == 0;      // the caller's array: wide loads only if it allows them
+    const bool local4 = ((uintptr_t)f->is_local & 3) == 0, local8 = ((uintptr_t)f->is_local & 7) == 0,      // the caller's array: wide loads only if it allows them
+               local16 = ((uintptr_t)f->is_local & 15) == 0;
     const int64_t sel_blocks = (n + SEL_TILE - 1) / SEL_TILE;
     uint64_t *block_tot = nullptr;
     RG_TRY(tmp.dev_n<uint64_t>((uint64_t)(sel_blocks ? sel_blocks : 1), &block_tot));
+    const int64_t sel_tiles = (sel_blocks + SCAN_TILE - 1) / SCAN_TILE;
+    uint64_t *tile_tot = nullptr;
+    RG_TRY(tmp.dev_n<uint64_t>((uint64_t)(sel_tiles ? sel_tiles : 1), &tile_tot));
     {
         ScopedTimer tm(KG_TOPK, st);
         const unsigned grid = (unsigned)std::max<int64_t>(1, std::min<int64_t>((n + TOPK_THREADS - 1) / TOPK_THREADS, (int64_t)n_cu * 16));
         for (int p = 0; p < passes; ++p) {
             const int shift = (passes - 1 - p) * DIGIT_BITS;
-            if (local4) hipLaunchKernelGGL(digit_histogram_kernel<true>, dim3(grid), dim3(TOPK_THREADS), 0, st, c->freq, f->is_local, n, stp, shift, bins);
+            if (narrow) {
+                if (local16) hipLaunchKernelGGL(digit_histogram8_kernel<true>, dim3(grid), dim3(TOPK_THREADS), 0, st, c->freq8, f->is_local, n, stp, bins);
+                else hipLaunchKernelGGL(digit_histogram8_kernel<false>, dim3(grid), dim3(TOPK_THREADS), 0, st, c->freq8, f->is_local, n, stp, bins);
+            } else if (local4) hipLaunchKernelGGL(digit_histogram_kernel<true>, dim3(grid), dim3(TOPK_THREADS), 0, st, c->freq, f->is_local, n, stp, shift, bins);
             else hipLaunchKernelGGL(digit_histogram_kernel<false>, dim3(grid), dim3(TOPK_THREADS), 0, st, c->freq, f->is_local, n, stp, shift, bins);
             hipLaunchKernelGGL(choose_digit_kernel, dim3(1), dim3(DIGIT_BINS), 0, st, stp, bins, shift, p == 0 ? 1 : 0, K);
         }
         if (sel_blocks > 0) {
-            if (local8) hipLaunchKernelGGL(select_block_totals<true>, dim3((unsigned)sel_blocks), dim3(TOPK_THREADS), 0, st, c->freq, f->is_local, n, stp, block_tot);
-            else hipLaunchKernelGGL(select_block_totals<false>, dim3((unsigned)sel_blocks), dim3(TOPK_THREADS), 0, st, c->freq, f->is_local, n, stp, block_tot);
-            hipLaunchKernelGGL(select_scan_totals, dim3(1), dim3(SCAN_THREADS), 0, st, block_tot, sel_blocks);
+            const dim3 sg((unsigned)sel_blocks), sb(TOPK_THREADS);
+            if (narrow && local8) hipLaunchKernelGGL((select_block_totals<true, uint8_t>), sg, sb, 0, st, c->freq8, f->is_local, n, stp, block_tot);
+            else if (narrow) hipLaunchKernelGGL((select_block_totals<false, uint8_t>), sg, sb, 0, st, c->freq8, f->is_local, n, stp, block_tot);
+            else if (local8) hipLaunchKernelGGL((select_block_totals<true, uint32_t>), sg, sb, 0, st, c->freq, f->is_local, n, stp, block_tot);
+            else hipLaunchKernelGGL((select_block_totals<false, uint32_t>), sg, sb, 0, st, c->freq, f->is_local, n, stp, block_tot);
+            hipLaunchKernelGGL(select_scan_tiles, dim3((unsigned)sel_tiles), dim3(TOPK_THREADS), 0, st, block_tot, sel_blocks, tile_tot);
+            hipLaunchKernelGGL(select_scan_totals, dim3(1), dim3(TOPK_THREADS), 0, st, tile_tot, sel_tiles);
         }
     }
     SelectState hs;
@@ -507,12 +654,19 @@ static rg_status build_cache_impl(const rg_schedule *const *epochs, uint32_t n_e
     }
     c->K_eff = hs.k_eff;
     RG_TRY(c->arena.dev_n<int32_t>(c->K_eff, &c->cache_ids));
+    int64_t *fill_entries = nullptr;
+    RG_TRY(tmp.dev_n<int64_t>(c->K_eff ? c->K_eff : 1, &fill_entries));
     if (sel_blocks > 0) {
         ScopedTimer tm(KG_TOPK, st);
-        if (local8) hipLaunchKernelGGL(select_emit_kernel<true>, dim3((unsigned)sel_blocks), dim3(TOPK_THREADS), 0, st, c->freq, f->is_local, n, stp, block_tot,
-                                       c->cache_ids, c->slot_of);
-        else hipLaunchKernelGGL(select_emit_kernel<false>, dim3((unsigned)sel_blocks), dim3(TOPK_THREADS), 0, st, c->freq, f->is_local, n, stp, block_tot,
-                                c->cache_ids, c->slot_of);
+        const dim3 sg((unsigned)sel_blocks), sb(TOPK_THREADS);
+        if (narrow && local8)
+            hipLaunchKernelGGL((select_emit_kernel<true, uint8_t>), sg, sb, 0, st, c->freq8, f->is_local, n, stp, block_tot, tile_tot, c->cache_ids, c->slot_of, f->row_of, fill_entries);
+        else if (narrow)
+            hipLaunchKernelGGL((select_emit_kernel<false, uint8_t>), sg, sb, 0, st, c->freq8, f->is_local, n, stp, block_tot, tile_tot, c->cache_ids, c->slot_of, f->row_of, fill_entries);
+        else if (local8)
+            hipLaunchKernelGGL((select_emit_kernel<true, uint32_t>), sg, sb, 0, st, c->freq, f->is_local, n, stp, block_tot, tile_tot, c->cache_ids, c->slot_of, f->row_of, fill_entries);
+        else
+            hipLaunchKernelGGL((select_emit_kernel<false, uint32_t>), sg, sb, 0, st, c->freq, f->is_local, n, stp, block_tot, tile_tot, c->cache_ids, c->slot_of, f->row_of, fill_entries);
     }
     RG_HIP(hipGetLastError());
 
@@ -526,14 +680,11 @@ static rg_status build_cache_impl(const rg_schedule *const *epochs, uint32_t n_e
         ~Forked() { if (side) (void)hipStreamSynchronize(side); }
     } forked;
     if (c->K_eff > 0) {
-        int64_t *fill_entries = nullptr;
-        RG_TRY(tmp.dev_n<int64_t>(c->K_eff, &fill_entries));
         hipStream_t side = nullptr;
         RG_TRY(helper_stream(&side));
         RG_HIP(hipEventRecord(c->ev_fork, st));
         RG_HIP(hipStreamWaitEvent(side, c->ev_fork, 0));
         forked.side = side;
-        hipLaunchKernelGGL(fill_entries_kernel, dim3((unsigned)((c->K_eff + 255) / 256)), dim3(256), 0, side, c->cache_ids, c->K_eff, f->row_of, fill_entries);
         RowSources src{(const uint8_t *)f->local_rows, f->local_stride, (const uint8_t *)c->rows, c->stride,
                        (const uint8_t *)f->remote_rows, f->remote_stride};
         RG_TRY(launch_gather(fill_entries, (int64_t)c->K_eff, nullptr, 0, 1, src, f->row_bytes, (uint8_t *)c->rows, c->stride, side, KG_FILL));

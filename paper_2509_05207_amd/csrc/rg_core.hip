@@ -672,7 +672,7 @@ rg_status rg_cache_view(const rg_cache *c, uint64_t *K_eff, const int32_t **cach
     if (!c) { set_error("rg_cache_view: null cache"); return RG_EINVAL; }
     if (K_eff) *K_eff = c->K_eff;
     if (cache_ids_dev) *cache_ids_dev = c->cache_ids;
-    if (freq_dev) *freq_dev = c->freq;
+    if (freq_dev) RG_TRY(cache_freq_view(c, freq_dev));
     if (slot_of_dev) *slot_of_dev = c->slot_of;
     if (rows_dev) *rows_dev = c->rows;
     if (stride) *stride = c->stride;

@@ -162,7 +162,9 @@ struct rg_cache {
     uint32_t row_bytes = 0;
     uint64_t stride = 0;
     int32_t *cache_ids = nullptr;    // dev, ascending
-    uint32_t *freq = nullptr;        // dev, [n_nodes]
+    uint32_t *freq = nullptr;        // dev, [n_nodes]; where the tally was kept in bytes: NULL until rg_cache_view asks for it
+    uint8_t *freq8 = nullptr;        // dev, [n_nodes rounded up to 16]: the tally in bytes (no frequency can exceed 255), or NULL
+    std::mutex view_mu;              // guards the widening of freq8 into freq
     int32_t *slot_of = nullptr;      // dev, [n_nodes]
     void *rows = nullptr;            // dev, K_eff * stride
     std::vector<rg::Plan> plans;
@@ -214,6 +216,9 @@ class Readback {
 // Handles whose destroy call found readers still in flight wait here (default allocator only); they are released by
 // a later library call once their readers have finished.  reap_retired(true) waits for all of them.
 void reap_retired(bool wait);
+
+// freq as rg_cache_view hands it out (widened from the byte tally at the first request)
+rg_status cache_freq_view(const rg_cache *c, const uint32_t **out);
 
 // One non-blocking stream per device, owned by the library and kept until the process ends: a call that has two
 // independent pieces of device work forks the second onto it (event from the caller's stream, event back) so that

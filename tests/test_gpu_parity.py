@@ -100,8 +100,12 @@ def test_blocks_match_oracle(case, rg, workspace):
     assert e.value.status == rg.RG_ERANGE
 
 
+@pytest.mark.parametrize("tally", ["bytes", "words"])
 @pytest.mark.parametrize("kmode", ["config", "zero", "all", "one"])
-def test_cache_matches_oracle(case, rg, orc, kmode):
+def test_cache_matches_oracle(case, rg, orc, kmode, tally, monkeypatch):
+    """(These epochs have fewer than 256 batches, so the tally counts in bytes unless told not to.)"""
+    if tally == "words":
+        monkeypatch.setenv("RAPIDGNN_NARROW_TALLY", "0")
     w = case.w
     freq = orc.frequency([case.osched], w.n_nodes)
     n_cand = int(((w.is_local.numpy() == 0) & (freq > 0)).sum())
@@ -184,6 +188,48 @@ def test_cache_over_two_epochs(rg, orc):
     c2.osched, c2.gsched = o2, g2
     check_gather(c, rg, orc, cache, slot, [0, 3], w.stride_bytes, True)
     check_gather(c2, rg, orc, cache, slot, [1, o2.n_batches - 1], w.stride_bytes, False)
+
+
+@pytest.mark.parametrize("frontier", ["0", "1"])
+def test_cache_of_an_epoch_with_more_than_255_batches(rg, orc, frontier, monkeypatch):
+    """Frequencies can pass 255 only where the epochs have more batches than that: the tally then counts in 32-bit
+    words.  Two-node batches of the small graph with fan-outs (20, 20): 365 batches, and hubs that most of them reach.  With the large-graph
+    frontier passes forced, the schedule carries no frequencies of its own and the cache tallies the input lists."""
+    monkeypatch.setenv("RAPIDGNN_SPARSE_FRONTIER", frontier)
+    c = Case("small", orc, rg, s0=11)
+    w = c.w
+    o = orc.Schedule(w.indptr.numpy(), w.indices.numpy(), w.train.numpy(), 2, [20, 20], 11, 0, 0)
+    g = rg.rg_build_schedule(c.indptr, c.indices, c.train, 2, [20, 20], 11, 0, 0)
+    assert o.n_batches > 255
+    freq = orc.frequency([o], w.n_nodes)
+    assert freq.max() > 255, "the case must need more than a byte per counter"
+    for K in (w.K, 7):
+        ids, slot = orc.top_hot(freq, w.is_local.numpy(), K)
+        v = rg.rg_cache_view(rg.rg_build_cache([g], c.gfeat, K), w.n_nodes)
+        assert np.array_equal(v["freq"].cpu().numpy().view(np.uint32), freq)
+        assert np.array_equal(v["cache_ids"].cpu().numpy(), ids)
+        assert np.array_equal(v["slot_of"].cpu().numpy(), slot)
+
+
+@pytest.mark.parametrize("tally", ["bytes", "words"])
+def test_cache_tallied_from_the_input_lists(rg, orc, tally, monkeypatch):
+    """A schedule built with the large-graph frontier passes carries no frequencies of its own: the cache tallies the
+    epochs' input lists, in bytes (four counters to a word) or in words."""
+    monkeypatch.setenv("RAPIDGNN_SPARSE_FRONTIER", "1")
+    if tally == "words":
+        monkeypatch.setenv("RAPIDGNN_NARROW_TALLY", "0")
+    c = Case("mid", orc, rg, s0=3)
+    w = c.w
+    o2 = orc.Schedule(w.indptr.numpy(), w.indices.numpy(), w.train.numpy(), w.cfg.batch_size, w.cfg.fanout, 3, 0, 1, n_threads=8)
+    g2 = rg.rg_build_schedule(c.indptr, c.indices, c.train, w.cfg.batch_size, w.cfg.fanout, 3, 0, 1)
+    freq = orc.frequency([c.osched, o2], w.n_nodes)
+    for K in (w.K, 1):
+        ids, slot = orc.top_hot(freq, w.is_local.numpy(), K)
+        v = rg.rg_cache_view(rg.rg_build_cache([c.gsched, g2], c.gfeat, K), w.n_nodes)
+        assert np.array_equal(v["freq"].cpu().numpy().view(np.uint32), freq)
+        assert np.array_equal(v["cache_ids"].cpu().numpy(), ids)
+        assert np.array_equal(v["slot_of"].cpu().numpy(), slot)
+        assert rg.rg_cache_view(rg.rg_build_cache([c.gsched, g2], c.gfeat, K), w.n_nodes)["K_eff"] == ids.size
 
 
 # ---------------------------------------------------------------- edge cases
@@ -612,9 +658,12 @@ def test_epoch_shuffle_at_the_bucket_bounds(rg, orc, T):
         assert off[-1] == T and len(off) == (T + 99) // 100 + 1
 
 
-def test_top_hot_with_an_unaligned_locality_array(case, rg, orc):
+@pytest.mark.parametrize("tally", ["bytes", "words"])
+def test_top_hot_with_an_unaligned_locality_array(case, rg, orc, tally, monkeypatch):
     """TopHot reads is_local with wide loads when its address allows them: the same array at an odd address (the
     one-by-one path) selects the same cache."""
+    if tally == "words":
+        monkeypatch.setenv("RAPIDGNN_NARROW_TALLY", "0")
     w = case.w
     shifted = torch.empty(w.n_nodes + 1, dtype=torch.uint8, device="cuda")
     shifted[1:] = case.is_local
