@@ -210,7 +210,10 @@ __device__ __forceinline__ uint64_t classify_node(uint32_t fv, uint8_t local, co
     return fv == st.t ? 1ull : 0ull;
 }
 
-constexpr int SEL_PER_THREAD = 8;         // runs of eight consecutive nodes (sixteen halves the scan of the per-workgroup totals on 10^8 nodes but costs the emit pass as much)
+#ifndef RG_SEL_PER_THREAD
+#define RG_SEL_PER_THREAD 8
+#endif
+constexpr int SEL_PER_THREAD = RG_SEL_PER_THREAD;         // runs of eight consecutive nodes (sixteen halves the scan of the per-workgroup totals on 10^8 nodes but costs the emit pass as much)
 constexpr int SEL_TILE = TOPK_THREADS * SEL_PER_THREAD;
 
 // The eight consecutive nodes of a thread, classified.  ALIGNED8 (is_local 8-byte aligned; freq always is, and a
@@ -349,7 +352,7 @@ __global__ void __launch_bounds__(TOPK_THREADS) select_scan_totals(uint64_t *__r
 template <bool ALIGNED8, typename F>
 __global__ void __launch_bounds__(TOPK_THREADS) select_emit_kernel(const F *__restrict__ freq, const uint8_t *__restrict__ is_local, int64_t n,
                                                                    const SelectState *__restrict__ stp, const uint64_t *__restrict__ block_base,
-                                                                   const uint64_t *__restrict__ tile_base, int32_t *__restrict__ cache_ids, int32_t *__restrict__ slot_of,
+                                                                   const uint64_t *__restrict__ tile_base, int32_t *__restrict__ cache_ids, uint2 *__restrict__ slot_pairs,
                                                                    const int32_t *__restrict__ row_of, int64_t *__restrict__ fill_entries)
 {
     // fill_entries[slot]: where VectorPull finds the row of the node in that slot (a8), written here while the node is at hand
@@ -363,29 +366,38 @@ __global__ void __launch_bounds__(TOPK_THREADS) select_emit_kernel(const F *__re
     for (int k = 0; k < SEL_PER_THREAD; ++k) s += c[k];
     uint64_t tot;
     uint64_t run = block_base[blockIdx.x] + tile_base[blockIdx.x / SCAN_TILE] + block_exclusive_scan_u64(s, &tot, lds);
-    int32_t slots[SEL_PER_THREAD];
+    static_assert(SEL_PER_THREAD == 8, "four consecutive lanes make up one pair of the slot map");
+    const uint64_t start = run;
+    uint32_t mine = 0;                                      // which of this thread's eight nodes are selected
 #pragma unroll
     for (int k = 0; k < SEL_PER_THREAD; ++k) {
         const int64_t v = first + k;
         const uint64_t gt_before = run >> 32, eq_before = run & 0xFFFFFFFFull;
         const bool sel = v < n && ((c[k] >> 32) != 0 || (c[k] == 1 && eq_before < st.r));
-        slots[k] = -1;
         if (sel) {
-            slots[k] = (int32_t)(gt_before + (eq_before < st.r ? eq_before : st.r));
-            cache_ids[slots[k]] = (int32_t)v;
-            fill_entries[slots[k]] = make_entry(TAG_REMOTE, row_of[v]);
+            const int64_t slot = (int64_t)(gt_before + (eq_before < st.r ? eq_before : st.r));
+            cache_ids[slot] = (int32_t)v;
+            fill_entries[slot] = make_entry(TAG_REMOTE, row_of[v]);
+            mine |= 1u << k;
         }
         run += c[k];
     }
-    if (first + SEL_PER_THREAD <= n) {                     // slot_of is the library's own array: 16-byte aligned at a multiple of eight
-#pragma unroll
-        for (int q = 0; q < SEL_PER_THREAD / 4; ++q)
-            *reinterpret_cast<int4 *>(slot_of + first + 4 * q) = make_int4(slots[4 * q], slots[4 * q + 1], slots[4 * q + 2], slots[4 * q + 3]);
-    } else {
-#pragma unroll
-        for (int k = 0; k < SEL_PER_THREAD; ++k)
-            if (first + k < n) slot_of[first + k] = slots[k];
+    // the slot map's pair for 32 node IDs (see slot_lookup): bits from four lanes, the rank from the first of them
+    const int lane = threadIdx.x & 63;
+    uint32_t word = mine << (8 * (lane & 3));
+    word |= __shfl_xor(word, 1, 64);
+    word |= __shfl_xor(word, 2, 64);
+    if ((lane & 3) == 0) {
+        const uint64_t gt_before = start >> 32, eq_before = start & 0xFFFFFFFFull;
+        slot_pairs[first >> 5] = make_uint2(word, (uint32_t)(gt_before + (eq_before < st.r ? eq_before : st.r)));
     }
+}
+
+// The slot map as the int32_t[n_nodes] array the cache's view hands out (made when first asked for).
+__global__ void widen_slots_kernel(const uint2 *__restrict__ pairs, int64_t n, int32_t *__restrict__ slot_of)
+{
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    for (int64_t v = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; v < n; v += stride) slot_of[v] = slot_lookup(pairs, (uint32_t)v);
 }
 
 // ---------------------------------------------------------------- a5/a9: routing plan
@@ -403,12 +415,12 @@ __device__ __forceinline__ uint32_t batch_of_pos(const int64_t *__restrict__ off
 struct RouteSources {
     const uint8_t *is_local;
     const int32_t *row_of;
-    const int32_t *slot_of;
+    const uint2 *slot_pairs;         // see slot_lookup
 };
 __device__ __forceinline__ int64_t route_of(const RouteSources &r, int64_t v)
 {
     if (r.is_local[v]) return make_entry(TAG_LOCAL, r.row_of[v]);
-    const int32_t slot = r.slot_of[v];
+    const int32_t slot = slot_lookup(r.slot_pairs, (uint32_t)v);
     return slot >= 0 ? make_entry(TAG_CACHE, slot) : make_entry(TAG_REMOTE, r.row_of[v]);
 }
 
@@ -558,6 +570,26 @@ rg_status cache_freq_view(const rg_cache *cc, const uint32_t **out)
     return RG_OK;
 }
 
+// slot_of as int32_t[n_nodes] for rg_cache_view, made from the slot map at the first request in the same way.
+rg_status cache_slot_view(const rg_cache *cc, const int32_t **out)
+{
+    rg_cache *c = const_cast<rg_cache *>(cc);
+    std::lock_guard<std::mutex> lk(c->view_mu);
+    if (!c->slot_of && c->slot_pairs && c->n_nodes > 0) {
+        hipStream_t side = nullptr;
+        RG_TRY(helper_stream(&side));
+        int32_t *wide = nullptr;
+        RG_TRY(c->arena.dev_n<int32_t>((uint64_t)c->n_nodes, &wide));
+        const unsigned grid = (unsigned)std::max<int64_t>(1, std::min<int64_t>((c->n_nodes + 255) / 256, 1 << 16));
+        hipLaunchKernelGGL(widen_slots_kernel, dim3(grid), dim3(256), 0, side, c->slot_pairs, c->n_nodes, wide);
+        RG_HIP(hipGetLastError());
+        RG_HIP(hipStreamSynchronize(side));
+        c->slot_of = wide;
+    }
+    *out = c->slot_of;
+    return RG_OK;
+}
+
 static rg_status build_cache_impl(const rg_schedule *const *epochs, uint32_t n_epochs, const rg_features *f, uint64_t K,
                                   const rg_allocator *a, hipStream_t st, rg_cache *c)
 {
@@ -585,7 +617,6 @@ static rg_status build_cache_impl(const rg_schedule *const *epochs, uint32_t n_e
     void *tally = nullptr;
     RG_TRY(c->arena.dev(tally_bytes ? tally_bytes : 16, &tally));
     if (narrow) c->freq8 = (uint8_t *)tally; else c->freq = (uint32_t *)tally;
-    RG_TRY(c->arena.dev_n<int32_t>((uint64_t)n, &c->slot_of));
     RG_HIP(hipMemsetAsync(tally, 0, tally_bytes, st));
     for (uint32_t e = 0; e < n_epochs; ++e) {
         const rg_schedule *s = epochs[e];
@@ -656,17 +687,18 @@ static rg_status build_cache_impl(const rg_schedule *const *epochs, uint32_t n_e
     RG_TRY(c->arena.dev_n<int32_t>(c->K_eff, &c->cache_ids));
     int64_t *fill_entries = nullptr;
     RG_TRY(tmp.dev_n<int64_t>(c->K_eff ? c->K_eff : 1, &fill_entries));
+    RG_TRY(c->arena.dev_n<uint2>((uint64_t)std::max<int64_t>(sel_blocks, 1) * (SEL_TILE / 32), &c->slot_pairs));      // whole tiles: every thread of the select pass writes its share
     if (sel_blocks > 0) {
         ScopedTimer tm(KG_TOPK, st);
         const dim3 sg((unsigned)sel_blocks), sb(TOPK_THREADS);
         if (narrow && local8)
-            hipLaunchKernelGGL((select_emit_kernel<true, uint8_t>), sg, sb, 0, st, c->freq8, f->is_local, n, stp, block_tot, tile_tot, c->cache_ids, c->slot_of, f->row_of, fill_entries);
+            hipLaunchKernelGGL((select_emit_kernel<true, uint8_t>), sg, sb, 0, st, c->freq8, f->is_local, n, stp, block_tot, tile_tot, c->cache_ids, c->slot_pairs, f->row_of, fill_entries);
         else if (narrow)
-            hipLaunchKernelGGL((select_emit_kernel<false, uint8_t>), sg, sb, 0, st, c->freq8, f->is_local, n, stp, block_tot, tile_tot, c->cache_ids, c->slot_of, f->row_of, fill_entries);
+            hipLaunchKernelGGL((select_emit_kernel<false, uint8_t>), sg, sb, 0, st, c->freq8, f->is_local, n, stp, block_tot, tile_tot, c->cache_ids, c->slot_pairs, f->row_of, fill_entries);
         else if (local8)
-            hipLaunchKernelGGL((select_emit_kernel<true, uint32_t>), sg, sb, 0, st, c->freq, f->is_local, n, stp, block_tot, tile_tot, c->cache_ids, c->slot_of, f->row_of, fill_entries);
+            hipLaunchKernelGGL((select_emit_kernel<true, uint32_t>), sg, sb, 0, st, c->freq, f->is_local, n, stp, block_tot, tile_tot, c->cache_ids, c->slot_pairs, f->row_of, fill_entries);
         else
-            hipLaunchKernelGGL((select_emit_kernel<false, uint32_t>), sg, sb, 0, st, c->freq, f->is_local, n, stp, block_tot, tile_tot, c->cache_ids, c->slot_of, f->row_of, fill_entries);
+            hipLaunchKernelGGL((select_emit_kernel<false, uint32_t>), sg, sb, 0, st, c->freq, f->is_local, n, stp, block_tot, tile_tot, c->cache_ids, c->slot_pairs, f->row_of, fill_entries);
     }
     RG_HIP(hipGetLastError());
 
@@ -693,7 +725,7 @@ static rg_status build_cache_impl(const rg_schedule *const *epochs, uint32_t n_e
 
     // ---- a5/a9: plans, miss lists and counts for every batch of every epoch
     c->plans.resize(n_epochs);
-    const RouteSources rs{f->is_local, f->row_of, c->slot_of};
+    const RouteSources rs{f->is_local, f->row_of, c->slot_pairs};
     int64_t listed = 0;                                   // input nodes over all epochs
     for (uint32_t e = 0; e < n_epochs; ++e) listed += epochs[e]->hop[epochs[e]->L].off_host[epochs[e]->n_batches];
     int64_t *route = nullptr;

@@ -673,7 +673,7 @@ rg_status rg_cache_view(const rg_cache *c, uint64_t *K_eff, const int32_t **cach
     if (K_eff) *K_eff = c->K_eff;
     if (cache_ids_dev) *cache_ids_dev = c->cache_ids;
     if (freq_dev) RG_TRY(cache_freq_view(c, freq_dev));
-    if (slot_of_dev) *slot_of_dev = c->slot_of;
+    if (slot_of_dev) RG_TRY(cache_slot_view(c, slot_of_dev));
     if (rows_dev) *rows_dev = c->rows;
     if (stride) *stride = c->stride;
     return RG_OK;

@@ -186,7 +186,7 @@ bool is_device_memory(const void *p)
 
 // Routing of a single batch computed on the spot (no cache, or a schedule the cache has no plan for).
 __global__ void route_batch_kernel(const int32_t *__restrict__ ids, int64_t n, const uint8_t *__restrict__ is_local, const int32_t *__restrict__ row_of,
-                                   const int32_t *__restrict__ slot_of, int64_t *__restrict__ entry, unsigned long long *__restrict__ counts /* local, hit, miss */)
+                                   const uint2 *__restrict__ slot_pairs /* see slot_lookup; NULL: no cache */, int64_t *__restrict__ entry, unsigned long long *__restrict__ counts /* local, hit, miss */)
 {
     const int64_t j = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     int64_t tag = -1;
@@ -195,7 +195,7 @@ __global__ void route_batch_kernel(const int32_t *__restrict__ ids, int64_t n, c
         int64_t row;
         if (is_local[v]) { tag = TAG_LOCAL; row = row_of[v]; }
         else {
-            const int32_t slot = slot_of ? slot_of[v] : -1;
+            const int32_t slot = slot_pairs ? slot_lookup(slot_pairs, (uint32_t)v) : -1;
             if (slot >= 0) { tag = TAG_CACHE; row = slot; }
             else { tag = TAG_REMOTE; row = row_of[v]; }
         }
@@ -281,7 +281,7 @@ extern "C" rg_status rg_gather_batch_noalloc(const rg_schedule *s, const rg_cach
     hipLaunchKernelGGL(clear_counts_kernel, dim3(1), dim3(64), 0, st, counts);
     if (m > 0) {
         hipLaunchKernelGGL(route_batch_kernel, dim3((unsigned)((m + 255) / 256)), dim3(256), 0, st, h.ids + off, m, f->is_local, f->row_of,
-                           c ? c->slot_of : nullptr, entry, counts);
+                           c ? c->slot_pairs : nullptr, entry, counts);
         RG_HIP(hipGetLastError());
         RG_TRY(launch_gather(entry, m, nullptr, 0, 1, src, f->row_bytes, (uint8_t *)out, out_stride, st, -1));      // (group -1: no event timers, they are created on demand)
     }
@@ -360,7 +360,7 @@ extern "C" rg_status rg_gather_batch(const rg_schedule *s, const rg_cache *c, co
         {
             ScopedTimer tm(KG_PLAN, st);
             hipLaunchKernelGGL(route_batch_kernel, dim3((unsigned)((m + 255) / 256)), dim3(256), 0, st, h.ids + off, m, f->is_local, f->row_of,
-                               c ? c->slot_of : nullptr, entry, counts);
+                               c ? c->slot_pairs : nullptr, entry, counts);
         }
         RG_HIP(hipGetLastError());
         RG_TRY(launch_gather(entry, m, nullptr, 0, 1, src, f->row_bytes, (uint8_t *)out, out_stride, st, KG_GATHER));
@@ -472,7 +472,7 @@ extern "C" rg_status rg_classify_batch(const rg_schedule *s, const rg_cache *c, 
     if (m > 0) {
         ScopedTimer tm(KG_PLAN, st);
         hipLaunchKernelGGL(route_batch_kernel, dim3((unsigned)((m + 255) / 256)), dim3(256), 0, st, h.ids + off, m, f->is_local, f->row_of,
-                           c ? c->slot_of : nullptr, entry, counts);
+                           c ? c->slot_pairs : nullptr, entry, counts);
     }
     unsigned long long hc[3] = {0, 0, 0};
     hipError_t e1 = hipGetLastError();

@@ -150,6 +150,19 @@ constexpr int64_t TAG_LOCAL = 0, TAG_CACHE = 1, TAG_REMOTE = 2;
 constexpr int TAG_SHIFT = 62;
 constexpr uint64_t ROW_MASK = ((uint64_t)1 << TAG_SHIFT) - 1;
 __host__ __device__ inline int64_t make_entry(int64_t tag, int64_t row) { return (int64_t)(((uint64_t)tag << TAG_SHIFT) | ((uint64_t)row & ROW_MASK)); }
+
+// ---------------------------------------------------------------- slot of a cached node
+// Slot j of the cache table holds the j-th smallest cached ID, so a node's slot is its rank among the cached IDs.
+// The cache keeps that as one pair per 32 node IDs -- x: which of them are cached, y: how many cached IDs lie in
+// front of the 32 -- a quarter of a byte per node instead of the four of a dense slot_of array (28 MB against
+// 444 MB on a graph of 10^8 nodes, so lookups meet cached lines and the select pass has next to nothing to write).
+__device__ __forceinline__ int32_t slot_lookup(const uint2 *__restrict__ pairs, uint32_t v)
+{
+    const uint2 p = pairs[v >> 5];
+    const uint32_t bit = 1u << (v & 31);
+    return (p.x & bit) ? (int32_t)(p.y + __popc(p.x & (bit - 1))) : -1;
+}
+
 __host__ __device__ inline int64_t entry_tag(int64_t e) { return (int64_t)((uint64_t)e >> TAG_SHIFT); }
 __host__ __device__ inline int64_t entry_row(int64_t e) { return (int64_t)((uint64_t)e & ROW_MASK); }
 
@@ -164,8 +177,9 @@ struct rg_cache {
     int32_t *cache_ids = nullptr;    // dev, ascending
     uint32_t *freq = nullptr;        // dev, [n_nodes]; where the tally was kept in bytes: NULL until rg_cache_view asks for it
     uint8_t *freq8 = nullptr;        // dev, [n_nodes rounded up to 16]: the tally in bytes (no frequency can exceed 255), or NULL
-    std::mutex view_mu;              // guards the widening of freq8 into freq
-    int32_t *slot_of = nullptr;      // dev, [n_nodes]
+    std::mutex view_mu;              // guards the making of freq and slot_of for rg_cache_view
+    uint2 *slot_pairs = nullptr;     // dev, one pair per 32 node IDs: the slot map (see slot_lookup)
+    int32_t *slot_of = nullptr;      // dev, [n_nodes]: NULL until rg_cache_view asks for it
     void *rows = nullptr;            // dev, K_eff * stride
     std::vector<rg::Plan> plans;
     hipEvent_t ev_fork = nullptr, ev_join = nullptr;
@@ -219,6 +233,7 @@ void reap_retired(bool wait);
 
 // freq as rg_cache_view hands it out (widened from the byte tally at the first request)
 rg_status cache_freq_view(const rg_cache *c, const uint32_t **out);
+rg_status cache_slot_view(const rg_cache *c, const int32_t **out);
 
 // One non-blocking stream per device, owned by the library and kept until the process ends: a call that has two
 // independent pieces of device work forks the second onto it (event from the caller's stream, event back) so that
