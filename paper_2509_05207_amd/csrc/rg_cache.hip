@@ -431,68 +431,110 @@ __global__ void route_table_kernel(int64_t n, RouteSources r, int64_t *__restric
     for (int64_t v = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; v < n; v += stride) route[v] = route_of(r, v);
 }
 
-// entry[j] = route[ids[j]] for every listed input node, the miss flag (for the miss-list scan) and
-// per-batch counts of local rows and cache hits.  A block covers PLAN_TILE consecutive positions and
-// adds its counts once when it lies inside one batch (nearly always), else position by position.
+// entry[j] = route[ids[j]] for every listed input node, which of them are misses (one bit each, in position order:
+// a wave's ballot is the 64-bit word of its 64 consecutive positions), the misses of every tile of PLAN_TILE
+// positions, and per-batch counts of local rows and cache hits.  A block covers one tile and adds its counts once
+// when it lies inside one batch (nearly always), else position by position.
 constexpr int PLAN_THREADS = 256;
 constexpr int PLAN_PER_THREAD = 4;
 constexpr int PLAN_TILE = PLAN_THREADS * PLAN_PER_THREAD;
+constexpr int PLAN_TILE_WORDS = PLAN_TILE / 64;          // miss-bit words per tile
 
 __global__ void __launch_bounds__(PLAN_THREADS) plan_kernel(const int32_t *__restrict__ ids, int64_t n, const int64_t *__restrict__ batch_off, uint32_t n_batches,
                                                             const int64_t *__restrict__ route /* or NULL: look the three arrays up */, RouteSources rs,
-                                                            int64_t *__restrict__ entry, int32_t *__restrict__ miss_flag,
+                                                            int64_t *__restrict__ entry, unsigned long long *__restrict__ miss_bits /* [tiles * PLAN_TILE_WORDS] */,
+                                                            int32_t *__restrict__ tile_miss /* [tiles] */,
                                                             unsigned long long *__restrict__ counts /* [n_batches][2]: local, hit */)
 {
-    __shared__ unsigned int red[2][PLAN_THREADS / 64];
+    __shared__ unsigned int red[3][PLAN_THREADS / 64];
     const int64_t tile0 = (int64_t)blockIdx.x * PLAN_TILE;
     const int64_t tile_last = (tile0 + PLAN_TILE <= n ? tile0 + PLAN_TILE : n) - 1;
     const uint32_t b_first = batch_of_pos(batch_off, n_batches, tile0);
     const bool one_batch = batch_off[b_first + 1] > tile_last;                 // block-uniform
-    unsigned int n_local = 0, n_hit = 0;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    unsigned int n_local = 0, n_hit = 0, n_miss = 0;                           // n_miss: of the wave (the same in all its lanes)
 #pragma unroll
     for (int k = 0; k < PLAN_PER_THREAD; ++k) {
         const int64_t j = tile0 + (int64_t)k * PLAN_THREADS + threadIdx.x;
+        int64_t tag = -1;
         if (j < n) {
             const int64_t e = route ? route[ids[j]] : route_of(rs, ids[j]);
-            const int64_t tag = entry_tag(e);
+            tag = entry_tag(e);
             entry[j] = e;
-            miss_flag[j] = tag == TAG_REMOTE ? 1 : 0;
             if (one_batch) { n_local += tag == TAG_LOCAL; n_hit += tag == TAG_CACHE; }
             else if (tag != TAG_REMOTE) {
                 const uint32_t b = batch_of_pos(batch_off, n_batches, j);
                 atomicAdd(&counts[2 * (uint64_t)b + (tag == TAG_CACHE ? 1 : 0)], 1ull);
             }
         }
+        const unsigned long long m = __ballot(tag == TAG_REMOTE);
+        if (lane == 0) miss_bits[(uint64_t)blockIdx.x * PLAN_TILE_WORDS + k * (PLAN_THREADS / 64) + wave] = m;
+        n_miss += (unsigned int)__popcll(m);
     }
-    if (!one_batch) return;
     for (int o = 32; o > 0; o >>= 1) { n_local += __shfl_down(n_local, o, 64); n_hit += __shfl_down(n_hit, o, 64); }
-    if ((threadIdx.x & 63) == 0) { red[0][threadIdx.x >> 6] = n_local; red[1][threadIdx.x >> 6] = n_hit; }
+    if (lane == 0) { red[0][wave] = n_local; red[1][wave] = n_hit; red[2][wave] = n_miss; }
     __syncthreads();
     if (threadIdx.x == 0) {
-        unsigned int a = 0, h = 0;
-        for (int w = 0; w < PLAN_THREADS / 64; ++w) { a += red[0][w]; h += red[1][w]; }
-        if (a) atomicAdd(&counts[2 * (uint64_t)b_first], (unsigned long long)a);
-        if (h) atomicAdd(&counts[2 * (uint64_t)b_first + 1], (unsigned long long)h);
+        unsigned int a = 0, h = 0, m = 0;
+        for (int w = 0; w < PLAN_THREADS / 64; ++w) { a += red[0][w]; h += red[1][w]; m += red[2][w]; }
+        tile_miss[blockIdx.x] = (int32_t)m;
+        if (one_batch) {
+            if (a) atomicAdd(&counts[2 * (uint64_t)b_first], (unsigned long long)a);
+            if (h) atomicAdd(&counts[2 * (uint64_t)b_first + 1], (unsigned long long)h);
+        }
     }
 }
 
-// miss_rows[miss_scan[j]] = j - batch_off[batch(j)] for every miss; miss_off[b] = miss_scan[batch_off[b]]
-__global__ void miss_list_kernel(const int32_t *__restrict__ miss_flag, const int64_t *__restrict__ miss_scan, int64_t n,
-                                 const int64_t *__restrict__ batch_off, uint32_t n_batches, int32_t *__restrict__ miss_rows)
+// Misses in front of position pos: those of the tiles in front of its tile (tile_scan) and of the words and bits in front of it inside the tile.
+__device__ __forceinline__ int64_t misses_before(const unsigned long long *__restrict__ miss_bits, const int64_t *__restrict__ tile_scan, int64_t pos)
 {
-    const int64_t j0 = (int64_t)blockIdx.x * blockDim.x, j = j0 + threadIdx.x;
-    // almost every workgroup lies inside one batch: its first row's batch then serves all of its rows
-    const uint32_t b_first = batch_of_pos(batch_off, n_batches, j0);
-    const int64_t end_first = batch_off[b_first + 1];
-    if (j >= n || !miss_flag[j]) return;
-    const uint32_t b = j < end_first ? b_first : batch_of_pos(batch_off, n_batches, j);
-    miss_rows[miss_scan[j]] = (int32_t)(j - batch_off[b]);
+    const int64_t tile = pos / PLAN_TILE, word = pos >> 6;
+    int64_t cnt = tile_scan[tile];
+    for (int64_t w = tile * PLAN_TILE_WORDS; w < word; ++w) cnt += __popcll(miss_bits[w]);
+    const int bit = (int)(pos & 63);
+    if (bit) cnt += __popcll(miss_bits[word] & ((1ull << bit) - 1ull));
+    return cnt;
 }
 
-__global__ void miss_offsets_kernel(const int64_t *__restrict__ miss_scan, const int64_t *__restrict__ batch_off, uint32_t n_batches, int64_t *__restrict__ miss_off)
+// miss_off[b] = misses in front of batch b's first position (miss_off[n_batches] = all of them)
+__global__ void miss_offsets_kernel(const unsigned long long *__restrict__ miss_bits, const int64_t *__restrict__ tile_scan, int64_t n, int64_t n_tiles,
+                                    const int64_t *__restrict__ batch_off, uint32_t n_batches, int64_t *__restrict__ miss_off)
 {
     const uint32_t b = blockIdx.x * blockDim.x + threadIdx.x;
-    if (b <= n_batches) miss_off[b] = miss_scan[batch_off[b]];
+    if (b > n_batches) return;
+    const int64_t pos = batch_off[b];
+    miss_off[b] = pos >= n ? tile_scan[n_tiles] : misses_before(miss_bits, tile_scan, pos);
+}
+
+// miss_rows[rank of the miss] = its position within its batch, for every miss.  A workgroup takes one tile: every
+// wave reads the tile's PLAN_TILE_WORDS words of miss bits (one per lane), scans their bit counts, and writes the
+// misses of every fourth word.
+__global__ void __launch_bounds__(256) miss_list_kernel(const unsigned long long *__restrict__ miss_bits, const int64_t *__restrict__ tile_scan,
+                                                        const int64_t *__restrict__ batch_off, uint32_t n_batches, int32_t *__restrict__ miss_rows)
+{
+    static_assert(PLAN_TILE_WORDS <= 64 && PLAN_TILE_WORDS % 4 == 0, "a lane per word; four waves share the words");
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int64_t tile = blockIdx.x;
+    const unsigned long long mine = lane < PLAN_TILE_WORDS ? miss_bits[tile * PLAN_TILE_WORDS + lane] : 0ull;
+    if (__ballot(mine != 0ull) == 0ull) return;                  // no miss in the tile
+    int incl = __popcll(mine);
+    for (int d = 1; d < PLAN_TILE_WORDS; d <<= 1) {
+        const int y = __shfl_up(incl, d, 64);
+        if (lane >= d) incl += y;
+    }
+    const int before_word = incl - __popcll(mine);               // misses of the tile in front of this lane's word
+    const int64_t tile0 = tile * PLAN_TILE, tile_base = tile_scan[tile];
+    // almost every tile lies inside one batch: its first position's batch then serves all of its positions
+    const uint32_t b_first = batch_of_pos(batch_off, n_batches, tile0);
+    const int64_t start_first = batch_off[b_first], end_first = batch_off[b_first + 1];
+    for (int w = wave; w < PLAN_TILE_WORDS; w += 4) {
+        const unsigned long long m = __shfl(mine, w, 64);
+        const int before = __shfl(before_word, w, 64);
+        if (!((m >> lane) & 1ull)) continue;
+        const int64_t j = tile0 + 64 * w + lane;
+        const int64_t start = j < end_first ? start_first : batch_off[batch_of_pos(batch_off, n_batches, j)];
+        miss_rows[tile_base + before + __popcll(m & ((1ull << lane) - 1ull))] = (int32_t)(j - start);
+    }
 }
 
 // Routing entries, miss lists and counts of one schedule from the per-node route table.  What the
@@ -508,21 +550,24 @@ rg_status build_plan(const rg_schedule *s, const int64_t *route, const RouteSour
     RG_TRY(keep.dev_n<int64_t>((uint64_t)n, &plan->entry));
     if (beta == 0) { RG_TRY(keep.dev_n<int32_t>(0, &plan->miss_rows)); return RG_OK; }
 
-    int32_t *miss_flag = nullptr;
-    int64_t *miss_scan = nullptr, *miss_off_dev = nullptr;
+    const int64_t n_tiles = (n + PLAN_TILE - 1) / PLAN_TILE, n_words = n_tiles * PLAN_TILE_WORDS;
+    unsigned long long *miss_bits = nullptr;
+    int32_t *tile_miss = nullptr;
+    int64_t *tile_scan = nullptr, *miss_off_dev = nullptr;
     unsigned long long *counts = nullptr;
-    RG_TRY(tmp.dev_n<int32_t>((uint64_t)n, &miss_flag));
-    RG_TRY(tmp.dev_n<int64_t>((uint64_t)n + 1, &miss_scan));
+    RG_TRY(tmp.dev_n<unsigned long long>((uint64_t)std::max<int64_t>(n_words, 1), &miss_bits));
+    RG_TRY(tmp.dev_n<int32_t>((uint64_t)std::max<int64_t>(n_tiles, 1), &tile_miss));
+    RG_TRY(tmp.dev_n<int64_t>((uint64_t)n_tiles + 1, &tile_scan));
     RG_TRY(tmp.dev_n<int64_t>((uint64_t)beta + 1, &miss_off_dev));
     RG_TRY(tmp.dev_n<unsigned long long>(2 * (uint64_t)beta, &counts));
     RG_HIP(hipMemsetAsync(counts, 0, 2 * (uint64_t)beta * sizeof(unsigned long long), st));
     {
         ScopedTimer tm(KG_PLAN, st);
         if (n > 0)
-            hipLaunchKernelGGL(plan_kernel, dim3((unsigned)((n + PLAN_TILE - 1) / PLAN_TILE)), dim3(PLAN_THREADS), 0, st, h.ids, n, h.off_dev, beta,
-                               route, rs, plan->entry, miss_flag, counts);
-        RG_TRY(scan_i32_to_i64(miss_flag, miss_scan, n, tmp, st));
-        hipLaunchKernelGGL(miss_offsets_kernel, dim3((beta + 1 + 255) / 256), dim3(256), 0, st, miss_scan, h.off_dev, beta, miss_off_dev);
+            hipLaunchKernelGGL(plan_kernel, dim3((unsigned)n_tiles), dim3(PLAN_THREADS), 0, st, h.ids, n, h.off_dev, beta,
+                               route, rs, plan->entry, miss_bits, tile_miss, counts);
+        RG_TRY(scan_i32_to_i64(tile_miss, tile_scan, n_tiles, tmp, st));
+        hipLaunchKernelGGL(miss_offsets_kernel, dim3((beta + 1 + 255) / 256), dim3(256), 0, st, miss_bits, tile_scan, n, n_tiles, h.off_dev, beta, miss_off_dev);
     }
     std::vector<unsigned long long> hc(2 * (size_t)beta);
     {
@@ -535,7 +580,7 @@ rg_status build_plan(const rg_schedule *s, const int64_t *route, const RouteSour
     RG_TRY(keep.dev_n<int32_t>((uint64_t)n_miss, &plan->miss_rows));
     if (n_miss > 0) {
         ScopedTimer tm(KG_PLAN, st);
-        hipLaunchKernelGGL(miss_list_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, miss_flag, miss_scan, n, h.off_dev, beta, plan->miss_rows);
+        hipLaunchKernelGGL(miss_list_kernel, dim3((unsigned)n_tiles), dim3(256), 0, st, miss_bits, tile_scan, h.off_dev, beta, plan->miss_rows);
     }
     RG_HIP(hipGetLastError());
     for (uint32_t b = 0; b < beta; ++b) {
