@@ -303,14 +303,34 @@ def rg_build_cache(schedules, features, K, allocator=None, stream=None):
     return Cache(out.value, (features, list(schedules), allocator))
 
 
+class CacheView(dict):
+    """K_eff, cache_ids, rows (device tensors over the cache's memory) and stride, fetched at once; "freq" and
+    "slot_of" are fetched when first read, since the library may have to make those two arrays (4 bytes per node
+    each) for the occasion."""
+
+    def __init__(self, c, n_nodes):
+        super().__init__()
+        self._c, self._n = c, n_nodes
+        k, ids, rows, stride = C.c_uint64(), C.c_void_p(), C.c_void_p(), C.c_uint64()
+        _check(lib().rg_cache_view(c.h, C.byref(k), C.byref(ids), None, None, C.byref(rows), C.byref(stride)))
+        self.update(K_eff=k.value, cache_ids=_view(ids.value, k.value, "<i4", c),
+                    rows=_view(rows.value, k.value * stride.value, "<u1", c), stride=stride.value)
+
+    def __missing__(self, key):
+        p = C.c_void_p()
+        if key == "freq":
+            _check(lib().rg_cache_view(self._c.h, None, None, C.byref(p), None, None, None))
+        elif key == "slot_of":
+            _check(lib().rg_cache_view(self._c.h, None, None, None, C.byref(p), None, None))
+        else:
+            raise KeyError(key)
+        self[key] = _view(p.value, self._n, "<i4", self._c)      # counts are < 2^31: reading them as int32 is exact
+        return self[key]
+
+
 def rg_cache_view(c, n_nodes):
-    """dict with K_eff, cache_ids, freq, slot_of (device tensors), rows pointer and stride."""
-    k, ids, fr, so, rows, stride = C.c_uint64(), C.c_void_p(), C.c_void_p(), C.c_void_p(), C.c_void_p(), C.c_uint64()
-    _check(lib().rg_cache_view(c.h, C.byref(k), C.byref(ids), C.byref(fr), C.byref(so), C.byref(rows), C.byref(stride)))
-    freq_i32 = _view(fr.value, n_nodes, "<i4", c)           # counts are < 2^31: reinterpretation is exact
-    return dict(K_eff=k.value, cache_ids=_view(ids.value, k.value, "<i4", c), freq=freq_i32,
-                slot_of=_view(so.value, n_nodes, "<i4", c),
-                rows=_view(rows.value, k.value * stride.value, "<u1", c), stride=stride.value)
+    """Mapping with K_eff, cache_ids, freq, slot_of, rows (device tensors) and stride; see CacheView."""
+    return CacheView(c, n_nodes)
 
 
 def rg_gather_batch(s, c, features, batch, out, out_stride=None, out_capacity_rows=None, stream=None, side_stream=None,
