@@ -352,7 +352,7 @@ __global__ void __launch_bounds__(TOPK_THREADS) select_scan_totals(uint64_t *__r
 template <bool ALIGNED8, typename F>
 __global__ void __launch_bounds__(TOPK_THREADS) select_emit_kernel(const F *__restrict__ freq, const uint8_t *__restrict__ is_local, int64_t n,
                                                                    const SelectState *__restrict__ stp, const uint64_t *__restrict__ block_base,
-                                                                   const uint64_t *__restrict__ tile_base, int32_t *__restrict__ cache_ids, uint2 *__restrict__ slot_pairs,
+                                                                   const uint64_t *__restrict__ tile_base, int32_t *__restrict__ cache_ids, SlotRec *__restrict__ slot_pairs,
                                                                    const int32_t *__restrict__ row_of, int64_t *__restrict__ fill_entries)
 {
     // fill_entries[slot]: where VectorPull finds the row of the node in that slot (a8), written here while the node is at hand
@@ -382,19 +382,30 @@ __global__ void __launch_bounds__(TOPK_THREADS) select_emit_kernel(const F *__re
         }
         run += c[k];
     }
-    // the slot map's pair for 32 node IDs (see slot_lookup): bits from four lanes, the rank from the first of them
+    // the slot map's record for 32 node IDs (see slot_lookup): bits from four lanes, the rank from the first of them
+    uint32_t local8 = 0;                                    // which of this thread's eight nodes are local
+    if (ALIGNED8 && first + SEL_PER_THREAD <= n) {
+        const uint64_t loc = *reinterpret_cast<const uint64_t *>(is_local + first);
+#pragma unroll
+        for (int k = 0; k < SEL_PER_THREAD; ++k)
+            if ((loc >> (8 * k)) & 0xFFull) local8 |= 1u << k;
+    } else {
+#pragma unroll
+        for (int k = 0; k < SEL_PER_THREAD; ++k)
+            if (first + k < n && is_local[first + k]) local8 |= 1u << k;
+    }
     const int lane = threadIdx.x & 63;
-    uint32_t word = mine << (8 * (lane & 3));
-    word |= __shfl_xor(word, 1, 64);
-    word |= __shfl_xor(word, 2, 64);
+    uint32_t word = mine << (8 * (lane & 3)), lword = local8 << (8 * (lane & 3));
+    word |= __shfl_xor(word, 1, 64); lword |= __shfl_xor(lword, 1, 64);
+    word |= __shfl_xor(word, 2, 64); lword |= __shfl_xor(lword, 2, 64);
     if ((lane & 3) == 0) {
         const uint64_t gt_before = start >> 32, eq_before = start & 0xFFFFFFFFull;
-        slot_pairs[first >> 5] = make_uint2(word, (uint32_t)(gt_before + (eq_before < st.r ? eq_before : st.r)));
+        slot_pairs[first >> 5] = make_uint4(word, (uint32_t)(gt_before + (eq_before < st.r ? eq_before : st.r)), lword, 0u);
     }
 }
 
 // The slot map as the int32_t[n_nodes] array the cache's view hands out (made when first asked for).
-__global__ void widen_slots_kernel(const uint2 *__restrict__ pairs, int64_t n, int32_t *__restrict__ slot_of)
+__global__ void widen_slots_kernel(const SlotRec *__restrict__ pairs, int64_t n, int32_t *__restrict__ slot_of)
 {
     const int64_t stride = (int64_t)gridDim.x * blockDim.x;
     for (int64_t v = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; v < n; v += stride) slot_of[v] = slot_lookup(pairs, (uint32_t)v);
@@ -411,17 +422,19 @@ __device__ __forceinline__ uint32_t batch_of_pos(const int64_t *__restrict__ off
     return lo;
 }
 
-// Where a request for v's feature row is served from: (tag << 62) | row.
+// Where a request for v's feature row is served from: (tag << 62) | row.  One record of the slot map says whether v
+// is local and whether (and where) it is cached; row_of is read for the others only.
 struct RouteSources {
-    const uint8_t *is_local;
     const int32_t *row_of;
-    const uint2 *slot_pairs;         // see slot_lookup
+    const SlotRec *slot_pairs;       // see slot_lookup
 };
 __device__ __forceinline__ int64_t route_of(const RouteSources &r, int64_t v)
 {
-    if (r.is_local[v]) return make_entry(TAG_LOCAL, r.row_of[v]);
-    const int32_t slot = slot_lookup(r.slot_pairs, (uint32_t)v);
-    return slot >= 0 ? make_entry(TAG_CACHE, slot) : make_entry(TAG_REMOTE, r.row_of[v]);
+    const SlotRec p = r.slot_pairs[v >> 5];
+    const uint32_t bit = 1u << (v & 31);
+    if (p.z & bit) return make_entry(TAG_LOCAL, r.row_of[v]);
+    if (p.x & bit) return make_entry(TAG_CACHE, (int64_t)(p.y + __popc(p.x & (bit - 1))));
+    return make_entry(TAG_REMOTE, r.row_of[v]);
 }
 
 // route[v] for every node ID: worth building when the epochs list far more input nodes than the graph has nodes.
@@ -732,7 +745,7 @@ static rg_status build_cache_impl(const rg_schedule *const *epochs, uint32_t n_e
     RG_TRY(c->arena.dev_n<int32_t>(c->K_eff, &c->cache_ids));
     int64_t *fill_entries = nullptr;
     RG_TRY(tmp.dev_n<int64_t>(c->K_eff ? c->K_eff : 1, &fill_entries));
-    RG_TRY(c->arena.dev_n<uint2>((uint64_t)std::max<int64_t>(sel_blocks, 1) * (SEL_TILE / 32), &c->slot_pairs));      // whole tiles: every thread of the select pass writes its share
+    RG_TRY(c->arena.dev_n<SlotRec>((uint64_t)std::max<int64_t>(sel_blocks, 1) * (SEL_TILE / 32), &c->slot_pairs));      // whole tiles: every thread of the select pass writes its share
     if (sel_blocks > 0) {
         ScopedTimer tm(KG_TOPK, st);
         const dim3 sg((unsigned)sel_blocks), sb(TOPK_THREADS);
@@ -770,7 +783,7 @@ static rg_status build_cache_impl(const rg_schedule *const *epochs, uint32_t n_e
 
     // ---- a5/a9: plans, miss lists and counts for every batch of every epoch
     c->plans.resize(n_epochs);
-    const RouteSources rs{f->is_local, f->row_of, c->slot_pairs};
+    const RouteSources rs{f->row_of, c->slot_pairs};
     int64_t listed = 0;                                   // input nodes over all epochs
     for (uint32_t e = 0; e < n_epochs; ++e) listed += epochs[e]->hop[epochs[e]->L].off_host[epochs[e]->n_batches];
     int64_t *route = nullptr;

@@ -186,7 +186,7 @@ bool is_device_memory(const void *p)
 
 // Routing of a single batch computed on the spot (no cache, or a schedule the cache has no plan for).
 __global__ void route_batch_kernel(const int32_t *__restrict__ ids, int64_t n, const uint8_t *__restrict__ is_local, const int32_t *__restrict__ row_of,
-                                   const uint2 *__restrict__ slot_pairs /* see slot_lookup; NULL: no cache */, int64_t *__restrict__ entry, unsigned long long *__restrict__ counts /* local, hit, miss */)
+                                   const SlotRec *__restrict__ slot_pairs /* see slot_lookup; NULL: no cache */, int64_t *__restrict__ entry, unsigned long long *__restrict__ counts /* local, hit, miss */)
 {
     const int64_t j = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     int64_t tag = -1;

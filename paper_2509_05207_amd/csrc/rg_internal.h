@@ -153,12 +153,14 @@ __host__ __device__ inline int64_t make_entry(int64_t tag, int64_t row) { return
 
 // ---------------------------------------------------------------- slot of a cached node
 // Slot j of the cache table holds the j-th smallest cached ID, so a node's slot is its rank among the cached IDs.
-// The cache keeps that as one pair per 32 node IDs -- x: which of them are cached, y: how many cached IDs lie in
-// front of the 32 -- a quarter of a byte per node instead of the four of a dense slot_of array (28 MB against
-// 444 MB on a graph of 10^8 nodes, so lookups meet cached lines and the select pass has next to nothing to write).
-__device__ __forceinline__ int32_t slot_lookup(const uint2 *__restrict__ pairs, uint32_t v)
+// The cache keeps that as one record per 32 node IDs -- x: which of them are cached, y: how many cached IDs lie in
+// front of the 32, z: which of them are local (the caller's is_local as bits), w: unused -- half a byte per node
+// instead of the four of a dense slot_of array plus the byte of is_local (55 MB against 555 MB on a graph of 10^8
+// nodes, so lookups meet cached lines and the select pass has next to nothing to write).
+typedef uint4 SlotRec;
+__device__ __forceinline__ int32_t slot_lookup(const SlotRec *__restrict__ recs, uint32_t v)
 {
-    const uint2 p = pairs[v >> 5];
+    const SlotRec p = recs[v >> 5];
     const uint32_t bit = 1u << (v & 31);
     return (p.x & bit) ? (int32_t)(p.y + __popc(p.x & (bit - 1))) : -1;
 }
@@ -178,7 +180,7 @@ struct rg_cache {
     uint32_t *freq = nullptr;        // dev, [n_nodes]; where the tally was kept in bytes: NULL until rg_cache_view asks for it
     uint8_t *freq8 = nullptr;        // dev, [n_nodes rounded up to 16]: the tally in bytes (no frequency can exceed 255), or NULL
     std::mutex view_mu;              // guards the making of freq and slot_of for rg_cache_view
-    uint2 *slot_pairs = nullptr;     // dev, one pair per 32 node IDs: the slot map (see slot_lookup)
+    rg::SlotRec *slot_pairs = nullptr;   // dev, one record per 32 node IDs: the slot map (see slot_lookup)
     int32_t *slot_of = nullptr;      // dev, [n_nodes]: NULL until rg_cache_view asks for it
     void *rows = nullptr;            // dev, K_eff * stride
     std::vector<rg::Plan> plans;
