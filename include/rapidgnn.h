@@ -208,20 +208,23 @@ typedef struct rg_features {
  *   K         n_hot, the cache capacity in rows (0 = no row cached)
  * Device memory of the table: K_eff * round_up(row_bytes, 16) <= n_hot * d
  * (one buffer of the bound in Sec. 3 "Invariants and bounds").  Beside it the
- * cache keeps slot_of (4 bytes per node) and the tally: 1 byte per node where
- * the given epochs have at most 255 batches together (no frequency can then
- * exceed 255), else 4.  Environment: RAPIDGNN_NARROW_TALLY=0 forbids the byte
- * form (same results either way).
+ * cache keeps a map from node to slot (half a byte per node: which IDs are
+ * cached and local, and ranks) and the tally: 1 byte per node where the given
+ * epochs have at most 255 batches together (no frequency can then exceed 255),
+ * else 4.  Environment: RAPIDGNN_NARROW_TALLY=0 forbids the byte form (same
+ * results either way).  The fill of the table runs on a stream the library
+ * owns, beside the routing work on `stream`; the call returns after both.
  */
 rg_status rg_build_cache(const rg_schedule *const *epochs, uint32_t n_epochs, const rg_features *f,
                          uint64_t K, const rg_allocator *a, void *stream, rg_cache **out);
 
 /* Views of the cache: K_eff, the cached ids (dev, ascending), freq (dev,
  * [n_nodes]), slot_of (dev, [n_nodes], -1 = not cached), the table and its row
- * stride.  Any output pointer may be NULL.  Where the tally was kept in bytes,
- * the first call that asks for freq makes the uint32_t array (4 bytes per node
- * from the cache's allocator, one kernel, waited for); calls that pass
- * freq_dev = NULL never pay for it. */
+ * stride.  Any output pointer may be NULL.  The cache itself keeps slot_of as
+ * a rank map and, where it could, the tally in bytes: the first call that asks
+ * for slot_of (for freq) makes the array (4 bytes per node from the cache's
+ * allocator, one kernel, waited for); calls that pass NULL for both never pay
+ * for them.  Safe to call from several threads. */
 rg_status rg_cache_view(const rg_cache *c, uint64_t *K_eff, const int32_t **cache_ids_dev,
                         const uint32_t **freq_dev, const int32_t **slot_of_dev,
                         const void **rows_dev, uint64_t *stride);
