@@ -768,6 +768,7 @@ struct HopArgs {
     uint32_t fanout;
     const int64_t *samp_off; int32_t *samp_nbr;
     const int64_t *tile_off; TileRecs tile; int64_t n_tiles; int32_t *tile_out;      // tile j writes tile_out[j * fanout ..)
+    int merge_span;                                                    // tiles a wave of sample_merge_kernel looks at per round
     ReachedMaps reached;
     unsigned long long *next_work;                                     // work items are handed out in order through this counter
 };
@@ -880,26 +881,40 @@ __global__ void __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(CAP <= 
     }
 }
 
-// One wave per tile job; the wave that holds a long row's first tile samples the row's
-// concatenated tile results (T * f IDs, row order, all distinct) into the final output.
+// A long row's concatenated tile results (T * f IDs, row order, all distinct) are sampled into the final output by
+// the wave that finds the row's first tile.  A wave looks at 64 tiles at once, a lane each (hub rows have hundreds of
+// tiles, so first tiles are few: walking the tiles one per wave-iteration cost two dependent loads per tile), and
+// then takes the rows whose first tiles it found one after the other.  a.merge_span <= 64 tiles per look: fewer
+// where the launch has too few tiles to give every wave 64 of them (rows of two or three tiles would queue up).
 template <int CAP, int MARK>
 __global__ void __launch_bounds__(64) sample_merge_kernel(HopArgs a)
 {
     __shared__ uint32_t buf[CAP];
     const int lane = threadIdx.x;
     const int f = (int)a.fanout;
-    for (int64_t w = blockIdx.x; w < a.n_tiles; w += gridDim.x) {
-        const int64_t i = a.tile.node[w];
-        if (a.tile_off[i] != w) continue;
-        const int64_t T = a.tile_off[i + 1] - a.tile_off[i];
-        const uint32_t b = a.rec.batch[i];
-        const uint64_t S = a.rec.state[i];
-        const int32_t *row = a.tile_out + w * f;
-        const int len = (int)(T * f);
-        u32x4 ahead = {0u, 0u, 0u, 0u};
-        if (len > 64) ahead = row_ahead(row, len, lane);
-        sample_row<CAP, MARK>(row, len, lane < len ? (uint32_t)row[lane] : 0u, ahead, f, (uint32_t)S, (uint32_t)(S >> 32), lane, buf,
-                              a.samp_nbr + a.samp_off[i], reached_of<MARK>(a.reached, b));
+    const int span = a.merge_span;
+    for (int64_t base = (int64_t)blockIdx.x * span; base < a.n_tiles; base += (int64_t)gridDim.x * span) {
+        int64_t i_lane = -1;
+        if (lane < span && base + lane < a.n_tiles) {
+            const int64_t i = a.tile.node[base + lane];
+            if (a.tile_off[i] == base + lane) i_lane = i;
+        }
+        unsigned long long firsts = ballot64(i_lane >= 0);
+        while (firsts != 0ull) {
+            const int l = __builtin_amdgcn_readfirstlane(__ffsll((long long)firsts) - 1);
+            firsts &= firsts - 1ull;
+            const int64_t i = bcast64(i_lane, l);
+            const int64_t w = base + l;
+            const int64_t T = a.tile_off[i + 1] - w;
+            const uint32_t b = a.rec.batch[i];
+            const uint64_t S = a.rec.state[i];
+            const int32_t *row = a.tile_out + w * f;
+            const int len = (int)(T * f);
+            u32x4 ahead = {0u, 0u, 0u, 0u};
+            if (len > 64) ahead = row_ahead(row, len, lane);
+            sample_row<CAP, MARK>(row, len, lane < len ? (uint32_t)row[lane] : 0u, ahead, f, (uint32_t)S, (uint32_t)(S >> 32), lane, buf,
+                                  a.samp_nbr + a.samp_off[i], reached_of<MARK>(a.reached, b));
+        }
     }
 }
 
@@ -1114,9 +1129,11 @@ rg_status sample_hop(const rg_graph *g, HopData &cur, uint32_t beta, const uint6
         unsigned long long *next_work = nullptr;
         RG_TRY(tmp.dev_n<unsigned long long>(1, &next_work));
         RG_HIP(hipMemsetAsync(next_work, 0, sizeof(unsigned long long), st));
-        HopArgs a{g->indices, cur.ids, n_cur, 0, 0, short_mode != 0 ? SHORT_ROW : 0, short_mode == 2 ? 1 : 0, rec, fanout, cur.samp_off, cur.samp_nbr, tile_off, tile, n_tiles, tile_out, reached, next_work};
+        int merge_span = 64;                              // tiles per look of a merging wave: 64 if that still occupies the chip's waves
+        while (merge_span > 1 && n_tiles / merge_span < (int64_t)n_cu * 32) merge_span >>= 1;
+        const unsigned merge_grid = (unsigned)std::max<int64_t>(1, std::min<int64_t>((n_tiles + merge_span - 1) / merge_span, (int64_t)n_cu * 64));
+        HopArgs a{g->indices, cur.ids, n_cur, 0, 0, short_mode != 0 ? SHORT_ROW : 0, short_mode == 2 ? 1 : 0, rec, fanout, cur.samp_off, cur.samp_nbr, tile_off, tile, n_tiles, tile_out, merge_span, reached, next_work};
         ScopedTimer tm(KG_SAMPLER, st);
-        const unsigned merge_grid = (unsigned)std::max<int64_t>(1, std::min<int64_t>(n_tiles, (int64_t)n_cu * 64));
         // worth it where a group is long work: rows of a thousand IDs on average, tiles aside (short rows finish a
         // group of 64 in no time, and four times the requests to the work counter then cost more than the tail does;
         // measured: Medium, 2,500 IDs per row, 4 % faster; large_sparse and partition_share, a few hundred, 1-8 % slower)
