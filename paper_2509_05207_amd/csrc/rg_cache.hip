@@ -210,10 +210,7 @@ __device__ __forceinline__ uint64_t classify_node(uint32_t fv, uint8_t local, co
     return fv == st.t ? 1ull : 0ull;
 }
 
-#ifndef RG_SEL_PER_THREAD
-#define RG_SEL_PER_THREAD 8
-#endif
-constexpr int SEL_PER_THREAD = RG_SEL_PER_THREAD;         // runs of eight consecutive nodes (sixteen halves the scan of the per-workgroup totals on 10^8 nodes but costs the emit pass as much)
+constexpr int SEL_PER_THREAD = 8;         // runs of eight consecutive nodes: a quarter of a slot-map record per thread (sixteen measured 8 % slower over the byte tally)
 constexpr int SEL_TILE = TOPK_THREADS * SEL_PER_THREAD;
 
 // The eight consecutive nodes of a thread, classified.  ALIGNED8 (is_local 8-byte aligned; freq always is, and a
@@ -268,7 +265,6 @@ __device__ __forceinline__ void classify_mine(const F *__restrict__ freq, const 
     for (int h = 0; h < SEL_PER_THREAD / 8; ++h) classify_eight<ALIGNED8>(freq, is_local, first + 8 * h, n, st, c + 8 * h);
 }
 
-template <int THREADS = TOPK_THREADS>
 __device__ __forceinline__ uint64_t block_exclusive_scan_u64(uint64_t x, uint64_t *total, uint64_t *lds)
 {
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -280,7 +276,7 @@ __device__ __forceinline__ uint64_t block_exclusive_scan_u64(uint64_t x, uint64_
     if (lane == 63) lds[wave] = incl;
     __syncthreads();
     uint64_t base = 0, tot = 0;
-    for (int w = 0; w < THREADS / 64; ++w) {
+    for (int w = 0; w < TOPK_THREADS / 64; ++w) {
         const uint64_t s = lds[w];
         if (w < wave) base += s;
         tot += s;
