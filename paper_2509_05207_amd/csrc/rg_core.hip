@@ -138,11 +138,33 @@ struct StagePool {
 StagePool g_stages;
 }  // namespace
 
+// Several small pieces are fetched by one kernel that writes them straight into the pinned block (host memory the
+// device can address), not by a copy each: a copy is a launch of its own, and they run one after the other.
+constexpr int PACK_PARTS = 8;
+struct PackArgs {
+    const uint8_t *src[PACK_PARTS];
+    uint32_t at[PACK_PARTS], bytes[PACK_PARTS];
+    int n;
+};
+__global__ void __launch_bounds__(256) pack_pieces_kernel(PackArgs a, uint8_t *__restrict__ stage)
+{
+    for (int p = 0; p < a.n; ++p) {
+        const uint8_t *src = a.src[p];
+        uint8_t *dst = stage + a.at[p];
+        const uint32_t bytes = a.bytes[p];
+        if ((((uintptr_t)src | bytes) & 3u) == 0) {                     // (the block's offsets are multiples of 16)
+            for (uint32_t i = threadIdx.x; i < bytes / 4; i += blockDim.x) reinterpret_cast<uint32_t *>(dst)[i] = reinterpret_cast<const uint32_t *>(src)[i];
+        } else {
+            for (uint32_t i = threadIdx.x; i < bytes; i += blockDim.x) dst[i] = src[i];
+        }
+    }
+}
+
 Readback::Readback(hipStream_t st) : st_(st) {}
 Readback::~Readback()
 {
     if (!stage_) return;
-    if (!parts_.empty()) (void)hipStreamSynchronize(st_);      // left without wait() (an error path): copies into the block may still be in flight
+    if (in_flight_) (void)hipStreamSynchronize(st_);      // left in the middle of wait() (an error path): writes into the block may still be in flight
     g_stages.give(stage_);
 }
 
@@ -155,15 +177,32 @@ rg_status Readback::add(void *host_dst, const void *dev_src, size_t bytes)
         RG_HIP(hipMemcpyAsync(host_dst, dev_src, bytes, hipMemcpyDeviceToHost, st_));
         return RG_OK;
     }
-    RG_HIP(hipMemcpyAsync(stage_ + at, dev_src, bytes, hipMemcpyDeviceToHost, st_));
-    parts_.push_back({host_dst, at, bytes});
+    parts_.push_back({host_dst, dev_src, at, bytes});
     used_ = at + bytes;
     return RG_OK;
 }
 
 rg_status Readback::wait()
 {
+    in_flight_ = true;
+    if (parts_.size() == 1) {
+        RG_HIP(hipMemcpyAsync(stage_ + parts_[0].at, parts_[0].src, parts_[0].bytes, hipMemcpyDeviceToHost, st_));
+    } else {
+        for (size_t first = 0; first < parts_.size(); first += PACK_PARTS) {
+            PackArgs a{};
+            a.n = (int)std::min<size_t>(PACK_PARTS, parts_.size() - first);
+            for (int p = 0; p < a.n; ++p) {
+                const Part &part = parts_[first + p];
+                a.src[p] = static_cast<const uint8_t *>(part.src);
+                a.at[p] = (uint32_t)part.at;
+                a.bytes[p] = (uint32_t)part.bytes;
+            }
+            hipLaunchKernelGGL(pack_pieces_kernel, dim3(1), dim3(256), 0, st_, a, stage_);
+            RG_HIP(hipGetLastError());
+        }
+    }
     RG_HIP(hipStreamSynchronize(st_));
+    in_flight_ = false;
     for (const Part &p : parts_) memcpy(p.dst, stage_ + p.at, p.bytes);
     parts_.clear();
     used_ = 0;

@@ -219,14 +219,15 @@ class Readback {
     ~Readback();
     Readback(const Readback &) = delete;
     Readback &operator=(const Readback &) = delete;
-    rg_status add(void *host_dst, const void *dev_src, size_t bytes);    // queues the copy
-    rg_status wait();                                                    // synchronises the stream; the destinations are valid afterwards
+    rg_status add(void *host_dst, const void *dev_src, size_t bytes);    // notes the piece (dev_src is read when wait() runs, in stream order)
+    rg_status wait();                                                    // fetches the pieces and synchronises the stream; the destinations are valid afterwards
   private:
-    struct Part { void *dst; size_t at, bytes; };
+    struct Part { void *dst; const void *src; size_t at, bytes; };
     hipStream_t st_;
     uint8_t *stage_ = nullptr;
     size_t used_ = 0;
     std::vector<Part> parts_;
+    bool in_flight_ = false;
 };
 
 // Handles whose destroy call found readers still in flight wait here (default allocator only); they are released by
