@@ -314,7 +314,7 @@ def test_ranges_of_batches_gathered_back_to_back(case, rg, orc, planned):
     assert e.value.status == rg.RG_ERANGE
 
 
-def test_schedule_survives_a_round_trip_through_a_file(case, rg, orc, tmp_path):
+def test_schedule_survives_a_round_trip_through_a_file(case, rg, orc, tmp_path, monkeypatch):
     """The metadata block on storage: saved, loaded into a new handle, equal to the oracle's schedule, and as good
     as the original for the cache, the plan, the gathers and the blocks."""
     w = case.w
@@ -333,8 +333,14 @@ def test_schedule_survives_a_round_trip_through_a_file(case, rg, orc, tmp_path):
     from test_gpu_parity import assert_schedules_equal
     assert_schedules_equal(rg, g, case.osched)
     ids, slot = oracle_cache(orc, case, case.osched)
-    c = rg.rg_build_cache([g], case.gfeat, w.K)
-    assert np.array_equal(rg.rg_cache_view(c, w.n_nodes)["cache_ids"].cpu().numpy(), ids)
+    freq = orc.frequency([case.osched], w.n_nodes)
+    for tally in ("0", "1"):                                   # a loaded schedule carries no frequencies: the cache tallies its input lists, in words or in bytes
+        monkeypatch.setenv("RAPIDGNN_NARROW_TALLY", tally)
+        c = rg.rg_build_cache([g], case.gfeat, w.K)
+        v = rg.rg_cache_view(c, w.n_nodes)
+        assert np.array_equal(v["cache_ids"].cpu().numpy(), ids)
+        assert np.array_equal(v["freq"].cpu().numpy().view(np.uint32), freq)
+        assert np.array_equal(v["slot_of"].cpu().numpy(), slot)
     _, off = case.osched.input_nodes()
     rows = int(off[-1])
     out = torch.empty(rows * w.row_bytes, dtype=torch.uint8, device="cuda")
