@@ -130,7 +130,7 @@ __global__ void mark_seeds_kernel(const int32_t *__restrict__ seeds, uint64_t T,
     if ((int64_t)v >= n_nodes) return;          // (refused by the host as soon as it has read check_train_kernel's count)
     const uint64_t word = (t / batch_size) * words_per_batch + (v >> 5);
     atomicOr(&seen[paired ? paired_word(word) : word], 1u << (v & 31));
-    seen_flags[word >> 3] = 1;
+    if (seen_flags) seen_flags[word >> 3] = 1;          // (NULL in the large-graph form: see clear_listed_seen_kernel)
 }
 
 // ---------------------------------------------------------------- a6 (first half): freq(v) of the epoch as column sums
@@ -493,7 +493,7 @@ __global__ void __launch_bounds__(FR_THREADS) fresh_emit_sparse_kernel(uint32_t 
                             }
                         }
                     }
-                    if (keep_seen) seen_flags[ag >> 3] = 1;
+                    if (keep_seen && seen_flags) seen_flags[ag >> 3] = 1;
                 }
             }
             *reinterpret_cast<uint4 *>(reached + 2 * ag) = make_uint4(0, 0, 0, 0);
@@ -528,6 +528,22 @@ __global__ void __launch_bounds__(FR_THREADS) clear_seen_kernel(uint32_t *__rest
             *reinterpret_cast<uint4 *>(p + 4) = make_uint4(0, 0, 0, 0);
         }
     reinterpret_cast<unsigned long long *>(seen_flags)[i] = 0ull;
+}
+
+// The large-graph form keeps no flags for `seen`: the IDs that were ever added to it are the frontier in front of the
+// last hop (the last hop's own new IDs are not added), so their groups' `seen` halves of the paired records are
+// cleared by walking that list -- one scattered 32-byte store per listed ID instead of a flag store per group in
+// every emit pass plus a pass over all flags.
+__global__ void clear_listed_seen_kernel(const int32_t *__restrict__ ids, const int64_t *__restrict__ off, uint32_t n_batches, int64_t n,
+                                         uint64_t words_per_batch, uint32_t *__restrict__ seen /* the first record's `seen` half */)
+{
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= n) return;
+    const uint32_t b = batch_of(off, n_batches, i);
+    const uint64_t word = (uint64_t)b * words_per_batch + ((uint32_t)ids[i] >> 5);
+    uint32_t *p = seen + paired_word(word & ~(uint64_t)7);
+    *reinterpret_cast<uint4 *>(p) = make_uint4(0, 0, 0, 0);
+    *reinterpret_cast<uint4 *>(p + 4) = make_uint4(0, 0, 0, 0);
 }
 
 std::atomic<uint64_t> g_next_schedule_uid{1};        // also taken by schedules loaded from a file
@@ -645,14 +661,14 @@ static rg_status build_schedule_impl(const rg_graph *g, const int32_t *train, ui
         RG_TRY(tmp.dev_zeroed(wpb * beta * sizeof(uint32_t), (void **)&reached_words, st));
     }
     RG_TRY(tmp.dev_zeroed(n_groups, (void **)&reached_flags, st));
-    RG_TRY(tmp.dev_zeroed(n_groups, (void **)&seen_flags, st));
+    if (!sparse_maps) RG_TRY(tmp.dev_zeroed(n_groups, (void **)&seen_flags, st));
     if (const char *check = getenv("RAPIDGNN_CHECK_ZERO_MAPS"); check && check[0] == '1') {
         // for tests: the maps, wherever they came from, really hold nothing but zeros (the pool of all-zero blocks keeps its promise)
         unsigned long long *n_dev = nullptr, n_host = 0;
         RG_TRY(tmp.dev_n<unsigned long long>(1, &n_dev));
         RG_HIP(hipMemsetAsync(n_dev, 0, sizeof(unsigned long long), st));
         const struct { const void *p; uint64_t bytes; } parts[4] = {{paired ? nullptr : seen, paired ? 0 : wpb * beta * 4}, {reached_words, wpb * beta * (paired ? 8u : 4u)},
-                                                                    {reached_flags, n_groups}, {seen_flags, n_groups}};
+                                                                    {reached_flags, n_groups}, {seen_flags, seen_flags ? n_groups : 0}};
         for (const auto &part : parts)
             if (part.bytes)
                 hipLaunchKernelGGL(count_nonzero_kernel, dim3(1024), dim3(256), 0, st, (const unsigned long long *)part.p, part.bytes / 8, n_dev);
@@ -733,14 +749,24 @@ static rg_status build_schedule_impl(const rg_graph *g, const int32_t *train, ui
         // fill costs per group of the whole map (scattered 32-byte stores against a streaming fill), and a group is
         // flagged by at least one input node: the fill wins unless fewer than an eighth of the groups can be flagged.
         ScopedTimer tm(KG_FRONTIER, st);
-        const uint64_t listed = L > 0 ? (uint64_t)s->hop[L].off_host[beta] : T;
-        if (listed > n_groups / (paired ? 4 : 8)) {          // (paired records: the fill covers twice the bytes)
-            if (paired) RG_HIP(hipMemsetAsync(paired, 0, 2 * n_groups * FR_WORDS_PER_THREAD * sizeof(uint32_t), st));
-            else RG_HIP(hipMemsetAsync(seen, 0, n_groups * FR_WORDS_PER_THREAD * sizeof(uint32_t), st));
-            RG_HIP(hipMemsetAsync(seen_flags, 0, n_groups, st));
+        if (paired) {
+            const HopData &added = s->hop[L > 0 ? L - 1 : 0];          // every ID that was added to `seen`
+            const int64_t listed = beta ? added.off_host[beta] : 0;
+            if ((uint64_t)listed > n_groups / 4) {                    // (the fill covers both halves of the records)
+                RG_HIP(hipMemsetAsync(paired, 0, 2 * n_groups * FR_WORDS_PER_THREAD * sizeof(uint32_t), st));
+            } else if (listed > 0) {
+                hipLaunchKernelGGL(clear_listed_seen_kernel, dim3((unsigned)((listed + 255) / 256)), dim3(256), 0, st, added.ids, added.off_dev, beta, listed, wpb, seen);
+                RG_HIP(hipGetLastError());
+            }
         } else {
-            hipLaunchKernelGGL(clear_seen_kernel, dim3((unsigned)((n_groups / 8 + FR_THREADS - 1) / FR_THREADS)), dim3(FR_THREADS), 0, st, seen, seen_flags, n_groups / 8, paired ? 1 : 0);
-            RG_HIP(hipGetLastError());
+            const uint64_t listed = L > 0 ? (uint64_t)s->hop[L].off_host[beta] : T;
+            if (listed > n_groups / 8) {
+                RG_HIP(hipMemsetAsync(seen, 0, n_groups * FR_WORDS_PER_THREAD * sizeof(uint32_t), st));
+                RG_HIP(hipMemsetAsync(seen_flags, 0, n_groups, st));
+            } else {
+                hipLaunchKernelGGL(clear_seen_kernel, dim3((unsigned)((n_groups / 8 + FR_THREADS - 1) / FR_THREADS)), dim3(FR_THREADS), 0, st, seen, seen_flags, n_groups / 8, 0);
+                RG_HIP(hipGetLastError());
+            }
         }
     }
     RG_HIP(hipStreamSynchronize(st));
@@ -748,7 +774,7 @@ static rg_status build_schedule_impl(const rg_graph *g, const int32_t *train, ui
     // every map is all-zero again and nothing writes them any more
     if (paired) tmp.free_zeroed(paired);
     else { tmp.free_zeroed(seen); tmp.free_zeroed(reached_words); }
-    tmp.free_zeroed(seen_flags);
+    if (seen_flags) tmp.free_zeroed(seen_flags);
     tmp.free_zeroed(reached_flags);
     if (maps.bytes) tmp.free_zeroed(maps.bytes);
     return RG_OK;
