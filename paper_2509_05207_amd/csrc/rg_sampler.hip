@@ -758,6 +758,30 @@ __global__ void tile_records_kernel(const int64_t *__restrict__ tile_off, const 
     r.state[j] = state[i];
 }
 
+// Tile jobs grouped by the piece of adjacency they read.  A hub's row is in the frontier of most batches, so the same
+// piece is read once per batch; in frontier order those reads lie a whole batch apart and every one of them comes
+// from HBM.  Handed out in an order in which the jobs of a piece follow each other, they run at about the same time
+// and all but the first are served by the caches.  Grouping, not sorting: a job's bucket is a hash of its piece's
+// start (pieces are thousands of IDs apart), jobs are counted per bucket, the counts prefix-summed, and every job
+// takes the next place of its bucket (in whatever order the adds arrive: a job's result goes to the job's own
+// place, so the order changes nothing but the timing).
+__device__ __forceinline__ uint32_t tile_bucket(int64_t begin, int bits)
+{
+    return ((uint32_t)((uint64_t)begin >> 12) * 0x9E3779B1u) >> (32 - bits);
+}
+// rank[j] = how many jobs of j's bucket came before it (by arrival); cnt[b] ends as the bucket's size
+__global__ void tile_bucket_count_kernel(const int64_t *__restrict__ begin, int64_t n_tiles, int bits, int32_t *__restrict__ cnt, int32_t *__restrict__ rank)
+{
+    const int64_t j = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (j < n_tiles) rank[j] = atomicAdd(&cnt[tile_bucket(begin[j], bits)], 1);
+}
+__global__ void tile_bucket_place_kernel(const int64_t *__restrict__ begin, int64_t n_tiles, int bits, const int64_t *__restrict__ off,
+                                         const int32_t *__restrict__ rank, int32_t *__restrict__ order)
+{
+    const int64_t j = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (j < n_tiles) order[off[tile_bucket(begin[j], bits)] + rank[j]] = (int32_t)j;
+}
+
 struct HopArgs {
     const int32_t *indices;
     const int32_t *frontier; int64_t n_frontier;
@@ -769,6 +793,7 @@ struct HopArgs {
     const int64_t *samp_off; int32_t *samp_nbr;
     const int64_t *tile_off; TileRecs tile; int64_t n_tiles; int32_t *tile_out;      // tile j writes tile_out[j * fanout ..)
     int merge_span;                                                    // tiles a wave of sample_merge_kernel looks at per round
+    const int32_t *tile_order;                                         // the k-th tile job to hand out, or NULL: job k
     ReachedMaps reached;
     unsigned long long *next_work;                                     // work items are handed out in order through this counter
 };
@@ -798,20 +823,24 @@ __global__ void __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(CAP <= 
     // length, the whole grid is resident (see launch_hop), and with the next tile known in advance its record is
     // fetched while the current one is streamed -- no wave waits for a counter or a record between tiles.
     {
-        int64_t w = blockIdx.x;
-        int64_t nb = 0; int nl = 0; uint64_t nS = 0;
-        if (w < a.n_tiles) { nb = a.tile.begin[w]; nl = a.tile.len[w]; nS = a.tile.state[w]; }
-        while (w < a.n_tiles) {
+        // Workgroup g runs on XCD g mod 8 (workgroups are dealt out to the XCDs in turn), and every XCD has an L2 of its
+        // own: in each round XCD x takes a contiguous eighth of the round's jobs, so the jobs of a piece -- neighbours
+        // in the grouped order -- meet in one L2 instead of being spread over all eight.
+        int64_t k = blockIdx.x;
+        if (a.tile_order && (gridDim.x & 7u) == 0) k = (int64_t)(blockIdx.x & 7u) * (gridDim.x >> 3) + (blockIdx.x >> 3);
+        int64_t w = 0, nb = 0; int nl = 0; uint64_t nS = 0;
+        if (k < a.n_tiles) { w = a.tile_order ? a.tile_order[k] : k; nb = a.tile.begin[w]; nl = a.tile.len[w]; nS = a.tile.state[w]; }
+        while (k < a.n_tiles) {
             const int32_t *row = a.indices + nb;
             const int len = nl;
             const uint64_t S = nS;
+            const int64_t w_now = w;
             const uint32_t first = (uint32_t)row[lane];
             const u32x4 ahead = row_ahead(row, len, lane);
-            const int64_t w_next = w + gridDim.x;
-            if (w_next < a.n_tiles) { nb = a.tile.begin[w_next]; nl = a.tile.len[w_next]; nS = a.tile.state[w_next]; }
-            sample_row<CAP, MARK_NONE>(row, len, first, ahead, f, (uint32_t)S, (uint32_t)(S >> 32), lane, buf, a.tile_out + w * f,
+            k += gridDim.x;
+            if (k < a.n_tiles) { w = a.tile_order ? a.tile_order[k] : k; nb = a.tile.begin[w]; nl = a.tile.len[w]; nS = a.tile.state[w]; }
+            sample_row<CAP, MARK_NONE>(row, len, first, ahead, f, (uint32_t)S, (uint32_t)(S >> 32), lane, buf, a.tile_out + w_now * f,
                                        ReachedOfBatch{nullptr, nullptr});
-            w = w_next;
         }
     }
     // Then the groups of 64 consecutive frontier nodes, taken as waves become free, so that uneven rows do not leave
@@ -1114,6 +1143,27 @@ rg_status sample_hop(const rg_graph *g, HopData &cur, uint32_t beta, const uint6
         ScopedTimer tm(KG_OFFSETS, st);
         hipLaunchKernelGGL(tile_records_kernel, dim3((unsigned)((n_tiles + 255) / 256)), dim3(256), 0, st, tile_off, rec.row_begin, rec.deg, rec.state, n_cur, n_tiles, tile);
     }
+    int32_t *tile_order = nullptr;
+    bool group_tiles = n_tiles >= (int64_t)n_cu * 64 && n_tiles <= 0x7FFFFFFF;     // fewer jobs than two rounds of the resident waves: nothing to bring together
+    if (const char *force = getenv("RAPIDGNN_GROUP_TILES")) group_tiles = force[0] == '1' && n_tiles > 0 && n_tiles <= 0x7FFFFFFF;     // same results either way; for tests and tuning
+    if (group_tiles) {
+        int bits = 12;                                    // about 32 jobs to a bucket: buckets that share pieces only widen the set in flight
+        while (bits < 20 && ((int64_t)32 << bits) < n_tiles) ++bits;
+        const uint64_t n_buckets = (uint64_t)1 << bits;
+        int32_t *cnt = nullptr, *rank = nullptr;
+        int64_t *off = nullptr;
+        RG_TRY(tmp.dev_n<int32_t>(n_buckets, &cnt));
+        RG_TRY(tmp.dev_n<int32_t>((uint64_t)n_tiles, &rank));
+        RG_TRY(tmp.dev_n<int64_t>(n_buckets + 1, &off));
+        RG_TRY(tmp.dev_n<int32_t>((uint64_t)n_tiles, &tile_order));
+        ScopedTimer tm(KG_OFFSETS, st);
+        RG_HIP(hipMemsetAsync(cnt, 0, n_buckets * sizeof(int32_t), st));
+        const dim3 grid((unsigned)((n_tiles + 255) / 256));
+        hipLaunchKernelGGL(tile_bucket_count_kernel, grid, dim3(256), 0, st, tile.begin, n_tiles, bits, cnt, rank);
+        RG_TRY(scan_i32_to_i64(cnt, off, (int64_t)n_buckets, tmp, st));
+        hipLaunchKernelGGL(tile_bucket_place_kernel, grid, dim3(256), 0, st, tile.begin, n_tiles, bits, off, rank, tile_order);
+        RG_HIP(hipGetLastError());
+    }
 
     if (fanout > 0 && n_cur > 0) {
         // Rows of up to SHORT_ROW IDs are sampled four at a time wherever a frontier has any: by a kernel of their own
@@ -1132,7 +1182,7 @@ rg_status sample_hop(const rg_graph *g, HopData &cur, uint32_t beta, const uint6
         int merge_span = 64;                              // tiles per look of a merging wave: 64 if that still occupies the chip's waves
         while (merge_span > 1 && n_tiles / merge_span < (int64_t)n_cu * 32) merge_span >>= 1;
         const unsigned merge_grid = (unsigned)std::max<int64_t>(1, std::min<int64_t>((n_tiles + merge_span - 1) / merge_span, (int64_t)n_cu * 64));
-        HopArgs a{g->indices, cur.ids, n_cur, 0, 0, short_mode != 0 ? SHORT_ROW : 0, short_mode == 2 ? 1 : 0, rec, fanout, cur.samp_off, cur.samp_nbr, tile_off, tile, n_tiles, tile_out, merge_span, reached, next_work};
+        HopArgs a{g->indices, cur.ids, n_cur, 0, 0, short_mode != 0 ? SHORT_ROW : 0, short_mode == 2 ? 1 : 0, rec, fanout, cur.samp_off, cur.samp_nbr, tile_off, tile, n_tiles, tile_out, merge_span, tile_order, reached, next_work};
         ScopedTimer tm(KG_SAMPLER, st);
         // worth it where a group is long work: rows of a thousand IDs on average, tiles aside (short rows finish a
         // group of 64 in no time, and four times the requests to the work counter then cost more than the tail does;
