@@ -92,3 +92,47 @@ def test_random_shape(rg, orc, shape, sampler, maps, monkeypatch):
         gso, gnb = rg.rg_schedule_samples(g, hop)
         assert np.array_equal(gso.cpu().numpy(), so), f"sample offsets differ at hop {hop}"
         assert np.array_equal(gnb.cpu().numpy(), nb), f"sampled neighbours differ at hop {hop}"
+
+
+@pytest.mark.parametrize("group_tiles", ["1", "0"])
+def test_rows_of_several_tiles(rg, orc, group_tiles, monkeypatch):
+    """Hub rows on both sides of the tiling threshold and of the tile length, up to three tiles, as seeds and as
+    neighbours of many short rows, so that every batch samples them in every hop; with the tile jobs handed out
+    grouped by the piece they read, and in frontier order."""
+    monkeypatch.setenv("RAPIDGNN_GROUP_TILES", group_tiles)
+    rng = np.random.default_rng(77)
+    n = 200_000
+    hub_deg = [16384, 16385, 40000, 65535, 65536, 65537, 70000, 131072, 131073, 150000, 196608, 199999]
+    hubs = rng.permutation(n)[:len(hub_deg)]
+    deg = rng.integers(1, 7, size=n)
+    rows = [None] * n
+    small = rng.integers(0, n, size=(n, 6))
+    with_hub = rng.random(n) < 0.3
+    for v in range(n):
+        r = small[v, :deg[v]]
+        if with_hub[v]:
+            r = np.append(r, hubs[rng.integers(0, len(hubs))])
+        r = np.unique(r)
+        rows[v] = r[r != v].astype(np.int32)
+    for h, d in zip(hubs, hub_deg):
+        cand = np.delete(np.arange(n, dtype=np.int32), h)
+        rows[h] = np.sort(rng.choice(cand, size=d, replace=False)).astype(np.int32)
+    indptr = np.zeros(n + 1, np.int64)
+    indptr[1:] = np.cumsum([r.size for r in rows])
+    indices = np.concatenate(rows)
+    train = np.concatenate([hubs, rng.permutation(n)[:300]]).astype(np.int32)
+    train = train[np.sort(np.unique(train, return_index=True)[1])]
+    fanout, batch = [12, 4], 64
+    o = orc.Schedule(indptr, indices, train, batch, fanout, 5, 1, 2, n_threads=8)
+    dp, dx, dt = torch.from_numpy(indptr).cuda(), torch.from_numpy(indices).cuda(), torch.from_numpy(train).cuda()
+    assert rg.rg_graph_validate(dp, dx) == 0
+    g = rg.rg_build_schedule(dp, dx, dt, batch, fanout, 5, 1, 2)
+    assert g.n_batches == o.n_batches
+    for hop in range(o.L + 1):
+        ids, off = o.frontier(hop)
+        gids, _, goff = rg.rg_schedule_frontier(g, hop)
+        assert np.array_equal(goff, off) and np.array_equal(gids.cpu().numpy(), ids), f"frontier {hop}"
+    for hop in range(o.L):
+        so, nb = o.samples(hop)
+        gso, gnb = rg.rg_schedule_samples(g, hop)
+        assert np.array_equal(gso.cpu().numpy(), so) and np.array_equal(gnb.cpu().numpy(), nb), f"samples {hop}"
