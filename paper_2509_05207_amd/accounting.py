@@ -36,3 +36,15 @@ def gather_group(n_batches: int, rows_per_epoch: int, stride_bytes: int) -> int:
     while g < 64 and g < n_batches and rows_per_epoch / n_batches * g * stride_bytes < (512 << 20):
         g *= 2
     return g
+
+
+# The sampler's arithmetic per scanned row entry: ten 32-bit integer operations for the key of a neighbour ID (an XOR,
+# three multiplies, three shifts, two XORs and one add folded into them as the instruction set allows) and one compare
+# against the running cut.  The vector unit's peak for such operations: 256 compute units x 64 lanes x 2.4 GHz, one
+# operation per lane and cycle (no fused multiply-add or packed forms apply to 32-bit integer multiplies and XORs).
+SAMPLER_INT_OPS_PER_ENTRY = 11
+INT32_VECTOR_PEAK_TOPS = 256 * 64 * 2.4e9 / 1e12
+
+
+def sampler_int_ops(scanned_row_entries: int) -> int:
+    return SAMPLER_INT_OPS_PER_ENTRY * int(scanned_row_entries)
