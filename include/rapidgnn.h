@@ -106,8 +106,10 @@ typedef struct rg_cache rg_cache;
  * reached map (never used together with those passes); RAPIDGNN_SHORT_ROWS=0 / 1 / 2
  * makes rows of up to 64 IDs be sampled one per wave / four at a time by a kernel
  * of their own / four at a time inside the main kernel (default: 1 in hops that
- * mark with byte stores, 2 in the others).  The result is the
- * same in every case.  The maps are drawn from a pool of blocks known to be
+ * mark with byte stores, 2 in the others); RAPIDGNN_GROUP_TILES=1 / 0 forces /
+ * forbids handing out the pieces of rows above 16,384 IDs grouped by the piece
+ * they read, so that batches that share a row meet in the caches (default: from
+ * 16,384 pieces on).  The result is the same in every case.  The maps are drawn from a pool of blocks known to be
  * all-zero and handed back to it after the build has cleared what it touched;
  * RAPIDGNN_CHECK_ZERO_MAPS=1 makes every build verify that on the device first.
  */
