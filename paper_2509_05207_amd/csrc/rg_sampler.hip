@@ -46,6 +46,7 @@
 namespace rg {
 
 
+constexpr int TINY_ROW = 8;              // rows of up to this many IDs that need no sampling are copied by one lane each
 constexpr int BIG_ROW = 16384;           // rows longer than this are sampled tile by tile ...
 constexpr int TILE_PIECE = 65536;        // ... in near-equal pieces of at most this many IDs.  (A row of 16,385 to 65,536 IDs is one tile: it is
                                          // sampled among the tile jobs, where the batches that share it meet in the caches.  Measured on the five
@@ -862,7 +863,25 @@ __global__ void __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(CAP <= 
         if (SHORT_INLINE) {
             // the group's rows of up to SHORT_ROW IDs first, four at a time (their marks and scattered little reads then
             // run beside the streaming of the other waves' long rows)
-            const bool mine = in && deg_lane > 0 && deg_lane <= SHORT_ROW;
+            // A row of at most TINY_ROW IDs that is no longer than the fan-out is its own sample: its node's lane copies
+            // and marks it, 64 rows at a time, four IDs of each in flight (on a graph whose typical row has two or three
+            // IDs these are nine rows in ten, and four at a time is sixteen rounds for what is one or two here).
+            const bool tiny = in && deg_lane > 0 && deg_lane <= f && deg_lane <= TINY_ROW;
+            if (ballot64(tiny) != 0ull) {
+                const int32_t *row = a.indices + rb_lane;
+                int32_t *out = a.samp_nbr + out_lane;
+                const ReachedOfBatch reached_b = reached_of<MARK>(a.reached, b_lane);
+                for (int j0 = 0; ballot64(tiny && j0 < deg_lane) != 0ull; j0 += 4) {
+                    int32_t u[4] = {0, 0, 0, 0};
+#pragma unroll
+                    for (int k = 0; k < 4; ++k)
+                        if (tiny && j0 + k < deg_lane) u[k] = row[j0 + k];
+#pragma unroll
+                    for (int k = 0; k < 4; ++k)
+                        if (tiny && j0 + k < deg_lane) { out[j0 + k] = u[k]; mark_reached<MARK>(reached_b, (uint32_t)u[k]); }
+                }
+            }
+            const bool mine = in && !tiny && deg_lane > 0 && deg_lane <= SHORT_ROW;
             const int count = __popcll(ballot64(mine));
             if (count != 0) {
                 const int at = short_row_slot(mine, deg_lane, lane);
