@@ -433,14 +433,7 @@ __device__ __forceinline__ int64_t route_of(const RouteSources &r, int64_t v)
     return make_entry(TAG_REMOTE, r.row_of[v]);
 }
 
-// route[v] for every node ID: worth building when the epochs list far more input nodes than the graph has nodes.
-__global__ void route_table_kernel(int64_t n, RouteSources r, int64_t *__restrict__ route)
-{
-    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
-    for (int64_t v = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; v < n; v += stride) route[v] = route_of(r, v);
-}
-
-// entry[j] = route[ids[j]] for every listed input node, which of them are misses (one bit each, in position order:
+// entry[j] = route_of(ids[j]) for every listed input node, which of them are misses (one bit each, in position order:
 // a wave's ballot is the 64-bit word of its 64 consecutive positions), the misses of every tile of PLAN_TILE
 // positions, and per-batch counts of local rows and cache hits.  A block covers one tile and adds its counts once
 // when it lies inside one batch (nearly always), else position by position.
@@ -450,7 +443,7 @@ constexpr int PLAN_TILE = PLAN_THREADS * PLAN_PER_THREAD;
 constexpr int PLAN_TILE_WORDS = PLAN_TILE / 64;          // miss-bit words per tile
 
 __global__ void __launch_bounds__(PLAN_THREADS) plan_kernel(const int32_t *__restrict__ ids, int64_t n, const int64_t *__restrict__ batch_off, uint32_t n_batches,
-                                                            const int64_t *__restrict__ route /* or NULL: look the three arrays up */, RouteSources rs,
+                                                            RouteSources rs,
                                                             int64_t *__restrict__ entry, unsigned long long *__restrict__ miss_bits /* [tiles * PLAN_TILE_WORDS] */,
                                                             int32_t *__restrict__ tile_miss /* [tiles] */,
                                                             unsigned long long *__restrict__ counts /* [n_batches][2]: local, hit */)
@@ -467,7 +460,7 @@ __global__ void __launch_bounds__(PLAN_THREADS) plan_kernel(const int32_t *__res
         const int64_t j = tile0 + (int64_t)k * PLAN_THREADS + threadIdx.x;
         int64_t tag = -1;
         if (j < n) {
-            const int64_t e = route ? route[ids[j]] : route_of(rs, ids[j]);
+            const int64_t e = route_of(rs, ids[j]);
             tag = entry_tag(e);
             entry[j] = e;
             if (one_batch) { n_local += tag == TAG_LOCAL; n_hit += tag == TAG_CACHE; }
@@ -546,9 +539,9 @@ __global__ void __launch_bounds__(256) miss_list_kernel(const unsigned long long
     }
 }
 
-// Routing entries, miss lists and counts of one schedule from the per-node route table.  What the
+// Routing entries, miss lists and counts of one schedule.  What the
 // plan keeps lives in `keep`; scratch in `tmp`.
-rg_status build_plan(const rg_schedule *s, const int64_t *route, const RouteSources &rs, Arena &keep, Arena &tmp, hipStream_t st, Plan *plan)
+rg_status build_plan(const rg_schedule *s, const RouteSources &rs, Arena &keep, Arena &tmp, hipStream_t st, Plan *plan)
 {
     const uint32_t beta = s->n_batches;
     const HopData &h = s->hop[s->L];
@@ -574,7 +567,7 @@ rg_status build_plan(const rg_schedule *s, const int64_t *route, const RouteSour
         ScopedTimer tm(KG_PLAN, st);
         if (n > 0)
             hipLaunchKernelGGL(plan_kernel, dim3((unsigned)n_tiles), dim3(PLAN_THREADS), 0, st, h.ids, n, h.off_dev, beta,
-                               route, rs, plan->entry, miss_bits, tile_miss, counts);
+                               rs, plan->entry, miss_bits, tile_miss, counts);
         RG_TRY(scan_i32_to_i64(tile_miss, tile_scan, n_tiles, tmp, st));
         hipLaunchKernelGGL(miss_offsets_kernel, dim3((beta + 1 + 255) / 256), dim3(256), 0, st, miss_bits, tile_scan, n, n_tiles, h.off_dev, beta, miss_off_dev);
     }
@@ -780,16 +773,7 @@ static rg_status build_cache_impl(const rg_schedule *const *epochs, uint32_t n_e
     // ---- a5/a9: plans, miss lists and counts for every batch of every epoch
     c->plans.resize(n_epochs);
     const RouteSources rs{f->row_of, c->slot_pairs};
-    int64_t listed = 0;                                   // input nodes over all epochs
-    for (uint32_t e = 0; e < n_epochs; ++e) listed += epochs[e]->hop[epochs[e]->L].off_host[epochs[e]->n_batches];
-    int64_t *route = nullptr;
-    if (n > 0 && listed >= n / 4) {                       // else three lookups per listed node cost less than a pass over every node
-        RG_TRY(tmp.dev_n<int64_t>((uint64_t)n, &route));
-        ScopedTimer tm(KG_PLAN, st);
-        const unsigned grid = (unsigned)std::max<int64_t>(1, std::min<int64_t>((n + 255) / 256, (int64_t)n_cu * 16));
-        hipLaunchKernelGGL(route_table_kernel, dim3(grid), dim3(256), 0, st, n, rs, route);
-    }
-    for (uint32_t e = 0; e < n_epochs; ++e) RG_TRY(build_plan(epochs[e], route, rs, c->arena, tmp, st, &c->plans[e]));
+    for (uint32_t e = 0; e < n_epochs; ++e) RG_TRY(build_plan(epochs[e], rs, c->arena, tmp, st, &c->plans[e]));
     if (forked.side) RG_HIP(hipStreamWaitEvent(st, c->ev_join, 0));
     RG_HIP(hipStreamSynchronize(st));
     if (forked.side) { RG_HIP(hipStreamSynchronize(forked.side)); forked.side = nullptr; }
